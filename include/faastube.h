@@ -1,0 +1,243 @@
+/*
+ * faastube.h - C ABI of the single-GPU batched scatter-gather transfer engine.
+ *
+ * The engine is the data-passing hot path of FaaSTube (arxiv 2411.01830) for
+ * one GPU: intermediate tensors of many concurrent functions move between
+ * pinned host memory and a pooled GPU store (Sec. 5.1 "Host-GPU"), and between
+ * two places of that store (Sec. 5.1 "Intra-GPU"), cut into fixed-size chunks
+ * that are interleaved across functions in proportion to per-function weights
+ * (Sec. 6.1), with the store handing out memory from a growable pool instead
+ * of the native allocator (Sec. 7.1).
+ *
+ * Conventions for every call
+ *   - Returns FT_OK (0) or a negative FT_E* code. On error nothing is launched
+ *     and no state changes. ft_strerror() names a code.
+ *   - "host pointer" / "device pointer" is stated per argument. The library
+ *     never takes ownership of caller memory.
+ *   - One mutex per pool: calls on one pool from several threads serialise.
+ *   - All multi-byte fields are little endian.
+ */
+#ifndef FAASTUBE_H
+#define FAASTUBE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ft_pool ft_pool; /* opaque; created by ft_pool_create, freed by ft_pool_destroy */
+typedef uint64_t ft_off_t;      /* byte offset in a pool's logical offset space */
+typedef uint64_t ft_job_t;      /* handle of one submit */
+
+/* address spaces of a descriptor side */
+enum { FT_HOST = 0, FT_POOL = 1 };
+
+/* link classes: each has its own chunk schedule and its own kernel */
+enum { FT_H2P = 0, FT_P2H = 1, FT_P2P = 2, FT_NCLASS = 3 };
+
+/* return codes */
+enum {
+  FT_OK = 0,
+  FT_EINVAL = -1,   /* malformed argument (see each call) */
+  FT_ENOMEM = -2,   /* no run of free slabs; the caller may ft_pool_grow and retry */
+  FT_ERANGE = -3,   /* a pool range is not inside one live allocation, or a host range is
+                       outside every registered host window */
+  FT_EOVERLAP = -4, /* with FT_VALIDATE: a destination byte is written twice or also read */
+  FT_EBUSY = -5,    /* ft_slab_free of an allocation a not-yet-waited job refers to */
+  FT_EHIP = -6      /* a HIP runtime call failed; ft_last_hip_error() gives its text */
+};
+
+/* flags of ft_submit_transfers */
+enum {
+  FT_VALIDATE = 1 << 0, /* exact overlap check, O(rows log rows) on the host */
+  FT_LOG = 1 << 1,      /* the kernel records begin/end device time of every ticket */
+  FT_PATH_DMA = 1 << 2, /* run the same schedule with hipMemcpyAsync / hipMemcpy2DAsync per
+                           chunk piece instead of the copy kernel (comparison path) */
+  FT_TIMING = 1 << 3,   /* bracket each class's work with timing events */
+  FT_DETACHED = 1 << 4, /* do not make the caller's stream wait for the job */
+  FT_KEEP = 1 << 5      /* keep the job record after ft_wait until ft_job_release;
+                           implied by FT_LOG and FT_TIMING */
+};
+
+/*
+ * One transfer: rows x row_bytes payload bytes, row r at src + r*src_pitch and
+ * dst + r*dst_pitch. Payload order (used by the chunk stream) is row major.
+ * After the job completes, for every payload index p with r = p / row_bytes,
+ * c = p % row_bytes:   DST[dst + r*dst_pitch + c] == SRC[src + r*src_pitch + c],
+ * SRC being memory as it was when the job started (Sec. 5.1: passing is a copy).
+ * No alignment is required of src, dst, row_bytes or the pitches.
+ */
+typedef struct ft_desc {
+  uint32_t func;      /* 0 .. nfunc-1: the function this data belongs to */
+  uint8_t src_space;  /* FT_HOST: src is a device-visible virtual address of pinned host
+                         memory. FT_POOL: src is an ft_off_t */
+  uint8_t dst_space;  /* same for dst. FT_HOST -> FT_HOST is invalid */
+  uint16_t flags;     /* must be 0 */
+  uint64_t src;
+  uint64_t dst;
+  uint64_t row_bytes; /* > 0 */
+  uint64_t rows;      /* >= 1; with rows == 1 the pitches are ignored */
+  uint64_t src_pitch; /* >= row_bytes when rows > 1 */
+  uint64_t dst_pitch; /* >= row_bytes when rows > 1 */
+  uint64_t _pad;      /* ignored */
+} ft_desc;            /* 64 bytes */
+
+/* Per-class figures of one job (ft_job_stats). */
+typedef struct ft_class_stats {
+  uint64_t payload_bytes; /* sum of rows*row_bytes of the class's descriptors */
+  uint64_t chunks;        /* N = sum over functions of ceil(S_f / chunk_bytes) */
+  uint64_t tickets;       /* chunks * tiles per chunk: what the device counter runs to */
+  uint64_t tile_bytes;    /* bytes one ticket moves (last tile of a chunk may be shorter) */
+  uint32_t workgroups;    /* persistent workgroups launched (0 on the DMA path) */
+  uint32_t _pad;
+  float device_ms;        /* FT_TIMING: event time around the class's work, else -1 */
+  float _pad2;
+} ft_class_stats;
+
+typedef struct ft_job_stats_t {
+  ft_class_stats cls[FT_NCLASS];
+  double host_submit_us; /* wall time spent inside ft_submit_transfers */
+} ft_job_stats_t;
+
+/* ------------------------------------------------------------------ pool (Sec. 7.1) */
+
+/*
+ * Create a pool over caller-owned device memory.
+ *   out        host pointer, receives the handle.
+ *   dev_base   device pointer, 256-byte aligned, valid for `bytes`; must outlive the pool.
+ *   bytes      positive multiple of slab_bytes.
+ *   slab_bytes positive multiple of 256: the allocation granule.
+ *   device     HIP device ordinal the memory lives on.
+ * No HIP call is made here; device resources (three internal streams, table
+ * buffers) are created by the first ft_submit_transfers.
+ * FT_EINVAL on a null pointer, misalignment or a size that is not a multiple.
+ */
+int ft_pool_create(ft_pool **out, void *dev_base, uint64_t bytes, uint64_t slab_bytes, int device);
+
+/*
+ * Append one segment (the store scales with demand, Sec. 7.1). The logical
+ * offset space is the concatenation of the segments in the order added; an
+ * allocation never straddles two segments. Same argument rules as create.
+ */
+int ft_pool_grow(ft_pool *p, void *dev_base, uint64_t bytes);
+
+/* Wait for every job, release all library-owned resources. Caller memory is untouched. */
+int ft_pool_destroy(ft_pool *p);
+
+/*
+ * Take the lowest-indexed run of ceil(nbytes / slab_bytes) free slabs that lies in one
+ * segment (first fit). *off_out (host pointer) receives its offset.
+ * FT_EINVAL if nbytes == 0; FT_ENOMEM if no run exists.
+ */
+int ft_slab_alloc(ft_pool *p, uint64_t nbytes, ft_off_t *off_out);
+
+/* Return an allocation. FT_EINVAL if off is not the start of a live allocation,
+ * FT_EBUSY if a job that has not been waited for refers to it. */
+int ft_slab_free(ft_pool *p, ft_off_t off);
+
+/* Device pointer of a pool offset, or NULL if off is outside the pool. */
+void *ft_pool_ptr(ft_pool *p, ft_off_t off);
+
+/*
+ * Declare a window of pinned, device-visible host memory (host pointer that the
+ * device can dereference at the same address, e.g. from hipHostMalloc). Once at
+ * least one window is registered, every FT_HOST range of a submit must lie inside
+ * one window (else FT_ERANGE). With no window registered host ranges are trusted.
+ */
+int ft_host_window_add(ft_pool *p, void *host_base, uint64_t bytes);
+
+/* ------------------------------------------------------- transfers (Sec. 5.1, 6.1) */
+
+/*
+ * Submit a batch of transfers of nfunc functions.
+ *   descs, weights  host pointers; copied before the call returns.
+ *   weights[f] >= 1 integer share of function f. chunk_bytes: positive multiple of 16
+ *   (the paper's default is 2 MB).
+ *   hip_stream      a hipStream_t (NULL = the null stream). The job starts after all work
+ *                   already on that stream; unless FT_DETACHED the stream also waits for
+ *                   the job, so two jobs on one stream run in submit order.
+ *
+ * Per link class (host->pool, pool->host, pool->pool) and function, the payloads of
+ * the function's descriptors in submission order form a byte stream of S_f bytes;
+ * chunk k is stream bytes [k*C, min((k+1)*C, S_f)). All chunks of a class are put in
+ * one total order: chunk j of function f carries the finish tag (j+1)/w_f, smaller
+ * tags first, equal tags by lower f - i.e. always serve the unfinished function with
+ * the smallest (served+1)/weight. Persistent workgroups draw tickets from a device
+ * counter in that order; the classes run concurrently on streams of their own.
+ *
+ * Validation order: FT_EINVAL conditions of the arguments and of every descriptor
+ * (null pointers with non-zero counts, nfunc == 0, a weight of 0, chunk_bytes not a
+ * positive multiple of 16, func >= nfunc, flags != 0, a space other than FT_HOST or
+ * FT_POOL, host->host, row_bytes == 0, rows == 0, a pitch < row_bytes with rows > 1,
+ * weights whose slot tables would exceed 2^22 entries), then FT_ERANGE of every
+ * descriptor, then (FT_VALIDATE) FT_EOVERLAP. ndesc == 0 is valid.
+ */
+int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
+                        uint32_t nfunc, uint64_t chunk_bytes, uint32_t flags, void *hip_stream,
+                        ft_job_t *job_out);
+
+/*
+ * Block until every chunk of the job is visible at its destination (device memory,
+ * and host memory for pool->host). A job can be waited for once; unless it was
+ * submitted with FT_KEEP/FT_LOG/FT_TIMING the handle is dead afterwards.
+ */
+int ft_wait(ft_pool *p, ft_job_t job);
+
+/* Drop the record of a kept job (after ft_wait). */
+int ft_job_release(ft_pool *p, ft_job_t job);
+
+/* Figures of a kept job; `out` is a host pointer. device_ms is valid after ft_wait. */
+int ft_job_stats(ft_pool *p, ft_job_t job, ft_job_stats_t *out);
+
+/*
+ * Test hook: the ticket order the device uses for one class of a kept job. A small
+ * kernel decodes every chunk rank with the same tables and device function as the
+ * copy kernel and the result is copied back. func_out / chunk_out are host arrays
+ * of `cap` entries; *n_out receives the number of chunks N (entries beyond cap are
+ * not written).
+ */
+int ft_job_schedule(ft_pool *p, ft_job_t job, int link_class, uint32_t *func_out,
+                    uint32_t *chunk_out, uint64_t cap, uint64_t *n_out);
+
+/*
+ * FT_LOG: per ticket of one class, after ft_wait: device clock (ns) at claim and at
+ * completion, the function, the chunk and the bytes moved. Host arrays of `cap`
+ * entries each (any may be NULL); *n_out receives the ticket count.
+ */
+int ft_job_log(ft_pool *p, ft_job_t job, int link_class, uint64_t *t_begin_ns, uint64_t *t_end_ns,
+               uint32_t *func_out, uint32_t *chunk_out, uint32_t *bytes_out, uint64_t cap,
+               uint64_t *n_out);
+
+/*
+ * Launch shape of one class: number of persistent workgroups (0 = default for the
+ * device) and bytes per ticket (0 = default; rounded to a multiple of 16 that
+ * divides the chunk into equal tiles). Applies to later submits.
+ */
+int ft_set_tuning(ft_pool *p, int link_class, uint32_t workgroups, uint64_t tile_bytes);
+
+/*
+ * Host-only: the chunk order for given per-function stream sizes, computed with
+ * the same table builder and rank decoder as the device path, on the CPU. Lets
+ * the schedule be checked where no GPU is present. Arrays as in ft_job_schedule.
+ */
+int ft_plan_schedule(const uint64_t *stream_bytes, const uint32_t *weights, uint32_t nfunc,
+                     uint64_t chunk_bytes, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap,
+                     uint64_t *n_out);
+
+/*
+ * Calibration: a plain grid-stride 16-byte copy of `bytes` (multiple of 16) from
+ * src to dst (device pointers, 16-byte aligned) on hip_stream, no tickets, no
+ * tables. The practical ceiling the engine is compared with, and the known-size
+ * kernel profiler byte counters are scaled by.
+ */
+int ft_plain_copy(void *dst, const void *src, uint64_t bytes, uint32_t workgroups, void *hip_stream);
+
+const char *ft_strerror(int rc);
+/* Text of the last failing HIP call on this pool ("" if none). */
+const char *ft_last_hip_error(ft_pool *p);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FAASTUBE_H */

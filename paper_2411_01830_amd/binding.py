@@ -1,0 +1,188 @@
+"""ctypes binding of include/faastube.h: same names, argument marshalling only."""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfaastube.so")
+
+FT_NCLASS = 3
+FT_H2P, FT_P2H, FT_P2P = 0, 1, 2
+FT_VALIDATE, FT_LOG, FT_PATH_DMA, FT_TIMING, FT_DETACHED, FT_KEEP = 1, 2, 4, 8, 16, 32
+
+EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
+           "ft_pool_ptr", "ft_host_window_add", "ft_submit_transfers", "ft_wait", "ft_job_release",
+           "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_set_tuning", "ft_plan_schedule",
+           "ft_plain_copy", "ft_strerror", "ft_last_hip_error"]
+
+
+class FtError(Exception):
+    def __init__(self, code, what=""):
+        super().__init__(f"faastube error {code}: {what}")
+        self.code = code
+
+
+class ClassStats(C.Structure):
+    _fields_ = [("payload_bytes", C.c_uint64), ("chunks", C.c_uint64), ("tickets", C.c_uint64),
+                ("tile_bytes", C.c_uint64), ("workgroups", C.c_uint32), ("_pad", C.c_uint32),
+                ("device_ms", C.c_float), ("_pad2", C.c_float)]
+
+
+class JobStats(C.Structure):
+    _fields_ = [("cls", ClassStats * FT_NCLASS), ("host_submit_us", C.c_double)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` (or "
+                          "paper_2411_01830_amd/build.py) first; there is no CPU fallback")
+    # PyTorch ships its own HIP runtime (same SONAME as the system one). The caller's
+    # device memory and streams live in that runtime, so it must be the one this library
+    # binds to: load it first and the dynamic linker resolves our dependency to it.
+    import torch  # noqa: F401
+    lib = C.CDLL(LIB_PATH)
+    vp, u64, u32, i32 = C.c_void_p, C.c_uint64, C.c_uint32, C.c_int
+    P = C.POINTER
+    sig = {
+        "ft_pool_create": (i32, [P(vp), vp, u64, u64, i32]),
+        "ft_pool_grow": (i32, [vp, vp, u64]),
+        "ft_pool_destroy": (i32, [vp]),
+        "ft_slab_alloc": (i32, [vp, u64, P(u64)]),
+        "ft_slab_free": (i32, [vp, u64]),
+        "ft_pool_ptr": (vp, [vp, u64]),
+        "ft_host_window_add": (i32, [vp, vp, u64]),
+        "ft_submit_transfers": (i32, [vp, vp, u32, vp, u32, u64, u32, vp, P(u64)]),
+        "ft_wait": (i32, [vp, u64]),
+        "ft_job_release": (i32, [vp, u64]),
+        "ft_job_stats": (i32, [vp, u64, P(JobStats)]),
+        "ft_job_schedule": (i32, [vp, u64, i32, vp, vp, u64, P(u64)]),
+        "ft_job_log": (i32, [vp, u64, i32, vp, vp, vp, vp, vp, u64, P(u64)]),
+        "ft_set_tuning": (i32, [vp, i32, u32, u64]),
+        "ft_plan_schedule": (i32, [vp, vp, u32, u64, vp, vp, u64, P(u64)]),
+        "ft_plain_copy": (i32, [vp, vp, u64, u32, vp]),
+        "ft_strerror": (C.c_char_p, [i32]),
+        "ft_last_hip_error": (C.c_char_p, [vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+_lib = _load()
+
+
+def _check(rc, pool=None):
+    if rc != 0:
+        what = _lib.ft_strerror(rc).decode()
+        if rc == -6 and pool:
+            what += " - " + _lib.ft_last_hip_error(pool).decode()
+        raise FtError(rc, what)
+
+
+def strerror(rc):
+    return _lib.ft_strerror(rc).decode()
+
+
+def pool_create(dev_base, nbytes, slab_bytes, device=0):
+    h = C.c_void_p()
+    _check(_lib.ft_pool_create(C.byref(h), dev_base, nbytes, slab_bytes, device))
+    return h
+
+
+def pool_grow(pool, dev_base, nbytes):
+    _check(_lib.ft_pool_grow(pool, dev_base, nbytes), pool)
+
+
+def pool_destroy(pool):
+    _check(_lib.ft_pool_destroy(pool))
+
+
+def slab_alloc(pool, nbytes):
+    off = C.c_uint64()
+    _check(_lib.ft_slab_alloc(pool, nbytes, C.byref(off)), pool)
+    return off.value
+
+
+def slab_free(pool, off):
+    _check(_lib.ft_slab_free(pool, off), pool)
+
+
+def pool_ptr(pool, off):
+    return _lib.ft_pool_ptr(pool, off)
+
+
+def host_window_add(pool, host_base, nbytes):
+    _check(_lib.ft_host_window_add(pool, host_base, nbytes), pool)
+
+
+def submit_transfers(pool, descs, weights, chunk_bytes, flags=0, stream=0):
+    """descs: contiguous array of the 64-byte descriptor dtype; weights: uint32 sequence."""
+    descs = np.ascontiguousarray(descs)
+    assert descs.dtype.itemsize == 64
+    w = np.ascontiguousarray(np.asarray(weights, dtype=np.uint32))
+    job = C.c_uint64()
+    _check(_lib.ft_submit_transfers(pool, descs.ctypes.data if len(descs) else None, len(descs),
+                                    w.ctypes.data if len(w) else None, len(w), chunk_bytes, flags,
+                                    stream, C.byref(job)), pool)
+    return job.value
+
+
+def wait(pool, job):
+    _check(_lib.ft_wait(pool, job), pool)
+
+
+def job_release(pool, job):
+    _check(_lib.ft_job_release(pool, job), pool)
+
+
+def job_stats(pool, job):
+    st = JobStats()
+    _check(_lib.ft_job_stats(pool, job, C.byref(st)), pool)
+    return st
+
+
+def job_schedule(pool, job, link_class):
+    n = C.c_uint64()
+    _check(_lib.ft_job_schedule(pool, job, link_class, None, None, 0, C.byref(n)), pool)
+    f = np.zeros(max(n.value, 1), dtype=np.uint32)
+    k = np.zeros(max(n.value, 1), dtype=np.uint32)
+    _check(_lib.ft_job_schedule(pool, job, link_class, f.ctypes.data, k.ctypes.data, n.value,
+                                C.byref(n)), pool)
+    return list(zip(f[:n.value].tolist(), k[:n.value].tolist()))
+
+
+def job_log(pool, job, link_class):
+    """dict of arrays: t_begin_ns, t_end_ns, func, chunk, bytes - one entry per ticket."""
+    n = C.c_uint64()
+    _check(_lib.ft_job_log(pool, job, link_class, None, None, None, None, None, 0, C.byref(n)), pool)
+    m = max(n.value, 1)
+    tb, te = np.zeros(m, np.uint64), np.zeros(m, np.uint64)
+    f, k, b = np.zeros(m, np.uint32), np.zeros(m, np.uint32), np.zeros(m, np.uint32)
+    _check(_lib.ft_job_log(pool, job, link_class, tb.ctypes.data, te.ctypes.data, f.ctypes.data,
+                           k.ctypes.data, b.ctypes.data, n.value, C.byref(n)), pool)
+    s = slice(0, n.value)
+    return {"t_begin_ns": tb[s], "t_end_ns": te[s], "func": f[s], "chunk": k[s], "bytes": b[s]}
+
+
+def set_tuning(pool, link_class, workgroups=0, tile_bytes=0):
+    _check(_lib.ft_set_tuning(pool, link_class, workgroups, tile_bytes), pool)
+
+
+def plan_schedule(stream_bytes, weights, chunk_bytes):
+    s = np.ascontiguousarray(np.asarray(stream_bytes, dtype=np.uint64))
+    w = np.ascontiguousarray(np.asarray(weights, dtype=np.uint32))
+    n = C.c_uint64()
+    _check(_lib.ft_plan_schedule(s.ctypes.data, w.ctypes.data, len(w), chunk_bytes, None, None, 0,
+                                 C.byref(n)))
+    f = np.zeros(max(n.value, 1), dtype=np.uint32)
+    k = np.zeros(max(n.value, 1), dtype=np.uint32)
+    _check(_lib.ft_plan_schedule(s.ctypes.data, w.ctypes.data, len(w), chunk_bytes, f.ctypes.data,
+                                 k.ctypes.data, n.value, C.byref(n)))
+    return list(zip(f[:n.value].tolist(), k[:n.value].tolist()))
+
+
+def plain_copy(dst_ptr, src_ptr, nbytes, workgroups=0, stream=0):
+    _check(_lib.ft_plain_copy(dst_ptr, src_ptr, nbytes, workgroups, stream))

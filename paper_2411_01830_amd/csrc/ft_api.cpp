@@ -1,0 +1,667 @@
+// C ABI of the transfer engine: pool handle, jobs, streams, table upload, launches.
+#include <hip/hip_runtime_api.h>
+
+#include <chrono>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/faastube.h"
+#include "ft_kernels.h"
+#include "ft_plan.h"
+#include "ft_pool.h"
+#include "ft_tables.h"
+
+namespace {
+
+using namespace ft;
+
+// A device buffer with a pinned host twin of the same size; recycled between jobs so
+// that a steady stream of submits allocates nothing.
+struct Blob {
+  char *dev = nullptr;
+  char *host = nullptr;  // null for device-only blobs
+  uint64_t cap = 0;
+};
+
+struct ClassRun {
+  bool used = false;
+  ClassTable table{};       // device addresses
+  ClassPlan plan;           // host copy (DMA path, log decoding, stats)
+  uint64_t tile_bytes = 0;
+  uint32_t tiles_per_chunk = 0;
+  uint32_t workgroups = 0;
+  hipEvent_t ev_begin = nullptr, ev_done = nullptr;
+  Blob log;
+  std::vector<LogEntry> log_host;
+  float device_ms = -1.f;
+};
+
+struct Job {
+  uint64_t id = 0;
+  uint32_t flags = 0;
+  bool keep = false;
+  bool waited = false;
+  ClassRun run[FT_NCLASS];
+  Blob tables;
+  std::vector<uint64_t> allocs;
+  uint64_t chunk_bytes = 0;
+  double host_submit_us = 0;
+};
+
+struct Tuning {
+  uint32_t workgroups = 0;
+  uint64_t tile_bytes = 0;
+};
+
+}  // namespace
+
+struct ft_pool {
+  std::mutex mu;
+  SlabPool slabs;
+  int device;
+  std::vector<HostWindow> windows;
+  bool dev_ready = false;
+  int cu_count = 0;
+  int clock_khz = 0;
+  hipStream_t streams[FT_NCLASS] = {nullptr, nullptr, nullptr};
+  std::vector<Blob> free_blobs;       // with a pinned twin
+  std::vector<Blob> free_dev_blobs;   // device only
+  std::vector<hipEvent_t> free_events, free_timing_events;
+  std::unordered_map<uint64_t, std::unique_ptr<Job>> jobs;
+  uint64_t next_job = 1;
+  Tuning tuning[FT_NCLASS];
+  std::string hip_error;
+
+  ft_pool(uint64_t slab_bytes, int dev) : slabs(slab_bytes), device(dev) {}
+};
+
+namespace {
+
+#define FT_HIP(p, call)                                                        \
+  do {                                                                         \
+    hipError_t e_ = (call);                                                    \
+    if (e_ != hipSuccess) {                                                    \
+      (p)->hip_error = std::string(#call) + ": " + hipGetErrorString(e_);      \
+      return FT_EHIP;                                                          \
+    }                                                                          \
+  } while (0)
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) == hipSuccess && prev != dev) ok = hipSetDevice(dev) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (ok) (void)hipSetDevice(prev);
+  }
+};
+
+int ensure_device(ft_pool *p) {
+  if (p->dev_ready) return FT_OK;
+  int count = 0;
+  FT_HIP(p, hipGetDeviceCount(&count));
+  if (p->device < 0 || p->device >= count) {
+    p->hip_error = "device ordinal out of range";
+    return FT_EHIP;
+  }
+  FT_HIP(p, hipDeviceGetAttribute(&p->cu_count, hipDeviceAttributeMultiprocessorCount, p->device));
+  FT_HIP(p, hipDeviceGetAttribute(&p->clock_khz, hipDeviceAttributeWallClockRate, p->device));
+  for (int c = 0; c < FT_NCLASS; ++c)
+    FT_HIP(p, hipStreamCreateWithFlags(&p->streams[c], hipStreamNonBlocking));
+  p->dev_ready = true;
+  return FT_OK;
+}
+
+uint64_t round_pow2(uint64_t v, uint64_t floor_) {
+  uint64_t c = floor_;
+  while (c < v) c <<= 1;
+  return c;
+}
+
+int get_blob(ft_pool *p, uint64_t need, bool pinned_twin, Blob *out) {
+  std::vector<Blob> &cache = pinned_twin ? p->free_blobs : p->free_dev_blobs;
+  size_t best = cache.size();
+  for (size_t i = 0; i < cache.size(); ++i)
+    if (cache[i].cap >= need && (best == cache.size() || cache[i].cap < cache[best].cap)) best = i;
+  if (best != cache.size()) {
+    *out = cache[best];
+    cache.erase(cache.begin() + (long)best);
+    return FT_OK;
+  }
+  Blob b;
+  b.cap = round_pow2(need, 64 * 1024);
+  FT_HIP(p, hipMalloc(reinterpret_cast<void **>(&b.dev), b.cap));
+  if (pinned_twin) {
+    hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&b.host), b.cap, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      (void)hipFree(b.dev);
+      p->hip_error = std::string("hipHostMalloc: ") + hipGetErrorString(e);
+      return FT_EHIP;
+    }
+  }
+  *out = b;
+  return FT_OK;
+}
+
+void put_blob(ft_pool *p, Blob &b) {
+  if (b.dev == nullptr) return;
+  (b.host ? p->free_blobs : p->free_dev_blobs).push_back(b);
+  b = Blob();
+}
+
+int get_event(ft_pool *p, bool timing, hipEvent_t *out) {
+  std::vector<hipEvent_t> &cache = timing ? p->free_timing_events : p->free_events;
+  if (!cache.empty()) {
+    *out = cache.back();
+    cache.pop_back();
+    return FT_OK;
+  }
+  FT_HIP(p, hipEventCreateWithFlags(out, timing ? hipEventDefault : hipEventDisableTiming));
+  return FT_OK;
+}
+
+void put_event(ft_pool *p, bool timing, hipEvent_t &e) {
+  if (e == nullptr) return;
+  (timing ? p->free_timing_events : p->free_events).push_back(e);
+  e = nullptr;
+}
+
+uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+// Byte layout of one class's tables inside the job's blob.
+struct Layout {
+  uint64_t ticket, phases, slots, funcs, xfers, end;
+};
+
+Layout layout_of(const ClassPlan &cp, uint64_t base) {
+  Layout l;
+  l.ticket = align_up(base, 256);
+  l.phases = l.ticket + 256;
+  l.slots = align_up(l.phases + cp.phases.size() * sizeof(Phase), 64);
+  l.funcs = align_up(l.slots + cp.slots.size() * sizeof(Slot), 64);
+  l.xfers = align_up(l.funcs + cp.funcs.size() * sizeof(Func), 64);
+  l.end = align_up(l.xfers + cp.xfers.size() * sizeof(Xfer), 256);
+  return l;
+}
+
+uint32_t default_workgroups(const ft_pool *p, int cls) {
+  // pool->pool is bound by HBM: fill every CU with as many wavefronts as it holds.
+  // The host link saturates with far fewer loads in flight; leave the CUs to others.
+  if (cls == FT_P2P) return (uint32_t)p->cu_count * 8u;
+  return 64u;
+}
+
+uint64_t default_tile(int cls) { return cls == FT_P2P ? 64u * 1024u : 32u * 1024u; }
+
+hipMemcpyKind kind_of(int cls) {
+  return cls == FT_H2P ? hipMemcpyHostToDevice : cls == FT_P2H ? hipMemcpyDeviceToHost : hipMemcpyDeviceToDevice;
+}
+
+// The comparison path: the same chunk order, one copy-engine call per chunk piece.
+int run_dma(ft_pool *p, const ClassPlan &cp, uint64_t C, int cls, hipStream_t stream) {
+  const hipMemcpyKind kind = kind_of(cls);
+  for (uint64_t rank = 0; rank < cp.nchunks; ++rank) {
+    const ChunkId id = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(),
+                                   cp.funcs.data(), rank);
+    const Func &fn = cp.funcs[id.fl];
+    uint64_t pos = id.k * C;
+    uint64_t end = pos + C < fn.stream_bytes ? pos + C : fn.stream_bytes;
+    uint32_t x = find_xfer(cp.xfers.data(), fn, pos);
+    while (pos < end) {
+      const Xfer &X = cp.xfers[x];
+      uint64_t q = pos - X.stream_off;
+      uint64_t take = X.row_bytes * X.rows - q;
+      if (take > end - pos) take = end - pos;
+      if (X.rows == 1) {
+        FT_HIP(p, hipMemcpyAsync(reinterpret_cast<void *>(X.dst + q), reinterpret_cast<void *>(X.src + q),
+                                 take, kind, stream));
+      } else {
+        uint64_t r = q / X.row_bytes, c = q % X.row_bytes, left = take;
+        if (c != 0) {  // rest of a row that was begun by the previous chunk
+          uint64_t n = X.row_bytes - c < left ? X.row_bytes - c : left;
+          FT_HIP(p, hipMemcpyAsync(reinterpret_cast<void *>(X.dst + r * X.dst_pitch + c),
+                                   reinterpret_cast<void *>(X.src + r * X.src_pitch + c), n, kind, stream));
+          left -= n;
+          r += 1;
+        }
+        uint64_t full = left / X.row_bytes;
+        if (full > 0) {
+          FT_HIP(p, hipMemcpy2DAsync(reinterpret_cast<void *>(X.dst + r * X.dst_pitch), X.dst_pitch,
+                                     reinterpret_cast<void *>(X.src + r * X.src_pitch), X.src_pitch,
+                                     X.row_bytes, full, kind, stream));
+          left -= full * X.row_bytes;
+          r += full;
+        }
+        if (left > 0)
+          FT_HIP(p, hipMemcpyAsync(reinterpret_cast<void *>(X.dst + r * X.dst_pitch),
+                                   reinterpret_cast<void *>(X.src + r * X.src_pitch), left, kind, stream));
+      }
+      pos += take;
+      ++x;
+    }
+  }
+  return FT_OK;
+}
+
+void retire(ft_pool *p, Job *job) {
+  for (uint64_t a : job->allocs) {
+    Allocation *al = p->slabs.at(a);
+    if (al && al->busy > 0) al->busy -= 1;
+  }
+  job->allocs.clear();
+}
+
+void release_device_side(ft_pool *p, Job *job) {
+  put_blob(p, job->tables);
+  const bool timing = (job->flags & FT_TIMING) != 0;
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    put_blob(p, job->run[c].log);
+    put_event(p, timing, job->run[c].ev_begin);
+    put_event(p, timing, job->run[c].ev_done);
+  }
+}
+
+int wait_locked(ft_pool *p, Job *job) {
+  DeviceGuard guard(p->device);
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    ClassRun &r = job->run[c];
+    if (!r.used) continue;
+    FT_HIP(p, hipEventSynchronize(r.ev_done));
+    if (job->flags & FT_TIMING) FT_HIP(p, hipEventElapsedTime(&r.device_ms, r.ev_begin, r.ev_done));
+    if ((job->flags & FT_LOG) && r.log.dev != nullptr) {
+      r.log_host.resize(r.table.ntickets);
+      FT_HIP(p, hipMemcpy(r.log_host.data(), r.log.dev, r.table.ntickets * sizeof(LogEntry),
+                          hipMemcpyDeviceToHost));
+    }
+  }
+  job->waited = true;
+  retire(p, job);
+  return FT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ft_pool_create(ft_pool **out, void *dev_base, uint64_t bytes, uint64_t slab_bytes, int device) {
+  if (out == nullptr) return FT_EINVAL;
+  int rc = SlabPool::check_segment(dev_base, bytes, slab_bytes);
+  if (rc != FT_OK) return rc;
+  if (device < 0) return FT_EINVAL;
+  ft_pool *p = new ft_pool(slab_bytes, device);
+  p->slabs.add_segment(dev_base, bytes);
+  *out = p;
+  return FT_OK;
+}
+
+int ft_pool_grow(ft_pool *p, void *dev_base, uint64_t bytes) {
+  if (p == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  return p->slabs.add_segment(dev_base, bytes);
+}
+
+int ft_pool_destroy(ft_pool *p) {
+  if (p == nullptr) return FT_EINVAL;
+  int rc = FT_OK;
+  {
+    std::lock_guard<std::mutex> lock(p->mu);
+    DeviceGuard guard(p->device);
+    for (auto &kv : p->jobs) {
+      Job *job = kv.second.get();
+      if (!job->waited && wait_locked(p, job) != FT_OK) rc = FT_EHIP;
+      release_device_side(p, job);
+    }
+    p->jobs.clear();
+    for (Blob &b : p->free_blobs) {
+      (void)hipFree(b.dev);
+      (void)hipHostFree(b.host);
+    }
+    for (Blob &b : p->free_dev_blobs) (void)hipFree(b.dev);
+    for (hipEvent_t e : p->free_events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : p->free_timing_events) (void)hipEventDestroy(e);
+    if (p->dev_ready)
+      for (int c = 0; c < FT_NCLASS; ++c) (void)hipStreamDestroy(p->streams[c]);
+  }
+  delete p;
+  return rc;
+}
+
+int ft_slab_alloc(ft_pool *p, uint64_t nbytes, ft_off_t *off_out) {
+  if (p == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  return p->slabs.alloc(nbytes, off_out);
+}
+
+int ft_slab_free(ft_pool *p, ft_off_t off) {
+  if (p == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  return p->slabs.free(off);
+}
+
+void *ft_pool_ptr(ft_pool *p, ft_off_t off) {
+  if (p == nullptr) return nullptr;
+  std::lock_guard<std::mutex> lock(p->mu);
+  return p->slabs.ptr(off);
+}
+
+int ft_host_window_add(ft_pool *p, void *host_base, uint64_t bytes) {
+  if (p == nullptr || host_base == nullptr || bytes == 0) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  p->windows.push_back(HostWindow{reinterpret_cast<uint64_t>(host_base), bytes});
+  return FT_OK;
+}
+
+int ft_set_tuning(ft_pool *p, int link_class, uint32_t workgroups, uint64_t tile_bytes) {
+  if (p == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  p->tuning[link_class].workgroups = workgroups;
+  p->tuning[link_class].tile_bytes = tile_bytes;
+  return FT_OK;
+}
+
+int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
+                        uint32_t nfunc, uint64_t chunk_bytes, uint32_t flags, void *hip_stream,
+                        ft_job_t *job_out) {
+  if (p == nullptr || job_out == nullptr) return FT_EINVAL;
+  const auto t0 = std::chrono::steady_clock::now();
+  std::lock_guard<std::mutex> lock(p->mu);
+  SubmitPlan plan;
+  int rc = plan_submit(p->slabs, p->windows, descs, ndesc, weights, nfunc, chunk_bytes, flags, &plan);
+  if (rc != FT_OK) return rc;
+
+  std::unique_ptr<Job> job(new Job());
+  job->flags = flags;
+  job->keep = (flags & (FT_KEEP | FT_LOG | FT_TIMING)) != 0;
+  job->chunk_bytes = chunk_bytes;
+  bool any = false;
+  for (int c = 0; c < FT_NCLASS; ++c) any = any || plan.cls[c].nchunks > 0;
+
+  if (any) {
+    DeviceGuard guard(p->device);
+    rc = ensure_device(p);
+    if (rc != FT_OK) return rc;
+    hipStream_t user = static_cast<hipStream_t>(hip_stream);
+    const bool timing = (flags & FT_TIMING) != 0;
+    const bool dma = (flags & FT_PATH_DMA) != 0;
+
+    // lay the tables of all classes out in one blob
+    Layout lay[FT_NCLASS];
+    uint64_t total = 0;
+    for (int c = 0; c < FT_NCLASS; ++c) {
+      lay[c] = layout_of(plan.cls[c], total);
+      if (plan.cls[c].nchunks > 0) total = lay[c].end;
+    }
+    // every failure from here on must hand back what it took
+    auto fail = [&](int code) {
+      // work already queued may still read the tables: drain it before they are recycled
+      if (job->tables.dev != nullptr) (void)hipDeviceSynchronize();
+      release_device_side(p, job.get());
+      return code;
+    };
+    rc = get_blob(p, total, true, &job->tables);
+    if (rc != FT_OK) return fail(rc);
+    std::memset(job->tables.host, 0, total);
+    for (int c = 0; c < FT_NCLASS; ++c) {
+      ClassPlan &cp = plan.cls[c];
+      if (cp.nchunks == 0) continue;
+      ClassRun &r = job->run[c];
+      r.used = true;
+      char *h = job->tables.host, *d = job->tables.dev;
+      std::memcpy(h + lay[c].phases, cp.phases.data(), cp.phases.size() * sizeof(Phase));
+      std::memcpy(h + lay[c].slots, cp.slots.data(), cp.slots.size() * sizeof(Slot));
+      std::memcpy(h + lay[c].funcs, cp.funcs.data(), cp.funcs.size() * sizeof(Func));
+      std::memcpy(h + lay[c].xfers, cp.xfers.data(), cp.xfers.size() * sizeof(Xfer));
+      const Tuning &tn = p->tuning[c];
+      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c), &r.tile_bytes, &r.tiles_per_chunk);
+      ClassTable &T = r.table;
+      T.phases = reinterpret_cast<const Phase *>(d + lay[c].phases);
+      T.slots = reinterpret_cast<const Slot *>(d + lay[c].slots);
+      T.funcs = reinterpret_cast<const Func *>(d + lay[c].funcs);
+      T.xfers = reinterpret_cast<const Xfer *>(d + lay[c].xfers);
+      T.ticket = reinterpret_cast<unsigned long long *>(d + lay[c].ticket);
+      T.log = nullptr;
+      T.nchunks = cp.nchunks;
+      T.ntickets = cp.nchunks * r.tiles_per_chunk;
+      T.chunk_bytes = chunk_bytes;
+      T.tile_bytes = r.tile_bytes;
+      T.tiles_per_chunk = r.tiles_per_chunk;
+      T.nphases = (uint32_t)cp.phases.size();
+      T.nfuncs = (uint32_t)cp.funcs.size();
+      T._pad = 0;
+      uint64_t wg = tn.workgroups ? tn.workgroups : default_workgroups(p, c);
+      if (wg > T.ntickets) wg = T.ntickets;
+      r.workgroups = dma ? 0 : (uint32_t)wg;
+      if ((flags & FT_LOG) && !dma) {
+        rc = get_blob(p, T.ntickets * sizeof(LogEntry), false, &r.log);
+        if (rc != FT_OK) return fail(rc);
+        T.log = reinterpret_cast<LogEntry *>(r.log.dev);
+      }
+      rc = get_event(p, timing, &r.ev_done);
+      if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_begin);
+      if (rc != FT_OK) return fail(rc);
+    }
+
+    // tables (and the zeroed ticket counters) travel on the caller's stream, then fork
+    hipEvent_t fork = nullptr;
+    rc = get_event(p, false, &fork);
+    if (rc != FT_OK) return fail(rc);
+    auto hip_fail = [&](hipError_t e, const char *what) {
+      p->hip_error = std::string(what) + ": " + hipGetErrorString(e);
+      put_event(p, false, fork);
+      return fail(FT_EHIP);
+    };
+    hipError_t e = hipMemcpyAsync(job->tables.dev, job->tables.host, total, hipMemcpyHostToDevice, user);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(tables)");
+    e = hipEventRecord(fork, user);
+    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(fork)");
+    for (int c = 0; c < FT_NCLASS; ++c) {
+      ClassRun &r = job->run[c];
+      if (!r.used) continue;
+      hipStream_t s = p->streams[c];
+      e = hipStreamWaitEvent(s, fork, 0);
+      if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(fork)");
+      if (timing) {
+        e = hipEventRecord(r.ev_begin, s);
+        if (e != hipSuccess) return hip_fail(e, "hipEventRecord(begin)");
+      }
+      if (dma) {
+        rc = run_dma(p, plan.cls[c], chunk_bytes, c, s);
+        if (rc != FT_OK) {
+          put_event(p, false, fork);
+          return fail(rc);
+        }
+      } else {
+        e = launch_copy(r.table, r.workgroups, true, s);
+        if (e != hipSuccess) return hip_fail(e, "launch_copy");
+      }
+      e = hipEventRecord(r.ev_done, s);
+      if (e != hipSuccess) return hip_fail(e, "hipEventRecord(done)");
+      if (!(flags & FT_DETACHED)) {
+        e = hipStreamWaitEvent(user, r.ev_done, 0);
+        if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(join)");
+      }
+    }
+    put_event(p, false, fork);
+  }
+
+  for (int c = 0; c < FT_NCLASS; ++c) job->run[c].plan = std::move(plan.cls[c]);
+  for (uint64_t a : plan.allocs) {
+    Allocation *al = p->slabs.at(a);
+    if (al) al->busy += 1;
+  }
+  job->allocs = plan.allocs;
+  job->id = p->next_job++;
+  *job_out = job->id;
+  job->host_submit_us =
+      std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+  p->jobs[job->id] = std::move(job);
+  return FT_OK;
+}
+
+int ft_wait(ft_pool *p, ft_job_t id) {
+  if (p == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || it->second->waited) return FT_EINVAL;
+  Job *job = it->second.get();
+  int rc = wait_locked(p, job);
+  if (rc != FT_OK) return rc;
+  if (!job->keep) {
+    release_device_side(p, job);
+    p->jobs.erase(it);
+  }
+  return FT_OK;
+}
+
+int ft_job_release(ft_pool *p, ft_job_t id) {
+  if (p == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->waited) return FT_EINVAL;
+  release_device_side(p, it->second.get());
+  p->jobs.erase(it);
+  return FT_OK;
+}
+
+int ft_job_stats(ft_pool *p, ft_job_t id, ft_job_stats_t *out) {
+  if (p == nullptr || out == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end()) return FT_EINVAL;
+  const Job *job = it->second.get();
+  std::memset(out, 0, sizeof(*out));
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    const ClassRun &r = job->run[c];
+    ft_class_stats &s = out->cls[c];
+    s.payload_bytes = r.plan.payload;
+    s.chunks = r.plan.nchunks;
+    s.tickets = r.used ? r.table.ntickets : 0;
+    s.tile_bytes = r.tile_bytes;
+    s.workgroups = r.workgroups;
+    s.device_ms = r.device_ms;
+  }
+  out->host_submit_us = job->host_submit_us;
+  return FT_OK;
+}
+
+int ft_job_schedule(ft_pool *p, ft_job_t id, int link_class, uint32_t *func_out, uint32_t *chunk_out,
+                    uint64_t cap, uint64_t *n_out) {
+  if (p == nullptr || n_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
+  if (cap != 0 && (func_out == nullptr || chunk_out == nullptr)) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->keep) return FT_EINVAL;
+  Job *job = it->second.get();
+  ClassRun &r = job->run[link_class];
+  *n_out = r.plan.nchunks;
+  uint64_t n = r.plan.nchunks < cap ? r.plan.nchunks : cap;
+  if (!r.used || n == 0) return FT_OK;
+  DeviceGuard guard(p->device);
+  uint32_t *dev = nullptr;
+  FT_HIP(p, hipMalloc(reinterpret_cast<void **>(&dev), 2 * n * sizeof(uint32_t)));
+  hipStream_t s = p->streams[link_class];  // ordered after the job's own kernel and table upload
+  hipError_t e = launch_decode(r.table, dev, dev + n, n, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e == hipSuccess) e = hipMemcpy(func_out, dev, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
+  if (e == hipSuccess) e = hipMemcpy(chunk_out, dev + n, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
+  (void)hipFree(dev);
+  if (e != hipSuccess) {
+    p->hip_error = std::string("ft_job_schedule: ") + hipGetErrorString(e);
+    return FT_EHIP;
+  }
+  return FT_OK;
+}
+
+int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, uint64_t *t_end_ns,
+               uint32_t *func_out, uint32_t *chunk_out, uint32_t *bytes_out, uint64_t cap, uint64_t *n_out) {
+  if (p == nullptr || n_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->waited || !(it->second->flags & FT_LOG)) return FT_EINVAL;
+  const Job *job = it->second.get();
+  const ClassRun &r = job->run[link_class];
+  const uint64_t nt = r.log_host.size();
+  *n_out = nt;
+  const ClassPlan &cp = r.plan;
+  const double ns_per_tick = p->clock_khz > 0 ? 1.0e6 / p->clock_khz : 10.0;
+  for (uint64_t t = 0; t < nt && t < cap; ++t) {
+    if (t_begin_ns) t_begin_ns[t] = (uint64_t)(r.log_host[t].t_begin * ns_per_tick);
+    if (t_end_ns) t_end_ns[t] = (uint64_t)(r.log_host[t].t_end * ns_per_tick);
+    if (func_out || chunk_out || bytes_out) {
+      const uint64_t rank = t / r.tiles_per_chunk, ti = t % r.tiles_per_chunk;
+      const ChunkId cid = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(),
+                                      cp.funcs.data(), rank);
+      const Func &fn = cp.funcs[cid.fl];
+      uint64_t lo = ti * r.tile_bytes, hi = lo + r.tile_bytes;
+      if (hi > job->chunk_bytes) hi = job->chunk_bytes;
+      uint64_t b0 = cid.k * job->chunk_bytes + lo, b1 = cid.k * job->chunk_bytes + hi;
+      if (b1 > fn.stream_bytes) b1 = fn.stream_bytes;
+      if (b0 > b1) b0 = b1;
+      if (func_out) func_out[t] = fn.func;
+      if (chunk_out) chunk_out[t] = (uint32_t)cid.k;
+      if (bytes_out) bytes_out[t] = (uint32_t)(b1 - b0);
+    }
+  }
+  return FT_OK;
+}
+
+int ft_plan_schedule(const uint64_t *stream_bytes, const uint32_t *weights, uint32_t nfunc,
+                     uint64_t chunk_bytes, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap,
+                     uint64_t *n_out) {
+  if (stream_bytes == nullptr || weights == nullptr || n_out == nullptr || nfunc == 0) return FT_EINVAL;
+  if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return FT_EINVAL;
+  if (cap != 0 && (func_out == nullptr || chunk_out == nullptr)) return FT_EINVAL;
+  std::vector<Func> funcs;
+  for (uint32_t f = 0; f < nfunc; ++f) {
+    if (weights[f] == 0) return FT_EINVAL;
+    if (stream_bytes[f] == 0) continue;
+    Func fn{};
+    fn.stream_bytes = stream_bytes[f];
+    fn.nchunks = stream_bytes[f] / chunk_bytes + (stream_bytes[f] % chunk_bytes != 0);
+    fn.func = f;
+    fn.weight = weights[f];
+    funcs.push_back(fn);
+  }
+  std::vector<Phase> phases;
+  std::vector<Slot> slots;
+  uint64_t n = 0;
+  int rc = build_phases(funcs, phases, slots, &n);
+  if (rc != FT_OK) return rc;
+  *n_out = n;
+  for (uint64_t rank = 0; rank < n && rank < cap; ++rank) {
+    const ChunkId id = decode_rank(phases.data(), (uint32_t)phases.size(), slots.data(), funcs.data(), rank);
+    func_out[rank] = funcs[id.fl].func;
+    chunk_out[rank] = (uint32_t)id.k;
+  }
+  return FT_OK;
+}
+
+int ft_plain_copy(void *dst, const void *src, uint64_t bytes, uint32_t workgroups, void *hip_stream) {
+  if (bytes == 0) return FT_OK;
+  if (dst == nullptr || src == nullptr || bytes % 16 != 0) return FT_EINVAL;
+  if (reinterpret_cast<uintptr_t>(dst) % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0) return FT_EINVAL;
+  hipError_t e = launch_plain_copy(dst, src, bytes, workgroups, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FT_OK : FT_EHIP;
+}
+
+const char *ft_strerror(int rc) {
+  switch (rc) {
+    case FT_OK: return "ok";
+    case FT_EINVAL: return "invalid argument";
+    case FT_ENOMEM: return "no run of free slabs";
+    case FT_ERANGE: return "range outside a live allocation or host window";
+    case FT_EOVERLAP: return "a destination byte is written twice or also read";
+    case FT_EBUSY: return "allocation is in use by a job that has not been waited for";
+    case FT_EHIP: return "HIP runtime error";
+    default: return "unknown code";
+  }
+}
+
+const char *ft_last_hip_error(ft_pool *p) { return p ? p->hip_error.c_str() : ""; }
+
+}  // extern "C"

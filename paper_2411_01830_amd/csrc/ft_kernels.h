@@ -1,0 +1,17 @@
+// Launchers of the HIP kernels (defined in ft_kernels.hip), private to the library.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include "ft_tables.h"
+
+namespace ft {
+
+// Persistent copy kernel of one link class. T.ticket must be zero when it starts.
+hipError_t launch_copy(const ClassTable &T, uint32_t workgroups, bool nontemporal, hipStream_t stream);
+// Decode every chunk rank with the device function the copy kernel uses (test hook).
+hipError_t launch_decode(const ClassTable &T, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap,
+                         hipStream_t stream);
+// Plain grid-stride copy, no tickets and no tables.
+hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, uint32_t workgroups, hipStream_t stream);
+
+}  // namespace ft

@@ -1,0 +1,321 @@
+#include "ft_plan.h"
+
+#include <algorithm>
+#include <numeric>
+
+namespace ft {
+
+void tile_shape(uint64_t chunk_bytes, uint64_t want_tile, uint64_t *tile_bytes, uint32_t *tiles_per_chunk) {
+  if (want_tile < 16) want_tile = 16;
+  uint64_t n = (chunk_bytes + want_tile - 1) / want_tile;
+  if (n > 0xffffu) n = 0xffffu;
+  uint64_t tile = (chunk_bytes + n - 1) / n;
+  tile = (tile + 15) & ~15ull;
+  *tile_bytes = tile;
+  *tiles_per_chunk = (uint32_t)((chunk_bytes + tile - 1) / tile);
+}
+
+namespace {
+
+// slot a before slot b: smaller finish tag (i+1)/w, ties to the lower function
+struct SlotLess {
+  const std::vector<Func> *funcs;
+  bool operator()(const Slot &a, const Slot &b) const {
+    uint64_t lhs = (uint64_t)(a.i + 1) * (*funcs)[b.fl].weight;
+    uint64_t rhs = (uint64_t)(b.i + 1) * (*funcs)[a.fl].weight;
+    if (lhs != rhs) return lhs < rhs;
+    return a.fl < b.fl;
+  }
+};
+
+}  // namespace
+
+int build_phases(std::vector<Func> &funcs, std::vector<Phase> &phases, std::vector<Slot> &slots,
+                 uint64_t *nchunks_out) {
+  phases.clear();
+  slots.clear();
+  *nchunks_out = 0;
+  const uint32_t F = (uint32_t)funcs.size();
+  if (F == 0) return FT_OK;
+  uint32_t g = 0;
+  for (auto &f : funcs) g = std::gcd(g, f.weight);
+  for (auto &f : funcs) f.weight /= g;
+
+  std::vector<uint64_t> q(F), r(F);
+  std::vector<char> present(F, 1);
+  uint64_t W = 0;
+  for (uint32_t i = 0; i < F; ++i) {
+    q[i] = funcs[i].nchunks / funcs[i].weight;
+    r[i] = funcs[i].nchunks % funcs[i].weight;
+    W += funcs[i].weight;
+  }
+  // A round can hold at most min(W, N) chunks, and there are at most 2F+1 phases.
+  uint64_t N = 0;
+  for (auto &f : funcs) N += f.nchunks;
+  if (std::min<uint64_t>(W, N) > kMaxSlots) return FT_EINVAL;
+
+  // full round of the present set, sorted once, then only filtered
+  std::vector<Slot> cur;
+  bool cur_valid = false;
+  auto rebuild = [&]() -> int {
+    uint64_t need = 0;
+    for (uint32_t i = 0; i < F; ++i)
+      if (present[i]) need += funcs[i].weight;
+    if (need > kMaxSlots) return FT_EINVAL;
+    cur.clear();
+    cur.reserve(need);
+    for (uint32_t i = 0; i < F; ++i)
+      if (present[i])
+        for (uint32_t j = 0; j < funcs[i].weight; ++j) cur.push_back(Slot{i, j});
+    std::sort(cur.begin(), cur.end(), SlotLess{&funcs});
+    cur_valid = true;
+    return FT_OK;
+  };
+
+  uint64_t R = 0, rank = 0;
+  uint32_t left = F;
+  while (left > 0) {
+    uint64_t Q = ~0ull;
+    for (uint32_t i = 0; i < F; ++i)
+      if (present[i]) Q = std::min(Q, q[i]);
+    if (Q > R) {
+      // rounds R .. Q-1: every present function fills its whole share
+      if (!cur_valid) {
+        int rc = rebuild();
+        if (rc != FT_OK) return rc;
+      }
+      if (slots.size() + cur.size() > kMaxSlots) return FT_EINVAL;
+      Phase ph;
+      ph.rank_base = rank;
+      ph.round_base = R;
+      ph.slot_off = (uint32_t)slots.size();
+      ph.nslots = (uint32_t)cur.size();
+      slots.insert(slots.end(), cur.begin(), cur.end());
+      phases.push_back(ph);
+      rank += (uint64_t)ph.nslots * (Q - R);
+      R = Q;
+    }
+    // round R: functions with q == R either are gone (r == 0) or fill r of their w slots
+    bool any_partial = false;
+    for (uint32_t i = 0; i < F; ++i)
+      if (present[i] && q[i] == R) {
+        if (r[i] == 0) {
+          present[i] = 0;
+          --left;
+          cur_valid = false;
+        } else {
+          any_partial = true;
+        }
+      }
+    if (!any_partial) continue;
+    // one irregular round. When the weights dwarf the chunk counts the full round may
+    // be far larger than what is left, so build from the remaining chunks directly.
+    std::vector<Slot> irr;
+    uint64_t need = 0;
+    for (uint32_t i = 0; i < F; ++i)
+      if (present[i]) need += (q[i] == R) ? r[i] : funcs[i].weight;
+    if (slots.size() + need > kMaxSlots) return FT_EINVAL;
+    irr.reserve(need);
+    for (uint32_t i = 0; i < F; ++i)
+      if (present[i]) {
+        uint32_t cnt = (q[i] == R) ? (uint32_t)r[i] : funcs[i].weight;
+        for (uint32_t j = 0; j < cnt; ++j) irr.push_back(Slot{i, j});
+      }
+    std::sort(irr.begin(), irr.end(), SlotLess{&funcs});
+    Phase ph;
+    ph.rank_base = rank;
+    ph.round_base = R;
+    ph.slot_off = (uint32_t)slots.size();
+    ph.nslots = (uint32_t)irr.size();
+    slots.insert(slots.end(), irr.begin(), irr.end());
+    phases.push_back(ph);
+    rank += ph.nslots;
+    for (uint32_t i = 0; i < F; ++i)
+      if (present[i] && q[i] == R) {
+        present[i] = 0;
+        --left;
+        cur_valid = false;
+      }
+    R += 1;
+  }
+  *nchunks_out = rank;
+  return FT_OK;
+}
+
+namespace {
+
+bool mul_overflow(uint64_t a, uint64_t b, uint64_t *out) { return __builtin_mul_overflow(a, b, out); }
+bool add_overflow(uint64_t a, uint64_t b, uint64_t *out) { return __builtin_add_overflow(a, b, out); }
+
+// bytes from the first to one past the last byte touched; false on wrap
+bool extent_of(uint64_t row_bytes, uint64_t rows, uint64_t pitch, uint64_t *out) {
+  uint64_t span;
+  if (rows == 1) {
+    *out = row_bytes;
+    return true;
+  }
+  if (mul_overflow(rows - 1, pitch, &span)) return false;
+  return !add_overflow(span, row_bytes, out);
+}
+
+struct Interval {
+  uint64_t lo, hi;
+};
+
+void push_rows(std::vector<Interval> &v, uint64_t base, uint64_t row_bytes, uint64_t rows, uint64_t pitch) {
+  if (rows == 1 || pitch == row_bytes) {
+    v.push_back(Interval{base, base + row_bytes * rows});
+    return;
+  }
+  for (uint64_t r = 0; r < rows; ++r) v.push_back(Interval{base + r * pitch, base + r * pitch + row_bytes});
+}
+
+bool overlaps(std::vector<Interval> &dst, std::vector<Interval> &src) {
+  auto by_lo = [](const Interval &a, const Interval &b) { return a.lo < b.lo; };
+  std::sort(dst.begin(), dst.end(), by_lo);
+  for (size_t i = 1; i < dst.size(); ++i)
+    if (dst[i].lo < dst[i - 1].hi) return true;
+  // destinations are disjoint and sorted, so their ends are sorted as well
+  for (const Interval &s : src) {
+    auto it = std::upper_bound(dst.begin(), dst.end(), s.lo,
+                               [](uint64_t v, const Interval &d) { return v < d.hi; });
+    if (it != dst.end() && it->lo < s.hi) return true;
+  }
+  return false;
+}
+
+}  // namespace
+
+int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft_desc *descs,
+                uint32_t ndesc, const uint32_t *weights, uint32_t nfunc, uint64_t chunk_bytes,
+                uint32_t flags, SubmitPlan *out) {
+  // ---- pass 1: malformed arguments
+  if (nfunc == 0 || weights == nullptr) return FT_EINVAL;
+  if (ndesc != 0 && descs == nullptr) return FT_EINVAL;
+  for (uint32_t f = 0; f < nfunc; ++f)
+    if (weights[f] == 0) return FT_EINVAL;
+  if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return FT_EINVAL;
+  for (uint32_t i = 0; i < ndesc; ++i) {
+    const ft_desc &d = descs[i];
+    if (d.func >= nfunc || d.flags != 0) return FT_EINVAL;
+    if (d.src_space > FT_POOL || d.dst_space > FT_POOL) return FT_EINVAL;
+    if (d.src_space == FT_HOST && d.dst_space == FT_HOST) return FT_EINVAL;
+    if (d.row_bytes == 0 || d.rows == 0) return FT_EINVAL;
+    if (d.rows > 1 && (d.src_pitch < d.row_bytes || d.dst_pitch < d.row_bytes)) return FT_EINVAL;
+  }
+
+  // ---- pass 2: ranges; resolve both sides to device-visible addresses
+  std::vector<Xfer> resolved(ndesc);
+  std::vector<uint64_t> used;
+  for (uint32_t i = 0; i < ndesc; ++i) {
+    const ft_desc &d = descs[i];
+    Xfer x;
+    x.row_bytes = d.row_bytes;
+    x.rows = d.rows;
+    x.src_pitch = d.rows > 1 ? d.src_pitch : d.row_bytes;
+    x.dst_pitch = d.rows > 1 ? d.dst_pitch : d.row_bytes;
+    x.stream_off = 0;
+    x._pad = 0;
+    uint64_t payload;
+    if (mul_overflow(d.row_bytes, d.rows, &payload)) return FT_ERANGE;
+    for (int side = 0; side < 2; ++side) {
+      uint64_t off = side == 0 ? d.src : d.dst;
+      uint8_t space = side == 0 ? d.src_space : d.dst_space;
+      uint64_t ext, end;
+      if (!extent_of(d.row_bytes, d.rows, side == 0 ? x.src_pitch : x.dst_pitch, &ext)) return FT_ERANGE;
+      if (add_overflow(off, ext, &end)) return FT_ERANGE;
+      uint64_t addr;
+      if (space == FT_POOL) {
+        uint64_t start;
+        if (pool.owner(off, ext, &start) == nullptr) return FT_ERANGE;
+        used.push_back(start);
+        addr = reinterpret_cast<uint64_t>(pool.ptr(off));
+      } else {
+        if (!windows.empty()) {
+          bool inside = false;
+          for (const HostWindow &w : windows)
+            if (off >= w.base && end <= w.base + w.bytes) inside = true;
+          if (!inside) return FT_ERANGE;
+        } else if (off == 0) {
+          return FT_ERANGE;
+        }
+        addr = off;
+      }
+      if (side == 0) x.src = addr; else x.dst = addr;
+    }
+    resolved[i] = x;
+  }
+
+  // ---- pass 3: exact aliasing check, on request
+  if (flags & FT_VALIDATE) {
+    for (int space = 0; space < 2; ++space) {
+      std::vector<Interval> dst, src;
+      for (uint32_t i = 0; i < ndesc; ++i) {
+        const ft_desc &d = descs[i];
+        const Xfer &x = resolved[i];
+        // compare in the caller's own coordinates of that space (offsets or addresses)
+        if (d.dst_space == space) push_rows(dst, d.dst, x.row_bytes, x.rows, x.dst_pitch);
+        if (d.src_space == space) push_rows(src, d.src, x.row_bytes, x.rows, x.src_pitch);
+      }
+      if (overlaps(dst, src)) return FT_EOVERLAP;
+    }
+  }
+
+  // ---- split by class, per-function streams in submission order
+  std::sort(used.begin(), used.end());
+  used.erase(std::unique(used.begin(), used.end()), used.end());
+  out->allocs = used;
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    ClassPlan &cp = out->cls[c];
+    cp = ClassPlan();
+    std::vector<uint64_t> stream(nfunc, 0);
+    std::vector<uint32_t> count(nfunc, 0);
+    auto class_of = [](const ft_desc &d) {
+      return d.src_space == FT_HOST ? FT_H2P : (d.dst_space == FT_HOST ? FT_P2H : FT_P2P);
+    };
+    for (uint32_t i = 0; i < ndesc; ++i)
+      if (class_of(descs[i]) == c) {
+        count[descs[i].func] += 1;
+        uint64_t pay = resolved[i].row_bytes * resolved[i].rows;
+        if (add_overflow(stream[descs[i].func], pay, &stream[descs[i].func])) return FT_ERANGE;
+      }
+    std::vector<int64_t> slot_of(nfunc, -1);
+    uint32_t off = 0;
+    for (uint32_t f = 0; f < nfunc; ++f) {
+      if (stream[f] == 0) continue;
+      Func fn;
+      fn.stream_bytes = stream[f];
+      fn.nchunks = stream[f] / chunk_bytes + (stream[f] % chunk_bytes != 0);
+      fn.func = f;
+      fn.weight = weights[f];
+      fn.desc_off = off;
+      fn.ndesc = count[f];
+      off += count[f];
+      slot_of[f] = (int64_t)cp.funcs.size();
+      cp.funcs.push_back(fn);
+      cp.payload += stream[f];
+    }
+    cp.xfers.resize(off);
+    std::vector<uint32_t> fill(cp.funcs.size(), 0);
+    std::vector<uint64_t> run(cp.funcs.size(), 0);
+    for (uint32_t i = 0; i < ndesc; ++i)
+      if (class_of(descs[i]) == c) {
+        size_t fl = (size_t)slot_of[descs[i].func];
+        Xfer x = resolved[i];
+        // a pitched descriptor whose rows touch is one contiguous run
+        if (x.rows > 1 && x.src_pitch == x.row_bytes && x.dst_pitch == x.row_bytes) {
+          x.row_bytes *= x.rows;
+          x.rows = 1;
+          x.src_pitch = x.dst_pitch = x.row_bytes;
+        }
+        x.stream_off = run[fl];
+        run[fl] += x.row_bytes * x.rows;
+        cp.xfers[cp.funcs[fl].desc_off + fill[fl]++] = x;
+      }
+    int rc = build_phases(cp.funcs, cp.phases, cp.slots, &cp.nchunks);
+    if (rc != FT_OK) return rc;
+  }
+  return FT_OK;
+}
+
+}  // namespace ft

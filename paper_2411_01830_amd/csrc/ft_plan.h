@@ -1,0 +1,48 @@
+// Host planning of one submit: validation, split by link class, per-function byte
+// streams, and the phase/slot tables that encode the proportional chunk order of
+// Sec. 6.1 (see ft_tables.h for the encoding).
+#pragma once
+#include <stdint.h>
+#include <vector>
+
+#include "../../include/faastube.h"
+#include "ft_pool.h"
+#include "ft_tables.h"
+
+namespace ft {
+
+struct HostWindow {
+  uint64_t base;
+  uint64_t bytes;
+};
+
+struct ClassPlan {
+  std::vector<Phase> phases;
+  std::vector<Slot> slots;
+  std::vector<Func> funcs;
+  std::vector<Xfer> xfers;
+  uint64_t nchunks = 0;
+  uint64_t payload = 0;
+};
+
+struct SubmitPlan {
+  ClassPlan cls[FT_NCLASS];
+  std::vector<uint64_t> allocs;  // start offsets of the pool allocations referred to (unique)
+};
+
+// Phases and slots for the given functions (nchunks > 0, weight >= 1 each, ascending
+// caller function id). Divides the weights by their gcd in place. FT_EINVAL if the
+// slot tables would exceed kMaxSlots entries.
+constexpr uint64_t kMaxSlots = 1ull << 22;
+int build_phases(std::vector<Func> &funcs, std::vector<Phase> &phases, std::vector<Slot> &slots,
+                 uint64_t *nchunks_out);
+
+// Full planning of a submit. Returns FT_OK or the first error in the documented order.
+int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft_desc *descs,
+                uint32_t ndesc, const uint32_t *weights, uint32_t nfunc, uint64_t chunk_bytes,
+                uint32_t flags, SubmitPlan *out);
+
+// Bytes per ticket and tickets per chunk for a chunk size and a wanted tile size.
+void tile_shape(uint64_t chunk_bytes, uint64_t want_tile, uint64_t *tile_bytes, uint32_t *tiles_per_chunk);
+
+}  // namespace ft

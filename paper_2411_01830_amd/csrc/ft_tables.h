@@ -1,0 +1,114 @@
+// Device-resident tables of one link class of one job, and the rank decoder.
+//
+// The chunk order of Sec. 6.1 (proportional interleave; stride reading: sort every
+// chunk (f, j) by finish tag (j+1)/w_f, then by f) is not stored chunk by chunk.
+// Chunk tags of different functions do not interact, so the order decomposes into
+// rounds: round R holds the chunks whose tag lies in (R, R+1], i.e. chunks
+// [R*w_f, (R+1)*w_f) of every function that still has them. While the set of
+// functions that fill their whole share of a round stays the same, every round has
+// the same slot pattern. The host therefore emits a few phases, each a run of rounds
+// sharing one slot table, plus at most one single-round phase per function for the
+// round in which it runs dry part-way. Decoding a chunk rank is a binary search over
+// at most 2F+1 phases, one division and one table read.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define FT_HD __host__ __device__ inline
+#else
+#define FT_HD inline
+#endif
+
+namespace ft {
+
+struct Phase {
+  uint64_t rank_base;   // rank (ticket / tiles_per_chunk) of the phase's first chunk
+  uint64_t round_base;  // round number R of its first round
+  uint32_t slot_off;    // first entry in the slot table
+  uint32_t nslots;      // chunks per round in this phase (> 0)
+};
+
+struct Slot {
+  uint32_t fl;  // index into the class's function table
+  uint32_t i;   // chunk index inside the round: k = R * w + i
+};
+
+struct Func {
+  uint64_t stream_bytes;  // S_f
+  uint64_t nchunks;       // ceil(S_f / C)
+  uint32_t func;          // caller's function id
+  uint32_t weight;        // w_f divided by the gcd of the class's weights
+  uint32_t desc_off;      // first descriptor of this function in the class's table
+  uint32_t ndesc;
+};
+
+// One transfer with both sides resolved to device-visible virtual addresses.
+struct Xfer {
+  uint64_t src;
+  uint64_t dst;
+  uint64_t row_bytes;
+  uint64_t rows;       // 1 => contiguous (pitches unused)
+  uint64_t src_pitch;
+  uint64_t dst_pitch;
+  uint64_t stream_off;  // payload bytes of the function's earlier descriptors
+  uint64_t _pad;
+};
+
+struct LogEntry {
+  uint64_t t_begin;
+  uint64_t t_end;
+};
+
+// Everything one class's kernel needs; passed by value as the kernel argument.
+struct ClassTable {
+  const Phase *phases;
+  const Slot *slots;
+  const Func *funcs;
+  const Xfer *xfers;
+  unsigned long long *ticket;  // device counter, zero at launch
+  LogEntry *log;               // one per ticket, or null
+  uint64_t nchunks;            // N
+  uint64_t ntickets;           // N * tiles_per_chunk
+  uint64_t chunk_bytes;        // C
+  uint64_t tile_bytes;         // bytes per ticket, multiple of 16
+  uint32_t tiles_per_chunk;
+  uint32_t nphases;
+  uint32_t nfuncs;
+  uint32_t _pad;
+};
+
+struct ChunkId {
+  uint32_t fl;  // index into funcs
+  uint64_t k;   // chunk index within that function's stream
+};
+
+// rank -> (function, chunk). rank < nchunks.
+FT_HD ChunkId decode_rank(const Phase *phases, uint32_t nphases, const Slot *slots,
+                          const Func *funcs, uint64_t rank) {
+  uint32_t lo = 0, hi = nphases;  // last phase with rank_base <= rank
+  while (hi - lo > 1) {
+    uint32_t mid = (lo + hi) >> 1;
+    if (phases[mid].rank_base <= rank) lo = mid; else hi = mid;
+  }
+  const Phase ph = phases[lo];
+  uint64_t rel = rank - ph.rank_base;
+  uint64_t round = rel / ph.nslots;
+  uint32_t s = (uint32_t)(rel - round * ph.nslots);
+  const Slot sl = slots[ph.slot_off + s];
+  ChunkId id;
+  id.fl = sl.fl;
+  id.k = (ph.round_base + round) * (uint64_t)funcs[sl.fl].weight + sl.i;
+  return id;
+}
+
+// Descriptor of function fn that holds stream byte `pos` (pos < stream_bytes).
+FT_HD uint32_t find_xfer(const Xfer *xfers, const Func &fn, uint64_t pos) {
+  uint32_t lo = fn.desc_off, hi = fn.desc_off + fn.ndesc;
+  while (hi - lo > 1) {
+    uint32_t mid = (lo + hi) >> 1;
+    if (xfers[mid].stream_off <= pos) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+}  // namespace ft

@@ -1,0 +1,113 @@
+"""Device and pinned memory for the engine, owned through PyTorch.
+
+``GpuEngine`` exposes the engine calls in the shape the workload runner expects
+(host addresses are offsets into one pinned arena; the pool's segments are uint8
+device tensors). PyTorch is used for memory, streams and read-back only; every
+transfer goes through the C ABI.
+"""
+import numpy as np
+import torch
+
+from . import binding as ft
+
+HOST_FILL = 0x5A
+POOL_FILL = 0xA5
+
+
+class GpuEngine:
+    def __init__(self, device=0, register_window=True):
+        if not torch.cuda.is_available():
+            raise RuntimeError("GpuEngine needs a GPU; the engine has no CPU path")
+        self.device = device
+        self.dev = torch.device("cuda", device)
+        self.pool = None
+        self.segments = []          # (tensor, logical first byte)
+        self.total = 0
+        self.host = None
+        self.host_np = None
+        self.register_window = register_window
+        self.default_flags = 0
+
+    # ---- caller-owned memory ---------------------------------------------------
+    def host_arena(self, nbytes, fill=HOST_FILL):
+        nbytes = max(int(nbytes), 4096)
+        self.host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        self.host_np = self.host.numpy()
+        if fill is not None:
+            self.host_np[:] = fill
+        if self.pool is not None and self.register_window:
+            ft.host_window_add(self.pool, self.host.data_ptr(), nbytes)
+
+    def write_host(self, off, data):
+        self.host_np[off:off + len(data)] = data
+
+    def read_host(self, off, n):
+        return self.host_np[off:off + n].copy()
+
+    def _segment(self, nbytes, fill):
+        t = torch.empty(int(nbytes), dtype=torch.uint8, device=self.dev)
+        if fill is not None:
+            t.fill_(fill)
+        assert t.data_ptr() % 256 == 0
+        return t
+
+    def _locate(self, off):
+        for t, first in self.segments:
+            if first <= off < first + t.numel():
+                return t, off - first
+        raise IndexError(off)
+
+    def write_pool(self, off, data):
+        t, o = self._locate(off)
+        t[o:o + len(data)].copy_(torch.from_numpy(np.ascontiguousarray(data)))
+
+    def read_pool(self, off, n):
+        t, o = self._locate(off)
+        return t[o:o + n].cpu().numpy()
+
+    # ---- pool --------------------------------------------------------------------
+    def pool_create(self, nbytes, slab_bytes, fill=POOL_FILL):
+        t = self._segment(nbytes, fill)
+        self._fill = fill
+        self.pool = ft.pool_create(t.data_ptr(), int(nbytes), int(slab_bytes), self.device)
+        self.segments = [(t, 0)]
+        self.total = int(nbytes)
+        if self.host is not None and self.register_window:
+            ft.host_window_add(self.pool, self.host.data_ptr(), self.host.numel())
+
+    def pool_grow(self, nbytes):
+        t = self._segment(nbytes, self._fill)
+        ft.pool_grow(self.pool, t.data_ptr(), int(nbytes))
+        self.segments.append((t, self.total))
+        self.total += int(nbytes)
+
+    def slab_alloc(self, nbytes):
+        return ft.slab_alloc(self.pool, int(nbytes))
+
+    def slab_free(self, off):
+        ft.slab_free(self.pool, int(off))
+
+    # ---- transfers ---------------------------------------------------------------
+    def submit(self, descs, weights, chunk_bytes, flags=0, stream=None):
+        d = np.array(descs, copy=True)
+        base = self.host.data_ptr() if self.host is not None else 0
+        d["src"][d["src_space"] == 0] += np.uint64(base)
+        d["dst"][d["dst_space"] == 0] += np.uint64(base)
+        s = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
+        return ft.submit_transfers(self.pool, d, weights, int(chunk_bytes),
+                                   int(flags) | self.default_flags, s)
+
+    def wait(self, job):
+        ft.wait(self.pool, job)
+
+    def job_schedule(self, job, cls):
+        return ft.job_schedule(self.pool, job, cls)
+
+    def close(self):
+        if self.pool is not None:
+            torch.cuda.synchronize(self.dev)
+            ft.pool_destroy(self.pool)
+            self.pool = None
+        self.segments = []
+        self.host = None
+        self.host_np = None

@@ -1,0 +1,261 @@
+"""Parity of the HIP path with the CPU oracle, byte for byte, through the C ABI."""
+import random
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import OracleEngine
+from workloads import configs, runner, make_descs, FT_HOST, FT_POOL
+from workloads import format as fmt
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2411_01830_amd import binding, harness
+    assert torch.cuda.is_available()
+    return binding, harness
+
+
+def _pool_image(eng):
+    import torch
+    return torch.cat([t for t, _ in eng.segments]).cpu().numpy()
+
+
+def _compare_images(orc, eng):
+    got_host = eng.host_np[:len(orc.host_mem)]
+    assert np.array_equal(got_host, orc.host_mem), "host image differs"
+    got_pool = _pool_image(eng)
+    assert got_pool.shape == orc.pool_mem.shape
+    if not np.array_equal(got_pool, orc.pool_mem):
+        bad = np.flatnonzero(got_pool != orc.pool_mem)
+        raise AssertionError(f"pool image differs at {len(bad)} bytes, first {bad[:8]}")
+
+
+SCALED = [("tiny", 0.3), ("traffic", 0.2), ("feature", 0.02), ("contended", 0.01), ("large_mixed", 0.008)]
+
+
+@pytest.mark.parametrize("name,scale", SCALED)
+@pytest.mark.parametrize("path", ["kernel", "dma"])
+def test_config_matches_oracle(gpu, name, scale, path):
+    binding, harness = gpu
+    print(f"case {name} scale {scale} path {path}", flush=True)
+    plan = configs.CONFIGS[name](scale)
+    orc = OracleEngine()
+    rec_o = runner.run_plan(plan, orc)
+    eng = harness.GpuEngine()
+    flags = fmt.FT_VALIDATE | binding.FT_KEEP | (fmt.FT_PATH_DMA if path == "dma" else 0)
+    try:
+        rec_g = runner.run_plan(plan, eng, flags=flags)
+        assert rec_g.alloc_off == rec_o.alloc_off
+        assert rec_g.grows == rec_o.grows
+        _compare_images(orc, eng)
+        for jname, job in rec_g.jobs.items():
+            for cls in (0, 1, 2):
+                assert eng.job_schedule(job, cls) == orc.job_schedule(rec_o.jobs[jname], cls), (jname, cls)
+            st = binding.job_stats(eng.pool, job)
+            for cls in (0, 1, 2):
+                assert st.cls[cls].payload_bytes == orc.job_class_bytes(rec_o.jobs[jname], cls)
+            binding.job_release(eng.pool, job)
+    finally:
+        eng.close()
+
+
+def _pair(gpu, host=1 << 20, pool=1 << 22, slab=4096, seed=0):
+    _, harness = gpu
+    orc, eng = OracleEngine(), harness.GpuEngine()
+    rng = np.random.default_rng(seed)
+    data = rng.integers(0, 256, host // 2, dtype=np.uint8)
+    for e in (orc, eng):
+        e.host_arena(host)
+        e.pool_create(pool, slab)
+        e.write_host(0, data)         # upper half of the arena keeps its fill: host destinations
+    return orc, eng, rng
+
+
+def _run_both(orc, eng, recs, w, C, flags=fmt.FT_VALIDATE):
+    d = make_descs(recs)
+    orc.wait(orc.submit(d, w, C))
+    eng.wait(eng.submit(d, w, C, flags))
+    _compare_images(orc, eng)
+
+
+def test_every_alignment_pair(gpu):
+    """src%16 x dst%16 for short, medium and long pieces, in all three classes; canaries
+    around every destination are part of the compared image."""
+    orc, eng, rng = _pair(gpu, host=1 << 25, pool=1 << 26, slab=16384)
+    try:
+        for n in (1, 7, 15, 16, 17, 31, 100, 255, 256, 257, 4095, 70001):
+            recs = []
+            hdst = (1 << 24)
+            for sa in range(16):
+                for da in range(16):
+                    cls = (sa + da) % 3
+                    span = n + 64
+                    if cls == 0:      # host -> pool
+                        b = orc.slab_alloc(span)
+                        assert eng.slab_alloc(span) == b
+                        recs.append(dict(func=(sa * 16 + da) % 3, src_space=FT_HOST, dst_space=FT_POOL,
+                                         src=1024 + sa + 16 * int(rng.integers(0, 1000)), dst=b + 16 + da, row_bytes=n))
+                    else:
+                        a = orc.slab_alloc(span)
+                        assert eng.slab_alloc(span) == a
+                        fill = rng.integers(0, 256, span, dtype=np.uint8)
+                        orc.write_pool(a, fill)
+                        eng.write_pool(a, fill)
+                        if cls == 1:  # pool -> host
+                            recs.append(dict(func=1, src_space=FT_POOL, dst_space=FT_HOST, src=a + 16 + sa,
+                                             dst=hdst + 16 + da, row_bytes=n))
+                            hdst += (n + 48 + 15) // 16 * 16
+                            assert hdst + n + 64 <= (1 << 25)
+                        else:
+                            b = orc.slab_alloc(span)
+                            assert eng.slab_alloc(span) == b
+                            recs.append(dict(func=2, src_space=FT_POOL, dst_space=FT_POOL, src=a + 16 + sa,
+                                             dst=b + 16 + da, row_bytes=n))
+            print(f"alignment case n={n} descs={len(recs)}", flush=True)
+            _run_both(orc, eng, recs, [1, 2, 3], 4096)
+            for off in list(orc.pool.allocs):
+                orc.slab_free(off)
+                eng.slab_free(off)
+    finally:
+        eng.close()
+
+
+def test_random_pitched_descriptors(gpu):
+    for seed in range(4):
+        orc, eng, rng = _pair(gpu, host=1 << 23, pool=1 << 27, slab=16384, seed=seed)
+        pyr = random.Random(seed)
+        try:
+            recs = []
+            hdst = 1 << 22
+            for i in range(60):
+                rows = pyr.choice([1, 2, 5, 33, 200])
+                rb = pyr.choice([1, 3, 16, 63, 64, 100, 255, 256, 257, 700, 1500, 3000])
+                sp = rb + pyr.choice([0, 0, 1, 13, 64, 500])
+                dp = rb + pyr.choice([0, 0, 1, 7, 64, 300])
+                es, ed = (rows - 1) * sp + rb, (rows - 1) * dp + rb
+                cls = pyr.choice([0, 1, 2, 2])
+                if cls == 0:
+                    if es + 16 > (1 << 22):
+                        continue
+                    b = orc.slab_alloc(ed + 32)
+                    assert eng.slab_alloc(ed + 32) == b
+                    recs.append(dict(func=i % 4, src_space=FT_HOST, dst_space=FT_POOL,
+                                     src=pyr.randint(0, (1 << 22) - es - 1), dst=b + pyr.randint(0, 31),
+                                     row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp))
+                    continue
+                a = orc.slab_alloc(es + 32)
+                assert eng.slab_alloc(es + 32) == a
+                fill = rng.integers(0, 256, es + 32, dtype=np.uint8)
+                orc.write_pool(a, fill)
+                eng.write_pool(a, fill)
+                if cls == 1:
+                    if hdst + ed + 64 > (1 << 23):
+                        continue
+                    recs.append(dict(func=i % 4, src_space=FT_POOL, dst_space=FT_HOST, src=a + pyr.randint(0, 31),
+                                     dst=hdst + pyr.randint(0, 15), row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp))
+                    hdst += ed + 32
+                else:
+                    b = orc.slab_alloc(ed + 32)
+                    assert eng.slab_alloc(ed + 32) == b
+                    recs.append(dict(func=i % 4, src_space=FT_POOL, dst_space=FT_POOL, src=a + pyr.randint(0, 31),
+                                     dst=b + pyr.randint(0, 31), row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp))
+            C = pyr.choice([16, 1024, 4096, 65536, 1 << 23])
+            print(f"pitched seed={seed} descs={len(recs)} C={C}", flush=True)
+            _run_both(orc, eng, recs, [1, 3, 2, 5], C)
+        finally:
+            eng.close()
+
+
+def test_chunk_and_tile_shapes(gpu):
+    """Chunks smaller than, equal to and not a multiple of the tile; tuned tile sizes."""
+    binding, _ = gpu
+    for C, tile in ((16, 0), (48, 32), (4096, 1000), (65536, 0), (65536 + 16, 0), (1 << 20, 4096), (3 << 16, 1 << 16)):
+        orc, eng, rng = _pair(gpu, seed=C % 97)
+        try:
+            for cls in (0, 1, 2):
+                binding.set_tuning(eng.pool, cls, 0, tile)
+            recs = []
+            for i in range(6):
+                n = int(rng.integers(1, 200000))
+                a = orc.slab_alloc(n)
+                assert eng.slab_alloc(n) == a
+                recs.append(dict(func=i % 2, src_space=FT_HOST, dst_space=FT_POOL, src=int(rng.integers(0, 300000)),
+                                 dst=a, row_bytes=n))
+            print(f"tile case C={C} tile={tile}", flush=True)
+            _run_both(orc, eng, recs, [2, 1], C)
+        finally:
+            eng.close()
+
+
+def test_jobs_on_one_stream_run_in_order(gpu):
+    """host->pool then pool->pool of the same bytes then pool->host: each job reads what
+    the previous one wrote, with no host synchronisation in between."""
+    orc, eng, rng = _pair(gpu)
+    try:
+        n = 300001
+        a = orc.slab_alloc(n); assert eng.slab_alloc(n) == a
+        b = orc.slab_alloc(n); assert eng.slab_alloc(n) == b
+        j1 = make_descs([dict(func=0, src_space=FT_HOST, dst_space=FT_POOL, src=5, dst=a, row_bytes=n)])
+        j2 = make_descs([dict(func=0, src_space=FT_POOL, dst_space=FT_POOL, src=a, dst=b + 0, row_bytes=n)])
+        j3 = make_descs([dict(func=0, src_space=FT_POOL, dst_space=FT_HOST, src=b, dst=(1 << 19) + 3, row_bytes=n)])
+        for d in (j1, j2, j3):
+            orc.wait(orc.submit(d, [1], 4096))
+        jobs = [eng.submit(d, [1], 4096) for d in (j1, j2, j3)]
+        for j in jobs:
+            eng.wait(j)
+        _compare_images(orc, eng)
+        assert np.array_equal(eng.read_host((1 << 19) + 3, n), eng.read_host(5, n))
+    finally:
+        eng.close()
+
+
+def test_busy_allocation_and_empty_job(gpu):
+    binding, _ = gpu
+    orc, eng, rng = _pair(gpu)
+    try:
+        a = eng.slab_alloc(1 << 20)
+        d = make_descs([dict(func=0, src_space=FT_HOST, dst_space=FT_POOL, src=0, dst=a, row_bytes=1 << 19)])
+        j = eng.submit(d, [1], 65536)
+        with pytest.raises(binding.FtError) as ei:
+            eng.slab_free(a)
+        assert ei.value.code == fmt.FT_EBUSY
+        eng.wait(j)
+        eng.slab_free(a)
+        j = eng.submit(make_descs([]), [1], 64)
+        eng.wait(j)
+    finally:
+        eng.close()
+
+
+def test_log_and_timing(gpu):
+    binding, _ = gpu
+    orc, eng, rng = _pair(gpu, pool=1 << 24)
+    try:
+        recs = []
+        sizes = [700000, 500000, 900000]
+        for f, n in enumerate(sizes):
+            a = eng.slab_alloc(n)
+            b = eng.slab_alloc(n)
+            eng.write_pool(a, rng.integers(0, 256, n, dtype=np.uint8))
+            recs.append(dict(func=f, src_space=FT_POOL, dst_space=FT_POOL, src=a, dst=b, row_bytes=n))
+        d = make_descs(recs)
+        j = eng.submit(d, [1, 2, 1], 65536, binding.FT_LOG | binding.FT_TIMING)
+        eng.wait(j)
+        st = binding.job_stats(eng.pool, j)
+        log = binding.job_log(eng.pool, j, 2)
+        assert len(log["bytes"]) == st.cls[2].tickets
+        assert int(log["bytes"].sum()) == sum(sizes) == st.cls[2].payload_bytes
+        for f, n in enumerate(sizes):
+            assert int(log["bytes"][log["func"] == f].sum()) == n
+        assert np.all(log["t_end_ns"] >= log["t_begin_ns"])
+        assert st.cls[2].device_ms > 0
+        span_ms = (int(log["t_end_ns"].max()) - int(log["t_begin_ns"].min())) / 1e6
+        assert span_ms <= st.cls[2].device_ms * 1.5 + 0.5
+        binding.job_release(eng.pool, j)
+    finally:
+        eng.close()

@@ -1,0 +1,257 @@
+"""The library's host side, without a GPU: exports, pool, schedule tables, validation.
+
+The expected values come from the oracle; the library is called through its C ABI.
+No call here reaches the device (every submit either fails validation or is empty)."""
+import ctypes
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import OracleEngine, OracleError, stride_order
+from paper_2411_01830_amd import binding as ft
+from workloads import make_descs, FT_HOST, FT_POOL
+from workloads import format as fmt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_BASE = 0x7F0000000000          # never dereferenced: no descriptor passes validation here
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "faastube.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ft_[a-z_0-9]+)\s*\(", text))
+    assert {"ft_pool_create", "ft_slab_alloc", "ft_slab_free", "ft_pool_grow",
+            "ft_submit_transfers", "ft_wait"} <= declared
+    lib = ctypes.CDLL(ft.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(ft.EXPORTS)
+
+
+def test_constants_match_between_header_binding_and_shared_format():
+    text = open(os.path.join(ROOT, "include", "faastube.h")).read()
+    for name in ("FT_EINVAL", "FT_ENOMEM", "FT_ERANGE", "FT_EOVERLAP", "FT_EBUSY", "FT_EHIP"):
+        m = re.search(name + r"\s*=\s*(-?\d+)", text)
+        assert int(m.group(1)) == getattr(fmt, name)
+    for name in ("FT_VALIDATE", "FT_LOG", "FT_PATH_DMA", "FT_TIMING", "FT_DETACHED"):
+        m = re.search(name + r"\s*=\s*1\s*<<\s*(\d+)", text)
+        assert 1 << int(m.group(1)) == getattr(fmt, name) == getattr(ft, name)
+    assert (oracle.EINVAL, oracle.ENOMEM, oracle.ERANGE, oracle.EOVERLAP, oracle.EBUSY) == \
+        (fmt.FT_EINVAL, fmt.FT_ENOMEM, fmt.FT_ERANGE, fmt.FT_EOVERLAP, fmt.FT_EBUSY)
+    assert ctypes.sizeof(ft.JobStats) == 3 * 48 + 8
+
+
+def _both(op, lib_call, oracle_call):
+    """Run the same call on both; return ('ok', value) or ('err', code) for each."""
+    def run(fn):
+        try:
+            return ("ok", fn())
+        except (ft.FtError, OracleError) as e:
+            return ("err", e.code)
+    a, b = run(lib_call), run(oracle_call)
+    assert a == b, (op, a, b)
+    return a
+
+
+def test_pool_matches_oracle_on_random_sequences():
+    rng = random.Random(2)
+    for trial in range(25):
+        slab = 256 * rng.randint(1, 8)
+        n0 = rng.randint(2, 40)
+        pool = ft.pool_create(FAKE_BASE, n0 * slab, slab, 0)
+        orc = oracle.Pool(n0 * slab, slab)
+        live = []
+        next_base = FAKE_BASE + (1 << 32)
+        for step in range(300):
+            r = rng.random()
+            if r < 0.04:
+                add = rng.randint(1, 20) * slab
+                _both("grow", lambda: ft.pool_grow(pool, next_base, add), lambda: orc.grow(add))
+                next_base += 1 << 32
+            elif r < 0.6 or not live:
+                nbytes = rng.randint(1, 7 * slab)
+                res = _both("alloc", lambda: ft.slab_alloc(pool, nbytes), lambda: orc.alloc(nbytes))
+                if res[0] == "ok":
+                    live.append(res[1])
+            else:
+                off = live.pop(rng.randrange(len(live)))
+                _both("free", lambda: ft.slab_free(pool, off), lambda: orc.free(off))
+        _both("free-bad", lambda: ft.slab_free(pool, 12345 * slab), lambda: orc.free(12345 * slab))
+        ft.pool_destroy(pool)
+
+
+def test_pool_ptr_follows_segments():
+    slab = 1024
+    pool = ft.pool_create(FAKE_BASE, 4 * slab, slab, 0)
+    ft.pool_grow(pool, FAKE_BASE + (1 << 30), 2 * slab)
+    assert ft.pool_ptr(pool, 0) == FAKE_BASE
+    assert ft.pool_ptr(pool, 4 * slab - 1) == FAKE_BASE + 4 * slab - 1
+    assert ft.pool_ptr(pool, 4 * slab + 5) == FAKE_BASE + (1 << 30) + 5
+    assert ft.pool_ptr(pool, 6 * slab) is None
+    ft.pool_destroy(pool)
+
+
+def test_pool_create_argument_rules():
+    for base, nbytes, slab in ((0, 1024, 256), (FAKE_BASE, 0, 256), (FAKE_BASE, 1000, 256),
+                               (FAKE_BASE, 1024, 0), (FAKE_BASE, 1024, 100), (FAKE_BASE + 16, 1024, 256)):
+        with pytest.raises(ft.FtError) as ei:
+            ft.pool_create(base, nbytes, slab, 0)
+        assert ei.value.code == fmt.FT_EINVAL
+    pool = ft.pool_create(FAKE_BASE, 1024, 256, 0)
+    for base, nbytes in ((0, 256), (FAKE_BASE + 8, 256), (FAKE_BASE, 100)):
+        with pytest.raises(ft.FtError) as ei:
+            ft.pool_grow(pool, base, nbytes)
+        assert ei.value.code == fmt.FT_EINVAL
+    with pytest.raises(ft.FtError) as ei:
+        ft.slab_alloc(pool, 0)
+    assert ei.value.code == fmt.FT_EINVAL
+    ft.pool_destroy(pool)
+
+
+def test_slab_alloc_is_microseconds():
+    import time
+    slab = 1 << 20
+    pool = ft.pool_create(FAKE_BASE, 16384 * slab, slab, 0)
+    t0 = time.perf_counter()
+    offs = [ft.slab_alloc(pool, (i % 7 + 1) * slab) for i in range(3000)]
+    for o in offs[::2]:
+        ft.slab_free(pool, o)
+    for i in range(1500):
+        ft.slab_alloc(pool, (i % 3 + 1) * slab)
+    per_call = (time.perf_counter() - t0) / 6000
+    ft.pool_destroy(pool)
+    assert per_call < 200e-6        # native allocation is millisecond-level (Sec. 7.1)
+
+
+def test_schedule_tables_match_oracle_order():
+    rng = random.Random(4)
+    for _ in range(400):
+        F = rng.randint(1, 8)
+        C = 16 * rng.randint(1, 8)
+        n = [rng.randint(0, 25) for _ in range(F)]
+        w = [rng.choice([1, 1, 2, 3, 4, 6, 8, 9, 30]) for _ in range(F)]
+        S = [0 if x == 0 else x * C - rng.randint(0, C - 1) for x in n]
+        assert ft.plan_schedule(S, w, C) == stride_order(n, w)
+
+
+def test_schedule_tables_weights_dwarf_chunk_counts():
+    # weights far larger than the number of chunks: only irregular rounds exist
+    w = [1000, 999, 7]
+    n = [3, 5, 2]
+    assert ft.plan_schedule([x * 64 for x in n], w, 64) == stride_order(n, w)
+    # common factor in the weights is divided out
+    assert ft.plan_schedule([640, 1280], [1 << 30, 1 << 31], 64) == stride_order([10, 20], [1, 2])
+
+
+def test_schedule_config_sizes():
+    w = [1, 1, 2, 2, 4, 4, 8, 8]
+    n = [40, 41, 80, 79, 150, 161, 333, 300]
+    assert ft.plan_schedule([x * 2097152 for x in n], w, 2097152) == stride_order(n, w)
+
+
+def test_schedule_rejects_oversized_slot_tables():
+    with pytest.raises(ft.FtError) as ei:
+        ft.plan_schedule([64 * (1 << 23)] * 2, [(1 << 23) - 1, (1 << 23) - 3], 64)
+    assert ei.value.code == fmt.FT_EINVAL
+
+
+def _setup_pair():
+    slab = 1024
+    pool = ft.pool_create(FAKE_BASE, 64 * slab, slab, 0)
+    host_base = 0x7E0000000000
+    ft.host_window_add(pool, host_base, 1 << 16)
+    orc = OracleEngine()
+    orc.host_arena(1 << 16)
+    orc.pool_create(64 * slab, slab)
+    return pool, orc, host_base
+
+
+def _submit_both(pool, orc, host_base, recs, w, C, flags=fmt.FT_VALIDATE):
+    d = make_descs(recs)
+    dl = d.copy()
+    dl["src"][dl["src_space"] == FT_HOST] += np.uint64(host_base)
+    dl["dst"][dl["dst_space"] == FT_HOST] += np.uint64(host_base)
+    return _both("submit", lambda: ft.submit_transfers(pool, dl, w, C, flags),
+                 lambda: orc.submit(d, w, C))
+
+
+def test_submit_validation_matches_oracle():
+    pool, orc, hb = _setup_pair()
+    a = _both("alloc", lambda: ft.slab_alloc(pool, 2048), lambda: orc.slab_alloc(2048))[1]
+    good = dict(func=0, src_space=FT_HOST, dst_space=FT_POOL, src=0, dst=a, row_bytes=100)
+    E = fmt
+    cases = [
+        ([good], [0], 64, E.FT_EINVAL),
+        ([good], [1], 0, E.FT_EINVAL),
+        ([good], [1], 24, E.FT_EINVAL),
+        ([dict(good, func=1)], [1], 64, E.FT_EINVAL),
+        ([dict(good, flags=1)], [1], 64, E.FT_EINVAL),
+        ([dict(good, dst_space=FT_HOST)], [1], 64, E.FT_EINVAL),
+        ([dict(good, src_space=3)], [1], 64, E.FT_EINVAL),
+        ([dict(good, row_bytes=0)], [1], 64, E.FT_EINVAL),
+        ([dict(good, rows=0)], [1], 64, E.FT_EINVAL),
+        ([dict(good, rows=2, src_pitch=99, dst_pitch=100)], [1], 64, E.FT_EINVAL),
+        ([dict(good, rows=2, src_pitch=100, dst_pitch=99)], [1], 64, E.FT_EINVAL),
+        ([dict(good, dst=a + 2048 - 99)], [1], 64, E.FT_ERANGE),
+        ([dict(good, dst=a + 4096)], [1], 64, E.FT_ERANGE),
+        ([dict(good, rows=3, src_pitch=100, dst_pitch=1000)], [1], 64, E.FT_ERANGE),
+        ([dict(good, src=(1 << 16) - 50)], [1], 64, E.FT_ERANGE),
+        ([dict(good, rows=1 << 40, row_bytes=1 << 30, src_pitch=1 << 30, dst_pitch=1 << 30)], [1], 64, E.FT_ERANGE),
+        ([good, dict(good, src=200, dst=a + 99)], [1], 64, E.FT_EOVERLAP),
+        ([dict(good, src_space=FT_POOL, src=a + 50)], [1], 64, E.FT_EOVERLAP),
+        ([dict(good, src_space=FT_POOL, src=a + 895, rows=4, row_bytes=10, src_pitch=10, dst_pitch=300)],
+         [1], 64, E.FT_EOVERLAP),
+        ([dict(good, dst=a + 4096), dict(good, row_bytes=0)], [1], 64, E.FT_EINVAL),
+        ([good, dict(good, src=200, dst=a + 99), dict(good, dst=a + 4096)], [1], 64, E.FT_ERANGE),
+    ]
+    for recs, w, C, want in cases:
+        got = _submit_both(pool, orc, hb, recs, w, C)
+        assert got == ("err", want), (recs, got)
+    # an empty submit is valid on both and completes at once
+    res = _submit_both(pool, orc, hb, [], [1], 64)
+    assert res[0] == "ok"
+    ft.wait(pool, res[1])
+    with pytest.raises(ft.FtError) as ei:
+        ft.wait(pool, res[1])
+    assert ei.value.code == E.FT_EINVAL
+    # null descriptor pointer with a non-zero count, and no functions at all
+    lib = ctypes.CDLL(ft.LIB_PATH)
+    job = ctypes.c_uint64()
+    w1 = (ctypes.c_uint32 * 1)(1)
+    lib.ft_submit_transfers.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32, ctypes.c_void_p,
+                                        ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p,
+                                        ctypes.POINTER(ctypes.c_uint64)]
+    assert lib.ft_submit_transfers(pool, None, 3, w1, 1, 64, 0, None, ctypes.byref(job)) == E.FT_EINVAL
+    assert lib.ft_submit_transfers(pool, None, 0, w1, 0, 64, 0, None, ctypes.byref(job)) == E.FT_EINVAL
+    ft.pool_destroy(pool)
+
+
+def test_random_overlap_decisions_match_oracle():
+    """Random small batches inside one allocation: both sides agree on accept/reject.
+    Accepted batches would need the device, so only rejected ones are submitted to the
+    library; the accepted ones are checked through the oracle's brute-force pin instead."""
+    pool, orc, hb = _setup_pair()
+    a = _both("alloc", lambda: ft.slab_alloc(pool, 8192), lambda: orc.slab_alloc(8192))[1]
+    rng = random.Random(8)
+    rejected = 0
+    for _ in range(400):
+        recs = []
+        for _ in range(rng.randint(2, 4)):
+            rows = rng.choice([1, 2, 3])
+            rb = rng.randint(1, 40)
+            recs.append(dict(func=0, src_space=rng.choice([FT_HOST, FT_POOL]), dst_space=FT_POOL,
+                             src=a + rng.randint(0, 300), dst=a + rng.randint(0, 300), row_bytes=rb,
+                             rows=rows, src_pitch=rb + rng.randint(0, 9), dst_pitch=rb + rng.randint(0, 9)))
+        for r in recs:
+            if r["src_space"] == FT_HOST:
+                r["src"] -= a
+        d = make_descs(recs)
+        if oracle.engine.find_overlap(d):
+            rejected += 1
+            assert _submit_both(pool, orc, hb, recs, [1], 64) == ("err", fmt.FT_EOVERLAP)
+    assert rejected > 100
+    ft.pool_destroy(pool)
