@@ -10,7 +10,11 @@ LIB = os.path.join(HERE, "libfaastube.so")
 SOURCES = ["ft_pool.cpp", "ft_plan.cpp", "ft_api.cpp", "ft_kernels.hip"]
 # packed fp32 code generation is switched off for every translation unit
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-result",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # The ticket draw is one lane's atomic whose result is needed a whole tile later.
+         # LLVM's wave-aggregation of uniform atomics would read the result back at once
+         # and stall the workgroup on the atomic's latency, so it is switched off.
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
 
 
 def hipcc():

@@ -190,13 +190,15 @@ Layout layout_of(const ClassPlan &cp, uint64_t base) {
 }
 
 uint32_t default_workgroups(const ft_pool *p, int cls) {
-  // pool->pool is bound by HBM: fill every CU with as many wavefronts as it holds.
+  // pool->pool is bound by HBM. One workgroup per CU, each holding a whole 64 KiB tile
+  // in registers, keeps the addresses in flight inside a window of a few MiB, which the
+  // memory controllers serve best; more resident workgroups measured slower.
   // The host link saturates with far fewer loads in flight; leave the CUs to others.
-  if (cls == FT_P2P) return (uint32_t)p->cu_count * 8u;
+  if (cls == FT_P2P) return (uint32_t)p->cu_count;
   return 64u;
 }
 
-uint64_t default_tile(int cls) { return cls == FT_P2P ? 64u * 1024u : 32u * 1024u; }
+uint64_t default_tile(int) { return 64u * 1024u; }
 
 hipMemcpyKind kind_of(int cls) {
   return cls == FT_H2P ? hipMemcpyHostToDevice : cls == FT_P2H ? hipMemcpyDeviceToHost : hipMemcpyDeviceToDevice;
@@ -211,7 +213,7 @@ int run_dma(ft_pool *p, const ClassPlan &cp, uint64_t C, int cls, hipStream_t st
     const Func &fn = cp.funcs[id.fl];
     uint64_t pos = id.k * C;
     uint64_t end = pos + C < fn.stream_bytes ? pos + C : fn.stream_bytes;
-    uint32_t x = find_xfer(cp.xfers.data(), fn, pos);
+    uint32_t x = find_xfer(cp.xfers.data(), fn.desc_off, fn.ndesc, pos);
     while (pos < end) {
       const Xfer &X = cp.xfers[x];
       uint64_t q = pos - X.stream_off;

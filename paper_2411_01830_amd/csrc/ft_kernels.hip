@@ -14,19 +14,69 @@ namespace ft {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr uint32_t kThreads = 256;  // 4 wavefronts per workgroup
-constexpr uint32_t kUnroll = 4;     // independent 16-byte loads per lane before the first store
+// The job's tables are written before the launch and never during it. Reading them
+// through constant-address-space pointers lets uniform reads go through the scalar
+// unit and its cache, which the streaming vector traffic does not evict.
+#define FT_CONST __attribute__((address_space(4)))
+typedef const FT_CONST Phase *CPhaseP;
+typedef const FT_CONST Slot *CSlotP;
+typedef const FT_CONST Func *CFuncP;
+typedef const FT_CONST Xfer *CXferP;
+
+struct ConstTables {
+  CPhaseP phases;
+  CSlotP slots;
+  CFuncP funcs;
+  CXferP xfers;
+};
+
+__device__ __forceinline__ ConstTables const_tables(const ClassTable &T) {
+  ConstTables c;
+  c.phases = reinterpret_cast<CPhaseP>(reinterpret_cast<uintptr_t>(T.phases));
+  c.slots = reinterpret_cast<CSlotP>(reinterpret_cast<uintptr_t>(T.slots));
+  c.funcs = reinterpret_cast<CFuncP>(reinterpret_cast<uintptr_t>(T.funcs));
+  c.xfers = reinterpret_cast<CXferP>(reinterpret_cast<uintptr_t>(T.xfers));
+  return c;
+}
+
+__device__ __forceinline__ Xfer read_xfer(CXferP xfers, uint32_t x) {
+  Xfer X;
+  X.src = xfers[x].src;
+  X.dst = xfers[x].dst;
+  X.row_bytes = xfers[x].row_bytes;
+  X.rows = xfers[x].rows;
+  X.src_pitch = xfers[x].src_pitch;
+  X.dst_pitch = xfers[x].dst_pitch;
+  X.stream_off = xfers[x].stream_off;
+  X._pad = 0;
+  return X;
+}
+
+constexpr uint32_t kThreads = 256;  // 4 wavefronts per workgroup, one workgroup per CU for pool->pool
+constexpr uint32_t kUnroll = 16;    // 16-byte loads a lane has in flight before its first store:
+                                    // 256 lanes x 16 x 16 B = one 64 KiB block per workgroup
+constexpr uint32_t kBlockVec = kThreads * kUnroll;
+constexpr uint32_t kStageVec = 2048;  // source granules staged through LDS per pass (32 KiB)
+
+// Every payload address (pool memory or pinned host memory) is a global-segment
+// address. Saying so keeps the copies off the flat path, whose loads also count on
+// the scalar/LDS wait counter and would serialise with the table reads.
+#define FT_GLOBAL __attribute__((address_space(1)))
+typedef u32x4 FT_GLOBAL *GVecP;
+typedef uint8_t FT_GLOBAL *GByteP;
 
 template <bool NT>
 __device__ __forceinline__ u32x4 ld16(uint64_t addr) {
-  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(addr));
-  return *reinterpret_cast<const u32x4 *>(addr);
+  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 FT_GLOBAL *>(addr));
+  return *reinterpret_cast<const u32x4 FT_GLOBAL *>(addr);
 }
 template <bool NT>
 __device__ __forceinline__ void st16(uint64_t addr, u32x4 v) {
-  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(addr));
-  else *reinterpret_cast<u32x4 *>(addr) = v;
+  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<GVecP>(addr));
+  else *reinterpret_cast<GVecP>(addr) = v;
 }
+__device__ __forceinline__ uint8_t ld8(uint64_t addr) { return *reinterpret_cast<const uint8_t FT_GLOBAL *>(addr); }
+__device__ __forceinline__ void st8(uint64_t addr, uint8_t v) { *reinterpret_cast<GByteP>(addr) = v; }
 
 // 16 bytes starting `shift` (1..15) bytes into the 32-byte pair (A, B).
 __device__ __forceinline__ u32x4 funnel(u32x4 A, u32x4 B, uint32_t shift) {
@@ -44,12 +94,26 @@ __device__ __forceinline__ u32x4 funnel(u32x4 A, u32x4 B, uint32_t shift) {
   return v;
 }
 
+// Write the bytes [lo, hi) of v to the aligned granule at ga.
+template <bool NT>
+__device__ __forceinline__ void store_granule(uint64_t ga, u32x4 v, uint32_t lo, uint32_t hi) {
+  if (lo == 0 && hi == 16) {
+    st16<NT>(ga, v);
+  } else {
+    for (uint32_t b = lo; b < hi; ++b) {
+      const uint32_t w = (b >> 2) == 0 ? v.x : (b >> 2) == 1 ? v.y : (b >> 2) == 2 ? v.z : v.w;
+      st8(ga + b, (uint8_t)(w >> ((b & 3) * 8)));
+    }
+  }
+}
+
 // Copy n bytes from s0 to d0, any alignment, with lanes lane, lane+L, ... of a group of
-// L lanes. Works in destination granules (aligned 16 bytes): full granules are written
-// with one vector store, the first and last with byte stores of only the bytes that
-// belong to the range. Source reads are aligned 16-byte loads of granules that hold at
-// least one byte of the source range, so nothing outside the pages of the range is
-// touched; when source and destination differ in alignment two loads are merged.
+// L lanes (short rows of pitched descriptors). Works in destination granules (aligned
+// 16 bytes): full granules are written with one vector store, the first and last with
+// byte stores of only the bytes that belong to the range. Source reads are aligned
+// 16-byte loads of granules that hold at least one byte of the source range, so
+// nothing outside the pages of the range is touched; when source and destination
+// differ in alignment two loads are merged.
 template <bool NT>
 __device__ __forceinline__ void copy_span(uint64_t d0, uint64_t s0, uint64_t n, uint32_t lane, uint32_t L) {
   const uint64_t d1 = d0 + n, s1 = s0 + n;
@@ -72,52 +136,129 @@ __device__ __forceinline__ void copy_span(uint64_t d0, uint64_t s0, uint64_t n, 
     }
     const uint32_t lo = ga < d0 ? (uint32_t)(d0 - ga) : 0u;
     const uint32_t hi = ga + 16 > d1 ? (uint32_t)(d1 - ga) : 16u;
-    if (lo == 0 && hi == 16) {
-      st16<NT>(ga, v);
-    } else {
-      for (uint32_t b = lo; b < hi; ++b) {
-        const uint32_t w = (b >> 2) == 0 ? v.x : (b >> 2) == 1 ? v.y : (b >> 2) == 2 ? v.z : v.w;
-        *reinterpret_cast<uint8_t *>(ga + b) = (uint8_t)(w >> ((b & 3) * 8));
-      }
-    }
+    store_granule<NT>(ga, v, lo, hi);
   }
 }
 
-// nvec aligned 16-byte vectors, all threads of the workgroup, kUnroll loads in flight per lane.
+// R rows of kThreads aligned vectors each (R * 4 KiB), every lane issuing its R loads
+// before its first store. No lane is predicated, so the code is one straight line and
+// the loads are waited for once, not one by one.
+template <bool NT, uint32_t R>
+__device__ __forceinline__ void copy_rows_of_vectors(uint64_t d, uint64_t s, uint32_t tid) {
+  u32x4 v[R];
+#pragma unroll
+  for (uint32_t j = 0; j < R; ++j) v[j] = ld16<NT>(s + ((uint64_t)(tid + j * kThreads) << 4));
+#pragma unroll
+  for (uint32_t j = 0; j < R; ++j) st16<NT>(d + ((uint64_t)(tid + j * kThreads) << 4), v[j]);
+}
+
+// nvec aligned 16-byte vectors with the whole workgroup: 64 KiB blocks first, then
+// the remainder as blocks of 8, 4, 2 and 1 rows and one partial row.
 template <bool NT>
 __device__ __forceinline__ void copy_vectors(uint64_t d, uint64_t s, uint64_t nvec, uint32_t tid) {
-  uint64_t i = tid;
-  for (; i + (kUnroll - 1) * kThreads < nvec; i += kUnroll * kThreads) {
-    u32x4 v[kUnroll];
-#pragma unroll
-    for (uint32_t j = 0; j < kUnroll; ++j) v[j] = ld16<NT>(s + ((i + j * kThreads) << 4));
-#pragma unroll
-    for (uint32_t j = 0; j < kUnroll; ++j) st16<NT>(d + ((i + j * kThreads) << 4), v[j]);
+  uint64_t rows = nvec / kThreads;
+  while (rows >= kUnroll) {
+    copy_rows_of_vectors<NT, kUnroll>(d, s, tid);
+    d += (uint64_t)kBlockVec << 4;
+    s += (uint64_t)kBlockVec << 4;
+    rows -= kUnroll;
   }
-  for (; i < nvec; i += kThreads) st16<NT>(d + (i << 4), ld16<NT>(s + (i << 4)));
+  if (rows & 8) {
+    copy_rows_of_vectors<NT, 8>(d, s, tid);
+    d += 8ull * kThreads << 4;
+    s += 8ull * kThreads << 4;
+  }
+  if (rows & 4) {
+    copy_rows_of_vectors<NT, 4>(d, s, tid);
+    d += 4ull * kThreads << 4;
+    s += 4ull * kThreads << 4;
+  }
+  if (rows & 2) {
+    copy_rows_of_vectors<NT, 2>(d, s, tid);
+    d += 2ull * kThreads << 4;
+    s += 2ull * kThreads << 4;
+  }
+  if (rows & 1) {
+    copy_rows_of_vectors<NT, 1>(d, s, tid);
+    d += 1ull * kThreads << 4;
+    s += 1ull * kThreads << 4;
+  }
+  const uint32_t rest = (uint32_t)(nvec % kThreads);
+  if (tid < rest) st16<NT>(d + ((uint64_t)tid << 4), ld16<NT>(s + ((uint64_t)tid << 4)));
+}
+
+// Source and destination differ in alignment: the aligned 16-byte granules that cover
+// the source run are loaded once, parked in LDS, and every lane builds one aligned
+// destination vector from the two neighbouring granules it needs. Global traffic is
+// the same as for the aligned case; only the first and last destination granule are
+// written byte-wise. Loads are never predicated: an index past the run is clamped to
+// the run's last granule (its value is parked but never used for a byte that is
+// stored), which keeps the load sequence a straight line.
+template <bool NT>
+__device__ __forceinline__ void copy_shifted(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid, u32x4 *stage) {
+  constexpr uint32_t kLoads = kStageVec / kThreads;  // per lane and pass
+  const uint32_t shift = (uint32_t)((s0 - d0) & 15);  // != 0
+  const uint64_t d1 = d0 + n, s1 = s0 + n;
+  const uint64_t first = s0 & ~15ull, last = (s1 - 1) & ~15ull;  // granules holding source bytes
+  uint64_t ga = d0 & ~15ull;  // first destination granule of this pass
+  while (ga < d1) {
+    // source byte that lands on ga, and the aligned granule holding it
+    const uint64_t sa = ga + (s0 - d0);
+    const uint64_t a0 = sa & ~15ull;
+    // destination granule i needs source granules i and i+1 of this pass
+    uint64_t ngran = (((d1 + 15) & ~15ull) - ga) >> 4;
+    if (ngran > kStageVec - 1) ngran = kStageVec - 1;
+    __syncthreads();  // the previous pass has finished reading the stage
+    u32x4 v[kLoads];
+#pragma unroll
+    for (uint32_t j = 0; j < kLoads; ++j) {
+      uint64_t a = a0 + ((uint64_t)(tid + j * kThreads) << 4);
+      a = a < first ? first : a;
+      a = a > last ? last : a;
+      v[j] = ld16<NT>(a);
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < kLoads; ++j) stage[tid + j * kThreads] = v[j];
+    __syncthreads();
+#pragma unroll
+    for (uint32_t j = 0; j < kLoads; ++j) {
+      const uint32_t i = tid + j * kThreads;
+      if (i < ngran) {
+        const uint64_t g = ga + ((uint64_t)i << 4);
+        const u32x4 out = funnel(stage[i], stage[i + 1], shift);
+        const uint32_t lo = g < d0 ? (uint32_t)(d0 - g) : 0u;
+        const uint32_t hi = g + 16 > d1 ? (uint32_t)(d1 - g) : 16u;
+        store_granule<NT>(g, out, lo, hi);
+      }
+    }
+    ga += ngran << 4;
+  }
 }
 
 // One contiguous piece with the whole workgroup.
 template <bool NT>
-__device__ __forceinline__ void copy_piece(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid) {
-  if (((d0 ^ s0) & 15) == 0 && n >= 256) {
+__device__ __forceinline__ void copy_piece(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid, u32x4 *stage) {
+  if (((d0 ^ s0) & 15) == 0) {
+    if (n < 64) {
+      if (tid < n) st8(d0 + tid, ld8(s0 + tid));
+      return;
+    }
     // same alignment on both sides: byte head up to the boundary, vector body, byte tail
     const uint64_t head = (16 - (d0 & 15)) & 15;
     const uint64_t nvec = (n - head) >> 4;
     const uint64_t tail = (n - head) & 15;
-    if (tid < head) *reinterpret_cast<uint8_t *>(d0 + tid) = *reinterpret_cast<const uint8_t *>(s0 + tid);
+    if (tid < head) st8(d0 + tid, ld8(s0 + tid));
     const uint64_t toff = head + (nvec << 4);
-    if (tid < tail)
-      *reinterpret_cast<uint8_t *>(d0 + toff + tid) = *reinterpret_cast<const uint8_t *>(s0 + toff + tid);
+    if (tid < tail) st8(d0 + toff + tid, ld8(s0 + toff + tid));
     copy_vectors<NT>(d0 + head, s0 + head, nvec, tid);
   } else {
-    copy_span<NT>(d0, s0, n, tid, kThreads);
+    copy_shifted<NT>(d0, s0, n, tid, stage);
   }
 }
 
 // Payload bytes [p, p+take) of a pitched descriptor.
 template <bool NT>
-__device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid) {
+__device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid, u32x4 *stage) {
   const uint64_t rb = X.row_bytes;
   const uint64_t pend = p + take;
   const uint64_t r0 = p / rb;
@@ -127,7 +268,7 @@ __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t ta
   if (rb > 2048) {
     for (uint64_t r = r0; r <= rl; ++r) {
       const uint64_t ca = r == r0 ? c0 : 0, cb = r == rl ? cl : rb;
-      copy_piece<NT>(X.dst + r * X.dst_pitch + ca, X.src + r * X.src_pitch + ca, cb - ca, tid);
+      copy_piece<NT>(X.dst + r * X.dst_pitch + ca, X.src + r * X.src_pitch + ca, cb - ca, tid, stage);
     }
   } else {
     // short rows: a group of L lanes per row, several rows per pass
@@ -147,14 +288,19 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
   return (uint64_t)hi << 32 | lo;
 }
 
-// The tile a ticket names: bytes [b0, b1) of function fl's stream (may be empty).
-struct Tile {
-  uint32_t fl;
-  uint64_t k;
+// What a ticket names, decoded: bytes [b0, b1) of one function's stream (empty if
+// b0 >= b1) and the descriptor holding b0.
+struct Work {
   uint64_t b0, b1;
+  uint32_t x;   // index of the descriptor that holds stream byte b0
+  Xfer first;   // that descriptor
 };
 
-__device__ __forceinline__ Tile tile_of(const ClassTable &T, uint64_t t) {
+__device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTables &CT, uint64_t t) {
+  Work w;
+  w.b0 = w.b1 = 0;
+  w.x = 0;
+  if (t >= T.ntickets) return w;
   uint64_t rank, ti;
   if (t < (1ull << 32)) {
     rank = (uint32_t)t / T.tiles_per_chunk;
@@ -163,79 +309,103 @@ __device__ __forceinline__ Tile tile_of(const ClassTable &T, uint64_t t) {
     rank = t / T.tiles_per_chunk;
     ti = t - rank * T.tiles_per_chunk;
   }
-  const ChunkId id = decode_rank(T.phases, T.nphases, T.slots, T.funcs, rank);
-  const uint64_t S = T.funcs[id.fl].stream_bytes;
+  const ChunkId id = decode_rank(CT.phases, T.nphases, CT.slots, CT.funcs, rank);
+  const uint64_t stream_bytes = CT.funcs[id.fl].stream_bytes;
   const uint64_t c0 = id.k * T.chunk_bytes;
   uint64_t lo = ti * T.tile_bytes, hi = lo + T.tile_bytes;
   if (hi > T.chunk_bytes) hi = T.chunk_bytes;
-  Tile tl;
-  tl.fl = id.fl;
-  tl.k = id.k;
-  tl.b0 = c0 + lo;
-  tl.b1 = c0 + hi;
-  if (tl.b1 > S) tl.b1 = S;
-  if (tl.b0 > tl.b1) tl.b0 = tl.b1;
-  return tl;
+  uint64_t b0 = c0 + lo, b1 = c0 + hi;
+  if (b1 > stream_bytes) b1 = stream_bytes;
+  if (b0 >= b1) return w;
+  w.b0 = b0;
+  w.b1 = b1;
+  w.x = find_xfer(CT.xfers, CT.funcs[id.fl].desc_off, CT.funcs[id.fl].ndesc, b0);
+  w.first = read_xfer(CT.xfers, w.x);
+  return w;
 }
 
+// Persistent workgroups. Tickets are drawn two ahead: while tile i moves, ticket i+1
+// is already known and the atomic for ticket i+2 is in flight. A workgroup moves its
+// tile in two phases - every load of the tile, then every store - and decodes ticket
+// i+1 (scalar table reads) while the stores drain; the barrier at the end of the
+// iteration waits for them. Keeping a CU's reads and writes in separate bursts, one
+// workgroup per CU, is what the memory controllers serve fastest.
 template <bool NT>
 __global__ __launch_bounds__(kThreads) void ft_copy_kernel(ClassTable T) {
   __shared__ unsigned long long s_ticket[2];
+  __shared__ u32x4 s_stage[kStageVec];
   const uint32_t tid = threadIdx.x;
-  if (tid == 0) s_ticket[0] = atomicAdd(T.ticket, 1ull);
+  if (tid == 0) {
+    const unsigned long long a = atomicAdd(T.ticket, 2ull);
+    s_ticket[0] = a;
+    s_ticket[1] = a + 1;
+  }
   __syncthreads();
-  uint64_t t = uniform64(s_ticket[0]);
-  uint32_t buf = 0;
-  while (t < T.ntickets) {
-    // draw the next ticket now; its latency hides behind this tile's copy
-    unsigned long long next = 0;
-    if (tid == 0) next = atomicAdd(T.ticket, 1ull);
+  uint64_t t_cur = uniform64(s_ticket[0]);
+  uint64_t t_next = uniform64(s_ticket[1]);
+  uint32_t slot = 0;  // where ticket i+2 goes
+  const ConstTables CT = const_tables(T);
+  Work cur = decode_ticket(T, CT, t_cur);
+  while (t_cur < T.ntickets) {
     uint64_t t_begin = 0;
     if (T.log) t_begin = wall_clock64();
+    unsigned long long claimed = 0;
 
-    const Tile tl = tile_of(T, t);
-    if (tl.b0 < tl.b1) {
-      const Func fn = T.funcs[tl.fl];
-      uint32_t x = find_xfer(T.xfers, fn, tl.b0);
-      uint64_t pos = tl.b0;
-      while (pos < tl.b1) {
-        const Xfer X = T.xfers[x];
+    const uint64_t p0 = cur.b0 - cur.first.stream_off;
+    const uint64_t len = cur.b1 - cur.b0;
+    const uint64_t fd = cur.first.dst + p0, fs = cur.first.src + p0;
+    if (cur.first.rows == 1 && len == (uint64_t)kBlockVec * 16 && ((fd | fs) & 15) == 0 &&
+        p0 + len <= cur.first.row_bytes) {
+      // the common case, one full aligned 64 KiB block: straight-line code from the
+      // ticket draw to the last store
+      if (tid == 0) claimed = atomicAdd(T.ticket, 1ull);
+      copy_rows_of_vectors<NT, kUnroll>(fd, fs, tid);
+    } else {
+      uint64_t pos = cur.b0;
+      uint32_t x = cur.x;
+      Xfer X = cur.first;
+      while (pos < cur.b1) {
         const uint64_t p = pos - X.stream_off;
-        const uint64_t size = X.row_bytes * X.rows;
-        uint64_t take = size - p;
-        if (take > tl.b1 - pos) take = tl.b1 - pos;
-        if (X.rows == 1) copy_piece<NT>(X.dst + p, X.src + p, take, tid);
-        else copy_rows<NT>(X, p, take, tid);
+        uint64_t take = X.row_bytes * X.rows - p;
+        if (take > cur.b1 - pos) take = cur.b1 - pos;
+        if (X.rows == 1) copy_piece<NT>(X.dst + p, X.src + p, take, tid, s_stage);
+        else copy_rows<NT>(X, p, take, tid, s_stage);
         pos += take;
-        ++x;
+        if (pos < cur.b1) X = read_xfer(CT.xfers, ++x);
       }
+      if (tid == 0) claimed = atomicAdd(T.ticket, 1ull);
     }
+    if (tid == 0) s_ticket[slot] = claimed;
+    const Work next = decode_ticket(T, CT, t_next);
+
     if (T.log) {
-      // the tile counts as done when every store of the workgroup has been issued and
-      // acknowledged
+      // the tile counts as done when every store of the workgroup has been acknowledged
       __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
       if (tid == 0) {
-        T.log[t].t_begin = t_begin;
-        T.log[t].t_end = wall_clock64();
+        T.log[t_cur].t_begin = t_begin;
+        T.log[t_cur].t_end = wall_clock64();
       }
     }
-    if (tid == 0) s_ticket[buf ^ 1] = next;
     __syncthreads();
-    buf ^= 1;
-    t = uniform64(s_ticket[buf]);
+    t_cur = t_next;
+    cur = next;
+    t_next = uniform64(s_ticket[slot]);
+    slot ^= 1;
   }
 }
 
 __global__ void ft_decode_kernel(ClassTable T, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap) {
   uint64_t rank = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (rank >= T.nchunks || rank >= cap) return;
-  const ChunkId id = decode_rank(T.phases, T.nphases, T.slots, T.funcs, rank);
-  func_out[rank] = T.funcs[id.fl].func;
+  const ConstTables CT = const_tables(T);
+  const ChunkId id = decode_rank(CT.phases, T.nphases, CT.slots, CT.funcs, rank);
+  func_out[rank] = CT.funcs[id.fl].func;
   chunk_out[rank] = (uint32_t)id.k;
 }
 
 __global__ __launch_bounds__(kThreads) void ft_plain_copy_kernel(u32x4 *dst, const u32x4 *src, uint64_t nvec) {
+  constexpr uint32_t kUnroll = 4;
   const uint64_t stride = (uint64_t)gridDim.x * kThreads;
   uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
   for (; i + (kUnroll - 1) * stride < nvec; i += kUnroll * stride) {

@@ -82,28 +82,30 @@ struct ChunkId {
   uint64_t k;   // chunk index within that function's stream
 };
 
-// rank -> (function, chunk). rank < nchunks.
-FT_HD ChunkId decode_rank(const Phase *phases, uint32_t nphases, const Slot *slots,
-                          const Func *funcs, uint64_t rank) {
+// rank -> (function, chunk). rank < nchunks. The pointer types are template
+// parameters so that the device can read the tables through constant-address-space
+// pointers (scalar loads); only scalar members are read through them.
+template <class PhaseP, class SlotP, class FuncP>
+FT_HD ChunkId decode_rank(PhaseP phases, uint32_t nphases, SlotP slots, FuncP funcs, uint64_t rank) {
   uint32_t lo = 0, hi = nphases;  // last phase with rank_base <= rank
   while (hi - lo > 1) {
     uint32_t mid = (lo + hi) >> 1;
     if (phases[mid].rank_base <= rank) lo = mid; else hi = mid;
   }
-  const Phase ph = phases[lo];
-  uint64_t rel = rank - ph.rank_base;
-  uint64_t round = rel / ph.nslots;
-  uint32_t s = (uint32_t)(rel - round * ph.nslots);
-  const Slot sl = slots[ph.slot_off + s];
+  const uint64_t rel = rank - phases[lo].rank_base;
+  const uint32_t nslots = phases[lo].nslots;
+  const uint64_t round = rel / nslots;
+  const uint32_t s = phases[lo].slot_off + (uint32_t)(rel - round * nslots);
   ChunkId id;
-  id.fl = sl.fl;
-  id.k = (ph.round_base + round) * (uint64_t)funcs[sl.fl].weight + sl.i;
+  id.fl = slots[s].fl;
+  id.k = (phases[lo].round_base + round) * (uint64_t)funcs[id.fl].weight + slots[s].i;
   return id;
 }
 
-// Descriptor of function fn that holds stream byte `pos` (pos < stream_bytes).
-FT_HD uint32_t find_xfer(const Xfer *xfers, const Func &fn, uint64_t pos) {
-  uint32_t lo = fn.desc_off, hi = fn.desc_off + fn.ndesc;
+// Descriptor among [desc_off, desc_off + ndesc) that holds stream byte `pos`.
+template <class XferP>
+FT_HD uint32_t find_xfer(XferP xfers, uint32_t desc_off, uint32_t ndesc, uint64_t pos) {
+  uint32_t lo = desc_off, hi = desc_off + ndesc;
   while (hi - lo > 1) {
     uint32_t mid = (lo + hi) >> 1;
     if (xfers[mid].stream_off <= pos) lo = mid; else hi = mid;
