@@ -1,0 +1,354 @@
+#!/usr/bin/env python3
+"""Benchmark of the transfer engine on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic workload: create the
+pool over resident device memory, slab-allocate every buffer (growing the pool when
+it runs full), validate/plan/submit every batch of transfers and wait for all of
+them. Inputs (pinned host sources, pool-resident sources) are in place before the
+timed region. The default workload is the large mixed one (1024 transfers, 8 GiB,
+60 % host->pool and 40 % pool->pool, pool growing 1 -> 16 GiB in 16 waves); the other
+four workloads are run once each for the ``per_workload`` block of the same line.
+
+Prints ONE JSON line. ``value`` is payload bytes per second over the timed steps.
+``roofline`` is for the pool->pool copy kernel (HBM bound): algorithmic bytes are
+2 x payload (one read, one write), durations are HIP events the library records on
+the kernel's own stream around every launch of the timed steps.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+METRIC = "aggregate GB/s (host->pool, pool->pool) as % of roofline; weighted-share error"
+HBM_PEAK_GBS = 8000.0
+# HBM bytes the profiler counted per algorithmic byte for the pool->pool kernel
+# (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy of known size); see
+# profiles/pmc_hbm_traffic_pool_to_pool_feature.md.
+TRAFFIC_PER_ALGO_BYTE = 1.0006
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large_mixed",
+                    choices=["tiny", "traffic", "feature", "contended", "large_mixed"])
+    ap.add_argument("--no-extras", action="store_true", help="skip the other workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--path", default="kernel", choices=["kernel", "dma"])
+    return ap.parse_args()
+
+
+class Replay:
+    """A workload made concrete once (memory allocated and filled, descriptors resolved
+    to addresses), then replayed step after step through the C ABI alone."""
+
+    def __init__(self, name, detached):
+        import torch
+        from paper_2411_01830_amd import binding as ft, harness
+        from workloads import configs, runner
+        self.ft = ft
+        self.torch = torch
+        self.name = name
+        self.plan = configs.CONFIGS[name](1.0)
+        self.eng = harness.GpuEngine(0, reuse_memory=True)
+        rec = runner.run_plan(self.plan, self.eng, flags=ft.FT_VALIDATE)     # fills inputs, checks aliasing once
+        torch.cuda.synchronize()
+        self.rec = rec
+        self.segs = list(self.eng._seg_cache)
+        self.host = self.eng.host
+        self.eng.close_pool()
+        base = np.uint64(self.host.data_ptr())
+        self.ops = []
+        for st in self.plan.steps:
+            if st[0] == "alloc":
+                self.ops.append(("alloc", int(st[2]), rec.alloc_off[st[1]]))
+            elif st[0] == "submit":
+                d = rec.descs[st[1]].copy()
+                d["src"][d["src_space"] == 0] += base
+                d["dst"][d["dst_space"] == 0] += base
+                self.ops.append(("submit", st[1], d, np.asarray(st[3], dtype=np.uint32), int(st[4])))
+            elif st[0] == "wait":
+                self.ops.append(("wait", st[1]))
+        self.detached = detached
+        self.payload = self.plan.payload_bytes()
+        self.stream = torch.cuda.current_stream().cuda_stream
+
+    def step(self, flags=0, collect=None, tuning=None):
+        ft = self.ft
+        pool = ft.pool_create(self.segs[0].data_ptr(), self.segs[0].numel(), self.plan.slab_bytes, 0)
+        ft.host_window_add(pool, self.host.data_ptr(), self.host.numel())
+        if tuning:
+            for cls, (wg, tile) in tuning.items():
+                ft.set_tuning(pool, cls, wg, tile)
+        nseg = 1
+        jobs = {}
+        flags |= ft.FT_TIMING | (ft.FT_DETACHED if self.detached else 0)
+        alloc_s = 0.0
+        for op in self.ops:
+            if op[0] == "alloc":
+                t0 = time.perf_counter()
+                while True:
+                    try:
+                        off = ft.slab_alloc(pool, op[1])
+                        break
+                    except ft.FtError as e:
+                        if e.code != -2 or nseg >= len(self.segs):
+                            raise
+                        ft.pool_grow(pool, self.segs[nseg].data_ptr(), self.segs[nseg].numel())
+                        nseg += 1
+                alloc_s += time.perf_counter() - t0
+                if off != op[2]:
+                    raise RuntimeError("allocator is not deterministic")
+            elif op[0] == "submit":
+                jobs[op[1]] = ft.submit_transfers(pool, op[2], op[3], op[4], flags, self.stream)
+            else:
+                ft.wait(pool, jobs[op[1]])
+        out = {}
+        for name, job in jobs.items():
+            out[name] = ft.job_stats(pool, job)
+            if collect is not None:
+                collect(name, pool, job, out[name])
+            ft.job_release(pool, job)
+        ft.pool_destroy(pool)
+        return out, alloc_s
+
+    def close(self):
+        self.eng.close()
+
+
+def time_steps(rp, steps, warmup, flags=0):
+    torch = rp.torch
+    for _ in range(warmup):
+        rp.step(flags)
+    torch.cuda.synchronize()
+    cls_ms = [0.0, 0.0, 0.0]
+    cls_bytes = [0, 0, 0]
+    cls_launches = [0, 0, 0]
+    submit_us = 0.0
+    alloc_s = 0.0
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        stats, a = rp.step(flags)
+        alloc_s += a
+        for st in stats.values():
+            submit_us += st.host_submit_us
+            for c in range(3):
+                if st.cls[c].payload_bytes:
+                    cls_ms[c] += st.cls[c].device_ms
+                    cls_bytes[c] += st.cls[c].payload_bytes
+                    cls_launches[c] += 1
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return {"wall_s": wall, "cls_ms": cls_ms, "cls_bytes": cls_bytes, "cls_launches": cls_launches,
+            "submit_us_per_step": submit_us / steps, "alloc_us_per_step": alloc_s * 1e6 / steps}
+
+
+def link_peak():
+    """Best large pinned hipMemcpyAsync in each direction, measured now (GB/s)."""
+    import torch
+    n = 1 << 30
+    h = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    d = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    out = {}
+    for key, fn in (("h2d", lambda: d.copy_(h, non_blocking=True)), ("d2h", lambda: h.copy_(d, non_blocking=True))):
+        best = 0.0
+        fn()
+        torch.cuda.synchronize()
+        for _ in range(5):
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record()
+            fn()
+            e.record()
+            torch.cuda.synchronize()
+            best = max(best, n / s.elapsed_time(e) / 1e6)
+        out[key] = best
+    return out
+
+
+def plain_copy_ceiling():
+    """A plain grid-stride copy of 2 GiB: the practical HBM ceiling on this machine (GB/s, read+write)."""
+    import torch
+    from paper_2411_01830_amd import binding as ft
+    n = 2 << 30
+    a = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    b = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    best = 0.0
+    for _ in range(6):
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        ft.plain_copy(b.data_ptr(), a.data_ptr(), n, 256, st)
+        e.record()
+        torch.cuda.synchronize()
+        best = max(best, 2 * n / s.elapsed_time(e) / 1e6)
+    return best
+
+
+def share_error(rp, cls):
+    """Timed per-function shares from the device log of one step (contended link):
+    over [0, T1], T1 = first time any function's last byte lands."""
+    ft = rp.ft
+    got = {}
+
+    def collect(name, pool, job, st):
+        got["log"] = ft.job_log(pool, job, cls)
+        got["weights"] = rp.rec.weights[name]
+
+    rp.step(ft.FT_LOG, collect)
+    log, w = got["log"], np.asarray(got["weights"], dtype=np.float64)
+    F = len(w)
+    t_end = log["t_end_ns"].astype(np.int64)
+    t0 = int(log["t_begin_ns"].min())
+    last = np.array([t_end[log["func"] == f].max() if np.any(log["func"] == f) else np.iinfo(np.int64).max
+                     for f in range(F)])
+    T1 = int(last.min())
+    active = np.array([np.any(log["func"] == f) for f in range(F)])
+    want = w * active / (w * active).sum()
+
+    def err_at(lo, hi):
+        m = (t_end > lo) & (t_end <= hi)
+        b = np.array([log["bytes"][m & (log["func"] == f)].sum() for f in range(F)], dtype=np.float64)
+        if b.sum() == 0:
+            return None
+        share = b / b.sum()
+        return float(np.max(np.abs(share - want)[active] / want[active]))
+
+    windows = [err_at(t0 + (T1 - t0) * i // 10, t0 + (T1 - t0) * (i + 1) // 10) for i in range(10)]
+    return {"window": "[0,T1], T1 = first function done", "T1_ms": (T1 - t0) / 1e6,
+            "max_rel_err": err_at(t0 - 1, T1),
+            "max_rel_err_tenths": [None if x is None else round(x, 4) for x in windows],
+            "weights": [int(x) for x in w]}
+
+
+def cpu_baseline():
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the first
+    waves of large_mixed at full size, as many as keep the leg around 10-30 s."""
+    from oracle import OracleEngine
+    from workloads import configs, runner
+    full = configs.large_mixed(1.0)
+    for waves in (4, 16):
+        plan = configs.first_submits(full, waves)
+        eng = OracleEngine()
+        t0 = time.perf_counter()
+        runner.run_plan(plan, eng, fill=False)
+        dt = time.perf_counter() - t0
+        del eng
+        if dt >= 4.0:
+            break
+    return {"value": plan.payload_bytes() / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {waves} of the 16 waves of large_mixed at full size "
+                      f"({plan.payload_bytes() / 2**30:.2f} GiB payload, allocation and pool growth included), "
+                      f"{dt:.1f} s, {os.cpu_count()} logical CPUs present"}
+
+
+def summarize(name, res, steps, rp, peaks):
+    ms_per_step = res["wall_s"] * 1e3 / steps
+    out = {"payload_GiB": round(rp.payload / 2**30, 3), "ms_per_step": round(ms_per_step, 3),
+           "GBps": round(rp.payload * steps / res["wall_s"] / 1e9, 2),
+           "submit_us_per_step": round(res["submit_us_per_step"], 1),
+           "alloc_us_per_step": round(res["alloc_us_per_step"], 1)}
+    names = ("h2p", "p2h", "p2p")
+    for c in range(3):
+        if res["cls_bytes"][c] == 0:
+            continue
+        gbps = res["cls_bytes"][c] / res["cls_ms"][c] / 1e6
+        entry = {"payload_GBps": round(gbps, 2), "launches": res["cls_launches"][c],
+                 "avg_launch_ms": round(res["cls_ms"][c] / res["cls_launches"][c], 4)}
+        if c == 2:
+            entry["hbm_frac"] = round(2 * gbps / HBM_PEAK_GBS, 4)
+        else:
+            entry["link_frac"] = round(gbps / peaks["h2d" if c == 0 else "d2h"], 4)
+        out[names[c]] = entry
+    return out
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this engine is a single-GPU build (one pool, one host link per GPU); "
+              "run with --gpus 1. Several GPUs would run independent engines.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU; there is no CPU path", file=sys.stderr)
+        sys.exit(2)
+    from paper_2411_01830_amd import binding as ft
+    flags = ft.FT_PATH_DMA if args.path == "dma" else 0
+    peaks = link_peak()
+    ceiling = plain_copy_ceiling()
+
+    detached = {"large_mixed": True}
+    rp = Replay(args.workload, detached.get(args.workload, False))
+    res = time_steps(rp, args.steps, args.warmup, flags)
+    main_sum = summarize(args.workload, res, args.steps, rp, peaks)
+    value = rp.payload * args.steps / res["wall_s"] / 1e9
+    line = {
+        "metric": METRIC, "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(res["wall_s"] * 1e3 / args.steps, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "payload_bytes_per_step": rp.payload,
+                   "path": args.path, "transfers": sum(len(o[2]) for o in rp.ops if o[0] == "submit"),
+                   "submits_per_step": sum(1 for o in rp.ops if o[0] == "submit")},
+    }
+    # roofline of the pool->pool copy kernel; if this workload has none, of the feature workload below
+    roof_src = res if res["cls_bytes"][2] else None
+    per = {args.workload: main_sum}
+    shares = None
+    if not args.no_extras or roof_src is None:
+        for other in ("feature", "contended", "traffic", "tiny"):
+            if other == args.workload:
+                if other == "contended":
+                    shares = share_error(rp, 0)
+                continue
+            if args.no_extras and not (other == "feature" and roof_src is None):
+                continue
+            rq = Replay(other, False)
+            k = 20 if other in ("feature", "tiny", "traffic") else 5
+            r = time_steps(rq, k, 2, flags)
+            per[other] = summarize(other, r, k, rq, peaks)
+            if other == "feature" and roof_src is None:
+                roof_src = r
+            if other == "contended":
+                shares = share_error(rq, 0)
+            rq.close()
+    if roof_src is not None and roof_src["cls_bytes"][2]:
+        algo = 2.0 * roof_src["cls_bytes"][2]
+        achieved = algo / roof_src["cls_ms"][2] / 1e6
+        line["roofline"] = {
+            "bound": "hbm", "kernel": "ft_copy_kernel<true, 2> (pool->pool)",
+            "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "algorithmic_bytes_per_launch": round(algo / roof_src["cls_launches"][2]),
+            "avg_launch_ms": round(roof_src["cls_ms"][2] / roof_src["cls_launches"][2], 5),
+            "launches": roof_src["cls_launches"][2],
+            "traffic": None if TRAFFIC_PER_ALGO_BYTE is None else
+            round(TRAFFIC_PER_ALGO_BYTE * algo / roof_src["cls_launches"][2]),
+            "plain_copy_ceiling_GBps": round(ceiling, 1),
+        }
+    if res["cls_bytes"][0]:
+        g = res["cls_bytes"][0] / res["cls_ms"][0] / 1e6
+        line["host_link"] = {"direction": "host->pool", "achieved": round(g, 2), "peak_measured": round(peaks["h2d"], 2),
+                             "unit": "GB/s", "frac": round(g / peaks["h2d"], 4),
+                             "peak_is": "best of 5 hipMemcpyAsync of 1 GiB pinned, same run",
+                             "d2h_peak_measured": round(peaks["d2h"], 2)}
+    if shares is not None:
+        line["share_error"] = shares
+    line["per_workload"] = per
+    rp.close()
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -109,8 +109,10 @@ typedef struct ft_job_stats_t {
  *   bytes      positive multiple of slab_bytes.
  *   slab_bytes positive multiple of 256: the allocation granule.
  *   device     HIP device ordinal the memory lives on.
- * No HIP call is made here; device resources (three internal streams, table
- * buffers) are created by the first ft_submit_transfers.
+ * No HIP call is made here. Device resources (one stream per link class, table
+ * buffers, events) belong to the device, not the pool: the first ft_submit_transfers
+ * on a device creates them, every pool on that device shares them, and they stay
+ * until the process ends, so creating and destroying pools is cheap.
  * FT_EINVAL on a null pointer, misalignment or a size that is not a multiple.
  */
 int ft_pool_create(ft_pool **out, void *dev_base, uint64_t bytes, uint64_t slab_bytes, int device);
@@ -122,7 +124,7 @@ int ft_pool_create(ft_pool **out, void *dev_base, uint64_t bytes, uint64_t slab_
  */
 int ft_pool_grow(ft_pool *p, void *dev_base, uint64_t bytes);
 
-/* Wait for every job, release all library-owned resources. Caller memory is untouched. */
+/* Wait for every job of the pool and free its bookkeeping. Caller memory is untouched. */
 int ft_pool_destroy(ft_pool *p);
 
 /*
@@ -169,9 +171,10 @@ int ft_host_window_add(ft_pool *p, void *host_base, uint64_t bytes);
  * Validation order: FT_EINVAL conditions of the arguments and of every descriptor
  * (null pointers with non-zero counts, nfunc == 0, a weight of 0, chunk_bytes not a
  * positive multiple of 16, func >= nfunc, flags != 0, a space other than FT_HOST or
- * FT_POOL, host->host, row_bytes == 0, rows == 0, a pitch < row_bytes with rows > 1,
- * weights whose slot tables would exceed 2^22 entries), then FT_ERANGE of every
- * descriptor, then (FT_VALIDATE) FT_EOVERLAP. ndesc == 0 is valid.
+ * FT_POOL, host->host, row_bytes == 0, rows == 0, a pitch < row_bytes with rows > 1),
+ * then FT_ERANGE of every descriptor, then (FT_VALIDATE) FT_EOVERLAP, and last
+ * FT_EINVAL if the weights are so large and so unlike that the schedule tables would
+ * exceed 2^22 entries. ndesc == 0 is valid.
  */
 int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
                         uint32_t nfunc, uint64_t chunk_bytes, uint32_t flags, void *hip_stream,

@@ -57,6 +57,34 @@ struct Tuning {
   uint64_t tile_bytes = 0;
 };
 
+// Per-device resources shared by every pool on that device and kept for the life of
+// the process: one stream per link class (so the three classes sit on three hardware
+// queues and really run side by side), recycled table buffers and events. Creating a
+// pool therefore costs no HIP call, and a steady stream of submits allocates nothing.
+struct DeviceCtx {
+  std::mutex mu;
+  int device = 0;
+  bool ready = false;
+  int cu_count = 0;
+  int clock_khz = 0;
+  hipStream_t streams[FT_NCLASS] = {nullptr, nullptr, nullptr};
+  std::vector<Blob> free_blobs;      // with a pinned twin
+  std::vector<Blob> free_dev_blobs;  // device only
+  std::vector<hipEvent_t> free_events, free_timing_events;
+};
+
+DeviceCtx *device_ctx(int device) {
+  static std::mutex table_mu;
+  static std::unordered_map<int, DeviceCtx *> table;
+  std::lock_guard<std::mutex> lock(table_mu);
+  auto it = table.find(device);
+  if (it != table.end()) return it->second;
+  DeviceCtx *c = new DeviceCtx();  // never freed: must outlive every pool and static destructors
+  c->device = device;
+  table[device] = c;
+  return c;
+}
+
 }  // namespace
 
 struct ft_pool {
@@ -64,19 +92,13 @@ struct ft_pool {
   SlabPool slabs;
   int device;
   std::vector<HostWindow> windows;
-  bool dev_ready = false;
-  int cu_count = 0;
-  int clock_khz = 0;
-  hipStream_t streams[FT_NCLASS] = {nullptr, nullptr, nullptr};
-  std::vector<Blob> free_blobs;       // with a pinned twin
-  std::vector<Blob> free_dev_blobs;   // device only
-  std::vector<hipEvent_t> free_events, free_timing_events;
+  DeviceCtx *ctx;
   std::unordered_map<uint64_t, std::unique_ptr<Job>> jobs;
   uint64_t next_job = 1;
   Tuning tuning[FT_NCLASS];
   std::string hip_error;
 
-  ft_pool(uint64_t slab_bytes, int dev) : slabs(slab_bytes), device(dev) {}
+  ft_pool(uint64_t slab_bytes, int dev) : slabs(slab_bytes), device(dev), ctx(device_ctx(dev)) {}
 };
 
 namespace {
@@ -102,18 +124,20 @@ struct DeviceGuard {
 };
 
 int ensure_device(ft_pool *p) {
-  if (p->dev_ready) return FT_OK;
+  DeviceCtx *c = p->ctx;
+  std::lock_guard<std::mutex> lock(c->mu);
+  if (c->ready) return FT_OK;
   int count = 0;
   FT_HIP(p, hipGetDeviceCount(&count));
   if (p->device < 0 || p->device >= count) {
     p->hip_error = "device ordinal out of range";
     return FT_EHIP;
   }
-  FT_HIP(p, hipDeviceGetAttribute(&p->cu_count, hipDeviceAttributeMultiprocessorCount, p->device));
-  FT_HIP(p, hipDeviceGetAttribute(&p->clock_khz, hipDeviceAttributeWallClockRate, p->device));
-  for (int c = 0; c < FT_NCLASS; ++c)
-    FT_HIP(p, hipStreamCreateWithFlags(&p->streams[c], hipStreamNonBlocking));
-  p->dev_ready = true;
+  FT_HIP(p, hipDeviceGetAttribute(&c->cu_count, hipDeviceAttributeMultiprocessorCount, p->device));
+  FT_HIP(p, hipDeviceGetAttribute(&c->clock_khz, hipDeviceAttributeWallClockRate, p->device));
+  for (int k = 0; k < FT_NCLASS; ++k)
+    if (c->streams[k] == nullptr) FT_HIP(p, hipStreamCreateWithFlags(&c->streams[k], hipStreamNonBlocking));
+  c->ready = true;
   return FT_OK;
 }
 
@@ -124,7 +148,8 @@ uint64_t round_pow2(uint64_t v, uint64_t floor_) {
 }
 
 int get_blob(ft_pool *p, uint64_t need, bool pinned_twin, Blob *out) {
-  std::vector<Blob> &cache = pinned_twin ? p->free_blobs : p->free_dev_blobs;
+  std::lock_guard<std::mutex> lock(p->ctx->mu);
+  std::vector<Blob> &cache = pinned_twin ? p->ctx->free_blobs : p->ctx->free_dev_blobs;
   size_t best = cache.size();
   for (size_t i = 0; i < cache.size(); ++i)
     if (cache[i].cap >= need && (best == cache.size() || cache[i].cap < cache[best].cap)) best = i;
@@ -150,12 +175,14 @@ int get_blob(ft_pool *p, uint64_t need, bool pinned_twin, Blob *out) {
 
 void put_blob(ft_pool *p, Blob &b) {
   if (b.dev == nullptr) return;
-  (b.host ? p->free_blobs : p->free_dev_blobs).push_back(b);
+  std::lock_guard<std::mutex> lock(p->ctx->mu);
+  (b.host ? p->ctx->free_blobs : p->ctx->free_dev_blobs).push_back(b);
   b = Blob();
 }
 
 int get_event(ft_pool *p, bool timing, hipEvent_t *out) {
-  std::vector<hipEvent_t> &cache = timing ? p->free_timing_events : p->free_events;
+  std::lock_guard<std::mutex> lock(p->ctx->mu);
+  std::vector<hipEvent_t> &cache = timing ? p->ctx->free_timing_events : p->ctx->free_events;
   if (!cache.empty()) {
     *out = cache.back();
     cache.pop_back();
@@ -167,7 +194,8 @@ int get_event(ft_pool *p, bool timing, hipEvent_t *out) {
 
 void put_event(ft_pool *p, bool timing, hipEvent_t &e) {
   if (e == nullptr) return;
-  (timing ? p->free_timing_events : p->free_events).push_back(e);
+  std::lock_guard<std::mutex> lock(p->ctx->mu);
+  (timing ? p->ctx->free_timing_events : p->ctx->free_events).push_back(e);
   e = nullptr;
 }
 
@@ -189,16 +217,27 @@ Layout layout_of(const ClassPlan &cp, uint64_t base) {
   return l;
 }
 
-uint32_t default_workgroups(const ft_pool *p, int cls) {
-  // pool->pool is bound by HBM. One workgroup per CU, each holding a whole 64 KiB tile
-  // in registers, keeps the addresses in flight inside a window of a few MiB, which the
-  // memory controllers serve best; more resident workgroups measured slower.
-  // The host link saturates with far fewer loads in flight; leave the CUs to others.
-  if (cls == FT_P2P) return (uint32_t)p->cu_count;
-  return 64u;
+// Launch shape when the caller has not tuned it.
+//
+// pool->pool is bound by HBM. One workgroup per CU, each holding a whole 64 KiB tile in
+// registers, keeps the addresses in flight inside a window of a few MiB, which the
+// memory controllers serve best; more resident workgroups measured slower.
+//
+// The host link needs little in flight: about 256 KiB of outstanding reads already
+// reach 96 % of what the copy engines get, 1 MiB reaches all of it. Every outstanding
+// host access holds a slot on the path from L2 to the fabric for microseconds, and
+// pool->pool traffic queues behind it: with 4 MiB of host reads in flight a concurrent
+// pool->pool kernel ran 20x slower. So a job that carries both kinds keeps the host
+// classes at 32 workgroups x 8 KiB; a job with host traffic only uses 64 x 16 KiB.
+uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
+  if (cls == FT_P2P) return (uint32_t)p->ctx->cu_count;
+  return with_p2p ? 32u : 64u;
 }
 
-uint64_t default_tile(int) { return 64u * 1024u; }
+uint64_t default_tile(int cls, bool with_p2p) {
+  if (cls == FT_P2P) return 64u * 1024u;
+  return with_p2p ? 8u * 1024u : 16u * 1024u;
+}
 
 hipMemcpyKind kind_of(int cls) {
   return cls == FT_H2P ? hipMemcpyHostToDevice : cls == FT_P2H ? hipMemcpyDeviceToHost : hipMemcpyDeviceToDevice;
@@ -319,15 +358,6 @@ int ft_pool_destroy(ft_pool *p) {
       release_device_side(p, job);
     }
     p->jobs.clear();
-    for (Blob &b : p->free_blobs) {
-      (void)hipFree(b.dev);
-      (void)hipHostFree(b.host);
-    }
-    for (Blob &b : p->free_dev_blobs) (void)hipFree(b.dev);
-    for (hipEvent_t e : p->free_events) (void)hipEventDestroy(e);
-    for (hipEvent_t e : p->free_timing_events) (void)hipEventDestroy(e);
-    if (p->dev_ready)
-      for (int c = 0; c < FT_NCLASS; ++c) (void)hipStreamDestroy(p->streams[c]);
   }
   delete p;
   return rc;
@@ -419,7 +449,9 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       std::memcpy(h + lay[c].funcs, cp.funcs.data(), cp.funcs.size() * sizeof(Func));
       std::memcpy(h + lay[c].xfers, cp.xfers.data(), cp.xfers.size() * sizeof(Xfer));
       const Tuning &tn = p->tuning[c];
-      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c), &r.tile_bytes, &r.tiles_per_chunk);
+      const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
+      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p), &r.tile_bytes,
+                 &r.tiles_per_chunk);
       ClassTable &T = r.table;
       T.phases = reinterpret_cast<const Phase *>(d + lay[c].phases);
       T.slots = reinterpret_cast<const Slot *>(d + lay[c].slots);
@@ -435,7 +467,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       T.nphases = (uint32_t)cp.phases.size();
       T.nfuncs = (uint32_t)cp.funcs.size();
       T._pad = 0;
-      uint64_t wg = tn.workgroups ? tn.workgroups : default_workgroups(p, c);
+      uint64_t wg = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
       if (wg > T.ntickets) wg = T.ntickets;
       r.workgroups = dma ? 0 : (uint32_t)wg;
       if ((flags & FT_LOG) && !dma) {
@@ -464,7 +496,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
     for (int c = 0; c < FT_NCLASS; ++c) {
       ClassRun &r = job->run[c];
       if (!r.used) continue;
-      hipStream_t s = p->streams[c];
+      hipStream_t s = p->ctx->streams[c];
       e = hipStreamWaitEvent(s, fork, 0);
       if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(fork)");
       if (timing) {
@@ -478,7 +510,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
           return fail(rc);
         }
       } else {
-        e = launch_copy(r.table, r.workgroups, true, s);
+        e = launch_copy(r.table, c, r.workgroups, s);
         if (e != hipSuccess) return hip_fail(e, "launch_copy");
       }
       e = hipEventRecord(r.ev_done, s);
@@ -566,7 +598,7 @@ int ft_job_schedule(ft_pool *p, ft_job_t id, int link_class, uint32_t *func_out,
   DeviceGuard guard(p->device);
   uint32_t *dev = nullptr;
   FT_HIP(p, hipMalloc(reinterpret_cast<void **>(&dev), 2 * n * sizeof(uint32_t)));
-  hipStream_t s = p->streams[link_class];  // ordered after the job's own kernel and table upload
+  hipStream_t s = p->ctx->streams[link_class];  // ordered after the job's own kernel and table upload
   hipError_t e = launch_decode(r.table, dev, dev + n, n, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e == hipSuccess) e = hipMemcpy(func_out, dev, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
@@ -590,7 +622,7 @@ int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, ui
   const uint64_t nt = r.log_host.size();
   *n_out = nt;
   const ClassPlan &cp = r.plan;
-  const double ns_per_tick = p->clock_khz > 0 ? 1.0e6 / p->clock_khz : 10.0;
+  const double ns_per_tick = p->ctx->clock_khz > 0 ? 1.0e6 / p->ctx->clock_khz : 10.0;
   for (uint64_t t = 0; t < nt && t < cap; ++t) {
     if (t_begin_ns) t_begin_ns[t] = (uint64_t)(r.log_host[t].t_begin * ns_per_tick);
     if (t_end_ns) t_end_ns[t] = (uint64_t)(r.log_host[t].t_end * ns_per_tick);

@@ -6,8 +6,9 @@
 
 namespace ft {
 
-// Persistent copy kernel of one link class. T.ticket must be zero when it starts.
-hipError_t launch_copy(const ClassTable &T, uint32_t workgroups, bool nontemporal, hipStream_t stream);
+// Persistent copy kernel of one link class (0 host->pool, 1 pool->host, 2 pool->pool).
+// T.ticket must be zero when it starts.
+hipError_t launch_copy(const ClassTable &T, int link_class, uint32_t workgroups, hipStream_t stream);
 // Decode every chunk rank with the device function the copy kernel uses (test hook).
 hipError_t launch_decode(const ClassTable &T, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap,
                          hipStream_t stream);

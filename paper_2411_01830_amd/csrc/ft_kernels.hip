@@ -330,7 +330,10 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
 // i+1 (scalar table reads) while the stores drain; the barrier at the end of the
 // iteration waits for them. Keeping a CU's reads and writes in separate bursts, one
 // workgroup per CU, is what the memory controllers serve fastest.
-template <bool NT>
+//
+// CLS (the link class) changes no code; it gives each class's kernel a name of its own
+// so that profiles keep host-link launches and pool->pool launches apart.
+template <bool NT, int CLS>
 __global__ __launch_bounds__(kThreads) void ft_copy_kernel(ClassTable T) {
   __shared__ unsigned long long s_ticket[2];
   __shared__ u32x4 s_stage[kStageVec];
@@ -418,12 +421,15 @@ __global__ __launch_bounds__(kThreads) void ft_plain_copy_kernel(u32x4 *dst, con
   for (; i < nvec; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
-hipError_t launch_copy(const ClassTable &T, uint32_t workgroups, bool nontemporal, hipStream_t stream) {
+hipError_t launch_copy(const ClassTable &T, int link_class, uint32_t workgroups, hipStream_t stream) {
   if (workgroups == 0) return hipErrorInvalidValue;
-  if (nontemporal)
-    hipLaunchKernelGGL(ft_copy_kernel<true>, dim3(workgroups), dim3(kThreads), 0, stream, T);
-  else
-    hipLaunchKernelGGL(ft_copy_kernel<false>, dim3(workgroups), dim3(kThreads), 0, stream, T);
+  const dim3 grid(workgroups), block(kThreads);
+  switch (link_class) {
+    case 0: hipLaunchKernelGGL((ft_copy_kernel<true, 0>), grid, block, 0, stream, T); break;
+    case 1: hipLaunchKernelGGL((ft_copy_kernel<true, 1>), grid, block, 0, stream, T); break;
+    case 2: hipLaunchKernelGGL((ft_copy_kernel<true, 2>), grid, block, 0, stream, T); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

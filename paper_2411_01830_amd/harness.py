@@ -15,7 +15,7 @@ POOL_FILL = 0xA5
 
 
 class GpuEngine:
-    def __init__(self, device=0, register_window=True):
+    def __init__(self, device=0, register_window=True, reuse_memory=False):
         if not torch.cuda.is_available():
             raise RuntimeError("GpuEngine needs a GPU; the engine has no CPU path")
         self.device = device
@@ -27,14 +27,23 @@ class GpuEngine:
         self.host_np = None
         self.register_window = register_window
         self.default_flags = 0
+        # reuse_memory: device segments and the pinned arena survive close_pool() and are
+        # handed out again, in the same order, to the next pool_create / pool_grow, so a
+        # benchmark step pays for the engine's work and not for hipMalloc
+        self.reuse_memory = reuse_memory
+        self._seg_cache = []
+        self._seg_next = 0
 
     # ---- caller-owned memory ---------------------------------------------------
     def host_arena(self, nbytes, fill=HOST_FILL):
         nbytes = max(int(nbytes), 4096)
-        self.host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
-        self.host_np = self.host.numpy()
-        if fill is not None:
-            self.host_np[:] = fill
+        if self.reuse_memory and self.host is not None and self.host.numel() == nbytes:
+            pass
+        else:
+            self.host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+            self.host_np = self.host.numpy()
+            if fill is not None:
+                self.host_np[:] = fill
         if self.pool is not None and self.register_window:
             ft.host_window_add(self.pool, self.host.data_ptr(), nbytes)
 
@@ -45,9 +54,18 @@ class GpuEngine:
         return self.host_np[off:off + n].copy()
 
     def _segment(self, nbytes, fill):
+        if self.reuse_memory and self._seg_next < len(self._seg_cache) and \
+                self._seg_cache[self._seg_next].numel() == int(nbytes):
+            t = self._seg_cache[self._seg_next]
+            self._seg_next += 1
+            return t
         t = torch.empty(int(nbytes), dtype=torch.uint8, device=self.dev)
         if fill is not None:
             t.fill_(fill)
+        if self.reuse_memory:
+            del self._seg_cache[self._seg_next:]
+            self._seg_cache.append(t)
+            self._seg_next += 1
         assert t.data_ptr() % 256 == 0
         return t
 
@@ -103,11 +121,18 @@ class GpuEngine:
     def job_schedule(self, job, cls):
         return ft.job_schedule(self.pool, job, cls)
 
-    def close(self):
+    def close_pool(self):
+        """Destroy the pool handle; with reuse_memory the memory stays for the next pool."""
         if self.pool is not None:
-            torch.cuda.synchronize(self.dev)
             ft.pool_destroy(self.pool)
             self.pool = None
         self.segments = []
+        self._seg_next = 0
+
+    def close(self):
+        if self.pool is not None:
+            torch.cuda.synchronize(self.dev)
+        self.close_pool()
+        self._seg_cache = []
         self.host = None
         self.host_np = None

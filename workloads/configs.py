@@ -230,5 +230,23 @@ def large_mixed(scale=1.0, seed=BASE_SEED + 5):
     return plan
 
 
+def first_submits(plan, count):
+    """The same plan cut after its first `count` submits (a bounded sample of the workload)."""
+    steps = []
+    seen = 0
+    names = []
+    for st in plan.steps:
+        if st[0] == "wait":
+            continue
+        steps.append(st)
+        if st[0] == "submit":
+            names.append(st[1])
+            seen += 1
+            if seen == count:
+                break
+    steps += [("wait", n) for n in names]
+    return Plan(plan.name, plan.slab_bytes, plan.pool_bytes, plan.host_bytes, list(plan.grow_to), steps)
+
+
 CONFIGS = {"tiny": tiny, "traffic": traffic, "feature": feature,
            "contended": contended, "large_mixed": large_mixed}
