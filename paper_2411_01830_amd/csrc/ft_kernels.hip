@@ -56,7 +56,6 @@ constexpr uint32_t kThreads = 256;  // 4 wavefronts per workgroup, one workgroup
 constexpr uint32_t kUnroll = 16;    // 16-byte loads a lane has in flight before its first store:
                                     // 256 lanes x 16 x 16 B = one 64 KiB block per workgroup
 constexpr uint32_t kBlockVec = kThreads * kUnroll;
-constexpr uint32_t kStageVec = 2048;  // source granules staged through LDS per pass (32 KiB)
 
 // Every payload address (pool memory or pinned host memory) is a global-segment
 // address. Saying so keeps the copies off the flat path, whose loads also count on
@@ -107,36 +106,48 @@ __device__ __forceinline__ void store_granule(uint64_t ga, u32x4 v, uint32_t lo,
   }
 }
 
-// Copy n bytes from s0 to d0, any alignment, with lanes lane, lane+L, ... of a group of
-// L lanes (short rows of pitched descriptors). Works in destination granules (aligned
-// 16 bytes): full granules are written with one vector store, the first and last with
-// byte stores of only the bytes that belong to the range. Source reads are aligned
-// 16-byte loads of granules that hold at least one byte of the source range, so
-// nothing outside the pages of the range is touched; when source and destination
-// differ in alignment two loads are merged.
-template <bool NT>
-__device__ __forceinline__ void copy_span(uint64_t d0, uint64_t s0, uint64_t n, uint32_t lane, uint32_t L) {
-  const uint64_t d1 = d0 + n, s1 = s0 + n;
-  const uint64_t g0 = d0 & ~15ull;
-  const uint64_t ngran = (((d1 + 15) & ~15ull) - g0) >> 4;
-  const uint64_t delta = s0 - d0;
-  const uint32_t shift = (uint32_t)(delta & 15);
-  for (uint64_t g = lane; g < ngran; g += L) {
-    const uint64_t ga = g0 + (g << 4);
-    const uint64_t sa = ga + delta;
-    u32x4 v;
-    if (shift == 0) {
-      v = ld16<NT>(sa);
-    } else {
-      const uint64_t a0 = sa & ~15ull, a1 = a0 + 16;
-      u32x4 A = {0, 0, 0, 0}, B = {0, 0, 0, 0};
-      if (a0 + 16 > s0 && a0 < s1) A = ld16<false>(a0);
-      if (a1 + 16 > s0 && a1 < s1) B = ld16<false>(a1);
-      v = funnel(A, B, shift);
+// Short rows of a pitched descriptor. A group of L lanes owns a row and every lane one
+// destination granule (aligned 16 bytes) of it, so L >= granules per row. Each pass a
+// group takes R rows: all 2*R aligned source loads are issued before the first store.
+// Loads are never predicated - the address of a granule that holds no byte of the row
+// is clamped into the row's own source range, and what it returns is never stored - so
+// the code stays a straight line. Stores write only bytes of the destination range:
+// whole granules with one vector store, the first and last of a row byte-wise.
+template <bool NT, uint32_t L, uint32_t R>
+__device__ __forceinline__ void copy_rows_grouped(const Xfer &X, uint64_t r0, uint64_t c0, uint64_t rl, uint64_t cl,
+                                                  uint32_t tid) {
+  constexpr uint32_t kGroups = kThreads / L;
+  const uint32_t g = tid / L, l = tid % L;
+  const uint64_t rb = X.row_bytes;
+  for (uint64_t base = r0; base <= rl; base += (uint64_t)kGroups * R) {
+    u32x4 A[R], B[R];
+    uint64_t ga[R];
+    uint32_t lo[R], hi[R], sh[R];
+#pragma unroll
+    for (uint32_t k = 0; k < R; ++k) {
+      uint64_t r = base + g + (uint64_t)k * kGroups;
+      const bool valid = r <= rl;
+      r = valid ? r : rl;
+      const uint64_t ca = r == r0 ? c0 : 0, cb = r == rl ? cl : rb;
+      const uint64_t d0 = X.dst + r * X.dst_pitch + ca, d1 = d0 + (cb - ca);
+      const uint64_t s0 = X.src + r * X.src_pitch + ca, s1 = s0 + (cb - ca);
+      const uint64_t first = s0 & ~15ull, last = (s1 - 1) & ~15ull;
+      ga[k] = (d0 & ~15ull) + ((uint64_t)l << 4);
+      const bool active = valid && ga[k] < d1;
+      lo[k] = ga[k] < d0 ? (uint32_t)(d0 - ga[k]) : 0u;
+      hi[k] = !active ? 0u : ga[k] + 16 > d1 ? (uint32_t)(d1 - ga[k]) : 16u;
+      const uint64_t sa = ga[k] + (s0 - d0);
+      sh[k] = (uint32_t)(sa & 15);
+      uint64_t a0 = sa & ~15ull, a1 = a0 + 16;
+      a0 = a0 < first ? first : a0 > last ? last : a0;
+      a1 = a1 < first ? first : a1 > last ? last : a1;
+      A[k] = ld16<NT>(a0);
+      B[k] = ld16<NT>(a1);
     }
-    const uint32_t lo = ga < d0 ? (uint32_t)(d0 - ga) : 0u;
-    const uint32_t hi = ga + 16 > d1 ? (uint32_t)(d1 - ga) : 16u;
-    store_granule<NT>(ga, v, lo, hi);
+#pragma unroll
+    for (uint32_t k = 0; k < R; ++k) {
+      if (lo[k] < hi[k]) store_granule<NT>(ga[k], funnel(A[k], B[k], sh[k]), lo[k], hi[k]);
+    }
   }
 }
 
@@ -187,57 +198,65 @@ __device__ __forceinline__ void copy_vectors(uint64_t d, uint64_t s, uint64_t nv
   if (tid < rest) st16<NT>(d + ((uint64_t)tid << 4), ld16<NT>(s + ((uint64_t)tid << 4)));
 }
 
-// Source and destination differ in alignment: the aligned 16-byte granules that cover
-// the source run are loaded once, parked in LDS, and every lane builds one aligned
-// destination vector from the two neighbouring granules it needs. Global traffic is
-// the same as for the aligned case; only the first and last destination granule are
-// written byte-wise. Loads are never predicated: an index past the run is clamped to
-// the run's last granule (its value is parked but never used for a byte that is
-// stored), which keeps the load sequence a straight line.
+// Source and destination differ in alignment. Work is laid out so that a wavefront
+// owns 1024 consecutive destination granules of a 64 KiB block (row j of the wavefront =
+// granules j*64 .. j*64+63): every lane loads the aligned source granule under each of
+// its destination granules, fetches the following granule from the next lane (lane 63
+// from lane 0 of the next row, all inside the wavefront), and funnels the two into one
+// aligned destination vector. HBM traffic equals the aligned case; no barrier and no
+// LDS storage is needed (the lane exchange uses the LDS crossbar only). Loads are never
+// predicated: an address outside the run is clamped to the run's first/last granule and
+// what it returns is never stored.
 template <bool NT>
-__device__ __forceinline__ void copy_shifted(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid, u32x4 *stage) {
-  constexpr uint32_t kLoads = kStageVec / kThreads;  // per lane and pass
+__device__ __forceinline__ void copy_shifted(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid) {
   const uint32_t shift = (uint32_t)((s0 - d0) & 15);  // != 0
   const uint64_t d1 = d0 + n, s1 = s0 + n;
   const uint64_t first = s0 & ~15ull, last = (s1 - 1) & ~15ull;  // granules holding source bytes
-  uint64_t ga = d0 & ~15ull;  // first destination granule of this pass
-  while (ga < d1) {
-    // source byte that lands on ga, and the aligned granule holding it
-    const uint64_t sa = ga + (s0 - d0);
-    const uint64_t a0 = sa & ~15ull;
-    // destination granule i needs source granules i and i+1 of this pass
-    uint64_t ngran = (((d1 + 15) & ~15ull) - ga) >> 4;
-    if (ngran > kStageVec - 1) ngran = kStageVec - 1;
-    __syncthreads();  // the previous pass has finished reading the stage
-    u32x4 v[kLoads];
+  const uint64_t g0 = d0 & ~15ull;                               // first destination granule
+  const uint64_t a_base = (g0 + (s0 - d0)) & ~15ull;             // source granule under it
+  const uint64_t ngran = (((d1 + 15) & ~15ull) - g0) >> 4;
+  const uint32_t wave = tid >> 6, lane = tid & 63;
+  for (uint64_t blk = 0; blk < ngran; blk += kBlockVec) {
+    const uint64_t wbase = blk + (uint64_t)wave * (kUnroll * 64);  // this wavefront's first granule
+    u32x4 A[kUnroll + 1];
 #pragma unroll
-    for (uint32_t j = 0; j < kLoads; ++j) {
-      uint64_t a = a0 + ((uint64_t)(tid + j * kThreads) << 4);
+    for (uint32_t j = 0; j <= kUnroll; ++j) {
+      uint64_t a = a_base + ((wbase + j * 64 + lane) << 4);
       a = a < first ? first : a;
       a = a > last ? last : a;
-      v[j] = ld16<NT>(a);
+      A[j] = ld16<NT>(a);
     }
 #pragma unroll
-    for (uint32_t j = 0; j < kLoads; ++j) stage[tid + j * kThreads] = v[j];
-    __syncthreads();
-#pragma unroll
-    for (uint32_t j = 0; j < kLoads; ++j) {
-      const uint32_t i = tid + j * kThreads;
-      if (i < ngran) {
-        const uint64_t g = ga + ((uint64_t)i << 4);
-        const u32x4 out = funnel(stage[i], stage[i + 1], shift);
+    for (uint32_t j = 0; j < kUnroll; ++j) {
+      // all 64 lanes are active here (control flow is uniform across the workgroup), so
+      // readfirstlane returns lane 0's value of the next row
+      u32x4 Nx, Bv;
+      Nx.x = __builtin_amdgcn_readfirstlane(A[j + 1].x);
+      Nx.y = __builtin_amdgcn_readfirstlane(A[j + 1].y);
+      Nx.z = __builtin_amdgcn_readfirstlane(A[j + 1].z);
+      Nx.w = __builtin_amdgcn_readfirstlane(A[j + 1].w);
+      // the exchange must run with every lane enabled (a disabled lane contributes
+      // nothing), so it is done before, not inside, the per-lane choice
+      const uint32_t sx = __shfl_down(A[j].x, 1), sy = __shfl_down(A[j].y, 1);
+      const uint32_t sz = __shfl_down(A[j].z, 1), sw = __shfl_down(A[j].w, 1);
+      Bv.x = lane == 63 ? Nx.x : sx;
+      Bv.y = lane == 63 ? Nx.y : sy;
+      Bv.z = lane == 63 ? Nx.z : sz;
+      Bv.w = lane == 63 ? Nx.w : sw;
+      const uint64_t gi = wbase + j * 64 + lane;
+      if (gi < ngran) {
+        const uint64_t g = g0 + (gi << 4);
         const uint32_t lo = g < d0 ? (uint32_t)(d0 - g) : 0u;
         const uint32_t hi = g + 16 > d1 ? (uint32_t)(d1 - g) : 16u;
-        store_granule<NT>(g, out, lo, hi);
+        store_granule<NT>(g, funnel(A[j], Bv, shift), lo, hi);
       }
     }
-    ga += ngran << 4;
   }
 }
 
 // One contiguous piece with the whole workgroup.
 template <bool NT>
-__device__ __forceinline__ void copy_piece(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid, u32x4 *stage) {
+__device__ __forceinline__ void copy_piece(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid) {
   if (((d0 ^ s0) & 15) == 0) {
     if (n < 64) {
       if (tid < n) st8(d0 + tid, ld8(s0 + tid));
@@ -252,32 +271,30 @@ __device__ __forceinline__ void copy_piece(uint64_t d0, uint64_t s0, uint64_t n,
     if (tid < tail) st8(d0 + toff + tid, ld8(s0 + toff + tid));
     copy_vectors<NT>(d0 + head, s0 + head, nvec, tid);
   } else {
-    copy_shifted<NT>(d0, s0, n, tid, stage);
+    copy_shifted<NT>(d0, s0, n, tid);
   }
 }
 
 // Payload bytes [p, p+take) of a pitched descriptor.
 template <bool NT>
-__device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid, u32x4 *stage) {
+__device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid) {
   const uint64_t rb = X.row_bytes;
   const uint64_t pend = p + take;
   const uint64_t r0 = p / rb;
   const uint64_t c0 = p - r0 * rb;
   const uint64_t rl = (pend - 1) / rb;
   const uint64_t cl = pend - rl * rb;  // one past the last column in the last row
-  if (rb > 2048) {
+  // a row of rb bytes at any alignment spans at most (rb + 30) / 16 granules
+  if (rb <= 16 * 16 - 30) {
+    copy_rows_grouped<NT, 16, 4>(X, r0, c0, rl, cl, tid);
+  } else if (rb <= 32 * 16 - 30) {
+    copy_rows_grouped<NT, 32, 4>(X, r0, c0, rl, cl, tid);
+  } else if (rb <= 128 * 16 - 30) {
+    copy_rows_grouped<NT, 128, 4>(X, r0, c0, rl, cl, tid);
+  } else {
     for (uint64_t r = r0; r <= rl; ++r) {
       const uint64_t ca = r == r0 ? c0 : 0, cb = r == rl ? cl : rb;
-      copy_piece<NT>(X.dst + r * X.dst_pitch + ca, X.src + r * X.src_pitch + ca, cb - ca, tid, stage);
-    }
-  } else {
-    // short rows: a group of L lanes per row, several rows per pass
-    const uint32_t L = rb <= 256 ? 16u : rb <= 512 ? 32u : rb <= 1024 ? 64u : 128u;
-    const uint32_t groups = kThreads / L;
-    const uint32_t g = tid / L, l = tid % L;
-    for (uint64_t r = r0 + g; r <= rl; r += groups) {
-      const uint64_t ca = r == r0 ? c0 : 0, cb = r == rl ? cl : rb;
-      copy_span<NT>(X.dst + r * X.dst_pitch + ca, X.src + r * X.src_pitch + ca, cb - ca, l, L);
+      copy_piece<NT>(X.dst + r * X.dst_pitch + ca, X.src + r * X.src_pitch + ca, cb - ca, tid);
     }
   }
 }
@@ -336,7 +353,6 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
 template <bool NT, int CLS>
 __global__ __launch_bounds__(kThreads) void ft_copy_kernel(ClassTable T) {
   __shared__ unsigned long long s_ticket[2];
-  __shared__ u32x4 s_stage[kStageVec];
   const uint32_t tid = threadIdx.x;
   if (tid == 0) {
     const unsigned long long a = atomicAdd(T.ticket, 2ull);
@@ -371,8 +387,8 @@ __global__ __launch_bounds__(kThreads) void ft_copy_kernel(ClassTable T) {
         const uint64_t p = pos - X.stream_off;
         uint64_t take = X.row_bytes * X.rows - p;
         if (take > cur.b1 - pos) take = cur.b1 - pos;
-        if (X.rows == 1) copy_piece<NT>(X.dst + p, X.src + p, take, tid, s_stage);
-        else copy_rows<NT>(X, p, take, tid, s_stage);
+        if (X.rows == 1) copy_piece<NT>(X.dst + p, X.src + p, take, tid);
+        else copy_rows<NT>(X, p, take, tid);
         pos += take;
         if (pos < cur.b1) X = read_xfer(CT.xfers, ++x);
       }

@@ -1,0 +1,132 @@
+"""Full-size workloads in the launch configuration bench.py times (default launch
+shapes, large_mixed submitted detached), checked by what holds at any size:
+
+  * every destination range equals its source range (compared on the device or, for
+    host memory, after one copy back) - the plain definition of the result;
+  * sampled descriptors one by one against the CPU oracle on a re-based copy of just
+    their source and destination windows (canary padding included);
+  * the device's ticket order of every job and class equals the oracle's order;
+  * allocation offsets and pool growth equal the oracle pool's.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import OracleEngine, stride_order, chunk_count
+from workloads import configs, runner, make_descs, FT_HOST, FT_POOL
+from workloads import format as fmt
+
+pytestmark = pytest.mark.gpu
+
+PAD = 64
+
+
+def _class_of(d):
+    return 0 if d["src_space"] == FT_HOST else (1 if d["dst_space"] == FT_HOST else 2)
+
+
+def _view(eng, space, off, n):
+    """uint8 tensor view of n bytes at `off` of the host arena or the pool."""
+    if space == FT_HOST:
+        return eng.host[off:off + n]
+    t, o = eng._locate(off)
+    return t[o:o + n]
+
+
+def _rows(eng, d, side):
+    space = int(d[side + "_space"])
+    rows, rb = int(d["rows"]), int(d["row_bytes"])
+    pitch = int(d[side + "_pitch"]) if rows > 1 else rb
+    ext = (rows - 1) * pitch + rb
+    v = _view(eng, space, int(d[side]), ext)
+    if rows == 1:
+        return v
+    return v.as_strided((rows, rb), (pitch, 1))
+
+
+def _oracle_one(eng, d):
+    """Run one descriptor through the oracle on re-based windows and compare the
+    destination window (with PAD bytes either side) with what the device holds."""
+    rows, rb = int(d["rows"]), int(d["row_bytes"])
+    sp = int(d["src_pitch"]) if rows > 1 else rb
+    dp = int(d["dst_pitch"]) if rows > 1 else rb
+    es, ed = (rows - 1) * sp + rb, (rows - 1) * dp + rb
+    src_bytes = _view(eng, int(d["src_space"]), int(d["src"]), es).cpu().numpy()
+    dst_lo = max(0, int(d["dst"]) - PAD)
+    lead = int(d["dst"]) - dst_lo
+    got = _view(eng, int(d["dst_space"]), dst_lo, lead + ed + PAD).cpu().numpy()
+    orc = OracleEngine()
+    slab = 4096
+    orc.host_arena(((es + ed + 4 * PAD) // slab + 2) * slab)
+    orc.pool_create(((es + ed + 4 * PAD) // slab + 2) * slab * 2, slab)
+    a = orc.slab_alloc(es)
+    b = orc.slab_alloc(lead + ed + PAD)
+    # the destination window starts as the device's window looked before the job,
+    # except inside the rows, which the job overwrites anyway
+    orc.write_pool(b, got)
+    orc.write_pool(a, src_bytes)
+    one = make_descs([dict(func=0, src_space=FT_POOL, dst_space=FT_POOL, src=a, dst=b + lead,
+                           row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp)])
+    orc.wait(orc.submit(one, [1], 4096))
+    want = orc.read_pool(b, lead + ed + PAD)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("name", ["tiny", "traffic", "feature", "contended", "large_mixed"])
+def test_full_size_workload(name):
+    import torch
+    from paper_2411_01830_amd import binding as ft, harness
+    print(f"full-size case {name}", flush=True)
+    plan = configs.CONFIGS[name](1.0)
+    # the oracle's pool bookkeeping alone (no memory image at this size)
+    pool = oracle.Pool(plan.pool_bytes, plan.slab_bytes)
+    want_off, total, targets, grows = {}, plan.pool_bytes, list(plan.grow_to), []
+    for st in plan.steps:
+        if st[0] != "alloc":
+            continue
+        while True:
+            try:
+                want_off[st[1]] = pool.alloc(st[2])
+                break
+            except oracle.OracleError as e:
+                assert e.code == oracle.ENOMEM
+                t = targets.pop(0)
+                pool.grow(t - total)
+                grows.append(t - total)
+                total = t
+    eng = harness.GpuEngine()
+    flags = ft.FT_KEEP | (ft.FT_DETACHED if name == "large_mixed" else 0)
+    try:
+        rec = runner.run_plan(plan, eng, flags=flags)
+        torch.cuda.synchronize()
+        assert rec.alloc_off == want_off
+        assert rec.grows == grows
+        rng = np.random.default_rng(5)
+        for jname, arr in rec.descs.items():
+            # (1) every destination equals its source
+            for d in arr:
+                s, t = _rows(eng, d, "src"), _rows(eng, d, "dst")
+                if s.device != t.device:
+                    s, t = s.cpu(), t.cpu()
+                assert torch.equal(s, t), (jname, int(d["src"]), int(d["dst"]))
+            # (2) sampled descriptors through the oracle: odd alignments, extremes, random
+            sizes = arr["row_bytes"].astype(np.int64) * arr["rows"].astype(np.int64)
+            odd = np.flatnonzero(((arr["src"] - arr["dst"]) % 16 != 0) & (sizes < (8 << 20)))
+            pick = set(odd[:6].tolist()) | {int(np.argmin(sizes))}
+            small = np.flatnonzero(sizes < (8 << 20))
+            pick |= set(rng.choice(small, size=min(6, len(small)), replace=False).tolist())
+            for i in sorted(pick):
+                _oracle_one(eng, arr[i])
+            # (3) the device's ticket order
+            w = rec.weights[jname]
+            C = rec.chunk_bytes[jname]
+            for cls in (0, 1, 2):
+                S = [0] * len(w)
+                for d in arr:
+                    if _class_of(d) == cls:
+                        S[int(d["func"])] += int(d["row_bytes"]) * int(d["rows"])
+                want = stride_order([chunk_count(x, C) for x in S], w)
+                assert eng.job_schedule(rec.jobs[jname], cls) == want, (jname, cls)
+            ft.job_release(eng.pool, rec.jobs[jname])
+    finally:
+        eng.close()
