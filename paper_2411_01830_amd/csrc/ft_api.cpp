@@ -234,8 +234,11 @@ uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
   return with_p2p ? 32u : 64u;
 }
 
-uint64_t default_tile(int cls, bool with_p2p) {
-  if (cls == FT_P2P) return 64u * 1024u;
+// short_rows: most of the class's payload sits in pitched descriptors with rows of at
+// most 2 KiB. Those tiles are bound by latency, not bandwidth, and a job of them has
+// few tiles per workgroup, so smaller tiles balance it better.
+uint64_t default_tile(int cls, bool with_p2p, bool short_rows) {
+  if (cls == FT_P2P) return short_rows ? 16u * 1024u : 64u * 1024u;
   return with_p2p ? 8u * 1024u : 16u * 1024u;
 }
 
@@ -450,8 +453,12 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       std::memcpy(h + lay[c].xfers, cp.xfers.data(), cp.xfers.size() * sizeof(Xfer));
       const Tuning &tn = p->tuning[c];
       const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
-      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p), &r.tile_bytes,
-                 &r.tiles_per_chunk);
+      uint64_t short_bytes = 0;
+      for (const Xfer &x : cp.xfers)
+        if (x.rows > 1 && x.row_bytes <= 2048) short_bytes += x.row_bytes * x.rows;
+      const bool short_rows = 2 * short_bytes > cp.payload;
+      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, short_rows),
+                 &r.tile_bytes, &r.tiles_per_chunk);
       ClassTable &T = r.table;
       T.phases = reinterpret_cast<const Phase *>(d + lay[c].phases);
       T.slots = reinterpret_cast<const Slot *>(d + lay[c].slots);

@@ -286,9 +286,9 @@ __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t ta
   const uint64_t cl = pend - rl * rb;  // one past the last column in the last row
   // a row of rb bytes at any alignment spans at most (rb + 30) / 16 granules
   if (rb <= 16 * 16 - 30) {
-    copy_rows_grouped<NT, 16, 4>(X, r0, c0, rl, cl, tid);
+    copy_rows_grouped<NT, 16, 8>(X, r0, c0, rl, cl, tid);
   } else if (rb <= 32 * 16 - 30) {
-    copy_rows_grouped<NT, 32, 4>(X, r0, c0, rl, cl, tid);
+    copy_rows_grouped<NT, 32, 8>(X, r0, c0, rl, cl, tid);
   } else if (rb <= 128 * 16 - 30) {
     copy_rows_grouped<NT, 128, 4>(X, r0, c0, rl, cl, tid);
   } else {

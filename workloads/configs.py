@@ -130,8 +130,11 @@ def traffic(scale=1.0, seed=BASE_SEED + 2):
                                 dst=("pool", rec_id[c], doff + ch * h * w)))
     slabs = sum(_up(frame_bytes, MiB) for _ in range(nframes)) + sum(_up(max(r, 16), MiB) for r in run)
     plan.pool_bytes = slabs + 4 * MiB
-    plan.steps += [("submit", "frames", a_descs, [1], 2 * MiB), ("wait", "frames"),
-                   ("submit", "crops", b_descs, [1, 1], 256 * KiB), ("wait", "crops")]
+    # both jobs go to one stream, which runs them in submit order: the crops job reads
+    # the frames only after they have landed, with no host wait in between
+    plan.steps += [("submit", "frames", a_descs, [1], 2 * MiB),
+                   ("submit", "crops", b_descs, [1, 1], 256 * KiB),
+                   ("wait", "frames"), ("wait", "crops")]
     return plan
 
 
