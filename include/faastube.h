@@ -91,7 +91,8 @@ typedef struct ft_class_stats {
   uint64_t tile_bytes;    /* bytes one ticket moves (last tile of a chunk may be shorter) */
   uint32_t workgroups;    /* persistent workgroups launched (0 on the DMA path) */
   uint32_t _pad;
-  float device_ms;        /* FT_TIMING: event time around the class's work, else -1 */
+  float device_ms;        /* FT_TIMING: duration of the class's kernel (events bound to its dispatch;
+                             on the FT_PATH_DMA path: events around its copy calls), else -1 */
   float _pad2;
 } ft_class_stats;
 
@@ -211,6 +212,17 @@ int ft_job_schedule(ft_pool *p, ft_job_t job, int link_class, uint32_t *func_out
 int ft_job_log(ft_pool *p, ft_job_t job, int link_class, uint64_t *t_begin_ns, uint64_t *t_end_ns,
                uint32_t *func_out, uint32_t *chunk_out, uint32_t *bytes_out, uint64_t cap,
                uint64_t *n_out);
+
+/*
+ * FT_LOG: which workgroup moved each ticket (host array of `cap` entries, may be NULL)
+ * and, per workgroup, the device clock (ns) when it started and when it found no
+ * ticket left (host arrays of `wg_cap` entries, may be NULL); *nwg_out receives the
+ * number of workgroups of the launch. Same clock as ft_job_log. For tuning: shows
+ * start-up skew, gaps between tiles and the idle tail of a launch.
+ */
+int ft_job_log_workgroups(ft_pool *p, ft_job_t job, int link_class, uint32_t *ticket_wg, uint64_t cap,
+                          uint64_t *wg_entry_ns, uint64_t *wg_exit_ns, uint32_t wg_cap,
+                          uint32_t *nwg_out);
 
 /*
  * Launch shape of one class: number of persistent workgroups (0 = default for the

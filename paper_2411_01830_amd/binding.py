@@ -13,7 +13,7 @@ FT_VALIDATE, FT_LOG, FT_PATH_DMA, FT_TIMING, FT_DETACHED, FT_KEEP = 1, 2, 4, 8, 
 
 EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
            "ft_pool_ptr", "ft_host_window_add", "ft_submit_transfers", "ft_wait", "ft_job_release",
-           "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_set_tuning", "ft_plan_schedule",
+           "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule",
            "ft_plain_copy", "ft_strerror", "ft_last_hip_error"]
 
 
@@ -58,6 +58,7 @@ def _load():
         "ft_job_stats": (i32, [vp, u64, P(JobStats)]),
         "ft_job_schedule": (i32, [vp, u64, i32, vp, vp, u64, P(u64)]),
         "ft_job_log": (i32, [vp, u64, i32, vp, vp, vp, vp, vp, u64, P(u64)]),
+        "ft_job_log_workgroups": (i32, [vp, u64, i32, vp, u64, vp, vp, u32, P(u32)]),
         "ft_set_tuning": (i32, [vp, i32, u32, u64]),
         "ft_plan_schedule": (i32, [vp, vp, u32, u64, vp, vp, u64, P(u64)]),
         "ft_plain_copy": (i32, [vp, vp, u64, u32, vp]),
@@ -165,6 +166,17 @@ def job_log(pool, job, link_class):
                            k.ctypes.data, b.ctypes.data, n.value, C.byref(n)), pool)
     s = slice(0, n.value)
     return {"t_begin_ns": tb[s], "t_end_ns": te[s], "func": f[s], "chunk": k[s], "bytes": b[s]}
+
+
+def job_log_workgroups(pool, job, link_class, ntickets):
+    """(workgroup of each ticket, entry ns per workgroup, exit ns per workgroup)."""
+    nwg = C.c_uint32()
+    _check(_lib.ft_job_log_workgroups(pool, job, link_class, None, 0, None, None, 0, C.byref(nwg)), pool)
+    wg = np.zeros(max(int(ntickets), 1), np.uint32)
+    t_in, t_out = np.zeros(max(nwg.value, 1), np.uint64), np.zeros(max(nwg.value, 1), np.uint64)
+    _check(_lib.ft_job_log_workgroups(pool, job, link_class, wg.ctypes.data, int(ntickets), t_in.ctypes.data,
+                                      t_out.ctypes.data, nwg.value, C.byref(nwg)), pool)
+    return wg[:int(ntickets)], t_in[:nwg.value], t_out[:nwg.value]
 
 
 def set_tuning(pool, link_class, workgroups=0, tile_bytes=0):

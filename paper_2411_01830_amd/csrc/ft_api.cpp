@@ -34,9 +34,13 @@ struct ClassRun {
   uint64_t tile_bytes = 0;
   uint32_t tiles_per_chunk = 0;
   uint32_t workgroups = 0;
-  hipEvent_t ev_begin = nullptr, ev_done = nullptr;
+  // ev_done orders the caller's stream and ft_wait after the class's work. With FT_TIMING,
+  // ev_begin / ev_end bracket it: bound to the kernel's dispatch on the kernel path,
+  // recorded around the copy calls on the DMA path.
+  hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_done = nullptr;
   Blob log;
   std::vector<LogEntry> log_host;
+  std::vector<WgLogEntry> wg_log_host;
   float device_ms = -1.f;
 };
 
@@ -203,7 +207,7 @@ uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 // Byte layout of one class's tables inside the job's blob.
 struct Layout {
-  uint64_t ticket, phases, slots, funcs, xfers, end;
+  uint64_t ticket, phases, slots, funcs, xfers, chunks, end;
 };
 
 Layout layout_of(const ClassPlan &cp, uint64_t base) {
@@ -213,7 +217,8 @@ Layout layout_of(const ClassPlan &cp, uint64_t base) {
   l.slots = align_up(l.phases + cp.phases.size() * sizeof(Phase), 64);
   l.funcs = align_up(l.slots + cp.slots.size() * sizeof(Slot), 64);
   l.xfers = align_up(l.funcs + cp.funcs.size() * sizeof(Func), 64);
-  l.end = align_up(l.xfers + cp.xfers.size() * sizeof(Xfer), 256);
+  l.chunks = align_up(l.xfers + cp.xfers.size() * sizeof(Xfer), 64);
+  l.end = align_up(l.chunks + cp.chunk_desc.size() * sizeof(uint32_t), 256);
   return l;
 }
 
@@ -250,12 +255,11 @@ hipMemcpyKind kind_of(int cls) {
 int run_dma(ft_pool *p, const ClassPlan &cp, uint64_t C, int cls, hipStream_t stream) {
   const hipMemcpyKind kind = kind_of(cls);
   for (uint64_t rank = 0; rank < cp.nchunks; ++rank) {
-    const ChunkId id = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(),
-                                   cp.funcs.data(), rank);
+    const ChunkId id = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(), rank);
     const Func &fn = cp.funcs[id.fl];
     uint64_t pos = id.k * C;
     uint64_t end = pos + C < fn.stream_bytes ? pos + C : fn.stream_bytes;
-    uint32_t x = find_xfer(cp.xfers.data(), fn.desc_off, fn.ndesc, pos);
+    uint32_t x = find_xfer(cp.xfers.data(), fn.desc_off, fn.desc_off + fn.ndesc - 1, pos);
     while (pos < end) {
       const Xfer &X = cp.xfers[x];
       uint64_t q = pos - X.stream_off;
@@ -302,11 +306,11 @@ void retire(ft_pool *p, Job *job) {
 
 void release_device_side(ft_pool *p, Job *job) {
   put_blob(p, job->tables);
-  const bool timing = (job->flags & FT_TIMING) != 0;
   for (int c = 0; c < FT_NCLASS; ++c) {
     put_blob(p, job->run[c].log);
-    put_event(p, timing, job->run[c].ev_begin);
-    put_event(p, timing, job->run[c].ev_done);
+    put_event(p, true, job->run[c].ev_begin);
+    put_event(p, true, job->run[c].ev_end);
+    put_event(p, false, job->run[c].ev_done);
   }
 }
 
@@ -316,11 +320,14 @@ int wait_locked(ft_pool *p, Job *job) {
     ClassRun &r = job->run[c];
     if (!r.used) continue;
     FT_HIP(p, hipEventSynchronize(r.ev_done));
-    if (job->flags & FT_TIMING) FT_HIP(p, hipEventElapsedTime(&r.device_ms, r.ev_begin, r.ev_done));
+    if (job->flags & FT_TIMING) FT_HIP(p, hipEventElapsedTime(&r.device_ms, r.ev_begin, r.ev_end));
     if ((job->flags & FT_LOG) && r.log.dev != nullptr) {
       r.log_host.resize(r.table.ntickets);
       FT_HIP(p, hipMemcpy(r.log_host.data(), r.log.dev, r.table.ntickets * sizeof(LogEntry),
                           hipMemcpyDeviceToHost));
+      r.wg_log_host.resize(r.workgroups);
+      FT_HIP(p, hipMemcpy(r.wg_log_host.data(), r.log.dev + r.table.ntickets * sizeof(LogEntry),
+                          r.workgroups * sizeof(WgLogEntry), hipMemcpyDeviceToHost));
     }
   }
   job->waited = true;
@@ -451,6 +458,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       std::memcpy(h + lay[c].slots, cp.slots.data(), cp.slots.size() * sizeof(Slot));
       std::memcpy(h + lay[c].funcs, cp.funcs.data(), cp.funcs.size() * sizeof(Func));
       std::memcpy(h + lay[c].xfers, cp.xfers.data(), cp.xfers.size() * sizeof(Xfer));
+      std::memcpy(h + lay[c].chunks, cp.chunk_desc.data(), cp.chunk_desc.size() * sizeof(uint32_t));
       const Tuning &tn = p->tuning[c];
       const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
       uint64_t short_bytes = 0;
@@ -464,8 +472,10 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       T.slots = reinterpret_cast<const Slot *>(d + lay[c].slots);
       T.funcs = reinterpret_cast<const Func *>(d + lay[c].funcs);
       T.xfers = reinterpret_cast<const Xfer *>(d + lay[c].xfers);
+      T.chunk_desc = cp.chunk_desc.empty() ? nullptr : reinterpret_cast<const uint32_t *>(d + lay[c].chunks);
       T.ticket = reinterpret_cast<unsigned long long *>(d + lay[c].ticket);
       T.log = nullptr;
+      T.wg_log = nullptr;
       T.nchunks = cp.nchunks;
       T.ntickets = cp.nchunks * r.tiles_per_chunk;
       T.chunk_bytes = chunk_bytes;
@@ -477,13 +487,17 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       uint64_t wg = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
       if (wg > T.ntickets) wg = T.ntickets;
       r.workgroups = dma ? 0 : (uint32_t)wg;
+      // workgroup b starts on tickets b and b + workgroups without asking the counter
+      *reinterpret_cast<unsigned long long *>(h + lay[c].ticket) = 2ull * wg;
       if ((flags & FT_LOG) && !dma) {
-        rc = get_blob(p, T.ntickets * sizeof(LogEntry), false, &r.log);
+        rc = get_blob(p, T.ntickets * sizeof(LogEntry) + wg * sizeof(WgLogEntry), false, &r.log);
         if (rc != FT_OK) return fail(rc);
         T.log = reinterpret_cast<LogEntry *>(r.log.dev);
+        T.wg_log = reinterpret_cast<WgLogEntry *>(r.log.dev + T.ntickets * sizeof(LogEntry));
       }
-      rc = get_event(p, timing, &r.ev_done);
+      rc = get_event(p, false, &r.ev_done);
       if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_begin);
+      if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_end);
       if (rc != FT_OK) return fail(rc);
     }
 
@@ -506,18 +520,22 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       hipStream_t s = p->ctx->streams[c];
       e = hipStreamWaitEvent(s, fork, 0);
       if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(fork)");
-      if (timing) {
-        e = hipEventRecord(r.ev_begin, s);
-        if (e != hipSuccess) return hip_fail(e, "hipEventRecord(begin)");
-      }
       if (dma) {
+        if (timing) {
+          e = hipEventRecord(r.ev_begin, s);
+          if (e != hipSuccess) return hip_fail(e, "hipEventRecord(begin)");
+        }
         rc = run_dma(p, plan.cls[c], chunk_bytes, c, s);
         if (rc != FT_OK) {
           put_event(p, false, fork);
           return fail(rc);
         }
+        if (timing) {
+          e = hipEventRecord(r.ev_end, s);
+          if (e != hipSuccess) return hip_fail(e, "hipEventRecord(end)");
+        }
       } else {
-        e = launch_copy(r.table, c, r.workgroups, s);
+        e = launch_copy(r.table, c, r.workgroups, s, r.ev_begin, r.ev_end);
         if (e != hipSuccess) return hip_fail(e, "launch_copy");
       }
       e = hipEventRecord(r.ev_done, s);
@@ -635,8 +653,7 @@ int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, ui
     if (t_end_ns) t_end_ns[t] = (uint64_t)(r.log_host[t].t_end * ns_per_tick);
     if (func_out || chunk_out || bytes_out) {
       const uint64_t rank = t / r.tiles_per_chunk, ti = t % r.tiles_per_chunk;
-      const ChunkId cid = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(),
-                                      cp.funcs.data(), rank);
+      const ChunkId cid = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(), rank);
       const Func &fn = cp.funcs[cid.fl];
       uint64_t lo = ti * r.tile_bytes, hi = lo + r.tile_bytes;
       if (hi > job->chunk_bytes) hi = job->chunk_bytes;
@@ -647,6 +664,24 @@ int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, ui
       if (chunk_out) chunk_out[t] = (uint32_t)cid.k;
       if (bytes_out) bytes_out[t] = (uint32_t)(b1 - b0);
     }
+  }
+  return FT_OK;
+}
+
+int ft_job_log_workgroups(ft_pool *p, ft_job_t id, int link_class, uint32_t *ticket_wg, uint64_t cap,
+                          uint64_t *wg_entry_ns, uint64_t *wg_exit_ns, uint32_t wg_cap, uint32_t *nwg_out) {
+  if (p == nullptr || nwg_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->waited || !(it->second->flags & FT_LOG)) return FT_EINVAL;
+  const ClassRun &r = it->second->run[link_class];
+  const double ns_per_tick = p->ctx->clock_khz > 0 ? 1.0e6 / p->ctx->clock_khz : 10.0;
+  if (ticket_wg)
+    for (uint64_t t = 0; t < r.log_host.size() && t < cap; ++t) ticket_wg[t] = r.log_host[t].wg;
+  *nwg_out = (uint32_t)r.wg_log_host.size();
+  for (uint32_t w = 0; w < r.wg_log_host.size() && w < wg_cap; ++w) {
+    if (wg_entry_ns) wg_entry_ns[w] = (uint64_t)(r.wg_log_host[w].t_entry * ns_per_tick);
+    if (wg_exit_ns) wg_exit_ns[w] = (uint64_t)(r.wg_log_host[w].t_exit * ns_per_tick);
   }
   return FT_OK;
 }
@@ -675,7 +710,7 @@ int ft_plan_schedule(const uint64_t *stream_bytes, const uint32_t *weights, uint
   if (rc != FT_OK) return rc;
   *n_out = n;
   for (uint64_t rank = 0; rank < n && rank < cap; ++rank) {
-    const ChunkId id = decode_rank(phases.data(), (uint32_t)phases.size(), slots.data(), funcs.data(), rank);
+    const ChunkId id = decode_rank(phases.data(), (uint32_t)phases.size(), slots.data(), rank);
     func_out[rank] = funcs[id.fl].func;
     chunk_out[rank] = (uint32_t)id.k;
   }

@@ -7,6 +7,7 @@
 // Bytes move as 16-byte vectors, one per lane, consecutive lanes on consecutive
 // vectors, so every wavefront load/store covers 1 KiB of contiguous memory.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "ft_kernels.h"
 
@@ -53,9 +54,15 @@ __device__ __forceinline__ Xfer read_xfer(CXferP xfers, uint32_t x) {
 }
 
 constexpr uint32_t kThreads = 256;  // 4 wavefronts per workgroup, one workgroup per CU for pool->pool
-constexpr uint32_t kUnroll = 16;    // 16-byte loads a lane has in flight before its first store:
-                                    // 256 lanes x 16 x 16 B = one 64 KiB block per workgroup
-constexpr uint32_t kBlockVec = kThreads * kUnroll;
+// U, a template parameter of the copy routines: 16-byte loads a lane has in flight before
+// its first store, so a workgroup moves blocks of 256 lanes x U x 16 B. pool->pool uses
+// U = 16 (64 KiB blocks, the whole tile in registers). The host-link classes use U = 4:
+// their tiles are 8-16 KiB, and the smaller register footprint lets a host-link
+// workgroup share a CU with a pool->pool workgroup instead of taking the CU for itself.
+template <int CLS>
+struct UnrollOf {
+  static constexpr uint32_t value = CLS == 2 ? 16u : 4u;
+};
 
 // Every payload address (pool memory or pinned host memory) is a global-segment
 // address. Saying so keeps the copies off the flat path, whose loads also count on
@@ -163,120 +170,180 @@ __device__ __forceinline__ void copy_rows_of_vectors(uint64_t d, uint64_t s, uin
   for (uint32_t j = 0; j < R; ++j) st16<NT>(d + ((uint64_t)(tid + j * kThreads) << 4), v[j]);
 }
 
-// nvec aligned 16-byte vectors with the whole workgroup: 64 KiB blocks first, then
-// the remainder as blocks of 8, 4, 2 and 1 rows and one partial row.
-template <bool NT>
-__device__ __forceinline__ void copy_vectors(uint64_t d, uint64_t s, uint64_t nvec, uint32_t tid) {
-  uint64_t rows = nvec / kThreads;
-  while (rows >= kUnroll) {
-    copy_rows_of_vectors<NT, kUnroll>(d, s, tid);
-    d += (uint64_t)kBlockVec << 4;
-    s += (uint64_t)kBlockVec << 4;
-    rows -= kUnroll;
+// 1 <= nvec <= R * kThreads aligned vectors in one pass. Loads are never predicated: a
+// lane whose vector lies past the end loads the last vector instead (and does not store
+// it), so all R loads of a lane are in flight before its first store whatever nvec is.
+template <bool NT, uint32_t R>
+__device__ __forceinline__ void copy_rows_clamped(uint64_t d, uint64_t s, uint32_t nvec, uint32_t tid) {
+  u32x4 v[R];
+  const uint32_t lastv = nvec - 1;
+#pragma unroll
+  for (uint32_t j = 0; j < R; ++j) {
+    uint32_t i = tid + j * kThreads;
+    i = i < lastv ? i : lastv;
+    v[j] = ld16<NT>(s + ((uint64_t)i << 4));
   }
-  if (rows & 8) {
-    copy_rows_of_vectors<NT, 8>(d, s, tid);
-    d += 8ull * kThreads << 4;
-    s += 8ull * kThreads << 4;
+#pragma unroll
+  for (uint32_t j = 0; j < R; ++j) {
+    const uint32_t i = tid + j * kThreads;
+    if (i < nvec) st16<NT>(d + ((uint64_t)i << 4), v[j]);
   }
-  if (rows & 4) {
-    copy_rows_of_vectors<NT, 4>(d, s, tid);
-    d += 4ull * kThreads << 4;
-    s += 4ull * kThreads << 4;
-  }
-  if (rows & 2) {
-    copy_rows_of_vectors<NT, 2>(d, s, tid);
-    d += 2ull * kThreads << 4;
-    s += 2ull * kThreads << 4;
-  }
-  if (rows & 1) {
-    copy_rows_of_vectors<NT, 1>(d, s, tid);
-    d += 1ull * kThreads << 4;
-    s += 1ull * kThreads << 4;
-  }
-  const uint32_t rest = (uint32_t)(nvec % kThreads);
-  if (tid < rest) st16<NT>(d + ((uint64_t)tid << 4), ld16<NT>(s + ((uint64_t)tid << 4)));
 }
 
-// Source and destination differ in alignment. Work is laid out so that a wavefront
-// owns 1024 consecutive destination granules of a 64 KiB block (row j of the wavefront =
-// granules j*64 .. j*64+63): every lane loads the aligned source granule under each of
-// its destination granules, fetches the following granule from the next lane (lane 63
-// from lane 0 of the next row, all inside the wavefront), and funnels the two into one
-// aligned destination vector. HBM traffic equals the aligned case; no barrier and no
-// LDS storage is needed (the lane exchange uses the LDS crossbar only). Loads are never
-// predicated: an address outside the run is clamped to the run's first/last granule and
+// nvec aligned 16-byte vectors with the whole workgroup: full blocks of U rows, then one
+// clamped pass over what is left.
+template <bool NT, uint32_t U>
+__device__ __forceinline__ void copy_vectors(uint64_t d, uint64_t s, uint64_t nvec, uint32_t tid) {
+  constexpr uint32_t kBlockVec = kThreads * U;
+  while (nvec >= kBlockVec) {
+    copy_rows_of_vectors<NT, U>(d, s, tid);
+    d += (uint64_t)kBlockVec << 4;
+    s += (uint64_t)kBlockVec << 4;
+    nvec -= kBlockVec;
+  }
+  const uint32_t rest = (uint32_t)nvec;
+  if (U > 4 && rest > 4 * kThreads) copy_rows_clamped<NT, U>(d, s, rest, tid);
+  else if (rest > kThreads) copy_rows_clamped<NT, 4>(d, s, rest, tid);
+  else if (rest > 0) copy_rows_clamped<NT, 1>(d, s, rest, tid);
+}
+
+// Lane i receives lane i+1's value of v; lane 63, which has no such neighbour, receives
+// `last` (wave_shl:1 moves data one lane towards lane 0 and leaves the old value in a
+// lane without a source). Must run with all 64 lanes enabled.
+__device__ __forceinline__ uint32_t from_next_lane(uint32_t v, uint32_t last) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)last, (int)v, 0x130 /* wave_shl:1 */, 0xf, 0xf, false);
+}
+
+// 16 bytes starting 4*Q + r bytes into the 32-byte pair (A, next granule), where the
+// next granule is the next lane's A, or for lane 63 lane 0's value of `nextrow`.
+// Q and r are the same for a whole run, so every selection is fixed at compile time:
+// Q+1 lane exchanges and four byte-aligns per vector.
+template <uint32_t Q>
+__device__ __forceinline__ u32x4 shifted_vector(u32x4 A, u32x4 nextrow, uint32_t r) {
+  uint32_t c[8] = {A.x, A.y, A.z, A.w, 0u, 0u, 0u, 0u};
+  c[4] = from_next_lane(A.x, __builtin_amdgcn_readfirstlane(nextrow.x));
+  if (Q >= 1) c[5] = from_next_lane(A.y, __builtin_amdgcn_readfirstlane(nextrow.y));
+  if (Q >= 2) c[6] = from_next_lane(A.z, __builtin_amdgcn_readfirstlane(nextrow.z));
+  if (Q >= 3) c[7] = from_next_lane(A.w, __builtin_amdgcn_readfirstlane(nextrow.w));
+  u32x4 v;
+  v.x = __builtin_amdgcn_alignbyte(c[Q + 1], c[Q + 0], r);
+  v.y = __builtin_amdgcn_alignbyte(c[Q + 2], c[Q + 1], r);
+  v.z = __builtin_amdgcn_alignbyte(c[Q + 3], c[Q + 2], r);
+  v.w = __builtin_amdgcn_alignbyte(c[Q + 4], c[Q + 3], r);
+  return v;
+}
+
+// One pass over up to R * kThreads whole destination granules of a run whose destination
+// is aligned and whose source is not. d, a: first destination granule of the pass and the
+// aligned source granule under it; left: granules the run still has from here on (> 0).
+// Destination granule i is made of source granules i and i+1, so the last source granule
+// the run touches has index `left`.
+// A wavefront owns R * 64 consecutive granules (row j = granules j*64 .. j*64+63): every
+// lane loads the source granule under each of its destination granules and takes the
+// following one from the next lane, lane 63 from lane 0 of the next row (the row after
+// the last one is one more granule, loaded at the same address by all lanes). HBM traffic
+// equals the aligned case, there is no barrier and nothing is parked in LDS. Loads are
+// never predicated: an index past the run's last source granule is clamped to it and
 // what it returns is never stored.
-template <bool NT>
-__device__ __forceinline__ void copy_shifted(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid) {
-  const uint32_t shift = (uint32_t)((s0 - d0) & 15);  // != 0
-  const uint64_t d1 = d0 + n, s1 = s0 + n;
-  const uint64_t first = s0 & ~15ull, last = (s1 - 1) & ~15ull;  // granules holding source bytes
-  const uint64_t g0 = d0 & ~15ull;                               // first destination granule
-  const uint64_t a_base = (g0 + (s0 - d0)) & ~15ull;             // source granule under it
-  const uint64_t ngran = (((d1 + 15) & ~15ull) - g0) >> 4;
+template <bool NT, uint32_t R, uint32_t Q>
+__device__ __forceinline__ void shifted_pass(uint64_t d, uint64_t a, uint32_t left, uint32_t r, uint32_t tid) {
   const uint32_t wave = tid >> 6, lane = tid & 63;
-  for (uint64_t blk = 0; blk < ngran; blk += kBlockVec) {
-    const uint64_t wbase = blk + (uint64_t)wave * (kUnroll * 64);  // this wavefront's first granule
-    u32x4 A[kUnroll + 1];
+  const uint32_t wbase = wave * (R * 64);
+  u32x4 A[R], N;
 #pragma unroll
-    for (uint32_t j = 0; j <= kUnroll; ++j) {
-      uint64_t a = a_base + ((wbase + j * 64 + lane) << 4);
-      a = a < first ? first : a;
-      a = a > last ? last : a;
-      A[j] = ld16<NT>(a);
-    }
+  for (uint32_t j = 0; j < R; ++j) {
+    uint32_t gi = wbase + j * 64 + lane;
+    gi = gi < left ? gi : left;
+    A[j] = ld16<NT>(a + ((uint64_t)gi << 4));
+  }
+  {
+    uint32_t gi = wbase + R * 64;
+    gi = gi < left ? gi : left;
+    N = ld16<NT>(a + ((uint64_t)gi << 4));
+  }
 #pragma unroll
-    for (uint32_t j = 0; j < kUnroll; ++j) {
-      // all 64 lanes are active here (control flow is uniform across the workgroup), so
-      // readfirstlane returns lane 0's value of the next row
-      u32x4 Nx, Bv;
-      Nx.x = __builtin_amdgcn_readfirstlane(A[j + 1].x);
-      Nx.y = __builtin_amdgcn_readfirstlane(A[j + 1].y);
-      Nx.z = __builtin_amdgcn_readfirstlane(A[j + 1].z);
-      Nx.w = __builtin_amdgcn_readfirstlane(A[j + 1].w);
-      // the exchange must run with every lane enabled (a disabled lane contributes
-      // nothing), so it is done before, not inside, the per-lane choice
-      const uint32_t sx = __shfl_down(A[j].x, 1), sy = __shfl_down(A[j].y, 1);
-      const uint32_t sz = __shfl_down(A[j].z, 1), sw = __shfl_down(A[j].w, 1);
-      Bv.x = lane == 63 ? Nx.x : sx;
-      Bv.y = lane == 63 ? Nx.y : sy;
-      Bv.z = lane == 63 ? Nx.z : sz;
-      Bv.w = lane == 63 ? Nx.w : sw;
-      const uint64_t gi = wbase + j * 64 + lane;
-      if (gi < ngran) {
-        const uint64_t g = g0 + (gi << 4);
-        const uint32_t lo = g < d0 ? (uint32_t)(d0 - g) : 0u;
-        const uint32_t hi = g + 16 > d1 ? (uint32_t)(d1 - g) : 16u;
-        store_granule<NT>(g, funnel(A[j], Bv, shift), lo, hi);
-      }
+  for (uint32_t j = 0; j < R; ++j) {
+    // control flow is uniform across the workgroup up to here, so all 64 lanes take part
+    // in the exchange; the per-lane choice comes after it
+    const u32x4 v = shifted_vector<Q>(A[j], j + 1 < R ? A[j + 1] : N, r);
+    const uint32_t gi = wbase + j * 64 + lane;
+    if (gi < left) st16<NT>(d + ((uint64_t)gi << 4), v);
+  }
+}
+
+// nfull whole destination granules from aligned d; s is the (unaligned) source of d.
+template <bool NT, uint32_t U, uint32_t Q>
+__device__ __forceinline__ void copy_shifted_q(uint64_t d, uint64_t s, uint64_t nfull, uint32_t tid) {
+  const uint32_t r = (uint32_t)s & 3;
+  const uint64_t a_base = s & ~15ull;
+  for (uint64_t blk = 0; blk < nfull;) {
+    const uint64_t left64 = nfull - blk;
+    const uint32_t left = left64 > 0x7fffffffull ? 0x7fffffffu : (uint32_t)left64;
+    if (left > kThreads) {
+      shifted_pass<NT, U, Q>(d + (blk << 4), a_base + (blk << 4), left, r, tid);
+      blk += kThreads * U;
+    } else {
+      shifted_pass<NT, 1, Q>(d + (blk << 4), a_base + (blk << 4), left, r, tid);
+      blk += kThreads;
     }
   }
+}
+
+// Source and destination differ in alignment: the bytes before the first and after the
+// last whole destination granule go one by one, the granules between as aligned vectors
+// built from shifted source granules.
+template <bool NT, uint32_t U>
+__device__ __forceinline__ void copy_shifted(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid) {
+  uint64_t head = (16 - (d0 & 15)) & 15;
+  if (head > n) head = n;
+  const uint64_t nfull = (n - head) >> 4;
+  const uint64_t tail = (n - head) & 15;
+  const uint64_t toff = head + (nfull << 4);
+  // lanes 0..15 carry the head bytes, lanes 16..31 the tail bytes; they are loaded
+  // before and stored after the body so that their latency is not paid on its own
+  const bool edge = tid < head || (tid >= 16 && tid - 16 < tail);
+  const uint64_t eoff = tid < 16 ? tid : toff + (tid - 16);
+  uint8_t ev = 0;
+  if (edge) ev = ld8(s0 + eoff);
+  if (nfull != 0) {
+    const uint64_t d = d0 + head, s = s0 + head;  // d is aligned, s is not
+    switch (((uint32_t)s & 15) >> 2) {
+      case 0: copy_shifted_q<NT, U, 0>(d, s, nfull, tid); break;
+      case 1: copy_shifted_q<NT, U, 1>(d, s, nfull, tid); break;
+      case 2: copy_shifted_q<NT, U, 2>(d, s, nfull, tid); break;
+      default: copy_shifted_q<NT, U, 3>(d, s, nfull, tid); break;
+    }
+  }
+  if (edge) st8(d0 + eoff, ev);
 }
 
 // One contiguous piece with the whole workgroup.
-template <bool NT>
+template <bool NT, uint32_t U>
 __device__ __forceinline__ void copy_piece(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid) {
   if (((d0 ^ s0) & 15) == 0) {
     if (n < 64) {
       if (tid < n) st8(d0 + tid, ld8(s0 + tid));
       return;
     }
-    // same alignment on both sides: byte head up to the boundary, vector body, byte tail
+    // same alignment on both sides: byte head up to the boundary, vector body, byte tail;
+    // head and tail bytes are loaded before and stored after the body
     const uint64_t head = (16 - (d0 & 15)) & 15;
     const uint64_t nvec = (n - head) >> 4;
     const uint64_t tail = (n - head) & 15;
-    if (tid < head) st8(d0 + tid, ld8(s0 + tid));
     const uint64_t toff = head + (nvec << 4);
-    if (tid < tail) st8(d0 + toff + tid, ld8(s0 + toff + tid));
-    copy_vectors<NT>(d0 + head, s0 + head, nvec, tid);
+    const bool edge = tid < head || (tid >= 16 && tid - 16 < tail);
+    const uint64_t eoff = tid < 16 ? tid : toff + (tid - 16);
+    uint8_t ev = 0;
+    if (edge) ev = ld8(s0 + eoff);
+    copy_vectors<NT, U>(d0 + head, s0 + head, nvec, tid);
+    if (edge) st8(d0 + eoff, ev);
   } else {
-    copy_shifted<NT>(d0, s0, n, tid);
+    copy_shifted<NT, U>(d0, s0, n, tid);
   }
 }
 
 // Payload bytes [p, p+take) of a pitched descriptor.
-template <bool NT>
+template <bool NT, uint32_t U>
 __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid) {
   const uint64_t rb = X.row_bytes;
   const uint64_t pend = p + take;
@@ -285,16 +352,17 @@ __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t ta
   const uint64_t rl = (pend - 1) / rb;
   const uint64_t cl = pend - rl * rb;  // one past the last column in the last row
   // a row of rb bytes at any alignment spans at most (rb + 30) / 16 granules
+  constexpr uint32_t RS = 4, RL = 2;  // rows per group and pass
   if (rb <= 16 * 16 - 30) {
-    copy_rows_grouped<NT, 16, 8>(X, r0, c0, rl, cl, tid);
+    copy_rows_grouped<NT, 16, RS>(X, r0, c0, rl, cl, tid);
   } else if (rb <= 32 * 16 - 30) {
-    copy_rows_grouped<NT, 32, 8>(X, r0, c0, rl, cl, tid);
+    copy_rows_grouped<NT, 32, RS>(X, r0, c0, rl, cl, tid);
   } else if (rb <= 128 * 16 - 30) {
-    copy_rows_grouped<NT, 128, 4>(X, r0, c0, rl, cl, tid);
+    copy_rows_grouped<NT, 128, RL>(X, r0, c0, rl, cl, tid);
   } else {
     for (uint64_t r = r0; r <= rl; ++r) {
       const uint64_t ca = r == r0 ? c0 : 0, cb = r == rl ? cl : rb;
-      copy_piece<NT>(X.dst + r * X.dst_pitch + ca, X.src + r * X.src_pitch + ca, cb - ca, tid);
+      copy_piece<NT, U>(X.dst + r * X.dst_pitch + ca, X.src + r * X.src_pitch + ca, cb - ca, tid);
     }
   }
 }
@@ -313,7 +381,30 @@ struct Work {
   Xfer first;   // that descriptor
 };
 
-__device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTables &CT, uint64_t t) {
+// Where a workgroup is in the phase table. The ranks it decodes only grow (its tickets
+// come from one counter that only grows), so the phase is found by stepping forward,
+// and for nearly every ticket without a single table read.
+struct PhaseCursor {
+  uint32_t idx;
+  uint32_t slot_off, nslots;
+  uint64_t rank_base, round_base;
+  uint64_t next_base;  // rank_base of the following phase; all ones after the last
+};
+
+__device__ __forceinline__ void cursor_set(PhaseCursor &pc, CPhaseP phases, uint32_t nphases, uint32_t idx) {
+  pc.idx = idx;
+  pc.rank_base = phases[idx].rank_base;
+  pc.round_base = phases[idx].round_base;
+  pc.slot_off = phases[idx].slot_off;
+  pc.nslots = phases[idx].nslots;
+  pc.next_base = idx + 1 < nphases ? phases[idx + 1].rank_base : ~0ull;
+}
+
+// Dependent table reads on the way from a ticket to its bytes: the slot; then the
+// function and the chunk's first and last descriptor index side by side; then the
+// descriptor itself (plus a short search when a chunk spans several descriptors).
+__device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTables &CT, PhaseCursor &pc,
+                                              uint64_t t) {
   Work w;
   w.b0 = w.b1 = 0;
   w.x = 0;
@@ -326,9 +417,32 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
     rank = t / T.tiles_per_chunk;
     ti = t - rank * T.tiles_per_chunk;
   }
-  const ChunkId id = decode_rank(CT.phases, T.nphases, CT.slots, CT.funcs, rank);
-  const uint64_t stream_bytes = CT.funcs[id.fl].stream_bytes;
-  const uint64_t c0 = id.k * T.chunk_bytes;
+  while (rank >= pc.next_base) cursor_set(pc, CT.phases, T.nphases, pc.idx + 1);
+  const uint64_t rel = rank - pc.rank_base;
+  uint64_t round;
+  uint32_t s;
+  if (rel < (1ull << 32)) {
+    round = (uint32_t)rel / pc.nslots;
+    s = pc.slot_off + ((uint32_t)rel - (uint32_t)round * pc.nslots);
+  } else {
+    round = rel / pc.nslots;
+    s = pc.slot_off + (uint32_t)(rel - round * pc.nslots);
+  }
+  const uint32_t fl = CT.slots[s].fl;
+  const uint64_t k = (pc.round_base + round) * (uint64_t)CT.slots[s].weight + CT.slots[s].i;
+  const uint64_t stream_bytes = CT.funcs[fl].stream_bytes;
+  uint32_t x0, x1;
+  if (T.chunk_desc != nullptr) {
+    const FT_CONST uint32_t *cd =
+        reinterpret_cast<const FT_CONST uint32_t *>(reinterpret_cast<uintptr_t>(T.chunk_desc));
+    const uint64_t e = (uint64_t)CT.slots[s].chunk_off + k;
+    x0 = cd[e];
+    x1 = cd[e + 1];
+  } else {
+    x0 = CT.funcs[fl].desc_off;
+    x1 = x0 + CT.funcs[fl].ndesc - 1;
+  }
+  const uint64_t c0 = k * T.chunk_bytes;
   uint64_t lo = ti * T.tile_bytes, hi = lo + T.tile_bytes;
   if (hi > T.chunk_bytes) hi = T.chunk_bytes;
   uint64_t b0 = c0 + lo, b1 = c0 + hi;
@@ -336,12 +450,14 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
   if (b0 >= b1) return w;
   w.b0 = b0;
   w.b1 = b1;
-  w.x = find_xfer(CT.xfers, CT.funcs[id.fl].desc_off, CT.funcs[id.fl].ndesc, b0);
+  w.x = x0 == x1 ? x0 : find_xfer(CT.xfers, x0, x1, b0);
   w.first = read_xfer(CT.xfers, w.x);
   return w;
 }
 
-// Persistent workgroups. Tickets are drawn two ahead: while tile i moves, ticket i+1
+// Persistent workgroups. Workgroup b starts on tickets b and b + gridDim.x (the counter
+// starts at 2 * gridDim.x, so a launch does not open with every workgroup queueing on
+// one atomic); after that tickets are drawn two ahead: while tile i moves, ticket i+1
 // is already known and the atomic for ticket i+2 is in flight. A workgroup moves its
 // tile in two phases - every load of the tile, then every store - and decodes ticket
 // i+1 (scalar table reads) while the stores drain; the barrier at the end of the
@@ -351,20 +467,18 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
 // CLS (the link class) changes no code; it gives each class's kernel a name of its own
 // so that profiles keep host-link launches and pool->pool launches apart.
 template <bool NT, int CLS>
-__global__ __launch_bounds__(kThreads) void ft_copy_kernel(ClassTable T) {
+__global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 3)) __attribute__((amdgpu_num_vgpr(336))) void ft_copy_kernel(ClassTable T) {
+  constexpr uint32_t U = UnrollOf<CLS>::value;
   __shared__ unsigned long long s_ticket[2];
   const uint32_t tid = threadIdx.x;
-  if (tid == 0) {
-    const unsigned long long a = atomicAdd(T.ticket, 2ull);
-    s_ticket[0] = a;
-    s_ticket[1] = a + 1;
-  }
-  __syncthreads();
-  uint64_t t_cur = uniform64(s_ticket[0]);
-  uint64_t t_next = uniform64(s_ticket[1]);
+  if (T.log && tid == 0) T.wg_log[blockIdx.x].t_entry = wall_clock64();
+  uint64_t t_cur = blockIdx.x;
+  uint64_t t_next = (uint64_t)blockIdx.x + gridDim.x;
   uint32_t slot = 0;  // where ticket i+2 goes
   const ConstTables CT = const_tables(T);
-  Work cur = decode_ticket(T, CT, t_cur);
+  PhaseCursor pc;
+  cursor_set(pc, CT.phases, T.nphases, 0);
+  Work cur = decode_ticket(T, CT, pc, t_cur);
   while (t_cur < T.ntickets) {
     uint64_t t_begin = 0;
     if (T.log) t_begin = wall_clock64();
@@ -373,12 +487,12 @@ __global__ __launch_bounds__(kThreads) void ft_copy_kernel(ClassTable T) {
     const uint64_t p0 = cur.b0 - cur.first.stream_off;
     const uint64_t len = cur.b1 - cur.b0;
     const uint64_t fd = cur.first.dst + p0, fs = cur.first.src + p0;
-    if (cur.first.rows == 1 && len == (uint64_t)kBlockVec * 16 && ((fd | fs) & 15) == 0 &&
+    if (cur.first.rows == 1 && len == (uint64_t)kThreads * U * 16 && ((fd | fs) & 15) == 0 &&
         p0 + len <= cur.first.row_bytes) {
-      // the common case, one full aligned 64 KiB block: straight-line code from the
-      // ticket draw to the last store
+      // the common case, one full aligned block (64 KiB for pool->pool): straight-line
+      // code from the ticket draw to the last store
       if (tid == 0) claimed = atomicAdd(T.ticket, 1ull);
-      copy_rows_of_vectors<NT, kUnroll>(fd, fs, tid);
+      copy_rows_of_vectors<NT, U>(fd, fs, tid);
     } else {
       uint64_t pos = cur.b0;
       uint32_t x = cur.x;
@@ -387,15 +501,15 @@ __global__ __launch_bounds__(kThreads) void ft_copy_kernel(ClassTable T) {
         const uint64_t p = pos - X.stream_off;
         uint64_t take = X.row_bytes * X.rows - p;
         if (take > cur.b1 - pos) take = cur.b1 - pos;
-        if (X.rows == 1) copy_piece<NT>(X.dst + p, X.src + p, take, tid);
-        else copy_rows<NT>(X, p, take, tid);
+        if (X.rows == 1) copy_piece<NT, U>(X.dst + p, X.src + p, take, tid);
+        else copy_rows<NT, U>(X, p, take, tid);
         pos += take;
         if (pos < cur.b1) X = read_xfer(CT.xfers, ++x);
       }
       if (tid == 0) claimed = atomicAdd(T.ticket, 1ull);
     }
     if (tid == 0) s_ticket[slot] = claimed;
-    const Work next = decode_ticket(T, CT, t_next);
+    const Work next = decode_ticket(T, CT, pc, t_next);
 
     if (T.log) {
       // the tile counts as done when every store of the workgroup has been acknowledged
@@ -404,6 +518,7 @@ __global__ __launch_bounds__(kThreads) void ft_copy_kernel(ClassTable T) {
       if (tid == 0) {
         T.log[t_cur].t_begin = t_begin;
         T.log[t_cur].t_end = wall_clock64();
+        T.log[t_cur].wg = blockIdx.x;
       }
     }
     __syncthreads();
@@ -412,13 +527,14 @@ __global__ __launch_bounds__(kThreads) void ft_copy_kernel(ClassTable T) {
     t_next = uniform64(s_ticket[slot]);
     slot ^= 1;
   }
+  if (T.log && tid == 0) T.wg_log[blockIdx.x].t_exit = wall_clock64();
 }
 
 __global__ void ft_decode_kernel(ClassTable T, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap) {
   uint64_t rank = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (rank >= T.nchunks || rank >= cap) return;
   const ConstTables CT = const_tables(T);
-  const ChunkId id = decode_rank(CT.phases, T.nphases, CT.slots, CT.funcs, rank);
+  const ChunkId id = decode_rank(CT.phases, T.nphases, CT.slots, rank);
   func_out[rank] = CT.funcs[id.fl].func;
   chunk_out[rank] = (uint32_t)id.k;
 }
@@ -437,13 +553,15 @@ __global__ __launch_bounds__(kThreads) void ft_plain_copy_kernel(u32x4 *dst, con
   for (; i < nvec; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
-hipError_t launch_copy(const ClassTable &T, int link_class, uint32_t workgroups, hipStream_t stream) {
+hipError_t launch_copy(const ClassTable &T, int link_class, uint32_t workgroups, hipStream_t stream,
+                       hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (workgroups == 0) return hipErrorInvalidValue;
   const dim3 grid(workgroups), block(kThreads);
+  // with events, they are bound to this dispatch: they read the kernel's own start and end
   switch (link_class) {
-    case 0: hipLaunchKernelGGL((ft_copy_kernel<true, 0>), grid, block, 0, stream, T); break;
-    case 1: hipLaunchKernelGGL((ft_copy_kernel<true, 1>), grid, block, 0, stream, T); break;
-    case 2: hipLaunchKernelGGL((ft_copy_kernel<true, 2>), grid, block, 0, stream, T); break;
+    case 0: hipExtLaunchKernelGGL((ft_copy_kernel<true, 0>), grid, block, 0, stream, ev_start, ev_stop, 0, T); break;
+    case 1: hipExtLaunchKernelGGL((ft_copy_kernel<true, 1>), grid, block, 0, stream, ev_start, ev_stop, 0, T); break;
+    case 2: hipExtLaunchKernelGGL((ft_copy_kernel<true, 2>), grid, block, 0, stream, ev_start, ev_stop, 0, T); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -40,6 +40,14 @@ int build_phases(std::vector<Func> &funcs, std::vector<Phase> &phases, std::vect
   uint32_t g = 0;
   for (auto &f : funcs) g = std::gcd(g, f.weight);
   for (auto &f : funcs) f.weight /= g;
+  {
+    // only meaningful while the chunk table is built (it is not when this would wrap)
+    uint64_t acc = 0;
+    for (auto &f : funcs) {
+      f.chunk_off = (uint32_t)acc;
+      acc += f.nchunks + 1;
+    }
+  }
 
   std::vector<uint64_t> q(F), r(F);
   std::vector<char> present(F, 1);
@@ -66,7 +74,7 @@ int build_phases(std::vector<Func> &funcs, std::vector<Phase> &phases, std::vect
     cur.reserve(need);
     for (uint32_t i = 0; i < F; ++i)
       if (present[i])
-        for (uint32_t j = 0; j < funcs[i].weight; ++j) cur.push_back(Slot{i, j});
+        for (uint32_t j = 0; j < funcs[i].weight; ++j) cur.push_back(Slot{i, j, funcs[i].weight, funcs[i].chunk_off});
     std::sort(cur.begin(), cur.end(), SlotLess{&funcs});
     cur_valid = true;
     return FT_OK;
@@ -119,7 +127,7 @@ int build_phases(std::vector<Func> &funcs, std::vector<Phase> &phases, std::vect
     for (uint32_t i = 0; i < F; ++i)
       if (present[i]) {
         uint32_t cnt = (q[i] == R) ? (uint32_t)r[i] : funcs[i].weight;
-        for (uint32_t j = 0; j < cnt; ++j) irr.push_back(Slot{i, j});
+        for (uint32_t j = 0; j < cnt; ++j) irr.push_back(Slot{i, j, funcs[i].weight, funcs[i].chunk_off});
       }
     std::sort(irr.begin(), irr.end(), SlotLess{&funcs});
     Phase ph;
@@ -290,6 +298,8 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
       fn.weight = weights[f];
       fn.desc_off = off;
       fn.ndesc = count[f];
+      fn.chunk_off = 0;
+      fn._pad[0] = fn._pad[1] = fn._pad[2] = 0;
       off += count[f];
       slot_of[f] = (int64_t)cp.funcs.size();
       cp.funcs.push_back(fn);
@@ -314,6 +324,20 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
       }
     int rc = build_phases(cp.funcs, cp.phases, cp.slots, &cp.nchunks);
     if (rc != FT_OK) return rc;
+    // chunk table: one forward walk over each function's descriptors
+    if (cp.nchunks + cp.funcs.size() <= kMaxChunkTable) {
+      cp.chunk_desc.reserve(cp.nchunks + cp.funcs.size());
+      for (const Func &fn : cp.funcs) {
+        const uint32_t last = fn.desc_off + fn.ndesc - 1;
+        uint32_t x = fn.desc_off;
+        for (uint64_t k = 0; k < fn.nchunks; ++k) {
+          const uint64_t pos = k * chunk_bytes;
+          while (x < last && cp.xfers[x + 1].stream_off <= pos) ++x;
+          cp.chunk_desc.push_back(x);
+        }
+        cp.chunk_desc.push_back(last);
+      }
+    }
   }
   return FT_OK;
 }

@@ -21,6 +21,7 @@ struct ClassPlan {
   std::vector<Slot> slots;
   std::vector<Func> funcs;
   std::vector<Xfer> xfers;
+  std::vector<uint32_t> chunk_desc;  // empty when the job has more chunks than kMaxChunkTable
   uint64_t nchunks = 0;
   uint64_t payload = 0;
 };
@@ -34,6 +35,9 @@ struct SubmitPlan {
 // caller function id). Divides the weights by their gcd in place. FT_EINVAL if the
 // slot tables would exceed kMaxSlots entries.
 constexpr uint64_t kMaxSlots = 1ull << 22;
+// Most entries the per-chunk descriptor table may have (4 bytes each); jobs with more
+// chunks than this search the function's whole descriptor range instead.
+constexpr uint64_t kMaxChunkTable = 1ull << 20;
 int build_phases(std::vector<Func> &funcs, std::vector<Phase> &phases, std::vector<Slot> &slots,
                  uint64_t *nchunks_out);
 

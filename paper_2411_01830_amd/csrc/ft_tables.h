@@ -9,7 +9,12 @@
 // the same slot pattern. The host therefore emits a few phases, each a run of rounds
 // sharing one slot table, plus at most one single-round phase per function for the
 // round in which it runs dry part-way. Decoding a chunk rank is a binary search over
-// at most 2F+1 phases, one division and one table read.
+// at most 2F+1 phases (the copy kernel, whose ranks only grow, keeps a cursor instead),
+// one division and one table read.
+//
+// A second table lists, per function and chunk, the descriptor that holds the chunk's
+// first stream byte, so that finding a tile's descriptor is a search over the few
+// descriptors of one chunk instead of all descriptors of the function.
 #pragma once
 #include <stdint.h>
 
@@ -29,8 +34,10 @@ struct Phase {
 };
 
 struct Slot {
-  uint32_t fl;  // index into the class's function table
-  uint32_t i;   // chunk index inside the round: k = R * w + i
+  uint32_t fl;         // index into the class's function table
+  uint32_t i;          // chunk index inside the round: k = R * w + i
+  uint32_t weight;     // copy of funcs[fl].weight: k is known after this one read
+  uint32_t chunk_off;  // copy of funcs[fl].chunk_off
 };
 
 struct Func {
@@ -40,6 +47,8 @@ struct Func {
   uint32_t weight;        // w_f divided by the gcd of the class's weights
   uint32_t desc_off;      // first descriptor of this function in the class's table
   uint32_t ndesc;
+  uint32_t chunk_off;     // first of the function's nchunks + 1 entries in the chunk table
+  uint32_t _pad[3];
 };
 
 // One transfer with both sides resolved to device-visible virtual addresses.
@@ -57,6 +66,13 @@ struct Xfer {
 struct LogEntry {
   uint64_t t_begin;
   uint64_t t_end;
+  uint32_t wg;  // workgroup that moved the ticket
+  uint32_t _pad[3];
+};
+
+struct WgLogEntry {
+  uint64_t t_entry;  // device clock when the workgroup started
+  uint64_t t_exit;   // and when it found no ticket left
 };
 
 // Everything one class's kernel needs; passed by value as the kernel argument.
@@ -65,8 +81,13 @@ struct ClassTable {
   const Slot *slots;
   const Func *funcs;
   const Xfer *xfers;
-  unsigned long long *ticket;  // device counter, zero at launch
+  // per function nchunks + 1 entries: descriptor (index into xfers) holding stream byte
+  // k * C for k < nchunks, then the function's last descriptor. Null when the job has
+  // too many chunks for the table to be worth its memory.
+  const uint32_t *chunk_desc;
+  unsigned long long *ticket;  // device counter; starts at 2 * workgroups (see ft_copy_kernel)
   LogEntry *log;               // one per ticket, or null
+  WgLogEntry *wg_log;          // one per workgroup; set whenever log is
   uint64_t nchunks;            // N
   uint64_t ntickets;           // N * tiles_per_chunk
   uint64_t chunk_bytes;        // C
@@ -85,8 +106,8 @@ struct ChunkId {
 // rank -> (function, chunk). rank < nchunks. The pointer types are template
 // parameters so that the device can read the tables through constant-address-space
 // pointers (scalar loads); only scalar members are read through them.
-template <class PhaseP, class SlotP, class FuncP>
-FT_HD ChunkId decode_rank(PhaseP phases, uint32_t nphases, SlotP slots, FuncP funcs, uint64_t rank) {
+template <class PhaseP, class SlotP>
+FT_HD ChunkId decode_rank(PhaseP phases, uint32_t nphases, SlotP slots, uint64_t rank) {
   uint32_t lo = 0, hi = nphases;  // last phase with rank_base <= rank
   while (hi - lo > 1) {
     uint32_t mid = (lo + hi) >> 1;
@@ -98,14 +119,15 @@ FT_HD ChunkId decode_rank(PhaseP phases, uint32_t nphases, SlotP slots, FuncP fu
   const uint32_t s = phases[lo].slot_off + (uint32_t)(rel - round * nslots);
   ChunkId id;
   id.fl = slots[s].fl;
-  id.k = (phases[lo].round_base + round) * (uint64_t)funcs[id.fl].weight + slots[s].i;
+  id.k = (phases[lo].round_base + round) * (uint64_t)slots[s].weight + slots[s].i;
   return id;
 }
 
-// Descriptor among [desc_off, desc_off + ndesc) that holds stream byte `pos`.
+// Descriptor among [first, last] (one function's, stream_off ascending, xfers[first]
+// at or before pos) that holds stream byte `pos`.
 template <class XferP>
-FT_HD uint32_t find_xfer(XferP xfers, uint32_t desc_off, uint32_t ndesc, uint64_t pos) {
-  uint32_t lo = desc_off, hi = desc_off + ndesc;
+FT_HD uint32_t find_xfer(XferP xfers, uint32_t first, uint32_t last, uint64_t pos) {
+  uint32_t lo = first, hi = last + 1;
   while (hi - lo > 1) {
     uint32_t mid = (lo + hi) >> 1;
     if (xfers[mid].stream_off <= pos) lo = mid; else hi = mid;
