@@ -87,7 +87,7 @@ typedef struct ft_desc {
 typedef struct ft_class_stats {
   uint64_t payload_bytes; /* sum of rows*row_bytes of the class's descriptors */
   uint64_t chunks;        /* N = sum over functions of ceil(S_f / chunk_bytes) */
-  uint64_t tickets;       /* chunks * tiles per chunk: what the device counter runs to */
+  uint64_t tickets;       /* tiles that hold bytes: what the device counter runs to */
   uint64_t tile_bytes;    /* bytes one ticket moves (last tile of a chunk may be shorter) */
   uint32_t workgroups;    /* persistent workgroups launched (0 on the DMA path) */
   uint32_t _pad;
@@ -239,6 +239,18 @@ int ft_set_tuning(ft_pool *p, int link_class, uint32_t workgroups, uint64_t tile
 int ft_plan_schedule(const uint64_t *stream_bytes, const uint32_t *weights, uint32_t nfunc,
                      uint64_t chunk_bytes, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap,
                      uint64_t *n_out);
+
+/*
+ * Host-only: the ticket list for given per-function stream sizes and a wanted tile
+ * size, computed with the planner's own tile shape, empty-tile runs and ticket
+ * mapping. Ticket t moves bytes [byte_off_out[t], byte_off_out[t] + bytes_out[t]) of
+ * function func_out[t]'s stream, all inside chunk chunk_out[t]. Host arrays of `cap`
+ * entries each; *n_out receives the ticket count. Tickets name only tiles that hold
+ * bytes, in the chunk order of ft_plan_schedule, tiles of a chunk in ascending order.
+ */
+int ft_plan_tickets(const uint64_t *stream_bytes, const uint32_t *weights, uint32_t nfunc,
+                    uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t *func_out, uint32_t *chunk_out,
+                    uint64_t *byte_off_out, uint32_t *bytes_out, uint64_t cap, uint64_t *n_out);
 
 /*
  * Calibration: a plain grid-stride 16-byte copy of `bytes` (multiple of 16) from

@@ -13,7 +13,7 @@ FT_VALIDATE, FT_LOG, FT_PATH_DMA, FT_TIMING, FT_DETACHED, FT_KEEP = 1, 2, 4, 8, 
 
 EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
            "ft_pool_ptr", "ft_host_window_add", "ft_submit_transfers", "ft_wait", "ft_job_release",
-           "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule",
+           "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
            "ft_plain_copy", "ft_strerror", "ft_last_hip_error"]
 
 
@@ -61,6 +61,7 @@ def _load():
         "ft_job_log_workgroups": (i32, [vp, u64, i32, vp, u64, vp, vp, u32, P(u32)]),
         "ft_set_tuning": (i32, [vp, i32, u32, u64]),
         "ft_plan_schedule": (i32, [vp, vp, u32, u64, vp, vp, u64, P(u64)]),
+        "ft_plan_tickets": (i32, [vp, vp, u32, u64, u64, vp, vp, vp, vp, u64, P(u64)]),
         "ft_plain_copy": (i32, [vp, vp, u64, u32, vp]),
         "ft_strerror": (C.c_char_p, [i32]),
         "ft_last_hip_error": (C.c_char_p, [vp]),
@@ -194,6 +195,22 @@ def plan_schedule(stream_bytes, weights, chunk_bytes):
     _check(_lib.ft_plan_schedule(s.ctypes.data, w.ctypes.data, len(w), chunk_bytes, f.ctypes.data,
                                  k.ctypes.data, n.value, C.byref(n)))
     return list(zip(f[:n.value].tolist(), k[:n.value].tolist()))
+
+
+def plan_tickets(stream_bytes, weights, chunk_bytes, tile_bytes):
+    """List of (func, chunk, byte offset in the function's stream, bytes), one per ticket."""
+    s = np.ascontiguousarray(np.asarray(stream_bytes, dtype=np.uint64))
+    w = np.ascontiguousarray(np.asarray(weights, dtype=np.uint32))
+    n = C.c_uint64()
+    _check(_lib.ft_plan_tickets(s.ctypes.data, w.ctypes.data, len(w), chunk_bytes, tile_bytes, None, None,
+                                None, None, 0, C.byref(n)))
+    m = max(n.value, 1)
+    f, k = np.zeros(m, np.uint32), np.zeros(m, np.uint32)
+    off, b = np.zeros(m, np.uint64), np.zeros(m, np.uint32)
+    _check(_lib.ft_plan_tickets(s.ctypes.data, w.ctypes.data, len(w), chunk_bytes, tile_bytes, f.ctypes.data,
+                                k.ctypes.data, off.ctypes.data, b.ctypes.data, n.value, C.byref(n)))
+    q = slice(0, n.value)
+    return list(zip(f[q].tolist(), k[q].tolist(), off[q].tolist(), b[q].tolist()))
 
 
 def plain_copy(dst_ptr, src_ptr, nbytes, workgroups=0, stream=0):

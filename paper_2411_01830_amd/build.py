@@ -24,6 +24,37 @@ def hipcc():
     return exe
 
 
+def check_registers(remarks):
+    """A host-link workgroup and a pool->pool workgroup must fit on one CU together
+    (one wavefront of each per SIMD, 512 registers per lane, allocated in eights):
+    a job with both kinds of traffic runs the two kernels side by side, and a
+    host-link workgroup that took a CU for itself would idle that CU's share of HBM."""
+    import re
+    regs = {}
+    name = None
+    for line in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            regs[name] = 0
+        m = re.search(r"\b(VGPRs|AGPRs): (\d+)", line)
+        if m and name and "Spill" not in line:
+            regs[name] += int(m.group(2))
+    up8 = lambda v: (v + 7) // 8 * 8
+    per_class = {}
+    for k, v in regs.items():
+        m = re.search(r"ft_copy_kernelILb1ELi(\d)E", k)
+        if m:
+            per_class[int(m.group(1))] = up8(v)
+    if sorted(per_class) != [0, 1, 2]:
+        raise RuntimeError(f"could not read the copy kernels' register counts: {regs}")
+    for host in (0, 1):
+        if per_class[host] + per_class[2] > 512:
+            raise RuntimeError(f"copy kernels no longer fit one CU together: class {host} uses "
+                               f"{per_class[host]} registers, pool->pool {per_class[2]}")
+    return per_class
+
+
 def build(verbose=False):
     out_dir = os.path.join(HERE, "_build")
     os.makedirs(out_dir, exist_ok=True)
@@ -31,9 +62,17 @@ def build(verbose=False):
     for src in SOURCES:
         obj = os.path.join(out_dir, os.path.splitext(src)[0] + ".o")
         cmd = [hipcc(), "-x", "hip", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        if src == "ft_kernels.hip":
+            cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
         if verbose:
             print(" ".join(cmd), flush=True)
-        subprocess.run(cmd, check=True)
+        res = subprocess.run(cmd, check=True, stderr=subprocess.PIPE, text=True)
+        if src == "ft_kernels.hip":
+            per_class = check_registers(res.stderr)
+            if verbose:
+                print("registers per lane (host->pool, pool->host, pool->pool):", per_class, flush=True)
+        else:
+            sys.stderr.write(res.stderr)
         objs.append(obj)
     cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB + ".tmp"]
     if verbose:

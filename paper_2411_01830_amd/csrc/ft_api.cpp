@@ -39,6 +39,7 @@ struct ClassRun {
   // recorded around the copy calls on the DMA path.
   hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_done = nullptr;
   Blob log;
+  std::vector<Skip> skips;
   std::vector<LogEntry> log_host;
   std::vector<WgLogEntry> wg_log_host;
   float device_ms = -1.f;
@@ -207,10 +208,11 @@ uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 // Byte layout of one class's tables inside the job's blob.
 struct Layout {
-  uint64_t ticket, phases, slots, funcs, xfers, chunks, end;
+  uint64_t ticket, phases, slots, funcs, xfers, chunks, skips, end;
 };
 
 Layout layout_of(const ClassPlan &cp, uint64_t base) {
+  // at most one run of empty tiles per function
   Layout l;
   l.ticket = align_up(base, 256);
   l.phases = l.ticket + 256;
@@ -218,7 +220,8 @@ Layout layout_of(const ClassPlan &cp, uint64_t base) {
   l.funcs = align_up(l.slots + cp.slots.size() * sizeof(Slot), 64);
   l.xfers = align_up(l.funcs + cp.funcs.size() * sizeof(Func), 64);
   l.chunks = align_up(l.xfers + cp.xfers.size() * sizeof(Xfer), 64);
-  l.end = align_up(l.chunks + cp.chunk_desc.size() * sizeof(uint32_t), 256);
+  l.skips = align_up(l.chunks + cp.chunk_desc.size() * sizeof(uint32_t), 64);
+  l.end = align_up(l.skips + cp.funcs.size() * sizeof(Skip), 256);
   return l;
 }
 
@@ -241,9 +244,11 @@ uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
 
 // short_rows: most of the class's payload sits in pitched descriptors with rows of at
 // most 2 KiB. Those tiles are bound by latency, not bandwidth, and a job of them has
-// few tiles per workgroup, so smaller tiles balance it better.
+// few tiles per workgroup, so smaller tiles balance it better. The row-gather routine
+// moves 3 destination granules per lane and pass: a tile of just under 12 KiB is one
+// pass even when its first granule is a partial one.
 uint64_t default_tile(int cls, bool with_p2p, bool short_rows) {
-  if (cls == FT_P2P) return short_rows ? 16u * 1024u : 64u * 1024u;
+  if (cls == FT_P2P) return short_rows ? 3u * 4096u - 16u : 64u * 1024u;
   return with_p2p ? 8u * 1024u : 16u * 1024u;
 }
 
@@ -476,19 +481,19 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       T.ticket = reinterpret_cast<unsigned long long *>(d + lay[c].ticket);
       T.log = nullptr;
       T.wg_log = nullptr;
+      build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &T.ntickets);
+      std::memcpy(h + lay[c].skips, r.skips.data(), r.skips.size() * sizeof(Skip));
+      T.skips = reinterpret_cast<const Skip *>(d + lay[c].skips);
+      T.nskips = (uint32_t)r.skips.size();
       T.nchunks = cp.nchunks;
-      T.ntickets = cp.nchunks * r.tiles_per_chunk;
       T.chunk_bytes = chunk_bytes;
       T.tile_bytes = r.tile_bytes;
       T.tiles_per_chunk = r.tiles_per_chunk;
       T.nphases = (uint32_t)cp.phases.size();
       T.nfuncs = (uint32_t)cp.funcs.size();
-      T._pad = 0;
       uint64_t wg = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
       if (wg > T.ntickets) wg = T.ntickets;
       r.workgroups = dma ? 0 : (uint32_t)wg;
-      // workgroup b starts on tickets b and b + workgroups without asking the counter
-      *reinterpret_cast<unsigned long long *>(h + lay[c].ticket) = 2ull * wg;
       if ((flags & FT_LOG) && !dma) {
         rc = get_blob(p, T.ntickets * sizeof(LogEntry) + wg * sizeof(WgLogEntry), false, &r.log);
         if (rc != FT_OK) return fail(rc);
@@ -652,7 +657,8 @@ int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, ui
     if (t_begin_ns) t_begin_ns[t] = (uint64_t)(r.log_host[t].t_begin * ns_per_tick);
     if (t_end_ns) t_end_ns[t] = (uint64_t)(r.log_host[t].t_end * ns_per_tick);
     if (func_out || chunk_out || bytes_out) {
-      const uint64_t rank = t / r.tiles_per_chunk, ti = t % r.tiles_per_chunk;
+      const uint64_t v = ticket_to_tile(r.skips.data(), (uint32_t)r.skips.size(), t);
+      const uint64_t rank = v / r.tiles_per_chunk, ti = v % r.tiles_per_chunk;
       const ChunkId cid = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(), rank);
       const Func &fn = cp.funcs[cid.fl];
       uint64_t lo = ti * r.tile_bytes, hi = lo + r.tile_bytes;
@@ -713,6 +719,50 @@ int ft_plan_schedule(const uint64_t *stream_bytes, const uint32_t *weights, uint
     const ChunkId id = decode_rank(phases.data(), (uint32_t)phases.size(), slots.data(), rank);
     func_out[rank] = funcs[id.fl].func;
     chunk_out[rank] = (uint32_t)id.k;
+  }
+  return FT_OK;
+}
+
+int ft_plan_tickets(const uint64_t *stream_bytes, const uint32_t *weights, uint32_t nfunc,
+                    uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t *func_out, uint32_t *chunk_out,
+                    uint64_t *byte_off_out, uint32_t *bytes_out, uint64_t cap, uint64_t *n_out) {
+  if (stream_bytes == nullptr || weights == nullptr || n_out == nullptr || nfunc == 0) return FT_EINVAL;
+  if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return FT_EINVAL;
+  if (cap != 0 && (func_out == nullptr || chunk_out == nullptr || byte_off_out == nullptr || bytes_out == nullptr))
+    return FT_EINVAL;
+  ClassPlan cp;
+  for (uint32_t f = 0; f < nfunc; ++f) {
+    if (weights[f] == 0) return FT_EINVAL;
+    if (stream_bytes[f] == 0) continue;
+    Func fn{};
+    fn.stream_bytes = stream_bytes[f];
+    fn.nchunks = stream_bytes[f] / chunk_bytes + (stream_bytes[f] % chunk_bytes != 0);
+    fn.func = f;
+    fn.weight = weights[f];
+    cp.funcs.push_back(fn);
+  }
+  int rc = build_phases(cp.funcs, cp.phases, cp.slots, &cp.nchunks);
+  if (rc != FT_OK) return rc;
+  uint64_t tile = 0, ntickets = 0;
+  uint32_t tpc = 0;
+  tile_shape(chunk_bytes, tile_bytes, &tile, &tpc);
+  std::vector<Skip> skips;
+  build_skips(cp, chunk_bytes, tile, tpc, &skips, &ntickets);
+  *n_out = ntickets;
+  for (uint64_t t = 0; t < ntickets && t < cap; ++t) {
+    const uint64_t v = ticket_to_tile(skips.data(), (uint32_t)skips.size(), t);
+    const uint64_t rank = v / tpc, ti = v % tpc;
+    const ChunkId id = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(), rank);
+    const Func &fn = cp.funcs[id.fl];
+    uint64_t lo = ti * tile, hi = lo + tile;
+    if (hi > chunk_bytes) hi = chunk_bytes;
+    uint64_t b0 = id.k * chunk_bytes + lo, b1 = id.k * chunk_bytes + hi;
+    if (b1 > fn.stream_bytes) b1 = fn.stream_bytes;
+    if (b0 > b1) b0 = b1;
+    func_out[t] = fn.func;
+    chunk_out[t] = (uint32_t)id.k;
+    byte_off_out[t] = b0;
+    bytes_out[t] = (uint32_t)(b1 - b0);
   }
   return FT_OK;
 }

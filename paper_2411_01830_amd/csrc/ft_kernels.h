@@ -7,7 +7,7 @@
 namespace ft {
 
 // Persistent copy kernel of one link class (0 host->pool, 1 pool->host, 2 pool->pool).
-// *T.ticket must be 2 * workgroups when it starts. ev_start / ev_stop (both or neither)
+// *T.ticket must be zero when it starts. ev_start / ev_stop (both or neither)
 // are timing events that will read the start and the end of this dispatch.
 hipError_t launch_copy(const ClassTable &T, int link_class, uint32_t workgroups, hipStream_t stream,
                        hipEvent_t ev_start, hipEvent_t ev_stop);

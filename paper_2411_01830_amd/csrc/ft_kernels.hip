@@ -23,12 +23,14 @@ typedef const FT_CONST Phase *CPhaseP;
 typedef const FT_CONST Slot *CSlotP;
 typedef const FT_CONST Func *CFuncP;
 typedef const FT_CONST Xfer *CXferP;
+typedef const FT_CONST Skip *CSkipP;
 
 struct ConstTables {
   CPhaseP phases;
   CSlotP slots;
   CFuncP funcs;
   CXferP xfers;
+  CSkipP skips;
 };
 
 __device__ __forceinline__ ConstTables const_tables(const ClassTable &T) {
@@ -37,6 +39,7 @@ __device__ __forceinline__ ConstTables const_tables(const ClassTable &T) {
   c.slots = reinterpret_cast<CSlotP>(reinterpret_cast<uintptr_t>(T.slots));
   c.funcs = reinterpret_cast<CFuncP>(reinterpret_cast<uintptr_t>(T.funcs));
   c.xfers = reinterpret_cast<CXferP>(reinterpret_cast<uintptr_t>(T.xfers));
+  c.skips = reinterpret_cast<CSkipP>(reinterpret_cast<uintptr_t>(T.skips));
   return c;
 }
 
@@ -84,19 +87,19 @@ __device__ __forceinline__ void st16(uint64_t addr, u32x4 v) {
 __device__ __forceinline__ uint8_t ld8(uint64_t addr) { return *reinterpret_cast<const uint8_t FT_GLOBAL *>(addr); }
 __device__ __forceinline__ void st8(uint64_t addr, uint8_t v) { *reinterpret_cast<GByteP>(addr) = v; }
 
-// 16 bytes starting `shift` (1..15) bytes into the 32-byte pair (A, B).
+// 16 bytes starting `shift` (0..15, per lane) bytes into the 32-byte pair (A, B): select
+// the five dwords by shift / 4 in two halving steps, then byte-align neighbours.
 __device__ __forceinline__ u32x4 funnel(u32x4 A, u32x4 B, uint32_t shift) {
-  const uint32_t q = shift >> 2, r8 = (shift & 3) * 8;
-  uint32_t x0 = q == 0 ? A.x : q == 1 ? A.y : q == 2 ? A.z : A.w;
-  uint32_t x1 = q == 0 ? A.y : q == 1 ? A.z : q == 2 ? A.w : B.x;
-  uint32_t x2 = q == 0 ? A.z : q == 1 ? A.w : q == 2 ? B.x : B.y;
-  uint32_t x3 = q == 0 ? A.w : q == 1 ? B.x : q == 2 ? B.y : B.z;
-  uint32_t x4 = q == 0 ? B.x : q == 1 ? B.y : q == 2 ? B.z : B.w;
+  const bool s1 = (shift & 4) != 0, s2 = (shift & 8) != 0;
+  const uint32_t r = shift & 3;
+  const uint32_t y0 = s1 ? A.y : A.x, y1 = s1 ? A.z : A.y, y2 = s1 ? A.w : A.z, y3 = s1 ? B.x : A.w;
+  const uint32_t y4 = s1 ? B.y : B.x, y5 = s1 ? B.z : B.y, y6 = s1 ? B.w : B.z;
+  const uint32_t z0 = s2 ? y2 : y0, z1 = s2 ? y3 : y1, z2 = s2 ? y4 : y2, z3 = s2 ? y5 : y3, z4 = s2 ? y6 : y4;
   u32x4 v;
-  v.x = (uint32_t)(((uint64_t)x1 << 32 | x0) >> r8);
-  v.y = (uint32_t)(((uint64_t)x2 << 32 | x1) >> r8);
-  v.z = (uint32_t)(((uint64_t)x3 << 32 | x2) >> r8);
-  v.w = (uint32_t)(((uint64_t)x4 << 32 | x3) >> r8);
+  v.x = __builtin_amdgcn_alignbyte(z1, z0, r);
+  v.y = __builtin_amdgcn_alignbyte(z2, z1, r);
+  v.z = __builtin_amdgcn_alignbyte(z3, z2, r);
+  v.w = __builtin_amdgcn_alignbyte(z4, z3, r);
   return v;
 }
 
@@ -342,6 +345,92 @@ __device__ __forceinline__ void copy_piece(uint64_t d0, uint64_t s0, uint64_t n,
   }
 }
 
+// Dword d of a 16-byte vector whose bytes at positions >= split come from b, the rest from a.
+__device__ __forceinline__ uint32_t merge_dword(uint32_t a, uint32_t b, uint32_t split, uint32_t d) {
+  const uint32_t first = 4 * d;
+  const uint32_t m = split <= first ? 0xffffffffu : split >= first + 4 ? 0u : 0xffffffffu << (8 * (split - first));
+  return (b & m) | (a & ~m);
+}
+
+// Rows gathered into a contiguous destination (dst_pitch == row_bytes >= 16): payload
+// bytes [p, p+take), take < 2^30, land in one run of destination bytes, so every lane
+// owns whole destination granules and only the first and last granule of the run are
+// partial. A granule holds bytes of at most two source rows: for each of the two pieces
+// a lane loads the two aligned source granules around it, funnels them into place and
+// merges the pieces, R granules per lane and pass, all 4*R loads before the first store.
+// Loads are never predicated: an address outside the aligned granules that hold bytes of
+// its piece is clamped into them and what it returns is never stored; a granule without
+// a second piece repeats the first piece's addresses.
+template <bool NT, uint32_t R>
+__device__ __forceinline__ void copy_rows_packed(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid) {
+  const uint32_t rb = (uint32_t)X.row_bytes;
+  const uint64_t d0 = X.dst + p, d1 = d0 + take;
+  const uint64_t g0 = d0 & ~15ull;
+  const uint32_t ngran = (uint32_t)((((d1 + 15) & ~15ull) - g0) >> 4);
+  const uint32_t head = (uint32_t)(d0 - g0);  // bytes of the first granule before the run
+  const uint64_t r_base = p / rb;
+  const uint32_t c_base = (uint32_t)(p - r_base * rb);
+  const uint64_t src_base = X.src + r_base * X.src_pitch;  // row r_base, column 0
+  const uint32_t magic = (uint32_t)((1ull << 32) / rb) + 1;  // e / rb = mulhi(e, magic) or one less
+  for (uint32_t blk = 0; blk < ngran; blk += R * kThreads) {
+    u32x4 A0[R], A1[R], B0[R], B1[R];
+    uint32_t meta[R];  // lo | hi << 5 | split << 10 | shift A << 15 | shift B << 20
+#pragma unroll
+    for (uint32_t k = 0; k < R; ++k) {
+      uint32_t gi = blk + tid + k * kThreads;
+      const bool active = gi < ngran;
+      gi = active ? gi : ngran - 1;
+      // bytes [lo, hi) of this granule belong to the run
+      const uint32_t lo = gi == 0 ? head : 0u;
+      const uint64_t gend = g0 + ((uint64_t)gi << 4) + 16;
+      const uint32_t top = gend > d1 ? 16u - (uint32_t)(gend - d1) : 16u;
+      const uint32_t hi = active ? top : lo;
+      const uint32_t n = top - lo;
+      // row (relative to r_base) and column of the granule's first run byte
+      const uint32_t e = c_base + (gi << 4) + lo - head;
+      uint32_t dr = __umulhi(e, magic);
+      dr -= (dr * rb > e) ? 1u : 0u;
+      const uint32_t c = e - dr * rb;
+      const uint32_t nA = n < rb - c ? n : rb - c;
+      const uint32_t nB = n - nA;
+      const uint32_t split = lo + nA;
+      const uint64_t sA = src_base + (uint64_t)dr * X.src_pitch + c;
+      const uint64_t sB = nB ? src_base + (uint64_t)(dr + 1) * X.src_pitch : sA;
+      const uint32_t lenB = nB ? nB : nA;
+      const uint32_t posB = nB ? split : lo;
+      // window of 16 bytes that puts piece A (B) at its place in the granule
+      const uint64_t wA = sA - lo, wB = sB - posB;
+      meta[k] = lo | hi << 5 | split << 10 | ((uint32_t)wA & 15) << 15 | ((uint32_t)wB & 15) << 20;
+      const uint64_t fA = sA & ~15ull, lA = (sA + nA - 1) & ~15ull;
+      const uint64_t fB = sB & ~15ull, lB = (sB + lenB - 1) & ~15ull;
+      uint64_t a0 = wA & ~15ull, a1 = a0 + 16, b0 = wB & ~15ull, b1 = b0 + 16;
+      a0 = a0 < fA ? fA : a0 > lA ? lA : a0;
+      a1 = a1 < fA ? fA : a1 > lA ? lA : a1;
+      b0 = b0 < fB ? fB : b0 > lB ? lB : b0;
+      b1 = b1 < fB ? fB : b1 > lB ? lB : b1;
+      A0[k] = ld16<NT>(a0);
+      A1[k] = ld16<NT>(a1);
+      B0[k] = ld16<NT>(b0);
+      B1[k] = ld16<NT>(b1);
+    }
+#pragma unroll
+    for (uint32_t k = 0; k < R; ++k) {
+      const uint32_t lo = meta[k] & 31, hi = (meta[k] >> 5) & 31, split = (meta[k] >> 10) & 31;
+      const u32x4 va = funnel(A0[k], A1[k], (meta[k] >> 15) & 15);
+      const u32x4 vb = funnel(B0[k], B1[k], (meta[k] >> 20) & 15);
+      u32x4 v;
+      v.x = merge_dword(va.x, vb.x, split, 0);
+      v.y = merge_dword(va.y, vb.y, split, 1);
+      v.z = merge_dword(va.z, vb.z, split, 2);
+      v.w = merge_dword(va.w, vb.w, split, 3);
+      if (lo < hi) {
+        const uint32_t gi = blk + tid + k * kThreads;
+        store_granule<NT>(g0 + ((uint64_t)gi << 4), v, lo, hi);
+      }
+    }
+  }
+}
+
 // Payload bytes [p, p+take) of a pitched descriptor.
 template <bool NT, uint32_t U>
 __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid) {
@@ -351,6 +440,10 @@ __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t ta
   const uint64_t c0 = p - r0 * rb;
   const uint64_t rl = (pend - 1) / rb;
   const uint64_t cl = pend - rl * rb;  // one past the last column in the last row
+  if (X.dst_pitch == rb && rb >= 16 && rb <= 4096 && take < (1ull << 30)) {
+    copy_rows_packed<NT, (U >= 16 ? 3 : 2)>(X, p, take, tid);
+    return;
+  }
   // a row of rb bytes at any alignment spans at most (rb + 30) / 16 granules
   constexpr uint32_t RS = 4, RL = 2;  // rows per group and pass
   if (rb <= 16 * 16 - 30) {
@@ -400,22 +493,35 @@ __device__ __forceinline__ void cursor_set(PhaseCursor &pc, CPhaseP phases, uint
   pc.next_base = idx + 1 < nphases ? phases[idx + 1].rank_base : ~0ull;
 }
 
+// Where a workgroup is in the list of empty-tile runs (its tickets only grow).
+struct SkipCursor {
+  uint32_t idx;
+  uint64_t acc;      // empty tiles before the current ticket
+  uint64_t next_at;  // ticket at which the next run applies; all ones after the last
+};
+
 // Dependent table reads on the way from a ticket to its bytes: the slot; then the
 // function and the chunk's first and last descriptor index side by side; then the
 // descriptor itself (plus a short search when a chunk spans several descriptors).
 __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTables &CT, PhaseCursor &pc,
-                                              uint64_t t) {
+                                              SkipCursor &sc, uint64_t t) {
   Work w;
   w.b0 = w.b1 = 0;
   w.x = 0;
   if (t >= T.ntickets) return w;
+  while (t >= sc.next_at) {
+    sc.acc += CT.skips[sc.idx].gap;
+    sc.idx += 1;
+    sc.next_at = sc.idx < T.nskips ? CT.skips[sc.idx].at : ~0ull;
+  }
+  const uint64_t v = t + sc.acc;  // tile of the uniform grid
   uint64_t rank, ti;
-  if (t < (1ull << 32)) {
-    rank = (uint32_t)t / T.tiles_per_chunk;
-    ti = (uint32_t)t - (uint32_t)rank * T.tiles_per_chunk;
+  if (v < (1ull << 32)) {
+    rank = (uint32_t)v / T.tiles_per_chunk;
+    ti = (uint32_t)v - (uint32_t)rank * T.tiles_per_chunk;
   } else {
-    rank = t / T.tiles_per_chunk;
-    ti = t - rank * T.tiles_per_chunk;
+    rank = v / T.tiles_per_chunk;
+    ti = v - rank * T.tiles_per_chunk;
   }
   while (rank >= pc.next_base) cursor_set(pc, CT.phases, T.nphases, pc.idx + 1);
   const uint64_t rel = rank - pc.rank_base;
@@ -455,34 +561,83 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
   return w;
 }
 
-// Persistent workgroups. Workgroup b starts on tickets b and b + gridDim.x (the counter
-// starts at 2 * gridDim.x, so a launch does not open with every workgroup queueing on
-// one atomic); after that tickets are drawn two ahead: while tile i moves, ticket i+1
-// is already known and the atomic for ticket i+2 is in flight. A workgroup moves its
-// tile in two phases - every load of the tile, then every store - and decodes ticket
-// i+1 (scalar table reads) while the stores drain; the barrier at the end of the
-// iteration waits for them. Keeping a CU's reads and writes in separate bursts, one
-// workgroup per CU, is what the memory controllers serve fastest.
+// A decoded ticket on its way from the first wavefront to the others, in LDS.
+struct WorkSlot {
+  uint64_t t;  // the ticket; >= ntickets: none left
+  uint64_t b0, b1;
+  uint64_t x;
+  Xfer first;
+};
+
+__device__ __forceinline__ void put_work(WorkSlot &slot, uint64_t t, const Work &w) {
+  slot.t = t;
+  slot.b0 = w.b0;
+  slot.b1 = w.b1;
+  slot.x = w.x;
+  slot.first = w.first;
+}
+
+__device__ __forceinline__ uint64_t get_work(const WorkSlot &slot, Work &w) {
+  w.b0 = uniform64(slot.b0);
+  w.b1 = uniform64(slot.b1);
+  w.x = (uint32_t)uniform64(slot.x);
+  w.first.src = uniform64(slot.first.src);
+  w.first.dst = uniform64(slot.first.dst);
+  w.first.row_bytes = uniform64(slot.first.row_bytes);
+  w.first.rows = uniform64(slot.first.rows);
+  w.first.src_pitch = uniform64(slot.first.src_pitch);
+  w.first.dst_pitch = uniform64(slot.first.dst_pitch);
+  w.first.stream_off = uniform64(slot.first.stream_off);
+  w.first._pad = 0;
+  return uniform64(slot.t);
+}
+
+// Persistent workgroups. Every ticket, the first included, comes from the counter, so a
+// workgroup that the GPU starts late (its CU was busy with other work) delays nothing:
+// the tickets go to whoever is running. (Handing workgroup b ticket b for free saves
+// the opening queue on the atomic, about 1 % of a 100 us launch, but leaves ticket b
+// waiting for workgroup b.) A workgroup holds one ticket beyond the one it is moving:
+// the atomic for ticket i+1 is issued before tile i's loads and read after its stores.
+// A workgroup moves its tile in two phases - every load of the tile, then every store.
+// While the stores drain, the first wavefront alone decodes ticket i+1 (scalar table
+// reads) and leaves the result in LDS; the barrier at the end of the iteration waits
+// for the stores and publishes it. Keeping a CU's reads and writes in separate bursts,
+// one workgroup per CU, is what the memory controllers serve fastest.
 //
-// CLS (the link class) changes no code; it gives each class's kernel a name of its own
-// so that profiles keep host-link launches and pool->pool launches apart.
+// CLS (the link class) selects the block size of the copy routines and gives each
+// class's kernel a name of its own, so that profiles keep host-link launches and
+// pool->pool launches apart.
 template <bool NT, int CLS>
-__global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 3)) __attribute__((amdgpu_num_vgpr(336))) void ft_copy_kernel(ClassTable T) {
+__global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(ClassTable T) {
   constexpr uint32_t U = UnrollOf<CLS>::value;
-  __shared__ unsigned long long s_ticket[2];
+  __shared__ WorkSlot s_work[2];
   const uint32_t tid = threadIdx.x;
+  const bool lead = tid < 64;  // the first wavefront: draws and decodes tickets
   if (T.log && tid == 0) T.wg_log[blockIdx.x].t_entry = wall_clock64();
-  uint64_t t_cur = blockIdx.x;
-  uint64_t t_next = (uint64_t)blockIdx.x + gridDim.x;
-  uint32_t slot = 0;  // where ticket i+2 goes
   const ConstTables CT = const_tables(T);
   PhaseCursor pc;
-  cursor_set(pc, CT.phases, T.nphases, 0);
-  Work cur = decode_ticket(T, CT, pc, t_cur);
-  while (t_cur < T.ntickets) {
+  SkipCursor sc;
+  if (lead) {
+    cursor_set(pc, CT.phases, T.nphases, 0);
+    sc.idx = 0;
+    sc.acc = 0;
+    sc.next_at = T.nskips ? CT.skips[0].at : ~0ull;
+    unsigned long long first = 0;
+    if (tid == 0) first = atomicAdd(T.ticket, 1ull);
+    const uint64_t t_first = uniform64(first);
+    const Work w = decode_ticket(T, CT, pc, sc, t_first);
+    if (tid == 0) put_work(s_work[0], t_first, w);
+  }
+  __syncthreads();
+  uint32_t slot = 0;
+  while (true) {
+    Work cur;
+    const uint64_t t_cur = get_work(s_work[slot], cur);
+    if (t_cur >= T.ntickets) break;
     uint64_t t_begin = 0;
     if (T.log) t_begin = wall_clock64();
     unsigned long long claimed = 0;
+    if (tid == 0) claimed = atomicAdd(T.ticket, 1ull);
 
     const uint64_t p0 = cur.b0 - cur.first.stream_off;
     const uint64_t len = cur.b1 - cur.b0;
@@ -491,7 +646,6 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 3)) __attribute__((amdgpu
         p0 + len <= cur.first.row_bytes) {
       // the common case, one full aligned block (64 KiB for pool->pool): straight-line
       // code from the ticket draw to the last store
-      if (tid == 0) claimed = atomicAdd(T.ticket, 1ull);
       copy_rows_of_vectors<NT, U>(fd, fs, tid);
     } else {
       uint64_t pos = cur.b0;
@@ -506,10 +660,13 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 3)) __attribute__((amdgpu
         pos += take;
         if (pos < cur.b1) X = read_xfer(CT.xfers, ++x);
       }
-      if (tid == 0) claimed = atomicAdd(T.ticket, 1ull);
     }
-    if (tid == 0) s_ticket[slot] = claimed;
-    const Work next = decode_ticket(T, CT, pc, t_next);
+    if (lead) {
+      // lane 0 holds the counter's answer; all 64 lanes of this wavefront are enabled
+      const uint64_t t_next = uniform64(claimed);
+      const Work next = decode_ticket(T, CT, pc, sc, t_next);
+      if (tid == 0) put_work(s_work[slot ^ 1], t_next, next);
+    }
 
     if (T.log) {
       // the tile counts as done when every store of the workgroup has been acknowledged
@@ -522,9 +679,6 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 3)) __attribute__((amdgpu
       }
     }
     __syncthreads();
-    t_cur = t_next;
-    cur = next;
-    t_next = uniform64(s_ticket[slot]);
     slot ^= 1;
   }
   if (T.log && tid == 0) T.wg_log[blockIdx.x].t_exit = wall_clock64();

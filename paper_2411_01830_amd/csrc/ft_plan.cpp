@@ -15,6 +15,48 @@ void tile_shape(uint64_t chunk_bytes, uint64_t want_tile, uint64_t *tile_bytes, 
   *tiles_per_chunk = (uint32_t)((chunk_bytes + tile - 1) / tile);
 }
 
+// Position of chunk j of function f in the proportional order: the chunks (g, i) with
+// (i+1)/w_g < (j+1)/w_f, or equal and g < f, come before it.
+static uint64_t rank_of_chunk(const std::vector<Func> &funcs, uint32_t f, uint64_t j) {
+  typedef unsigned __int128 u128;
+  const u128 num = (u128)(j + 1);
+  const uint64_t wf = funcs[f].weight;
+  uint64_t rank = j;
+  for (uint32_t g = 0; g < funcs.size(); ++g) {
+    if (g == f) continue;
+    const u128 prod = num * funcs[g].weight;
+    u128 c = prod / wf;                           // i + 1 <= prod / wf
+    if (g > f && prod % wf == 0) c -= 1;          // ties go to the lower function
+    rank += c < funcs[g].nchunks ? (uint64_t)c : funcs[g].nchunks;
+  }
+  return rank;
+}
+
+void build_skips(const ClassPlan &cp, uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t tiles_per_chunk,
+                 std::vector<Skip> *skips, uint64_t *ntickets) {
+  skips->clear();
+  struct Short {
+    uint64_t rank, tiles;
+  };
+  std::vector<Short> shorts;
+  for (uint32_t f = 0; f < cp.funcs.size(); ++f) {
+    const Func &fn = cp.funcs[f];
+    const uint64_t last_bytes = fn.stream_bytes - (fn.nchunks - 1) * chunk_bytes;
+    const uint64_t tiles = (last_bytes + tile_bytes - 1) / tile_bytes;
+    if (tiles < tiles_per_chunk) shorts.push_back(Short{rank_of_chunk(cp.funcs, f, fn.nchunks - 1), tiles});
+  }
+  std::sort(shorts.begin(), shorts.end(), [](const Short &a, const Short &b) { return a.rank < b.rank; });
+  uint64_t gone = 0;
+  for (const Short &sh : shorts) {
+    Skip sk;
+    sk.at = sh.rank * tiles_per_chunk + sh.tiles - gone;
+    sk.gap = tiles_per_chunk - sh.tiles;
+    gone += sk.gap;
+    skips->push_back(sk);
+  }
+  *ntickets = cp.nchunks * tiles_per_chunk - gone;
+}
+
 namespace {
 
 // slot a before slot b: smaller finish tag (i+1)/w, ties to the lower function

@@ -46,6 +46,11 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
                 uint32_t ndesc, const uint32_t *weights, uint32_t nfunc, uint64_t chunk_bytes,
                 uint32_t flags, SubmitPlan *out);
 
+// Runs of empty tiles (past the end of each function's last chunk) for the given tile
+// shape, in ticket order, and the number of tickets left once they are taken out.
+void build_skips(const ClassPlan &cp, uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t tiles_per_chunk,
+                 std::vector<Skip> *skips, uint64_t *ntickets);
+
 // Bytes per ticket and tickets per chunk for a chunk size and a wanted tile size.
 void tile_shape(uint64_t chunk_bytes, uint64_t want_tile, uint64_t *tile_bytes, uint32_t *tiles_per_chunk);
 

@@ -63,6 +63,15 @@ struct Xfer {
   uint64_t _pad;
 };
 
+// Tickets number only tiles that hold bytes. Tile v of the uniform grid (chunk rank
+// v / tiles_per_chunk, tile v % tiles_per_chunk) is empty when it lies past the end of a
+// function's last chunk; `at` is the first ticket at or after such a run of empty tiles
+// and `gap` their number: v = t + the gaps of all entries with at <= t.
+struct Skip {
+  uint64_t at;
+  uint64_t gap;
+};
+
 struct LogEntry {
   uint64_t t_begin;
   uint64_t t_end;
@@ -85,18 +94,26 @@ struct ClassTable {
   // k * C for k < nchunks, then the function's last descriptor. Null when the job has
   // too many chunks for the table to be worth its memory.
   const uint32_t *chunk_desc;
-  unsigned long long *ticket;  // device counter; starts at 2 * workgroups (see ft_copy_kernel)
+  const Skip *skips;           // ascending `at`
+  unsigned long long *ticket;  // device counter, zero at launch
   LogEntry *log;               // one per ticket, or null
   WgLogEntry *wg_log;          // one per workgroup; set whenever log is
   uint64_t nchunks;            // N
-  uint64_t ntickets;           // N * tiles_per_chunk
+  uint64_t ntickets;           // N * tiles_per_chunk minus the empty tiles
   uint64_t chunk_bytes;        // C
   uint64_t tile_bytes;         // bytes per ticket, multiple of 16
   uint32_t tiles_per_chunk;
   uint32_t nphases;
   uint32_t nfuncs;
-  uint32_t _pad;
+  uint32_t nskips;
 };
+
+// Ticket -> tile of the uniform grid (host side; the copy kernel keeps a cursor).
+inline uint64_t ticket_to_tile(const Skip *skips, uint32_t nskips, uint64_t t) {
+  uint64_t v = t;
+  for (uint32_t j = 0; j < nskips && skips[j].at <= t; ++j) v += skips[j].gap;
+  return v;
+}
 
 struct ChunkId {
   uint32_t fl;  // index into funcs

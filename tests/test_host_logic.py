@@ -138,6 +138,33 @@ def test_schedule_tables_match_oracle_order():
         assert ft.plan_schedule(S, w, C) == stride_order(n, w)
 
 
+def test_tickets_name_every_nonempty_tile_once_in_chunk_order():
+    """Tickets skip the empty tiles past the end of each function's last chunk: the list
+    must be the oracle's chunk order with every chunk cut into tiles, nothing else."""
+    rng = random.Random(11)
+    for case in range(300):
+        F = rng.randint(1, 8)
+        C = 16 * rng.randint(1, 64)
+        want_tile = 16 * rng.randint(1, 24)
+        n = [rng.randint(0, 12) for _ in range(F)]
+        w = [rng.choice([1, 1, 2, 3, 4, 8]) for _ in range(F)]
+        S = [0 if x == 0 else x * C - rng.randint(0, C - 1) for x in n]
+        got = ft.plan_tickets(S, w, C, want_tile)
+        # the planner's tile shape: equal tiles, multiple of 16, at most `want_tile` rounded
+        ntile = -(-C // max(want_tile, 16))
+        tile = -(-(-(-C // ntile)) // 16) * 16
+        expect = []
+        for f, k in stride_order(n, w):
+            lo, hi = k * C, min((k + 1) * C, S[f])
+            b = lo
+            while b < hi:
+                expect.append((f, k, b, min(tile, lo + C - b, hi - b)))
+                b += tile
+        assert got == expect, (case, S, w, C, want_tile)
+        assert all(x[3] > 0 for x in got)
+        assert sum(x[3] for x in got) == sum(S)
+
+
 def test_schedule_tables_weights_dwarf_chunk_counts():
     # weights far larger than the number of chunks: only irregular rounds exist
     w = [1000, 999, 7]
