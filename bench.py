@@ -11,8 +11,9 @@ four workloads are run once each for the ``per_workload`` block of the same line
 
 Prints ONE JSON line. ``value`` is payload bytes per second over the timed steps.
 ``roofline`` is for the pool->pool copy kernel (HBM bound): algorithmic bytes are
-2 x payload (one read, one write), durations are HIP events the library records on
-the kernel's own stream around every launch of the timed steps.
+2 x payload (one read, one write), durations come from HIP timing events that the
+library binds to every launch of the timed steps on the kernel's own stream (they read
+the start and the end of that dispatch).
 """
 import argparse
 import json
@@ -28,10 +29,10 @@ import numpy as np
 
 METRIC = "aggregate GB/s (host->pool, pool->pool) as % of roofline; weighted-share error"
 HBM_PEAK_GBS = 8000.0
-# HBM bytes the profiler counted per algorithmic byte for the pool->pool kernel
-# (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy of known size); see
-# profiles/pmc_hbm_traffic_pool_to_pool_feature.md.
-TRAFFIC_PER_ALGO_BYTE = 1.0006
+# HBM bytes the profiler counted per algorithmic byte for the pool->pool kernel of the
+# default workload (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy of known
+# size); see profiles/pmc_hbm_traffic_pool_to_pool_large_mixed.md.
+TRAFFIC_PER_ALGO_BYTE = 1.0092
 
 
 def parse_args():
