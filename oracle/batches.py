@@ -1,0 +1,66 @@
+"""Batched transfer triggering of Sec. 6.1 with functions that arrive while a
+link is busy.
+
+Sec. 6.1: a chunk transfer cannot be interrupted once triggered, so the
+chunks of a link are triggered in batches (5 chunks by default); functions
+that arrive meanwhile get bandwidth by having their chunks included in the
+batches that follow.
+
+Reading taken here. A link class works through a sequence of batches of at
+most `batch_chunks` chunks. A job is a set of functions (stream sizes in
+chunks, weights). Job 0 is there from the start; a later job carries
+`arrive`, the number of batches that had already been triggered when it
+showed up, so batch `arrive` is the first that may hold its chunks. Whenever
+jobs join at a batch boundary, the proportional order (stride order of
+schedule.py) is built afresh over everything not yet triggered: the
+remaining chunks of every earlier function, renumbered from where each
+stands, and all chunks of the new functions; functions are ordered by (job,
+function index) for the tie rule. Between arrivals the order in force is
+simply continued, five chunks at a time. A job that arrives after the link
+has run dry starts a new sequence at once.
+
+TEST INFRASTRUCTURE ONLY (see the package docstring).
+"""
+from .schedule import stride_order
+
+
+def batched_order(jobs, batch_chunks=5):
+    """jobs: list of dicts with keys `n` (chunks per function), `w` (weights) and,
+    for every job but the first, `arrive`. Returns the list of batches; a batch is
+    a list of (job, function, chunk)."""
+    if batch_chunks < 1:
+        raise ValueError("batch_chunks")
+    waiting = sorted(range(1, len(jobs)), key=lambda j: (jobs[j]["arrive"], j))
+    funcs = [(0, f) for f in range(len(jobs[0]["n"]))]   # (job, function) in tie order
+    served = {(0, f): 0 for f in range(len(jobs[0]["n"]))}
+    batches = []
+    order = None      # the order in force: list of (index into funcs, fresh chunk number)
+    pos = 0
+    base = {}         # chunk number each function stood at when the order was built
+    while True:
+        joined = False
+        while waiting and (jobs[waiting[0]]["arrive"] <= len(batches) or
+                           (order is not None and pos >= len(order))):
+            j = waiting.pop(0)
+            for f in range(len(jobs[j]["n"])):
+                funcs.append((j, f))
+                served[(j, f)] = 0
+            joined = True
+        if order is None or joined:
+            live = [jf for jf in funcs if served[jf] < jobs[jf[0]]["n"][jf[1]]]
+            base = {jf: served[jf] for jf in live}
+            n = [jobs[j]["n"][f] - served[(j, f)] for j, f in live]
+            w = [jobs[j]["w"][f] for j, f in live]
+            order = [(live[i], k) for i, k in stride_order(n, w)]
+            pos = 0
+        if pos >= len(order):
+            if not waiting:
+                break
+            continue
+        batch = []
+        for jf, k in order[pos:pos + batch_chunks]:
+            batch.append((jf[0], jf[1], base[jf] + k))
+            served[jf] += 1
+        pos += len(batch)
+        batches.append(batch)
+    return batches
