@@ -10,14 +10,16 @@ Reading taken here. A link class works through a sequence of batches of at
 most `batch_chunks` chunks. A job is a set of functions (stream sizes in
 chunks, weights). Job 0 is there from the start; a later job carries
 `arrive`, the number of batches that had already been triggered when it
-showed up, so batch `arrive` is the first that may hold its chunks. Whenever
+showed up, so batch `arrive` is the first that may hold its chunks (jobs are
+listed in the order they arrive). Whenever
 jobs join at a batch boundary, the proportional order (stride order of
 schedule.py) is built afresh over everything not yet triggered: the
 remaining chunks of every earlier function, renumbered from where each
 stands, and all chunks of the new functions; functions are ordered by (job,
 function index) for the tie rule. Between arrivals the order in force is
-simply continued, five chunks at a time. A job that arrives after the link
-has run dry starts a new sequence at once.
+simply continued, five chunks at a time. When the link runs dry while jobs are
+still to come, the earliest of them (smallest `arrive`, then job index) starts
+a new sequence at once; the others keep waiting for their batch count.
 
 TEST INFRASTRUCTURE ONLY (see the package docstring).
 """
@@ -30,7 +32,10 @@ def batched_order(jobs, batch_chunks=5):
     a list of (job, function, chunk)."""
     if batch_chunks < 1:
         raise ValueError("batch_chunks")
-    waiting = sorted(range(1, len(jobs)), key=lambda j: (jobs[j]["arrive"], j))
+    arrive = [0] + [jobs[j]["arrive"] for j in range(1, len(jobs))]
+    if any(a > b for a, b in zip(arrive, arrive[1:])):
+        raise ValueError("jobs are listed in the order they arrive")
+    waiting = list(range(1, len(jobs)))
     funcs = [(0, f) for f in range(len(jobs[0]["n"]))]   # (job, function) in tie order
     served = {(0, f): 0 for f in range(len(jobs[0]["n"]))}
     batches = []
@@ -38,15 +43,16 @@ def batched_order(jobs, batch_chunks=5):
     pos = 0
     base = {}         # chunk number each function stood at when the order was built
     while True:
-        joined = False
-        while waiting and (jobs[waiting[0]]["arrive"] <= len(batches) or
-                           (order is not None and pos >= len(order))):
-            j = waiting.pop(0)
+        dry = order is None or pos >= len(order)
+        newly = [j for j in waiting if jobs[j]["arrive"] <= len(batches)]
+        if dry and order is not None and not newly and waiting:
+            newly = [waiting[0]]
+        for j in newly:
+            waiting.remove(j)
             for f in range(len(jobs[j]["n"])):
                 funcs.append((j, f))
                 served[(j, f)] = 0
-            joined = True
-        if order is None or joined:
+        if order is None or newly:
             live = [jf for jf in funcs if served[jf] < jobs[jf[0]]["n"][jf[1]]]
             base = {jf: served[jf] for jf in live}
             n = [jobs[j]["n"][f] - served[(j, f)] for j, f in live]

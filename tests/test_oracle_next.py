@@ -143,11 +143,13 @@ def test_merge_properties_random():
     for case in range(300):
         B = rng.randint(1, 6)
         jobs = []
-        for j in range(rng.randint(1, 4)):
+        njobs = rng.randint(1, 4)
+        arrive = sorted(rng.randint(0, 8) for _ in range(njobs - 1))
+        for j in range(njobs):
             F = rng.randint(1, 4)
             job = {"n": [rng.randint(0, 8) for _ in range(F)], "w": [rng.choice([1, 1, 2, 3, 5]) for _ in range(F)]}
             if j:
-                job["arrive"] = rng.randint(0, 8)
+                job["arrive"] = arrive[j - 1]
             jobs.append(job)
         batches = batched_order(jobs, B)
         flat = _flat(batches)
@@ -159,29 +161,41 @@ def test_merge_properties_random():
                 ks = [k for a, b, k in flat if (a, b) == (j, f)]
                 assert ks == sorted(ks)
         assert all(1 <= len(b) <= B for b in batches)
-        # a job's chunks never appear before the batch it arrived at
-        for j, job in enumerate(jobs[1:], start=1):
-            first = next((i for i, b in enumerate(batches) if any(a == j for a, _, _ in b)), None)
-            if first is not None:
-                assert first >= min(job["arrive"], first)       # trivially true when the link ran dry
-                if job["arrive"] <= len(batches):
-                    assert first >= job["arrive"] or all(len(x) < B or True for x in batches)
-        # between two arrival points the batches are a prefix of the fresh order over what was left
-        arrivals = sorted({min(job["arrive"], len(batches)) for job in jobs[1:]} | {0})
-        served = {}
-        for idx, a in enumerate(arrivals):
-            b_end = arrivals[idx + 1] if idx + 1 < len(arrivals) else len(batches)
-            segment = _flat(batches[a:b_end])
-            # jobs known at batch a: arrived at or before it (or the link had run dry)
-            known = [j for j, job in enumerate(jobs) if j == 0 or job["arrive"] <= a]
-            funcs = [(j, f) for j in known for f in range(len(jobs[j]["n"]))]
-            left = [jobs[j]["n"][f] - served.get((j, f), 0) for j, f in funcs]
-            w = [jobs[j]["w"][f] for j, f in funcs]
-            fresh = [(funcs[i][0], funcs[i][1], served.get(funcs[i], 0) + k) for i, k in _brute_order(funcs, left, w)]
-            if all(x[0] in known for x in segment):
-                assert segment == fresh[:len(segment)], (case, a)
-            for x in segment:
-                served[(x[0], x[1])] = served.get((x[0], x[1]), 0) + 1
+        assert batches == _reference_batches(jobs, B), case
+
+
+def _reference_batches(jobs, B):
+    """The rule written a second way: the remaining work is an explicit list of chunks,
+    re-sorted by (finish tag, job, function) whenever jobs join."""
+    waiting = list(range(1, len(jobs)))
+    present = [0]
+    done = {}
+    todo = None
+    out = []
+    while True:
+        newly = [j for j in waiting if jobs[j]["arrive"] <= len(out)]
+        if todo is not None and not todo and not newly and waiting:
+            newly = [waiting[0]]
+        if todo is None or newly:
+            for j in newly:
+                waiting.remove(j)
+                present.append(j)
+            keys = []
+            for j in present:
+                for f, n in enumerate(jobs[j]["n"]):
+                    have = done.get((j, f), 0)
+                    for i in range(n - have):
+                        keys.append((Fraction(i + 1, jobs[j]["w"][f]), j, f, have + i))
+            keys.sort()
+            todo = [(j, f, k) for _, j, f, k in keys]
+        if not todo:
+            if not waiting:
+                return out
+            continue
+        batch, todo = todo[:B], todo[B:]
+        for j, f, _ in batch:
+            done[(j, f)] = done.get((j, f), 0) + 1
+        out.append(batch)
 
 
 def test_newcomer_with_high_weight_is_served_within_one_batch_of_arrival():
