@@ -45,7 +45,9 @@ enum {
                        outside every registered host window */
   FT_EOVERLAP = -4, /* with FT_VALIDATE: a destination byte is written twice or also read */
   FT_EBUSY = -5,    /* ft_slab_free of an allocation a not-yet-waited job refers to */
-  FT_EHIP = -6      /* a HIP runtime call failed; ft_last_hip_error() gives its text */
+  FT_EHIP = -6,     /* a HIP runtime call failed; ft_last_hip_error() gives its text */
+  FT_ECLOSED = -7   /* ft_submit_merge: the open job has no batch left to trigger on a link
+                       class the new transfers use; submit them as a job of their own */
 };
 
 /* flags of ft_submit_transfers */
@@ -56,8 +58,11 @@ enum {
                            chunk piece instead of the copy kernel (comparison path) */
   FT_TIMING = 1 << 3,   /* bracket each class's work with timing events */
   FT_DETACHED = 1 << 4, /* do not make the caller's stream wait for the job */
-  FT_KEEP = 1 << 5      /* keep the job record after ft_wait until ft_job_release;
+  FT_KEEP = 1 << 5,     /* keep the job record after ft_wait until ft_job_release;
                            implied by FT_LOG and FT_TIMING */
+  FT_OPEN = 1 << 6      /* trigger the chunks in batches and accept ft_submit_merge meanwhile
+                           (Sec. 6.1, batched transfer triggering); implies FT_DETACHED; not
+                           with FT_LOG or FT_PATH_DMA */
 };
 
 /*
@@ -180,6 +185,61 @@ int ft_host_window_add(ft_pool *p, void *host_base, uint64_t bytes);
 int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
                         uint32_t nfunc, uint64_t chunk_bytes, uint32_t flags, void *hip_stream,
                         ft_job_t *job_out);
+
+/*
+ * Batched transfer triggering (Sec. 6.1). A job submitted with FT_OPEN does not hand its
+ * whole chunk order to the device at once: per link class a feeder thread launches the
+ * copy kernel once per batch of `batch_chunks` consecutive chunks of the order (5 unless
+ * ft_set_batch says otherwise) and keeps `depth` batches (2) queued ahead of the device.
+ * Transfers merged meanwhile join at the first batch not yet triggered: the order is
+ * rebuilt over the chunks not yet triggered of every function already there - each
+ * restarting its finish tags at 1/w - plus all chunks of the new functions, functions
+ * of earlier jobs before those of later ones in the tie rule, and the following batches
+ * come from that order. So a newcomer waits for at most `depth` batches, whatever the
+ * length of the jobs before it, and from then on shares the link by weight with them.
+ *
+ * ft_submit_merge: arguments as ft_submit_transfers; the chunk size is the open job's.
+ * The new transfers form a job of their own (own ft_wait, own weights for its nfunc
+ * functions, weighed against the other jobs' weights as given). Returns FT_ECLOSED,
+ * with nothing merged, if the open job has already triggered its last batch on a link
+ * class the new transfers use. Flags: FT_VALIDATE, FT_KEEP (others are taken from the
+ * open job). The caller's stream is never made to wait (as with FT_DETACHED); the
+ * transfers start after the work already on hip_stream.
+ */
+int ft_submit_merge(ft_pool *p, ft_job_t open_job, const ft_desc *descs, uint32_t ndesc,
+                    const uint32_t *weights, uint32_t nfunc, uint32_t flags, void *hip_stream,
+                    ft_job_t *job_out);
+
+/* Chunks per batch (>= 1) and batches queued ahead (>= 1) for open jobs submitted later. */
+int ft_set_batch(ft_pool *p, uint32_t batch_chunks, uint32_t depth);
+
+/*
+ * Number of batches of `link_class` that the open job had triggered when `job` joined
+ * it (0 for the open job itself): the first batch that may hold the job's chunks.
+ */
+int ft_job_arrival(ft_pool *p, ft_job_t job, int link_class, uint64_t *batch_out);
+
+/*
+ * Test hook: what an open job submitted with FT_KEEP has triggered on `link_class` so
+ * far, chunk by chunk in order: the job the chunk belongs to, its function in that job,
+ * the chunk's index in the function's stream and the number of the batch. Host arrays
+ * of `cap` entries each; *n_out receives the number of chunks triggered.
+ */
+int ft_job_batches(ft_pool *p, ft_job_t open_job, int link_class, uint64_t *job_out, uint32_t *func_out,
+                   uint32_t *chunk_out, uint32_t *batch_out, uint64_t cap, uint64_t *n_out);
+
+/*
+ * Function transfer rate control (Sec. 6.1), host-only. For n functions with data sizes
+ * (bytes), latency objectives l_slo and inference times l_infer (seconds) on a link of
+ * bw_all bytes/s: Rate_least = data_size / (L_slo - L_infer) each; what the link has
+ * beyond the sum of the least rates goes to the function with the least time left
+ * (lowest index on a tie); nothing is added when the sum already exceeds the link.
+ * rate_out (may be NULL) receives the rates, weights_out the integer weights for
+ * ft_submit_transfers: each function's share of the rate sum times `total` (0 = 64),
+ * rounded half up, at least 1. FT_EINVAL if n == 0, bw_all <= 0 or some L_slo <= L_infer.
+ */
+int ft_slo_weights(const double *data_size, const double *l_slo, const double *l_infer, uint32_t n,
+                   double bw_all, uint32_t total, double *rate_out, uint32_t *weights_out);
 
 /*
  * Block until every chunk of the job is visible at its destination (device memory,

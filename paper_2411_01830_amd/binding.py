@@ -9,10 +9,12 @@ LIB_PATH = os.path.join(_HERE, "libfaastube.so")
 
 FT_NCLASS = 3
 FT_H2P, FT_P2H, FT_P2P = 0, 1, 2
-FT_VALIDATE, FT_LOG, FT_PATH_DMA, FT_TIMING, FT_DETACHED, FT_KEEP = 1, 2, 4, 8, 16, 32
+FT_VALIDATE, FT_LOG, FT_PATH_DMA, FT_TIMING, FT_DETACHED, FT_KEEP, FT_OPEN = 1, 2, 4, 8, 16, 32, 64
+FT_ECLOSED = -7
 
 EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
-           "ft_pool_ptr", "ft_host_window_add", "ft_submit_transfers", "ft_wait", "ft_job_release",
+           "ft_pool_ptr", "ft_host_window_add", "ft_submit_transfers", "ft_submit_merge", "ft_set_batch",
+           "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
            "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
            "ft_plain_copy", "ft_strerror", "ft_last_hip_error"]
 
@@ -53,6 +55,11 @@ def _load():
         "ft_pool_ptr": (vp, [vp, u64]),
         "ft_host_window_add": (i32, [vp, vp, u64]),
         "ft_submit_transfers": (i32, [vp, vp, u32, vp, u32, u64, u32, vp, P(u64)]),
+        "ft_submit_merge": (i32, [vp, u64, vp, u32, vp, u32, u32, vp, P(u64)]),
+        "ft_set_batch": (i32, [vp, u32, u32]),
+        "ft_job_arrival": (i32, [vp, u64, i32, P(u64)]),
+        "ft_job_batches": (i32, [vp, u64, i32, vp, vp, vp, vp, u64, P(u64)]),
+        "ft_slo_weights": (i32, [vp, vp, vp, u32, C.c_double, u32, vp, vp]),
         "ft_wait": (i32, [vp, u64]),
         "ft_job_release": (i32, [vp, u64]),
         "ft_job_stats": (i32, [vp, u64, P(JobStats)]),
@@ -195,6 +202,51 @@ def plan_schedule(stream_bytes, weights, chunk_bytes):
     _check(_lib.ft_plan_schedule(s.ctypes.data, w.ctypes.data, len(w), chunk_bytes, f.ctypes.data,
                                  k.ctypes.data, n.value, C.byref(n)))
     return list(zip(f[:n.value].tolist(), k[:n.value].tolist()))
+
+
+def submit_merge(pool, open_job, descs, weights, flags=0, stream=0):
+    d = np.ascontiguousarray(descs)
+    w = np.ascontiguousarray(np.asarray(weights, dtype=np.uint32))
+    job = C.c_uint64()
+    _check(_lib.ft_submit_merge(pool, open_job, d.ctypes.data, len(d), w.ctypes.data, len(w), flags, stream,
+                                C.byref(job)), pool)
+    return job.value
+
+
+def set_batch(pool, batch_chunks=5, depth=2):
+    _check(_lib.ft_set_batch(pool, batch_chunks, depth), pool)
+
+
+def job_arrival(pool, job, link_class):
+    b = C.c_uint64()
+    _check(_lib.ft_job_arrival(pool, job, link_class, C.byref(b)), pool)
+    return b.value
+
+
+def job_batches(pool, open_job, link_class):
+    """List of batches; a batch is a list of (job handle, function, chunk)."""
+    n = C.c_uint64()
+    _check(_lib.ft_job_batches(pool, open_job, link_class, None, None, None, None, 0, C.byref(n)), pool)
+    m = max(n.value, 1)
+    j, f, k, b = np.zeros(m, np.uint64), np.zeros(m, np.uint32), np.zeros(m, np.uint32), np.zeros(m, np.uint32)
+    _check(_lib.ft_job_batches(pool, open_job, link_class, j.ctypes.data, f.ctypes.data, k.ctypes.data,
+                               b.ctypes.data, n.value, C.byref(n)), pool)
+    out = []
+    for i in range(min(n.value, m)):
+        while len(out) <= int(b[i]):
+            out.append([])
+        out[int(b[i])].append((int(j[i]), int(f[i]), int(k[i])))
+    return out
+
+
+def slo_weights(data_size, l_slo, l_infer, bw_all, total=0):
+    """(rates, weights) of Sec. 6.1's transfer rate control."""
+    a = [np.ascontiguousarray(np.asarray(x, dtype=np.float64)) for x in (data_size, l_slo, l_infer)]
+    n = len(a[0])
+    rate, w = np.zeros(max(n, 1), np.float64), np.zeros(max(n, 1), np.uint32)
+    _check(_lib.ft_slo_weights(a[0].ctypes.data, a[1].ctypes.data, a[2].ctypes.data, n, float(bw_all), total,
+                               rate.ctypes.data, w.ctypes.data))
+    return rate[:n].tolist(), w[:n].tolist()
 
 
 def plan_tickets(stream_bytes, weights, chunk_bytes, tile_bytes):

@@ -7,7 +7,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfaastube.so")
-SOURCES = ["ft_pool.cpp", "ft_plan.cpp", "ft_api.cpp", "ft_kernels.hip"]
+SOURCES = ["ft_pool.cpp", "ft_plan.cpp", "ft_api.cpp", "ft_open.cpp", "ft_kernels.hip"]
 # packed fp32 code generation is switched off for every translation unit
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-result",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -66,7 +66,10 @@ def build(verbose=False):
             cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
         if verbose:
             print(" ".join(cmd), flush=True)
-        res = subprocess.run(cmd, check=True, stderr=subprocess.PIPE, text=True)
+        res = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+        if res.returncode != 0:
+            sys.stderr.write(res.stderr)
+            raise RuntimeError(f"hipcc failed on {src}")
         if src == "ft_kernels.hip":
             per_class = check_registers(res.stderr)
             if verbose:

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <chrono>
+#include <cmath>
 #include <cstring>
 #include <memory>
 #include <mutex>
@@ -9,74 +10,9 @@
 #include <unordered_map>
 #include <vector>
 
-#include "../../include/faastube.h"
-#include "ft_kernels.h"
-#include "ft_plan.h"
-#include "ft_pool.h"
-#include "ft_tables.h"
+#include "ft_internal.h"
 
-namespace {
-
-using namespace ft;
-
-// A device buffer with a pinned host twin of the same size; recycled between jobs so
-// that a steady stream of submits allocates nothing.
-struct Blob {
-  char *dev = nullptr;
-  char *host = nullptr;  // null for device-only blobs
-  uint64_t cap = 0;
-};
-
-struct ClassRun {
-  bool used = false;
-  ClassTable table{};       // device addresses
-  ClassPlan plan;           // host copy (DMA path, log decoding, stats)
-  uint64_t tile_bytes = 0;
-  uint32_t tiles_per_chunk = 0;
-  uint32_t workgroups = 0;
-  // ev_done orders the caller's stream and ft_wait after the class's work. With FT_TIMING,
-  // ev_begin / ev_end bracket it: bound to the kernel's dispatch on the kernel path,
-  // recorded around the copy calls on the DMA path.
-  hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_done = nullptr;
-  Blob log;
-  std::vector<Skip> skips;
-  std::vector<LogEntry> log_host;
-  std::vector<WgLogEntry> wg_log_host;
-  float device_ms = -1.f;
-};
-
-struct Job {
-  uint64_t id = 0;
-  uint32_t flags = 0;
-  bool keep = false;
-  bool waited = false;
-  ClassRun run[FT_NCLASS];
-  Blob tables;
-  std::vector<uint64_t> allocs;
-  uint64_t chunk_bytes = 0;
-  double host_submit_us = 0;
-};
-
-struct Tuning {
-  uint32_t workgroups = 0;
-  uint64_t tile_bytes = 0;
-};
-
-// Per-device resources shared by every pool on that device and kept for the life of
-// the process: one stream per link class (so the three classes sit on three hardware
-// queues and really run side by side), recycled table buffers and events. Creating a
-// pool therefore costs no HIP call, and a steady stream of submits allocates nothing.
-struct DeviceCtx {
-  std::mutex mu;
-  int device = 0;
-  bool ready = false;
-  int cu_count = 0;
-  int clock_khz = 0;
-  hipStream_t streams[FT_NCLASS] = {nullptr, nullptr, nullptr};
-  std::vector<Blob> free_blobs;      // with a pinned twin
-  std::vector<Blob> free_dev_blobs;  // device only
-  std::vector<hipEvent_t> free_events, free_timing_events;
-};
+namespace ft {
 
 DeviceCtx *device_ctx(int device) {
   static std::mutex table_mu;
@@ -89,44 +25,6 @@ DeviceCtx *device_ctx(int device) {
   table[device] = c;
   return c;
 }
-
-}  // namespace
-
-struct ft_pool {
-  std::mutex mu;
-  SlabPool slabs;
-  int device;
-  std::vector<HostWindow> windows;
-  DeviceCtx *ctx;
-  std::unordered_map<uint64_t, std::unique_ptr<Job>> jobs;
-  uint64_t next_job = 1;
-  Tuning tuning[FT_NCLASS];
-  std::string hip_error;
-
-  ft_pool(uint64_t slab_bytes, int dev) : slabs(slab_bytes), device(dev), ctx(device_ctx(dev)) {}
-};
-
-namespace {
-
-#define FT_HIP(p, call)                                                        \
-  do {                                                                         \
-    hipError_t e_ = (call);                                                    \
-    if (e_ != hipSuccess) {                                                    \
-      (p)->hip_error = std::string(#call) + ": " + hipGetErrorString(e_);      \
-      return FT_EHIP;                                                          \
-    }                                                                          \
-  } while (0)
-
-struct DeviceGuard {
-  int prev = -1;
-  bool ok = false;
-  explicit DeviceGuard(int dev) {
-    if (hipGetDevice(&prev) == hipSuccess && prev != dev) ok = hipSetDevice(dev) == hipSuccess;
-  }
-  ~DeviceGuard() {
-    if (ok) (void)hipSetDevice(prev);
-  }
-};
 
 int ensure_device(ft_pool *p) {
   DeviceCtx *c = p->ctx;
@@ -206,23 +104,50 @@ void put_event(ft_pool *p, bool timing, hipEvent_t &e) {
 
 uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
-// Byte layout of one class's tables inside the job's blob.
-struct Layout {
-  uint64_t ticket, phases, slots, funcs, xfers, chunks, skips, end;
-};
-
-Layout layout_of(const ClassPlan &cp, uint64_t base) {
-  // at most one run of empty tiles per function
+Layout layout_of(const ClassPlan &cp, uint64_t base, uint64_t ncounters) {
   Layout l;
   l.ticket = align_up(base, 256);
-  l.phases = l.ticket + 256;
+  // the counters of successive launches sit 8 bytes apart: one launch runs at a time
+  l.phases = l.ticket + align_up(ncounters * 8, 256);
   l.slots = align_up(l.phases + cp.phases.size() * sizeof(Phase), 64);
   l.funcs = align_up(l.slots + cp.slots.size() * sizeof(Slot), 64);
   l.xfers = align_up(l.funcs + cp.funcs.size() * sizeof(Func), 64);
   l.chunks = align_up(l.xfers + cp.xfers.size() * sizeof(Xfer), 64);
   l.skips = align_up(l.chunks + cp.chunk_desc.size() * sizeof(uint32_t), 64);
+  // at most one run of empty tiles per function
   l.end = align_up(l.skips + cp.funcs.size() * sizeof(Skip), 256);
   return l;
+}
+
+void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, ClassTable *T) {
+  std::memcpy(h + lay.phases, cp.phases.data(), cp.phases.size() * sizeof(Phase));
+  std::memcpy(h + lay.slots, cp.slots.data(), cp.slots.size() * sizeof(Slot));
+  std::memcpy(h + lay.funcs, cp.funcs.data(), cp.funcs.size() * sizeof(Func));
+  std::memcpy(h + lay.xfers, cp.xfers.data(), cp.xfers.size() * sizeof(Xfer));
+  std::memcpy(h + lay.chunks, cp.chunk_desc.data(), cp.chunk_desc.size() * sizeof(uint32_t));
+  T->phases = reinterpret_cast<const Phase *>(d + lay.phases);
+  T->slots = reinterpret_cast<const Slot *>(d + lay.slots);
+  T->funcs = reinterpret_cast<const Func *>(d + lay.funcs);
+  T->xfers = reinterpret_cast<const Xfer *>(d + lay.xfers);
+  T->chunk_desc = cp.chunk_desc.empty() ? nullptr : reinterpret_cast<const uint32_t *>(d + lay.chunks);
+  T->skips = reinterpret_cast<const Skip *>(d + lay.skips);
+  T->ticket = reinterpret_cast<unsigned long long *>(d + lay.ticket);
+  T->log = nullptr;
+  T->wg_log = nullptr;
+  T->nchunks = cp.nchunks;
+  T->nphases = (uint32_t)cp.phases.size();
+  T->nfuncs = (uint32_t)cp.funcs.size();
+  T->ticket_base = 0;
+  T->skip_acc0 = 0;
+  T->skip0 = 0;
+  T->phase0 = 0;
+}
+
+bool mostly_short_rows(const ClassPlan &cp) {
+  uint64_t short_bytes = 0;
+  for (const Xfer &x : cp.xfers)
+    if (x.rows > 1 && x.row_bytes <= 2048) short_bytes += x.row_bytes * x.rows;
+  return 2 * short_bytes > cp.payload;
 }
 
 // Launch shape when the caller has not tuned it.
@@ -262,7 +187,7 @@ int run_dma(ft_pool *p, const ClassPlan &cp, uint64_t C, int cls, hipStream_t st
   for (uint64_t rank = 0; rank < cp.nchunks; ++rank) {
     const ChunkId id = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(), rank);
     const Func &fn = cp.funcs[id.fl];
-    uint64_t pos = id.k * C;
+    uint64_t pos = (fn.chunk_base + id.k) * C;
     uint64_t end = pos + C < fn.stream_bytes ? pos + C : fn.stream_bytes;
     uint32_t x = find_xfer(cp.xfers.data(), fn.desc_off, fn.desc_off + fn.ndesc - 1, pos);
     while (pos < end) {
@@ -340,7 +265,9 @@ int wait_locked(ft_pool *p, Job *job) {
   return FT_OK;
 }
 
-}  // namespace
+}  // namespace ft
+
+using namespace ft;
 
 extern "C" {
 
@@ -369,10 +296,15 @@ int ft_pool_destroy(ft_pool *p) {
     DeviceGuard guard(p->device);
     for (auto &kv : p->jobs) {
       Job *job = kv.second.get();
-      if (!job->waited && wait_locked(p, job) != FT_OK) rc = FT_EHIP;
+      if (job->open) {
+        if (open_wait(p, job->open, job->id) != FT_OK) rc = FT_EHIP;
+        retire(p, job);
+      } else if (!job->waited && wait_locked(p, job) != FT_OK) {
+        rc = FT_EHIP;
+      }
       release_device_side(p, job);
     }
-    p->jobs.clear();
+    p->jobs.clear();  // the last job of an open sequence joins its feeder threads here
   }
   delete p;
   return rc;
@@ -421,14 +353,26 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
   int rc = plan_submit(p->slabs, p->windows, descs, ndesc, weights, nfunc, chunk_bytes, flags, &plan);
   if (rc != FT_OK) return rc;
 
+  if ((flags & FT_OPEN) && (flags & (FT_LOG | FT_PATH_DMA))) return FT_EINVAL;
   std::unique_ptr<Job> job(new Job());
   job->flags = flags;
   job->keep = (flags & (FT_KEEP | FT_LOG | FT_TIMING)) != 0;
   job->chunk_bytes = chunk_bytes;
+  job->id = p->next_job;
   bool any = false;
-  for (int c = 0; c < FT_NCLASS; ++c) any = any || plan.cls[c].nchunks > 0;
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    any = any || plan.cls[c].nchunks > 0;
+    job->class_payload[c] = plan.cls[c].payload;
+    job->class_chunks[c] = plan.cls[c].nchunks;
+  }
 
-  if (any) {
+  if (any && (flags & FT_OPEN)) {
+    DeviceGuard guard(p->device);
+    rc = ensure_device(p);
+    if (rc != FT_OK) return rc;
+    rc = open_submit(p, job.get(), plan, weights, chunk_bytes, static_cast<hipStream_t>(hip_stream));
+    if (rc != FT_OK) return rc;
+  } else if (any) {
     DeviceGuard guard(p->device);
     rc = ensure_device(p);
     if (rc != FT_OK) return rc;
@@ -440,7 +384,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
     Layout lay[FT_NCLASS];
     uint64_t total = 0;
     for (int c = 0; c < FT_NCLASS; ++c) {
-      lay[c] = layout_of(plan.cls[c], total);
+      lay[c] = layout_of(plan.cls[c], total, 1);
       if (plan.cls[c].nchunks > 0) total = lay[c].end;
     }
     // every failure from here on must hand back what it took
@@ -459,38 +403,18 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       ClassRun &r = job->run[c];
       r.used = true;
       char *h = job->tables.host, *d = job->tables.dev;
-      std::memcpy(h + lay[c].phases, cp.phases.data(), cp.phases.size() * sizeof(Phase));
-      std::memcpy(h + lay[c].slots, cp.slots.data(), cp.slots.size() * sizeof(Slot));
-      std::memcpy(h + lay[c].funcs, cp.funcs.data(), cp.funcs.size() * sizeof(Func));
-      std::memcpy(h + lay[c].xfers, cp.xfers.data(), cp.xfers.size() * sizeof(Xfer));
-      std::memcpy(h + lay[c].chunks, cp.chunk_desc.data(), cp.chunk_desc.size() * sizeof(uint32_t));
       const Tuning &tn = p->tuning[c];
       const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
-      uint64_t short_bytes = 0;
-      for (const Xfer &x : cp.xfers)
-        if (x.rows > 1 && x.row_bytes <= 2048) short_bytes += x.row_bytes * x.rows;
-      const bool short_rows = 2 * short_bytes > cp.payload;
-      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, short_rows),
+      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
                  &r.tile_bytes, &r.tiles_per_chunk);
       ClassTable &T = r.table;
-      T.phases = reinterpret_cast<const Phase *>(d + lay[c].phases);
-      T.slots = reinterpret_cast<const Slot *>(d + lay[c].slots);
-      T.funcs = reinterpret_cast<const Func *>(d + lay[c].funcs);
-      T.xfers = reinterpret_cast<const Xfer *>(d + lay[c].xfers);
-      T.chunk_desc = cp.chunk_desc.empty() ? nullptr : reinterpret_cast<const uint32_t *>(d + lay[c].chunks);
-      T.ticket = reinterpret_cast<unsigned long long *>(d + lay[c].ticket);
-      T.log = nullptr;
-      T.wg_log = nullptr;
+      fill_tables(cp, lay[c], h, d, &T);
       build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &T.ntickets);
       std::memcpy(h + lay[c].skips, r.skips.data(), r.skips.size() * sizeof(Skip));
-      T.skips = reinterpret_cast<const Skip *>(d + lay[c].skips);
       T.nskips = (uint32_t)r.skips.size();
-      T.nchunks = cp.nchunks;
       T.chunk_bytes = chunk_bytes;
       T.tile_bytes = r.tile_bytes;
       T.tiles_per_chunk = r.tiles_per_chunk;
-      T.nphases = (uint32_t)cp.phases.size();
-      T.nfuncs = (uint32_t)cp.funcs.size();
       uint64_t wg = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
       if (wg > T.ntickets) wg = T.ntickets;
       r.workgroups = dma ? 0 : (uint32_t)wg;
@@ -559,7 +483,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
     if (al) al->busy += 1;
   }
   job->allocs = plan.allocs;
-  job->id = p->next_job++;
+  p->next_job += 1;
   *job_out = job->id;
   job->host_submit_us =
       std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
@@ -567,13 +491,76 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
   return FT_OK;
 }
 
+int ft_submit_merge(ft_pool *p, ft_job_t open_id, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
+                    uint32_t nfunc, uint32_t flags, void *hip_stream, ft_job_t *job_out) {
+  if (p == nullptr || job_out == nullptr) return FT_EINVAL;
+  if (flags & ~(uint32_t)(FT_VALIDATE | FT_KEEP)) return FT_EINVAL;
+  const auto t0 = std::chrono::steady_clock::now();
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(open_id);
+  if (it == p->jobs.end() || !it->second->open || !(it->second->flags & FT_OPEN)) return FT_EINVAL;
+  Job *open_job = it->second.get();
+  SubmitPlan plan;
+  int rc = plan_submit(p->slabs, p->windows, descs, ndesc, weights, nfunc, open_job->chunk_bytes, flags, &plan);
+  if (rc != FT_OK) return rc;
+  std::unique_ptr<Job> job(new Job());
+  job->flags = flags | FT_DETACHED;
+  job->keep = (flags & FT_KEEP) != 0;
+  job->chunk_bytes = open_job->chunk_bytes;
+  job->id = p->next_job;
+  bool any = false;
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    any = any || plan.cls[c].nchunks > 0;
+    job->class_payload[c] = plan.cls[c].payload;
+    job->class_chunks[c] = plan.cls[c].nchunks;
+  }
+  if (any) {
+    DeviceGuard guard(p->device);
+    rc = open_merge(p, open_job, job.get(), plan, weights, static_cast<hipStream_t>(hip_stream));
+    if (rc != FT_OK) return rc;
+  }
+  for (uint64_t a : plan.allocs) {
+    Allocation *al = p->slabs.at(a);
+    if (al) al->busy += 1;
+  }
+  job->allocs = plan.allocs;
+  p->next_job += 1;
+  *job_out = job->id;
+  job->host_submit_us =
+      std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+  p->jobs[job->id] = std::move(job);
+  return FT_OK;
+}
+
+int ft_set_batch(ft_pool *p, uint32_t batch_chunks, uint32_t depth) {
+  if (p == nullptr || batch_chunks == 0 || depth == 0) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  p->batch_chunks = batch_chunks;
+  p->batch_depth = depth;
+  return FT_OK;
+}
+
 int ft_wait(ft_pool *p, ft_job_t id) {
   if (p == nullptr) return FT_EINVAL;
-  std::lock_guard<std::mutex> lock(p->mu);
+  std::unique_lock<std::mutex> lock(p->mu);
   auto it = p->jobs.find(id);
   if (it == p->jobs.end() || it->second->waited) return FT_EINVAL;
   Job *job = it->second.get();
-  int rc = wait_locked(p, job);
+  int rc;
+  if (job->open) {
+    // the feeder threads never take the pool's mutex; other callers (a merge) must get in
+    std::shared_ptr<OpenState> st = job->open;
+    job->waited = true;  // a second ft_wait on the same job is refused while this one blocks
+    lock.unlock();
+    rc = open_wait(p, st, id);
+    lock.lock();
+    it = p->jobs.find(id);
+    if (it == p->jobs.end()) return FT_EINVAL;
+    job = it->second.get();
+    retire(p, job);
+  } else {
+    rc = wait_locked(p, job);
+  }
   if (rc != FT_OK) return rc;
   if (!job->keep) {
     release_device_side(p, job);
@@ -602,12 +589,17 @@ int ft_job_stats(ft_pool *p, ft_job_t id, ft_job_stats_t *out) {
   for (int c = 0; c < FT_NCLASS; ++c) {
     const ClassRun &r = job->run[c];
     ft_class_stats &s = out->cls[c];
-    s.payload_bytes = r.plan.payload;
-    s.chunks = r.plan.nchunks;
+    s.payload_bytes = job->class_payload[c];
+    s.chunks = job->class_chunks[c];
     s.tickets = r.used ? r.table.ntickets : 0;
     s.tile_bytes = r.tile_bytes;
     s.workgroups = r.workgroups;
     s.device_ms = r.device_ms;
+    if (job->open && (job->flags & FT_OPEN)) {
+      // the whole sequence so far, merged jobs included: tickets and kernel time of all batches
+      uint64_t batches = 0;
+      open_stats(job->open, c, &s.tickets, &s.tile_bytes, &s.workgroups, &s.device_ms, &batches);
+    }
   }
   out->host_submit_us = job->host_submit_us;
   return FT_OK;
@@ -663,11 +655,12 @@ int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, ui
       const Func &fn = cp.funcs[cid.fl];
       uint64_t lo = ti * r.tile_bytes, hi = lo + r.tile_bytes;
       if (hi > job->chunk_bytes) hi = job->chunk_bytes;
-      uint64_t b0 = cid.k * job->chunk_bytes + lo, b1 = cid.k * job->chunk_bytes + hi;
+      const uint64_t kabs = fn.chunk_base + cid.k;
+      uint64_t b0 = kabs * job->chunk_bytes + lo, b1 = kabs * job->chunk_bytes + hi;
       if (b1 > fn.stream_bytes) b1 = fn.stream_bytes;
       if (b0 > b1) b0 = b1;
       if (func_out) func_out[t] = fn.func;
-      if (chunk_out) chunk_out[t] = (uint32_t)cid.k;
+      if (chunk_out) chunk_out[t] = (uint32_t)kabs;
       if (bytes_out) bytes_out[t] = (uint32_t)(b1 - b0);
     }
   }
@@ -688,6 +681,63 @@ int ft_job_log_workgroups(ft_pool *p, ft_job_t id, int link_class, uint32_t *tic
   for (uint32_t w = 0; w < r.wg_log_host.size() && w < wg_cap; ++w) {
     if (wg_entry_ns) wg_entry_ns[w] = (uint64_t)(r.wg_log_host[w].t_entry * ns_per_tick);
     if (wg_exit_ns) wg_exit_ns[w] = (uint64_t)(r.wg_log_host[w].t_exit * ns_per_tick);
+  }
+  return FT_OK;
+}
+
+int ft_job_arrival(ft_pool *p, ft_job_t id, int link_class, uint64_t *batch_out) {
+  if (p == nullptr || batch_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->open) return FT_EINVAL;
+  return open_arrival(it->second->open, id, link_class, batch_out);
+}
+
+int ft_job_batches(ft_pool *p, ft_job_t id, int link_class, uint64_t *job_out, uint32_t *func_out,
+                   uint32_t *chunk_out, uint32_t *batch_out, uint64_t cap, uint64_t *n_out) {
+  if (p == nullptr || n_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
+  if (cap != 0 && (job_out == nullptr || func_out == nullptr || chunk_out == nullptr || batch_out == nullptr))
+    return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->open || !(it->second->flags & FT_OPEN) ||
+      !(it->second->flags & FT_KEEP))
+    return FT_EINVAL;
+  *n_out = open_order(it->second->open, link_class, job_out, func_out, chunk_out, batch_out, cap);
+  return FT_OK;
+}
+
+int ft_slo_weights(const double *data_size, const double *l_slo, const double *l_infer, uint32_t n,
+                   double bw_all, uint32_t total, double *rate_out, uint32_t *weights_out) {
+  if (data_size == nullptr || l_slo == nullptr || l_infer == nullptr || weights_out == nullptr || n == 0)
+    return FT_EINVAL;
+  if (!(bw_all > 0.0)) return FT_EINVAL;
+  if (total == 0) total = 64;
+  std::vector<double> rate(n);
+  double sum = 0.0;
+  for (uint32_t i = 0; i < n; ++i) {
+    const double slack = l_slo[i] - l_infer[i];
+    if (!(slack > 0.0) || data_size[i] < 0.0) return FT_EINVAL;
+    rate[i] = data_size[i] / slack;
+    sum = sum + rate[i];
+  }
+  const double idle = bw_all - sum;
+  if (idle > 0.0) {
+    uint32_t tight = 0;
+    for (uint32_t i = 1; i < n; ++i)
+      if (l_slo[i] - l_infer[i] < l_slo[tight] - l_infer[tight]) tight = i;
+    rate[tight] = rate[tight] + idle;
+  }
+  double s = 0.0;
+  for (uint32_t i = 0; i < n; ++i) s = s + rate[i];
+  for (uint32_t i = 0; i < n; ++i) {
+    if (rate_out) rate_out[i] = rate[i];
+    if (!(s > 0.0)) {
+      weights_out[i] = 1;
+      continue;
+    }
+    const double w = std::floor(rate[i] / s * (double)total + 0.5);
+    weights_out[i] = w >= 1.0 ? (w > 4294967295.0 ? 4294967295u : (uint32_t)w) : 1u;
   }
   return FT_OK;
 }
@@ -784,6 +834,7 @@ const char *ft_strerror(int rc) {
     case FT_EOVERLAP: return "a destination byte is written twice or also read";
     case FT_EBUSY: return "allocation is in use by a job that has not been waited for";
     case FT_EHIP: return "HIP runtime error";
+    case FT_ECLOSED: return "the open job has triggered its last batch";
     default: return "unknown code";
   }
 }

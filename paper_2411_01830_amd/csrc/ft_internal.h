@@ -1,0 +1,159 @@
+// Internals shared by the translation units of the library (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <memory>
+#include <mutex>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/faastube.h"
+#include "ft_kernels.h"
+#include "ft_plan.h"
+#include "ft_pool.h"
+#include "ft_tables.h"
+
+namespace ft {
+
+struct OpenState;  // ft_open.cpp: a job that triggers its chunks in batches and accepts merges
+
+// A device buffer with a pinned host twin of the same size; recycled between jobs so
+// that a steady stream of submits allocates nothing.
+struct Blob {
+  char *dev = nullptr;
+  char *host = nullptr;  // null for device-only blobs
+  uint64_t cap = 0;
+};
+
+struct ClassRun {
+  bool used = false;
+  ClassTable table{};       // device addresses
+  ClassPlan plan;           // host copy (DMA path, log decoding, stats)
+  uint64_t tile_bytes = 0;
+  uint32_t tiles_per_chunk = 0;
+  uint32_t workgroups = 0;
+  // ev_done orders the caller's stream and ft_wait after the class's work. With FT_TIMING,
+  // ev_begin / ev_end bracket it: bound to the kernel's dispatch on the kernel path,
+  // recorded around the copy calls on the DMA path.
+  hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_done = nullptr;
+  Blob log;
+  std::vector<Skip> skips;
+  std::vector<LogEntry> log_host;
+  std::vector<WgLogEntry> wg_log_host;
+  float device_ms = -1.f;
+};
+
+struct Job {
+  uint64_t id = 0;
+  uint32_t flags = 0;
+  bool keep = false;
+  bool waited = false;
+  ClassRun run[FT_NCLASS];
+  Blob tables;
+  std::vector<uint64_t> allocs;
+  uint64_t chunk_bytes = 0;
+  double host_submit_us = 0;
+  std::shared_ptr<OpenState> open;  // set for a job submitted with FT_OPEN or merged into one
+  uint64_t class_payload[FT_NCLASS] = {0, 0, 0};
+  uint64_t class_chunks[FT_NCLASS] = {0, 0, 0};
+};
+
+struct Tuning {
+  uint32_t workgroups = 0;
+  uint64_t tile_bytes = 0;
+};
+
+// Per-device resources shared by every pool on that device and kept for the life of
+// the process: one stream per link class (so the three classes sit on three hardware
+// queues and really run side by side), recycled table buffers and events. Creating a
+// pool therefore costs no HIP call, and a steady stream of submits allocates nothing.
+struct DeviceCtx {
+  std::mutex mu;
+  int device = 0;
+  bool ready = false;
+  int cu_count = 0;
+  int clock_khz = 0;
+  hipStream_t streams[FT_NCLASS] = {nullptr, nullptr, nullptr};
+  std::vector<Blob> free_blobs;      // with a pinned twin
+  std::vector<Blob> free_dev_blobs;  // device only
+  std::vector<hipEvent_t> free_events, free_timing_events;
+};
+
+DeviceCtx *device_ctx(int device);
+
+}  // namespace ft
+
+struct ft_pool {
+  std::mutex mu;
+  ft::SlabPool slabs;
+  int device;
+  std::vector<ft::HostWindow> windows;
+  ft::DeviceCtx *ctx;
+  std::unordered_map<uint64_t, std::unique_ptr<ft::Job>> jobs;
+  uint64_t next_job = 1;
+  ft::Tuning tuning[FT_NCLASS];
+  uint32_t batch_chunks = 5;  // chunks per triggered batch of an open job (Sec. 6.1 default)
+  uint32_t batch_depth = 2;   // batches an open job keeps queued ahead of the device
+  std::string hip_error;
+
+  ft_pool(uint64_t slab_bytes, int dev) : slabs(slab_bytes), device(dev), ctx(ft::device_ctx(dev)) {}
+};
+
+namespace ft {
+
+#define FT_HIP(p, call)                                                        \
+  do {                                                                         \
+    hipError_t e_ = (call);                                                    \
+    if (e_ != hipSuccess) {                                                    \
+      (p)->hip_error = std::string(#call) + ": " + hipGetErrorString(e_);      \
+      return FT_EHIP;                                                          \
+    }                                                                          \
+  } while (0)
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) == hipSuccess && prev != dev) ok = hipSetDevice(dev) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (ok) (void)hipSetDevice(prev);
+  }
+};
+
+
+int ensure_device(ft_pool *p);
+int get_blob(ft_pool *p, uint64_t need, bool pinned_twin, Blob *out);
+void put_blob(ft_pool *p, Blob &b);
+int get_event(ft_pool *p, bool timing, hipEvent_t *out);
+void put_event(ft_pool *p, bool timing, hipEvent_t &e);
+uint64_t align_up(uint64_t v, uint64_t a);
+
+// Byte layout of one class's tables inside a table blob.
+struct Layout {
+  uint64_t ticket, phases, slots, funcs, xfers, chunks, skips, end;
+};
+// nbatches: ticket counters to reserve (one per launch that will use these tables)
+Layout layout_of(const ClassPlan &cp, uint64_t base, uint64_t ncounters = 1);
+// Copies the plan's tables into the host twin at `h` and fills the device pointers of T.
+void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, ClassTable *T);
+
+uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p);
+uint64_t default_tile(int cls, bool with_p2p, bool short_rows);
+bool mostly_short_rows(const ClassPlan &cp);
+
+// ft_open.cpp. All but open_wait are called with the pool's mutex held and the pool's
+// device current; open_wait blocks and must be called without the pool's mutex.
+int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights, uint64_t chunk_bytes,
+                hipStream_t user);
+int open_merge(ft_pool *p, Job *open_job, Job *job, SubmitPlan &plan, const uint32_t *weights,
+               hipStream_t user);
+int open_wait(ft_pool *p, const std::shared_ptr<OpenState> &st, uint64_t job_id);
+void open_stats(const std::shared_ptr<OpenState> &st, int c, uint64_t *tickets, uint64_t *tile_bytes,
+                uint32_t *workgroups, float *kernel_ms, uint64_t *batches);
+int open_arrival(const std::shared_ptr<OpenState> &st, uint64_t job_id, int c, uint64_t *batch);
+uint64_t open_order(const std::shared_ptr<OpenState> &st, int c, uint64_t *job_out, uint32_t *func_out,
+                    uint32_t *chunk_out, uint32_t *batch_out, uint64_t cap);
+
+}  // namespace ft

@@ -548,7 +548,7 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
     x0 = CT.funcs[fl].desc_off;
     x1 = x0 + CT.funcs[fl].ndesc - 1;
   }
-  const uint64_t c0 = k * T.chunk_bytes;
+  const uint64_t c0 = (CT.funcs[fl].chunk_base + k) * T.chunk_bytes;
   uint64_t lo = ti * T.tile_bytes, hi = lo + T.tile_bytes;
   if (hi > T.chunk_bytes) hi = T.chunk_bytes;
   uint64_t b0 = c0 + lo, b1 = c0 + hi;
@@ -618,13 +618,13 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
   PhaseCursor pc;
   SkipCursor sc;
   if (lead) {
-    cursor_set(pc, CT.phases, T.nphases, 0);
-    sc.idx = 0;
-    sc.acc = 0;
-    sc.next_at = T.nskips ? CT.skips[0].at : ~0ull;
+    cursor_set(pc, CT.phases, T.nphases, T.phase0);
+    sc.idx = T.skip0;
+    sc.acc = T.skip_acc0;
+    sc.next_at = T.skip0 < T.nskips ? CT.skips[T.skip0].at : ~0ull;
     unsigned long long first = 0;
     if (tid == 0) first = atomicAdd(T.ticket, 1ull);
-    const uint64_t t_first = uniform64(first);
+    const uint64_t t_first = T.ticket_base + uniform64(first);
     const Work w = decode_ticket(T, CT, pc, sc, t_first);
     if (tid == 0) put_work(s_work[0], t_first, w);
   }
@@ -663,7 +663,7 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
     }
     if (lead) {
       // lane 0 holds the counter's answer; all 64 lanes of this wavefront are enabled
-      const uint64_t t_next = uniform64(claimed);
+      const uint64_t t_next = T.ticket_base + uniform64(claimed);
       const Work next = decode_ticket(T, CT, pc, sc, t_next);
       if (tid == 0) put_work(s_work[slot ^ 1], t_next, next);
     }
@@ -690,7 +690,7 @@ __global__ void ft_decode_kernel(ClassTable T, uint32_t *func_out, uint32_t *chu
   const ConstTables CT = const_tables(T);
   const ChunkId id = decode_rank(CT.phases, T.nphases, CT.slots, rank);
   func_out[rank] = CT.funcs[id.fl].func;
-  chunk_out[rank] = (uint32_t)id.k;
+  chunk_out[rank] = (uint32_t)(CT.funcs[id.fl].chunk_base + id.k);
 }
 
 __global__ __launch_bounds__(kThreads) void ft_plain_copy_kernel(u32x4 *dst, const u32x4 *src, uint64_t nvec) {

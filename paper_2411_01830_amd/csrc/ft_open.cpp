@@ -1,0 +1,444 @@
+// Open jobs: batched transfer triggering of Sec. 6.1.
+//
+// A chunk that has been handed to the device cannot be taken back, so a job whose whole
+// order is launched at once leaves later arrivals waiting until it is done. An open job
+// instead triggers its chunks in batches (5 chunks by default, as in the paper): one
+// launch of the persistent copy kernel per batch, a small fixed number of batches queued
+// ahead of the device, launched by a feeder thread per link class. Functions that arrive
+// meanwhile (ft_submit_merge) join at the next batch that has not been triggered: the
+// proportional order is built afresh over the chunks not yet triggered of every earlier
+// function plus all chunks of the new ones, earlier functions first in the tie rule, and
+// the following batches come from that order. Each order in force has its own tables on
+// the device ("generation"); batches already queued keep the tables they were launched
+// with.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <condition_variable>
+#include <cstring>
+#include <deque>
+#include <thread>
+
+#include "ft_internal.h"
+
+namespace ft {
+
+namespace {
+
+struct OpenFn {
+  uint64_t job;           // pool job id
+  uint32_t func;          // function index inside that job
+  uint32_t weight;
+  uint64_t stream_bytes;
+  uint64_t nchunks;       // of the whole stream
+  uint64_t next_chunk;    // first chunk not yet triggered
+  std::vector<Xfer> xfers;
+};
+
+struct Generation {
+  ClassPlan plan;                   // plan.funcs[i].func = index into OpenClass::fns
+  std::vector<Skip> skips;
+  Blob blob;
+  ClassTable table{};               // device addresses; per batch: counter, range, cursors
+  uint64_t ntickets = 0;
+  uint64_t next_rank = 0;           // first rank of this order not yet triggered
+  uint32_t next_counter = 0;
+  uint32_t inflight = 0;            // batches launched with these tables and not seen complete
+  hipEvent_t uploaded = nullptr;    // the class's stream waits for it before the first batch
+  bool waited_upload = false;
+};
+
+struct OpenBatch {
+  std::shared_ptr<Generation> gen;
+  hipEvent_t done = nullptr, t_begin = nullptr, t_end = nullptr;
+  std::vector<std::pair<uint64_t, uint64_t>> job_chunks;  // job id, chunks of it in this batch
+};
+
+struct BatchRec {
+  uint64_t job;
+  uint32_t func;
+  uint32_t chunk;
+  uint32_t batch;
+};
+
+struct OpenClass {
+  bool used = false;
+  bool closed = false;              // ran dry: no batch left to trigger, feeder gone
+  std::vector<OpenFn> fns;
+  std::shared_ptr<Generation> gen;  // the order in force
+  std::deque<OpenBatch> inflight;
+  uint64_t batches_triggered = 0;
+  uint64_t tile_bytes = 0;
+  uint32_t tiles_per_chunk = 0;
+  uint32_t workgroups = 0;
+  uint64_t tickets = 0;
+  double kernel_ms = 0;
+  std::vector<BatchRec> order;
+  std::thread feeder;
+};
+
+}  // namespace
+
+struct OpenState {
+  std::mutex mu;
+  std::condition_variable cv;
+  ft_pool *pool = nullptr;
+  uint64_t chunk_bytes = 0;
+  uint32_t batch_chunks = 5;
+  uint32_t depth = 2;               // batches queued ahead of the device
+  uint32_t flags = 0;
+  OpenClass cls[FT_NCLASS];
+  std::unordered_map<uint64_t, uint64_t> left;      // job id -> chunks not yet complete
+  std::unordered_map<uint64_t, uint64_t> arrival;   // job id << 2 | class -> batches triggered when it joined
+  int error = FT_OK;
+  std::string error_text;
+
+  ~OpenState() {
+    for (OpenClass &c : cls)
+      if (c.feeder.joinable()) c.feeder.join();
+  }
+};
+
+namespace {
+
+void set_error(OpenState *st, hipError_t e, const char *what) {
+  if (st->error == FT_OK) {
+    st->error = FT_EHIP;
+    st->error_text = std::string(what) + ": " + hipGetErrorString(e);
+  }
+}
+
+// First ticket of chunk rank r in the generation's numbering, and where the empty-tile
+// cursor stands there.
+void ticket_of_rank(const Generation &g, uint32_t tpc, uint64_t rank, uint64_t *ticket, uint32_t *skip_idx,
+                    uint64_t *skip_acc) {
+  uint64_t t = rank * tpc, acc = 0;
+  uint32_t j = 0;
+  // run j starts inside a chunk of rank (at_j + acc_j) / tpc; it lies before `rank` iff that is smaller
+  while (j < g.skips.size() && (g.skips[j].at + acc) / tpc < rank) {
+    acc += g.skips[j].gap;
+    ++j;
+  }
+  *ticket = t - acc;
+  *skip_idx = j;
+  *skip_acc = acc;
+}
+
+// Tables of the order over everything not yet triggered; uploaded on `user`.
+int build_generation(ft_pool *p, OpenState *st, int c, hipStream_t user, std::shared_ptr<Generation> *out) {
+  OpenClass &oc = st->cls[c];
+  std::shared_ptr<Generation> g(new Generation());
+  ClassPlan &cp = g->plan;
+  for (uint32_t i = 0; i < oc.fns.size(); ++i) {
+    const OpenFn &fn = oc.fns[i];
+    if (fn.next_chunk >= fn.nchunks) continue;
+    Func f{};
+    f.stream_bytes = fn.stream_bytes;
+    f.nchunks = fn.nchunks - fn.next_chunk;
+    f.func = i;
+    f.weight = fn.weight;
+    f.desc_off = (uint32_t)cp.xfers.size();
+    f.ndesc = (uint32_t)fn.xfers.size();
+    f.chunk_base = fn.next_chunk;
+    cp.xfers.insert(cp.xfers.end(), fn.xfers.begin(), fn.xfers.end());
+    cp.payload += fn.stream_bytes;
+    cp.funcs.push_back(f);
+  }
+  int rc = build_phases(cp.funcs, cp.phases, cp.slots, &cp.nchunks);
+  if (rc != FT_OK) return rc;
+  build_chunk_table(cp, st->chunk_bytes);
+  build_skips(cp, st->chunk_bytes, oc.tile_bytes, oc.tiles_per_chunk, &g->skips, &g->ntickets);
+  const uint64_t ncounters = (cp.nchunks + st->batch_chunks - 1) / st->batch_chunks;
+  const Layout lay = layout_of(cp, 0, ncounters);
+  rc = get_blob(p, lay.end, true, &g->blob);
+  if (rc != FT_OK) return rc;
+  std::memset(g->blob.host, 0, lay.end);
+  fill_tables(cp, lay, g->blob.host, g->blob.dev, &g->table);
+  std::memcpy(g->blob.host + lay.skips, g->skips.data(), g->skips.size() * sizeof(Skip));
+  g->table.nskips = (uint32_t)g->skips.size();
+  g->table.chunk_bytes = st->chunk_bytes;
+  g->table.tile_bytes = oc.tile_bytes;
+  g->table.tiles_per_chunk = oc.tiles_per_chunk;
+  rc = get_event(p, false, &g->uploaded);
+  if (rc != FT_OK) {
+    put_blob(p, g->blob);
+    return rc;
+  }
+  hipError_t e = hipMemcpyAsync(g->blob.dev, g->blob.host, lay.end, hipMemcpyHostToDevice, user);
+  if (e == hipSuccess) e = hipEventRecord(g->uploaded, user);
+  if (e != hipSuccess) {
+    // the copy may have been queued: drain before the buffers are recycled
+    (void)hipStreamSynchronize(user);
+    put_event(p, false, g->uploaded);
+    put_blob(p, g->blob);
+    p->hip_error = std::string("open job table upload: ") + hipGetErrorString(e);
+    return FT_EHIP;
+  }
+  *out = g;
+  return FT_OK;
+}
+
+void drop_generation(ft_pool *p, Generation *g) {
+  put_event(p, false, g->uploaded);
+  put_blob(p, g->blob);
+}
+
+// Triggers the next batch of class c. Called with st->mu held, on the pool's device.
+bool launch_batch(OpenState *st, int c) {
+  ft_pool *p = st->pool;
+  OpenClass &oc = st->cls[c];
+  Generation &g = *oc.gen;
+  const ClassPlan &cp = g.plan;
+  const uint64_t r0 = g.next_rank;
+  const uint64_t r1 = std::min<uint64_t>(r0 + st->batch_chunks, cp.nchunks);
+  ClassTable T = g.table;
+  uint64_t t0, t1, acc1;
+  uint32_t idx1;
+  ticket_of_rank(g, oc.tiles_per_chunk, r0, &t0, &T.skip0, &T.skip_acc0);
+  if (r1 == cp.nchunks) t1 = g.ntickets;
+  else ticket_of_rank(g, oc.tiles_per_chunk, r1, &t1, &idx1, &acc1);
+  T.ticket_base = t0;
+  T.ntickets = t1;
+  T.ticket = g.table.ticket + g.next_counter;
+  {
+    uint32_t lo = 0, hi = (uint32_t)cp.phases.size();
+    while (hi - lo > 1) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (cp.phases[mid].rank_base <= r0) lo = mid; else hi = mid;
+    }
+    T.phase0 = lo;
+  }
+  OpenBatch b;
+  b.gen = oc.gen;
+  const bool timing = (st->flags & FT_TIMING) != 0;
+  if (get_event(p, false, &b.done) != FT_OK || (timing && (get_event(p, true, &b.t_begin) != FT_OK ||
+                                                           get_event(p, true, &b.t_end) != FT_OK))) {
+    if (st->error == FT_OK) st->error = FT_EHIP, st->error_text = p->hip_error;
+    return false;
+  }
+  hipStream_t s = p->ctx->streams[c];
+  hipError_t e = hipSuccess;
+  if (!g.waited_upload) {
+    e = hipStreamWaitEvent(s, g.uploaded, 0);
+    g.waited_upload = true;
+  }
+  uint64_t wg = oc.workgroups;
+  if (wg > t1 - t0) wg = t1 - t0;
+  if (e == hipSuccess) e = launch_copy(T, c, (uint32_t)wg, s, b.t_begin, b.t_end);
+  if (e == hipSuccess) e = hipEventRecord(b.done, s);
+  if (e != hipSuccess) {
+    set_error(st, e, "open job batch launch");
+    put_event(p, false, b.done);
+    put_event(p, true, b.t_begin);
+    put_event(p, true, b.t_end);
+    return false;
+  }
+  // what the batch holds, on the host: advances every function's count of triggered chunks
+  const uint32_t batch_no = (uint32_t)oc.batches_triggered;
+  for (uint64_t r = r0; r < r1; ++r) {
+    const ChunkId id = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(), r);
+    const Func &f = cp.funcs[id.fl];
+    OpenFn &fn = oc.fns[f.func];
+    const uint64_t k = f.chunk_base + id.k;
+    fn.next_chunk = k + 1;
+    bool found = false;
+    for (auto &jc : b.job_chunks)
+      if (jc.first == fn.job) jc.second += 1, found = true;
+    if (!found) b.job_chunks.push_back({fn.job, 1});
+    if (st->flags & FT_KEEP) oc.order.push_back(BatchRec{fn.job, fn.func, (uint32_t)k, batch_no});
+  }
+  g.next_rank = r1;
+  g.next_counter += 1;
+  g.inflight += 1;
+  oc.tickets += t1 - t0;
+  oc.batches_triggered += 1;
+  oc.inflight.push_back(std::move(b));
+  return true;
+}
+
+void feeder_main(OpenState *st, int c) {
+  ft_pool *p = st->pool;
+  (void)hipSetDevice(p->device);
+  OpenClass &oc = st->cls[c];
+  std::unique_lock<std::mutex> lock(st->mu);
+  for (;;) {
+    while (st->error == FT_OK && oc.inflight.size() < st->depth && oc.gen->next_rank < oc.gen->plan.nchunks)
+      if (!launch_batch(st, c)) break;
+    if (oc.inflight.empty()) {
+      // dry (or failed): later arrivals start a sequence of their own
+      oc.closed = true;
+      drop_generation(p, oc.gen.get());
+      // chunks that will never be triggered count as done so that no waiter hangs
+      if (st->error != FT_OK) {
+        for (auto &kv : st->left) kv.second = 0;
+      }
+      st->cv.notify_all();
+      return;
+    }
+    OpenBatch b = std::move(oc.inflight.front());
+    oc.inflight.pop_front();
+    lock.unlock();
+    hipError_t e = hipEventSynchronize(b.done);
+    float ms = 0;
+    if (e == hipSuccess && b.t_begin != nullptr) e = hipEventElapsedTime(&ms, b.t_begin, b.t_end);
+    lock.lock();
+    if (e != hipSuccess) set_error(st, e, "open job batch");
+    oc.kernel_ms += ms;
+    put_event(p, false, b.done);
+    put_event(p, true, b.t_begin);
+    put_event(p, true, b.t_end);
+    b.gen->inflight -= 1;
+    if (b.gen->inflight == 0 && b.gen != oc.gen) drop_generation(p, b.gen.get());
+    for (auto &jc : b.job_chunks) {
+      auto it = st->left.find(jc.first);
+      if (it != st->left.end()) it->second = it->second > jc.second ? it->second - jc.second : 0;
+    }
+    st->cv.notify_all();
+  }
+}
+
+void add_functions(OpenClass &oc, uint64_t job_id, const ClassPlan &cp, uint64_t chunk_bytes) {
+  for (const Func &f : cp.funcs) {
+    OpenFn fn;
+    fn.job = job_id;
+    fn.func = f.func;
+    fn.weight = f.weight;  // divided by the gcd of its own job's weights: ratios inside a job are kept;
+    fn.stream_bytes = f.stream_bytes;
+    fn.nchunks = f.nchunks;
+    fn.next_chunk = 0;
+    fn.xfers.assign(cp.xfers.begin() + f.desc_off, cp.xfers.begin() + f.desc_off + f.ndesc);
+    oc.fns.push_back(std::move(fn));
+  }
+  (void)chunk_bytes;
+}
+
+}  // namespace
+
+int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights, uint64_t chunk_bytes,
+                hipStream_t user) {
+  std::shared_ptr<OpenState> st(new OpenState());
+  st->pool = p;
+  st->chunk_bytes = chunk_bytes;
+  st->batch_chunks = p->batch_chunks ? p->batch_chunks : 5;
+  st->depth = p->batch_depth ? p->batch_depth : 2;
+  st->flags = job->flags;
+  uint64_t chunks = 0;
+  const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
+  std::unique_lock<std::mutex> lock(st->mu);
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    ClassPlan &cp = plan.cls[c];
+    if (cp.nchunks == 0) continue;
+    OpenClass &oc = st->cls[c];
+    oc.used = true;
+    // the caller's weights, not the gcd-reduced ones: functions of later jobs are weighed against them
+    for (Func &f : cp.funcs) f.weight = weights[f.func];
+    add_functions(oc, job->id, cp, chunk_bytes);
+    const Tuning &tn = p->tuning[c];
+    tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
+               &oc.tile_bytes, &oc.tiles_per_chunk);
+    oc.workgroups = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
+    int rc = build_generation(p, st.get(), c, user, &oc.gen);
+    if (rc != FT_OK) {
+      for (int k = 0; k < c; ++k)
+        if (st->cls[k].gen) {
+          (void)hipStreamSynchronize(user);
+          drop_generation(p, st->cls[k].gen.get());
+        }
+      return rc;
+    }
+    chunks += cp.nchunks;
+    st->arrival[job->id << 2 | (uint64_t)c] = 0;
+  }
+  st->left[job->id] = chunks;
+  for (int c = 0; c < FT_NCLASS; ++c)
+    if (st->cls[c].used) st->cls[c].feeder = std::thread(feeder_main, st.get(), c);
+  lock.unlock();
+  job->open = st;
+  return FT_OK;
+}
+
+int open_merge(ft_pool *p, Job *open_job, Job *job, SubmitPlan &plan, const uint32_t *weights,
+               hipStream_t user) {
+  std::shared_ptr<OpenState> st = open_job->open;
+  if (!st) return FT_EINVAL;
+  std::unique_lock<std::mutex> lock(st->mu);
+  if (st->error != FT_OK) {
+    p->hip_error = st->error_text;
+    return st->error;
+  }
+  // all or nothing: every class the newcomer uses must still have batches to trigger
+  for (int c = 0; c < FT_NCLASS; ++c)
+    if (plan.cls[c].nchunks > 0 && (!st->cls[c].used || st->cls[c].closed)) return FT_ECLOSED;
+  uint64_t chunks = 0;
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    ClassPlan &cp = plan.cls[c];
+    if (cp.nchunks == 0) continue;
+    OpenClass &oc = st->cls[c];
+    for (Func &f : cp.funcs) f.weight = weights[f.func];
+    const size_t before = oc.fns.size();
+    add_functions(oc, job->id, cp, st->chunk_bytes);
+    std::shared_ptr<Generation> g;
+    int rc = build_generation(p, st.get(), c, user, &g);
+    if (rc != FT_OK) {
+      oc.fns.resize(before);
+      return rc;  // classes merged before this one stay merged; the caller sees the error
+    }
+    std::shared_ptr<Generation> old = oc.gen;
+    oc.gen = g;
+    if (old->inflight == 0) drop_generation(p, old.get());
+    st->arrival[job->id << 2 | (uint64_t)c] = oc.batches_triggered;
+    chunks += cp.nchunks;
+  }
+  st->left[job->id] = chunks;
+  lock.unlock();
+  st->cv.notify_all();
+  job->open = st;
+  return FT_OK;
+}
+
+int open_wait(ft_pool *p, const std::shared_ptr<OpenState> &st, uint64_t job_id) {
+  std::unique_lock<std::mutex> lock(st->mu);
+  st->cv.wait(lock, [&] {
+    auto it = st->left.find(job_id);
+    return it == st->left.end() || it->second == 0;
+  });
+  if (st->error != FT_OK) {
+    p->hip_error = st->error_text;
+    return st->error;
+  }
+  return FT_OK;
+}
+
+void open_stats(const std::shared_ptr<OpenState> &st, int c, uint64_t *tickets, uint64_t *tile_bytes,
+                uint32_t *workgroups, float *kernel_ms, uint64_t *batches) {
+  std::lock_guard<std::mutex> lock(st->mu);
+  const OpenClass &oc = st->cls[c];
+  *tickets = oc.tickets;
+  *tile_bytes = oc.tile_bytes;
+  *workgroups = oc.workgroups;
+  *kernel_ms = (st->flags & FT_TIMING) ? (float)oc.kernel_ms : -1.f;
+  *batches = oc.batches_triggered;
+}
+
+int open_arrival(const std::shared_ptr<OpenState> &st, uint64_t job_id, int c, uint64_t *batch) {
+  std::lock_guard<std::mutex> lock(st->mu);
+  auto it = st->arrival.find(job_id << 2 | (uint64_t)c);
+  if (it == st->arrival.end()) return FT_EINVAL;
+  *batch = it->second;
+  return FT_OK;
+}
+
+uint64_t open_order(const std::shared_ptr<OpenState> &st, int c, uint64_t *job_out, uint32_t *func_out,
+                    uint32_t *chunk_out, uint32_t *batch_out, uint64_t cap) {
+  std::lock_guard<std::mutex> lock(st->mu);
+  const OpenClass &oc = st->cls[c];
+  for (uint64_t i = 0; i < oc.order.size() && i < cap; ++i) {
+    job_out[i] = oc.order[i].job;
+    func_out[i] = oc.order[i].func;
+    chunk_out[i] = oc.order[i].chunk;
+    batch_out[i] = oc.order[i].batch;
+  }
+  return oc.order.size();
+}
+
+}  // namespace ft

@@ -32,6 +32,23 @@ static uint64_t rank_of_chunk(const std::vector<Func> &funcs, uint32_t f, uint64
   return rank;
 }
 
+void build_chunk_table(ClassPlan &cp, uint64_t chunk_bytes) {
+  cp.chunk_desc.clear();
+  if (cp.nchunks + cp.funcs.size() > kMaxChunkTable) return;
+  cp.chunk_desc.reserve(cp.nchunks + cp.funcs.size());
+  // one forward walk over each function's descriptors
+  for (const Func &fn : cp.funcs) {
+    const uint32_t last = fn.desc_off + fn.ndesc - 1;
+    uint32_t x = fn.desc_off;
+    for (uint64_t k = 0; k < fn.nchunks; ++k) {
+      const uint64_t pos = (fn.chunk_base + k) * chunk_bytes;
+      while (x < last && cp.xfers[x + 1].stream_off <= pos) ++x;
+      cp.chunk_desc.push_back(x);
+    }
+    cp.chunk_desc.push_back(last);
+  }
+}
+
 void build_skips(const ClassPlan &cp, uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t tiles_per_chunk,
                  std::vector<Skip> *skips, uint64_t *ntickets) {
   skips->clear();
@@ -41,7 +58,7 @@ void build_skips(const ClassPlan &cp, uint64_t chunk_bytes, uint64_t tile_bytes,
   std::vector<Short> shorts;
   for (uint32_t f = 0; f < cp.funcs.size(); ++f) {
     const Func &fn = cp.funcs[f];
-    const uint64_t last_bytes = fn.stream_bytes - (fn.nchunks - 1) * chunk_bytes;
+    const uint64_t last_bytes = fn.stream_bytes - (fn.chunk_base + fn.nchunks - 1) * chunk_bytes;
     const uint64_t tiles = (last_bytes + tile_bytes - 1) / tile_bytes;
     if (tiles < tiles_per_chunk) shorts.push_back(Short{rank_of_chunk(cp.funcs, f, fn.nchunks - 1), tiles});
   }
@@ -341,7 +358,8 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
       fn.desc_off = off;
       fn.ndesc = count[f];
       fn.chunk_off = 0;
-      fn._pad[0] = fn._pad[1] = fn._pad[2] = 0;
+      fn._pad = 0;
+      fn.chunk_base = 0;
       off += count[f];
       slot_of[f] = (int64_t)cp.funcs.size();
       cp.funcs.push_back(fn);
@@ -366,20 +384,7 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
       }
     int rc = build_phases(cp.funcs, cp.phases, cp.slots, &cp.nchunks);
     if (rc != FT_OK) return rc;
-    // chunk table: one forward walk over each function's descriptors
-    if (cp.nchunks + cp.funcs.size() <= kMaxChunkTable) {
-      cp.chunk_desc.reserve(cp.nchunks + cp.funcs.size());
-      for (const Func &fn : cp.funcs) {
-        const uint32_t last = fn.desc_off + fn.ndesc - 1;
-        uint32_t x = fn.desc_off;
-        for (uint64_t k = 0; k < fn.nchunks; ++k) {
-          const uint64_t pos = k * chunk_bytes;
-          while (x < last && cp.xfers[x + 1].stream_off <= pos) ++x;
-          cp.chunk_desc.push_back(x);
-        }
-        cp.chunk_desc.push_back(last);
-      }
-    }
+    build_chunk_table(cp, chunk_bytes);
   }
   return FT_OK;
 }

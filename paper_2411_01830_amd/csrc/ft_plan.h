@@ -46,6 +46,10 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
                 uint32_t ndesc, const uint32_t *weights, uint32_t nfunc, uint64_t chunk_bytes,
                 uint32_t flags, SubmitPlan *out);
 
+// Per function and chunk of the order, the descriptor holding the chunk's first stream
+// byte (left empty above kMaxChunkTable entries). Needs funcs, xfers and nchunks.
+void build_chunk_table(ClassPlan &cp, uint64_t chunk_bytes);
+
 // Runs of empty tiles (past the end of each function's last chunk) for the given tile
 // shape, in ticket order, and the number of tickets left once they are taken out.
 void build_skips(const ClassPlan &cp, uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t tiles_per_chunk,

@@ -42,13 +42,15 @@ struct Slot {
 
 struct Func {
   uint64_t stream_bytes;  // S_f
-  uint64_t nchunks;       // ceil(S_f / C)
+  uint64_t nchunks;       // chunks in this order: ceil(S_f / C) - chunk_base
   uint32_t func;          // caller's function id
   uint32_t weight;        // w_f divided by the gcd of the class's weights
   uint32_t desc_off;      // first descriptor of this function in the class's table
   uint32_t ndesc;
   uint32_t chunk_off;     // first of the function's nchunks + 1 entries in the chunk table
-  uint32_t _pad[3];
+  uint32_t _pad;
+  uint64_t chunk_base;    // stream chunk that the function's chunk 0 of this order is: 0 unless
+                          // the order was rebuilt when jobs joined (then: chunks triggered before)
 };
 
 // One transfer with both sides resolved to device-visible virtual addresses.
@@ -99,7 +101,12 @@ struct ClassTable {
   LogEntry *log;               // one per ticket, or null
   WgLogEntry *wg_log;          // one per workgroup; set whenever log is
   uint64_t nchunks;            // N
-  uint64_t ntickets;           // N * tiles_per_chunk minus the empty tiles
+  uint64_t ntickets;           // end of this launch's tickets (at most N * tiles_per_chunk minus
+                               // the empty tiles)
+  uint64_t ticket_base;        // first ticket of this launch: ticket = ticket_base + counter
+  uint64_t skip_acc0;          // where the cursors stand at ticket_base: empty tiles before it,
+  uint32_t skip0;              // index of the next run of empty tiles,
+  uint32_t phase0;             // and the phase that holds its chunk
   uint64_t chunk_bytes;        // C
   uint64_t tile_bytes;         // bytes per ticket, multiple of 16
   uint32_t tiles_per_chunk;
@@ -117,7 +124,7 @@ inline uint64_t ticket_to_tile(const Skip *skips, uint32_t nskips, uint64_t t) {
 
 struct ChunkId {
   uint32_t fl;  // index into funcs
-  uint64_t k;   // chunk index within that function's stream
+  uint64_t k;   // chunk index within this order; the stream chunk is funcs[fl].chunk_base + k
 };
 
 // rank -> (function, chunk). rank < nchunks. The pointer types are template

@@ -115,6 +115,14 @@ class GpuEngine:
         return ft.submit_transfers(self.pool, d, weights, int(chunk_bytes),
                                    int(flags) | self.default_flags, s)
 
+    def merge(self, open_job, descs, weights, flags=0, stream=None):
+        d = np.array(descs, copy=True)
+        base = self.host.data_ptr() if self.host is not None else 0
+        d["src"][d["src_space"] == 0] += np.uint64(base)
+        d["dst"][d["dst_space"] == 0] += np.uint64(base)
+        s = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
+        return ft.submit_merge(self.pool, open_job, d, weights, int(flags), s)
+
     def wait(self, job):
         ft.wait(self.pool, job)
 

@@ -1,0 +1,203 @@
+"""Open jobs (batched transfer triggering, Sec. 6.1) against the oracle: bytes, and the
+order of the batches given the batch at which the library says each job joined."""
+import time
+
+import numpy as np
+import pytest
+
+from oracle import OracleEngine
+from oracle.batches import batched_order
+from oracle.schedule import chunk_count
+from workloads import make_descs, FT_HOST, FT_POOL
+from workloads import format as fmt
+
+pytestmark = pytest.mark.gpu
+
+KiB, MiB = 1 << 10, 1 << 20
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2411_01830_amd import binding, harness
+    assert torch.cuda.is_available()
+    return binding, harness
+
+
+def _engines(gpu, host_bytes, pool_bytes, slab=64 * KiB, seed=0):
+    _, harness = gpu
+    orc, eng = OracleEngine(), harness.GpuEngine()
+    rng = np.random.default_rng(seed)
+    data = rng.integers(0, 256, host_bytes // 2, dtype=np.uint8)
+    for e in (orc, eng):
+        e.host_arena(host_bytes)
+        e.pool_create(pool_bytes, slab)
+        e.write_host(0, data)
+    return orc, eng, rng
+
+
+def _images_equal(orc, eng):
+    import torch
+    assert np.array_equal(eng.host_np[:len(orc.host_mem)], orc.host_mem), "host image differs"
+    got = torch.cat([t for t, _ in eng.segments]).cpu().numpy()
+    assert np.array_equal(got, orc.pool_mem), "pool image differs"
+
+
+def _h2p_job(orc, eng, rng, sizes, host_limit):
+    """One host->pool descriptor per function; returns (records, chunk streams)."""
+    recs = []
+    for f, n in enumerate(sizes):
+        a = orc.slab_alloc(n + 32)
+        assert eng.slab_alloc(n + 32) == a
+        src = int(rng.integers(0, (host_limit - n) // 16)) * 16 + int(rng.integers(0, 2)) * 3
+        recs.append(dict(func=f, src_space=FT_HOST, dst_space=FT_POOL, src=src, dst=a + int(rng.integers(0, 16)),
+                         row_bytes=n))
+    return recs
+
+
+def test_open_job_alone_is_the_plain_order_in_batches(gpu):
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 64 * MiB, 96 * MiB)
+    try:
+        C = 256 * KiB
+        sizes = [5 * MiB + 1234, 9 * MiB, 3 * MiB + 16, 700 * KiB]
+        w = [1, 2, 4, 1]
+        recs = _h2p_job(orc, eng, rng, sizes, 32 * MiB)
+        d = make_descs(recs)
+        binding.set_batch(eng.pool, 5, 2)
+        orc.wait(orc.submit(d, w, C))
+        job = eng.submit(d, w, C, fmt.FT_OPEN | fmt.FT_KEEP | fmt.FT_VALIDATE)
+        assert binding.job_arrival(eng.pool, job, 0) == 0
+        eng.wait(job)
+        _images_equal(orc, eng)
+        got = binding.job_batches(eng.pool, job, 0)
+        n = [chunk_count(s, C) for s in sizes]
+        want = batched_order([{"n": n, "w": w}], 5)
+        assert [[(f, k) for _, f, k in b] for b in got] == [[(f, k) for _, f, k in b] for b in want]
+        assert all(j == job for b in got for j, _, _ in b)
+        st = binding.job_stats(eng.pool, job)
+        assert st.cls[0].payload_bytes == sum(sizes) and st.cls[0].chunks == sum(n)
+        binding.job_release(eng.pool, job)
+    finally:
+        eng.close()
+
+
+@pytest.mark.parametrize("batch,depth", [(5, 2), (2, 1), (16, 3)])
+def test_merged_jobs_match_oracle(gpu, batch, depth):
+    """A long host->pool job, then two more merged while it runs. Whatever batch each one
+    joins at (the library says), the batches must be the oracle's for those arrivals and the
+    bytes the plain copy."""
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 192 * MiB, 256 * MiB, seed=batch)
+    try:
+        C = 256 * KiB
+        binding.set_batch(eng.pool, batch, depth)
+        jobs_sizes = [[40 * MiB, 24 * MiB + 48, 17 * MiB + 5], [1 * MiB + 7, 300 * KiB], [3 * MiB, 2 * MiB + 1, 64 * KiB]]
+        jobs_w = [[1, 2, 1], [8, 8], [4, 1, 2]]
+        descs = [make_descs(_h2p_job(orc, eng, rng, s, 96 * MiB)) for s in jobs_sizes]
+        for d, w in zip(descs, jobs_w):
+            orc.wait(orc.submit(d, w, C))
+        print(f"open job batch={batch} depth={depth}", flush=True)
+        handles = [eng.submit(descs[0], jobs_w[0], C, fmt.FT_OPEN | fmt.FT_KEEP)]
+        closed = []
+        for i in (1, 2):
+            try:
+                handles.append(eng.merge(handles[0], descs[i], jobs_w[i], fmt.FT_KEEP))
+            except binding.FtError as e:          # the open job was already done: legal, run it alone
+                assert e.code == fmt.FT_ECLOSED
+                closed.append(i)
+                handles.append(eng.submit(descs[i], jobs_w[i], C, fmt.FT_KEEP))
+            time.sleep(0.0002)
+        for h in reversed(handles):
+            eng.wait(h)
+        _images_equal(orc, eng)
+        spec = [{"n": [chunk_count(s, C) for s in jobs_sizes[0]], "w": jobs_w[0]}]
+        index = {handles[0]: 0}
+        for i in (1, 2):
+            if i in closed:
+                continue
+            a = binding.job_arrival(eng.pool, handles[i], 0)
+            index[handles[i]] = len(spec)
+            spec.append({"n": [chunk_count(s, C) for s in jobs_sizes[i]], "w": jobs_w[i], "arrive": a})
+        got = binding.job_batches(eng.pool, handles[0], 0)
+        got = [[(index[j], f, k) for j, f, k in b] for b in got]
+        assert got == batched_order(spec, batch)
+        print("arrivals", [s.get("arrive", 0) for s in spec], "batches", len(got), "closed", closed, flush=True)
+        for h in handles:
+            binding.job_release(eng.pool, h)
+    finally:
+        eng.close()
+
+
+def test_merge_other_classes_and_busy_allocations(gpu):
+    """pool->host and pool->pool traffic merged into an open job that has all three classes;
+    allocations of a merged job stay busy until it has been waited for."""
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 128 * MiB, 256 * MiB, seed=5)
+    try:
+        C = 128 * KiB
+        binding.set_batch(eng.pool, 4, 2)
+
+        def alloc(n):
+            a = orc.slab_alloc(n)
+            assert eng.slab_alloc(n) == a
+            return a
+
+        def filled(n):
+            a = alloc(n)
+            data = rng.integers(0, 256, n, dtype=np.uint8)
+            orc.write_pool(a, data)
+            eng.write_pool(a, data)
+            return a
+
+        big = 24 * MiB
+        recs0 = [dict(func=0, src_space=FT_HOST, dst_space=FT_POOL, src=4096, dst=alloc(big), row_bytes=big),
+                 dict(func=1, src_space=FT_POOL, dst_space=FT_HOST, src=filled(big), dst=64 * MiB, row_bytes=big),
+                 dict(func=2, src_space=FT_POOL, dst_space=FT_POOL, src=filled(big) + 3, dst=alloc(big) + 8,
+                      row_bytes=big - 16)]
+        small_src = filled(2 * MiB)
+        small_dst = alloc(2 * MiB)
+        recs1 = [dict(func=0, src_space=FT_POOL, dst_space=FT_HOST, src=small_src, dst=64 * MiB + big + 4096,
+                      row_bytes=2 * MiB - 5),
+                 dict(func=0, src_space=FT_HOST, dst_space=FT_POOL, src=20 * MiB + 1, dst=small_dst, row_bytes=1 * MiB)]
+        d0, d1 = make_descs(recs0), make_descs(recs1)
+        orc.wait(orc.submit(d0, [1, 1, 1], C))
+        orc.wait(orc.submit(d1, [5], C))
+        j0 = eng.submit(d0, [1, 1, 1], C, fmt.FT_OPEN | fmt.FT_KEEP)
+        try:
+            j1 = eng.merge(j0, d1, [5], fmt.FT_KEEP)
+            merged = True
+        except binding.FtError as e:
+            assert e.code == fmt.FT_ECLOSED
+            j1 = eng.submit(d1, [5], C, fmt.FT_KEEP)
+            merged = False
+        with pytest.raises(binding.FtError) as ei:
+            eng.slab_free(small_dst)
+        assert ei.value.code == fmt.FT_EBUSY
+        eng.wait(j1)
+        eng.slab_free(small_dst)
+        orc.slab_free(small_dst)
+        eng.wait(j0)
+        _images_equal(orc, eng)
+        print("merged" if merged else "closed before the merge", flush=True)
+        # once everything is done the open job accepts nothing more
+        with pytest.raises(binding.FtError) as ei:
+            eng.merge(j0, d1[:1], [5])
+        assert ei.value.code == fmt.FT_ECLOSED
+        binding.job_release(eng.pool, j0)
+        binding.job_release(eng.pool, j1)
+    finally:
+        eng.close()
+
+
+def test_open_rejects_log_and_dma(gpu):
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 4 * MiB, 8 * MiB)
+    try:
+        d = make_descs(_h2p_job(orc, eng, rng, [64 * KiB], 1 * MiB))
+        for extra in (fmt.FT_LOG, fmt.FT_PATH_DMA):
+            with pytest.raises(binding.FtError) as ei:
+                eng.submit(d, [1], 4096, fmt.FT_OPEN | extra)
+            assert ei.value.code == fmt.FT_EINVAL
+    finally:
+        eng.close()

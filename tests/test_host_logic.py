@@ -282,3 +282,24 @@ def test_random_overlap_decisions_match_oracle():
             assert _submit_both(pool, orc, hb, recs, [1], 64) == ("err", fmt.FT_EOVERLAP)
     assert rejected > 100
     ft.pool_destroy(pool)
+
+
+def test_slo_weights_match_the_oracle_rule():
+    """Sec. 6.1 transfer rate control: the library's host routine and the oracle compute the
+    same expression in the same order in IEEE double, so rates and weights are identical."""
+    from oracle.rate import allocate_rates, slo_weights
+    rng = random.Random(21)
+    for _ in range(500):
+        n = rng.randint(1, 10)
+        size = [rng.randint(0, 1 << 31) for _ in range(n)]
+        infer = [rng.uniform(0.0005, 0.05) for _ in range(n)]
+        slo = [x + rng.uniform(0.0005, 0.2) for x in infer]
+        bw = rng.uniform(1e8, 64e9)
+        total = rng.choice([0, 16, 64, 1000])
+        rates, weights = ft.slo_weights(size, slo, infer, bw, total)
+        assert rates == allocate_rates(size, slo, infer, bw)
+        assert weights == slo_weights(size, slo, infer, bw, total or 64)
+    for bad in (([1.0], [0.01], [0.01], 1e9), ([1.0], [0.01], [0.02], 1e9), ([1.0], [0.02], [0.01], 0.0)):
+        with pytest.raises(ft.FtError) as ei:
+            ft.slo_weights(*bad)
+        assert ei.value.code == fmt.FT_EINVAL

@@ -20,12 +20,15 @@ FT_ERANGE = -3
 FT_EOVERLAP = -4
 FT_EBUSY = -5
 FT_EHIP = -6
+FT_ECLOSED = -7
 
 FT_VALIDATE = 1 << 0   # exact overlap check of the submit
 FT_LOG = 1 << 1        # per-ticket device timestamps
 FT_PATH_DMA = 1 << 2   # run the same schedule on the copy engines
 FT_TIMING = 1 << 3     # device events around each class's kernel
 FT_DETACHED = 1 << 4   # caller's stream does not wait for the job
+FT_KEEP = 1 << 5       # keep the job record after wait
+FT_OPEN = 1 << 6       # trigger the chunks in batches and accept merges meanwhile
 
 DESC_DTYPE = np.dtype([
     ("func", "<u4"),
