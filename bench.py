@@ -230,6 +230,62 @@ def share_error(rp, cls):
             "weights": [int(x) for x in w]}
 
 
+def batched_triggering(peaks):
+    """Sec. 6.1 on the contended host link: 16 background functions stream 256 MiB each
+    (objective 1 s, 0.1 s of it inference); 10 ms into the job an urgent function arrives
+    with 8 MiB, a 3 ms objective and 1 ms of inference. Weights come from the rate-control
+    rule (ft_slo_weights, link = the measured peak). Closed job: the newcomer queues behind
+    the 4 GiB. Open job: it joins at the next batch. Reports the newcomer's transfer latency
+    (merge call to wait) and what batching costs the background job."""
+    import torch
+    from paper_2411_01830_amd import binding as ft
+    from workloads import make_descs
+    rp = Replay("contended", False)
+    sub = [o for o in rp.ops if o[0] == "submit"][0]
+    descs, chunk = sub[2], sub[4]
+    allocs = [o for o in rp.ops if o[0] == "alloc"]
+    nbg, small = len(sub[3]), 8 << 20
+    sizes = [float(256 << 20)] * nbg + [float(small)]
+    rates, w = ft.slo_weights(sizes, [1.0] * nbg + [0.003], [0.1] * nbg + [0.001], peaks["h2d"] * 1e9)
+    out = {"weights_background": w[0], "weight_urgent": w[-1], "urgent_rate_GBps": round(rates[-1] / 1e9, 2),
+           "urgent_budget_ms": 2.0, "urgent_bytes": small, "chunk_bytes": chunk, "cases": {}}
+    for name, batch in (("closed", 0), ("open_batch5", 5), ("open_batch20", 20)):
+        lat, tot = [], []
+        for _ in range(3):
+            pool = ft.pool_create(rp.segs[0].data_ptr(), rp.segs[0].numel(), rp.plan.slab_bytes, 0)
+            ft.host_window_add(pool, rp.host.data_ptr(), rp.host.numel())
+            for a in allocs:
+                ft.slab_alloc(pool, a[1])
+            off = ft.slab_alloc(pool, small)
+            urgent = make_descs([dict(func=0, src_space=0, dst_space=1, src=rp.host.data_ptr() + 4096, dst=off,
+                                      row_bytes=small)])
+            if batch:
+                ft.set_batch(pool, batch, 3)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            j1 = ft.submit_transfers(pool, descs, w[:nbg], chunk, ft.FT_OPEN if batch else ft.FT_DETACHED, rp.stream)
+            time.sleep(0.010)
+            t1 = time.perf_counter()
+            if batch:
+                j2 = ft.submit_merge(pool, j1, urgent, w[-1:], 0, rp.stream)
+            else:
+                j2 = ft.submit_transfers(pool, urgent, w[-1:], chunk, ft.FT_DETACHED, rp.stream)
+            ft.wait(pool, j2)
+            t2 = time.perf_counter()
+            ft.wait(pool, j1)
+            t3 = time.perf_counter()
+            lat.append((t2 - t1) * 1e3)
+            tot.append((t3 - t0) * 1e3)
+            ft.pool_destroy(pool)
+        lat.sort()
+        tot.sort()
+        out["cases"][name] = {"urgent_latency_ms": round(lat[1], 3), "background_ms": round(tot[1], 2),
+                              "background_GBps": round(rp.payload / tot[1] / 1e6, 2),
+                              "urgent_within_budget": bool(lat[1] <= 2.0)}
+    rp.close()
+    return out
+
+
 def cpu_baseline():
     """The CPU oracle, as it stands, on a bounded sample of the same workload: the first
     waves of large_mixed at full size, as many as keep the leg around 10-30 s."""
@@ -346,6 +402,8 @@ def main():
         line["share_error"] = shares
     line["per_workload"] = per
     rp.close()
+    if not args.no_extras:
+        line["batched_triggering"] = batched_triggering(peaks)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline()
     print(json.dumps(line))

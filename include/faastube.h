@@ -190,7 +190,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
  * Batched transfer triggering (Sec. 6.1). A job submitted with FT_OPEN does not hand its
  * whole chunk order to the device at once: per link class a feeder thread launches the
  * copy kernel once per batch of `batch_chunks` consecutive chunks of the order (5 unless
- * ft_set_batch says otherwise) and keeps `depth` batches (2) queued ahead of the device.
+ * ft_set_batch says otherwise) and keeps `depth` batches (3) queued ahead of the device.
  * Transfers merged meanwhile join at the first batch not yet triggered: the order is
  * rebuilt over the chunks not yet triggered of every function already there - each
  * restarting its finish tags at 1/w - plus all chunks of the new functions, functions

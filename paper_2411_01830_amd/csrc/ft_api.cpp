@@ -40,6 +40,8 @@ int ensure_device(ft_pool *p) {
   FT_HIP(p, hipDeviceGetAttribute(&c->clock_khz, hipDeviceAttributeWallClockRate, p->device));
   for (int k = 0; k < FT_NCLASS; ++k)
     if (c->streams[k] == nullptr) FT_HIP(p, hipStreamCreateWithFlags(&c->streams[k], hipStreamNonBlocking));
+  for (int k = 0; k < FT_NCLASS; ++k)
+    if (c->alt_streams[k] == nullptr) FT_HIP(p, hipStreamCreateWithFlags(&c->alt_streams[k], hipStreamNonBlocking));
   c->ready = true;
   return FT_OK;
 }

@@ -44,8 +44,8 @@ struct Generation {
   uint64_t next_rank = 0;           // first rank of this order not yet triggered
   uint32_t next_counter = 0;
   uint32_t inflight = 0;            // batches launched with these tables and not seen complete
-  hipEvent_t uploaded = nullptr;    // the class's stream waits for it before the first batch
-  bool waited_upload = false;
+  hipEvent_t uploaded = nullptr;    // each of the class's two streams waits for it before its first batch
+  bool waited_upload[2] = {false, false};
 };
 
 struct OpenBatch {
@@ -85,7 +85,7 @@ struct OpenState {
   ft_pool *pool = nullptr;
   uint64_t chunk_bytes = 0;
   uint32_t batch_chunks = 5;
-  uint32_t depth = 2;               // batches queued ahead of the device
+  uint32_t depth = 3;               // batches queued ahead of the device
   uint32_t flags = 0;
   OpenClass cls[FT_NCLASS];
   std::unordered_map<uint64_t, uint64_t> left;      // job id -> chunks not yet complete
@@ -216,11 +216,12 @@ bool launch_batch(OpenState *st, int c) {
     if (st->error == FT_OK) st->error = FT_EHIP, st->error_text = p->hip_error;
     return false;
   }
-  hipStream_t s = p->ctx->streams[c];
+  const uint32_t lane = (uint32_t)(oc.batches_triggered & 1);
+  hipStream_t s = lane ? p->ctx->alt_streams[c] : p->ctx->streams[c];
   hipError_t e = hipSuccess;
-  if (!g.waited_upload) {
+  if (!g.waited_upload[lane]) {
     e = hipStreamWaitEvent(s, g.uploaded, 0);
-    g.waited_upload = true;
+    g.waited_upload[lane] = true;
   }
   uint64_t wg = oc.workgroups;
   if (wg > t1 - t0) wg = t1 - t0;
@@ -320,7 +321,7 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
   st->pool = p;
   st->chunk_bytes = chunk_bytes;
   st->batch_chunks = p->batch_chunks ? p->batch_chunks : 5;
-  st->depth = p->batch_depth ? p->batch_depth : 2;
+  st->depth = p->batch_depth ? p->batch_depth : 3;
   st->flags = job->flags;
   uint64_t chunks = 0;
   const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
