@@ -34,6 +34,8 @@ EBUSY = -5
 
 HOST = 0
 POOL = 1
+PAGEABLE = 2   # ordinary host memory; a source only (Sec. 6.1: it travels through a pinned ring,
+               # which is transport and leaves the result a plain copy)
 
 H2P, P2H, P2P = 0, 1, 2
 

@@ -16,7 +16,7 @@ the pool as one flat array over its logical offset space.
 """
 import numpy as np
 
-from . import (OracleError, EINVAL, ERANGE, EOVERLAP, EBUSY, HOST, POOL,
+from . import (OracleError, EINVAL, ERANGE, EOVERLAP, EBUSY, HOST, POOL, PAGEABLE,
                H2P, P2H, P2P)
 from .pool import Pool
 from .schedule import link_class, chunk_count, stride_order, chunk_segments
@@ -89,12 +89,20 @@ class OracleEngine:
         self.pool = None
         self.pool_mem = None
         self.host_mem = np.zeros(0, dtype=np.uint8)
+        self.pageable_mem = np.zeros(0, dtype=np.uint8)
         self.jobs = {}
         self._next_job = 1
 
     # ---- memory the caller owns -------------------------------------------------
     def host_arena(self, nbytes, fill=0x5A):
         self.host_mem = np.full(nbytes, fill, dtype=np.uint8)
+
+    def pageable_arena(self, nbytes, fill=0x3C):
+        """Ordinary host memory: sources only. Addresses are offsets into it."""
+        self.pageable_mem = np.full(nbytes, fill, dtype=np.uint8)
+
+    def write_pageable(self, off, data):
+        self.pageable_mem[off:off + len(data)] = data
 
     def write_host(self, off, data):
         self.host_mem[off:off + len(data)] = data
@@ -141,7 +149,7 @@ class OracleEngine:
         for d in descs:
             if int(d["func"]) >= nfunc or int(d["flags"]) != 0:
                 raise OracleError(EINVAL, "bad func or flags")
-            if int(d["src_space"]) not in (HOST, POOL) or int(d["dst_space"]) not in (HOST, POOL):
+            if int(d["src_space"]) not in (HOST, POOL, PAGEABLE) or int(d["dst_space"]) not in (HOST, POOL):
                 raise OracleError(EINVAL, "bad space")
             link_class(int(d["src_space"]), int(d["dst_space"]))
             if int(d["row_bytes"]) == 0 or int(d["rows"]) == 0:
@@ -162,6 +170,9 @@ class OracleEngine:
                     if a is None:
                         raise OracleError(ERANGE, "pool range not inside one live allocation")
                     used.add(a)
+                elif int(d[side + "_space"]) == PAGEABLE:
+                    if off + ext > len(self.pageable_mem):
+                        raise OracleError(ERANGE, "pageable range outside its window")
                 else:
                     if off + ext > len(self.host_mem):
                         raise OracleError(ERANGE, "host range outside the arena")
@@ -170,7 +181,7 @@ class OracleEngine:
         return used
 
     def _mem(self, space):
-        return self.host_mem if space == HOST else self.pool_mem
+        return self.host_mem if space == HOST else self.pageable_mem if space == PAGEABLE else self.pool_mem
 
     def submit(self, descs, weights, chunk_bytes, flags=0):
         used = self._check(descs, weights, chunk_bytes)

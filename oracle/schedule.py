@@ -13,13 +13,13 @@ descriptor, form one byte stream; chunk k is stream bytes [kC, (k+1)C).
 """
 from fractions import Fraction
 
-from . import HOST, POOL, H2P, P2H, P2P, OracleError, EINVAL
+from . import HOST, POOL, PAGEABLE, H2P, P2H, P2P, OracleError, EINVAL
 
 
 def link_class(src_space, dst_space):
     """Sec. 5.1 lists host<->GPU and intra-GPU passing as different methods;
     each direction of the host link and the on-device path is its own class."""
-    if src_space == HOST and dst_space == POOL:
+    if src_space in (HOST, PAGEABLE) and dst_space == POOL:
         return H2P
     if src_space == POOL and dst_space == HOST:
         return P2H

@@ -13,7 +13,7 @@ FT_VALIDATE, FT_LOG, FT_PATH_DMA, FT_TIMING, FT_DETACHED, FT_KEEP, FT_OPEN = 1, 
 FT_ECLOSED = -7
 
 EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
-           "ft_pool_ptr", "ft_host_window_add", "ft_submit_transfers", "ft_submit_merge", "ft_set_batch",
+           "ft_pool_ptr", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_submit_transfers", "ft_submit_merge", "ft_set_batch",
            "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
            "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
            "ft_plain_copy", "ft_strerror", "ft_last_hip_error"]
@@ -54,6 +54,8 @@ def _load():
         "ft_slab_free": (i32, [vp, u64]),
         "ft_pool_ptr": (vp, [vp, u64]),
         "ft_host_window_add": (i32, [vp, vp, u64]),
+        "ft_pageable_window_add": (i32, [vp, vp, u64]),
+        "ft_set_stage_threads": (i32, [vp, u32]),
         "ft_submit_transfers": (i32, [vp, vp, u32, vp, u32, u64, u32, vp, P(u64)]),
         "ft_submit_merge": (i32, [vp, u64, vp, u32, vp, u32, u32, vp, P(u64)]),
         "ft_set_batch": (i32, [vp, u32, u32]),
@@ -211,6 +213,14 @@ def submit_merge(pool, open_job, descs, weights, flags=0, stream=0):
     _check(_lib.ft_submit_merge(pool, open_job, d.ctypes.data, len(d), w.ctypes.data, len(w), flags, stream,
                                 C.byref(job)), pool)
     return job.value
+
+
+def pageable_window_add(pool, host_ptr, nbytes):
+    _check(_lib.ft_pageable_window_add(pool, host_ptr, nbytes), pool)
+
+
+def set_stage_threads(pool, threads):
+    _check(_lib.ft_set_stage_threads(pool, threads), pool)
 
 
 def set_batch(pool, batch_chunks=5, depth=2):

@@ -106,6 +106,32 @@ void put_event(ft_pool *p, bool timing, hipEvent_t &e) {
 
 uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
+int get_pinned(ft_pool *p, uint64_t need, char **out, uint64_t *cap) {
+  {
+    std::lock_guard<std::mutex> lock(p->ctx->mu);
+    auto &cache = p->ctx->free_pinned;
+    size_t best = cache.size();
+    for (size_t i = 0; i < cache.size(); ++i)
+      if (cache[i].second >= need && (best == cache.size() || cache[i].second < cache[best].second)) best = i;
+    if (best != cache.size()) {
+      *out = cache[best].first;
+      *cap = cache[best].second;
+      cache.erase(cache.begin() + (long)best);
+      return FT_OK;
+    }
+  }
+  const uint64_t bytes = round_pow2(need, 1 << 20);
+  FT_HIP(p, hipHostMalloc(reinterpret_cast<void **>(out), bytes, hipHostMallocDefault));
+  *cap = bytes;
+  return FT_OK;
+}
+
+void put_pinned(ft_pool *p, char *ptr, uint64_t cap) {
+  if (ptr == nullptr) return;
+  std::lock_guard<std::mutex> lock(p->ctx->mu);
+  p->ctx->free_pinned.push_back({ptr, cap});
+}
+
 Layout layout_of(const ClassPlan &cp, uint64_t base, uint64_t ncounters) {
   Layout l;
   l.ticket = align_up(base, 256);
@@ -139,6 +165,9 @@ void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, Class
   T->nchunks = cp.nchunks;
   T->nphases = (uint32_t)cp.phases.size();
   T->nfuncs = (uint32_t)cp.funcs.size();
+  T->stage_base = 0;
+  T->stage_rank0 = 0;
+  T->stage_slot0 = 0;
   T->ticket_base = 0;
   T->skip_acc0 = 0;
   T->skip0 = 0;
@@ -333,7 +362,14 @@ void *ft_pool_ptr(ft_pool *p, ft_off_t off) {
 int ft_host_window_add(ft_pool *p, void *host_base, uint64_t bytes) {
   if (p == nullptr || host_base == nullptr || bytes == 0) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);
-  p->windows.push_back(HostWindow{reinterpret_cast<uint64_t>(host_base), bytes});
+  p->windows.push_back(HostWindow{reinterpret_cast<uint64_t>(host_base), bytes, false});
+  return FT_OK;
+}
+
+int ft_pageable_window_add(ft_pool *p, void *host_base, uint64_t bytes) {
+  if (p == nullptr || host_base == nullptr || bytes == 0) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  p->windows.push_back(HostWindow{reinterpret_cast<uint64_t>(host_base), bytes, true});
   return FT_OK;
 }
 
@@ -356,6 +392,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
   if (rc != FT_OK) return rc;
 
   if ((flags & FT_OPEN) && (flags & (FT_LOG | FT_PATH_DMA))) return FT_EINVAL;
+  if (plan.has_pageable && !(flags & FT_OPEN)) return FT_EINVAL;  // staged batch by batch
   std::unique_ptr<Job> job(new Job());
   job->flags = flags;
   job->keep = (flags & (FT_KEEP | FT_LOG | FT_TIMING)) != 0;
@@ -531,6 +568,13 @@ int ft_submit_merge(ft_pool *p, ft_job_t open_id, const ft_desc *descs, uint32_t
   job->host_submit_us =
       std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
   p->jobs[job->id] = std::move(job);
+  return FT_OK;
+}
+
+int ft_set_stage_threads(ft_pool *p, uint32_t threads) {
+  if (p == nullptr || threads == 0 || threads > 64) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  p->stage_threads = threads;
   return FT_OK;
 }
 

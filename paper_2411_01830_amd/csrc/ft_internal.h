@@ -82,6 +82,7 @@ struct DeviceCtx {
   std::vector<Blob> free_blobs;      // with a pinned twin
   std::vector<Blob> free_dev_blobs;  // device only
   std::vector<hipEvent_t> free_events, free_timing_events;
+  std::vector<std::pair<char *, uint64_t>> free_pinned;  // staging rings between jobs
 };
 
 DeviceCtx *device_ctx(int device);
@@ -99,6 +100,7 @@ struct ft_pool {
   ft::Tuning tuning[FT_NCLASS];
   uint32_t batch_chunks = 5;  // chunks per triggered batch of an open job (Sec. 6.1 default)
   uint32_t batch_depth = 3;   // batches an open job keeps queued ahead of the device
+  uint32_t stage_threads = 4; // threads (the feeder included) that fill the staging ring
   std::string hip_error;
 
   ft_pool(uint64_t slab_bytes, int dev) : slabs(slab_bytes), device(dev), ctx(ft::device_ctx(dev)) {}
@@ -133,6 +135,9 @@ void put_blob(ft_pool *p, Blob &b);
 int get_event(ft_pool *p, bool timing, hipEvent_t *out);
 void put_event(ft_pool *p, bool timing, hipEvent_t &e);
 uint64_t align_up(uint64_t v, uint64_t a);
+// Pinned host memory for a staging ring (kept for the life of the process and reused).
+int get_pinned(ft_pool *p, uint64_t need, char **out, uint64_t *cap);
+void put_pinned(ft_pool *p, char *ptr, uint64_t cap);
 
 // Byte layout of one class's tables inside a table blob.
 struct Layout {

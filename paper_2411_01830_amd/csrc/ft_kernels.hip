@@ -52,7 +52,7 @@ __device__ __forceinline__ Xfer read_xfer(CXferP xfers, uint32_t x) {
   X.src_pitch = xfers[x].src_pitch;
   X.dst_pitch = xfers[x].dst_pitch;
   X.stream_off = xfers[x].stream_off;
-  X._pad = 0;
+  X.staged = xfers[x].staged;
   return X;
 }
 
@@ -470,9 +470,19 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
 // b0 >= b1) and the descriptor holding b0.
 struct Work {
   uint64_t b0, b1;
-  uint32_t x;   // index of the descriptor that holds stream byte b0
-  Xfer first;   // that descriptor
+  uint32_t x;      // index of the descriptor that holds stream byte b0
+  uint64_t stage;  // address of stream byte 0 of this function if its chunk's ring slot went on for ever
+  Xfer first;      // that descriptor (already pointing into the ring if it is staged)
 };
+
+// A staged descriptor's bytes of the current chunk lie in the chunk's ring slot, packed
+// in stream order: stream byte b at `stage + b`.
+__device__ __forceinline__ void into_ring(Xfer &X, uint64_t stage) {
+  if (X.staged) {
+    X.src = stage + X.stream_off;
+    X.src_pitch = X.row_bytes;
+  }
+}
 
 // Where a workgroup is in the phase table. The ranks it decodes only grow (its tickets
 // come from one counter that only grows), so the phase is found by stepping forward,
@@ -508,6 +518,7 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
   Work w;
   w.b0 = w.b1 = 0;
   w.x = 0;
+  w.stage = 0;
   if (t >= T.ntickets) return w;
   while (t >= sc.next_at) {
     sc.acc += CT.skips[sc.idx].gap;
@@ -558,6 +569,8 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
   w.b1 = b1;
   w.x = x0 == x1 ? x0 : find_xfer(CT.xfers, x0, x1, b0);
   w.first = read_xfer(CT.xfers, w.x);
+  w.stage = T.stage_base + (T.stage_slot0 + (rank - T.stage_rank0)) * T.chunk_bytes - c0;
+  into_ring(w.first, w.stage);
   return w;
 }
 
@@ -566,6 +579,7 @@ struct WorkSlot {
   uint64_t t;  // the ticket; >= ntickets: none left
   uint64_t b0, b1;
   uint64_t x;
+  uint64_t stage;
   Xfer first;
 };
 
@@ -574,6 +588,7 @@ __device__ __forceinline__ void put_work(WorkSlot &slot, uint64_t t, const Work 
   slot.b0 = w.b0;
   slot.b1 = w.b1;
   slot.x = w.x;
+  slot.stage = w.stage;
   slot.first = w.first;
 }
 
@@ -581,6 +596,7 @@ __device__ __forceinline__ uint64_t get_work(const WorkSlot &slot, Work &w) {
   w.b0 = uniform64(slot.b0);
   w.b1 = uniform64(slot.b1);
   w.x = (uint32_t)uniform64(slot.x);
+  w.stage = uniform64(slot.stage);
   w.first.src = uniform64(slot.first.src);
   w.first.dst = uniform64(slot.first.dst);
   w.first.row_bytes = uniform64(slot.first.row_bytes);
@@ -588,7 +604,7 @@ __device__ __forceinline__ uint64_t get_work(const WorkSlot &slot, Work &w) {
   w.first.src_pitch = uniform64(slot.first.src_pitch);
   w.first.dst_pitch = uniform64(slot.first.dst_pitch);
   w.first.stream_off = uniform64(slot.first.stream_off);
-  w.first._pad = 0;
+  w.first.staged = 0;  // already applied
   return uniform64(slot.t);
 }
 
@@ -658,7 +674,10 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
         if (X.rows == 1) copy_piece<NT, U>(X.dst + p, X.src + p, take, tid);
         else copy_rows<NT, U>(X, p, take, tid);
         pos += take;
-        if (pos < cur.b1) X = read_xfer(CT.xfers, ++x);
+        if (pos < cur.b1) {
+          X = read_xfer(CT.xfers, ++x);
+          into_ring(X, cur.stage);
+        }
       }
     }
     if (lead) {

@@ -11,9 +11,19 @@
 // the following batches come from that order. Each order in force has its own tables on
 // the device ("generation"); batches already queued keep the tables they were launched
 // with.
+//
+// Circular pinned buffer of Sec. 6.1: sources in pageable host memory (FT_PAGEABLE) cannot
+// be read by the device. Pinning the caller's buffers per call is what the paper measures
+// as too slow and caching a pinned copy of everything as too large; instead one fixed
+// ring of pinned memory, (depth + 1) * batch_chunks slots of one chunk each, is shared by
+// all functions: before a batch is launched the feeder and a few helper threads copy the
+// stream bytes of the batch's pageable descriptors into the batch's slots (chunk i of
+// batch q has slot (q mod (depth + 1)) * batch_chunks + i), the kernel reads them there,
+// and the slots are used again depth + 1 batches later, when that batch is long complete.
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <chrono>
 #include <condition_variable>
 #include <cstring>
 #include <deque>
@@ -32,6 +42,7 @@ struct OpenFn {
   uint64_t stream_bytes;
   uint64_t nchunks;       // of the whole stream
   uint64_t next_chunk;    // first chunk not yet triggered
+  bool staged;            // some descriptor reads pageable host memory
   std::vector<Xfer> xfers;
 };
 
@@ -50,8 +61,68 @@ struct Generation {
 
 struct OpenBatch {
   std::shared_ptr<Generation> gen;
+  uint32_t lane = 0;                // which of the class's two streams
   hipEvent_t done = nullptr, t_begin = nullptr, t_end = nullptr;
   std::vector<std::pair<uint64_t, uint64_t>> job_chunks;  // job id, chunks of it in this batch
+};
+
+struct StageCopy {
+  char *dst;
+  const char *src;
+  uint64_t n;
+};
+
+// A few helper threads that copy pageable bytes into the ring; the feeder takes part.
+class StagePool {
+ public:
+  explicit StagePool(unsigned helpers) {
+    for (unsigned i = 0; i < helpers; ++i) threads_.emplace_back([this] { work(false); });
+  }
+  ~StagePool() {
+    {
+      std::lock_guard<std::mutex> lock(mu_);
+      quit_ = true;
+    }
+    cv_.notify_all();
+    for (std::thread &t : threads_) t.join();
+  }
+  void run(const std::vector<StageCopy> &copies) {
+    if (copies.empty()) return;
+    {
+      std::lock_guard<std::mutex> lock(mu_);
+      copies_ = &copies;
+      next_ = 0;
+      left_ = copies.size();
+    }
+    cv_.notify_all();
+    work(true);
+    std::unique_lock<std::mutex> lock(mu_);
+    done_.wait(lock, [this] { return left_ == 0; });
+    copies_ = nullptr;
+  }
+
+ private:
+  void work(bool caller) {
+    std::unique_lock<std::mutex> lock(mu_);
+    for (;;) {
+      if (copies_ != nullptr && next_ < copies_->size()) {
+        const StageCopy c = (*copies_)[next_++];
+        lock.unlock();
+        std::memcpy(c.dst, c.src, c.n);
+        lock.lock();
+        if (--left_ == 0) done_.notify_all();
+        continue;
+      }
+      if (caller || quit_) return;
+      cv_.wait(lock);
+    }
+  }
+  std::mutex mu_;
+  std::condition_variable cv_, done_;
+  std::vector<std::thread> threads_;
+  const std::vector<StageCopy> *copies_ = nullptr;
+  size_t next_ = 0, left_ = 0;
+  bool quit_ = false;
 };
 
 struct BatchRec {
@@ -74,6 +145,12 @@ struct OpenClass {
   uint64_t tickets = 0;
   double kernel_ms = 0;
   std::vector<BatchRec> order;
+  // staging ring, present once a function with pageable sources has joined
+  char *ring = nullptr;
+  uint64_t ring_cap = 0, ring_slots = 0;
+  uint64_t staged_bytes = 0;
+  double stage_ms = 0;
+  std::unique_ptr<StagePool> stagers;
   std::thread feeder;
 };
 
@@ -94,8 +171,11 @@ struct OpenState {
   std::string error_text;
 
   ~OpenState() {
-    for (OpenClass &c : cls)
+    for (OpenClass &c : cls) {
       if (c.feeder.joinable()) c.feeder.join();
+      c.stagers.reset();
+      put_pinned(pool, c.ring, c.ring_cap);
+    }
   }
 };
 
@@ -183,15 +263,57 @@ void drop_generation(ft_pool *p, Generation *g) {
   put_blob(p, g->blob);
 }
 
-// Triggers the next batch of class c. Called with st->mu held, on the pool's device.
-bool launch_batch(OpenState *st, int c) {
+constexpr uint64_t kStagePiece = 256 * 1024;  // longest single copy handed to a helper
+
+struct Prepared {
+  OpenBatch batch;
+  ClassTable T;
+  uint32_t workgroups = 0;
+  bool wait_upload = false;
+  std::vector<StageCopy> copies;
+};
+
+// Copies that bring the pageable bytes of chunk (f, k) into its ring slot.
+void stage_chunk(const ClassPlan &cp, const Func &f, uint64_t k, uint64_t chunk_bytes, char *slot,
+                 std::vector<StageCopy> *copies, uint64_t *bytes) {
+  const uint64_t c0 = k * chunk_bytes;
+  const uint64_t c1 = std::min(c0 + chunk_bytes, f.stream_bytes);
+  uint32_t x = find_xfer(cp.xfers.data(), f.desc_off, f.desc_off + f.ndesc - 1, c0);
+  for (uint64_t pos = c0; pos < c1; ++x) {
+    const Xfer &X = cp.xfers[x];
+    const uint64_t q = pos - X.stream_off;
+    uint64_t take = X.row_bytes * X.rows - q;
+    if (take > c1 - pos) take = c1 - pos;
+    if (X.staged) {
+      // rows of the source, packed in stream order at offset (stream position - c0) of the slot
+      uint64_t r = q / X.row_bytes, c = q % X.row_bytes, left = take, at = pos - c0;
+      while (left > 0) {
+        uint64_t n = std::min(X.row_bytes - c, left);
+        const char *src = reinterpret_cast<const char *>(X.src + r * X.src_pitch + c);
+        *bytes += n;
+        left -= n;
+        for (uint64_t o = 0; o < n; o += kStagePiece)
+          copies->push_back(StageCopy{slot + at + o, src + o, std::min(kStagePiece, n - o)});
+        at += n;
+        r += 1;
+        c = 0;
+      }
+    }
+    pos += take;
+  }
+}
+
+// Decides the next batch of class c and books it (ranks, counter, what it holds).
+// Called with st->mu held.
+bool prepare_batch(OpenState *st, int c, Prepared *out) {
   ft_pool *p = st->pool;
   OpenClass &oc = st->cls[c];
   Generation &g = *oc.gen;
   const ClassPlan &cp = g.plan;
   const uint64_t r0 = g.next_rank;
   const uint64_t r1 = std::min<uint64_t>(r0 + st->batch_chunks, cp.nchunks);
-  ClassTable T = g.table;
+  ClassTable &T = out->T;
+  T = g.table;
   uint64_t t0, t1, acc1;
   uint32_t idx1;
   ticket_of_rank(g, oc.tiles_per_chunk, r0, &t0, &T.skip0, &T.skip_acc0);
@@ -208,32 +330,27 @@ bool launch_batch(OpenState *st, int c) {
     }
     T.phase0 = lo;
   }
-  OpenBatch b;
+  const uint64_t slot0 = oc.ring_slots ? (oc.batches_triggered % (st->depth + 1)) * st->batch_chunks : 0;
+  T.stage_base = reinterpret_cast<uint64_t>(oc.ring);
+  T.stage_rank0 = r0;
+  T.stage_slot0 = slot0;
+  OpenBatch &b = out->batch;
   b.gen = oc.gen;
+  b.lane = (uint32_t)(oc.batches_triggered & 1);
   const bool timing = (st->flags & FT_TIMING) != 0;
   if (get_event(p, false, &b.done) != FT_OK || (timing && (get_event(p, true, &b.t_begin) != FT_OK ||
                                                            get_event(p, true, &b.t_end) != FT_OK))) {
     if (st->error == FT_OK) st->error = FT_EHIP, st->error_text = p->hip_error;
-    return false;
-  }
-  const uint32_t lane = (uint32_t)(oc.batches_triggered & 1);
-  hipStream_t s = lane ? p->ctx->alt_streams[c] : p->ctx->streams[c];
-  hipError_t e = hipSuccess;
-  if (!g.waited_upload[lane]) {
-    e = hipStreamWaitEvent(s, g.uploaded, 0);
-    g.waited_upload[lane] = true;
-  }
-  uint64_t wg = oc.workgroups;
-  if (wg > t1 - t0) wg = t1 - t0;
-  if (e == hipSuccess) e = launch_copy(T, c, (uint32_t)wg, s, b.t_begin, b.t_end);
-  if (e == hipSuccess) e = hipEventRecord(b.done, s);
-  if (e != hipSuccess) {
-    set_error(st, e, "open job batch launch");
     put_event(p, false, b.done);
     put_event(p, true, b.t_begin);
     put_event(p, true, b.t_end);
     return false;
   }
+  out->wait_upload = !g.waited_upload[b.lane];
+  g.waited_upload[b.lane] = true;
+  uint64_t wg = oc.workgroups;
+  if (wg > t1 - t0) wg = t1 - t0;
+  out->workgroups = (uint32_t)wg;
   // what the batch holds, on the host: advances every function's count of triggered chunks
   const uint32_t batch_no = (uint32_t)oc.batches_triggered;
   for (uint64_t r = r0; r < r1; ++r) {
@@ -247,14 +364,28 @@ bool launch_batch(OpenState *st, int c) {
       if (jc.first == fn.job) jc.second += 1, found = true;
     if (!found) b.job_chunks.push_back({fn.job, 1});
     if (st->flags & FT_KEEP) oc.order.push_back(BatchRec{fn.job, fn.func, (uint32_t)k, batch_no});
+    if (fn.staged)
+      stage_chunk(cp, f, k, st->chunk_bytes, oc.ring + (slot0 + (r - r0)) * st->chunk_bytes, &out->copies,
+                  &oc.staged_bytes);
   }
   g.next_rank = r1;
   g.next_counter += 1;
   g.inflight += 1;
   oc.tickets += t1 - t0;
   oc.batches_triggered += 1;
-  oc.inflight.push_back(std::move(b));
   return true;
+}
+
+// Launches a prepared batch; only the class's feeder thread launches, so batches reach
+// their streams in order. Called without st->mu.
+hipError_t launch_batch(ft_pool *p, int c, Prepared &pr) {
+  OpenBatch &b = pr.batch;
+  hipStream_t s = b.lane ? p->ctx->alt_streams[c] : p->ctx->streams[c];
+  hipError_t e = hipSuccess;
+  if (pr.wait_upload) e = hipStreamWaitEvent(s, b.gen->uploaded, 0);
+  if (e == hipSuccess) e = launch_copy(pr.T, c, pr.workgroups, s, b.t_begin, b.t_end);
+  if (e == hipSuccess) e = hipEventRecord(b.done, s);
+  return e;
 }
 
 void feeder_main(OpenState *st, int c) {
@@ -263,8 +394,33 @@ void feeder_main(OpenState *st, int c) {
   OpenClass &oc = st->cls[c];
   std::unique_lock<std::mutex> lock(st->mu);
   for (;;) {
-    while (st->error == FT_OK && oc.inflight.size() < st->depth && oc.gen->next_rank < oc.gen->plan.nchunks)
-      if (!launch_batch(st, c)) break;
+    while (st->error == FT_OK && oc.inflight.size() < st->depth && oc.gen->next_rank < oc.gen->plan.nchunks) {
+      Prepared pr;
+      if (!prepare_batch(st, c, &pr)) break;
+      StagePool *stagers = oc.stagers.get();
+      lock.unlock();
+      // the ring slots of this batch were last used depth + 1 batches ago; at most depth - 1
+      // batches are in flight, so that one is complete
+      if (!pr.copies.empty()) {
+        const auto s0 = std::chrono::steady_clock::now();
+        stagers->run(pr.copies);
+        const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - s0).count();
+        lock.lock();
+        oc.stage_ms += ms;
+        lock.unlock();
+      }
+      const hipError_t e = launch_batch(p, c, pr);
+      lock.lock();
+      if (e != hipSuccess) {
+        set_error(st, e, "open job batch launch");
+        put_event(p, false, pr.batch.done);
+        put_event(p, true, pr.batch.t_begin);
+        put_event(p, true, pr.batch.t_end);
+        pr.batch.gen->inflight -= 1;
+        break;
+      }
+      oc.inflight.push_back(std::move(pr.batch));
+    }
     if (oc.inflight.empty()) {
       // dry (or failed): later arrivals start a sequence of their own
       oc.closed = true;
@@ -298,6 +454,18 @@ void feeder_main(OpenState *st, int c) {
   }
 }
 
+// Pinned ring and helper threads for class c, once, when the first pageable function joins.
+int ensure_ring(ft_pool *p, OpenState *st, int c) {
+  OpenClass &oc = st->cls[c];
+  if (oc.ring != nullptr) return FT_OK;
+  const uint64_t slots = (uint64_t)(st->depth + 1) * st->batch_chunks;
+  int rc = get_pinned(p, slots * st->chunk_bytes, &oc.ring, &oc.ring_cap);
+  if (rc != FT_OK) return rc;
+  oc.ring_slots = slots;
+  oc.stagers.reset(new StagePool(p->stage_threads ? p->stage_threads - 1 : 3));
+  return FT_OK;
+}
+
 void add_functions(OpenClass &oc, uint64_t job_id, const ClassPlan &cp, uint64_t chunk_bytes) {
   for (const Func &f : cp.funcs) {
     OpenFn fn;
@@ -308,6 +476,8 @@ void add_functions(OpenClass &oc, uint64_t job_id, const ClassPlan &cp, uint64_t
     fn.nchunks = f.nchunks;
     fn.next_chunk = 0;
     fn.xfers.assign(cp.xfers.begin() + f.desc_off, cp.xfers.begin() + f.desc_off + f.ndesc);
+    fn.staged = false;
+    for (const Xfer &x : fn.xfers) fn.staged = fn.staged || x.staged != 0;
     oc.fns.push_back(std::move(fn));
   }
   (void)chunk_bytes;
@@ -334,6 +504,10 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
     // the caller's weights, not the gcd-reduced ones: functions of later jobs are weighed against them
     for (Func &f : cp.funcs) f.weight = weights[f.func];
     add_functions(oc, job->id, cp, chunk_bytes);
+    if (plan.has_pageable && c == FT_H2P) {
+      int rc = ensure_ring(p, st.get(), c);
+      if (rc != FT_OK) return rc;
+    }
     const Tuning &tn = p->tuning[c];
     tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
                &oc.tile_bytes, &oc.tiles_per_chunk);
@@ -379,7 +553,8 @@ int open_merge(ft_pool *p, Job *open_job, Job *job, SubmitPlan &plan, const uint
     const size_t before = oc.fns.size();
     add_functions(oc, job->id, cp, st->chunk_bytes);
     std::shared_ptr<Generation> g;
-    int rc = build_generation(p, st.get(), c, user, &g);
+    int rc = (plan.has_pageable && c == FT_H2P) ? ensure_ring(p, st.get(), c) : FT_OK;
+    if (rc == FT_OK) rc = build_generation(p, st.get(), c, user, &g);
     if (rc != FT_OK) {
       oc.fns.resize(before);
       return rc;  // classes merged before this one stay merged; the caller sees the error

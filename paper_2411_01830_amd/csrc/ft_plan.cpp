@@ -256,6 +256,7 @@ bool overlaps(std::vector<Interval> &dst, std::vector<Interval> &src) {
 int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft_desc *descs,
                 uint32_t ndesc, const uint32_t *weights, uint32_t nfunc, uint64_t chunk_bytes,
                 uint32_t flags, SubmitPlan *out) {
+  out->has_pageable = false;
   // ---- pass 1: malformed arguments
   if (nfunc == 0 || weights == nullptr) return FT_EINVAL;
   if (ndesc != 0 && descs == nullptr) return FT_EINVAL;
@@ -265,8 +266,8 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
   for (uint32_t i = 0; i < ndesc; ++i) {
     const ft_desc &d = descs[i];
     if (d.func >= nfunc || d.flags != 0) return FT_EINVAL;
-    if (d.src_space > FT_POOL || d.dst_space > FT_POOL) return FT_EINVAL;
-    if (d.src_space == FT_HOST && d.dst_space == FT_HOST) return FT_EINVAL;
+    if (d.src_space > FT_PAGEABLE || d.dst_space > FT_POOL) return FT_EINVAL;
+    if (d.src_space != FT_POOL && d.dst_space == FT_HOST) return FT_EINVAL;
     if (d.row_bytes == 0 || d.rows == 0) return FT_EINVAL;
     if (d.rows > 1 && (d.src_pitch < d.row_bytes || d.dst_pitch < d.row_bytes)) return FT_EINVAL;
   }
@@ -282,7 +283,8 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
     x.src_pitch = d.rows > 1 ? d.src_pitch : d.row_bytes;
     x.dst_pitch = d.rows > 1 ? d.dst_pitch : d.row_bytes;
     x.stream_off = 0;
-    x._pad = 0;
+    x.staged = d.src_space == FT_PAGEABLE ? 1 : 0;
+    if (x.staged) out->has_pageable = true;
     uint64_t payload;
     if (mul_overflow(d.row_bytes, d.rows, &payload)) return FT_ERANGE;
     for (int side = 0; side < 2; ++side) {
@@ -297,15 +299,21 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
         if (pool.owner(off, ext, &start) == nullptr) return FT_ERANGE;
         used.push_back(start);
         addr = reinterpret_cast<uint64_t>(pool.ptr(off));
+      } else if (space == FT_PAGEABLE) {
+        // read by the library's own threads: only from memory the caller has vouched for
+        bool inside = false;
+        for (const HostWindow &w : windows)
+          if (w.pageable && off >= w.base && end <= w.base + w.bytes) inside = true;
+        if (!inside) return FT_ERANGE;
+        addr = off;
       } else {
-        if (!windows.empty()) {
-          bool inside = false;
-          for (const HostWindow &w : windows)
-            if (off >= w.base && end <= w.base + w.bytes) inside = true;
-          if (!inside) return FT_ERANGE;
-        } else if (off == 0) {
-          return FT_ERANGE;
+        bool any = false, inside = false;
+        for (const HostWindow &w : windows) {
+          if (w.pageable) continue;
+          any = true;
+          if (off >= w.base && end <= w.base + w.bytes) inside = true;
         }
+        if (any ? !inside : off == 0) return FT_ERANGE;
         addr = off;
       }
       if (side == 0) x.src = addr; else x.dst = addr;
@@ -338,7 +346,7 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
     std::vector<uint64_t> stream(nfunc, 0);
     std::vector<uint32_t> count(nfunc, 0);
     auto class_of = [](const ft_desc &d) {
-      return d.src_space == FT_HOST ? FT_H2P : (d.dst_space == FT_HOST ? FT_P2H : FT_P2P);
+      return d.src_space != FT_POOL ? FT_H2P : (d.dst_space == FT_HOST ? FT_P2H : FT_P2P);
     };
     for (uint32_t i = 0; i < ndesc; ++i)
       if (class_of(descs[i]) == c) {

@@ -14,6 +14,7 @@ namespace ft {
 struct HostWindow {
   uint64_t base;
   uint64_t bytes;
+  bool pageable;  // ordinary host memory (FT_PAGEABLE sources), not device-visible pinned memory
 };
 
 struct ClassPlan {
@@ -29,6 +30,7 @@ struct ClassPlan {
 struct SubmitPlan {
   ClassPlan cls[FT_NCLASS];
   std::vector<uint64_t> allocs;  // start offsets of the pool allocations referred to (unique)
+  bool has_pageable = false;     // some source is pageable host memory: needs the staging ring
 };
 
 // Phases and slots for the given functions (nchunks > 0, weight >= 1 each, ascending

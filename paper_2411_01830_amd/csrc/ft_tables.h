@@ -62,7 +62,8 @@ struct Xfer {
   uint64_t src_pitch;
   uint64_t dst_pitch;
   uint64_t stream_off;  // payload bytes of the function's earlier descriptors
-  uint64_t _pad;
+  uint64_t staged;      // 1: src is pageable host memory that the device cannot read; the bytes
+                        // reach it through the staging ring (see ClassTable::stage_base)
 };
 
 // Tickets number only tiles that hold bytes. Tile v of the uniform grid (chunk rank
@@ -107,6 +108,12 @@ struct ClassTable {
   uint64_t skip_acc0;          // where the cursors stand at ticket_base: empty tiles before it,
   uint32_t skip0;              // index of the next run of empty tiles,
   uint32_t phase0;             // and the phase that holds its chunk
+  // Staging ring (pinned host memory, slots of chunk_bytes): chunk rank r of this launch has
+  // slot stage_slot0 + (r - stage_rank0); the host has put the stream bytes of the chunk's
+  // staged descriptors there, each at its offset inside the chunk.
+  uint64_t stage_base;
+  uint64_t stage_rank0;
+  uint64_t stage_slot0;
   uint64_t chunk_bytes;        // C
   uint64_t tile_bytes;         // bytes per ticket, multiple of 16
   uint32_t tiles_per_chunk;

@@ -25,6 +25,7 @@ class GpuEngine:
         self.total = 0
         self.host = None
         self.host_np = None
+        self.pageable_np = None
         self.register_window = register_window
         self.default_flags = 0
         # reuse_memory: device segments and the pinned arena survive close_pool() and are
@@ -46,6 +47,15 @@ class GpuEngine:
                 self.host_np[:] = fill
         if self.pool is not None and self.register_window:
             ft.host_window_add(self.pool, self.host.data_ptr(), nbytes)
+
+    def pageable_arena(self, nbytes, fill=0x3C):
+        """Ordinary (not pinned) host memory for FT_PAGEABLE sources; addresses are offsets into it."""
+        self.pageable_np = np.full(int(nbytes), fill, dtype=np.uint8)
+        if self.pool is not None:
+            ft.pageable_window_add(self.pool, self.pageable_np.ctypes.data, int(nbytes))
+
+    def write_pageable(self, off, data):
+        self.pageable_np[off:off + len(data)] = data
 
     def write_host(self, off, data):
         self.host_np[off:off + len(data)] = data
@@ -92,6 +102,8 @@ class GpuEngine:
         self.total = int(nbytes)
         if self.host is not None and self.register_window:
             ft.host_window_add(self.pool, self.host.data_ptr(), self.host.numel())
+        if self.pageable_np is not None:
+            ft.pageable_window_add(self.pool, self.pageable_np.ctypes.data, len(self.pageable_np))
 
     def pool_grow(self, nbytes):
         t = self._segment(nbytes, self._fill)
@@ -111,6 +123,8 @@ class GpuEngine:
         base = self.host.data_ptr() if self.host is not None else 0
         d["src"][d["src_space"] == 0] += np.uint64(base)
         d["dst"][d["dst_space"] == 0] += np.uint64(base)
+        if np.any(d["src_space"] == 2):
+            d["src"][d["src_space"] == 2] += np.uint64(self.pageable_np.ctypes.data)
         s = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
         return ft.submit_transfers(self.pool, d, weights, int(chunk_bytes),
                                    int(flags) | self.default_flags, s)
@@ -120,6 +134,8 @@ class GpuEngine:
         base = self.host.data_ptr() if self.host is not None else 0
         d["src"][d["src_space"] == 0] += np.uint64(base)
         d["dst"][d["dst_space"] == 0] += np.uint64(base)
+        if np.any(d["src_space"] == 2):
+            d["src"][d["src_space"] == 2] += np.uint64(self.pageable_np.ctypes.data)
         s = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
         return ft.submit_merge(self.pool, open_job, d, weights, int(flags), s)
 

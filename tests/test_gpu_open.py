@@ -201,3 +201,67 @@ def test_open_rejects_log_and_dma(gpu):
             assert ei.value.code == fmt.FT_EINVAL
     finally:
         eng.close()
+
+
+@pytest.mark.parametrize("batch,depth,threads", [(5, 3, 4), (2, 1, 1), (3, 2, 2)])
+def test_pageable_sources_through_the_ring(gpu, batch, depth, threads):
+    """Sources in ordinary host memory (Sec. 6.1, circular pinned buffer): many more batches than
+    ring slots, odd sizes and alignments, a pitched source, pinned and pageable descriptors mixed
+    in one function, and a pageable job merged into a running one. Bytes must match the oracle."""
+    from workloads import FT_PAGEABLE
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 64 * MiB, 192 * MiB, seed=17 + batch)
+    try:
+        C = 64 * KiB
+        page = rng.integers(0, 256, 48 * MiB, dtype=np.uint8)
+        for e in (orc, eng):
+            e.pageable_arena(48 * MiB)
+            e.write_pageable(0, page)
+        binding.set_batch(eng.pool, batch, depth)
+        binding.set_stage_threads(eng.pool, threads)
+
+        def alloc(n):
+            a = orc.slab_alloc(n)
+            assert eng.slab_alloc(n) == a
+            return a
+
+        recs0 = [
+            dict(func=0, src_space=FT_PAGEABLE, dst_space=FT_POOL, src=1, dst=alloc(9 * MiB) + 5, row_bytes=8 * MiB + 333),
+            dict(func=1, src_space=FT_PAGEABLE, dst_space=FT_POOL, src=10 * MiB + 16, dst=alloc(3 * MiB), row_bytes=3 * MiB),
+            # pinned and pageable pieces in one function's stream
+            dict(func=1, src_space=FT_HOST, dst_space=FT_POOL, src=4096 + 3, dst=alloc(1 * MiB) + 1, row_bytes=700001),
+            dict(func=1, src_space=FT_PAGEABLE, dst_space=FT_POOL, src=14 * MiB + 7, dst=alloc(1 * MiB), row_bytes=99),
+            # rows of 200 bytes out of a pitch of 1000, packed at the destination
+            dict(func=2, src_space=FT_PAGEABLE, dst_space=FT_POOL, src=16 * MiB + 9, dst=alloc(2 * MiB) + 2, row_bytes=200,
+                 rows=9000, src_pitch=1000, dst_pitch=200),
+            dict(func=2, src_space=FT_HOST, dst_space=FT_POOL, src=8 * MiB, dst=alloc(4 * MiB), row_bytes=4 * MiB),
+        ]
+        recs1 = [dict(func=0, src_space=FT_PAGEABLE, dst_space=FT_POOL, src=30 * MiB + 11, dst=alloc(2 * MiB) + 3,
+                      row_bytes=1 * MiB + 17)]
+        d0, d1 = make_descs(recs0), make_descs(recs1)
+        orc.wait(orc.submit(d0, [1, 2, 3], C))
+        orc.wait(orc.submit(d1, [9], C))
+        print(f"pageable batch={batch} depth={depth} threads={threads}", flush=True)
+        # outside an open job the ring does not exist
+        with pytest.raises(binding.FtError) as ei:
+            eng.submit(d1, [9], C, 0)
+        assert ei.value.code == fmt.FT_EINVAL
+        j0 = eng.submit(d0, [1, 2, 3], C, fmt.FT_OPEN | fmt.FT_KEEP | fmt.FT_VALIDATE)
+        try:
+            j1 = eng.merge(j0, d1, [9], fmt.FT_KEEP)
+        except binding.FtError as e:
+            assert e.code == fmt.FT_ECLOSED
+            j1 = eng.submit(d1, [9], C, fmt.FT_OPEN | fmt.FT_KEEP)
+        eng.wait(j1)
+        eng.wait(j0)
+        _images_equal(orc, eng)
+        binding.job_release(eng.pool, j0)
+        binding.job_release(eng.pool, j1)
+        # a source outside every pageable window is refused
+        bad = make_descs([dict(func=0, src_space=FT_PAGEABLE, dst_space=FT_POOL, src=48 * MiB - 8, dst=alloc(4096),
+                               row_bytes=64)])
+        with pytest.raises(binding.FtError) as ei:
+            eng.submit(bad, [1], C, fmt.FT_OPEN)
+        assert ei.value.code == fmt.FT_ERANGE
+    finally:
+        eng.close()

@@ -253,3 +253,40 @@ def test_workloads_round_trip_through_definition(name, scale):
     assert np.array_equal(e.pool_mem, e2.pool_mem)
     moved = sum(int(d["rows"]) * int(d["row_bytes"]) for arr in rec.descs.values() for d in arr)
     assert moved == plan.payload_bytes()
+
+
+def test_pageable_source_is_a_plain_copy():
+    """Sec. 6.1's circular pinned buffer is transport: a source in ordinary host memory gives the
+    same result as any other copy (NumPy slicing), chunked or not; it is a source only."""
+    import oracle
+    from oracle import OracleEngine, OracleError
+    from workloads import make_descs
+    rng = np.random.default_rng(77)
+    eng = OracleEngine()
+    eng.host_arena(1 << 16)
+    eng.pageable_arena(1 << 18)
+    eng.pool_create(1 << 20, 4096)
+    data = rng.integers(0, 256, 1 << 18, dtype=np.uint8)
+    eng.write_pageable(0, data)
+    a = eng.slab_alloc(100000)
+    b = eng.slab_alloc(64 * 300)
+    recs = [dict(func=0, src_space=oracle.PAGEABLE, dst_space=oracle.POOL, src=12345, dst=a + 7, row_bytes=90001),
+            dict(func=1, src_space=oracle.PAGEABLE, dst_space=oracle.POOL, src=150000, dst=b, row_bytes=64, rows=300,
+                 src_pitch=200, dst_pitch=64)]
+    before = eng.pool_mem.copy()
+    eng.wait(eng.submit(make_descs(recs), [1, 3], 4096))
+    want = before
+    want[a + 7:a + 7 + 90001] = data[12345:12345 + 90001]
+    rows = np.lib.stride_tricks.as_strided(data[150000:], shape=(300, 64), strides=(200, 1))
+    want[b:b + 64 * 300] = rows.reshape(-1)
+    assert np.array_equal(eng.pool_mem, want)
+    assert oracle.link_class(oracle.PAGEABLE, oracle.POOL) == oracle.H2P
+    for bad in (dict(func=0, src_space=oracle.PAGEABLE, dst_space=oracle.HOST, src=0, dst=0, row_bytes=16),
+                dict(func=0, src_space=oracle.POOL, dst_space=oracle.PAGEABLE, src=a, dst=0, row_bytes=16)):
+        with pytest.raises(OracleError) as ei:
+            eng.submit(make_descs([bad]), [1], 4096)
+        assert ei.value.code == oracle.EINVAL
+    with pytest.raises(OracleError) as ei:
+        eng.submit(make_descs([dict(func=0, src_space=oracle.PAGEABLE, dst_space=oracle.POOL, src=(1 << 18) - 8, dst=a,
+                                    row_bytes=16)]), [1], 4096)
+    assert ei.value.code == oracle.ERANGE
