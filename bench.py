@@ -286,6 +286,49 @@ def batched_triggering(peaks):
     return out
 
 
+def pinned_ring(peaks):
+    """Sec. 6.1, circular pinned buffer: 1 GiB of four functions from ordinary (pageable) host
+    memory into the pool through the open job's ring (2 MiB chunks, batches of 5, 3 queued
+    ahead: a 40 MiB ring), against the runtime's own copy from pageable memory."""
+    import torch
+    from paper_2411_01830_amd import binding as ft, harness
+    from workloads import make_descs
+    total, nf, chunk = 1 << 30, 4, 2 << 20
+    eng = harness.GpuEngine()
+    eng.host_arena(4096)
+    eng.pageable_arena(total, fill=7)
+    eng.pool_create(total + (64 << 20), 1 << 20, fill=None)
+    per = total // nf
+    d = make_descs([dict(func=f, src_space=2, dst_space=1, src=f * per, dst=eng.slab_alloc(per), row_bytes=per)
+                    for f in range(nf)])
+    src_t = torch.from_numpy(eng.pageable_np)
+    dst_t = torch.empty(total, dtype=torch.uint8, device="cuda:0")
+    best = 0.0
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        dst_t.copy_(src_t)
+        torch.cuda.synchronize()
+        best = max(best, total / (time.perf_counter() - t0) / 1e9)
+    out = {"bytes": total, "chunk_bytes": chunk, "batch_chunks": 5, "depth": 3, "ring_MiB": 40,
+           "runtime_copy_from_pageable_GBps": round(best, 2), "ring_GBps": {}}
+    del dst_t
+    for threads in (1, 4, 8):
+        ft.set_batch(eng.pool, 5, 3)
+        ft.set_stage_threads(eng.pool, threads)
+        ts = []
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            eng.wait(eng.submit(d, [1] * nf, chunk, ft.FT_OPEN))
+            ts.append(time.perf_counter() - t0)
+        ts.sort()
+        out["ring_GBps"][f"{threads}_threads"] = round(total / ts[1] / 1e9, 2)
+    out["ring_4_threads_link_frac"] = round(out["ring_GBps"]["4_threads"] / peaks["h2d"], 4)
+    eng.close()
+    return out
+
+
 def cpu_baseline():
     """The CPU oracle, as it stands, on a bounded sample of the same workload: the first
     waves of large_mixed at full size, as many as keep the leg around 10-30 s."""
@@ -404,6 +447,7 @@ def main():
     rp.close()
     if not args.no_extras:
         line["batched_triggering"] = batched_triggering(peaks)
+        line["pinned_ring"] = pinned_ring(peaks)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline()
     print(json.dumps(line))
