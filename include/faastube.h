@@ -150,6 +150,18 @@ int ft_slab_alloc(ft_pool *p, uint64_t nbytes, ft_off_t *off_out);
  * FT_EBUSY if a job that has not been waited for refers to it. */
 int ft_slab_free(ft_pool *p, ft_off_t off);
 
+/*
+ * Give memory back (Sec. 7.1: reserved memory that is no longer needed is reclaimed).
+ * Drops the pool's last segment if no allocation lies in it and hands its base and size
+ * back to the caller, who owns the memory. FT_EBUSY if an allocation lives there,
+ * FT_EINVAL if it is the pool's only segment. First-fit allocation at the lowest offset
+ * keeps the late segments empty, so growth and shrinkage are both at the end.
+ */
+int ft_pool_shrink(ft_pool *p, void **dev_base_out, uint64_t *bytes_out);
+
+/* Bytes of the pool's segments, and bytes of its live allocations (whole slabs). */
+int ft_pool_usage(ft_pool *p, uint64_t *total_bytes_out, uint64_t *live_bytes_out);
+
 /* Device pointer of a pool offset, or NULL if off is outside the pool. */
 void *ft_pool_ptr(ft_pool *p, ft_off_t off);
 
@@ -264,6 +276,46 @@ int ft_job_batches(ft_pool *p, ft_job_t open_job, int link_class, uint64_t *job_
  */
 int ft_slo_weights(const double *data_size, const double *l_slo, const double *l_infer, uint32_t n,
                    double bw_all, uint32_t total, double *rate_out, uint32_t *weights_out);
+
+/* ------------------------------------------------- elastic data store policies (Sec. 7) */
+
+/*
+ * Auto-scaling pool (Sec. 7.1), host only. Per function three histories are kept: the
+ * interval between its requests, the size of its intermediate data, and how many of its
+ * results are held at once; R_window, R_size, R_con are their `quantile`-th percentiles
+ * (nearest rank; 0 = 0.99). ft_sizer_observe(func, t, data_size, concurrency), called
+ * after an execution of the function at time t (seconds), reserves R_size * R_con bytes
+ * until t + R_window (default_window while the function has been seen only once);
+ * ft_sizer_target(t) is the sum of the reservations whose window holds t, at least
+ * min_bytes (the paper keeps 300 MB). The caller grows or shrinks the pool to it.
+ */
+typedef struct ft_sizer ft_sizer;
+int ft_sizer_create(ft_sizer **out, uint64_t min_bytes, double quantile, double default_window);
+int ft_sizer_observe(ft_sizer *s, uint32_t func, double t, uint64_t data_size, uint32_t concurrency);
+int ft_sizer_target(ft_sizer *s, double t, uint64_t *bytes_out);
+int ft_sizer_destroy(ft_sizer *s);
+
+/*
+ * Queue-aware migration (Sec. 7.2), host only. objs: the stored intermediate data, each
+ * with its size, whether it is in GPU memory (resident) and the position in the request
+ * queue of the function that will consume it (0 = next). If resident bytes + incoming
+ * exceed capacity, evict_ids receives, in order, what to move to host memory until they
+ * fit: FT_EVICT_QUEUE_AWARE takes the furthest consumer first (ties: larger id, i.e.
+ * stored later); FT_EVICT_LRU, the yardstick, the smallest id first. If nothing has to
+ * go, FT_EVICT_QUEUE_AWARE lists in reload_ids what to bring back, nearest consumer
+ * first, while it fits entirely. Both arrays hold n entries. The moves themselves are
+ * ordinary pool->host and host->pool transfers.
+ */
+enum { FT_EVICT_QUEUE_AWARE = 0, FT_EVICT_LRU = 1 };
+typedef struct ft_object {
+  uint64_t id;
+  uint64_t bytes;
+  uint64_t queue_pos;
+  uint32_t resident;
+  uint32_t _pad;
+} ft_object;
+int ft_migrate_plan(const ft_object *objs, uint32_t n, uint64_t capacity, uint64_t incoming, uint32_t policy,
+                    uint64_t *evict_ids, uint32_t *n_evict, uint64_t *reload_ids, uint32_t *n_reload);
 
 /*
  * Block until every chunk of the job is visible at its destination (device memory,

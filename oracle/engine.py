@@ -127,6 +127,11 @@ class OracleEngine:
         self.pool_mem = np.concatenate(
             [self.pool_mem, np.full(nbytes, self._fill, dtype=np.uint8)])
 
+    def pool_shrink(self):
+        n = self.pool.shrink()
+        self.pool_mem = self.pool_mem[:len(self.pool_mem) - n].copy()
+        return n
+
     def slab_alloc(self, nbytes):
         return self.pool.alloc(nbytes)
 

@@ -6,9 +6,11 @@ demand. It gives no allocation algorithm. Reading taken here: the pool is an
 ordered list of segments, its logical byte-offset space is their
 concatenation, a request takes the lowest-indexed run of free slabs that is
 long enough and lies inside one segment (first fit), growth appends a
-segment, nothing shrinks.
+segment, and the pool gives memory back (Sec. 7.1: reserved memory that is no
+longer needed is reclaimed) by dropping its last segment when nothing lives in
+it - never the first one.
 """
-from . import OracleError, EINVAL, ENOMEM
+from . import OracleError, EINVAL, ENOMEM, EBUSY
 
 
 class Pool:
@@ -36,6 +38,21 @@ class Pool:
         if nbytes <= 0 or nbytes % self.slab_bytes != 0:
             raise OracleError(EINVAL, "segment must be a positive multiple of slab_bytes")
         self._append(nbytes)
+
+    def shrink(self):
+        """Drop the last segment; returns its size in bytes."""
+        if len(self.segments) < 2:
+            raise OracleError(EINVAL, "the first segment stays")
+        first, n = self.segments[-1]
+        if any(self.used[first:first + n]):
+            raise OracleError(EBUSY, "an allocation lives in the last segment")
+        self.segments.pop()
+        del self.used[first:]
+        return n * self.slab_bytes
+
+    @property
+    def live_bytes(self):
+        return sum(self.allocs.values()) * self.slab_bytes
 
     def alloc(self, nbytes):
         if nbytes <= 0:

@@ -12,7 +12,8 @@ FT_H2P, FT_P2H, FT_P2P = 0, 1, 2
 FT_VALIDATE, FT_LOG, FT_PATH_DMA, FT_TIMING, FT_DETACHED, FT_KEEP, FT_OPEN = 1, 2, 4, 8, 16, 32, 64
 FT_ECLOSED = -7
 
-EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
+EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_shrink", "ft_pool_usage", "ft_sizer_create",
+           "ft_sizer_observe", "ft_sizer_target", "ft_sizer_destroy", "ft_migrate_plan", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
            "ft_pool_ptr", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_submit_transfers", "ft_submit_merge", "ft_set_batch",
            "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
            "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
@@ -50,6 +51,13 @@ def _load():
         "ft_pool_create": (i32, [P(vp), vp, u64, u64, i32]),
         "ft_pool_grow": (i32, [vp, vp, u64]),
         "ft_pool_destroy": (i32, [vp]),
+        "ft_pool_shrink": (i32, [vp, P(vp), P(u64)]),
+        "ft_pool_usage": (i32, [vp, P(u64), P(u64)]),
+        "ft_sizer_create": (i32, [P(vp), u64, C.c_double, C.c_double]),
+        "ft_sizer_observe": (i32, [vp, u32, C.c_double, u64, u32]),
+        "ft_sizer_target": (i32, [vp, C.c_double, P(u64)]),
+        "ft_sizer_destroy": (i32, [vp]),
+        "ft_migrate_plan": (i32, [vp, u32, u64, u64, u32, vp, P(u32), vp, P(u32)]),
         "ft_slab_alloc": (i32, [vp, u64, P(u64)]),
         "ft_slab_free": (i32, [vp, u64]),
         "ft_pool_ptr": (vp, [vp, u64]),
@@ -105,6 +113,56 @@ def pool_create(dev_base, nbytes, slab_bytes, device=0):
 
 def pool_grow(pool, dev_base, nbytes):
     _check(_lib.ft_pool_grow(pool, dev_base, nbytes), pool)
+
+
+def pool_shrink(pool):
+    """(device pointer, bytes) of the segment that was dropped."""
+    base, n = C.c_void_p(), C.c_uint64()
+    _check(_lib.ft_pool_shrink(pool, C.byref(base), C.byref(n)), pool)
+    return base.value, n.value
+
+
+def pool_usage(pool):
+    total, live = C.c_uint64(), C.c_uint64()
+    _check(_lib.ft_pool_usage(pool, C.byref(total), C.byref(live)), pool)
+    return total.value, live.value
+
+
+OBJECT_DTYPE = np.dtype([("id", "<u8"), ("bytes", "<u8"), ("queue_pos", "<u8"), ("resident", "<u4"), ("_pad", "<u4")])
+FT_EVICT_QUEUE_AWARE, FT_EVICT_LRU = 0, 1
+
+
+class Sizer:
+    """Histogram rule of Sec. 7.1 (ft_sizer_*)."""
+
+    def __init__(self, min_bytes, quantile=0.0, default_window=60.0):
+        self._h = C.c_void_p()
+        _check(_lib.ft_sizer_create(C.byref(self._h), min_bytes, quantile, default_window))
+
+    def observe(self, func, t, data_size, concurrency):
+        _check(_lib.ft_sizer_observe(self._h, func, t, data_size, concurrency))
+
+    def target(self, t):
+        out = C.c_uint64()
+        _check(_lib.ft_sizer_target(self._h, t, C.byref(out)))
+        return out.value
+
+    def close(self):
+        if self._h:
+            _lib.ft_sizer_destroy(self._h)
+            self._h = None
+
+
+def migrate_plan(objects, capacity, incoming=0, policy=FT_EVICT_QUEUE_AWARE):
+    """objects: list of dicts id, bytes, queue_pos, resident -> (evict ids, reload ids)."""
+    a = np.zeros(max(len(objects), 1), dtype=OBJECT_DTYPE)
+    for i, o in enumerate(objects):
+        a[i] = (o["id"], o["bytes"], o["queue_pos"], 1 if o["resident"] else 0, 0)
+    ev, rl = np.zeros(len(a), np.uint64), np.zeros(len(a), np.uint64)
+    ne, nr = C.c_uint32(), C.c_uint32()
+    _check(_lib.ft_migrate_plan(a.ctypes.data, len(objects), capacity, incoming, policy, ev.ctypes.data,
+                                C.byref(ne), rl.ctypes.data, C.byref(nr)))
+    return ev[:ne.value].tolist(), rl[:nr.value].tolist()
 
 
 def pool_destroy(pool):

@@ -319,6 +319,20 @@ int ft_pool_grow(ft_pool *p, void *dev_base, uint64_t bytes) {
   return p->slabs.add_segment(dev_base, bytes);
 }
 
+int ft_pool_shrink(ft_pool *p, void **dev_base_out, uint64_t *bytes_out) {
+  if (p == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  return p->slabs.drop_last_segment(dev_base_out, bytes_out);
+}
+
+int ft_pool_usage(ft_pool *p, uint64_t *total_bytes_out, uint64_t *live_bytes_out) {
+  if (p == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  if (total_bytes_out) *total_bytes_out = p->slabs.total_bytes();
+  if (live_bytes_out) *live_bytes_out = p->slabs.live_bytes();
+  return FT_OK;
+}
+
 int ft_pool_destroy(ft_pool *p) {
   if (p == nullptr) return FT_EINVAL;
   int rc = FT_OK;

@@ -26,6 +26,26 @@ int SlabPool::add_segment(void *base, uint64_t bytes) {
   return FT_OK;
 }
 
+int SlabPool::drop_last_segment(void **base_out, uint64_t *bytes_out) {
+  if (segs_.size() < 2) return FT_EINVAL;
+  const Segment s = segs_.back();
+  // a segment without allocations is exactly one free run
+  auto it = free_runs_.find(s.first_slab);
+  if (it == free_runs_.end() || it->second != s.nslabs) return FT_EBUSY;
+  free_runs_.erase(it);
+  segs_.pop_back();
+  total_slabs_ -= s.nslabs;
+  if (base_out) *base_out = s.base;
+  if (bytes_out) *bytes_out = s.bytes;
+  return FT_OK;
+}
+
+uint64_t SlabPool::live_bytes() const {
+  uint64_t n = 0;
+  for (const auto &kv : allocs_) n += kv.second.nslabs;
+  return n * slab_;
+}
+
 const Segment *SlabPool::segment_of_slab(uint64_t slab) const {
   size_t lo = 0, hi = segs_.size();
   if (hi == 0 || slab >= total_slabs_) return nullptr;

@@ -26,6 +26,10 @@ class SlabPool {
 
   SlabPool(uint64_t slab_bytes) : slab_(slab_bytes) {}
   int add_segment(void *base, uint64_t bytes);
+  // Drops the last segment if no allocation lies in it (FT_EBUSY otherwise; FT_EINVAL if
+  // it is the only one): the pool never shrinks below its first segment.
+  int drop_last_segment(void **base_out, uint64_t *bytes_out);
+  uint64_t live_bytes() const;
   int alloc(uint64_t nbytes, uint64_t *off_out);
   int free(uint64_t off);
   // Live allocation containing [off, off+extent), or nullptr. *start_out = its offset.
