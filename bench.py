@@ -329,6 +329,107 @@ def pinned_ring(peaks):
     return out
 
 
+def elastic_store():
+    """Sec. 7 with the library's host-side policies on synthetic traces (the paper's Azure trace
+    is not available; seeded arrivals with quiet and bursty periods and lognormal result sizes
+    stand in for it). Pool sizing: reserved bytes over time under the histogram rule against a
+    caching pool that never gives memory back, and how often a result fitted into what was
+    reserved when it arrived. Migration: consumers that found their input moved out to host
+    memory, queue-aware against least-recently-stored eviction. Also the cost of the
+    allocation calls themselves against native device allocation."""
+    import torch
+    from paper_2411_01830_amd import binding as ft
+    rng = np.random.Generator(np.random.PCG64(241101830 + 7))
+    # ---- pool sizing
+    sizer = ft.Sizer(300 << 20, 0.99, 60.0)
+    horizon, t, events = 3600.0, 0.0, []
+    for f, (rate_quiet, rate_burst, med) in enumerate(((0.002, 4.0, 24 << 20), (0.002, 1.0, 96 << 20), (0.5, 0.5, 6 << 20))):
+        t = 0.0
+        while t < horizon:
+            burst = (t // 300) % 4 == f
+            t += float(rng.exponential(1.0 / (rate_burst if burst else rate_quiet)))
+            size = int(min(max(rng.lognormal(np.log(med), 0.6), 1 << 20), 1 << 30))
+            events.append((t, f, size, int(rng.integers(1, 5 if burst else 2))))
+    events.sort()
+    reserved_sum = held_sum = peak = 0.0
+    hits = 0
+    last_t, cur, held = 0.0, sizer.target(0.0), 300 << 20
+    for (t, f, size, con) in events:
+        if t >= horizon:
+            break
+        cur = sizer.target(t)
+        hits += size * con <= cur
+        reserved_sum += cur * (t - last_t)
+        held = max(held, cur)
+        held_sum += held * (t - last_t)
+        peak = max(peak, cur)
+        last_t = t
+        sizer.observe(f, t, size, con)
+    sizer.close()
+    sizing = {"trace": "3 functions, 3600 s; two are busy for 300 s in every 1200 s and nearly idle otherwise, one is steady; lognormal sizes (synthetic)",
+              "requests": len(events), "mean_reserved_MiB": round(reserved_sum / last_t / 2**20, 1),
+              "never_release_mean_MiB": round(held_sum / last_t / 2**20, 1), "peak_MiB": round(peak / 2**20, 1),
+              "memory_vs_never_release": round(reserved_sum / held_sum, 3),
+              "requests_fitting_reservation": round(hits / len(events), 3)}
+    # ---- migration
+    n, look, cap = 2000, 12, 1 << 30
+    sizes = [int(min(max(rng.lognormal(np.log(96 << 20), 0.7), 1 << 20), 512 << 20)) for _ in range(n)]
+
+    def simulate(policy):
+        objs, stalls, moved = {}, 0, 0
+
+        def view(head, skip=None):
+            return [dict(id=i, bytes=o[0], queue_pos=i - head, resident=o[1]) for i, o in sorted(objs.items()) if i != skip]
+
+        def apply(ev, rl):
+            nonlocal moved
+            for i in ev:
+                objs[i][1] = False
+                moved += objs[i][0]
+            for i in rl:
+                objs[i][1] = True
+                moved += objs[i][0]
+        for i in range(look):
+            apply(ft.migrate_plan(view(0), cap, sizes[i], policy)[0], [])
+            objs[i] = [sizes[i], True]
+        for head in range(n):
+            j = head + look
+            if j < n:
+                apply(ft.migrate_plan(view(head), cap, sizes[j], policy)[0], [])
+                objs[j] = [sizes[j], True]
+            if not objs[head][1]:
+                stalls += 1
+                apply(ft.migrate_plan(view(head, head), cap, sizes[head], policy)[0], [head])
+            del objs[head]
+            apply(*ft.migrate_plan(view(head + 1), cap, 0, policy))
+        return stalls, moved
+    qa, lru = simulate(ft.FT_EVICT_QUEUE_AWARE), simulate(ft.FT_EVICT_LRU)
+    migration = {"trace": f"{n} requests of a two-stage workflow, producers {look} requests ahead, 1 GiB store, "
+                          "lognormal results (median 96 MiB, synthetic)",
+                 "queue_aware": {"stalled_consumers": qa[0], "GiB_moved": round(qa[1] / 2**30, 1)},
+                 "least_recently_stored": {"stalled_consumers": lru[0], "GiB_moved": round(lru[1] / 2**30, 1)}}
+    # ---- allocation cost
+    seg = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    pool = ft.pool_create(seg.data_ptr(), seg.numel(), 1 << 20, 0)
+    t0 = time.perf_counter()
+    offs = [ft.slab_alloc(pool, 8 << 20) for _ in range(100)]
+    for o in offs:
+        ft.slab_free(pool, o)
+    pool_us = (time.perf_counter() - t0) / 200 * 1e6
+    ft.pool_destroy(pool)
+    del seg
+    torch.cuda.empty_cache()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        x = torch.empty(8 << 20, dtype=torch.uint8, device="cuda:0")
+        del x
+        torch.cuda.empty_cache()
+    torch.cuda.synchronize()
+    native_us = (time.perf_counter() - t0) / 20 * 1e6
+    return {"pool_sizing": sizing, "migration": migration,
+            "allocation": {"slab_alloc_or_free_us": round(pool_us, 2), "native_alloc_plus_free_8MiB_us": round(native_us, 1)}}
+
+
 def cpu_baseline():
     """The CPU oracle, as it stands, on a bounded sample of the same workload: the first
     waves of large_mixed at full size, as many as keep the leg around 10-30 s."""
@@ -448,6 +549,7 @@ def main():
     if not args.no_extras:
         line["batched_triggering"] = batched_triggering(peaks)
         line["pinned_ring"] = pinned_ring(peaks)
+        line["elastic_store"] = elastic_store()
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline()
     print(json.dumps(line))
