@@ -430,6 +430,38 @@ def elastic_store():
             "allocation": {"slab_alloc_or_free_us": round(pool_us, 2), "native_alloc_plus_free_8MiB_us": round(native_us, 1)}}
 
 
+def path_planner():
+    """Sec. 6.2, Alg. 1 as a host-side planner (one GPU here, so nothing is moved): bandwidth of the
+    parallel paths it finds on two synthetic 8-GPU topologies and what a selection costs."""
+    from paper_2411_01830_amd import binding as ft
+    n = 8
+    cube = [[0] * n for _ in range(n)]
+    for a, b in ((0, 3), (1, 2), (4, 7), (5, 6), (0, 4), (1, 5), (2, 6), (3, 7)):
+        cube[a][b] = cube[b][a] = 48
+    for a, b in ((0, 1), (0, 2), (1, 3), (2, 3), (4, 5), (4, 6), (5, 7), (6, 7)):
+        cube[a][b] = cube[b][a] = 24
+    mesh = [[0 if a == b else 64 for b in range(n)] for a in range(n)]
+    out = {}
+    for name, topo, hops, (s, d) in (("hybrid_cube_mesh_24_48", cube, 0, (0, 3)), ("full_mesh_64", mesh, 3, (0, 5))):
+        links = ft.Links(topo, hops)
+        paths = links.select(1, s, d)
+        links.release(1)
+        links.select(1, s, d)          # the candidate lists are cached from here on
+        links.release(1)
+        t0 = time.perf_counter()
+        reps = 200
+        for i in range(reps):
+            ft._lib.ft_links_select(links._h, 2 + i, s, d)
+            ft._lib.ft_links_release(links._h, 2 + i)
+        us = (time.perf_counter() - t0) / reps * 1e6
+        links.close()
+        bw = [b for _, b in paths]
+        out[name] = {"pair": [s, d], "direct_GBps": topo[s][d], "paths": len(paths), "parallel_GBps": sum(bw),
+                     "select_plus_release_us": round(us, 1),
+                     "first_chunks_to_paths": ft.stripe_chunks(bw, 12)}
+    return out
+
+
 def cpu_baseline():
     """The CPU oracle, as it stands, on a bounded sample of the same workload: the first
     waves of large_mixed at full size, as many as keep the leg around 10-30 s."""
@@ -550,6 +582,7 @@ def main():
         line["batched_triggering"] = batched_triggering(peaks)
         line["pinned_ring"] = pinned_ring(peaks)
         line["elastic_store"] = elastic_store()
+        line["path_planner"] = path_planner()
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline()
     print(json.dumps(line))

@@ -317,6 +317,43 @@ typedef struct ft_object {
 int ft_migrate_plan(const ft_object *objs, uint32_t n, uint64_t capacity, uint64_t incoming, uint32_t policy,
                     uint64_t *evict_ids, uint32_t *n_evict, uint64_t *reload_ids, uint32_t *n_reload);
 
+/* -------------------------------------- parallel paths between GPUs (Sec. 6.2, Alg. 1) */
+
+/*
+ * Host-only planner; this library moves no data between GPUs. The server's links are a
+ * directed graph: topo[u*n + v] = bandwidth of the link u -> v (0 = none), n <= 16 GPUs.
+ * ft_links_select(func, src, dst) chooses parallel paths for a function that sends from
+ * src to dst: (1) the loop-free paths from src to dst, fewer hops first and then in
+ * lexicographic order of their node sequence, at most max_hops links long (0 = n - 1;
+ * at most 4 when n > 8): a path all of whose links are idle is taken, carries the
+ * bandwidth of its narrowest link, and that much is subtracted from the free bandwidth of
+ * each of its links; this stops when src has no free outgoing or dst no free incoming
+ * bandwidth. (2) If both still have some: a busy path is taken over if exactly one path of
+ * one other function blocks it, that function holds more bandwidth in total than `func`,
+ * and having given the blocking path up it finds an idle path between the same two GPUs
+ * that shares no link with the path wanted; it moves there and `func` takes the path.
+ * ft_links_paths lists a function's current paths (node sequences back to back in
+ * nodes_out, their lengths and bandwidths); ft_links_release gives a function's paths
+ * back; ft_links_free copies the n*n matrix of free bandwidth.
+ * FT_EINVAL: bad sizes, src == dst, a function that already has paths (select) or has
+ * none (paths, release), output arrays too small.
+ */
+typedef struct ft_links ft_links;
+int ft_links_create(ft_links **out, uint32_t n, const uint32_t *topo, uint32_t max_hops);
+int ft_links_select(ft_links *l, uint32_t func, uint32_t src, uint32_t dst);
+int ft_links_paths(ft_links *l, uint32_t func, uint32_t *nodes_out, uint32_t cap_nodes, uint32_t *len_out,
+                   uint32_t *bw_out, uint32_t cap_paths, uint32_t *npaths_out);
+int ft_links_release(ft_links *l, uint32_t func);
+int ft_links_free(ft_links *l, uint32_t *free_out);
+int ft_links_destroy(ft_links *l);
+
+/*
+ * Chunks over parallel paths in proportion to the paths' bandwidths (Sec. 6.2): chunk c
+ * goes to the path with the smallest (sent + 1) / bandwidth, ties to the lower index -
+ * the proportional order of ft_submit_transfers with paths in place of functions.
+ */
+int ft_stripe_chunks(const uint32_t *path_bw, uint32_t npaths, uint64_t nchunks, uint32_t *path_of_chunk);
+
 /*
  * Block until every chunk of the job is visible at its destination (device memory,
  * and host memory for pool->host). A job can be waited for once; unless it was

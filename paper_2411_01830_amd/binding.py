@@ -13,7 +13,9 @@ FT_VALIDATE, FT_LOG, FT_PATH_DMA, FT_TIMING, FT_DETACHED, FT_KEEP, FT_OPEN = 1, 
 FT_ECLOSED = -7
 
 EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_shrink", "ft_pool_usage", "ft_sizer_create",
-           "ft_sizer_observe", "ft_sizer_target", "ft_sizer_destroy", "ft_migrate_plan", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
+           "ft_sizer_observe", "ft_sizer_target", "ft_sizer_destroy", "ft_migrate_plan", "ft_links_create",
+           "ft_links_select", "ft_links_paths", "ft_links_release", "ft_links_free", "ft_links_destroy",
+           "ft_stripe_chunks", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
            "ft_pool_ptr", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_submit_transfers", "ft_submit_merge", "ft_set_batch",
            "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
            "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
@@ -58,6 +60,13 @@ def _load():
         "ft_sizer_target": (i32, [vp, C.c_double, P(u64)]),
         "ft_sizer_destroy": (i32, [vp]),
         "ft_migrate_plan": (i32, [vp, u32, u64, u64, u32, vp, P(u32), vp, P(u32)]),
+        "ft_links_create": (i32, [P(vp), u32, vp, u32]),
+        "ft_links_select": (i32, [vp, u32, u32, u32]),
+        "ft_links_paths": (i32, [vp, u32, vp, u32, vp, vp, u32, P(u32)]),
+        "ft_links_release": (i32, [vp, u32]),
+        "ft_links_free": (i32, [vp, vp]),
+        "ft_links_destroy": (i32, [vp]),
+        "ft_stripe_chunks": (i32, [vp, u32, u64, vp]),
         "ft_slab_alloc": (i32, [vp, u64, P(u64)]),
         "ft_slab_free": (i32, [vp, u64]),
         "ft_pool_ptr": (vp, [vp, u64]),
@@ -163,6 +172,51 @@ def migrate_plan(objects, capacity, incoming=0, policy=FT_EVICT_QUEUE_AWARE):
     _check(_lib.ft_migrate_plan(a.ctypes.data, len(objects), capacity, incoming, policy, ev.ctypes.data,
                                 C.byref(ne), rl.ctypes.data, C.byref(nr)))
     return ev[:ne.value].tolist(), rl[:nr.value].tolist()
+
+
+class Links:
+    """Path planner of Sec. 6.2 (ft_links_*)."""
+
+    def __init__(self, topo, max_hops=0):
+        t = np.ascontiguousarray(np.asarray(topo, dtype=np.uint32))
+        self.n = t.shape[0]
+        self._h = C.c_void_p()
+        _check(_lib.ft_links_create(C.byref(self._h), self.n, t.ctypes.data, max_hops))
+
+    def select(self, func, src, dst):
+        _check(_lib.ft_links_select(self._h, func, src, dst))
+        return self.paths(func)
+
+    def paths(self, func):
+        n = C.c_uint32()
+        nodes, ln, bw = np.zeros(4096, np.uint32), np.zeros(256, np.uint32), np.zeros(256, np.uint32)
+        _check(_lib.ft_links_paths(self._h, func, nodes.ctypes.data, len(nodes), ln.ctypes.data, bw.ctypes.data,
+                                   len(ln), C.byref(n)))
+        out, at = [], 0
+        for i in range(n.value):
+            out.append((tuple(int(x) for x in nodes[at:at + ln[i]]), int(bw[i])))
+            at += int(ln[i])
+        return out
+
+    def release(self, func):
+        _check(_lib.ft_links_release(self._h, func))
+
+    def free(self):
+        f = np.zeros(self.n * self.n, np.uint32)
+        _check(_lib.ft_links_free(self._h, f.ctypes.data))
+        return f.reshape(self.n, self.n).tolist()
+
+    def close(self):
+        if self._h:
+            _lib.ft_links_destroy(self._h)
+            self._h = None
+
+
+def stripe_chunks(path_bw, nchunks):
+    b = np.ascontiguousarray(np.asarray(path_bw, dtype=np.uint32))
+    out = np.zeros(max(nchunks, 1), np.uint32)
+    _check(_lib.ft_stripe_chunks(b.ctypes.data, len(b), nchunks, out.ctypes.data))
+    return out[:nchunks].tolist()
 
 
 def pool_destroy(pool):
