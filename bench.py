@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes the profiler counted per algorithmic byte for the pool->pool kernel of the
 # default workload (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy of known
 # size); see profiles/pmc_hbm_traffic_pool_to_pool_large_mixed.md.
-TRAFFIC_PER_ALGO_BYTE = 1.0092
+TRAFFIC_PER_ALGO_BYTE = 1.0095
 
 
 def parse_args():
@@ -420,14 +420,14 @@ def elastic_store():
     del seg
     torch.cuda.empty_cache()
     t0 = time.perf_counter()
-    for _ in range(20):
-        x = torch.empty(8 << 20, dtype=torch.uint8, device="cuda:0")
+    for _ in range(10):
+        x = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")   # above every caching threshold
         del x
-        torch.cuda.empty_cache()
+        torch.cuda.empty_cache()                                          # hands it back to the driver
     torch.cuda.synchronize()
-    native_us = (time.perf_counter() - t0) / 20 * 1e6
+    native_us = (time.perf_counter() - t0) / 10 * 1e6
     return {"pool_sizing": sizing, "migration": migration,
-            "allocation": {"slab_alloc_or_free_us": round(pool_us, 2), "native_alloc_plus_free_8MiB_us": round(native_us, 1)}}
+            "allocation": {"slab_alloc_or_free_us": round(pool_us, 2), "native_alloc_plus_free_256MiB_us": round(native_us, 1)}}
 
 
 def path_planner():
