@@ -15,14 +15,28 @@ What it follows:
                  proportion to the bandwidth given to each function.
   * engine.py    Sec. 5.1: host<->GPU and intra-GPU passing are copies; the
                  chunks are transport only, so the data result is the plain
-                 definition dst[i] = src[i].
+                 definition dst[i] = src[i]. Sources in ordinary host memory
+                 (Sec. 6.1's circular pinned buffer) are copies like any other.
+  * rate.py      Sec. 6.1, function transfer rate control: least rate from the
+                 SLO, idle bandwidth to the tightest SLO, integer weights.
+  * batches.py   Sec. 6.1, batched transfer triggering: the batches of a link
+                 when functions arrive while it is busy.
+  * store.py     Sec. 7: histogram sizing of the pool, queue-aware choice of
+                 what to move to host memory and back, and the least-recently-
+                 stored rule it is measured against.
+  * paths.py     Sec. 6.2 / Alg. 1: contention-aware parallel paths between two
+                 GPUs and chunk striping in proportion to path bandwidth.
 
 Parity pins (all in tests/, run without a GPU): hand-derived orders under
 tests/golden/, the sort-by-finish-tag brute force, a closed-form rank,
 round-robin and single-function special cases, the within-one-chunk share
 invariant, periodicity, per-byte coverage counts, byte-loop data movement,
-NumPy strided views and a brute-force slab bitmap. The timed bandwidth
-shares have no oracle (they depend on the machine): parity unpinned.
+NumPy strided views and a brute-force slab bitmap; for the later modules
+hand-worked rates, orders, reservations and path selections (tests/golden/),
+a second formulation of the batched order, NumPy's inverted-CDF percentile,
+the paper's own migration example, brute-force path enumeration and SciPy's
+maximum flow as an upper bound. The timed bandwidth shares have no oracle
+(they depend on the machine): parity unpinned.
 """
 
 OK = 0

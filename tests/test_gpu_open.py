@@ -265,3 +265,48 @@ def test_pageable_sources_through_the_ring(gpu, batch, depth, threads):
         assert ei.value.code == fmt.FT_ERANGE
     finally:
         eng.close()
+
+
+def test_merges_from_another_thread_while_the_open_job_is_waited_for(gpu):
+    """ft_wait on an open job must not keep the pool's other calls out: one thread waits for the long
+    job while this one merges small ones into it and waits for each."""
+    import threading
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 160 * MiB, 256 * MiB, seed=41)
+    try:
+        C = 256 * KiB
+        binding.set_batch(eng.pool, 4, 2)
+        big = make_descs(_h2p_job(orc, eng, rng, [48 * MiB, 40 * MiB], 80 * MiB))
+        smalls = [make_descs(_h2p_job(orc, eng, rng, [int(rng.integers(64 * KiB, 900 * KiB))], 80 * MiB)) for _ in range(12)]
+        orc.wait(orc.submit(big, [1, 1], C))
+        for d in smalls:
+            orc.wait(orc.submit(d, [7], C))
+        j0 = eng.submit(big, [1, 1], C, fmt.FT_OPEN | fmt.FT_TIMING)
+        err = []
+
+        def waiter():
+            try:
+                eng.wait(j0)
+            except Exception as e:      # noqa: BLE001
+                err.append(e)
+        th = threading.Thread(target=waiter)
+        th.start()
+        merged = 0
+        for d in smalls:
+            try:
+                j = eng.merge(j0, d, [7])
+                merged += 1
+            except binding.FtError as e:
+                assert e.code == fmt.FT_ECLOSED
+                j = eng.submit(d, [7], C, 0)
+            eng.wait(j)
+        th.join(timeout=60)
+        assert not th.is_alive() and not err
+        st = binding.job_stats(eng.pool, j0)
+        assert st.cls[0].device_ms > 0 and st.cls[0].tickets > 0
+        binding.job_release(eng.pool, j0)
+        _images_equal(orc, eng)
+        print(f"{merged} of {len(smalls)} merged while another thread waited", flush=True)
+        assert merged >= 1
+    finally:
+        eng.close()
