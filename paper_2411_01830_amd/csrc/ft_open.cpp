@@ -512,6 +512,10 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
     tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
                &oc.tile_bytes, &oc.tiles_per_chunk);
     oc.workgroups = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
+    // consecutive batches overlap on the class's two streams, so each launch gets a share of
+    // the host link's in-flight budget: 16 workgroups (contended workload, batches of 2.5 MiB:
+    // 50 GB/s with 64 workgroups per launch, 57 with 16)
+    if (!tn.workgroups && c != FT_P2P) oc.workgroups = 16;
     int rc = build_generation(p, st.get(), c, user, &oc.gen);
     if (rc != FT_OK) {
       for (int k = 0; k < c; ++k)
