@@ -619,7 +619,7 @@ int ft_wait(ft_pool *p, ft_job_t id) {
     it = p->jobs.find(id);
     if (it == p->jobs.end()) return FT_EINVAL;
     job = it->second.get();
-    retire(p, job);
+    retire(p, job);  // also after a failure: nothing of the job is in flight any more
   } else {
     rc = wait_locked(p, job);
   }

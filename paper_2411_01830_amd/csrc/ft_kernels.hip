@@ -576,15 +576,27 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
 
 // A decoded ticket on its way from the first wavefront to the others, in LDS.
 struct WorkSlot {
-  uint64_t t;  // the ticket; >= ntickets: none left
+  // what the common case needs, in the first 32 bytes: one full aligned block
+  uint64_t t;     // the ticket; >= ntickets: none left
+  uint64_t fd;    // destination and
+  uint64_t fs;    // source of the block, or 0 / 0 if the ticket is not of that kind
+  uint64_t _pad;
+  // everything else
   uint64_t b0, b1;
   uint64_t x;
   uint64_t stage;
   Xfer first;
 };
 
-__device__ __forceinline__ void put_work(WorkSlot &slot, uint64_t t, const Work &w) {
+// block_bytes: the size of a full block of this class's copy routines
+__device__ __forceinline__ void put_work(WorkSlot &slot, uint64_t t, const Work &w, uint64_t block_bytes) {
+  const uint64_t p0 = w.b0 - w.first.stream_off;
+  const uint64_t len = w.b1 - w.b0;
+  const uint64_t fd = w.first.dst + p0, fs = w.first.src + p0;
+  const bool fast = w.first.rows == 1 && len == block_bytes && ((fd | fs) & 15) == 0 && p0 + len <= w.first.row_bytes;
   slot.t = t;
+  slot.fd = fast ? fd : 0;
+  slot.fs = fast ? fs : 0;
   slot.b0 = w.b0;
   slot.b1 = w.b1;
   slot.x = w.x;
@@ -592,7 +604,7 @@ __device__ __forceinline__ void put_work(WorkSlot &slot, uint64_t t, const Work 
   slot.first = w.first;
 }
 
-__device__ __forceinline__ uint64_t get_work(const WorkSlot &slot, Work &w) {
+__device__ __forceinline__ void get_work(const WorkSlot &slot, Work &w) {
   w.b0 = uniform64(slot.b0);
   w.b1 = uniform64(slot.b1);
   w.x = (uint32_t)uniform64(slot.x);
@@ -605,7 +617,6 @@ __device__ __forceinline__ uint64_t get_work(const WorkSlot &slot, Work &w) {
   w.first.dst_pitch = uniform64(slot.first.dst_pitch);
   w.first.stream_off = uniform64(slot.first.stream_off);
   w.first.staged = 0;  // already applied
-  return uniform64(slot.t);
 }
 
 // Persistent workgroups. Every ticket, the first included, comes from the counter, so a
@@ -642,28 +653,26 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
     if (tid == 0) first = atomicAdd(T.ticket, 1ull);
     const uint64_t t_first = T.ticket_base + uniform64(first);
     const Work w = decode_ticket(T, CT, pc, sc, t_first);
-    if (tid == 0) put_work(s_work[0], t_first, w);
+    if (tid == 0) put_work(s_work[0], t_first, w, (uint64_t)kThreads * U * 16);
   }
   __syncthreads();
   uint32_t slot = 0;
   while (true) {
-    Work cur;
-    const uint64_t t_cur = get_work(s_work[slot], cur);
+    const uint64_t t_cur = uniform64(s_work[slot].t);
     if (t_cur >= T.ntickets) break;
+    const uint64_t fd = uniform64(s_work[slot].fd), fs = uniform64(s_work[slot].fs);
     uint64_t t_begin = 0;
     if (T.log) t_begin = wall_clock64();
     unsigned long long claimed = 0;
     if (tid == 0) claimed = atomicAdd(T.ticket, 1ull);
 
-    const uint64_t p0 = cur.b0 - cur.first.stream_off;
-    const uint64_t len = cur.b1 - cur.b0;
-    const uint64_t fd = cur.first.dst + p0, fs = cur.first.src + p0;
-    if (cur.first.rows == 1 && len == (uint64_t)kThreads * U * 16 && ((fd | fs) & 15) == 0 &&
-        p0 + len <= cur.first.row_bytes) {
-      // the common case, one full aligned block (64 KiB for pool->pool): straight-line
-      // code from the ticket draw to the last store
+    if (fd != 0) {
+      // the common case, one full aligned block (64 KiB for pool->pool): 32 bytes read
+      // from LDS, then straight-line code from the ticket draw to the last store
       copy_rows_of_vectors<NT, U>(fd, fs, tid);
     } else {
+      Work cur;
+      get_work(s_work[slot], cur);
       uint64_t pos = cur.b0;
       uint32_t x = cur.x;
       Xfer X = cur.first;
@@ -684,7 +693,7 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
       // lane 0 holds the counter's answer; all 64 lanes of this wavefront are enabled
       const uint64_t t_next = T.ticket_base + uniform64(claimed);
       const Work next = decode_ticket(T, CT, pc, sc, t_next);
-      if (tid == 0) put_work(s_work[slot ^ 1], t_next, next);
+      if (tid == 0) put_work(s_work[slot ^ 1], t_next, next, (uint64_t)kThreads * U * 16);
     }
 
     if (T.log) {
