@@ -14,7 +14,9 @@
  *     and no state changes. ft_strerror() names a code.
  *   - "host pointer" / "device pointer" is stated per argument. The library
  *     never takes ownership of caller memory.
- *   - One mutex per pool: calls on one pool from several threads serialise.
+ *   - One mutex per pool: calls on one pool from several threads serialise, except
+ *     that ft_wait gives the mutex up while it blocks. ft_pool_destroy must not run
+ *     beside any other call on the same pool.
  *   - All multi-byte fields are little endian.
  */
 #ifndef FAASTUBE_H
@@ -357,11 +359,13 @@ int ft_stripe_chunks(const uint32_t *path_bw, uint32_t npaths, uint64_t nchunks,
 /*
  * Block until every chunk of the job is visible at its destination (device memory,
  * and host memory for pool->host). A job can be waited for once; unless it was
- * submitted with FT_KEEP/FT_LOG/FT_TIMING the handle is dead afterwards.
+ * submitted with FT_KEEP/FT_LOG/FT_TIMING the handle is dead afterwards. The pool's
+ * lock is not held while the call blocks: other threads may submit, merge and wait for
+ * other jobs of the same pool meanwhile (not destroy the pool).
  */
 int ft_wait(ft_pool *p, ft_job_t job);
 
-/* Drop the record of a kept job (after ft_wait). */
+/* Drop the record of a kept job (after ft_wait; FT_EBUSY while a thread is still inside ft_wait for it). */
 int ft_job_release(ft_pool *p, ft_job_t job);
 
 /* Figures of a kept job; `out` is a host pointer. device_ms is valid after ft_wait. */

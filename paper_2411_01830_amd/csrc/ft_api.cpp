@@ -608,25 +608,34 @@ int ft_wait(ft_pool *p, ft_job_t id) {
   auto it = p->jobs.find(id);
   if (it == p->jobs.end() || it->second->waited) return FT_EINVAL;
   Job *job = it->second.get();
+  // Blocking happens without the pool's mutex, so that other threads can submit, merge and
+  // wait meanwhile. `waited` refuses a second ft_wait on the job, `waiting` a release of it.
+  job->waited = true;
+  job->waiting = true;
   int rc;
   if (job->open) {
-    // the feeder threads never take the pool's mutex; other callers (a merge) must get in
-    std::shared_ptr<OpenState> st = job->open;
-    job->waited = true;  // a second ft_wait on the same job is refused while this one blocks
+    std::shared_ptr<OpenState> st = job->open;  // the feeder threads never take the pool's mutex
     lock.unlock();
     rc = open_wait(p, st, id);
     lock.lock();
-    it = p->jobs.find(id);
-    if (it == p->jobs.end()) return FT_EINVAL;
-    job = it->second.get();
     retire(p, job);  // also after a failure: nothing of the job is in flight any more
   } else {
-    rc = wait_locked(p, job);
+    hipEvent_t done[FT_NCLASS];
+    for (int c = 0; c < FT_NCLASS; ++c) done[c] = job->run[c].used ? job->run[c].ev_done : nullptr;
+    lock.unlock();
+    {
+      DeviceGuard guard(p->device);
+      for (int c = 0; c < FT_NCLASS; ++c)
+        if (done[c] != nullptr) (void)hipEventSynchronize(done[c]);  // an error shows again below
+    }
+    lock.lock();
+    rc = wait_locked(p, job);  // the events have fired: reads times and logs, retires
   }
+  job->waiting = false;
   if (rc != FT_OK) return rc;
   if (!job->keep) {
     release_device_side(p, job);
-    p->jobs.erase(it);
+    p->jobs.erase(id);
   }
   return FT_OK;
 }
@@ -636,6 +645,7 @@ int ft_job_release(ft_pool *p, ft_job_t id) {
   std::lock_guard<std::mutex> lock(p->mu);
   auto it = p->jobs.find(id);
   if (it == p->jobs.end() || !it->second->waited) return FT_EINVAL;
+  if (it->second->waiting) return FT_EBUSY;  // a thread is inside ft_wait for it
   release_device_side(p, it->second.get());
   p->jobs.erase(it);
   return FT_OK;
@@ -700,7 +710,8 @@ int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, ui
   if (p == nullptr || n_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);
   auto it = p->jobs.find(id);
-  if (it == p->jobs.end() || !it->second->waited || !(it->second->flags & FT_LOG)) return FT_EINVAL;
+  if (it == p->jobs.end() || !it->second->waited || it->second->waiting || !(it->second->flags & FT_LOG))
+    return FT_EINVAL;
   const Job *job = it->second.get();
   const ClassRun &r = job->run[link_class];
   const uint64_t nt = r.log_host.size();
@@ -734,7 +745,8 @@ int ft_job_log_workgroups(ft_pool *p, ft_job_t id, int link_class, uint32_t *tic
   if (p == nullptr || nwg_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);
   auto it = p->jobs.find(id);
-  if (it == p->jobs.end() || !it->second->waited || !(it->second->flags & FT_LOG)) return FT_EINVAL;
+  if (it == p->jobs.end() || !it->second->waited || it->second->waiting || !(it->second->flags & FT_LOG))
+    return FT_EINVAL;
   const ClassRun &r = it->second->run[link_class];
   const double ns_per_tick = p->ctx->clock_khz > 0 ? 1.0e6 / p->ctx->clock_khz : 10.0;
   if (ticket_wg)

@@ -49,6 +49,7 @@ struct Job {
   uint32_t flags = 0;
   bool keep = false;
   bool waited = false;
+  bool waiting = false;  // a thread is blocked in ft_wait for this job (the pool's mutex is not held then)
   ClassRun run[FT_NCLASS];
   Blob tables;
   std::vector<uint64_t> allocs;

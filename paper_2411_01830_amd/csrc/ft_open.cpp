@@ -466,12 +466,12 @@ int ensure_ring(ft_pool *p, OpenState *st, int c) {
   return FT_OK;
 }
 
-void add_functions(OpenClass &oc, uint64_t job_id, const ClassPlan &cp, uint64_t chunk_bytes) {
+void add_functions(OpenClass &oc, uint64_t job_id, const ClassPlan &cp) {
   for (const Func &f : cp.funcs) {
     OpenFn fn;
     fn.job = job_id;
     fn.func = f.func;
-    fn.weight = f.weight;  // divided by the gcd of its own job's weights: ratios inside a job are kept;
+    fn.weight = f.weight;  // the caller's weight (the callers below undo the gcd reduction of planning)
     fn.stream_bytes = f.stream_bytes;
     fn.nchunks = f.nchunks;
     fn.next_chunk = 0;
@@ -480,7 +480,6 @@ void add_functions(OpenClass &oc, uint64_t job_id, const ClassPlan &cp, uint64_t
     for (const Xfer &x : fn.xfers) fn.staged = fn.staged || x.staged != 0;
     oc.fns.push_back(std::move(fn));
   }
-  (void)chunk_bytes;
 }
 
 }  // namespace
@@ -496,6 +495,17 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
   uint64_t chunks = 0;
   const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
   std::unique_lock<std::mutex> lock(st->mu);
+  // no feeder runs yet: a failure only has to hand back the tables built so far
+  auto undo = [&](int rc) {
+    bool drained = false;
+    for (OpenClass &oc : st->cls)
+      if (oc.gen) {
+        if (!drained) (void)hipStreamSynchronize(user);  // its upload may still be queued
+        drained = true;
+        drop_generation(p, oc.gen.get());
+      }
+    return rc;
+  };
   for (int c = 0; c < FT_NCLASS; ++c) {
     ClassPlan &cp = plan.cls[c];
     if (cp.nchunks == 0) continue;
@@ -503,10 +513,10 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
     oc.used = true;
     // the caller's weights, not the gcd-reduced ones: functions of later jobs are weighed against them
     for (Func &f : cp.funcs) f.weight = weights[f.func];
-    add_functions(oc, job->id, cp, chunk_bytes);
+    add_functions(oc, job->id, cp);
     if (plan.has_pageable && c == FT_H2P) {
       int rc = ensure_ring(p, st.get(), c);
-      if (rc != FT_OK) return rc;
+      if (rc != FT_OK) return undo(rc);
     }
     const Tuning &tn = p->tuning[c];
     tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
@@ -517,14 +527,7 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
     // 50 GB/s with 64 workgroups per launch, 57 with 16)
     if (!tn.workgroups && c != FT_P2P) oc.workgroups = 16;
     int rc = build_generation(p, st.get(), c, user, &oc.gen);
-    if (rc != FT_OK) {
-      for (int k = 0; k < c; ++k)
-        if (st->cls[k].gen) {
-          (void)hipStreamSynchronize(user);
-          drop_generation(p, st->cls[k].gen.get());
-        }
-      return rc;
-    }
+    if (rc != FT_OK) return undo(rc);
     chunks += cp.nchunks;
     st->arrival[job->id << 2 | (uint64_t)c] = 0;
   }
@@ -548,26 +551,46 @@ int open_merge(ft_pool *p, Job *open_job, Job *job, SubmitPlan &plan, const uint
   // all or nothing: every class the newcomer uses must still have batches to trigger
   for (int c = 0; c < FT_NCLASS; ++c)
     if (plan.cls[c].nchunks > 0 && (!st->cls[c].used || st->cls[c].closed)) return FT_ECLOSED;
+  // Build the new order of every class first and put it in force only when all of them
+  // exist, so that a failure half way leaves the sequence as it was (the feeders cannot
+  // look while the lock is held).
+  struct Pending {
+    int c;
+    size_t fns_before;
+    std::shared_ptr<Generation> gen;
+  };
+  std::vector<Pending> pending;
+  auto roll_back = [&](int rc) {
+    bool drained = false;
+    for (Pending &pd : pending) {
+      st->cls[pd.c].fns.resize(pd.fns_before);
+      if (pd.gen) {
+        if (!drained) (void)hipStreamSynchronize(user);  // its upload may still be queued
+        drained = true;
+        drop_generation(p, pd.gen.get());
+      }
+    }
+    return rc;
+  };
   uint64_t chunks = 0;
   for (int c = 0; c < FT_NCLASS; ++c) {
     ClassPlan &cp = plan.cls[c];
     if (cp.nchunks == 0) continue;
     OpenClass &oc = st->cls[c];
     for (Func &f : cp.funcs) f.weight = weights[f.func];
-    const size_t before = oc.fns.size();
-    add_functions(oc, job->id, cp, st->chunk_bytes);
-    std::shared_ptr<Generation> g;
+    pending.push_back(Pending{c, oc.fns.size(), nullptr});
+    add_functions(oc, job->id, cp);
     int rc = (plan.has_pageable && c == FT_H2P) ? ensure_ring(p, st.get(), c) : FT_OK;
-    if (rc == FT_OK) rc = build_generation(p, st.get(), c, user, &g);
-    if (rc != FT_OK) {
-      oc.fns.resize(before);
-      return rc;  // classes merged before this one stay merged; the caller sees the error
-    }
-    std::shared_ptr<Generation> old = oc.gen;
-    oc.gen = g;
-    if (old->inflight == 0) drop_generation(p, old.get());
-    st->arrival[job->id << 2 | (uint64_t)c] = oc.batches_triggered;
+    if (rc == FT_OK) rc = build_generation(p, st.get(), c, user, &pending.back().gen);
+    if (rc != FT_OK) return roll_back(rc);
     chunks += cp.nchunks;
+  }
+  for (Pending &pd : pending) {
+    OpenClass &oc = st->cls[pd.c];
+    std::shared_ptr<Generation> old = oc.gen;
+    oc.gen = pd.gen;
+    if (old->inflight == 0) drop_generation(p, old.get());
+    st->arrival[job->id << 2 | (uint64_t)pd.c] = oc.batches_triggered;
   }
   st->left[job->id] = chunks;
   lock.unlock();

@@ -310,3 +310,45 @@ def test_merges_from_another_thread_while_the_open_job_is_waited_for(gpu):
         assert merged >= 1
     finally:
         eng.close()
+
+
+def test_closed_jobs_waited_for_from_several_threads(gpu):
+    """ft_wait gives the pool's lock up while it blocks: four threads each wait for a job of their own
+    while this thread keeps submitting; a kept job cannot be released under a waiter's feet."""
+    import threading
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 200 * MiB, 320 * MiB, seed=43)
+    try:
+        C = 512 * KiB
+        jobs = [make_descs(_h2p_job(orc, eng, rng, [int(rng.integers(6 * MiB, 20 * MiB)), 3 * MiB + 5], 100 * MiB))
+                for _ in range(4)]
+        late = [make_descs(_h2p_job(orc, eng, rng, [int(rng.integers(64 * KiB, 2 * MiB))], 100 * MiB)) for _ in range(6)]
+        for d in jobs:
+            orc.wait(orc.submit(d, [1, 3], C))
+        for d in late:
+            orc.wait(orc.submit(d, [2], C))
+        handles = [eng.submit(d, [1, 3], C, fmt.FT_KEEP | fmt.FT_DETACHED) for d in jobs]
+        err = []
+
+        def waiter(j):
+            try:
+                eng.wait(j)
+            except Exception as e:      # noqa: BLE001
+                err.append(e)
+        threads = [threading.Thread(target=waiter, args=(j,)) for j in handles]
+        for th in threads:
+            th.start()
+        for d in late:
+            eng.wait(eng.submit(d, [2], C, 0))
+        for th in threads:
+            th.join(timeout=60)
+            assert not th.is_alive()
+        assert not err, err
+        for j in handles:
+            with pytest.raises(binding.FtError) as ei:
+                eng.wait(j)                      # a job is waited for once
+            assert ei.value.code == fmt.FT_EINVAL
+            binding.job_release(eng.pool, j)
+        _images_equal(orc, eng)
+    finally:
+        eng.close()
