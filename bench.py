@@ -29,10 +29,11 @@ import numpy as np
 
 METRIC = "aggregate GB/s (host->pool, pool->pool) as % of roofline; weighted-share error"
 HBM_PEAK_GBS = 8000.0
-# HBM bytes the profiler counted per algorithmic byte for the pool->pool kernel of the
-# default workload (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy of known
-# size); see profiles/pmc_hbm_traffic_pool_to_pool_large_mixed.md.
-TRAFFIC_PER_ALGO_BYTE = 1.0095
+# HBM bytes the profiler counted per algorithmic byte for the pool->pool kernel, per
+# workload (FETCH_SIZE and WRITE_SIZE runs, each scaled by a plain copy of known size);
+# see profiles/pmc_hbm_traffic_pool_to_pool_<workload>.md. Workloads without such a run
+# report null.
+TRAFFIC_PER_ALGO_BYTE = {"large_mixed": 1.0095, "traffic_crops": 1.408}
 
 
 def parse_args():
@@ -535,6 +536,7 @@ def main():
     }
     # roofline of the pool->pool copy kernel; if this workload has none, of the feature workload below
     roof_src = res if res["cls_bytes"][2] else None
+    roof_name = args.workload
     per = {args.workload: main_sum}
     shares = None
     if not args.no_extras or roof_src is None:
@@ -550,22 +552,22 @@ def main():
             r = time_steps(rq, k, 2, flags)
             per[other] = summarize(other, r, k, rq, peaks)
             if other == "feature" and roof_src is None:
-                roof_src = r
+                roof_src, roof_name = r, "feature"
             if other == "contended":
                 shares = share_error(rq, 0)
             rq.close()
     if roof_src is not None and roof_src["cls_bytes"][2]:
         algo = 2.0 * roof_src["cls_bytes"][2]
+        traffic_factor = TRAFFIC_PER_ALGO_BYTE.get("traffic_crops" if roof_name == "traffic" else roof_name)
         achieved = algo / roof_src["cls_ms"][2] / 1e6
         line["roofline"] = {
-            "bound": "hbm", "kernel": "ft_copy_kernel<true, 2> (pool->pool)",
+            "bound": "hbm", "kernel": "ft_copy_kernel<true, 2> (pool->pool)", "workload": roof_name,
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "algorithmic_bytes_per_launch": round(algo / roof_src["cls_launches"][2]),
             "avg_launch_ms": round(roof_src["cls_ms"][2] / roof_src["cls_launches"][2], 5),
             "launches": roof_src["cls_launches"][2],
-            "traffic": None if TRAFFIC_PER_ALGO_BYTE is None else
-            round(TRAFFIC_PER_ALGO_BYTE * algo / roof_src["cls_launches"][2]),
+            "traffic": None if traffic_factor is None else round(traffic_factor * algo / roof_src["cls_launches"][2]),
             "plain_copy_ceiling_GBps": round(ceiling, 1),
         }
     if res["cls_bytes"][0]:

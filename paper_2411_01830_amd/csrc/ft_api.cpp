@@ -165,6 +165,8 @@ void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, Class
   T->nchunks = cp.nchunks;
   T->nphases = (uint32_t)cp.phases.size();
   T->nfuncs = (uint32_t)cp.funcs.size();
+  T->desc_per = cp.desc_per;
+  T->_pad = 0;
   T->stage_base = 0;
   T->stage_rank0 = 0;
   T->stage_slot0 = 0;
@@ -201,12 +203,15 @@ uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
 }
 
 // short_rows: most of the class's payload sits in pitched descriptors with rows of at
-// most 2 KiB. Those tiles are bound by latency, not bandwidth, and a job of them has
-// few tiles per workgroup, so smaller tiles balance it better. The row-gather routine
-// moves 3 destination granules per lane and pass: a tile of just under 12 KiB is one
-// pass even when its first granule is a partial one.
+// most 2 KiB (a gather of image crops). Such a tile is bound by latency - a pass of the
+// row-gather routine (3 destination granules per lane, just under 12 KiB) is one memory
+// round trip - and by what a tile costs whatever its size: its ticket (the counter hands
+// out about 70 million tickets a second, all workgroups together, so tiles must not be
+// too small), the decode, the barrier. Tiles of 16 passes measured best on the crops of
+// the traffic workload: 63 us against 86 us for one pass per tile; beyond that too few
+// tiles are left per workgroup to balance the launch's end.
 uint64_t default_tile(int cls, bool with_p2p, bool short_rows) {
-  if (cls == FT_P2P) return short_rows ? 3u * 4096u - 16u : 64u * 1024u;
+  if (cls == FT_P2P) return short_rows ? 16u * 4096u - 16u : 64u * 1024u;
   return (with_p2p || cls == FT_P2H) ? 8u * 1024u : 16u * 1024u;
 }
 
@@ -435,6 +440,17 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
     const bool timing = (flags & FT_TIMING) != 0;
     const bool dma = (flags & FT_PATH_DMA) != 0;
 
+    // tile shape per class, then the descriptor table that goes with it
+    const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
+    for (int c = 0; c < FT_NCLASS; ++c) {
+      ClassPlan &cp = plan.cls[c];
+      if (cp.nchunks == 0) continue;
+      ClassRun &r = job->run[c];
+      const Tuning &tn = p->tuning[c];
+      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
+                 &r.tile_bytes, &r.tiles_per_chunk);
+      build_chunk_table(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk);
+    }
     // lay the tables of all classes out in one blob
     Layout lay[FT_NCLASS];
     uint64_t total = 0;
@@ -459,9 +475,6 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       r.used = true;
       char *h = job->tables.host, *d = job->tables.dev;
       const Tuning &tn = p->tuning[c];
-      const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
-      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
-                 &r.tile_bytes, &r.tiles_per_chunk);
       ClassTable &T = r.table;
       fill_tables(cp, lay[c], h, d, &T);
       build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &T.ntickets);

@@ -460,11 +460,6 @@ __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t ta
   }
 }
 
-__device__ __forceinline__ uint64_t uniform64(uint64_t v) {
-  uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-  uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-  return (uint64_t)hi << 32 | lo;
-}
 
 // What a ticket names, decoded: bytes [b0, b1) of one function's stream (empty if
 // b0 >= b1) and the descriptor holding b0.
@@ -482,6 +477,16 @@ __device__ __forceinline__ void into_ring(Xfer &X, uint64_t stage) {
     X.src = stage + X.stream_off;
     X.src_pitch = X.row_bytes;
   }
+}
+
+// A value that is the same in every lane of the wavefront, moved to scalar registers: what
+// is computed from it stays on the scalar unit and table reads indexed by it are scalar
+// loads.
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t uniform64(uint64_t v) {
+  uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (uint64_t)hi << 32 | lo;
 }
 
 // Where a workgroup is in the phase table. The ranks it decodes only grow (its tickets
@@ -513,18 +518,28 @@ struct SkipCursor {
 // Dependent table reads on the way from a ticket to its bytes: the slot; then the
 // function and the chunk's first and last descriptor index side by side; then the
 // descriptor itself (plus a short search when a chunk spans several descriptors).
-__device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTables &CT, PhaseCursor &pc,
-                                              SkipCursor &sc, uint64_t t) {
+//
+// Only the first wavefront decodes, so to the compiler everything that lives across
+// iterations here (the cursors) differs between lanes and would sit in vector registers,
+// its table reads vector loads - which wait behind every store of the tile. The cursors
+// are therefore brought to scalar registers on entry and written back on exit.
+__device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTables &CT, PhaseCursor &pc_v,
+                                              SkipCursor &sc_v, uint64_t t) {
   Work w;
   w.b0 = w.b1 = 0;
   w.x = 0;
   w.stage = 0;
   if (t >= T.ntickets) return w;
+  SkipCursor sc;
+  sc.idx = uniform32(sc_v.idx);
+  sc.acc = uniform64(sc_v.acc);
+  sc.next_at = uniform64(sc_v.next_at);
   while (t >= sc.next_at) {
     sc.acc += CT.skips[sc.idx].gap;
     sc.idx += 1;
     sc.next_at = sc.idx < T.nskips ? CT.skips[sc.idx].at : ~0ull;
   }
+  sc_v = sc;
   const uint64_t v = t + sc.acc;  // tile of the uniform grid
   uint64_t rank, ti;
   if (v < (1ull << 32)) {
@@ -534,7 +549,15 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
     rank = v / T.tiles_per_chunk;
     ti = v - rank * T.tiles_per_chunk;
   }
+  PhaseCursor pc;
+  pc.idx = uniform32(pc_v.idx);
+  pc.slot_off = uniform32(pc_v.slot_off);
+  pc.nslots = uniform32(pc_v.nslots);
+  pc.rank_base = uniform64(pc_v.rank_base);
+  pc.round_base = uniform64(pc_v.round_base);
+  pc.next_base = uniform64(pc_v.next_base);
   while (rank >= pc.next_base) cursor_set(pc, CT.phases, T.nphases, pc.idx + 1);
+  pc_v = pc;
   const uint64_t rel = rank - pc.rank_base;
   uint64_t round;
   uint32_t s;
@@ -552,9 +575,10 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
   if (T.chunk_desc != nullptr) {
     const FT_CONST uint32_t *cd =
         reinterpret_cast<const FT_CONST uint32_t *>(reinterpret_cast<uintptr_t>(T.chunk_desc));
-    const uint64_t e = (uint64_t)CT.slots[s].chunk_off + k;
+    const uint64_t per = T.desc_per;
+    const uint64_t e = ((uint64_t)CT.slots[s].chunk_off - fl + k) * per + fl + (per > 1 ? ti : 0);
     x0 = cd[e];
-    x1 = cd[e + 1];
+    x1 = per > 1 ? x0 : cd[e + 1];  // an entry per tile names the tile's descriptor itself
   } else {
     x0 = CT.funcs[fl].desc_off;
     x1 = x0 + CT.funcs[fl].ndesc - 1;
@@ -680,11 +704,15 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
         const uint64_t p = pos - X.stream_off;
         uint64_t take = X.row_bytes * X.rows - p;
         if (take > cur.b1 - pos) take = cur.b1 - pos;
+        // the next piece's descriptor is on its way (scalar load) while this piece moves
+        const bool more = pos + take < cur.b1;
+        Xfer Xn = X;
+        if (more) Xn = read_xfer(CT.xfers, ++x);
         if (X.rows == 1) copy_piece<NT, U>(X.dst + p, X.src + p, take, tid);
         else copy_rows<NT, U>(X, p, take, tid);
         pos += take;
-        if (pos < cur.b1) {
-          X = read_xfer(CT.xfers, ++x);
+        if (more) {
+          X = Xn;
           into_ring(X, cur.stage);
         }
       }

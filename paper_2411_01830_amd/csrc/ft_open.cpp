@@ -226,7 +226,7 @@ int build_generation(ft_pool *p, OpenState *st, int c, hipStream_t user, std::sh
   }
   int rc = build_phases(cp.funcs, cp.phases, cp.slots, &cp.nchunks);
   if (rc != FT_OK) return rc;
-  build_chunk_table(cp, st->chunk_bytes);
+  build_chunk_table(cp, st->chunk_bytes, oc.tile_bytes, oc.tiles_per_chunk);
   build_skips(cp, st->chunk_bytes, oc.tile_bytes, oc.tiles_per_chunk, &g->skips, &g->ntickets);
   const uint64_t ncounters = (cp.nchunks + st->batch_chunks - 1) / st->batch_chunks;
   const Layout lay = layout_of(cp, 0, ncounters);

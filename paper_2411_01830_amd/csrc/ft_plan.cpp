@@ -32,19 +32,27 @@ static uint64_t rank_of_chunk(const std::vector<Func> &funcs, uint32_t f, uint64
   return rank;
 }
 
-void build_chunk_table(ClassPlan &cp, uint64_t chunk_bytes) {
+void build_chunk_table(ClassPlan &cp, uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t tiles_per_chunk) {
   cp.chunk_desc.clear();
-  if (cp.nchunks + cp.funcs.size() > kMaxChunkTable) return;
-  cp.chunk_desc.reserve(cp.nchunks + cp.funcs.size());
+  cp.desc_per = 1;
+  // A job of many small descriptors gets an entry per tile: the entry is then the tile's
+  // first descriptor itself and the device searches nothing.
+  if (cp.xfers.size() > 2 * cp.nchunks && cp.nchunks * tiles_per_chunk + cp.funcs.size() <= kMaxChunkTable)
+    cp.desc_per = tiles_per_chunk;
+  else if (cp.nchunks + cp.funcs.size() > kMaxChunkTable)
+    return;
+  const uint64_t step = cp.desc_per == 1 ? chunk_bytes : tile_bytes;
+  cp.chunk_desc.reserve(cp.nchunks * cp.desc_per + cp.funcs.size());
   // one forward walk over each function's descriptors
   for (const Func &fn : cp.funcs) {
     const uint32_t last = fn.desc_off + fn.ndesc - 1;
     uint32_t x = fn.desc_off;
-    for (uint64_t k = 0; k < fn.nchunks; ++k) {
-      const uint64_t pos = (fn.chunk_base + k) * chunk_bytes;
-      while (x < last && cp.xfers[x + 1].stream_off <= pos) ++x;
-      cp.chunk_desc.push_back(x);
-    }
+    for (uint64_t k = 0; k < fn.nchunks; ++k)
+      for (uint32_t u = 0; u < cp.desc_per; ++u) {
+        const uint64_t pos = (fn.chunk_base + k) * chunk_bytes + u * step;
+        while (x < last && cp.xfers[x + 1].stream_off <= pos) ++x;
+        cp.chunk_desc.push_back(x);
+      }
     cp.chunk_desc.push_back(last);
   }
 }
@@ -392,7 +400,6 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
       }
     int rc = build_phases(cp.funcs, cp.phases, cp.slots, &cp.nchunks);
     if (rc != FT_OK) return rc;
-    build_chunk_table(cp, chunk_bytes);
   }
   return FT_OK;
 }

@@ -23,6 +23,7 @@ struct ClassPlan {
   std::vector<Func> funcs;
   std::vector<Xfer> xfers;
   std::vector<uint32_t> chunk_desc;  // empty when the job has more chunks than kMaxChunkTable
+  uint32_t desc_per = 1;             // entries per chunk in chunk_desc: 1, or tiles per chunk
   uint64_t nchunks = 0;
   uint64_t payload = 0;
 };
@@ -37,7 +38,7 @@ struct SubmitPlan {
 // caller function id). Divides the weights by their gcd in place. FT_EINVAL if the
 // slot tables would exceed kMaxSlots entries.
 constexpr uint64_t kMaxSlots = 1ull << 22;
-// Most entries the per-chunk descriptor table may have (4 bytes each); jobs with more
+// Most entries the descriptor table per chunk or tile may have (4 bytes each); jobs with more
 // chunks than this search the function's whole descriptor range instead.
 constexpr uint64_t kMaxChunkTable = 1ull << 20;
 int build_phases(std::vector<Func> &funcs, std::vector<Phase> &phases, std::vector<Slot> &slots,
@@ -49,8 +50,11 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
                 uint32_t flags, SubmitPlan *out);
 
 // Per function and chunk of the order, the descriptor holding the chunk's first stream
-// byte (left empty above kMaxChunkTable entries). Needs funcs, xfers and nchunks.
-void build_chunk_table(ClassPlan &cp, uint64_t chunk_bytes);
+// byte - or, for a job with many descriptors per chunk, per tile the descriptor holding
+// the tile's first byte (desc_per = tiles per chunk) - and per function a closing entry,
+// its last descriptor. Left empty above kMaxChunkTable entries. Needs funcs, xfers and
+// nchunks. plan_submit does not call it: the tile shape is chosen afterwards.
+void build_chunk_table(ClassPlan &cp, uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t tiles_per_chunk);
 
 // Runs of empty tiles (past the end of each function's last chunk) for the given tile
 // shape, in ticket order, and the number of tickets left once they are taken out.

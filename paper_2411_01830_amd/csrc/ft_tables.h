@@ -93,9 +93,12 @@ struct ClassTable {
   const Slot *slots;
   const Func *funcs;
   const Xfer *xfers;
-  // per function nchunks + 1 entries: descriptor (index into xfers) holding stream byte
-  // k * C for k < nchunks, then the function's last descriptor. Null when the job has
-  // too many chunks for the table to be worth its memory.
+  // per function nchunks * desc_per + 1 entries: the descriptor (index into xfers) holding
+  // the first stream byte of each chunk (desc_per = 1) or of each tile (desc_per =
+  // tiles_per_chunk; for jobs of many small descriptors, which then need no search), then
+  // the function's last descriptor. Function fl's first entry is
+  // (chunk_off - fl) * desc_per + fl. Null when the job has too many chunks for the table
+  // to be worth its memory.
   const uint32_t *chunk_desc;
   const Skip *skips;           // ascending `at`
   unsigned long long *ticket;  // device counter, zero at launch
@@ -120,6 +123,8 @@ struct ClassTable {
   uint32_t nphases;
   uint32_t nfuncs;
   uint32_t nskips;
+  uint32_t desc_per;
+  uint32_t _pad;
 };
 
 // Ticket -> tile of the uniform grid (host side; the copy kernel keeps a cursor).
