@@ -352,3 +352,54 @@ def test_closed_jobs_waited_for_from_several_threads(gpu):
         _images_equal(orc, eng)
     finally:
         eng.close()
+
+
+def test_open_jobs_of_many_small_descriptors(gpu):
+    """Functions made of hundreds of small transfers (several descriptors per tile, so the library
+    keeps a descriptor entry per tile) in an open job, with a merge that rebuilds the order in the
+    middle of the streams; pool->pool pieces at every alignment."""
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 96 * MiB, 160 * MiB, seed=47)
+    try:
+        C = 128 * KiB
+        binding.set_batch(eng.pool, 3, 2)
+
+        def many(nfunc, per_func, lo, hi, space):
+            recs = []
+            for f in range(nfunc):
+                for _ in range(per_func):
+                    n = int(rng.integers(lo, hi))
+                    a = orc.slab_alloc(n + 32)
+                    assert eng.slab_alloc(n + 32) == a
+                    if space == FT_HOST:
+                        src = int(rng.integers(0, 40 * MiB)) + int(rng.integers(0, 16))
+                    else:
+                        src = orc.slab_alloc(n + 32)
+                        assert eng.slab_alloc(n + 32) == src
+                        fill = rng.integers(0, 256, n + 32, dtype=np.uint8)
+                        orc.write_pool(src, fill)
+                        eng.write_pool(src, fill)
+                        src += int(rng.integers(0, 16))
+                    recs.append(dict(func=f, src_space=space, dst_space=FT_POOL, src=src,
+                                     dst=a + int(rng.integers(0, 16)), row_bytes=n))
+            return make_descs(recs)
+        first = many(3, 260, 3000, 40000, FT_HOST)
+        second = many(2, 150, 500, 9000, FT_HOST)
+        third = many(2, 200, 2000, 30000, FT_POOL)
+        orc.wait(orc.submit(first, [1, 2, 3], C))
+        orc.wait(orc.submit(second, [5, 5], C))
+        orc.wait(orc.submit(third, [1, 4], C))
+        j0 = eng.submit(first, [1, 2, 3], C, fmt.FT_OPEN | fmt.FT_KEEP)
+        try:
+            j1 = eng.merge(j0, second, [5, 5], fmt.FT_KEEP)
+            print("second job joined at batch", binding.job_arrival(eng.pool, j1, 0), flush=True)
+        except binding.FtError as e:
+            assert e.code == fmt.FT_ECLOSED
+            j1 = eng.submit(second, [5, 5], C, fmt.FT_KEEP)
+        j2 = eng.submit(third, [1, 4], C, fmt.FT_OPEN | fmt.FT_KEEP)   # an open pool->pool sequence of its own
+        for j in (j2, j1, j0):
+            eng.wait(j)
+            binding.job_release(eng.pool, j)
+        _images_equal(orc, eng)
+    finally:
+        eng.close()
