@@ -174,6 +174,9 @@ void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, Class
   T->skip_acc0 = 0;
   T->skip0 = 0;
   T->phase0 = 0;
+  T->first_phase = Phase{};
+  T->first_next_base = ~0ull;
+  T->first_skip_at = ~0ull;
 }
 
 bool mostly_short_rows(const ClassPlan &cp) {
@@ -480,6 +483,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &T.ntickets);
       std::memcpy(h + lay[c].skips, r.skips.data(), r.skips.size() * sizeof(Skip));
       T.nskips = (uint32_t)r.skips.size();
+      set_cursor_start(T, cp.phases.data(), (uint32_t)cp.phases.size(), r.skips.data(), T.nskips);
       T.chunk_bytes = chunk_bytes;
       T.tile_bytes = r.tile_bytes;
       T.tiles_per_chunk = r.tiles_per_chunk;

@@ -643,12 +643,15 @@ __device__ __forceinline__ void get_work(const WorkSlot &slot, Work &w) {
   w.first.staged = 0;  // already applied
 }
 
-// Persistent workgroups. Every ticket, the first included, comes from the counter, so a
-// workgroup that the GPU starts late (its CU was busy with other work) delays nothing:
-// the tickets go to whoever is running. (Handing workgroup b ticket b for free saves
-// the opening queue on the atomic, about 1 % of a 100 us launch, but leaves ticket b
-// waiting for workgroup b.) A workgroup holds one ticket beyond the one it is moving:
-// the atomic for ticket i+1 is issued before tile i's loads and read after its stores.
+// Persistent workgroups. Workgroup b starts on ticket b and every later ticket comes from
+// the counter (which therefore hands out the tickets from the grid size on; the host never
+// launches more workgroups than there are tickets). When all workgroups of a launch ask
+// the counter at once it answers them one after the other, about 14 ns each: the last of
+// 256 would wait 4 us for its first tile, against 2 us for the decode alone. A workgroup
+// that the GPU starts late (its CU was busy with other work) holds its first tile back
+// until then, but the launch could not have ended before that workgroup has run anyway.
+// A workgroup holds one ticket beyond the one it is moving: the atomic for ticket i+1 is
+// issued before tile i's loads and read after its stores.
 // A workgroup moves its tile in two phases - every load of the tile, then every store.
 // While the stores drain, the first wavefront alone decodes ticket i+1 (scalar table
 // reads) and leaves the result in LDS; the barrier at the end of the iteration waits
@@ -669,13 +672,17 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
   PhaseCursor pc;
   SkipCursor sc;
   if (lead) {
-    cursor_set(pc, CT.phases, T.nphases, T.phase0);
+    pc.idx = T.phase0;
+    pc.rank_base = T.first_phase.rank_base;
+    pc.round_base = T.first_phase.round_base;
+    pc.slot_off = T.first_phase.slot_off;
+    pc.nslots = T.first_phase.nslots;
+    pc.next_base = T.first_next_base;
     sc.idx = T.skip0;
     sc.acc = T.skip_acc0;
-    sc.next_at = T.skip0 < T.nskips ? CT.skips[T.skip0].at : ~0ull;
-    unsigned long long first = 0;
-    if (tid == 0) first = atomicAdd(T.ticket, 1ull);
-    const uint64_t t_first = T.ticket_base + uniform64(first);
+    sc.next_at = T.first_skip_at;
+    // workgroup b starts on ticket b; the counter hands out the tickets from gridDim.x on
+    const uint64_t t_first = T.ticket_base + blockIdx.x;
     const Work w = decode_ticket(T, CT, pc, sc, t_first);
     if (tid == 0) put_work(s_work[0], t_first, w, (uint64_t)kThreads * U * 16);
   }
@@ -719,7 +726,7 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
     }
     if (lead) {
       // lane 0 holds the counter's answer; all 64 lanes of this wavefront are enabled
-      const uint64_t t_next = T.ticket_base + uniform64(claimed);
+      const uint64_t t_next = T.ticket_base + gridDim.x + uniform64(claimed);
       const Work next = decode_ticket(T, CT, pc, sc, t_next);
       if (tid == 0) put_work(s_work[slot ^ 1], t_next, next, (uint64_t)kThreads * U * 16);
     }

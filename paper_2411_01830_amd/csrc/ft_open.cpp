@@ -330,6 +330,7 @@ bool prepare_batch(OpenState *st, int c, Prepared *out) {
     }
     T.phase0 = lo;
   }
+  set_cursor_start(T, cp.phases.data(), (uint32_t)cp.phases.size(), g.skips.data(), (uint32_t)g.skips.size());
   const uint64_t slot0 = oc.ring_slots ? (oc.batches_triggered % (st->depth + 1)) * st->batch_chunks : 0;
   T.stage_base = reinterpret_cast<uint64_t>(oc.ring);
   T.stage_rank0 = r0;

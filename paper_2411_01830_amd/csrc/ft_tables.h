@@ -111,6 +111,11 @@ struct ClassTable {
   uint64_t skip_acc0;          // where the cursors stand at ticket_base: empty tiles before it,
   uint32_t skip0;              // index of the next run of empty tiles,
   uint32_t phase0;             // and the phase that holds its chunk
+  // copies of phases[phase0], of the next phase's rank_base and of skips[skip0].at (all ones
+  // where there is none): a workgroup's first decode starts without reading those tables
+  Phase first_phase;
+  uint64_t first_next_base;
+  uint64_t first_skip_at;
   // Staging ring (pinned host memory, slots of chunk_bytes): chunk rank r of this launch has
   // slot stage_slot0 + (r - stage_rank0); the host has put the stream bytes of the chunk's
   // staged descriptors there, each at its offset inside the chunk.
@@ -126,6 +131,14 @@ struct ClassTable {
   uint32_t desc_per;
   uint32_t _pad;
 };
+
+// Fills first_phase / first_next_base / first_skip_at from phase0 and skip0 (host side).
+inline void set_cursor_start(ClassTable &T, const Phase *phases, uint32_t nphases, const Skip *skips,
+                             uint32_t nskips) {
+  T.first_phase = phases[T.phase0];
+  T.first_next_base = T.phase0 + 1 < nphases ? phases[T.phase0 + 1].rank_base : ~0ull;
+  T.first_skip_at = T.skip0 < nskips ? skips[T.skip0].at : ~0ull;
+}
 
 // Ticket -> tile of the uniform grid (host side; the copy kernel keeps a cursor).
 inline uint64_t ticket_to_tile(const Skip *skips, uint32_t nskips, uint64_t t) {
