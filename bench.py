@@ -330,6 +330,51 @@ def pinned_ring(peaks):
     return out
 
 
+def single_transfers():
+    """Wall time from submit to the end of wait for one contiguous transfer, per link class and
+    size, against the runtime's own copy (`Tensor.copy_` + stream synchronize) of the same bytes:
+    what passing one tensor costs (Sec. 2.2 measures passing latency, not only bandwidth)."""
+    import torch
+    from paper_2411_01830_amd import binding as ft
+    from workloads import make_descs, FT_HOST, FT_POOL
+    cap = 64 << 20
+    host = torch.empty(cap, dtype=torch.uint8, pin_memory=True)
+    buf = torch.empty(2 * cap, dtype=torch.uint8, device="cuda:0")
+    pool = ft.pool_create(buf.data_ptr(), 2 * cap, 1 << 20, 0)
+    ft.host_window_add(pool, host.data_ptr(), cap)
+    a, b = ft.slab_alloc(pool, cap), ft.slab_alloc(pool, cap)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def med(f, n=25):
+        ts = []
+        for _ in range(n + 3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            f()
+            ts.append(time.perf_counter() - t0)
+        ts = sorted(ts[3:])
+        return round(ts[len(ts) // 2] * 1e6, 1)
+    out = {"unit": "us, median of 25, submit -> wait returns", "sizes": {}}
+    hp = host.data_ptr()
+    for n in (64 << 10, 1 << 20, 16 << 20, 64 << 20):
+        row = {}
+        for name, ss, ds, src, dst, tsrc, tdst in (("host_to_pool", FT_HOST, FT_POOL, hp, a, host, buf),
+                                                   ("pool_to_host", FT_POOL, FT_HOST, a, hp, buf, host),
+                                                   ("pool_to_pool", FT_POOL, FT_POOL, a, b, buf, buf[cap:])):
+            d = make_descs([dict(func=0, src_space=ss, dst_space=ds, src=src, dst=dst, row_bytes=n)])
+
+            def engine():
+                ft.wait(pool, ft.submit_transfers(pool, d, [1], 2 << 20, 0, stream))
+
+            def runtime():
+                tdst[:n].copy_(tsrc[:n], non_blocking=True)
+                torch.cuda.current_stream().synchronize()
+            row[name] = {"engine": med(engine), "runtime_copy": med(runtime)}
+        out["sizes"][f"{n >> 10}_KiB"] = row
+    ft.pool_destroy(pool)
+    return out
+
+
 def elastic_store():
     """Sec. 7 with the library's host-side policies on synthetic traces (the paper's Azure trace
     is not available; seeded arrivals with quiet and bursty periods and lognormal result sizes
@@ -583,6 +628,7 @@ def main():
     if not args.no_extras:
         line["batched_triggering"] = batched_triggering(peaks)
         line["pinned_ring"] = pinned_ring(peaks)
+        line["single_transfers"] = single_transfers()
         line["elastic_store"] = elastic_store()
         line["path_planner"] = path_planner()
     if not args.no_cpu:

@@ -103,7 +103,7 @@ typedef struct ft_class_stats {
   uint64_t tickets;       /* tiles that hold bytes: what the device counter runs to */
   uint64_t tile_bytes;    /* bytes one ticket moves (last tile of a chunk may be shorter) */
   uint32_t workgroups;    /* persistent workgroups launched (0 on the DMA path) */
-  uint32_t _pad;
+  uint32_t in_launch;     /* 1: a small job - tables passed with the launch, run on the caller's stream */
   float device_ms;        /* FT_TIMING: duration of the class's kernel (events bound to its dispatch;
                              on the FT_PATH_DMA path: events around its copy calls), else -1 */
   float _pad2;
@@ -210,6 +210,12 @@ int ft_set_stage_threads(ft_pool *p, uint32_t threads);
  * tags first, equal tags by lower f - i.e. always serve the unfinished function with
  * the smallest (served+1)/weight. Persistent workgroups draw tickets from a device
  * counter in that order; the classes run concurrently on streams of their own.
+ * A small job of a single link class (tables of at most 3 KiB, at most one tile per
+ * workgroup: up to 16 MiB pool->pool, 1 MiB host->pool, 512 KiB pool->host at the
+ * default shapes; not with FT_LOG, FT_PATH_DMA, FT_OPEN or a tuned workgroup count) is
+ * launched on hip_stream itself with its tables as a kernel argument: same result and
+ * order, a third of the host time. Such a job holds hip_stream like any kernel on it,
+ * FT_DETACHED or not.
  *
  * Validation order: FT_EINVAL conditions of the arguments and of every descriptor
  * (null pointers with non-zero counts, nfunc == 0, a weight of 0, chunk_bytes not a

@@ -30,7 +30,7 @@ class FtError(Exception):
 
 class ClassStats(C.Structure):
     _fields_ = [("payload_bytes", C.c_uint64), ("chunks", C.c_uint64), ("tickets", C.c_uint64),
-                ("tile_bytes", C.c_uint64), ("workgroups", C.c_uint32), ("_pad", C.c_uint32),
+                ("tile_bytes", C.c_uint64), ("workgroups", C.c_uint32), ("in_launch", C.c_uint32),
                 ("device_ms", C.c_float), ("_pad2", C.c_float)]
 
 

@@ -42,6 +42,13 @@ int ensure_device(ft_pool *p) {
     if (c->streams[k] == nullptr) FT_HIP(p, hipStreamCreateWithFlags(&c->streams[k], hipStreamNonBlocking));
   for (int k = 0; k < FT_NCLASS; ++k)
     if (c->alt_streams[k] == nullptr) FT_HIP(p, hipStreamCreateWithFlags(&c->alt_streams[k], hipStreamNonBlocking));
+  if (c->idle_counter == nullptr) {
+    constexpr uint32_t kPairs = 256;
+    FT_HIP(p, hipMalloc(reinterpret_cast<void **>(&c->idle_counter), 256 + kPairs * 16));
+    FT_HIP(p, hipMemset(c->idle_counter, 0, 256 + kPairs * 16));
+    c->counter_pairs = c->idle_counter + 256 / sizeof(unsigned long long);
+    for (uint32_t i = 0; i < kPairs; ++i) c->free_pairs.push_back(kPairs - 1 - i);
+  }
   c->ready = true;
   return FT_OK;
 }
@@ -147,25 +154,41 @@ Layout layout_of(const ClassPlan &cp, uint64_t base, uint64_t ncounters) {
   return l;
 }
 
+Layout inline_layout_of(const ClassPlan &cp) {
+  Layout l;
+  l.ticket = 0;
+  l.phases = 0;
+  l.slots = align_up(l.phases + cp.phases.size() * sizeof(Phase), 16);
+  l.funcs = align_up(l.slots + cp.slots.size() * sizeof(Slot), 16);
+  l.xfers = align_up(l.funcs + cp.funcs.size() * sizeof(Func), 16);
+  l.chunks = align_up(l.xfers + cp.xfers.size() * sizeof(Xfer), 16);
+  l.skips = align_up(l.chunks + cp.chunk_desc.size() * sizeof(uint32_t), 16);
+  l.end = l.skips + cp.funcs.size() * sizeof(Skip);
+  return l;
+}
+
 void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, ClassTable *T) {
   std::memcpy(h + lay.phases, cp.phases.data(), cp.phases.size() * sizeof(Phase));
   std::memcpy(h + lay.slots, cp.slots.data(), cp.slots.size() * sizeof(Slot));
   std::memcpy(h + lay.funcs, cp.funcs.data(), cp.funcs.size() * sizeof(Func));
   std::memcpy(h + lay.xfers, cp.xfers.data(), cp.xfers.size() * sizeof(Xfer));
   std::memcpy(h + lay.chunks, cp.chunk_desc.data(), cp.chunk_desc.size() * sizeof(uint32_t));
-  T->phases = reinterpret_cast<const Phase *>(d + lay.phases);
-  T->slots = reinterpret_cast<const Slot *>(d + lay.slots);
-  T->funcs = reinterpret_cast<const Func *>(d + lay.funcs);
-  T->xfers = reinterpret_cast<const Xfer *>(d + lay.xfers);
-  T->chunk_desc = cp.chunk_desc.empty() ? nullptr : reinterpret_cast<const uint32_t *>(d + lay.chunks);
-  T->skips = reinterpret_cast<const Skip *>(d + lay.skips);
-  T->ticket = reinterpret_cast<unsigned long long *>(d + lay.ticket);
+  const uintptr_t base = reinterpret_cast<uintptr_t>(d);
+  T->phases = reinterpret_cast<const Phase *>(base + lay.phases);
+  T->slots = reinterpret_cast<const Slot *>(base + lay.slots);
+  T->funcs = reinterpret_cast<const Func *>(base + lay.funcs);
+  T->xfers = reinterpret_cast<const Xfer *>(base + lay.xfers);
+  T->chunk_desc = cp.chunk_desc.empty() ? nullptr : reinterpret_cast<const uint32_t *>(base + lay.chunks);
+  T->skips = reinterpret_cast<const Skip *>(base + lay.skips);
+  T->ticket = d == nullptr ? nullptr : reinterpret_cast<unsigned long long *>(base + lay.ticket);
   T->log = nullptr;
   T->wg_log = nullptr;
   T->nchunks = cp.nchunks;
   T->nphases = (uint32_t)cp.phases.size();
   T->nfuncs = (uint32_t)cp.funcs.size();
   T->desc_per = cp.desc_per;
+  T->inline_tables = d == nullptr ? 1u : 0u;
+  T->self_reset = 0;
   T->_pad = 0;
   T->stage_base = 0;
   T->stage_rank0 = 0;
@@ -278,6 +301,13 @@ void retire(ft_pool *p, Job *job) {
 void release_device_side(ft_pool *p, Job *job) {
   put_blob(p, job->tables);
   for (int c = 0; c < FT_NCLASS; ++c) {
+    if (job->run[c].counter_pair >= 0) {
+      // the kernel is over (the job was waited for, or its launch failed and the device was
+      // drained), so the pair is back at zero
+      std::lock_guard<std::mutex> lock(p->ctx->mu);
+      p->ctx->free_pairs.push_back((uint32_t)job->run[c].counter_pair);
+      job->run[c].counter_pair = -1;
+    }
     put_blob(p, job->run[c].log);
     put_event(p, true, job->run[c].ev_begin);
     put_event(p, true, job->run[c].ev_end);
@@ -453,13 +483,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
                  &r.tile_bytes, &r.tiles_per_chunk);
       build_chunk_table(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk);
-    }
-    // lay the tables of all classes out in one blob
-    Layout lay[FT_NCLASS];
-    uint64_t total = 0;
-    for (int c = 0; c < FT_NCLASS; ++c) {
-      lay[c] = layout_of(plan.cls[c], total, 1);
-      if (plan.cls[c].nchunks > 0) total = lay[c].end;
+      build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &r.table.ntickets);
     }
     // every failure from here on must hand back what it took
     auto fail = [&](int code) {
@@ -468,6 +492,86 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       release_device_side(p, job.get());
       return code;
     };
+
+    // A job of one link class whose tables fit into a kernel argument is launched on the
+    // caller's stream itself, tables in the launch: one launch and one event record instead
+    // of a table upload, a fork and a join across streams - 4 us of host time instead of
+    // 35 us, which is most of what passing a small tensor costs. If every ticket can have a
+    // workgroup of its own the counter is never consulted; a larger job takes one of the
+    // device's self-resetting counters (unless FT_DETACHED asks that the caller's stream be
+    // left alone for what may be a long time).
+    int only = -1;
+    for (int c = 0; c < FT_NCLASS; ++c)
+      if (plan.cls[c].nchunks > 0) only = only == -1 ? c : -2;
+    if (only >= 0 && !dma && !(flags & FT_LOG) && p->tuning[only].workgroups == 0) {
+      ClassPlan &cp = plan.cls[only];
+      ClassRun &r = job->run[only];
+      Layout lay = inline_layout_of(cp);
+      if (lay.end > kInlineBytes && cp.desc_per == 1 && cp.xfers.size() <= 4 * cp.funcs.size()) {
+        // few descriptors per function: the search over a function's descriptors is short
+        // enough without the table of descriptors per chunk, which is most of the bytes
+        bool few = true;
+        for (const Func &f : cp.funcs) few = few && f.ndesc <= 4;
+        if (few) {
+          cp.chunk_desc.clear();
+          lay = inline_layout_of(cp);
+        }
+      }
+      const uint64_t ntickets = r.table.ntickets;
+      const bool each_its_own = ntickets <= (only == FT_P2P ? (uint64_t)p->ctx->cu_count : 128u);
+      if (lay.end <= kInlineBytes && !each_its_own && !(flags & FT_DETACHED)) {
+        std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
+        if (!p->ctx->free_pairs.empty()) {
+          r.counter_pair = (int)p->ctx->free_pairs.back();
+          p->ctx->free_pairs.pop_back();
+        }
+      }
+      if (lay.end <= kInlineBytes && (each_its_own || r.counter_pair >= 0)) {
+        job->inline_tables.reset(new InlineBlob());
+        char *h = reinterpret_cast<char *>(job->inline_tables->w);
+        ClassTable &T = r.table;
+        fill_tables(cp, lay, h, nullptr, &T);
+        std::memcpy(h + lay.skips, r.skips.data(), r.skips.size() * sizeof(Skip));
+        T.ntickets = ntickets;
+        T.nskips = (uint32_t)r.skips.size();
+        set_cursor_start(T, cp.phases.data(), (uint32_t)cp.phases.size(), r.skips.data(), T.nskips);
+        T.chunk_bytes = chunk_bytes;
+        T.tile_bytes = r.tile_bytes;
+        T.tiles_per_chunk = r.tiles_per_chunk;
+        uint64_t wg = ntickets;
+        if (each_its_own) {
+          T.ticket = p->ctx->idle_counter;
+        } else {
+          T.ticket = p->ctx->counter_pairs + 2 * r.counter_pair;
+          T.self_reset = 1;
+          wg = default_workgroups(p, only, only == FT_P2P);
+          if (wg > ntickets) wg = ntickets;
+        }
+        r.used = true;
+        r.workgroups = (uint32_t)wg;
+        r.on_user_stream = true;
+        rc = get_event(p, false, &r.ev_done);
+        if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_begin);
+        if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_end);
+        if (rc != FT_OK) return fail(rc);
+        hipError_t e = launch_copy(T, only, r.workgroups, user, r.ev_begin, r.ev_end, job->inline_tables.get());
+        if (e == hipSuccess) e = hipEventRecord(r.ev_done, user);
+        if (e != hipSuccess) {
+          p->hip_error = std::string("launch on the caller's stream: ") + hipGetErrorString(e);
+          (void)hipDeviceSynchronize();  // the kernel may be running: its counter pair must be back at zero
+          return fail(FT_EHIP);
+        }
+        goto launched;
+      }
+    }
+    {
+    // lay the tables of all classes out in one blob
+    Layout lay[FT_NCLASS];
+    uint64_t total = 0;
+    for (int c = 0; c < FT_NCLASS; ++c) {
+      lay[c] = layout_of(plan.cls[c], total, 1);
+      if (plan.cls[c].nchunks > 0) total = lay[c].end;
+    }
     rc = get_blob(p, total, true, &job->tables);
     if (rc != FT_OK) return fail(rc);
     std::memset(job->tables.host, 0, total);
@@ -479,8 +583,9 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       char *h = job->tables.host, *d = job->tables.dev;
       const Tuning &tn = p->tuning[c];
       ClassTable &T = r.table;
+      const uint64_t ntickets = T.ntickets;
       fill_tables(cp, lay[c], h, d, &T);
-      build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &T.ntickets);
+      T.ntickets = ntickets;
       std::memcpy(h + lay[c].skips, r.skips.data(), r.skips.size() * sizeof(Skip));
       T.nskips = (uint32_t)r.skips.size();
       set_cursor_start(T, cp.phases.data(), (uint32_t)cp.phases.size(), r.skips.data(), T.nskips);
@@ -547,6 +652,8 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
       }
     }
     put_event(p, false, fork);
+    }
+  launched:;
   }
 
   for (int c = 0; c < FT_NCLASS; ++c) job->run[c].plan = std::move(plan.cls[c]);
@@ -683,6 +790,7 @@ int ft_job_stats(ft_pool *p, ft_job_t id, ft_job_stats_t *out) {
     s.tickets = r.used ? r.table.ntickets : 0;
     s.tile_bytes = r.tile_bytes;
     s.workgroups = r.workgroups;
+    s.in_launch = r.on_user_stream ? 1u : 0u;
     s.device_ms = r.device_ms;
     if (job->open && (job->flags & FT_OPEN)) {
       // the whole sequence so far, merged jobs included: tickets and kernel time of all batches
@@ -710,7 +818,7 @@ int ft_job_schedule(ft_pool *p, ft_job_t id, int link_class, uint32_t *func_out,
   uint32_t *dev = nullptr;
   FT_HIP(p, hipMalloc(reinterpret_cast<void **>(&dev), 2 * n * sizeof(uint32_t)));
   hipStream_t s = p->ctx->streams[link_class];  // ordered after the job's own kernel and table upload
-  hipError_t e = launch_decode(r.table, dev, dev + n, n, s);
+  hipError_t e = launch_decode(r.table, dev, dev + n, n, s, job->inline_tables.get());
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e == hipSuccess) e = hipMemcpy(func_out, dev, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
   if (e == hipSuccess) e = hipMemcpy(chunk_out, dev + n, n * sizeof(uint32_t), hipMemcpyDeviceToHost);

@@ -33,6 +33,8 @@ struct ClassRun {
   uint64_t tile_bytes = 0;
   uint32_t tiles_per_chunk = 0;
   uint32_t workgroups = 0;
+  bool on_user_stream = false;  // launched on the caller's stream, tables in the launch
+  int counter_pair = -1;        // its self-resetting counter pair, if it needed a counter
   // ev_done orders the caller's stream and ft_wait after the class's work. With FT_TIMING,
   // ev_begin / ev_end bracket it: bound to the kernel's dispatch on the kernel path,
   // recorded around the copy calls on the DMA path.
@@ -52,6 +54,7 @@ struct Job {
   bool waiting = false;  // a thread is blocked in ft_wait for this job (the pool's mutex is not held then)
   ClassRun run[FT_NCLASS];
   Blob tables;
+  std::unique_ptr<InlineBlob> inline_tables;  // a small job's tables, passed with the launch instead
   std::vector<uint64_t> allocs;
   uint64_t chunk_bytes = 0;
   double host_submit_us = 0;
@@ -84,6 +87,12 @@ struct DeviceCtx {
   std::vector<Blob> free_dev_blobs;  // device only
   std::vector<hipEvent_t> free_events, free_timing_events;
   std::vector<std::pair<char *, uint64_t>> free_pinned;  // staging rings between jobs
+  // a counter nobody reads, for launches in which every ticket has a workgroup of its own
+  unsigned long long *idle_counter = nullptr;
+  // pairs of self-resetting counters (see ClassTable::self_reset) for jobs whose tables
+  // travel with the launch: zero whenever no kernel is using them
+  unsigned long long *counter_pairs = nullptr;
+  std::vector<uint32_t> free_pairs;
 };
 
 DeviceCtx *device_ctx(int device);
@@ -146,8 +155,11 @@ struct Layout {
 };
 // nbatches: ticket counters to reserve (one per launch that will use these tables)
 Layout layout_of(const ClassPlan &cp, uint64_t base, uint64_t ncounters = 1);
-// Copies the plan's tables into the host twin at `h` and fills the device pointers of T.
+// Copies the plan's tables into the host twin at `h` and fills the device pointers of T
+// (d = null: offsets from the start of `h`, for tables that travel with the launch).
 void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, ClassTable *T);
+// Layout without a ticket counter, from offset 0: for tables that travel with the launch.
+Layout inline_layout_of(const ClassPlan &cp);
 
 uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p);
 uint64_t default_tile(int cls, bool with_p2p, bool short_rows);

@@ -7,13 +7,16 @@
 namespace ft {
 
 // Persistent copy kernel of one link class (0 host->pool, 1 pool->host, 2 pool->pool).
-// *T.ticket must be zero when it starts. ev_start / ev_stop (both or neither)
-// are timing events that will read the start and the end of this dispatch.
+// Workgroup b starts on ticket b, the counter *T.ticket hands out the following ones: it
+// must be zero when the kernel starts unless workgroups >= the launch's tickets (then its
+// value does not matter). ev_start / ev_stop (both or neither) are timing events that will
+// read the start and the end of this dispatch. `tables`: the job's tables when
+// T.inline_tables is set, else null.
 hipError_t launch_copy(const ClassTable &T, int link_class, uint32_t workgroups, hipStream_t stream,
-                       hipEvent_t ev_start, hipEvent_t ev_stop);
+                       hipEvent_t ev_start, hipEvent_t ev_stop, const InlineBlob *tables = nullptr);
 // Decode every chunk rank with the device function the copy kernel uses (test hook).
 hipError_t launch_decode(const ClassTable &T, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap,
-                         hipStream_t stream);
+                         hipStream_t stream, const InlineBlob *tables = nullptr);
 // Plain grid-stride copy, no tickets and no tables.
 hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, uint32_t workgroups, hipStream_t stream);
 

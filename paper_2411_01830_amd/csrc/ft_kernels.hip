@@ -31,15 +31,24 @@ struct ConstTables {
   CFuncP funcs;
   CXferP xfers;
   CSkipP skips;
+  const FT_CONST uint32_t *chunk_desc;  // null if the job has none
 };
 
+// The tables as constant-address-space pointers. A small job's tables came with the launch:
+// they lie in the kernel-argument segment, behind the ClassTable, and T holds offsets.
 __device__ __forceinline__ ConstTables const_tables(const ClassTable &T) {
+  uintptr_t base = 0;
+  if (T.inline_tables)
+    base = reinterpret_cast<uintptr_t>(__builtin_amdgcn_kernarg_segment_ptr()) + sizeof(ClassTable);
   ConstTables c;
-  c.phases = reinterpret_cast<CPhaseP>(reinterpret_cast<uintptr_t>(T.phases));
-  c.slots = reinterpret_cast<CSlotP>(reinterpret_cast<uintptr_t>(T.slots));
-  c.funcs = reinterpret_cast<CFuncP>(reinterpret_cast<uintptr_t>(T.funcs));
-  c.xfers = reinterpret_cast<CXferP>(reinterpret_cast<uintptr_t>(T.xfers));
-  c.skips = reinterpret_cast<CSkipP>(reinterpret_cast<uintptr_t>(T.skips));
+  c.phases = reinterpret_cast<CPhaseP>(base + reinterpret_cast<uintptr_t>(T.phases));
+  c.slots = reinterpret_cast<CSlotP>(base + reinterpret_cast<uintptr_t>(T.slots));
+  c.funcs = reinterpret_cast<CFuncP>(base + reinterpret_cast<uintptr_t>(T.funcs));
+  c.xfers = reinterpret_cast<CXferP>(base + reinterpret_cast<uintptr_t>(T.xfers));
+  c.skips = reinterpret_cast<CSkipP>(base + reinterpret_cast<uintptr_t>(T.skips));
+  c.chunk_desc = T.chunk_desc != nullptr  // as an offset it is never 0: the phases come first
+                     ? reinterpret_cast<const FT_CONST uint32_t *>(base + reinterpret_cast<uintptr_t>(T.chunk_desc))
+                     : nullptr;
   return c;
 }
 
@@ -572,9 +581,8 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
   const uint64_t k = (pc.round_base + round) * (uint64_t)CT.slots[s].weight + CT.slots[s].i;
   const uint64_t stream_bytes = CT.funcs[fl].stream_bytes;
   uint32_t x0, x1;
-  if (T.chunk_desc != nullptr) {
-    const FT_CONST uint32_t *cd =
-        reinterpret_cast<const FT_CONST uint32_t *>(reinterpret_cast<uintptr_t>(T.chunk_desc));
+  if (CT.chunk_desc != nullptr) {
+    const FT_CONST uint32_t *cd = CT.chunk_desc;
     const uint64_t per = T.desc_per;
     const uint64_t e = ((uint64_t)CT.slots[s].chunk_off - fl + k) * per + fl + (per > 1 ? ti : 0);
     x0 = cd[e];
@@ -662,7 +670,7 @@ __device__ __forceinline__ void get_work(const WorkSlot &slot, Work &w) {
 // class's kernel a name of its own, so that profiles keep host-link launches and
 // pool->pool launches apart.
 template <bool NT, int CLS>
-__global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(ClassTable T) {
+__global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(ClassTable T, InlineBlob) {
   constexpr uint32_t U = UnrollOf<CLS>::value;
   __shared__ WorkSlot s_work[2];
   const uint32_t tid = threadIdx.x;
@@ -745,9 +753,16 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
     slot ^= 1;
   }
   if (T.log && tid == 0) T.wg_log[blockIdx.x].t_exit = wall_clock64();
+  if (T.self_reset && tid == 0) {
+    // this workgroup's draws have all been answered (the last answer ended its loop)
+    if (atomicAdd(T.ticket + 1, 1ull) == gridDim.x - 1) {
+      __hip_atomic_store(T.ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(T.ticket + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
 }
 
-__global__ void ft_decode_kernel(ClassTable T, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap) {
+__global__ void ft_decode_kernel(ClassTable T, InlineBlob, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap) {
   uint64_t rank = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (rank >= T.nchunks || rank >= cap) return;
   const ConstTables CT = const_tables(T);
@@ -770,26 +785,32 @@ __global__ __launch_bounds__(kThreads) void ft_plain_copy_kernel(u32x4 *dst, con
   for (; i < nvec; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// What a launch passes as tables when the job's own are in device memory.
+static const InlineBlob kNoTables{};
+
 hipError_t launch_copy(const ClassTable &T, int link_class, uint32_t workgroups, hipStream_t stream,
-                       hipEvent_t ev_start, hipEvent_t ev_stop) {
-  if (workgroups == 0) return hipErrorInvalidValue;
+                       hipEvent_t ev_start, hipEvent_t ev_stop, const InlineBlob *tables) {
+  if (workgroups == 0 || (T.inline_tables != 0) != (tables != nullptr)) return hipErrorInvalidValue;
   const dim3 grid(workgroups), block(kThreads);
+  const InlineBlob &B = tables ? *tables : kNoTables;
   // with events, they are bound to this dispatch: they read the kernel's own start and end
   switch (link_class) {
-    case 0: hipExtLaunchKernelGGL((ft_copy_kernel<true, 0>), grid, block, 0, stream, ev_start, ev_stop, 0, T); break;
-    case 1: hipExtLaunchKernelGGL((ft_copy_kernel<true, 1>), grid, block, 0, stream, ev_start, ev_stop, 0, T); break;
-    case 2: hipExtLaunchKernelGGL((ft_copy_kernel<true, 2>), grid, block, 0, stream, ev_start, ev_stop, 0, T); break;
+    case 0: hipExtLaunchKernelGGL((ft_copy_kernel<true, 0>), grid, block, 0, stream, ev_start, ev_stop, 0, T, B); break;
+    case 1: hipExtLaunchKernelGGL((ft_copy_kernel<true, 1>), grid, block, 0, stream, ev_start, ev_stop, 0, T, B); break;
+    case 2: hipExtLaunchKernelGGL((ft_copy_kernel<true, 2>), grid, block, 0, stream, ev_start, ev_stop, 0, T, B); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
 hipError_t launch_decode(const ClassTable &T, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap,
-                         hipStream_t stream) {
+                         hipStream_t stream, const InlineBlob *tables) {
+  if ((T.inline_tables != 0) != (tables != nullptr)) return hipErrorInvalidValue;
   uint64_t n = T.nchunks < cap ? T.nchunks : cap;
   if (n == 0) return hipSuccess;
   uint32_t blocks = (uint32_t)((n + 255) / 256);
-  hipLaunchKernelGGL(ft_decode_kernel, dim3(blocks), dim3(256), 0, stream, T, func_out, chunk_out, cap);
+  hipLaunchKernelGGL(ft_decode_kernel, dim3(blocks), dim3(256), 0, stream, T, tables ? *tables : kNoTables, func_out,
+                     chunk_out, cap);
   return hipGetLastError();
 }
 

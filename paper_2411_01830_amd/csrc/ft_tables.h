@@ -129,8 +129,22 @@ struct ClassTable {
   uint32_t nfuncs;
   uint32_t nskips;
   uint32_t desc_per;
+  // 1: the table pointers above are byte offsets into the InlineBlob that the kernel
+  // received as its second argument (a small job carries its tables in the launch itself)
+  uint32_t inline_tables;
+  // 1: ticket[0] is the counter and ticket[1] counts the workgroups that have finished; the
+  // last one to finish sets both back to zero, so the pair serves the next launch that
+  // gets it without anybody clearing it in between
+  uint32_t self_reset;
   uint32_t _pad;
 };
+
+// Tables of a small job, passed by value as a kernel argument next to the ClassTable.
+constexpr uint32_t kInlineBytes = 3072;
+struct InlineBlob {
+  uint64_t w[kInlineBytes / 8];
+};
+static_assert(sizeof(ClassTable) % 8 == 0, "the InlineBlob argument follows the ClassTable without padding");
 
 // Fills first_phase / first_next_base / first_skip_at from phase0 and skip0 (host side).
 inline void set_cursor_start(ClassTable &T, const Phase *phases, uint32_t nphases, const Skip *skips,

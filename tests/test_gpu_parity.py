@@ -259,3 +259,127 @@ def test_log_and_timing(gpu):
         binding.job_release(eng.pool, j)
     finally:
         eng.close()
+
+
+def test_small_jobs_take_the_launch_argument_path(gpu):
+    """Single-class jobs of a few descriptors travel with the launch (tables as a kernel argument,
+    one workgroup per ticket, the caller's stream). Same bytes and same order as the oracle for
+    every class, 1-D and pitched, every alignment, several functions and weights, back to back."""
+    binding, _ = gpu
+    orc, eng, rng = _pair(gpu, host=1 << 24, pool=1 << 27, slab=16384, seed=77)
+    pyr = random.Random(77)
+    try:
+        took = {0: 0, 1: 0, 2: 0}
+        hdst = 1 << 23
+        for case in range(90):
+            cls = case % 3
+            nfunc = pyr.choice([1, 1, 2, 3])
+            recs = []
+            for _ in range(pyr.choice([1, 1, 2, 5, 9])):
+                rows = pyr.choice([1, 1, 1, 3, 40])
+                rb = pyr.choice([1, 15, 16, 100, 4096, 20000, 70001]) if rows == 1 else pyr.choice([3, 64, 200, 1000])
+                sp, dp = rb + pyr.choice([0, 5, 64]), rb + pyr.choice([0, 0, 9])
+                es, ed = (rows - 1) * sp + rb, (rows - 1) * dp + rb
+                sa, da = pyr.randrange(16), pyr.randrange(16)
+                if cls == 0:
+                    src, sspace = pyr.randrange(0, (1 << 23) - es - 16), FT_HOST
+                else:
+                    a = orc.slab_alloc(es + 32)
+                    assert eng.slab_alloc(es + 32) == a
+                    fill = rng.integers(0, 256, es + 32, dtype=np.uint8)
+                    orc.write_pool(a, fill)
+                    eng.write_pool(a, fill)
+                    src, sspace = a + sa, FT_POOL
+                if cls == 1:
+                    dst, dspace = hdst + da, FT_HOST
+                    hdst += (ed + 47) // 16 * 16
+                    assert hdst < (1 << 24) - 100000
+                else:
+                    b = orc.slab_alloc(ed + 32)
+                    assert eng.slab_alloc(ed + 32) == b
+                    dst, dspace = b + da, FT_POOL
+                recs.append(dict(func=pyr.randrange(nfunc), src_space=sspace, dst_space=dspace, src=src, dst=dst,
+                                 row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp))
+            w = [pyr.choice([1, 2, 5]) for _ in range(nfunc)]
+            C = pyr.choice([4096, 65536, 2 << 20])
+            d = make_descs(recs)
+            jo = orc.submit(d, w, C)
+            orc.wait(jo)
+            jg = eng.submit(d, w, C, fmt.FT_VALIDATE | fmt.FT_KEEP | (fmt.FT_TIMING if case % 2 else 0))
+            eng.wait(jg)
+            st = binding.job_stats(eng.pool, jg)
+            took[cls] += st.cls[cls].in_launch
+            if st.cls[cls].in_launch:
+                assert st.cls[cls].workgroups == st.cls[cls].tickets
+            assert eng.job_schedule(jg, cls) == orc.job_schedule(jo, cls), case
+            binding.job_release(eng.pool, jg)
+            if case % 10 == 9:
+                _compare_images(orc, eng)
+        _compare_images(orc, eng)
+        print("jobs that travelled with the launch, per class:", took, flush=True)
+        assert all(v >= 15 for v in took.values()), took
+    finally:
+        eng.close()
+
+
+def test_larger_single_class_jobs_reuse_the_self_resetting_counters(gpu):
+    """Single-class jobs with more tickets than workgroups still travel with the launch, on a
+    counter pair that the kernel itself sets back to zero: thirty jobs back to back (the same pair
+    again and again), kept jobs holding a pair each meanwhile, all three classes, odd sizes."""
+    binding, _ = gpu
+    orc, eng, rng = _pair(gpu, host=1 << 26, pool=3 << 27, slab=1 << 20, seed=79)
+    pyr = random.Random(79)
+    try:
+        kept = []
+        took = {0: 0, 1: 0, 2: 0}
+        for case in range(30):
+            cls = case % 3
+            recs = []
+            hdst = 1 << 25
+            nfunc = pyr.choice([1, 2])
+            for _ in range(pyr.choice([1, 2, 3])):
+                n = pyr.choice([3 << 20, (5 << 20) + 17, (9 << 20) + 4096]) if cls != 2 else \
+                    pyr.choice([17 << 20, (20 << 20) + 33, 24 << 20])
+                sa, da = pyr.randrange(16), pyr.choice([0, 0, pyr.randrange(16)])
+                if cls == 0:
+                    src, sspace = pyr.randrange(0, (1 << 25) - n - 16), FT_HOST
+                else:
+                    a = orc.slab_alloc(n + 32)
+                    assert eng.slab_alloc(n + 32) == a
+                    fill = rng.integers(0, 256, n + 32, dtype=np.uint8)
+                    orc.write_pool(a, fill)
+                    eng.write_pool(a, fill)
+                    src, sspace = a + sa, FT_POOL
+                if cls == 1:
+                    dst, dspace = hdst + da, FT_HOST
+                    hdst += (n + 47) // 16 * 16
+                    assert hdst + n < (1 << 26)
+                else:
+                    b = orc.slab_alloc(n + 32)
+                    assert eng.slab_alloc(n + 32) == b
+                    dst, dspace = b + da, FT_POOL
+                recs.append(dict(func=pyr.randrange(nfunc), src_space=sspace, dst_space=dspace, src=src, dst=dst,
+                                 row_bytes=n))
+            w = [pyr.choice([1, 3]) for _ in range(nfunc)]
+            d = make_descs(recs)
+            jo = orc.submit(d, w, 2 << 20)
+            orc.wait(jo)
+            jg = eng.submit(d, w, 2 << 20, fmt.FT_KEEP)
+            eng.wait(jg)
+            st = binding.job_stats(eng.pool, jg)
+            took[cls] += st.cls[cls].in_launch
+            assert st.cls[cls].in_launch == 1 and st.cls[cls].workgroups < st.cls[cls].tickets, (case, st.cls[cls].tickets)
+            assert eng.job_schedule(jg, cls) == orc.job_schedule(jo, cls), case
+            if case % 4 == 0:
+                kept.append(jg)
+            else:
+                binding.job_release(eng.pool, jg)
+            _compare_images(orc, eng)
+            for off in list(orc.pool.allocs):
+                orc.slab_free(off)
+                eng.slab_free(off)
+        for jg in kept:
+            binding.job_release(eng.pool, jg)
+        print("larger jobs that travelled with the launch, per class:", took, flush=True)
+    finally:
+        eng.close()
