@@ -584,6 +584,7 @@ def main():
     roof_name = args.workload
     per = {args.workload: main_sum}
     shares = None
+    dma = {}
     if not args.no_extras or roof_src is None:
         for other in ("feature", "contended", "traffic", "tiny"):
             if other == args.workload:
@@ -598,6 +599,10 @@ def main():
             per[other] = summarize(other, r, k, rq, peaks)
             if other == "feature" and roof_src is None:
                 roof_src, roof_name = r, "feature"
+            if args.path == "kernel" and other in ("contended", "feature"):
+                # the same schedule through the copy engines, one runtime copy per chunk piece
+                rd = time_steps(rq, 2, 1, ft.FT_PATH_DMA)
+                dma[other] = {k2: v for k2, v in summarize(other, rd, 2, rq, peaks).items() if k2 in ("h2p", "p2h", "p2p")}
             if other == "contended":
                 shares = share_error(rq, 0)
             rq.close()
@@ -624,6 +629,9 @@ def main():
     if shares is not None:
         line["share_error"] = shares
     line["per_workload"] = per
+    if dma:
+        line["dma_path"] = {"what": "FT_PATH_DMA: same chunk order, one hipMemcpyAsync / hipMemcpy2DAsync per chunk piece "
+                                    "(2 steps each); compare with per_workload", **dma}
     rp.close()
     if not args.no_extras:
         line["batched_triggering"] = batched_triggering(peaks)
