@@ -189,7 +189,7 @@ void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, Class
   T->desc_per = cp.desc_per;
   T->inline_tables = d == nullptr ? 1u : 0u;
   T->self_reset = 0;
-  T->_pad = 0;
+  T->single = 0;
   T->stage_base = 0;
   T->stage_rank0 = 0;
   T->stage_slot0 = 0;
@@ -538,6 +538,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
         T.chunk_bytes = chunk_bytes;
         T.tile_bytes = r.tile_bytes;
         T.tiles_per_chunk = r.tiles_per_chunk;
+        T.single = cp.funcs.size() == 1 && cp.xfers.size() == 1 && cp.funcs[0].chunk_base == 0 ? 1u : 0u;
         uint64_t wg = ntickets;
         if (each_its_own) {
           T.ticket = p->ctx->idle_counter;

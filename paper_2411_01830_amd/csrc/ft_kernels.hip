@@ -539,6 +539,28 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
   w.x = 0;
   w.stage = 0;
   if (t >= T.ntickets) return w;
+  if (T.single) {
+    // the only run of empty tiles lies behind the last ticket
+    uint64_t rank, ti;
+    if (t < (1ull << 32)) {
+      rank = (uint32_t)t / T.tiles_per_chunk;
+      ti = (uint32_t)t - (uint32_t)rank * T.tiles_per_chunk;
+    } else {
+      rank = t / T.tiles_per_chunk;
+      ti = t - rank * T.tiles_per_chunk;
+    }
+    w.first = read_xfer(CT.xfers, 0);
+    const uint64_t stream_bytes = w.first.row_bytes * w.first.rows;
+    const uint64_t c0 = rank * T.chunk_bytes;
+    uint64_t lo = ti * T.tile_bytes, hi = lo + T.tile_bytes;
+    if (hi > T.chunk_bytes) hi = T.chunk_bytes;
+    uint64_t b0 = c0 + lo, b1 = c0 + hi;
+    if (b1 > stream_bytes) b1 = stream_bytes;
+    if (b0 >= b1) return w;
+    w.b0 = b0;
+    w.b1 = b1;
+    return w;
+  }
   SkipCursor sc;
   sc.idx = uniform32(sc_v.idx);
   sc.acc = uniform64(sc_v.acc);

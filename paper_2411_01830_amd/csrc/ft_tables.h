@@ -136,7 +136,10 @@ struct ClassTable {
   // last one to finish sets both back to zero, so the pair serves the next launch that
   // gets it without anybody clearing it in between
   uint32_t self_reset;
-  uint32_t _pad;
+  // 1: one function with one descriptor (xfers[0]) and no chunks triggered before: tile v
+  // is stream bytes [v / tiles_per_chunk * chunk_bytes + v % tiles_per_chunk * tile_bytes, ...)
+  // of that descriptor and ticket t is tile t, so the decode reads no schedule table
+  uint32_t single;
 };
 
 // Tables of a small job, passed by value as a kernel argument next to the ClassTable.
