@@ -210,12 +210,13 @@ int ft_set_stage_threads(ft_pool *p, uint32_t threads);
  * tags first, equal tags by lower f - i.e. always serve the unfinished function with
  * the smallest (served+1)/weight. Persistent workgroups draw tickets from a device
  * counter in that order; the classes run concurrently on streams of their own.
- * A small job of a single link class (tables of at most 3 KiB, at most one tile per
- * workgroup: up to 16 MiB pool->pool, 1 MiB host->pool, 512 KiB pool->host at the
- * default shapes; not with FT_LOG, FT_PATH_DMA, FT_OPEN or a tuned workgroup count) is
- * launched on hip_stream itself with its tables as a kernel argument: same result and
- * order, a third of the host time. Such a job holds hip_stream like any kernel on it,
- * FT_DETACHED or not.
+ * A job of a single link class whose tables fit 3 KiB (not with FT_LOG, FT_PATH_DMA,
+ * FT_OPEN or a tuned workgroup count) is launched on hip_stream itself with its tables
+ * as a kernel argument: same result and order, a tenth of the host time. If it has at
+ * most one tile per workgroup (256 tiles pool->pool, 64 host->pool, 128 pool->host) it
+ * needs no counter; a larger one takes one of 256 self-clearing counter pairs per device
+ * (and the ordinary route if none is free or if FT_DETACHED is set, since the job holds
+ * hip_stream like any kernel on it).
  *
  * Validation order: FT_EINVAL conditions of the arguments and of every descriptor
  * (null pointers with non-zero counts, nfunc == 0, a weight of 0, chunk_bytes not a
