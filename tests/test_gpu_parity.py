@@ -383,3 +383,76 @@ def test_larger_single_class_jobs_reuse_the_self_resetting_counters(gpu):
         print("larger jobs that travelled with the launch, per class:", took, flush=True)
     finally:
         eng.close()
+
+
+def test_random_sequences_of_mixed_jobs(gpu):
+    """Sixty jobs per seed, each a random mix of classes, sizes from bytes to MiB, pitched and plain,
+    every alignment, random weights, chunk sizes, tile sizes and workgroup counts (tuned and default, so
+    both launch routes are taken), allocations freed and taken again in between. After every tenth job
+    the whole host image and the whole pool image are the oracle's."""
+    binding, _ = gpu
+    for seed in (101, 102, 103):
+        orc, eng, rng = _pair(gpu, host=1 << 25, pool=1 << 28, slab=1 << 16, seed=seed)
+        pyr = random.Random(seed)
+        try:
+            live = []
+            for job in range(60):
+                hdst = 1 << 24
+                recs = []
+                nfunc = pyr.choice([1, 2, 3, 6])
+                classes = pyr.choice([[0], [1], [2], [0, 2], [0, 1, 2]])
+                for _ in range(pyr.choice([1, 2, 4, 12])):
+                    cls = pyr.choice(classes)
+                    rows = pyr.choice([1, 1, 1, 2, 17, 120])
+                    if rows == 1:
+                        rb = pyr.choice([1, 9, 16, 250, 4096, 70000, 300001, (1 << 20) + 5, 3 << 20])
+                    else:
+                        rb = pyr.choice([2, 16, 31, 64, 190, 512, 1100, 5000])
+                    sp = rb + pyr.choice([0, 0, 3, 64, 900])
+                    dp = rb + pyr.choice([0, 0, 0, 5, 128])
+                    es, ed = (rows - 1) * sp + rb, (rows - 1) * dp + rb
+                    if cls == 0:
+                        src, sspace = pyr.randrange(0, (1 << 24) - es), FT_HOST
+                    else:
+                        a = orc.slab_alloc(es + 32)
+                        assert eng.slab_alloc(es + 32) == a
+                        live.append(a)
+                        fill = rng.integers(0, 256, es + 32, dtype=np.uint8)
+                        orc.write_pool(a, fill)
+                        eng.write_pool(a, fill)
+                        src, sspace = a + pyr.randrange(32), FT_POOL
+                    if cls == 1:
+                        if hdst + ed + 64 > (1 << 25):
+                            continue
+                        dst, dspace = hdst + pyr.randrange(16), FT_HOST
+                        hdst += (ed + 47) // 16 * 16
+                    else:
+                        b = orc.slab_alloc(ed + 32)
+                        assert eng.slab_alloc(ed + 32) == b
+                        live.append(b)
+                        dst, dspace = b + pyr.randrange(32), FT_POOL
+                    recs.append(dict(func=pyr.randrange(nfunc), src_space=sspace, dst_space=dspace, src=src, dst=dst,
+                                     row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp))
+                w = [pyr.choice([1, 1, 2, 3, 7]) for _ in range(nfunc)]
+                C = pyr.choice([64, 4096, 65536, 1 << 20, 2 << 20])
+                for cls in (0, 1, 2):
+                    binding.set_tuning(eng.pool, cls, pyr.choice([0, 0, 1, 3, 64, 300]),
+                                       pyr.choice([0, 0, 0, 16, 1000, 4096, 12272, 1 << 16]))
+                d = make_descs(recs)
+                jo = orc.submit(d, w, C)
+                orc.wait(jo)
+                jg = eng.submit(d, w, C, fmt.FT_KEEP | (fmt.FT_VALIDATE if job % 3 == 0 else 0))
+                eng.wait(jg)
+                for cls in (0, 1, 2):
+                    assert eng.job_schedule(jg, cls) == orc.job_schedule(jo, cls), (seed, job, cls)
+                binding.job_release(eng.pool, jg)
+                if job % 10 == 9:
+                    _compare_images(orc, eng)
+                    pyr.shuffle(live)
+                    for off in live[:len(live) * 2 // 3]:
+                        orc.slab_free(off)
+                        eng.slab_free(off)
+                    live = live[len(live) * 2 // 3:]
+            print(f"random sequence seed={seed} done", flush=True)
+        finally:
+            eng.close()
