@@ -45,6 +45,36 @@ def test_constants_match_between_header_binding_and_shared_format():
     assert ctypes.sizeof(ft.JobStats) == 3 * 48 + 8
 
 
+def test_header_is_plain_c_and_its_layouts_are_the_bindings(tmp_path):
+    """The public header must compile as C99 on its own, and the structures it declares must have the
+    sizes and field offsets that the Python side marshals (the descriptor record, the stats records)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    fields = [n for n in fmt.DESC_DTYPE.names]
+    src = ['#include <stddef.h>', '#include <stdio.h>', '#include "faastube.h"', 'int main(void) {',
+           '  printf("%zu %zu %zu\\n", sizeof(ft_desc), sizeof(ft_class_stats), sizeof(ft_job_stats_t));']
+    for n in fields:
+        src.append(f'  printf("{n} %zu\\n", offsetof(ft_desc, {n}));')
+    for n, _ in ft.ClassStats._fields_:
+        src.append(f'  printf("{n} %zu\\n", offsetof(ft_class_stats, {n}));')
+    src += ['  printf("%d %d %d %d %d\\n", FT_HOST, FT_POOL, FT_PAGEABLE, FT_OPEN, FT_ECLOSED);', '  return 0;', '}']
+    c = tmp_path / "layout.c"
+    c.write_text("\n".join(src))
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(c), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    assert out[0].split() == ["64", str(ctypes.sizeof(ft.ClassStats)), str(ctypes.sizeof(ft.JobStats))]
+    got = dict(line.split() for line in out[1:1 + len(fields)])
+    assert {n: int(v) for n, v in got.items()} == {n: fmt.DESC_DTYPE.fields[n][1] for n in fields}
+    got = dict(line.split() for line in out[1 + len(fields):1 + len(fields) + len(ft.ClassStats._fields_)])
+    assert {n: int(v) for n, v in got.items()} == {n: getattr(ft.ClassStats, n).offset for n, _ in ft.ClassStats._fields_}
+    assert [int(v) for v in out[-2].split()] == [FT_HOST, FT_POOL, oracle.PAGEABLE, ft.FT_OPEN, ft.FT_ECLOSED]
+
+
 def _both(op, lib_call, oracle_call):
     """Run the same call on both; return ('ok', value) or ('err', code) for each."""
     def run(fn):
