@@ -48,8 +48,9 @@ EBUSY = -5
 
 HOST = 0
 POOL = 1
-PAGEABLE = 2   # ordinary host memory; a source only (Sec. 6.1: it travels through a pinned ring,
-               # which is transport and leaves the result a plain copy)
+PAGEABLE = 2   # ordinary host memory, as the source of a host->pool or the destination of a pool->host
+               # transfer (Sec. 6.1: it travels through a pinned ring, which is transport and leaves
+               # the result a plain copy)
 
 H2P, P2H, P2P = 0, 1, 2
 

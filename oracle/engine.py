@@ -54,7 +54,7 @@ def find_overlap(descs):
 
     Disjoint destinations make the result independent of the order in which
     chunks complete; that is why aliasing is rejected."""
-    for space in (HOST, POOL):
+    for space in (HOST, POOL, PAGEABLE):
         d0, d1 = _row_intervals(descs, "dst", space)
         if len(d0) == 0:
             continue
@@ -154,7 +154,7 @@ class OracleEngine:
         for d in descs:
             if int(d["func"]) >= nfunc or int(d["flags"]) != 0:
                 raise OracleError(EINVAL, "bad func or flags")
-            if int(d["src_space"]) not in (HOST, POOL, PAGEABLE) or int(d["dst_space"]) not in (HOST, POOL):
+            if int(d["src_space"]) not in (HOST, POOL, PAGEABLE) or int(d["dst_space"]) not in (HOST, POOL, PAGEABLE):
                 raise OracleError(EINVAL, "bad space")
             link_class(int(d["src_space"]), int(d["dst_space"]))
             if int(d["row_bytes"]) == 0 or int(d["rows"]) == 0:

@@ -21,7 +21,7 @@ def link_class(src_space, dst_space):
     each direction of the host link and the on-device path is its own class."""
     if src_space in (HOST, PAGEABLE) and dst_space == POOL:
         return H2P
-    if src_space == POOL and dst_space == HOST:
+    if src_space == POOL and dst_space in (HOST, PAGEABLE):
         return P2H
     if src_space == POOL and dst_space == POOL:
         return P2P

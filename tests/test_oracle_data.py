@@ -257,7 +257,7 @@ def test_workloads_round_trip_through_definition(name, scale):
 
 def test_pageable_source_is_a_plain_copy():
     """Sec. 6.1's circular pinned buffer is transport: a source in ordinary host memory gives the
-    same result as any other copy (NumPy slicing), chunked or not; it is a source only."""
+    same result as any other copy (NumPy slicing), chunked or not; host to host stays invalid."""
     import oracle
     from oracle import OracleEngine, OracleError
     from workloads import make_descs
@@ -282,11 +282,59 @@ def test_pageable_source_is_a_plain_copy():
     assert np.array_equal(eng.pool_mem, want)
     assert oracle.link_class(oracle.PAGEABLE, oracle.POOL) == oracle.H2P
     for bad in (dict(func=0, src_space=oracle.PAGEABLE, dst_space=oracle.HOST, src=0, dst=0, row_bytes=16),
-                dict(func=0, src_space=oracle.POOL, dst_space=oracle.PAGEABLE, src=a, dst=0, row_bytes=16)):
+                dict(func=0, src_space=oracle.HOST, dst_space=oracle.PAGEABLE, src=0, dst=0, row_bytes=16),
+                dict(func=0, src_space=oracle.PAGEABLE, dst_space=oracle.PAGEABLE, src=0, dst=64, row_bytes=16)):
         with pytest.raises(OracleError) as ei:
             eng.submit(make_descs([bad]), [1], 4096)
         assert ei.value.code == oracle.EINVAL
     with pytest.raises(OracleError) as ei:
         eng.submit(make_descs([dict(func=0, src_space=oracle.PAGEABLE, dst_space=oracle.POOL, src=(1 << 18) - 8, dst=a,
+                                    row_bytes=16)]), [1], 4096)
+    assert ei.value.code == oracle.ERANGE
+
+
+def test_pageable_destination_is_a_plain_copy():
+    """The other direction of the host link through the same buffer (Sec. 6.1 names the buffer for PCIe
+    transfers as such): pool -> ordinary host memory is the plain copy too, nothing else in that memory
+    changes, it is a pool->host transfer for the schedule, and aliasing inside it is still refused."""
+    import oracle
+    from oracle import OracleEngine, OracleError
+    from workloads import make_descs
+    rng = np.random.default_rng(78)
+    eng = OracleEngine()
+    eng.host_arena(1 << 16)
+    eng.pageable_arena(1 << 18, fill=0x3C)
+    eng.pool_create(1 << 20, 4096)
+    a = eng.slab_alloc(120000)
+    b = eng.slab_alloc(50 * 333)
+    data = rng.integers(0, 256, 120000, dtype=np.uint8)
+    rowsrc = rng.integers(0, 256, 50 * 333, dtype=np.uint8)
+    eng.write_pool(a, data)
+    eng.write_pool(b, rowsrc)
+    recs = [dict(func=0, src_space=oracle.POOL, dst_space=oracle.PAGEABLE, src=a + 3, dst=1001, row_bytes=100003),
+            dict(func=1, src_space=oracle.POOL, dst_space=oracle.PAGEABLE, src=b, dst=150001, row_bytes=50, rows=333,
+                 src_pitch=50, dst_pitch=77),
+            dict(func=1, src_space=oracle.POOL, dst_space=oracle.HOST, src=a, dst=5, row_bytes=999)]
+    pool_before, host_before = eng.pool_mem.copy(), eng.host_mem.copy()
+    job = eng.submit(make_descs(recs), [2, 1], 4096)
+    eng.wait(job)
+    want = np.full(1 << 18, 0x3C, dtype=np.uint8)
+    want[1001:1001 + 100003] = data[3:3 + 100003]
+    for r in range(333):
+        want[150001 + 77 * r:150001 + 77 * r + 50] = rowsrc[50 * r:50 * r + 50]
+    assert np.array_equal(eng.pageable_mem, want)
+    assert np.array_equal(eng.pool_mem, pool_before)
+    host_before[5:5 + 999] = data[:999]
+    assert np.array_equal(eng.host_mem, host_before)
+    assert oracle.link_class(oracle.POOL, oracle.PAGEABLE) == oracle.P2H
+    assert eng.job_class_bytes(job, oracle.P2H) == 100003 + 50 * 333 + 999
+    assert len(eng.job_schedule(job, oracle.P2H)) == -(-100003 // 4096) + -(-(50 * 333 + 999) // 4096)
+    twice = [dict(func=0, src_space=oracle.POOL, dst_space=oracle.PAGEABLE, src=a, dst=100, row_bytes=64),
+             dict(func=0, src_space=oracle.POOL, dst_space=oracle.PAGEABLE, src=a + 64, dst=163, row_bytes=64)]
+    with pytest.raises(OracleError) as ei:
+        eng.submit(make_descs(twice), [1], 4096)
+    assert ei.value.code == oracle.EOVERLAP
+    with pytest.raises(OracleError) as ei:
+        eng.submit(make_descs([dict(func=0, src_space=oracle.POOL, dst_space=oracle.PAGEABLE, src=a, dst=(1 << 18) - 8,
                                     row_bytes=16)]), [1], 4096)
     assert ei.value.code == oracle.ERANGE
