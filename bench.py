@@ -302,18 +302,7 @@ def pinned_ring(peaks):
     per = total // nf
     d = make_descs([dict(func=f, src_space=2, dst_space=1, src=f * per, dst=eng.slab_alloc(per), row_bytes=per)
                     for f in range(nf)])
-    src_t = torch.from_numpy(eng.pageable_np)
-    dst_t = torch.empty(total, dtype=torch.uint8, device="cuda:0")
-    best = 0.0
-    for _ in range(3):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        dst_t.copy_(src_t)
-        torch.cuda.synchronize()
-        best = max(best, total / (time.perf_counter() - t0) / 1e9)
-    out = {"bytes": total, "chunk_bytes": chunk, "batch_chunks": 5, "depth": 3, "ring_MiB": 40,
-           "runtime_copy_from_pageable_GBps": round(best, 2), "ring_GBps": {}}
-    del dst_t
+    out = {"bytes": total, "chunk_bytes": chunk, "batch_chunks": 5, "depth": 3, "ring_MiB": 40, "ring_GBps": {}}
     for threads in (1, 4, 8):
         ft.set_batch(eng.pool, 5, 3)
         ft.set_stage_threads(eng.pool, threads)
@@ -326,6 +315,33 @@ def pinned_ring(peaks):
         ts.sort()
         out["ring_GBps"][f"{threads}_threads"] = round(total / ts[1] / 1e9, 2)
     out["ring_4_threads_link_frac"] = round(out["ring_GBps"]["4_threads"] / peaks["h2d"], 4)
+    # the other direction: pool -> ordinary host memory
+    back = make_descs([dict(func=f, src_space=1, dst_space=2, src=int(d["dst"][f]), dst=f * per, row_bytes=per)
+                       for f in range(nf)])
+    ft.set_stage_threads(eng.pool, 4)
+    ts = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        eng.wait(eng.submit(back, [1] * nf, chunk, ft.FT_OPEN))
+        ts.append(time.perf_counter() - t0)
+    ts.sort()
+    out["to_pageable"] = {"ring_4_threads_GBps": round(total / ts[1] / 1e9, 2),
+                          "ring_link_frac": round(total / ts[1] / 1e9 / peaks["d2h"], 4)}
+    # the runtime's own copies between the same pageable memory and the device, measured last (after
+    # the runtime has copied from or to that memory, the library's threads move it more slowly: 45 against 52 GB/s)
+    host_t = torch.from_numpy(eng.pageable_np)
+    dev_t = torch.empty(total, dtype=torch.uint8, device="cuda:0")
+    for key, dst, src in (("runtime_copy_from_pageable_GBps", dev_t, host_t), ("runtime_copy_to_pageable_GBps", host_t, dev_t)):
+        best = 0.0
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            dst.copy_(src)
+            torch.cuda.synchronize()
+            best = max(best, total / (time.perf_counter() - t0) / 1e9)
+        out[key] = round(best, 2)
+    del dev_t
     eng.close()
     return out
 

@@ -36,8 +36,9 @@ typedef uint64_t ft_job_t;      /* handle of one submit */
 enum {
   FT_HOST = 0,     /* pinned host memory the device can address */
   FT_POOL = 1,     /* the pool's logical offset space */
-  FT_PAGEABLE = 2  /* ordinary host memory, as a source only, only into the pool, and only in
-                      open jobs: it travels through the circular pinned buffer (Sec. 6.1) */
+  FT_PAGEABLE = 2  /* ordinary host memory, as the source of a host->pool or the destination of a
+                      pool->host transfer, only in open jobs: it travels through the circular
+                      pinned buffer (Sec. 6.1) */
 };
 
 /* link classes: each has its own chunk schedule and its own kernel */
@@ -83,9 +84,9 @@ enum {
 typedef struct ft_desc {
   uint32_t func;      /* 0 .. nfunc-1: the function this data belongs to */
   uint8_t src_space;  /* FT_HOST: src is a device-visible virtual address of pinned host
-                         memory. FT_POOL: src is an ft_off_t. FT_PAGEABLE: src is a host
-                         virtual address inside a window given to ft_pageable_window_add */
-  uint8_t dst_space;  /* FT_HOST or FT_POOL. A host source with a host destination is invalid */
+                         memory. FT_POOL: src is an ft_off_t. FT_PAGEABLE: a host virtual
+                         address inside a window given to ft_pageable_window_add */
+  uint8_t dst_space;  /* FT_HOST, FT_POOL or FT_PAGEABLE, as for src. One side must be FT_POOL */
   uint16_t flags;     /* must be 0 */
   uint64_t src;
   uint64_t dst;
@@ -176,16 +177,19 @@ void *ft_pool_ptr(ft_pool *p, ft_off_t off);
 int ft_host_window_add(ft_pool *p, void *host_base, uint64_t bytes);
 
 /*
- * Declare a window of ordinary (pageable) host memory that FT_PAGEABLE sources may lie
- * in; every such source must lie inside one (else FT_ERANGE): the library's own threads
- * read it. Circular pinned buffer of Sec. 6.1: the device cannot read such memory, and
- * pinning it call by call or keeping a pinned copy of everything is what the paper rules
- * out, so an open job owns one fixed ring of pinned memory, (depth + 1) * batch_chunks
- * slots of one chunk each, shared by all its functions; before a batch is launched the
- * stream bytes of its pageable descriptors are copied into the batch's slots by
- * `threads` host threads (ft_set_batch's neighbour ft_set_stage_threads, default 4), the
- * copy kernel reads them from there, and the slots are reused depth + 1 batches later.
- * The source memory must stay valid and unchanged until the job has been waited for.
+ * Declare a window of ordinary (pageable) host memory that FT_PAGEABLE sources and
+ * destinations may lie in; every one must lie inside one (else FT_ERANGE): the library's
+ * own threads read and write it. Circular pinned buffer of Sec. 6.1: the device cannot
+ * reach such memory, and pinning it call by call or keeping a pinned copy of everything
+ * is what the paper rules out, so an open job owns, per direction of the host link in
+ * use, one fixed ring of pinned memory, (depth + 1) * batch_chunks slots of one chunk
+ * each, shared by all its functions. Host->pool: before a batch is launched the stream
+ * bytes of its pageable descriptors are copied into the batch's slots by `threads` host
+ * threads (ft_set_batch's neighbour ft_set_stage_threads, default 4) and the copy kernel
+ * reads them from there. Pool->host: the kernel writes the batch's slots and the same
+ * threads copy them on to the destinations when the batch is complete; ft_wait returns
+ * after that. Slots are reused depth + 1 batches later. Source memory must stay valid
+ * and unchanged, destination memory valid, until the job has been waited for.
  */
 int ft_pageable_window_add(ft_pool *p, void *host_base, uint64_t bytes);
 
@@ -221,7 +225,7 @@ int ft_set_stage_threads(ft_pool *p, uint32_t threads);
  * Validation order: FT_EINVAL conditions of the arguments and of every descriptor
  * (null pointers with non-zero counts, nfunc == 0, a weight of 0, chunk_bytes not a
  * positive multiple of 16, func >= nfunc, flags != 0, a space other than FT_HOST,
- * FT_POOL or (source only) FT_PAGEABLE, host->host, row_bytes == 0, rows == 0, a pitch <
+ * FT_POOL or FT_PAGEABLE, neither side in the pool, row_bytes == 0, rows == 0, a pitch <
  * row_bytes with rows > 1; FT_PAGEABLE without FT_OPEN is FT_EINVAL after the range checks),
  * then FT_ERANGE of every descriptor, then (FT_VALIDATE) FT_EOVERLAP, and last
  * FT_EINVAL if the weights are so large and so unlike that the schedule tables would

@@ -482,9 +482,13 @@ struct Work {
 // A staged descriptor's bytes of the current chunk lie in the chunk's ring slot, packed
 // in stream order: stream byte b at `stage + b`.
 __device__ __forceinline__ void into_ring(Xfer &X, uint64_t stage) {
-  if (X.staged) {
+  if (X.staged & kStagedSrc) {
     X.src = stage + X.stream_off;
     X.src_pitch = X.row_bytes;
+  }
+  if (X.staged & kStagedDst) {
+    X.dst = stage + X.stream_off;
+    X.dst_pitch = X.row_bytes;
   }
 }
 

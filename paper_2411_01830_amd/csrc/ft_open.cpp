@@ -12,14 +12,17 @@
 // the device ("generation"); batches already queued keep the tables they were launched
 // with.
 //
-// Circular pinned buffer of Sec. 6.1: sources in pageable host memory (FT_PAGEABLE) cannot
-// be read by the device. Pinning the caller's buffers per call is what the paper measures
+// Circular pinned buffer of Sec. 6.1: pageable host memory (FT_PAGEABLE) cannot be read or
+// written by the device. Pinning the caller's buffers per call is what the paper measures
 // as too slow and caching a pinned copy of everything as too large; instead one fixed
 // ring of pinned memory, (depth + 1) * batch_chunks slots of one chunk each, is shared by
 // all functions: before a batch is launched the feeder and a few helper threads copy the
 // stream bytes of the batch's pageable descriptors into the batch's slots (chunk i of
 // batch q has slot (q mod (depth + 1)) * batch_chunks + i), the kernel reads them there,
 // and the slots are used again depth + 1 batches later, when that batch is long complete.
+// In the other direction (pool -> pageable host memory) the kernel writes a chunk into its
+// slot and, once the batch is complete, the same threads copy it on to the destination;
+// only then do the batch's chunks count as done.
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
@@ -42,7 +45,7 @@ struct OpenFn {
   uint64_t stream_bytes;
   uint64_t nchunks;       // of the whole stream
   uint64_t next_chunk;    // first chunk not yet triggered
-  bool staged;            // some descriptor reads pageable host memory
+  bool staged;            // some descriptor reads or writes pageable host memory
   std::vector<Xfer> xfers;
 };
 
@@ -59,17 +62,18 @@ struct Generation {
   bool waited_upload[2] = {false, false};
 };
 
+struct StageCopy {
+  char *dst;
+  const char *src;
+  uint64_t n;
+};
+
 struct OpenBatch {
   std::shared_ptr<Generation> gen;
   uint32_t lane = 0;                // which of the class's two streams
   hipEvent_t done = nullptr, t_begin = nullptr, t_end = nullptr;
   std::vector<std::pair<uint64_t, uint64_t>> job_chunks;  // job id, chunks of it in this batch
-};
-
-struct StageCopy {
-  char *dst;
-  const char *src;
-  uint64_t n;
+  std::vector<StageCopy> unstage;   // ring -> pageable destinations, once the batch is complete
 };
 
 // A few helper threads that copy pageable bytes into the ring; the feeder takes part.
@@ -273,9 +277,11 @@ struct Prepared {
   std::vector<StageCopy> copies;
 };
 
-// Copies that bring the pageable bytes of chunk (f, k) into its ring slot.
+// Copies between chunk (f, k)'s ring slot and the pageable memory of its staged descriptors:
+// `in` brings pageable sources into the slot before the launch, `out` takes what the device
+// wrote for pageable destinations away after it.
 void stage_chunk(const ClassPlan &cp, const Func &f, uint64_t k, uint64_t chunk_bytes, char *slot,
-                 std::vector<StageCopy> *copies, uint64_t *bytes) {
+                 std::vector<StageCopy> *in, std::vector<StageCopy> *out, uint64_t *bytes) {
   const uint64_t c0 = k * chunk_bytes;
   const uint64_t c1 = std::min(c0 + chunk_bytes, f.stream_bytes);
   uint32_t x = find_xfer(cp.xfers.data(), f.desc_off, f.desc_off + f.ndesc - 1, c0);
@@ -285,15 +291,20 @@ void stage_chunk(const ClassPlan &cp, const Func &f, uint64_t k, uint64_t chunk_
     uint64_t take = X.row_bytes * X.rows - q;
     if (take > c1 - pos) take = c1 - pos;
     if (X.staged) {
-      // rows of the source, packed in stream order at offset (stream position - c0) of the slot
+      // rows of the descriptor, packed in stream order at offset (stream position - c0) of the slot
+      const bool inward = (X.staged & kStagedSrc) != 0;
+      const uint64_t base = inward ? X.src : X.dst, pitch = inward ? X.src_pitch : X.dst_pitch;
       uint64_t r = q / X.row_bytes, c = q % X.row_bytes, left = take, at = pos - c0;
       while (left > 0) {
         uint64_t n = std::min(X.row_bytes - c, left);
-        const char *src = reinterpret_cast<const char *>(X.src + r * X.src_pitch + c);
+        char *mem = reinterpret_cast<char *>(base + r * pitch + c);
         *bytes += n;
         left -= n;
-        for (uint64_t o = 0; o < n; o += kStagePiece)
-          copies->push_back(StageCopy{slot + at + o, src + o, std::min(kStagePiece, n - o)});
+        for (uint64_t o = 0; o < n; o += kStagePiece) {
+          const uint64_t m = std::min(kStagePiece, n - o);
+          if (inward) in->push_back(StageCopy{slot + at + o, mem + o, m});
+          else out->push_back(StageCopy{mem + o, slot + at + o, m});
+        }
         at += n;
         r += 1;
         c = 0;
@@ -367,7 +378,7 @@ bool prepare_batch(OpenState *st, int c, Prepared *out) {
     if (st->flags & FT_KEEP) oc.order.push_back(BatchRec{fn.job, fn.func, (uint32_t)k, batch_no});
     if (fn.staged)
       stage_chunk(cp, f, k, st->chunk_bytes, oc.ring + (slot0 + (r - r0)) * st->chunk_bytes, &out->copies,
-                  &oc.staged_bytes);
+                  &b.unstage, &oc.staged_bytes);
   }
   g.next_rank = r1;
   g.next_counter += 1;
@@ -394,6 +405,16 @@ void feeder_main(OpenState *st, int c) {
   (void)hipSetDevice(p->device);
   OpenClass &oc = st->cls[c];
   std::unique_lock<std::mutex> lock(st->mu);
+  // the chunks of a batch are complete: the jobs they belong to are told (lock held)
+  auto count_done = [&](const OpenBatch &b) {
+    for (auto &jc : b.job_chunks) {
+      auto it = st->left.find(jc.first);
+      if (it != st->left.end()) it->second = it->second > jc.second ? it->second - jc.second : 0;
+    }
+    st->cv.notify_all();
+  };
+  OpenBatch carry;  // complete on the device, its bytes still to be taken out of the ring
+  bool have_carry = false;
   for (;;) {
     while (st->error == FT_OK && oc.inflight.size() < st->depth && oc.gen->next_rank < oc.gen->plan.nchunks) {
       Prepared pr;
@@ -422,6 +443,22 @@ void feeder_main(OpenState *st, int c) {
       }
       oc.inflight.push_back(std::move(pr.batch));
     }
+    if (have_carry) {
+      // A complete batch whose ring slots hold bytes for pageable destinations. The batch
+      // that follows the ones in flight has just been launched (above), so the link stays
+      // busy while these bytes go on to where they belong. Their slots are handed out again
+      // only to a batch that this thread prepares later.
+      StagePool *stagers = oc.stagers.get();
+      lock.unlock();
+      const auto s0 = std::chrono::steady_clock::now();
+      stagers->run(carry.unstage);
+      const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - s0).count();
+      lock.lock();
+      oc.stage_ms += ms;
+      count_done(carry);
+      have_carry = false;
+      continue;
+    }
     if (oc.inflight.empty()) {
       // dry (or failed): later arrivals start a sequence of their own
       oc.closed = true;
@@ -447,15 +484,17 @@ void feeder_main(OpenState *st, int c) {
     put_event(p, true, b.t_end);
     b.gen->inflight -= 1;
     if (b.gen->inflight == 0 && b.gen != oc.gen) drop_generation(p, b.gen.get());
-    for (auto &jc : b.job_chunks) {
-      auto it = st->left.find(jc.first);
-      if (it != st->left.end()) it->second = it->second > jc.second ? it->second - jc.second : 0;
+    if (st->error == FT_OK && !b.unstage.empty()) {
+      carry = std::move(b);
+      have_carry = true;
+    } else {
+      count_done(b);
     }
-    st->cv.notify_all();
   }
 }
 
-// Pinned ring and helper threads for class c, once, when the first pageable function joins.
+// Pinned ring and helper threads for class c, once, when the first function with pageable
+// memory on its host side joins.
 int ensure_ring(ft_pool *p, OpenState *st, int c) {
   OpenClass &oc = st->cls[c];
   if (oc.ring != nullptr) return FT_OK;
@@ -465,6 +504,12 @@ int ensure_ring(ft_pool *p, OpenState *st, int c) {
   oc.ring_slots = slots;
   oc.stagers.reset(new StagePool(p->stage_threads ? p->stage_threads - 1 : 3));
   return FT_OK;
+}
+
+bool any_staged(const ClassPlan &cp) {
+  for (const Xfer &x : cp.xfers)
+    if (x.staged != 0) return true;
+  return false;
 }
 
 void add_functions(OpenClass &oc, uint64_t job_id, const ClassPlan &cp) {
@@ -515,7 +560,7 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
     // the caller's weights, not the gcd-reduced ones: functions of later jobs are weighed against them
     for (Func &f : cp.funcs) f.weight = weights[f.func];
     add_functions(oc, job->id, cp);
-    if (plan.has_pageable && c == FT_H2P) {
+    if (any_staged(cp)) {
       int rc = ensure_ring(p, st.get(), c);
       if (rc != FT_OK) return undo(rc);
     }
@@ -581,7 +626,7 @@ int open_merge(ft_pool *p, Job *open_job, Job *job, SubmitPlan &plan, const uint
     for (Func &f : cp.funcs) f.weight = weights[f.func];
     pending.push_back(Pending{c, oc.fns.size(), nullptr});
     add_functions(oc, job->id, cp);
-    int rc = (plan.has_pageable && c == FT_H2P) ? ensure_ring(p, st.get(), c) : FT_OK;
+    int rc = any_staged(cp) ? ensure_ring(p, st.get(), c) : FT_OK;
     if (rc == FT_OK) rc = build_generation(p, st.get(), c, user, &pending.back().gen);
     if (rc != FT_OK) return roll_back(rc);
     chunks += cp.nchunks;

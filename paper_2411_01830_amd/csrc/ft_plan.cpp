@@ -274,8 +274,8 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
   for (uint32_t i = 0; i < ndesc; ++i) {
     const ft_desc &d = descs[i];
     if (d.func >= nfunc || d.flags != 0) return FT_EINVAL;
-    if (d.src_space > FT_PAGEABLE || d.dst_space > FT_POOL) return FT_EINVAL;
-    if (d.src_space != FT_POOL && d.dst_space == FT_HOST) return FT_EINVAL;
+    if (d.src_space > FT_PAGEABLE || d.dst_space > FT_PAGEABLE) return FT_EINVAL;
+    if (d.src_space != FT_POOL && d.dst_space != FT_POOL) return FT_EINVAL;  // host to host
     if (d.row_bytes == 0 || d.rows == 0) return FT_EINVAL;
     if (d.rows > 1 && (d.src_pitch < d.row_bytes || d.dst_pitch < d.row_bytes)) return FT_EINVAL;
   }
@@ -291,7 +291,7 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
     x.src_pitch = d.rows > 1 ? d.src_pitch : d.row_bytes;
     x.dst_pitch = d.rows > 1 ? d.dst_pitch : d.row_bytes;
     x.stream_off = 0;
-    x.staged = d.src_space == FT_PAGEABLE ? 1 : 0;
+    x.staged = (d.src_space == FT_PAGEABLE ? kStagedSrc : 0) | (d.dst_space == FT_PAGEABLE ? kStagedDst : 0);
     if (x.staged) out->has_pageable = true;
     uint64_t payload;
     if (mul_overflow(d.row_bytes, d.rows, &payload)) return FT_ERANGE;
@@ -308,7 +308,7 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
         used.push_back(start);
         addr = reinterpret_cast<uint64_t>(pool.ptr(off));
       } else if (space == FT_PAGEABLE) {
-        // read by the library's own threads: only from memory the caller has vouched for
+        // read or written by the library's own threads: only memory the caller has vouched for
         bool inside = false;
         for (const HostWindow &w : windows)
           if (w.pageable && off >= w.base && end <= w.base + w.bytes) inside = true;
@@ -331,7 +331,7 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
 
   // ---- pass 3: exact aliasing check, on request
   if (flags & FT_VALIDATE) {
-    for (int space = 0; space < 2; ++space) {
+    for (int space = 0; space <= FT_PAGEABLE; ++space) {
       std::vector<Interval> dst, src;
       for (uint32_t i = 0; i < ndesc; ++i) {
         const ft_desc &d = descs[i];
@@ -354,7 +354,7 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
     std::vector<uint64_t> stream(nfunc, 0);
     std::vector<uint32_t> count(nfunc, 0);
     auto class_of = [](const ft_desc &d) {
-      return d.src_space != FT_POOL ? FT_H2P : (d.dst_space == FT_HOST ? FT_P2H : FT_P2P);
+      return d.src_space != FT_POOL ? FT_H2P : (d.dst_space != FT_POOL ? FT_P2H : FT_P2P);
     };
     for (uint32_t i = 0; i < ndesc; ++i)
       if (class_of(descs[i]) == c) {

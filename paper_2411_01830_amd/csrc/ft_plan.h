@@ -14,7 +14,7 @@ namespace ft {
 struct HostWindow {
   uint64_t base;
   uint64_t bytes;
-  bool pageable;  // ordinary host memory (FT_PAGEABLE sources), not device-visible pinned memory
+  bool pageable;  // ordinary host memory (FT_PAGEABLE), not device-visible pinned memory
 };
 
 struct ClassPlan {
@@ -31,7 +31,7 @@ struct ClassPlan {
 struct SubmitPlan {
   ClassPlan cls[FT_NCLASS];
   std::vector<uint64_t> allocs;  // start offsets of the pool allocations referred to (unique)
-  bool has_pageable = false;     // some source is pageable host memory: needs the staging ring
+  bool has_pageable = false;     // some source or destination is pageable host memory: needs the staging ring
 };
 
 // Phases and slots for the given functions (nchunks > 0, weight >= 1 each, ascending

@@ -62,9 +62,11 @@ struct Xfer {
   uint64_t src_pitch;
   uint64_t dst_pitch;
   uint64_t stream_off;  // payload bytes of the function's earlier descriptors
-  uint64_t staged;      // 1: src is pageable host memory that the device cannot read; the bytes
-                        // reach it through the staging ring (see ClassTable::stage_base)
+  uint64_t staged;      // kStagedSrc: src is pageable host memory that the device cannot read, the
+                        // bytes reach it through the staging ring (see ClassTable::stage_base);
+                        // kStagedDst: dst is pageable host memory, the device writes the ring
 };
+constexpr uint64_t kStagedSrc = 1, kStagedDst = 2;
 
 // Tickets number only tiles that hold bytes. Tile v of the uniform grid (chunk rank
 // v / tiles_per_chunk, tile v % tiles_per_chunk) is empty when it lies past the end of a
@@ -117,8 +119,10 @@ struct ClassTable {
   uint64_t first_next_base;
   uint64_t first_skip_at;
   // Staging ring (pinned host memory, slots of chunk_bytes): chunk rank r of this launch has
-  // slot stage_slot0 + (r - stage_rank0); the host has put the stream bytes of the chunk's
-  // staged descriptors there, each at its offset inside the chunk.
+  // slot stage_slot0 + (r - stage_rank0). The stream bytes of the chunk's staged descriptors
+  // lie there, each at its offset inside the chunk: put there by the host before the launch
+  // (pageable sources) or by the device for the host to take away after it (pageable
+  // destinations).
   uint64_t stage_base;
   uint64_t stage_rank0;
   uint64_t stage_slot0;

@@ -49,7 +49,7 @@ class GpuEngine:
             ft.host_window_add(self.pool, self.host.data_ptr(), nbytes)
 
     def pageable_arena(self, nbytes, fill=0x3C):
-        """Ordinary (not pinned) host memory for FT_PAGEABLE sources; addresses are offsets into it."""
+        """Ordinary (not pinned) host memory for FT_PAGEABLE; addresses are offsets into it."""
         self.pageable_np = np.full(int(nbytes), fill, dtype=np.uint8)
         if self.pool is not None:
             ft.pageable_window_add(self.pool, self.pageable_np.ctypes.data, int(nbytes))
@@ -125,6 +125,8 @@ class GpuEngine:
         d["dst"][d["dst_space"] == 0] += np.uint64(base)
         if np.any(d["src_space"] == 2):
             d["src"][d["src_space"] == 2] += np.uint64(self.pageable_np.ctypes.data)
+        if np.any(d["dst_space"] == 2):
+            d["dst"][d["dst_space"] == 2] += np.uint64(self.pageable_np.ctypes.data)
         s = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
         return ft.submit_transfers(self.pool, d, weights, int(chunk_bytes),
                                    int(flags) | self.default_flags, s)
@@ -136,6 +138,8 @@ class GpuEngine:
         d["dst"][d["dst_space"] == 0] += np.uint64(base)
         if np.any(d["src_space"] == 2):
             d["src"][d["src_space"] == 2] += np.uint64(self.pageable_np.ctypes.data)
+        if np.any(d["dst_space"] == 2):
+            d["dst"][d["dst_space"] == 2] += np.uint64(self.pageable_np.ctypes.data)
         s = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
         return ft.submit_merge(self.pool, open_job, d, weights, int(flags), s)
 

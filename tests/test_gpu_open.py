@@ -403,3 +403,85 @@ def test_open_jobs_of_many_small_descriptors(gpu):
         _images_equal(orc, eng)
     finally:
         eng.close()
+
+
+@pytest.mark.parametrize("batch,depth,threads", [(5, 3, 4), (2, 1, 1), (4, 2, 3)])
+def test_pageable_destinations_through_the_ring(gpu, batch, depth, threads):
+    """Pool -> ordinary host memory: the device writes the pinned ring and the library's threads
+    carry each finished batch on to its destination. Many more batches than slots, odd sizes and
+    alignments, a pitched destination, pinned and pageable destinations in one function, a job in
+    the other direction (pageable sources) in the same open sequence, a merge. Pageable memory,
+    pinned memory and the pool must all be the oracle's afterwards."""
+    from workloads import FT_PAGEABLE
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 64 * MiB, 192 * MiB, seed=29 + batch)
+    try:
+        C = 64 * KiB
+        page = rng.integers(0, 256, 24 * MiB, dtype=np.uint8)
+        for e in (orc, eng):
+            e.pageable_arena(64 * MiB)
+            e.write_pageable(0, page)          # lower part: sources; upper part keeps its fill: destinations
+        binding.set_batch(eng.pool, batch, depth)
+        binding.set_stage_threads(eng.pool, threads)
+
+        def filled(n):
+            a = orc.slab_alloc(n)
+            assert eng.slab_alloc(n) == a
+            data = rng.integers(0, 256, n, dtype=np.uint8)
+            orc.write_pool(a, data)
+            eng.write_pool(a, data)
+            return a
+
+        def alloc(n):
+            a = orc.slab_alloc(n)
+            assert eng.slab_alloc(n) == a
+            return a
+        out = 32 * MiB
+        recs0 = [
+            dict(func=0, src_space=FT_POOL, dst_space=FT_PAGEABLE, src=filled(8 * MiB) + 3, dst=out + 1, row_bytes=7 * MiB + 777),
+            dict(func=1, src_space=FT_POOL, dst_space=FT_PAGEABLE, src=filled(3 * MiB), dst=out + 8 * MiB + 16, row_bytes=3 * MiB),
+            # pinned and pageable destinations in one function's stream
+            dict(func=1, src_space=FT_POOL, dst_space=FT_HOST, src=filled(1 * MiB) + 9, dst=40 * MiB + 5, row_bytes=600001),
+            dict(func=1, src_space=FT_POOL, dst_space=FT_PAGEABLE, src=filled(4096), dst=out + 12 * MiB + 7, row_bytes=99),
+            # packed rows of 200 bytes scattered at a pitch of 1000
+            dict(func=2, src_space=FT_POOL, dst_space=FT_PAGEABLE, src=filled(2 * MiB) + 2, dst=out + 13 * MiB + 9,
+                 row_bytes=200, rows=9000, src_pitch=200, dst_pitch=1000),
+            # the other direction in the same job: a ring of its own
+            dict(func=2, src_space=FT_PAGEABLE, dst_space=FT_POOL, src=5 * MiB + 1, dst=alloc(5 * MiB) + 4, row_bytes=4 * MiB + 5),
+            dict(func=0, src_space=FT_POOL, dst_space=FT_POOL, src=filled(2 * MiB), dst=alloc(2 * MiB) + 1, row_bytes=2 * MiB - 9),
+        ]
+        recs1 = [dict(func=0, src_space=FT_POOL, dst_space=FT_PAGEABLE, src=filled(2 * MiB) + 1, dst=out + 24 * MiB + 3,
+                      row_bytes=1 * MiB + 19)]
+        d0, d1 = make_descs(recs0), make_descs(recs1)
+        orc.wait(orc.submit(d0, [1, 2, 3], C))
+        orc.wait(orc.submit(d1, [9], C))
+        print(f"pageable destinations batch={batch} depth={depth} threads={threads}", flush=True)
+        with pytest.raises(binding.FtError) as ei:
+            eng.submit(d1, [9], C, 0)                      # outside an open job the ring does not exist
+        assert ei.value.code == fmt.FT_EINVAL
+        j0 = eng.submit(d0, [1, 2, 3], C, fmt.FT_OPEN | fmt.FT_KEEP | fmt.FT_VALIDATE)
+        try:
+            j1 = eng.merge(j0, d1, [9], fmt.FT_KEEP)
+        except binding.FtError as e:
+            assert e.code == fmt.FT_ECLOSED
+            j1 = eng.submit(d1, [9], C, fmt.FT_OPEN | fmt.FT_KEEP)
+        eng.wait(j1)
+        # the small job's bytes are at their destination when its own wait returns
+        assert np.array_equal(eng.pageable_np[out + 24 * MiB + 3:out + 25 * MiB + 22],
+                              orc.pageable_mem[out + 24 * MiB + 3:out + 25 * MiB + 22])
+        eng.wait(j0)
+        _images_equal(orc, eng)
+        assert np.array_equal(eng.pageable_np, orc.pageable_mem), "pageable image differs"
+        binding.job_release(eng.pool, j0)
+        binding.job_release(eng.pool, j1)
+        # refused: a destination outside every pageable window; host to host in any flavour
+        for bad, code in ((dict(func=0, src_space=FT_POOL, dst_space=FT_PAGEABLE, src=filled(4096), dst=64 * MiB - 8,
+                                row_bytes=64), fmt.FT_ERANGE),
+                          (dict(func=0, src_space=FT_HOST, dst_space=FT_PAGEABLE, src=0, dst=out, row_bytes=64), fmt.FT_EINVAL),
+                          (dict(func=0, src_space=FT_PAGEABLE, dst_space=FT_PAGEABLE, src=0, dst=out, row_bytes=64),
+                           fmt.FT_EINVAL)):
+            with pytest.raises(binding.FtError) as ei:
+                eng.submit(make_descs([bad]), [1], C, fmt.FT_OPEN)
+            assert ei.value.code == code
+    finally:
+        eng.close()

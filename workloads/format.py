@@ -8,7 +8,7 @@ import numpy as np
 
 FT_HOST = 0   # address space of pinned host memory
 FT_POOL = 1   # logical byte-offset space of the device pool
-FT_PAGEABLE = 2   # ordinary host memory (source only, open jobs only): goes through the pinned ring
+FT_PAGEABLE = 2   # ordinary host memory (host side of a transfer, open jobs only): goes through the pinned ring
 
 # link classes (one independent weighted schedule each)
 H2P, P2H, P2P = 0, 1, 2
