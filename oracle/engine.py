@@ -98,7 +98,7 @@ class OracleEngine:
         self.host_mem = np.full(nbytes, fill, dtype=np.uint8)
 
     def pageable_arena(self, nbytes, fill=0x3C):
-        """Ordinary host memory: sources only. Addresses are offsets into it."""
+        """Ordinary host memory (the host side of a transfer). Addresses are offsets into it."""
         self.pageable_mem = np.full(nbytes, fill, dtype=np.uint8)
 
     def write_pageable(self, off, data):
