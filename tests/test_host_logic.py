@@ -249,6 +249,14 @@ def test_submit_validation_matches_oracle():
         ([dict(good, flags=1)], [1], 64, E.FT_EINVAL),
         ([dict(good, dst_space=FT_HOST)], [1], 64, E.FT_EINVAL),
         ([dict(good, src_space=3)], [1], 64, E.FT_EINVAL),
+        ([dict(good, dst_space=3)], [1], 64, E.FT_EINVAL),
+        # ordinary host memory is a host side like the pinned one: never both sides
+        ([dict(good, dst_space=2)], [1], 64, E.FT_EINVAL),
+        ([dict(good, src_space=2, dst_space=FT_HOST)], [1], 64, E.FT_EINVAL),
+        ([dict(good, src_space=2, dst_space=2)], [1], 64, E.FT_EINVAL),
+        # ... and with no window declared for it every range in it is outside
+        ([dict(good, src_space=2)], [1], 64, E.FT_ERANGE),
+        ([dict(good, src_space=FT_POOL, src=a, dst_space=2, dst=64)], [1], 64, E.FT_ERANGE),
         ([dict(good, row_bytes=0)], [1], 64, E.FT_EINVAL),
         ([dict(good, rows=0)], [1], 64, E.FT_EINVAL),
         ([dict(good, rows=2, src_pitch=99, dst_pitch=100)], [1], 64, E.FT_EINVAL),
