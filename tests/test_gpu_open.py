@@ -485,3 +485,54 @@ def test_pageable_destinations_through_the_ring(gpu, batch, depth, threads):
             assert ei.value.code == code
     finally:
         eng.close()
+
+
+def test_pool_to_pool_open_job_triggers_sixteen_times_larger_batches(gpu):
+    """The on-device class puts 16 x batch_chunks chunks into a batch; the batches it triggers are the
+    oracle's for that batch size, merged job included."""
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 4 * MiB, 256 * MiB, seed=53)
+    try:
+        C = 64 * KiB
+        binding.set_batch(eng.pool, 2, 2)
+
+        def job(sizes):
+            recs = []
+            for f, n in enumerate(sizes):
+                a = orc.slab_alloc(n + 32)
+                assert eng.slab_alloc(n + 32) == a
+                b = orc.slab_alloc(n + 32)
+                assert eng.slab_alloc(n + 32) == b
+                data = rng.integers(0, 256, n + 32, dtype=np.uint8)
+                orc.write_pool(a, data)
+                eng.write_pool(a, data)
+                recs.append(dict(func=f, src_space=FT_POOL, dst_space=FT_POOL, src=a + int(rng.integers(0, 16)),
+                                 dst=b + int(rng.integers(0, 16)), row_bytes=n))
+            return make_descs(recs)
+        sizes0, w0 = [30 * MiB + 5, 22 * MiB, 9 * MiB + 4096], [1, 2, 1]
+        sizes1, w1 = [3 * MiB + 7], [6]
+        d0, d1 = job(sizes0), job(sizes1)
+        orc.wait(orc.submit(d0, w0, C))
+        orc.wait(orc.submit(d1, w1, C))
+        j0 = eng.submit(d0, w0, C, fmt.FT_OPEN | fmt.FT_KEEP)
+        spec = [{"n": [chunk_count(s, C) for s in sizes0], "w": w0}]
+        index = {j0: 0}
+        try:
+            j1 = eng.merge(j0, d1, w1, fmt.FT_KEEP)
+            spec.append({"n": [chunk_count(s, C) for s in sizes1], "w": w1, "arrive": binding.job_arrival(eng.pool, j1, 2)})
+            index[j1] = 1
+        except binding.FtError as e:
+            assert e.code == fmt.FT_ECLOSED
+            j1 = eng.submit(d1, w1, C, fmt.FT_KEEP)
+        eng.wait(j1)
+        eng.wait(j0)
+        _images_equal(orc, eng)
+        got = binding.job_batches(eng.pool, j0, 2)
+        got = [[(index[j], f, k) for j, f, k in b] for b in got]
+        assert got == batched_order(spec, 32)
+        assert max(len(b) for b in got) == 32
+        print("pool->pool batches", len(got), "arrivals", [s.get("arrive", 0) for s in spec], flush=True)
+        binding.job_release(eng.pool, j0)
+        binding.job_release(eng.pool, j1)
+    finally:
+        eng.close()
