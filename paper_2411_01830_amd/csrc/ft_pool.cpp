@@ -1,5 +1,7 @@
 #include "ft_pool.h"
 
+#include <cstddef>
+
 #include "../../include/faastube.h"
 
 namespace ft {
