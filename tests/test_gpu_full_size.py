@@ -130,3 +130,59 @@ def test_full_size_workload(name):
             ft.job_release(eng.pool, rec.jobs[jname])
     finally:
         eng.close()
+
+
+@pytest.mark.parametrize("route", ["launch_argument", "uploaded_tables"])
+def test_transfers_larger_than_four_gib(route):
+    """Maximum sizes: one contiguous transfer of more than 4 GiB at unlike alignments and a pitched one
+    whose extent passes 4 GiB, so every offset, stream position and pitch product needs its upper 32
+    bits. Checked on the device by the definition of the result (destination rows equal source rows,
+    canaries either side untouched), and the ticket order against the oracle's order."""
+    import torch
+    from paper_2411_01830_amd import binding as ft
+    GiB = 1 << 30
+    n1 = 4 * GiB + 123457
+    rows, rb, sp, dp = 5, GiB + 48, GiB + 4096, GiB + 1000
+    slab = 1 << 20
+    need = lambda n: (n + slab - 1) // slab * slab
+    sizes = [need(n1 + 64), need(n1 + 64), need((rows - 1) * sp + rb + 64), need((rows - 1) * dp + rb + 64)]
+    total = sum(sizes)
+    buf = torch.empty(total, dtype=torch.uint8, device="cuda:0")
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(4242)
+    step = 1 << 28
+    for o in range(0, total, step):
+        m = min(step, total - o)
+        buf[o:o + m] = torch.randint(0, 256, (m,), dtype=torch.uint8, device="cuda:0", generator=g)
+    pool = ft.pool_create(buf.data_ptr(), total, slab, 0)
+    try:
+        a, b, c, d = (ft.slab_alloc(pool, s) for s in sizes)
+        buf[b:b + sizes[1]] = 0xA5
+        buf[d:d + sizes[3]] = 0xA5
+        descs = make_descs([
+            dict(func=0, src_space=FT_POOL, dst_space=FT_POOL, src=a + 3, dst=b + 9, row_bytes=n1),
+            dict(func=1, src_space=FT_POOL, dst_space=FT_POOL, src=c + 5, dst=d + 16, row_bytes=rb, rows=rows,
+                 src_pitch=sp, dst_pitch=dp)])
+        flags = ft.FT_KEEP | (ft.FT_DETACHED if route == "uploaded_tables" else 0)
+        chunk = 2 << 20
+        w = [1, 3]
+        print(f"huge transfers, route {route}", flush=True)
+        job = ft.submit_transfers(pool, descs, w, chunk, flags, torch.cuda.current_stream().cuda_stream)
+        ft.wait(pool, job)
+        st = ft.job_stats(pool, job)
+        assert st.cls[2].payload_bytes == n1 + rows * rb
+        assert st.cls[2].in_launch == (1 if route == "launch_argument" else 0)
+        assert torch.equal(buf[b + 9:b + 9 + n1], buf[a + 3:a + 3 + n1])
+        assert bool((buf[b:b + 9] == 0xA5).all()) and bool((buf[b + 9 + n1:b + 9 + n1 + 55] == 0xA5).all())
+        for r in range(rows):
+            assert torch.equal(buf[d + 16 + r * dp:d + 16 + r * dp + rb], buf[c + 5 + r * sp:c + 5 + r * sp + rb]), r
+            gap_end = d + 16 + (r + 1) * dp if r + 1 < rows else d + 16 + r * dp + rb + 48
+            assert bool((buf[d + 16 + r * dp + rb:gap_end] == 0xA5).all()), r
+        assert bool((buf[d:d + 16] == 0xA5).all())
+        n = [chunk_count(n1, chunk), chunk_count(rows * rb, chunk)]
+        assert ft.job_schedule(pool, job, 2) == stride_order(n, w)
+        ft.job_release(pool, job)
+    finally:
+        ft.pool_destroy(pool)
+        del buf
+        torch.cuda.empty_cache()
