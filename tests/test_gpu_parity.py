@@ -456,3 +456,33 @@ def test_random_sequences_of_mixed_jobs(gpu):
             print(f"random sequence seed={seed} done", flush=True)
         finally:
             eng.close()
+
+
+@pytest.mark.parametrize("weights", [[1000, 1, 4096, 3], [1, 1, 1, 1], [4000000000, 1, 1, 2], [7, 7, 7, 7], [3, 5, 1000003, 2]])
+def test_device_order_with_extreme_weights(gpu, weights):
+    """Weights that dwarf the chunk counts, equal weights, a weight near 2^32, weights with a common
+    factor and a large prime: the order the device decodes (uploaded tables) is the oracle's, and so
+    are the bytes."""
+    orc, eng, rng = _pair(gpu, host=1 << 22, pool=1 << 24, slab=4096, seed=sum(weights) % 1000)
+    try:
+        C = 4096
+        sizes = [3 * C - 5, 50 * C, 7 * C + 1, 200 * C - 4095]
+        recs = []
+        for f, n in enumerate(sizes):
+            a = orc.slab_alloc(n)
+            assert eng.slab_alloc(n) == a
+            recs.append(dict(func=f, src_space=FT_HOST, dst_space=FT_POOL, src=int(rng.integers(0, 1 << 20)), dst=a,
+                             row_bytes=n))
+        d = make_descs(recs)
+        jo = orc.submit(d, weights, C)
+        orc.wait(jo)
+        # a tuned workgroup count keeps the job on the route with uploaded tables and a counter
+        from paper_2411_01830_amd import binding
+        binding.set_tuning(eng.pool, 0, 7, 0)
+        jg = eng.submit(d, weights, C, fmt.FT_KEEP | fmt.FT_VALIDATE)
+        eng.wait(jg)
+        assert eng.job_schedule(jg, 0) == orc.job_schedule(jo, 0)
+        binding.job_release(eng.pool, jg)
+        _compare_images(orc, eng)
+    finally:
+        eng.close()
