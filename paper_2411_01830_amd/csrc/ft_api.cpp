@@ -338,6 +338,207 @@ int wait_locked(ft_pool *p, Job *job) {
 
 }  // namespace ft
 
+namespace ft {
+
+// Tile shape per class, then the descriptor table and the runs of empty tiles that go with it.
+void shape_classes(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chunk_bytes) {
+  const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    ClassPlan &cp = plan.cls[c];
+    if (cp.nchunks == 0) continue;
+    ClassRun &r = job->run[c];
+    const Tuning &tn = p->tuning[c];
+    tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
+               &r.tile_bytes, &r.tiles_per_chunk);
+    build_chunk_table(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk);
+    build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &r.table.ntickets);
+  }
+}
+
+// A submit that fails after it has taken device resources hands them back.
+int fail_submit(ft_pool *p, Job *job, int code) {
+  // work already queued may still read the tables: drain it before they are recycled
+  if (job->tables.dev != nullptr) (void)hipDeviceSynchronize();
+  release_device_side(p, job);
+  return code;
+}
+
+// What is the same for both ways of launching: the class's table header once its tables lie at `d`
+// (or, d = null, travel with the launch), and the events of the class.
+int prepare_class(ft_pool *p, Job *job, int c, const ClassPlan &cp, const Layout &lay, char *h, char *d,
+                  uint64_t chunk_bytes, bool timing) {
+  ClassRun &r = job->run[c];
+  ClassTable &T = r.table;
+  const uint64_t ntickets = T.ntickets;  // from shape_classes
+  fill_tables(cp, lay, h, d, &T);
+  T.ntickets = ntickets;
+  std::memcpy(h + lay.skips, r.skips.data(), r.skips.size() * sizeof(Skip));
+  T.nskips = (uint32_t)r.skips.size();
+  set_cursor_start(T, cp.phases.data(), (uint32_t)cp.phases.size(), r.skips.data(), T.nskips);
+  T.chunk_bytes = chunk_bytes;
+  T.tile_bytes = r.tile_bytes;
+  T.tiles_per_chunk = r.tiles_per_chunk;
+  r.used = true;
+  int rc = get_event(p, false, &r.ev_done);
+  if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_begin);
+  if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_end);
+  return rc;
+}
+
+// A job of one link class whose tables fit into a kernel argument is launched on the
+// caller's stream itself, tables in the launch: one launch and one event record instead
+// of a table upload, a fork and a join across streams - 4 us of host time instead of
+// 35 us, which is most of what passing a small tensor costs. If every ticket can have a
+// workgroup of its own the counter is never consulted; a larger job takes one of the
+// device's self-resetting counters (unless FT_DETACHED asks that the caller's stream be
+// left alone for what may be a long time). *launched says whether the job went this way.
+int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chunk_bytes, uint32_t flags,
+                           hipStream_t user, bool *launched) {
+  *launched = false;
+  int only = -1;
+  for (int c = 0; c < FT_NCLASS; ++c)
+    if (plan.cls[c].nchunks > 0) only = only == -1 ? c : -2;
+  if (only < 0 || (flags & (FT_PATH_DMA | FT_LOG)) || p->tuning[only].workgroups != 0) return FT_OK;
+  ClassPlan &cp = plan.cls[only];
+  ClassRun &r = job->run[only];
+  Layout lay = inline_layout_of(cp);
+  if (lay.end > kInlineBytes && cp.desc_per == 1 && cp.xfers.size() <= 4 * cp.funcs.size()) {
+    // few descriptors per function: the search over a function's descriptors is short
+    // enough without the table of descriptors per chunk, which is most of the bytes
+    bool few = true;
+    for (const Func &f : cp.funcs) few = few && f.ndesc <= 4;
+    if (few) {
+      cp.chunk_desc.clear();
+      lay = inline_layout_of(cp);
+    }
+  }
+  if (lay.end > kInlineBytes) return FT_OK;
+  const uint64_t ntickets = r.table.ntickets;
+  // host->pool: more than 64 tiles of 16 KiB requested at once is more than the link
+  // takes (2 MiB as 128 x 16 KiB: 52 us; as 64 workgroups drawing tickets: 43 us)
+  const uint64_t most = only == FT_P2P ? (uint64_t)p->ctx->cu_count : only == FT_H2P ? 64u : 128u;
+  const bool each_its_own = ntickets <= most;
+  if (!each_its_own) {
+    if (flags & FT_DETACHED) return FT_OK;
+    std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
+    if (p->ctx->free_pairs.empty()) return FT_OK;
+    r.counter_pair = (int)p->ctx->free_pairs.back();
+    p->ctx->free_pairs.pop_back();
+  }
+  job->inline_tables.reset(new InlineBlob());
+  char *h = reinterpret_cast<char *>(job->inline_tables->w);
+  int rc = prepare_class(p, job, only, cp, lay, h, nullptr, chunk_bytes, (flags & FT_TIMING) != 0);
+  if (rc != FT_OK) return fail_submit(p, job, rc);
+  ClassTable &T = r.table;
+  T.single = cp.funcs.size() == 1 && cp.xfers.size() == 1 && cp.funcs[0].chunk_base == 0 ? 1u : 0u;
+  uint64_t wg = ntickets;
+  if (each_its_own) {
+    T.ticket = p->ctx->idle_counter;
+  } else {
+    T.ticket = p->ctx->counter_pairs + 2 * r.counter_pair;
+    T.self_reset = 1;
+    wg = default_workgroups(p, only, only == FT_P2P);
+    if (wg > ntickets) wg = ntickets;
+  }
+  r.workgroups = (uint32_t)wg;
+  r.on_user_stream = true;
+  hipError_t e = launch_copy(T, only, r.workgroups, user, r.ev_begin, r.ev_end, job->inline_tables.get());
+  if (e == hipSuccess) e = hipEventRecord(r.ev_done, user);
+  if (e != hipSuccess) {
+    p->hip_error = std::string("launch on the caller's stream: ") + hipGetErrorString(e);
+    (void)hipDeviceSynchronize();  // the kernel may be running: its counter pair must be back at zero
+    return fail_submit(p, job, FT_EHIP);
+  }
+  *launched = true;
+  return FT_OK;
+}
+
+// The general way: the tables of all classes in one blob, copied to the device on the caller's
+// stream; each class's stream waits for that copy, runs its kernel (or, FT_PATH_DMA, its chunk
+// copies) and the caller's stream waits for it unless FT_DETACHED.
+int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chunk_bytes, uint32_t flags,
+                                hipStream_t user) {
+  const bool timing = (flags & FT_TIMING) != 0;
+  const bool dma = (flags & FT_PATH_DMA) != 0;
+  const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
+  Layout lay[FT_NCLASS];
+  uint64_t total = 0;
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    lay[c] = layout_of(plan.cls[c], total, 1);
+    if (plan.cls[c].nchunks > 0) total = lay[c].end;
+  }
+  int rc = get_blob(p, total, true, &job->tables);
+  if (rc != FT_OK) return fail_submit(p, job, rc);
+  std::memset(job->tables.host, 0, total);
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    const ClassPlan &cp = plan.cls[c];
+    if (cp.nchunks == 0) continue;
+    ClassRun &r = job->run[c];
+    rc = prepare_class(p, job, c, cp, lay[c], job->tables.host, job->tables.dev, chunk_bytes, timing);
+    if (rc != FT_OK) return fail_submit(p, job, rc);
+    ClassTable &T = r.table;
+    const Tuning &tn = p->tuning[c];
+    uint64_t wg = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
+    if (wg > T.ntickets) wg = T.ntickets;
+    r.workgroups = dma ? 0 : (uint32_t)wg;
+    if ((flags & FT_LOG) && !dma) {
+      rc = get_blob(p, T.ntickets * sizeof(LogEntry) + wg * sizeof(WgLogEntry), false, &r.log);
+      if (rc != FT_OK) return fail_submit(p, job, rc);
+      T.log = reinterpret_cast<LogEntry *>(r.log.dev);
+      T.wg_log = reinterpret_cast<WgLogEntry *>(r.log.dev + T.ntickets * sizeof(LogEntry));
+    }
+  }
+
+  // tables (and the zeroed ticket counters) travel on the caller's stream, then fork
+  hipEvent_t fork = nullptr;
+  rc = get_event(p, false, &fork);
+  if (rc != FT_OK) return fail_submit(p, job, rc);
+  auto hip_fail = [&](hipError_t e, const char *what) {
+    p->hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    put_event(p, false, fork);
+    return fail_submit(p, job, FT_EHIP);
+  };
+  hipError_t e = hipMemcpyAsync(job->tables.dev, job->tables.host, total, hipMemcpyHostToDevice, user);
+  if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(tables)");
+  e = hipEventRecord(fork, user);
+  if (e != hipSuccess) return hip_fail(e, "hipEventRecord(fork)");
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    ClassRun &r = job->run[c];
+    if (!r.used) continue;
+    hipStream_t s = p->ctx->streams[c];
+    e = hipStreamWaitEvent(s, fork, 0);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(fork)");
+    if (dma) {
+      if (timing) {
+        e = hipEventRecord(r.ev_begin, s);
+        if (e != hipSuccess) return hip_fail(e, "hipEventRecord(begin)");
+      }
+      rc = run_dma(p, plan.cls[c], chunk_bytes, c, s);
+      if (rc != FT_OK) {
+        put_event(p, false, fork);
+        return fail_submit(p, job, rc);
+      }
+      if (timing) {
+        e = hipEventRecord(r.ev_end, s);
+        if (e != hipSuccess) return hip_fail(e, "hipEventRecord(end)");
+      }
+    } else {
+      e = launch_copy(r.table, c, r.workgroups, s, r.ev_begin, r.ev_end);
+      if (e != hipSuccess) return hip_fail(e, "launch_copy");
+    }
+    e = hipEventRecord(r.ev_done, s);
+    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(done)");
+    if (!(flags & FT_DETACHED)) {
+      e = hipStreamWaitEvent(user, r.ev_done, 0);
+      if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(join)");
+    }
+  }
+  put_event(p, false, fork);
+  return FT_OK;
+}
+
+}  // namespace ft
+
 using namespace ft;
 
 extern "C" {
@@ -470,194 +671,11 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
     rc = ensure_device(p);
     if (rc != FT_OK) return rc;
     hipStream_t user = static_cast<hipStream_t>(hip_stream);
-    const bool timing = (flags & FT_TIMING) != 0;
-    const bool dma = (flags & FT_PATH_DMA) != 0;
-
-    // tile shape per class, then the descriptor table that goes with it
-    const bool with_p2p = plan.cls[FT_P2P].nchunks > 0;
-    for (int c = 0; c < FT_NCLASS; ++c) {
-      ClassPlan &cp = plan.cls[c];
-      if (cp.nchunks == 0) continue;
-      ClassRun &r = job->run[c];
-      const Tuning &tn = p->tuning[c];
-      tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
-                 &r.tile_bytes, &r.tiles_per_chunk);
-      build_chunk_table(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk);
-      build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &r.table.ntickets);
-    }
-    // every failure from here on must hand back what it took
-    auto fail = [&](int code) {
-      // work already queued may still read the tables: drain it before they are recycled
-      if (job->tables.dev != nullptr) (void)hipDeviceSynchronize();
-      release_device_side(p, job.get());
-      return code;
-    };
-
-    // A job of one link class whose tables fit into a kernel argument is launched on the
-    // caller's stream itself, tables in the launch: one launch and one event record instead
-    // of a table upload, a fork and a join across streams - 4 us of host time instead of
-    // 35 us, which is most of what passing a small tensor costs. If every ticket can have a
-    // workgroup of its own the counter is never consulted; a larger job takes one of the
-    // device's self-resetting counters (unless FT_DETACHED asks that the caller's stream be
-    // left alone for what may be a long time).
-    int only = -1;
-    for (int c = 0; c < FT_NCLASS; ++c)
-      if (plan.cls[c].nchunks > 0) only = only == -1 ? c : -2;
-    if (only >= 0 && !dma && !(flags & FT_LOG) && p->tuning[only].workgroups == 0) {
-      ClassPlan &cp = plan.cls[only];
-      ClassRun &r = job->run[only];
-      Layout lay = inline_layout_of(cp);
-      if (lay.end > kInlineBytes && cp.desc_per == 1 && cp.xfers.size() <= 4 * cp.funcs.size()) {
-        // few descriptors per function: the search over a function's descriptors is short
-        // enough without the table of descriptors per chunk, which is most of the bytes
-        bool few = true;
-        for (const Func &f : cp.funcs) few = few && f.ndesc <= 4;
-        if (few) {
-          cp.chunk_desc.clear();
-          lay = inline_layout_of(cp);
-        }
-      }
-      const uint64_t ntickets = r.table.ntickets;
-      // host->pool: more than 64 tiles of 16 KiB requested at once is more than the link
-      // takes (2 MiB as 128 x 16 KiB: 52 us; as 64 workgroups drawing tickets: 43 us)
-      const uint64_t most = only == FT_P2P ? (uint64_t)p->ctx->cu_count : only == FT_H2P ? 64u : 128u;
-      const bool each_its_own = ntickets <= most;
-      if (lay.end <= kInlineBytes && !each_its_own && !(flags & FT_DETACHED)) {
-        std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
-        if (!p->ctx->free_pairs.empty()) {
-          r.counter_pair = (int)p->ctx->free_pairs.back();
-          p->ctx->free_pairs.pop_back();
-        }
-      }
-      if (lay.end <= kInlineBytes && (each_its_own || r.counter_pair >= 0)) {
-        job->inline_tables.reset(new InlineBlob());
-        char *h = reinterpret_cast<char *>(job->inline_tables->w);
-        ClassTable &T = r.table;
-        fill_tables(cp, lay, h, nullptr, &T);
-        std::memcpy(h + lay.skips, r.skips.data(), r.skips.size() * sizeof(Skip));
-        T.ntickets = ntickets;
-        T.nskips = (uint32_t)r.skips.size();
-        set_cursor_start(T, cp.phases.data(), (uint32_t)cp.phases.size(), r.skips.data(), T.nskips);
-        T.chunk_bytes = chunk_bytes;
-        T.tile_bytes = r.tile_bytes;
-        T.tiles_per_chunk = r.tiles_per_chunk;
-        T.single = cp.funcs.size() == 1 && cp.xfers.size() == 1 && cp.funcs[0].chunk_base == 0 ? 1u : 0u;
-        uint64_t wg = ntickets;
-        if (each_its_own) {
-          T.ticket = p->ctx->idle_counter;
-        } else {
-          T.ticket = p->ctx->counter_pairs + 2 * r.counter_pair;
-          T.self_reset = 1;
-          wg = default_workgroups(p, only, only == FT_P2P);
-          if (wg > ntickets) wg = ntickets;
-        }
-        r.used = true;
-        r.workgroups = (uint32_t)wg;
-        r.on_user_stream = true;
-        rc = get_event(p, false, &r.ev_done);
-        if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_begin);
-        if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_end);
-        if (rc != FT_OK) return fail(rc);
-        hipError_t e = launch_copy(T, only, r.workgroups, user, r.ev_begin, r.ev_end, job->inline_tables.get());
-        if (e == hipSuccess) e = hipEventRecord(r.ev_done, user);
-        if (e != hipSuccess) {
-          p->hip_error = std::string("launch on the caller's stream: ") + hipGetErrorString(e);
-          (void)hipDeviceSynchronize();  // the kernel may be running: its counter pair must be back at zero
-          return fail(FT_EHIP);
-        }
-        goto launched;
-      }
-    }
-    {
-    // lay the tables of all classes out in one blob
-    Layout lay[FT_NCLASS];
-    uint64_t total = 0;
-    for (int c = 0; c < FT_NCLASS; ++c) {
-      lay[c] = layout_of(plan.cls[c], total, 1);
-      if (plan.cls[c].nchunks > 0) total = lay[c].end;
-    }
-    rc = get_blob(p, total, true, &job->tables);
-    if (rc != FT_OK) return fail(rc);
-    std::memset(job->tables.host, 0, total);
-    for (int c = 0; c < FT_NCLASS; ++c) {
-      ClassPlan &cp = plan.cls[c];
-      if (cp.nchunks == 0) continue;
-      ClassRun &r = job->run[c];
-      r.used = true;
-      char *h = job->tables.host, *d = job->tables.dev;
-      const Tuning &tn = p->tuning[c];
-      ClassTable &T = r.table;
-      const uint64_t ntickets = T.ntickets;
-      fill_tables(cp, lay[c], h, d, &T);
-      T.ntickets = ntickets;
-      std::memcpy(h + lay[c].skips, r.skips.data(), r.skips.size() * sizeof(Skip));
-      T.nskips = (uint32_t)r.skips.size();
-      set_cursor_start(T, cp.phases.data(), (uint32_t)cp.phases.size(), r.skips.data(), T.nskips);
-      T.chunk_bytes = chunk_bytes;
-      T.tile_bytes = r.tile_bytes;
-      T.tiles_per_chunk = r.tiles_per_chunk;
-      uint64_t wg = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
-      if (wg > T.ntickets) wg = T.ntickets;
-      r.workgroups = dma ? 0 : (uint32_t)wg;
-      if ((flags & FT_LOG) && !dma) {
-        rc = get_blob(p, T.ntickets * sizeof(LogEntry) + wg * sizeof(WgLogEntry), false, &r.log);
-        if (rc != FT_OK) return fail(rc);
-        T.log = reinterpret_cast<LogEntry *>(r.log.dev);
-        T.wg_log = reinterpret_cast<WgLogEntry *>(r.log.dev + T.ntickets * sizeof(LogEntry));
-      }
-      rc = get_event(p, false, &r.ev_done);
-      if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_begin);
-      if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_end);
-      if (rc != FT_OK) return fail(rc);
-    }
-
-    // tables (and the zeroed ticket counters) travel on the caller's stream, then fork
-    hipEvent_t fork = nullptr;
-    rc = get_event(p, false, &fork);
-    if (rc != FT_OK) return fail(rc);
-    auto hip_fail = [&](hipError_t e, const char *what) {
-      p->hip_error = std::string(what) + ": " + hipGetErrorString(e);
-      put_event(p, false, fork);
-      return fail(FT_EHIP);
-    };
-    hipError_t e = hipMemcpyAsync(job->tables.dev, job->tables.host, total, hipMemcpyHostToDevice, user);
-    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(tables)");
-    e = hipEventRecord(fork, user);
-    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(fork)");
-    for (int c = 0; c < FT_NCLASS; ++c) {
-      ClassRun &r = job->run[c];
-      if (!r.used) continue;
-      hipStream_t s = p->ctx->streams[c];
-      e = hipStreamWaitEvent(s, fork, 0);
-      if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(fork)");
-      if (dma) {
-        if (timing) {
-          e = hipEventRecord(r.ev_begin, s);
-          if (e != hipSuccess) return hip_fail(e, "hipEventRecord(begin)");
-        }
-        rc = run_dma(p, plan.cls[c], chunk_bytes, c, s);
-        if (rc != FT_OK) {
-          put_event(p, false, fork);
-          return fail(rc);
-        }
-        if (timing) {
-          e = hipEventRecord(r.ev_end, s);
-          if (e != hipSuccess) return hip_fail(e, "hipEventRecord(end)");
-        }
-      } else {
-        e = launch_copy(r.table, c, r.workgroups, s, r.ev_begin, r.ev_end);
-        if (e != hipSuccess) return hip_fail(e, "launch_copy");
-      }
-      e = hipEventRecord(r.ev_done, s);
-      if (e != hipSuccess) return hip_fail(e, "hipEventRecord(done)");
-      if (!(flags & FT_DETACHED)) {
-        e = hipStreamWaitEvent(user, r.ev_done, 0);
-        if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(join)");
-      }
-    }
-    put_event(p, false, fork);
-    }
-  launched:;
+    shape_classes(p, job.get(), plan, chunk_bytes);
+    bool launched = false;
+    rc = launch_with_the_launch(p, job.get(), plan, chunk_bytes, flags, user, &launched);
+    if (rc == FT_OK && !launched) rc = launch_with_uploaded_tables(p, job.get(), plan, chunk_bytes, flags, user);
+    if (rc != FT_OK) return rc;
   }
 
   for (int c = 0; c < FT_NCLASS; ++c) job->run[c].plan = std::move(plan.cls[c]);
