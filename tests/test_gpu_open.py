@@ -536,3 +536,55 @@ def test_pool_to_pool_open_job_triggers_sixteen_times_larger_batches(gpu):
         binding.job_release(eng.pool, j1)
     finally:
         eng.close()
+
+
+def test_two_pools_driven_from_two_threads(gpu):
+    """Two pools on one device share its streams, table buffers, events and counter pairs. Two threads
+    run twenty jobs each (small ones that travel with the launch, larger ones with uploaded tables, an
+    open job with a merge) at the same time; each pool's memory must be its own oracle's."""
+    import threading
+    binding, harness = gpu
+    pairs = []
+    for t in range(2):
+        orc, eng, rng = _engines(gpu, 48 * MiB, 128 * MiB, seed=61 + t)
+        pairs.append((orc, eng, rng))
+    err = []
+
+    def work(t):
+        orc, eng, rng = pairs[t]
+        try:
+            for i in range(20):
+                kind = i % 4
+                sizes = [[int(rng.integers(1, 200000))], [int(rng.integers(1 * MiB, 3 * MiB)), 70001],
+                         [5 * MiB + 3, 2 * MiB], [int(rng.integers(64 * KiB, 900 * KiB))]][kind]
+                d = make_descs(_h2p_job(orc, eng, rng, sizes, 24 * MiB))
+                w = [1 + (i + f) % 3 for f in range(len(sizes))]
+                orc.wait(orc.submit(d, w, 256 * KiB))
+                if kind == 2:
+                    extra = make_descs(_h2p_job(orc, eng, rng, [300001], 24 * MiB))
+                    orc.wait(orc.submit(extra, [4], 256 * KiB))
+                    j0 = eng.submit(d, w, 256 * KiB, fmt.FT_OPEN)
+                    try:
+                        j1 = eng.merge(j0, extra, [4])
+                    except binding.FtError as e:
+                        assert e.code == fmt.FT_ECLOSED
+                        j1 = eng.submit(extra, [4], 256 * KiB, 0)
+                    eng.wait(j1)
+                    eng.wait(j0)
+                else:
+                    eng.wait(eng.submit(d, w, 256 * KiB, fmt.FT_DETACHED if kind == 1 else 0))
+        except Exception as e:      # noqa: BLE001
+            err.append((t, repr(e)))
+    try:
+        threads = [threading.Thread(target=work, args=(t,)) for t in range(2)]
+        for th in threads:
+            th.start()
+        for th in threads:
+            th.join(timeout=120)
+            assert not th.is_alive()
+        assert not err, err
+        for orc, eng, _ in pairs:
+            _images_equal(orc, eng)
+    finally:
+        for _, eng, _ in pairs:
+            eng.close()
