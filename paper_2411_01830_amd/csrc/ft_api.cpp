@@ -837,14 +837,17 @@ int ft_job_schedule(ft_pool *p, ft_job_t id, int link_class, uint32_t *func_out,
   uint64_t n = r.plan.nchunks < cap ? r.plan.nchunks : cap;
   if (!r.used || n == 0) return FT_OK;
   DeviceGuard guard(p->device);
-  uint32_t *dev = nullptr;
-  FT_HIP(p, hipMalloc(reinterpret_cast<void **>(&dev), 2 * n * sizeof(uint32_t)));
+  Blob out;  // recycled like the table buffers
+  int rc = get_blob(p, 2 * n * sizeof(uint32_t), false, &out);
+  if (rc != FT_OK) return rc;
+  uint32_t *dev = reinterpret_cast<uint32_t *>(out.dev);
   hipStream_t s = p->ctx->streams[link_class];  // ordered after the job's own kernel and table upload
   hipError_t e = launch_decode(r.table, dev, dev + n, n, s, job->inline_tables.get());
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e == hipSuccess) e = hipMemcpy(func_out, dev, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
   if (e == hipSuccess) e = hipMemcpy(chunk_out, dev + n, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
-  (void)hipFree(dev);
+  if (e != hipSuccess) (void)hipDeviceSynchronize();  // the decode may still be writing
+  put_blob(p, out);
   if (e != hipSuccess) {
     p->hip_error = std::string("ft_job_schedule: ") + hipGetErrorString(e);
     return FT_EHIP;
