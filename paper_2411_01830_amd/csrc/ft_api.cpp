@@ -230,12 +230,12 @@ uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
 
 // short_rows: most of the class's payload sits in pitched descriptors with rows of at
 // most 2 KiB (a gather of image crops). Such a tile is bound by latency - a pass of the
-// row-gather routine (3 destination granules per lane, just under 12 KiB) is one memory
-// round trip - and by what a tile costs whatever its size: its ticket (the counter hands
-// out about 70 million tickets a second, all workgroups together, so tiles must not be
-// too small), the decode, the barrier. Tiles of 16 passes measured best on the crops of
-// the traffic workload: 63 us against 86 us for one pass per tile; beyond that too few
-// tiles are left per workgroup to balance the launch's end.
+// row-gather routine (4 destination granules per lane, 16 KiB) is one memory round trip -
+// and by what a tile costs whatever its size: its ticket (the counter hands out about 70
+// million tickets a second, all workgroups together, so tiles must not be too small), the
+// decode, the barrier. Tiles of just under 64 KiB measured best on the crops of the
+// traffic workload (58 us; 76 us at 16 KiB, 64 us at 32 KiB); beyond that too few tiles
+// are left per workgroup to balance the launch's end.
 uint64_t default_tile(int cls, bool with_p2p, bool short_rows) {
   if (cls == FT_P2P) return short_rows ? 16u * 4096u - 16u : 64u * 1024u;
   return (with_p2p || cls == FT_P2H) ? 8u * 1024u : 16u * 1024u;
