@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # workload (FETCH_SIZE and WRITE_SIZE runs, each scaled by a plain copy of known size);
 # see profiles/pmc_hbm_traffic_pool_to_pool_<workload>.md. Workloads without such a run
 # report null.
-TRAFFIC_PER_ALGO_BYTE = {"large_mixed": 1.0124, "feature": 1.0009, "traffic_crops": 1.4125}
+TRAFFIC_PER_ALGO_BYTE = {"large_mixed": 1.0124, "feature": 1.0009, "traffic_crops": 1.4118}
 
 
 def parse_args():
@@ -328,8 +328,7 @@ def pinned_ring(peaks):
     ts.sort()
     out["to_pageable"] = {"ring_4_threads_GBps": round(total / ts[1] / 1e9, 2),
                           "ring_link_frac": round(total / ts[1] / 1e9 / peaks["d2h"], 4)}
-    # the runtime's own copies between the same pageable memory and the device, measured last (after
-    # the runtime has copied from or to that memory, the library's threads move it more slowly: 45 against 52 GB/s)
+    # the runtime's own copies between the same pageable memory and the device, measured last
     host_t = torch.from_numpy(eng.pageable_np)
     dev_t = torch.empty(total, dtype=torch.uint8, device="cuda:0")
     for key, dst, src in (("runtime_copy_from_pageable_GBps", dev_t, host_t), ("runtime_copy_to_pageable_GBps", host_t, dev_t)):

@@ -50,7 +50,16 @@ class GpuEngine:
 
     def pageable_arena(self, nbytes, fill=0x3C):
         """Ordinary (not pinned) host memory for FT_PAGEABLE; addresses are offsets into it."""
-        self.pageable_np = np.full(int(nbytes), fill, dtype=np.uint8)
+        # anonymous memory that the kernel may back with huge pages, as a long-lived process's heap would be
+        import mmap
+        self._pageable_map = mmap.mmap(-1, int(nbytes))
+        if hasattr(mmap, "MADV_HUGEPAGE"):
+            try:
+                self._pageable_map.madvise(mmap.MADV_HUGEPAGE)
+            except OSError:
+                pass
+        self.pageable_np = np.frombuffer(self._pageable_map, dtype=np.uint8)
+        self.pageable_np[:] = fill
         if self.pool is not None:
             ft.pageable_window_add(self.pool, self.pageable_np.ctypes.data, int(nbytes))
 
