@@ -144,3 +144,114 @@ def simulate_queue(sizes, capacity, lookahead, policy):
         ev, rl = policy(view(head + 1), capacity, 0)
         apply(ev, rl)
     return {"stalls": stalls, "bytes_out": bytes_out, "bytes_in": bytes_in}
+
+
+class Store:
+    """The store of Sec. 7.2 over any engine object (slab_alloc / slab_free / submit / wait): results
+    wait in the pool under a byte budget; the queue-aware rule above decides what moves to host memory
+    and back, each move being one pool->host or host->pool transfer. The spill arena is a first-fit
+    allocator in units of 4096 bytes over [spill_off, spill_off + spill_bytes) of the engine's host
+    arena. Operations and their order of effects:
+
+      put(id, nbytes, queue_pos)  evictions named by plan_queue_aware(objects, capacity, nbytes), in its
+                                  order; then the allocation. Returns the pool offset.
+      get(id)                     if the result is out: evictions named by the plan over the other
+                                  objects with its bytes incoming, then it is brought back (a stall).
+                                  Returns (offset, was_out).
+      done(id)                    the result is dropped; then plan(objects, capacity, 0): evictions (none
+                                  unless the budget was passed) and reloads in its order, a reload that
+                                  finds no run of free slabs ends them.
+      advance(steps)              every queue_pos decreases by steps, not below 0.
+    """
+
+    def __init__(self, engine, spill_off, spill_bytes, capacity, chunk_bytes, make_descs, host_space, pool_space):
+        self.eng = engine
+        self.spill_off, self.capacity, self.chunk = spill_off, capacity, chunk_bytes
+        self.units = [False] * (spill_bytes // 4096)
+        self.objs = {}
+        self.make_descs, self.HOST, self.POOL = make_descs, host_space, pool_space
+        self.log = []
+        self.stalls = 0
+
+    def _spill_alloc(self, nbytes):
+        need = -(-nbytes // 4096)
+        run = 0
+        for i, used in enumerate(self.units):
+            run = 0 if used else run + 1
+            if run == need:
+                first = i - need + 1
+                for j in range(first, i + 1):
+                    self.units[j] = True
+                return first * 4096
+        raise MemoryError("spill arena full")
+
+    def _spill_free(self, at, nbytes):
+        for j in range(at // 4096, at // 4096 + -(-nbytes // 4096)):
+            self.units[j] = False
+
+    def _move(self, src_space, src, dst_space, dst, n):
+        d = self.make_descs([dict(func=0, src_space=src_space, dst_space=dst_space, src=src, dst=dst, row_bytes=n)])
+        self.eng.wait(self.eng.submit(d, [1], self.chunk))
+
+    def _view(self, skip=None):
+        return [dict(id=i, bytes=o["bytes"], queue_pos=o["queue_pos"], resident=o["resident"])
+                for i, o in sorted(self.objs.items()) if i != skip]
+
+    def _out(self, i):
+        o = self.objs[i]
+        o["spill"] = self._spill_alloc(o["bytes"])
+        self._move(self.POOL, o["off"], self.HOST, self.spill_off + o["spill"], o["bytes"])
+        self.eng.slab_free(o["off"])
+        o["resident"] = False
+        self.log.append(("out", i))
+
+    def _in(self, i):
+        o = self.objs[i]
+        o["off"] = self.eng.slab_alloc(o["bytes"])
+        self._move(self.HOST, self.spill_off + o["spill"], self.POOL, o["off"], o["bytes"])
+        self._spill_free(o["spill"], o["bytes"])
+        o["resident"] = True
+        self.log.append(("in", i, o["off"]))
+
+    def put(self, i, nbytes, queue_pos):
+        assert i not in self.objs and 0 < nbytes <= self.capacity
+        evict, _ = plan_queue_aware(self._view(), self.capacity, nbytes)
+        for e in evict:
+            self._out(e)
+        off = self.eng.slab_alloc(nbytes)
+        self.objs[i] = dict(bytes=nbytes, queue_pos=queue_pos, resident=True, off=off)
+        self.log.append(("put", i, off))
+        return off
+
+    def get(self, i):
+        o = self.objs[i]
+        was_out = not o["resident"]
+        if was_out:
+            evict, _ = plan_queue_aware(self._view(skip=i), self.capacity, o["bytes"])
+            for e in evict:
+                self._out(e)
+            self._in(i)
+            self.stalls += 1
+        return o["off"], was_out
+
+    def done(self, i):
+        o = self.objs.pop(i)
+        assert o["resident"]
+        self.eng.slab_free(o["off"])
+        evict, reload = plan_queue_aware(self._view(), self.capacity, 0)
+        for e in evict:
+            self._out(e)
+        for r in reload:
+            try:
+                self._in(r)
+            except Exception as e:      # noqa: BLE001  (the engine's "no run of free slabs")
+                if getattr(e, "code", None) != -2:
+                    raise
+                break
+
+    def advance(self, steps):
+        for o in self.objs.values():
+            o["queue_pos"] = max(o["queue_pos"] - steps, 0)
+
+    def resident_bytes(self):
+        return sum(o["bytes"] for o in self.objs.values() if o["resident"])

@@ -210,3 +210,85 @@ def test_library_pool_shrink_matches_oracle():
             assert ft.pool_shrink(pool) == (seg_bases.pop(), want)
         assert ft.pool_usage(pool) == (orc.total_bytes, orc.live_bytes)
     ft.pool_destroy(pool)
+
+
+def _oracle_store(capacity, pool_bytes=1 << 20, spill_bytes=1 << 20, slab=4096):
+    from oracle import OracleEngine
+    from oracle.store import Store
+    from workloads import make_descs, FT_HOST, FT_POOL
+    eng = OracleEngine()
+    eng.host_arena(spill_bytes + 4096)
+    eng.pool_create(pool_bytes, slab)
+    return eng, Store(eng, 4096, spill_bytes, capacity, 4096, make_descs, FT_HOST, FT_POOL)
+
+
+def test_store_follows_the_papers_example():
+    """Sec. 7.2's example as a run of the store: the outputs of a1 and a2 fill it, b1 is next in the
+    queue and b2 after it. A third output arrives: the output whose consumer is furthest back (a2's)
+    goes to the host, not the oldest one (a1's, which b1 is about to read); once b1 is done with a1's
+    output, a2's comes back before b2 asks for it, so b2 does not stall."""
+    eng, st = _oracle_store(capacity=2 * 8192)
+    o1 = st.put(1, 8192, 0)
+    o2 = st.put(2, 8192, 1)
+    eng.write_pool(o1, np.full(8192, 11, np.uint8))
+    eng.write_pool(o2, np.full(8192, 22, np.uint8))
+    o3 = st.put(3, 8192, 2)
+    eng.write_pool(o3, np.full(8192, 33, np.uint8))
+    # a3's own consumer is the furthest of all, but the rule only moves what is already stored: a2's goes
+    assert [e for e in st.log if e[0] == "out"] == [("out", 2)]
+    assert st.get(1) == (o1, False)
+    st.done(1)
+    assert ("in", 2, st.objs[2]["off"]) in st.log            # came back as soon as there was room
+    st.advance(1)
+    off, was_out = st.get(2)
+    assert not was_out and st.stalls == 0
+    assert np.all(eng.read_pool(off, 8192) == 22)            # and its bytes made the round trip
+
+
+def test_store_random_runs_keep_the_budget_and_the_bytes():
+    """Random puts, gets, dones and queue steps: the pool never holds more than the budget, a result
+    read after any number of moves is the bytes that were stored, a get of a resident result moves
+    nothing, no eviction is made that the budget did not require, spilled copies never overlap."""
+    rng = np.random.default_rng(5)
+    for trial in range(20):
+        cap = int(rng.integers(6, 20)) * 4096
+        eng, st = _oracle_store(capacity=cap)
+        content = {}
+        next_id = 0
+        for step in range(120):
+            op = rng.choice(["put", "put", "get", "done", "advance"])
+            ids = sorted(st.objs)
+            if op == "put":
+                n = int(rng.integers(1, 5 * 4096))
+                before_out = sum(1 for e in st.log if e[0] == "out")
+                res_before = st.resident_bytes()
+                off = st.put(next_id, n, int(rng.integers(0, 12)))
+                data = rng.integers(0, 256, n, dtype=np.uint8)
+                eng.write_pool(off, data)
+                content[next_id] = data
+                outs = [e[1] for e in st.log if e[0] == "out"][before_out:]
+                if outs:        # without the last eviction the budget would have been passed
+                    assert res_before - sum(len(content[i]) for i in outs[:-1]) + n > cap
+                next_id += 1
+            elif op == "get" and ids:
+                i = int(rng.choice(ids))
+                moves = len(st.log)
+                resident = st.objs[i]["resident"]
+                off, was_out = st.get(i)
+                assert was_out == (not resident)
+                if resident:
+                    assert len(st.log) == moves
+                assert np.array_equal(eng.read_pool(off, len(content[i])), content[i])
+            elif op == "done" and ids:
+                i = int(rng.choice(ids))
+                st.get(i)
+                st.done(i)
+                del content[i]
+            elif op == "advance":
+                st.advance(int(rng.integers(0, 3)))
+            assert st.resident_bytes() <= cap
+            spans = sorted((o["spill"], o["spill"] + o["bytes"]) for o in st.objs.values() if not o["resident"])
+            assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
+        for i in sorted(st.objs):
+            off, _ = st.get(i)
+            assert np.array_equal(eng.read_pool(off, len(content[i])), content[i])
