@@ -335,6 +335,46 @@ typedef struct ft_object {
 int ft_migrate_plan(const ft_object *objs, uint32_t n, uint64_t capacity, uint64_t incoming, uint32_t policy,
                     uint64_t *evict_ids, uint32_t *n_evict, uint64_t *reload_ids, uint32_t *n_reload);
 
+/*
+ * A store of intermediate results under a byte budget, with the queue-aware migration of
+ * Sec. 7.2 carried out by the engine itself. `capacity` bytes of results may wait in the
+ * pool; `spill_base` / `spill_bytes` is pinned host memory (device-visible, 4096-byte
+ * aligned, a multiple of 4096 bytes, owned by the caller; the store declares it to the
+ * pool as a host window) that takes what does not fit. ids must grow with store time
+ * (ties of the rule go by id); queue_pos is the position of the result's consumer in the
+ * request queue (0 = next to run).
+ *   ft_store_put      makes room by the rule of ft_migrate_plan (furthest consumer out
+ *                     first), allocates nbytes from the pool and returns the offset; the
+ *                     caller then writes the result there. FT_ENOMEM: nbytes > capacity,
+ *                     the spill arena is full, or the pool has no run of free slabs (grow
+ *                     it and call again; what has been moved out stays out).
+ *   ft_store_get      the consumer runs now: if the result was moved out, room is made
+ *                     and it is brought back first (*was_out = 1, host pointer, may be
+ *                     NULL). Returns where it is.
+ *   ft_store_done     the consumer has finished (and its transfers have been waited for,
+ *                     else FT_EBUSY): the result is dropped, and results that were moved
+ *                     out come back while they fit, nearest consumer first.
+ *   ft_store_advance  the queue has moved: every queue_pos decreases by `steps` (not below 0).
+ * Every move is one pool->host or host->pool job on hip_stream, waited for inside the
+ * call. One mutex per store.
+ */
+typedef struct ft_store ft_store;
+typedef struct ft_store_stats_t {
+  uint64_t objects;        /* results held, in the pool or out */
+  uint64_t resident_bytes; /* of them, bytes in the pool */
+  uint64_t moved_out, bytes_out;
+  uint64_t moved_in, bytes_in;
+  uint64_t stalls;         /* ft_store_get calls that had to bring the result back */
+} ft_store_stats_t;
+int ft_store_create(ft_store **out, ft_pool *pool, void *spill_base, uint64_t spill_bytes, uint64_t capacity,
+                    uint64_t chunk_bytes, void *hip_stream);
+int ft_store_put(ft_store *s, uint64_t id, uint64_t nbytes, uint64_t queue_pos, ft_off_t *off_out);
+int ft_store_get(ft_store *s, uint64_t id, ft_off_t *off_out, uint32_t *was_out);
+int ft_store_done(ft_store *s, uint64_t id);
+int ft_store_advance(ft_store *s, uint64_t steps);
+int ft_store_stats(ft_store *s, ft_store_stats_t *out);
+int ft_store_destroy(ft_store *s);
+
 /* -------------------------------------- parallel paths between GPUs (Sec. 6.2, Alg. 1) */
 
 /*

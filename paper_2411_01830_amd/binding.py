@@ -16,7 +16,7 @@ EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_shrink", "ft_pool_usage", 
            "ft_sizer_observe", "ft_sizer_target", "ft_sizer_destroy", "ft_migrate_plan", "ft_links_create",
            "ft_links_select", "ft_links_paths", "ft_links_release", "ft_links_free", "ft_links_destroy",
            "ft_stripe_chunks", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
-           "ft_pool_ptr", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_submit_transfers", "ft_submit_merge", "ft_set_batch",
+           "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_submit_transfers", "ft_submit_merge", "ft_set_batch",
            "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
            "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
            "ft_plain_copy", "ft_strerror", "ft_last_hip_error"]
@@ -32,6 +32,11 @@ class ClassStats(C.Structure):
     _fields_ = [("payload_bytes", C.c_uint64), ("chunks", C.c_uint64), ("tickets", C.c_uint64),
                 ("tile_bytes", C.c_uint64), ("workgroups", C.c_uint32), ("in_launch", C.c_uint32),
                 ("device_ms", C.c_float), ("_pad2", C.c_float)]
+
+
+class StoreStats(C.Structure):
+    _fields_ = [("objects", C.c_uint64), ("resident_bytes", C.c_uint64), ("moved_out", C.c_uint64),
+                ("bytes_out", C.c_uint64), ("moved_in", C.c_uint64), ("bytes_in", C.c_uint64), ("stalls", C.c_uint64)]
 
 
 class JobStats(C.Structure):
@@ -60,6 +65,13 @@ def _load():
         "ft_sizer_target": (i32, [vp, C.c_double, P(u64)]),
         "ft_sizer_destroy": (i32, [vp]),
         "ft_migrate_plan": (i32, [vp, u32, u64, u64, u32, vp, P(u32), vp, P(u32)]),
+        "ft_store_create": (i32, [C.POINTER(vp), vp, vp, u64, u64, u64, vp]),
+        "ft_store_put": (i32, [vp, u64, u64, u64, C.POINTER(u64)]),
+        "ft_store_get": (i32, [vp, u64, C.POINTER(u64), C.POINTER(u32)]),
+        "ft_store_done": (i32, [vp, u64]),
+        "ft_store_advance": (i32, [vp, u64]),
+        "ft_store_stats": (i32, [vp, C.POINTER(StoreStats)]),
+        "ft_store_destroy": (i32, [vp]),
         "ft_links_create": (i32, [P(vp), u32, vp, u32]),
         "ft_links_select": (i32, [vp, u32, u32, u32]),
         "ft_links_paths": (i32, [vp, u32, vp, u32, vp, vp, u32, P(u32)]),
@@ -172,6 +184,41 @@ def migrate_plan(objects, capacity, incoming=0, policy=FT_EVICT_QUEUE_AWARE):
     _check(_lib.ft_migrate_plan(a.ctypes.data, len(objects), capacity, incoming, policy, ev.ctypes.data,
                                 C.byref(ne), rl.ctypes.data, C.byref(nr)))
     return ev[:ne.value].tolist(), rl[:nr.value].tolist()
+
+
+class Store:
+    """Store of intermediate results with queue-aware migration (Sec. 7.2; ft_store_*)."""
+
+    def __init__(self, pool, spill_ptr, spill_bytes, capacity, chunk_bytes, stream=None):
+        self._h = C.c_void_p()
+        self.pool = pool
+        _check(_lib.ft_store_create(C.byref(self._h), pool, spill_ptr, spill_bytes, capacity, chunk_bytes, stream), pool)
+
+    def put(self, obj_id, nbytes, queue_pos):
+        off = C.c_uint64()
+        _check(_lib.ft_store_put(self._h, obj_id, nbytes, queue_pos, C.byref(off)), self.pool)
+        return off.value
+
+    def get(self, obj_id):
+        off, was_out = C.c_uint64(), C.c_uint32()
+        _check(_lib.ft_store_get(self._h, obj_id, C.byref(off), C.byref(was_out)), self.pool)
+        return off.value, bool(was_out.value)
+
+    def done(self, obj_id):
+        _check(_lib.ft_store_done(self._h, obj_id), self.pool)
+
+    def advance(self, steps):
+        _check(_lib.ft_store_advance(self._h, steps), self.pool)
+
+    def stats(self):
+        st = StoreStats()
+        _check(_lib.ft_store_stats(self._h, C.byref(st)), self.pool)
+        return st
+
+    def close(self):
+        if self._h:
+            _lib.ft_store_destroy(self._h)
+            self._h = None
 
 
 class Links:

@@ -160,3 +160,73 @@ def test_elastic_store_matches_oracle():
         gsz.close()
     finally:
         eng.close()
+
+
+def test_native_store_matches_the_oracle_store():
+    """The library's own store (ft_store_*) against the oracle's store on a two-stage workflow under
+    memory pressure with out-of-order consumers: every offset it hands out, every stall, the counts and
+    bytes of its moves, and afterwards the whole pool, the whole spill arena and what each consumer read."""
+    import torch
+    from oracle.store import Store as OracleStore
+    from paper_2411_01830_amd import binding as ft, harness
+    rng = np.random.default_rng(11)
+    n, lookahead = 60, 7
+    sizes = [int(x) for x in rng.integers(100 * KiB, 900 * KiB, n)]
+    sizes[25:31] = [int(x) for x in rng.integers(1500 * KiB, 2500 * KiB, 6)]
+    capacity, pool_bytes = 5 * MiB, 12 * MiB
+    spill_off, spill_bytes, results_off = 4 * MiB, 40 * MiB, 1 * MiB
+    payload = [rng.integers(0, 256, s, dtype=np.uint8) for s in sizes]
+    order = list(range(n))
+    for k in range(0, n - 3, 5):                      # now and then a later request overtakes
+        order[k + 1], order[k + 2] = order[k + 2], order[k + 1]
+
+    def run(eng, store):
+        trace = []
+        stored = 0
+        for step, head in enumerate(order):
+            while stored < n and stored <= step + lookahead:
+                off = store.put(stored, sizes[stored], stored - step if stored > step else 0)
+                eng.write_pool(off, payload[stored])
+                trace.append(("put", stored, off))
+                stored += 1
+            off, was_out = store.get(head)
+            trace.append(("get", head, off, was_out))
+            take = min(4096, sizes[head])
+            d = make_descs([dict(func=0, src_space=FT_POOL, dst_space=FT_HOST, src=off, dst=results_off + head * 4096,
+                                 row_bytes=take)])
+            eng.wait(eng.submit(d, [1], 256 * KiB))
+            store.done(head)
+            store.advance(1)
+        return trace
+
+    orc = OracleEngine()
+    orc.host_arena(spill_off + spill_bytes)
+    orc.pool_create(pool_bytes, 64 * KiB)
+    ost = OracleStore(orc, spill_off, spill_bytes, capacity, 256 * KiB, make_descs, FT_HOST, FT_POOL)
+    trace_o = run(orc, ost)
+
+    eng = harness.GpuEngine()
+    try:
+        eng.host_arena(spill_off + spill_bytes)
+        eng.pool_create(pool_bytes, 64 * KiB)
+        gst = ft.Store(eng.pool, eng.host.data_ptr() + spill_off, spill_bytes, capacity, 256 * KiB,
+                       torch.cuda.current_stream().cuda_stream)
+        trace_g = run(eng, gst)
+        assert trace_g == trace_o
+        st = gst.stats()
+        outs = [e for e in ost.log if e[0] == "out"]
+        ins = [e for e in ost.log if e[0] == "in"]
+        assert (st.moved_out, st.moved_in, st.stalls) == (len(outs), len(ins), ost.stalls)
+        assert st.bytes_out == sum(sizes[e[1]] for e in outs) and st.bytes_in == sum(sizes[e[1]] for e in ins)
+        assert st.objects == 0 and st.resident_bytes == 0
+        assert len(outs) >= 10 and ost.stalls >= 1 and len(ins) > ost.stalls      # moves, stalls and early returns all occur
+        assert np.array_equal(eng.host_np, orc.host_mem), "host image (results and spill arena) differs"
+        got = torch.cat([t for t, _ in eng.segments]).cpu().numpy()
+        assert np.array_equal(got, orc.pool_mem), "pool image differs"
+        for i in range(n):
+            take = min(4096, sizes[i])
+            assert np.array_equal(eng.host_np[results_off + i * 4096:results_off + i * 4096 + take], payload[i][:take]), i
+        print("store moves:", {"out": st.moved_out, "in": st.moved_in, "stalls": st.stalls}, flush=True)
+        gst.close()
+    finally:
+        eng.close()
