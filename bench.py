@@ -503,26 +503,29 @@ def store_on_device():
     pool_bytes, spill_bytes = 2 << 30, 4 << 30
     dev = torch.empty(pool_bytes, dtype=torch.uint8, device="cuda:0")
     host = torch.empty(spill_bytes, dtype=torch.uint8, pin_memory=True)
-    pool = ft.pool_create(dev.data_ptr(), pool_bytes, 1 << 20, 0)
-    store = ft.Store(pool, host.data_ptr(), spill_bytes, cap, 2 << 20, torch.cuda.current_stream().cuda_stream)
-    stored = 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for head in range(n):
-        while stored < n and stored <= head + lookahead:
-            store.put(stored, int(sizes[stored]), stored - head)
-            stored += 1
-        store.get(head)
-        store.done(head)
-        store.advance(1)
-    wall = time.perf_counter() - t0
-    st = store.stats()
+    # twice: the first pass also pays for the device's first writes into the fresh pinned arena
+    # (moves out at 25 GB/s instead of 55)
+    for _ in range(2):
+        pool = ft.pool_create(dev.data_ptr(), pool_bytes, 1 << 20, 0)
+        store = ft.Store(pool, host.data_ptr(), spill_bytes, cap, 2 << 20, torch.cuda.current_stream().cuda_stream)
+        stored = 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for head in range(n):
+            while stored < n and stored <= head + lookahead:
+                store.put(stored, int(sizes[stored]), stored - head)
+                stored += 1
+            store.get(head)
+            store.done(head)
+            store.advance(1)
+        wall = time.perf_counter() - t0
+        st = store.stats()
+        store.close()
+        ft.pool_destroy(pool)
     out = {"requests": n, "capacity_GiB": 1.0, "stored_GiB": round(float(sizes.sum()) / 2**30, 2),
            "moved_out": st.moved_out, "moved_in": st.moved_in, "stalled_consumers": st.stalls,
            "GiB_moved": round((st.bytes_out + st.bytes_in) / 2**30, 2), "ms_per_request": round(wall * 1e3 / n, 3),
            "moves_GBps": round((st.bytes_out + st.bytes_in) / wall / 1e9, 1)}
-    store.close()
-    ft.pool_destroy(pool)
     return out
 
 
