@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "ft_internal.h"
+#include "ft_guard.h"
 
 namespace ft {
 
@@ -543,7 +544,7 @@ using namespace ft;
 
 extern "C" {
 
-int ft_pool_create(ft_pool **out, void *dev_base, uint64_t bytes, uint64_t slab_bytes, int device) {
+int ft_pool_create(ft_pool **out, void *dev_base, uint64_t bytes, uint64_t slab_bytes, int device) try {
   if (out == nullptr) return FT_EINVAL;
   int rc = SlabPool::check_segment(dev_base, bytes, slab_bytes);
   if (rc != FT_OK) return rc;
@@ -553,12 +554,14 @@ int ft_pool_create(ft_pool **out, void *dev_base, uint64_t bytes, uint64_t slab_
   *out = p;
   return FT_OK;
 }
+FT_CATCH_ALL
 
-int ft_pool_grow(ft_pool *p, void *dev_base, uint64_t bytes) {
+int ft_pool_grow(ft_pool *p, void *dev_base, uint64_t bytes) try {
   if (p == nullptr) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);
   return p->slabs.add_segment(dev_base, bytes);
 }
+FT_CATCH_ALL
 
 int ft_pool_shrink(ft_pool *p, void **dev_base_out, uint64_t *bytes_out) {
   if (p == nullptr) return FT_EINVAL;
@@ -596,11 +599,12 @@ int ft_pool_destroy(ft_pool *p) {
   return rc;
 }
 
-int ft_slab_alloc(ft_pool *p, uint64_t nbytes, ft_off_t *off_out) {
+int ft_slab_alloc(ft_pool *p, uint64_t nbytes, ft_off_t *off_out) try {
   if (p == nullptr) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);
   return p->slabs.alloc(nbytes, off_out);
 }
+FT_CATCH_ALL
 
 int ft_slab_free(ft_pool *p, ft_off_t off) {
   if (p == nullptr) return FT_EINVAL;
@@ -638,7 +642,7 @@ int ft_set_tuning(ft_pool *p, int link_class, uint32_t workgroups, uint64_t tile
 
 int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
                         uint32_t nfunc, uint64_t chunk_bytes, uint32_t flags, void *hip_stream,
-                        ft_job_t *job_out) {
+                        ft_job_t *job_out) try {
   if (p == nullptr || job_out == nullptr) return FT_EINVAL;
   const auto t0 = std::chrono::steady_clock::now();
   std::lock_guard<std::mutex> lock(p->mu);
@@ -691,9 +695,10 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
   p->jobs[job->id] = std::move(job);
   return FT_OK;
 }
+FT_CATCH_ALL
 
 int ft_submit_merge(ft_pool *p, ft_job_t open_id, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
-                    uint32_t nfunc, uint32_t flags, void *hip_stream, ft_job_t *job_out) {
+                    uint32_t nfunc, uint32_t flags, void *hip_stream, ft_job_t *job_out) try {
   if (p == nullptr || job_out == nullptr) return FT_EINVAL;
   if (flags & ~(uint32_t)(FT_VALIDATE | FT_KEEP)) return FT_EINVAL;
   const auto t0 = std::chrono::steady_clock::now();
@@ -732,6 +737,7 @@ int ft_submit_merge(ft_pool *p, ft_job_t open_id, const ft_desc *descs, uint32_t
   p->jobs[job->id] = std::move(job);
   return FT_OK;
 }
+FT_CATCH_ALL
 
 int ft_set_stage_threads(ft_pool *p, uint32_t threads) {
   if (p == nullptr || threads == 0 || threads > 64) return FT_EINVAL;
@@ -825,7 +831,7 @@ int ft_job_stats(ft_pool *p, ft_job_t id, ft_job_stats_t *out) {
 }
 
 int ft_job_schedule(ft_pool *p, ft_job_t id, int link_class, uint32_t *func_out, uint32_t *chunk_out,
-                    uint64_t cap, uint64_t *n_out) {
+                    uint64_t cap, uint64_t *n_out) try {
   if (p == nullptr || n_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
   if (cap != 0 && (func_out == nullptr || chunk_out == nullptr)) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);
@@ -854,9 +860,10 @@ int ft_job_schedule(ft_pool *p, ft_job_t id, int link_class, uint32_t *func_out,
   }
   return FT_OK;
 }
+FT_CATCH_ALL
 
 int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, uint64_t *t_end_ns,
-               uint32_t *func_out, uint32_t *chunk_out, uint32_t *bytes_out, uint64_t cap, uint64_t *n_out) {
+               uint32_t *func_out, uint32_t *chunk_out, uint32_t *bytes_out, uint64_t cap, uint64_t *n_out) try {
   if (p == nullptr || n_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);
   auto it = p->jobs.find(id);
@@ -889,6 +896,7 @@ int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, ui
   }
   return FT_OK;
 }
+FT_CATCH_ALL
 
 int ft_job_log_workgroups(ft_pool *p, ft_job_t id, int link_class, uint32_t *ticket_wg, uint64_t cap,
                           uint64_t *wg_entry_ns, uint64_t *wg_exit_ns, uint32_t wg_cap, uint32_t *nwg_out) {
@@ -968,7 +976,7 @@ int ft_slo_weights(const double *data_size, const double *l_slo, const double *l
 
 int ft_plan_schedule(const uint64_t *stream_bytes, const uint32_t *weights, uint32_t nfunc,
                      uint64_t chunk_bytes, uint32_t *func_out, uint32_t *chunk_out, uint64_t cap,
-                     uint64_t *n_out) {
+                     uint64_t *n_out) try {
   if (stream_bytes == nullptr || weights == nullptr || n_out == nullptr || nfunc == 0) return FT_EINVAL;
   if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return FT_EINVAL;
   if (cap != 0 && (func_out == nullptr || chunk_out == nullptr)) return FT_EINVAL;
@@ -996,10 +1004,11 @@ int ft_plan_schedule(const uint64_t *stream_bytes, const uint32_t *weights, uint
   }
   return FT_OK;
 }
+FT_CATCH_ALL
 
 int ft_plan_tickets(const uint64_t *stream_bytes, const uint32_t *weights, uint32_t nfunc,
                     uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t *func_out, uint32_t *chunk_out,
-                    uint64_t *byte_off_out, uint32_t *bytes_out, uint64_t cap, uint64_t *n_out) {
+                    uint64_t *byte_off_out, uint32_t *bytes_out, uint64_t cap, uint64_t *n_out) try {
   if (stream_bytes == nullptr || weights == nullptr || n_out == nullptr || nfunc == 0) return FT_EINVAL;
   if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return FT_EINVAL;
   if (cap != 0 && (func_out == nullptr || chunk_out == nullptr || byte_off_out == nullptr || bytes_out == nullptr))
@@ -1040,6 +1049,7 @@ int ft_plan_tickets(const uint64_t *stream_bytes, const uint32_t *weights, uint3
   }
   return FT_OK;
 }
+FT_CATCH_ALL
 
 int ft_plain_copy(void *dst, const void *src, uint64_t bytes, uint32_t workgroups, void *hip_stream) {
   if (bytes == 0) return FT_OK;

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../include/faastube.h"
+#include "ft_guard.h"
 
 namespace {
 
@@ -102,7 +103,7 @@ struct ft_links {
 
 extern "C" {
 
-int ft_links_create(ft_links **out, uint32_t n, const uint32_t *topo, uint32_t max_hops) {
+int ft_links_create(ft_links **out, uint32_t n, const uint32_t *topo, uint32_t max_hops) try {
   if (out == nullptr || topo == nullptr || n < 2 || n > 16) return FT_EINVAL;
   if (max_hops == 0) max_hops = n - 1;
   if (n > 8 && max_hops > 4) return FT_EINVAL;  // keeps the number of candidate paths small
@@ -116,6 +117,7 @@ int ft_links_create(ft_links **out, uint32_t n, const uint32_t *topo, uint32_t m
   *out = l;
   return FT_OK;
 }
+FT_CATCH_ALL
 
 int ft_links_destroy(ft_links *l) {
   if (l == nullptr) return FT_EINVAL;
@@ -139,7 +141,7 @@ int ft_links_free(ft_links *l, uint32_t *free_out) {
 }
 
 int ft_links_paths(ft_links *l, uint32_t func, uint32_t *nodes_out, uint32_t cap_nodes, uint32_t *len_out,
-                   uint32_t *bw_out, uint32_t cap_paths, uint32_t *npaths_out) {
+                   uint32_t *bw_out, uint32_t cap_paths, uint32_t *npaths_out) try {
   if (l == nullptr || npaths_out == nullptr) return FT_EINVAL;
   auto it = l->paths.find(func);
   if (it == l->paths.end()) return FT_EINVAL;
@@ -155,8 +157,9 @@ int ft_links_paths(ft_links *l, uint32_t func, uint32_t *nodes_out, uint32_t cap
   }
   return FT_OK;
 }
+FT_CATCH_ALL
 
-int ft_links_select(ft_links *l, uint32_t func, uint32_t src, uint32_t dst) {
+int ft_links_select(ft_links *l, uint32_t func, uint32_t src, uint32_t dst) try {
   if (l == nullptr || src >= l->n || dst >= l->n || src == dst) return FT_EINVAL;
   if (l->paths.count(func)) return FT_EINVAL;
   std::vector<Held> &mine = l->paths[func];
@@ -213,8 +216,9 @@ int ft_links_select(ft_links *l, uint32_t func, uint32_t src, uint32_t dst) {
   }
   return FT_OK;
 }
+FT_CATCH_ALL
 
-int ft_stripe_chunks(const uint32_t *path_bw, uint32_t npaths, uint64_t nchunks, uint32_t *path_of_chunk) {
+int ft_stripe_chunks(const uint32_t *path_bw, uint32_t npaths, uint64_t nchunks, uint32_t *path_of_chunk) try {
   if (path_bw == nullptr || npaths == 0 || (nchunks != 0 && path_of_chunk == nullptr)) return FT_EINVAL;
   for (uint32_t p = 0; p < npaths; ++p)
     if (path_bw[p] == 0) return FT_EINVAL;
@@ -232,5 +236,6 @@ int ft_stripe_chunks(const uint32_t *path_bw, uint32_t npaths, uint64_t nchunks,
   }
   return FT_OK;
 }
+FT_CATCH_ALL
 
 }  // extern "C"

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "../../include/faastube.h"
+#include "ft_guard.h"
 
 namespace {
 
@@ -42,7 +43,7 @@ struct ft_sizer {
 
 extern "C" {
 
-int ft_sizer_create(ft_sizer **out, uint64_t min_bytes, double quantile, double default_window) {
+int ft_sizer_create(ft_sizer **out, uint64_t min_bytes, double quantile, double default_window) try {
   if (out == nullptr || quantile < 0.0 || quantile > 1.0 || !(default_window >= 0.0)) return FT_EINVAL;
   ft_sizer *s = new ft_sizer();
   s->min_bytes = min_bytes;
@@ -51,6 +52,7 @@ int ft_sizer_create(ft_sizer **out, uint64_t min_bytes, double quantile, double 
   *out = s;
   return FT_OK;
 }
+FT_CATCH_ALL
 
 int ft_sizer_destroy(ft_sizer *s) {
   if (s == nullptr) return FT_EINVAL;
@@ -58,7 +60,7 @@ int ft_sizer_destroy(ft_sizer *s) {
   return FT_OK;
 }
 
-int ft_sizer_observe(ft_sizer *s, uint32_t func, double t, uint64_t data_size, uint32_t concurrency) {
+int ft_sizer_observe(ft_sizer *s, uint32_t func, double t, uint64_t data_size, uint32_t concurrency) try {
   if (s == nullptr) return FT_EINVAL;
   FuncHist &h = s->funcs[func];
   if (h.seen) h.intervals.push_back(t - h.last);
@@ -73,6 +75,7 @@ int ft_sizer_observe(ft_sizer *s, uint32_t func, double t, uint64_t data_size, u
   h.expires = t + r_window;
   return FT_OK;
 }
+FT_CATCH_ALL
 
 int ft_sizer_target(ft_sizer *s, double t, uint64_t *bytes_out) {
   if (s == nullptr || bytes_out == nullptr) return FT_EINVAL;
@@ -84,7 +87,7 @@ int ft_sizer_target(ft_sizer *s, double t, uint64_t *bytes_out) {
 }
 
 int ft_migrate_plan(const ft_object *objs, uint32_t n, uint64_t capacity, uint64_t incoming, uint32_t policy,
-                    uint64_t *evict_ids, uint32_t *n_evict, uint64_t *reload_ids, uint32_t *n_reload) {
+                    uint64_t *evict_ids, uint32_t *n_evict, uint64_t *reload_ids, uint32_t *n_reload) try {
   if ((n != 0 && objs == nullptr) || n_evict == nullptr || n_reload == nullptr) return FT_EINVAL;
   if (policy != FT_EVICT_QUEUE_AWARE && policy != FT_EVICT_LRU) return FT_EINVAL;
   if (n != 0 && (evict_ids == nullptr || reload_ids == nullptr)) return FT_EINVAL;
@@ -127,5 +130,6 @@ int ft_migrate_plan(const ft_object *objs, uint32_t n, uint64_t capacity, uint64
   *n_reload = nr;
   return FT_OK;
 }
+FT_CATCH_ALL
 
 }  // extern "C"

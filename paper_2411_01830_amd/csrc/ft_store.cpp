@@ -14,6 +14,7 @@
 
 #include "../../include/faastube.h"
 #include "ft_pool.h"
+#include "ft_guard.h"
 
 namespace {
 
@@ -132,7 +133,7 @@ int make_room(ft_store *s, uint64_t incoming, const uint64_t *skip, bool reload)
 extern "C" {
 
 int ft_store_create(ft_store **out, ft_pool *pool, void *spill_base, uint64_t spill_bytes, uint64_t capacity,
-                    uint64_t chunk_bytes, void *hip_stream) {
+                    uint64_t chunk_bytes, void *hip_stream) try {
   if (out == nullptr || pool == nullptr || capacity == 0) return FT_EINVAL;
   if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return FT_EINVAL;
   int rc = ft::SlabPool::check_segment(spill_base, spill_bytes, 4096);
@@ -144,8 +145,9 @@ int ft_store_create(ft_store **out, ft_pool *pool, void *spill_base, uint64_t sp
   *out = s;
   return FT_OK;
 }
+FT_CATCH_ALL
 
-int ft_store_put(ft_store *s, uint64_t id, uint64_t nbytes, uint64_t queue_pos, ft_off_t *off_out) {
+int ft_store_put(ft_store *s, uint64_t id, uint64_t nbytes, uint64_t queue_pos, ft_off_t *off_out) try {
   if (s == nullptr || off_out == nullptr || nbytes == 0) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(s->mu);
   if (s->objs.count(id)) return FT_EINVAL;
@@ -166,8 +168,9 @@ int ft_store_put(ft_store *s, uint64_t id, uint64_t nbytes, uint64_t queue_pos, 
   *off_out = off;
   return FT_OK;
 }
+FT_CATCH_ALL
 
-int ft_store_get(ft_store *s, uint64_t id, ft_off_t *off_out, uint32_t *was_out) {
+int ft_store_get(ft_store *s, uint64_t id, ft_off_t *off_out, uint32_t *was_out) try {
   if (s == nullptr || off_out == nullptr) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(s->mu);
   auto it = s->objs.find(id);
@@ -183,8 +186,9 @@ int ft_store_get(ft_store *s, uint64_t id, ft_off_t *off_out, uint32_t *was_out)
   *off_out = it->second.off;
   return FT_OK;
 }
+FT_CATCH_ALL
 
-int ft_store_done(ft_store *s, uint64_t id) {
+int ft_store_done(ft_store *s, uint64_t id) try {
   if (s == nullptr) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(s->mu);
   auto it = s->objs.find(id);
@@ -196,6 +200,7 @@ int ft_store_done(ft_store *s, uint64_t id) {
   s->objs.erase(it);
   return make_room(s, 0, nullptr, true);
 }
+FT_CATCH_ALL
 
 int ft_store_advance(ft_store *s, uint64_t steps) {
   if (s == nullptr) return FT_EINVAL;
