@@ -196,7 +196,7 @@ def plain_copy_ceiling():
 
 
 def share_error(rp, cls):
-    """Timed per-function shares from the device log of one step (contended link):
+    """Timed per-function shares of one link class from the device log of one step:
     over [0, T1], T1 = first time any function's last byte lands."""
     ft = rp.ft
     got = {}
@@ -206,7 +206,11 @@ def share_error(rp, cls):
         got["weights"] = rp.rec.weights[name]
 
     rp.step(ft.FT_LOG, collect)
-    log, w = got["log"], np.asarray(got["weights"], dtype=np.float64)
+    return shares_from_log(got["log"], got["weights"])
+
+
+def shares_from_log(log, weights):
+    w = np.asarray(weights, dtype=np.float64)
     F = len(w)
     t_end = log["t_end_ns"].astype(np.int64)
     t0 = int(log["t_begin_ns"].min())
@@ -229,6 +233,35 @@ def share_error(rp, cls):
             "max_rel_err": err_at(t0 - 1, T1),
             "max_rel_err_tenths": [None if x is None else round(x, 4) for x in windows],
             "weights": [int(x) for x in w]}
+
+
+def share_error_pool_to_pool():
+    """The same measure for the on-device class: eight functions with the feature workload's weights
+    (1:1:2:2:4:4:8:8), each moving 1 GiB between slabs in 2 MiB chunks, so that the window in which all
+    eight are active holds some two thousand chunks (in the feature workload itself it is 29 us long and
+    a weight-1 function moves one or two chunks in it)."""
+    import torch
+    from paper_2411_01830_amd import binding as ft
+    from workloads import make_descs, FT_POOL
+    nf, per = 8, 1 << 30
+    w = [1, 1, 2, 2, 4, 4, 8, 8]
+    buf = torch.empty(2 * nf * per, dtype=torch.uint8, device="cuda:0")
+    pool = ft.pool_create(buf.data_ptr(), buf.numel(), 1 << 20, 0)
+    src = [ft.slab_alloc(pool, per) for _ in range(nf)]
+    dst = [ft.slab_alloc(pool, per) for _ in range(nf)]
+    d = make_descs([dict(func=f, src_space=FT_POOL, dst_space=FT_POOL, src=src[f], dst=dst[f], row_bytes=per)
+                    for f in range(nf)])
+    stream = torch.cuda.current_stream().cuda_stream
+    ft.wait(pool, ft.submit_transfers(pool, d, w, 2 << 20, 0, stream))      # touch everything once
+    job = ft.submit_transfers(pool, d, w, 2 << 20, ft.FT_LOG | ft.FT_TIMING, stream)
+    ft.wait(pool, job)
+    out = shares_from_log(ft.job_log(pool, job, 2), w)
+    gbps = nf * per / ft.job_stats(pool, job).cls[2].device_ms / 1e6
+    out["payload_GBps"] = round(gbps, 1)
+    out["hbm_frac"] = round(2 * gbps / HBM_PEAK_GBS, 4)      # with the per-ticket log being written
+    ft.job_release(pool, job)
+    ft.pool_destroy(pool)
+    return out
 
 
 def batched_triggering(peaks):
@@ -688,7 +721,8 @@ def main():
     rp.close()
     if not args.no_extras:
         # the blocks that widen the path; one that fails must not take the headline figures with it
-        for key, block in (("batched_triggering", lambda: batched_triggering(peaks)),
+        for key, block in (("share_error_pool_to_pool", share_error_pool_to_pool),
+                           ("batched_triggering", lambda: batched_triggering(peaks)),
                            ("pinned_ring", lambda: pinned_ring(peaks)),
                            ("single_transfers", single_transfers),
                            ("elastic_store", elastic_store),
