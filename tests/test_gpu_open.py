@@ -588,3 +588,87 @@ def test_two_pools_driven_from_two_threads(gpu):
     finally:
         for _, eng, _ in pairs:
             eng.close()
+
+
+def _random_open_sequences(gpu, seeds):
+    from workloads import FT_PAGEABLE
+    binding, _ = gpu
+    for seed in seeds:
+        orc, eng, rng = _engines(gpu, 64 * MiB, 256 * MiB, seed=seed)
+        pyr = __import__("random").Random(seed)
+        try:
+            page = rng.integers(0, 256, 24 * MiB, dtype=np.uint8)
+            for e in (orc, eng):
+                e.pageable_arena(48 * MiB)
+                e.write_pageable(0, page)
+            hdst = [40 * MiB]          # pinned destinations
+            pdst = [24 * MiB]          # pageable destinations
+
+            def job(nfunc):
+                recs = []
+                for _ in range(pyr.choice([1, 2, 3, 5])):
+                    kind = pyr.choice(["h2p", "h2p", "pg2p", "p2h", "p2pg", "p2p"])
+                    rows = pyr.choice([1, 1, 1, 7, 300])
+                    rb = pyr.choice([33, 4096, 250001, 1 * MiB + 3, 3 * MiB]) if rows == 1 else pyr.choice([48, 200, 1000])
+                    sp, dp = rb + pyr.choice([0, 8, 100]), rb + pyr.choice([0, 0, 24])
+                    es, ed = (rows - 1) * sp + rb, (rows - 1) * dp + rb
+                    if kind in ("h2p", "pg2p"):
+                        src = pyr.randrange(0, 20 * MiB - es)
+                        sspace = FT_HOST if kind == "h2p" else FT_PAGEABLE
+                    else:
+                        a = orc.slab_alloc(es + 32)
+                        assert eng.slab_alloc(es + 32) == a
+                        fill = rng.integers(0, 256, es + 32, dtype=np.uint8)
+                        orc.write_pool(a, fill)
+                        eng.write_pool(a, fill)
+                        src, sspace = a + pyr.randrange(16), FT_POOL
+                    if kind == "p2h":
+                        dst, dspace = hdst[0] + pyr.randrange(16), FT_HOST
+                        hdst[0] += (ed + 47) // 16 * 16
+                    elif kind == "p2pg":
+                        dst, dspace = pdst[0] + pyr.randrange(16), FT_PAGEABLE
+                        pdst[0] += (ed + 47) // 16 * 16
+                    else:
+                        b = orc.slab_alloc(ed + 32)
+                        assert eng.slab_alloc(ed + 32) == b
+                        dst, dspace = b + pyr.randrange(16), FT_POOL
+                    assert hdst[0] < 62 * MiB and pdst[0] < 46 * MiB
+                    recs.append(dict(func=pyr.randrange(nfunc), src_space=sspace, dst_space=dspace, src=src, dst=dst,
+                                     row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp))
+                return make_descs(recs)
+            for rnd in range(4):
+                C = pyr.choice([64 * KiB, 256 * KiB])
+                binding.set_batch(eng.pool, pyr.choice([1, 2, 5]), pyr.choice([1, 2, 3]))
+                binding.set_stage_threads(eng.pool, pyr.choice([1, 2, 4]))
+                nf0 = pyr.choice([1, 2, 4])
+                w0 = [pyr.choice([1, 2, 5]) for _ in range(nf0)]
+                d0 = job(nf0)
+                later = []
+                for _ in range(pyr.choice([0, 1, 3])):
+                    nf = pyr.choice([1, 2])
+                    later.append((job(nf), [pyr.choice([1, 3, 9]) for _ in range(nf)]))
+                orc.wait(orc.submit(d0, w0, C))
+                for d, w in later:
+                    orc.wait(orc.submit(d, w, C))
+                handles = [eng.submit(d0, w0, C, fmt.FT_OPEN | (fmt.FT_VALIDATE if rnd % 2 else 0))]
+                for d, w in later:
+                    try:
+                        handles.append(eng.merge(handles[0], d, w))
+                    except binding.FtError as e:
+                        assert e.code == fmt.FT_ECLOSED, e.code
+                        handles.append(eng.submit(d, w, C, fmt.FT_OPEN))
+                pyr.shuffle(handles)
+                for h in handles:
+                    eng.wait(h)
+                _images_equal(orc, eng)
+                assert np.array_equal(eng.pageable_np, orc.pageable_mem), (seed, rnd)
+            print(f"random open sequences seed={seed} done", flush=True)
+        finally:
+            eng.close()
+
+
+def test_random_open_jobs_with_merges_and_both_rings(gpu):
+    """Random open jobs (pinned and pageable host sides in both directions, pool->pool, pitched pieces, any
+    alignment), random batch size, depth and staging threads, up to three later jobs merged while each runs
+    (or started on their own when the open one has already closed), waited for in random order."""
+    _random_open_sequences(gpu, (301, 302, 303))
