@@ -21,6 +21,14 @@ simply continued, five chunks at a time. When the link runs dry while jobs are
 still to come, the earliest of them (smallest `arrive`, then job index) starts
 a new sequence at once; the others keep waiting for their batch count.
 
+Rate control (Sec. 6.1) changes shares while functions run: when a function arrives or
+leaves, the bandwidth left over moves to whichever SLO is then the tightest. A job may
+therefore carry `reweight`, a list of (batches triggered when the change was made, new
+weights of its functions): from the first batch not yet triggered at that moment the
+order is built afresh over everything not yet triggered, exactly as for an arrival, with
+the new weights in force. A change made before the job has arrived takes effect with its
+arrival; a change made once the link is dry changes nothing.
+
 TEST INFRASTRUCTURE ONLY (see the package docstring).
 """
 from .schedule import stride_order
@@ -36,6 +44,8 @@ def batched_order(jobs, batch_chunks=5):
     if any(a > b for a, b in zip(arrive, arrive[1:])):
         raise ValueError("jobs are listed in the order they arrive")
     waiting = list(range(1, len(jobs)))
+    weights = [list(job["w"]) for job in jobs]            # the weights in force
+    changes = sorted((at, j, list(w)) for j, job in enumerate(jobs) for at, w in job.get("reweight", []))
     funcs = [(0, f) for f in range(len(jobs[0]["n"]))]   # (job, function) in tie order
     served = {(0, f): 0 for f in range(len(jobs[0]["n"]))}
     batches = []
@@ -52,11 +62,18 @@ def batched_order(jobs, batch_chunks=5):
             for f in range(len(jobs[j]["n"])):
                 funcs.append((j, f))
                 served[(j, f)] = 0
-        if order is None or newly:
+        changed = False
+        while changes and changes[0][0] <= len(batches):
+            _, j, w = changes.pop(0)
+            if len(w) != len(jobs[j]["n"]) or min(w) < 1:
+                raise ValueError("reweight")
+            weights[j] = w
+            changed = True
+        if order is None or newly or (changed and not dry):
             live = [jf for jf in funcs if served[jf] < jobs[jf[0]]["n"][jf[1]]]
             base = {jf: served[jf] for jf in live}
             n = [jobs[j]["n"][f] - served[(j, f)] for j, f in live]
-            w = [jobs[j]["w"][f] for j, f in live]
+            w = [weights[j][f] for j, f in live]
             order = [(live[i], k) for i, k in stride_order(n, w)]
             pos = 0
         if pos >= len(order):

@@ -204,3 +204,96 @@ def test_newcomer_with_high_weight_is_served_within_one_batch_of_arrival():
     batches = batched_order(jobs, 5)
     where = [i for i, b in enumerate(batches) for c in b if c[0] == 1]
     assert where == [10, 10, 10, 10]
+
+
+def _reference_batches_reweighted(jobs, B):
+    """The second formulation above with weight changes: the explicit list of remaining chunks is
+    re-sorted with the weights then in force whenever jobs join or a change falls due."""
+    waiting = list(range(1, len(jobs)))
+    present = [0]
+    w = [list(j["w"]) for j in jobs]
+    changes = sorted((at, j, list(x)) for j, job in enumerate(jobs) for at, x in job.get("reweight", []))
+    done = {}
+    todo = None
+    out = []
+    while True:
+        newly = [j for j in waiting if jobs[j]["arrive"] <= len(out)]
+        if todo is not None and not todo and not newly and waiting:
+            newly = [waiting[0]]
+        changed = False
+        while changes and changes[0][0] <= len(out):
+            _, j, x = changes.pop(0)
+            w[j] = x
+            changed = True
+        if todo is None or newly or (changed and todo):
+            for j in newly:
+                waiting.remove(j)
+                present.append(j)
+            keys = []
+            for j in present:
+                for f, n in enumerate(jobs[j]["n"]):
+                    have = done.get((j, f), 0)
+                    for i in range(n - have):
+                        keys.append((Fraction(i + 1, w[j][f]), j, f, have + i))
+            keys.sort()
+            todo = [(j, f, k) for _, j, f, k in keys]
+        if not todo:
+            if not waiting:
+                return out
+            continue
+        batch, todo = todo[:B], todo[B:]
+        for j, f, _ in batch:
+            done[(j, f)] = done.get((j, f), 0) + 1
+        out.append(batch)
+
+
+def test_reweighting_hand_case_and_second_formulation():
+    # two functions 1:1, ten chunks each, batches of 4; after two batches function 1 gets weight 3:
+    # the first two batches alternate, then of every four chunks three are function 1's until it runs out
+    jobs = [{"n": [10, 10], "w": [1, 1], "reweight": [(2, [1, 3])]}]
+    got = batched_order(jobs, 4)
+    assert got[:2] == [[(0, 0, 0), (0, 1, 0), (0, 0, 1), (0, 1, 1)], [(0, 0, 2), (0, 1, 2), (0, 0, 3), (0, 1, 3)]]
+    # tags from the rebuild: f1 at 1/3, 2/3, 1, f0 at 1 (ties to the lower function), ...
+    assert got[2] == [(0, 1, 4), (0, 1, 5), (0, 0, 4), (0, 1, 6)]
+    assert got[3] == [(0, 1, 7), (0, 1, 8), (0, 0, 5), (0, 1, 9)]
+    assert _flat(got[4:]) == [(0, 0, k) for k in range(6, 10)]
+    # a change that restores the old weights still restarts the tags (it is a rebuild like any other)
+    same = batched_order([{"n": [10, 10], "w": [1, 2], "reweight": [(1, [1, 2])]}], 3)
+    assert sorted(_flat(same)) == sorted(_flat(batched_order([{"n": [10, 10], "w": [1, 2]}], 3)))
+    rng = random.Random(13)
+    for case in range(300):
+        B = rng.randint(1, 6)
+        njobs = rng.randint(1, 3)
+        arrive = sorted(rng.randint(0, 8) for _ in range(njobs - 1))
+        jobs = []
+        for j in range(njobs):
+            F = rng.randint(1, 3)
+            job = {"n": [rng.randint(0, 9) for _ in range(F)], "w": [rng.choice([1, 2, 3, 5]) for _ in range(F)]}
+            if j:
+                job["arrive"] = arrive[j - 1]
+            if rng.random() < 0.7:
+                job["reweight"] = sorted((rng.randint(0, 10), [rng.choice([1, 2, 4, 7]) for _ in range(F)])
+                                         for _ in range(rng.randint(1, 2)))
+            jobs.append(job)
+        got = batched_order(jobs, B)
+        want = sorted((j, f, k) for j, job in enumerate(jobs) for f, n in enumerate(job["n"]) for k in range(n))
+        assert sorted(_flat(got)) == want, case
+        assert got == _reference_batches_reweighted(jobs, B), case
+
+
+def test_rate_rule_drives_the_reweighting():
+    """Sec. 6.1 end to end on paper: two functions share the link by their least rates plus the idle
+    part for the tighter one; when a third, tighter function arrives the idle part moves to it, so the
+    second function's weight drops back to its least rate - the order after the arrival follows the new
+    weights of all three."""
+    size, slo, infer, bw = [64e6, 64e6], [0.050, 0.020], [0.010, 0.010], 12.8e9
+    w2 = slo_weights(size, slo, infer, bw)
+    assert w2[1] > w2[0]
+    size3, slo3, infer3 = size + [8e6], slo + [0.012], infer + [0.010]
+    w3 = slo_weights(size3, slo3, infer3, bw)
+    assert w3 == [8, 32, 24] and w2 == [8, 56]       # 1.6, 6.4, 4 GB/s least; 0.8 (then 4.8) GB/s idle moves on
+    jobs = [{"n": [40, 40], "w": w2, "reweight": [(3, w3[:2])]}, {"n": [4], "w": [w3[2]], "arrive": 3}]
+    got = batched_order(jobs, 5)
+    assert got == _reference_batches_reweighted(jobs, 5)
+    first_after = [c for b in got[3:5] for c in b]
+    assert sum(1 for c in first_after if c[0] == 1) == 4     # the newcomer is through within two batches
