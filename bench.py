@@ -316,6 +316,30 @@ def batched_triggering(peaks):
         out["cases"][name] = {"urgent_latency_ms": round(lat[1], 3), "background_ms": round(tot[1], 2),
                               "background_GBps": round(rp.payload / tot[1] / 1e6, 2),
                               "urgent_within_budget": bool(lat[1] <= 2.0)}
+    # rate control on the running sequence: all 16 equal, 10 ms in function 0 gets 8 of 23 parts
+    pool = ft.pool_create(rp.segs[0].data_ptr(), rp.segs[0].numel(), rp.plan.slab_bytes, 0)
+    ft.host_window_add(pool, rp.host.data_ptr(), rp.host.numel())
+    for a in allocs:
+        ft.slab_alloc(pool, a[1])
+    ft.set_batch(pool, 5, 3)
+    torch.cuda.synchronize()
+    job = ft.submit_transfers(pool, descs, [1] * nbg, chunk, ft.FT_OPEN | ft.FT_KEEP, rp.stream)
+    time.sleep(0.010)
+    t0 = time.perf_counter()
+    at = ft.job_reweight(pool, job, [8] + [1] * (nbg - 1), rp.stream)[0]
+    call_us = (time.perf_counter() - t0) * 1e6
+    ft.wait(pool, job)
+    batches = ft.job_batches(pool, job, 0)
+    if at is not None:
+        before = [f for b in batches[:at] for _, f, _ in b]
+        last0 = max(i for i, b in enumerate(batches) if any(f == 0 for _, f, _ in b))
+        after = [f for b in batches[at:last0] for _, f, _ in b]
+        out["reweight"] = {"call_us": round(call_us, 1), "from_batch": at, "batches": len(batches),
+                           "share_before": round(before.count(0) / max(len(before), 1), 4), "want_before": round(1 / nbg, 4),
+                           "share_after": round(after.count(0) / max(len(after), 1), 4),
+                           "want_after": round(8 / (8 + nbg - 1), 4), "function0_done_at_batch": last0}
+    ft.job_release(pool, job)
+    ft.pool_destroy(pool)
     rp.close()
     return out
 

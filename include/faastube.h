@@ -268,6 +268,23 @@ int ft_submit_merge(ft_pool *p, ft_job_t open_job, const ft_desc *descs, uint32_
 int ft_set_batch(ft_pool *p, uint32_t batch_chunks, uint32_t depth);
 
 /*
+ * Rate control while transfers run (Sec. 6.1: when functions arrive or leave, the idle
+ * bandwidth moves to whichever SLO is then the tightest, so the shares of functions
+ * already in flight change). Gives the functions of `job` - an open job or one merged
+ * into it - new weights, weights[f] >= 1 for each of the nfunc functions the job was
+ * submitted with. Batches already triggered are not touched; from the first batch not
+ * yet triggered the order is rebuilt over every chunk of the sequence that is left, as
+ * for an arrival, with the new weights in force. All or nothing across link classes.
+ * batch_out (host, FT_NCLASS entries, may be NULL) receives per link class the number
+ * of that first batch, UINT64_MAX where no chunk of the job is left to trigger (the
+ * call changes nothing there). The small table upload goes on hip_stream. Thread-safe
+ * like ft_submit_merge. FT_EINVAL: unknown job, not part of an open sequence, nfunc
+ * differs from the job's, a zero weight.
+ */
+int ft_job_reweight(ft_pool *p, ft_job_t job, const uint32_t *weights, uint32_t nfunc, void *hip_stream,
+                    uint64_t *batch_out);
+
+/*
  * Number of batches of `link_class` that the open job had triggered when `job` joined
  * it (0 for the open job itself): the first batch that may hold the job's chunks.
  */

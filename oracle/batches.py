@@ -27,7 +27,8 @@ therefore carry `reweight`, a list of (batches triggered when the change was mad
 weights of its functions): from the first batch not yet triggered at that moment the
 order is built afresh over everything not yet triggered, exactly as for an arrival, with
 the new weights in force. A change made before the job has arrived takes effect with its
-arrival; a change made once the link is dry changes nothing.
+arrival; a change made once the link is dry changes nothing; of two changes to one job
+made at the same count of batches the later one holds.
 
 TEST INFRASTRUCTURE ONLY (see the package docstring).
 """
@@ -45,7 +46,9 @@ def batched_order(jobs, batch_chunks=5):
         raise ValueError("jobs are listed in the order they arrive")
     waiting = list(range(1, len(jobs)))
     weights = [list(job["w"]) for job in jobs]            # the weights in force
-    changes = sorted((at, j, list(w)) for j, job in enumerate(jobs) for at, w in job.get("reweight", []))
+    # in time order; of two changes to one job made at the same count the later in its list holds
+    changes = sorted(((at, j, list(w)) for j, job in enumerate(jobs) for at, w in job.get("reweight", [])),
+                     key=lambda change: change[0])
     funcs = [(0, f) for f in range(len(jobs[0]["n"]))]   # (job, function) in tie order
     served = {(0, f): 0 for f in range(len(jobs[0]["n"]))}
     batches = []

@@ -656,6 +656,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
   job->flags = flags;
   job->keep = (flags & (FT_KEEP | FT_LOG | FT_TIMING)) != 0;
   job->chunk_bytes = chunk_bytes;
+  job->nfunc = nfunc;
   job->id = p->next_job;
   bool any = false;
   for (int c = 0; c < FT_NCLASS; ++c) {
@@ -713,6 +714,7 @@ int ft_submit_merge(ft_pool *p, ft_job_t open_id, const ft_desc *descs, uint32_t
   job->flags = flags | FT_DETACHED;
   job->keep = (flags & FT_KEEP) != 0;
   job->chunk_bytes = open_job->chunk_bytes;
+  job->nfunc = nfunc;
   job->id = p->next_job;
   bool any = false;
   for (int c = 0; c < FT_NCLASS; ++c) {
@@ -735,6 +737,24 @@ int ft_submit_merge(ft_pool *p, ft_job_t open_id, const ft_desc *descs, uint32_t
   job->host_submit_us =
       std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
   p->jobs[job->id] = std::move(job);
+  return FT_OK;
+}
+FT_CATCH_ALL
+
+int ft_job_reweight(ft_pool *p, ft_job_t id, const uint32_t *weights, uint32_t nfunc, void *hip_stream,
+                    uint64_t *batch_out) try {
+  if (p == nullptr || weights == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->open || it->second->nfunc != nfunc) return FT_EINVAL;
+  for (uint32_t f = 0; f < nfunc; ++f)
+    if (weights[f] == 0) return FT_EINVAL;
+  uint64_t batches[FT_NCLASS];
+  DeviceGuard guard(p->device);
+  int rc = open_reweight(p, it->second.get(), weights, static_cast<hipStream_t>(hip_stream), batches);
+  if (rc != FT_OK) return rc;
+  if (batch_out != nullptr)
+    for (int c = 0; c < FT_NCLASS; ++c) batch_out[c] = batches[c];
   return FT_OK;
 }
 FT_CATCH_ALL

@@ -57,6 +57,7 @@ struct Job {
   std::unique_ptr<InlineBlob> inline_tables;  // a small job's tables, passed with the launch instead
   std::vector<uint64_t> allocs;
   uint64_t chunk_bytes = 0;
+  uint32_t nfunc = 0;    // functions the job was submitted with
   double host_submit_us = 0;
   std::shared_ptr<OpenState> open;  // set for a job submitted with FT_OPEN or merged into one
   uint64_t class_payload[FT_NCLASS] = {0, 0, 0};
@@ -171,6 +172,10 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
                 hipStream_t user);
 int open_merge(ft_pool *p, Job *open_job, Job *job, SubmitPlan &plan, const uint32_t *weights,
                hipStream_t user);
+// New weights (one per function of the job) from the first batch of every class not yet
+// triggered; batch_out[FT_NCLASS] receives that batch's number, UINT64_MAX for a class in
+// which nothing of the job is left to trigger.
+int open_reweight(ft_pool *p, Job *job, const uint32_t *weights, hipStream_t user, uint64_t *batch_out);
 int open_wait(ft_pool *p, const std::shared_ptr<OpenState> &st, uint64_t job_id);
 void open_stats(const std::shared_ptr<OpenState> &st, int c, uint64_t *tickets, uint64_t *tile_bytes,
                 uint32_t *workgroups, float *kernel_ms, uint64_t *batches);

@@ -653,6 +653,62 @@ int open_merge(ft_pool *p, Job *open_job, Job *job, SubmitPlan &plan, const uint
   return FT_OK;
 }
 
+int open_reweight(ft_pool *p, Job *job, const uint32_t *weights, hipStream_t user, uint64_t *batch_out) {
+  std::shared_ptr<OpenState> st = job->open;
+  if (!st) return FT_EINVAL;
+  std::unique_lock<std::mutex> lock(st->mu);
+  if (st->error != FT_OK) {
+    p->hip_error = st->error_text;
+    return st->error;
+  }
+  // As for a merge: the new order of every class is built first and put in force only when
+  // all of them exist; a failure half way restores the old weights.
+  struct Pending {
+    int c;
+    std::vector<std::pair<uint32_t, uint32_t>> old_weights;  // index into fns, weight before
+    std::shared_ptr<Generation> gen;
+  };
+  std::vector<Pending> pending;
+  auto roll_back = [&](int rc) {
+    bool drained = false;
+    for (Pending &pd : pending) {
+      for (auto &ow : pd.old_weights) st->cls[pd.c].fns[ow.first].weight = ow.second;
+      if (pd.gen) {
+        if (!drained) (void)hipStreamSynchronize(user);  // its upload may still be queued
+        drained = true;
+        drop_generation(p, pd.gen.get());
+      }
+    }
+    return rc;
+  };
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    batch_out[c] = UINT64_MAX;
+    OpenClass &oc = st->cls[c];
+    if (!oc.used || oc.closed || oc.gen->next_rank >= oc.gen->plan.nchunks) continue;  // nothing left to reorder
+    Pending pd{c, {}, nullptr};
+    bool differs = false;
+    for (uint32_t i = 0; i < oc.fns.size(); ++i) {
+      OpenFn &fn = oc.fns[i];
+      if (fn.job != job->id || fn.next_chunk >= fn.nchunks) continue;
+      pd.old_weights.push_back({i, fn.weight});
+      differs = true;
+    }
+    if (!differs) continue;  // every chunk of the job in this class has been triggered
+    pending.push_back(std::move(pd));
+    for (auto &ow : pending.back().old_weights) oc.fns[ow.first].weight = weights[oc.fns[ow.first].func];
+    int rc = build_generation(p, st.get(), c, user, &pending.back().gen);
+    if (rc != FT_OK) return roll_back(rc);
+  }
+  for (Pending &pd : pending) {
+    OpenClass &oc = st->cls[pd.c];
+    std::shared_ptr<Generation> old = oc.gen;
+    oc.gen = pd.gen;
+    if (old->inflight == 0) drop_generation(p, old.get());
+    batch_out[pd.c] = oc.batches_triggered;
+  }
+  return FT_OK;
+}
+
 int open_wait(ft_pool *p, const std::shared_ptr<OpenState> &st, uint64_t job_id) {
   std::unique_lock<std::mutex> lock(st->mu);
   st->cv.wait(lock, [&] {

@@ -657,6 +657,14 @@ def _random_open_sequences(gpu, seeds):
                     except binding.FtError as e:
                         assert e.code == fmt.FT_ECLOSED, e.code
                         handles.append(eng.submit(d, w, C, fmt.FT_OPEN))
+                # weights changed at random moments: whatever order results, the bytes are the plain copy
+                nfuncs = [nf0] + [len(w) for _, w in later]
+                for _ in range(pyr.choice([0, 1, 3])):
+                    i = pyr.randrange(len(handles))
+                    try:
+                        binding.job_reweight(eng.pool, handles[i], [pyr.choice([1, 2, 11]) for _ in range(nfuncs[i])])
+                    except binding.FtError as e:      # a later job that ran on its own as a closed job
+                        assert e.code == fmt.FT_EINVAL, e.code
                 pyr.shuffle(handles)
                 for h in handles:
                     eng.wait(h)
@@ -672,3 +680,120 @@ def test_random_open_jobs_with_merges_and_both_rings(gpu):
     alignment), random batch size, depth and staging threads, up to three later jobs merged while each runs
     (or started on their own when the open one has already closed), waited for in random order."""
     _random_open_sequences(gpu, (301, 302, 303))
+
+
+@pytest.mark.parametrize("batch,depth", [(5, 2), (2, 1)])
+def test_weights_changed_while_the_sequence_runs(gpu, batch, depth):
+    """Sec. 6.1's rate control on a running sequence: a long host->pool job, a second one merged, then the
+    weights of both changed (the first one twice). The library says from which batch each change holds;
+    with those counts the batches must be the oracle's, and the bytes the plain copy whatever the order."""
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 192 * MiB, 256 * MiB, seed=40 + batch)
+    try:
+        C = 256 * KiB
+        binding.set_batch(eng.pool, batch, depth)
+        jobs_sizes = [[48 * MiB, 30 * MiB + 48, 11 * MiB + 5], [6 * MiB + 7, 5 * MiB]]
+        jobs_w = [[1, 1, 1], [2, 2]]
+        descs = [make_descs(_h2p_job(orc, eng, rng, s, 96 * MiB)) for s in jobs_sizes]
+        for d, w in zip(descs, jobs_w):
+            orc.wait(orc.submit(d, w, C))
+        print(f"reweight batch={batch} depth={depth}", flush=True)
+        handles = [eng.submit(descs[0], jobs_w[0], C, fmt.FT_OPEN | fmt.FT_KEEP)]
+        changes = {0: [], 1: []}
+        at = binding.job_reweight(eng.pool, handles[0], [1, 6, 1])
+        assert at[1] is None and at[2] is None
+        if at[0] is not None:
+            changes[0].append((at[0], [1, 6, 1]))
+        merged = True
+        try:
+            handles.append(eng.merge(handles[0], descs[1], jobs_w[1], fmt.FT_KEEP))
+        except binding.FtError as e:
+            assert e.code == fmt.FT_ECLOSED
+            merged = False
+            handles.append(eng.submit(descs[1], jobs_w[1], C, fmt.FT_KEEP))
+        time.sleep(0.0003)
+        for j, w in ((1, [9, 1]), (0, [3, 1, 7])):
+            if j == 1 and not merged:
+                continue
+            at = binding.job_reweight(eng.pool, handles[j], w)
+            if at[0] is not None:
+                changes[j].append((at[0], w))
+        # bad arguments change nothing
+        for bad in ([1, 2], [1, 0, 1]):
+            with pytest.raises(binding.FtError) as err:
+                binding.job_reweight(eng.pool, handles[0], bad)
+            assert err.value.code == fmt.FT_EINVAL
+        for h in handles:
+            eng.wait(h)
+        _images_equal(orc, eng)
+        spec = [{"n": [chunk_count(s, C) for s in jobs_sizes[0]], "w": jobs_w[0], "reweight": changes[0]}]
+        index = {handles[0]: 0}
+        if merged:
+            index[handles[1]] = 1
+            spec.append({"n": [chunk_count(s, C) for s in jobs_sizes[1]], "w": jobs_w[1],
+                         "arrive": binding.job_arrival(eng.pool, handles[1], 0), "reweight": changes[1]})
+        got = binding.job_batches(eng.pool, handles[0], 0)
+        got = [[(index[j], f, k) for j, f, k in b] for b in got]
+        assert got == batched_order(spec, batch)
+        print("changes", changes, "merged", merged, "batches", len(got), flush=True)
+        # once everything is triggered a change is accepted and reports that nothing is left
+        assert binding.job_reweight(eng.pool, handles[0], [1, 1, 1]) == [None, None, None]
+        for h in handles:
+            binding.job_release(eng.pool, h)
+        # a closed job is not part of a sequence
+        d = make_descs(_h2p_job(orc, eng, rng, [300 * KiB], 96 * MiB))
+        orc.wait(orc.submit(d, [1], C))
+        plain = eng.submit(d, [1], C)
+        with pytest.raises(binding.FtError) as err:
+            binding.job_reweight(eng.pool, plain, [2])
+        assert err.value.code == fmt.FT_EINVAL
+        eng.wait(plain)
+    finally:
+        eng.close()
+
+
+def test_weights_changed_on_every_class_at_once(gpu):
+    """One open job with host->pool, pool->host and pool->pool functions, reweighted while it runs: each
+    class reports its own batch, each class's batches are the oracle's for that count."""
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 160 * MiB, 512 * MiB, seed=77)
+    try:
+        C = 256 * KiB
+        binding.set_batch(eng.pool, 4, 2)
+        sizes = [20 * MiB, 12 * MiB + 40, 18 * MiB, 9 * MiB + 8, 96 * MiB, 64 * MiB + 16]
+        recs, hdst = [], 80 * MiB
+        for f, n in enumerate(sizes):
+            a = orc.slab_alloc(n + 32)
+            assert eng.slab_alloc(n + 32) == a
+            if f < 2:
+                recs.append(dict(func=f, src_space=FT_HOST, dst_space=FT_POOL, src=f * 24 * MiB + 3 * f, dst=a + 5,
+                                 row_bytes=n))
+                continue
+            fill = rng.integers(0, 256, n + 32, dtype=np.uint8)
+            orc.write_pool(a, fill)
+            eng.write_pool(a, fill)
+            if f < 4:
+                recs.append(dict(func=f, src_space=FT_POOL, dst_space=FT_HOST, src=a + 1, dst=hdst + 7, row_bytes=n))
+                hdst += 24 * MiB
+            else:
+                b = orc.slab_alloc(n + 32)
+                assert eng.slab_alloc(n + 32) == b
+                recs.append(dict(func=f, src_space=FT_POOL, dst_space=FT_POOL, src=a + 2, dst=b + 9, row_bytes=n))
+        d = make_descs(recs)
+        w0, w1 = [1, 1, 1, 1, 1, 1], [1, 5, 4, 1, 2, 7]
+        orc.wait(orc.submit(d, w0, C))
+        job = eng.submit(d, w0, C, fmt.FT_OPEN | fmt.FT_KEEP)
+        at = binding.job_reweight(eng.pool, job, w1)
+        eng.wait(job)
+        _images_equal(orc, eng)
+        print("reweighted at", at, flush=True)
+        for c, fs, B in ((0, (0, 1), 4), (1, (2, 3), 4), (2, (4, 5), 64)):
+            spec = {"n": [chunk_count(sizes[f], C) for f in fs], "w": [w0[f] for f in fs]}
+            if at[c] is not None:
+                spec["reweight"] = [(at[c], [w1[f] for f in fs])]
+            got = binding.job_batches(eng.pool, job, c)
+            got = [[(fs.index(f), k) for _, f, k in b] for b in got]
+            assert got == [[(f, k) for _, f, k in b] for b in batched_order([spec], B)], c
+        binding.job_release(eng.pool, job)
+    finally:
+        eng.close()

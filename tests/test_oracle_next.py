@@ -212,7 +212,8 @@ def _reference_batches_reweighted(jobs, B):
     waiting = list(range(1, len(jobs)))
     present = [0]
     w = [list(j["w"]) for j in jobs]
-    changes = sorted((at, j, list(x)) for j, job in enumerate(jobs) for at, x in job.get("reweight", []))
+    changes = [(at, j, list(x)) for j, job in enumerate(jobs) for at, x in job.get("reweight", [])]
+    changes.sort(key=lambda t: t[0])
     done = {}
     todo = None
     out = []
@@ -260,6 +261,9 @@ def test_reweighting_hand_case_and_second_formulation():
     # a change that restores the old weights still restarts the tags (it is a rebuild like any other)
     same = batched_order([{"n": [10, 10], "w": [1, 2], "reweight": [(1, [1, 2])]}], 3)
     assert sorted(_flat(same)) == sorted(_flat(batched_order([{"n": [10, 10], "w": [1, 2]}], 3)))
+    # two changes at the same count: the one made later holds
+    twice = batched_order([{"n": [10, 10], "w": [1, 1], "reweight": [(2, [5, 1]), (2, [1, 3])]}], 4)
+    assert twice == got
     rng = random.Random(13)
     for case in range(300):
         B = rng.randint(1, 6)
@@ -272,8 +276,8 @@ def test_reweighting_hand_case_and_second_formulation():
             if j:
                 job["arrive"] = arrive[j - 1]
             if rng.random() < 0.7:
-                job["reweight"] = sorted((rng.randint(0, 10), [rng.choice([1, 2, 4, 7]) for _ in range(F)])
-                                         for _ in range(rng.randint(1, 2)))
+                job["reweight"] = sorted(((rng.randint(0, 10), [rng.choice([1, 2, 4, 7]) for _ in range(F)])
+                                          for _ in range(rng.randint(1, 2))), key=lambda t: t[0])
             jobs.append(job)
         got = batched_order(jobs, B)
         want = sorted((j, f, k) for j, job in enumerate(jobs) for f, n in enumerate(job["n"]) for k in range(n))
