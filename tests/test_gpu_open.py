@@ -783,14 +783,18 @@ def test_weights_changed_on_every_class_at_once(gpu):
         w0, w1 = [1, 1, 1, 1, 1, 1], [1, 5, 4, 1, 2, 7]
         orc.wait(orc.submit(d, w0, C))
         job = eng.submit(d, w0, C, fmt.FT_OPEN | fmt.FT_KEEP)
+        w2 = [3, 1, 1, 6, 5, 1]
         at = binding.job_reweight(eng.pool, job, w1)
+        time.sleep(0.0003)
+        at2 = binding.job_reweight(eng.pool, job, w2)
         eng.wait(job)
         _images_equal(orc, eng)
-        print("reweighted at", at, flush=True)
+        print("reweighted at", at, "and", at2, flush=True)
         for c, fs, B in ((0, (0, 1), 4), (1, (2, 3), 4), (2, (4, 5), 64)):
-            spec = {"n": [chunk_count(sizes[f], C) for f in fs], "w": [w0[f] for f in fs]}
-            if at[c] is not None:
-                spec["reweight"] = [(at[c], [w1[f] for f in fs])]
+            spec = {"n": [chunk_count(sizes[f], C) for f in fs], "w": [w0[f] for f in fs], "reweight": []}
+            for when, w in ((at[c], w1), (at2[c], w2)):
+                if when is not None:
+                    spec["reweight"].append((when, [w[f] for f in fs]))
             got = binding.job_batches(eng.pool, job, c)
             got = [[(fs.index(f), k) for _, f, k in b] for b in got]
             assert got == [[(f, k) for _, f, k in b] for b in batched_order([spec], B)], c

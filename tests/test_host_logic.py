@@ -341,3 +341,33 @@ def test_slo_weights_match_the_oracle_rule():
         with pytest.raises(ft.FtError) as ei:
             ft.slo_weights(*bad)
         assert ei.value.code == fmt.FT_EINVAL
+
+
+def test_every_ticket_walks_the_tables_in_bounds(tmp_path):
+    """tests/host/walk_tables.cpp: the planner's sources compiled for the host with sanitizers, random
+    submits, every ticket decoded as the kernel decodes it with each table read bounds-checked."""
+    import shutil
+    import subprocess
+    gxx = shutil.which("g++")
+    if gxx is None:
+        pytest.skip("no host compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    csrc = os.path.join(root, "paper_2411_01830_amd", "csrc")
+    exe = str(tmp_path / "walk_tables")
+    cmd = [gxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           os.path.join(root, "tests", "host", "walk_tables.cpp"), os.path.join(csrc, "ft_plan.cpp"),
+           os.path.join(csrc, "ft_pool.cpp"), "-o", exe]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0 and "sanitize" in res.stderr:
+        cmd = [c for c in cmd if "sanitize" not in c]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
+    run = subprocess.run([exe, "1", "150"], capture_output=True, text=True, timeout=300, env=env)
+    if run.returncode != 0 and "runtime does not come first" in run.stderr:
+        # another library is preloaded ahead of the sanitizer's: run the walk's own bounds checks alone
+        res = subprocess.run([c for c in cmd if "sanitize" not in c], capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr[-2000:]
+        run = subprocess.run([exe, "1", "150"], capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0, (run.stdout[-1000:], run.stderr[-3000:])
+    assert "done 1..150" in run.stdout
