@@ -10,11 +10,11 @@
 #include <vector>
 #include "../../paper_2411_01830_amd/csrc/ft_plan.h"
 using namespace ft;
-#define CHECK(c) do { if (!(c)) { std::printf("FAIL %s line %d seed %llu\n", #c, __LINE__, (unsigned long long)g_seed); std::abort(); } } while (0)
+#define CHECK(c) do { if (!(c)) { std::fprintf(stderr, "FAIL %s line %d seed %llu\n", #c, __LINE__, (unsigned long long)g_seed); std::abort(); } } while (0)
 static uint64_t g_seed;
 static uint64_t n_per = 0, n_notable = 0, n_skips = 0, n_cls = 0, n_tickets = 0;
 template <class T> const T &at(const std::vector<T> &v, uint64_t i, int line) {
-  if (i >= v.size()) { std::printf("OOB read line %d idx %llu size %zu seed %llu\n", line, (unsigned long long)i, v.size(), (unsigned long long)g_seed); std::abort(); }
+  if (i >= v.size()) { std::fprintf(stderr, "OOB read line %d idx %llu size %zu seed %llu\n", line, (unsigned long long)i, v.size(), (unsigned long long)g_seed); std::abort(); }
   return v[i];
 }
 #define AT(v, i) at(v, i, __LINE__)

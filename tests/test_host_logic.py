@@ -343,9 +343,8 @@ def test_slo_weights_match_the_oracle_rule():
         assert ei.value.code == fmt.FT_EINVAL
 
 
-def test_every_ticket_walks_the_tables_in_bounds(tmp_path):
-    """tests/host/walk_tables.cpp: the planner's sources compiled for the host with sanitizers, random
-    submits, every ticket decoded as the kernel decodes it with each table read bounds-checked."""
+def _host_sanitizer_run(tmp_path, name, sources, args, expect):
+    """Build tests/host/<name>.cpp with the given library sources for the host, with sanitizers, and run it."""
     import shutil
     import subprocess
     gxx = shutil.which("g++")
@@ -353,21 +352,31 @@ def test_every_ticket_walks_the_tables_in_bounds(tmp_path):
         pytest.skip("no host compiler")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     csrc = os.path.join(root, "paper_2411_01830_amd", "csrc")
-    exe = str(tmp_path / "walk_tables")
+    exe = str(tmp_path / name)
     cmd = [gxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
-           os.path.join(root, "tests", "host", "walk_tables.cpp"), os.path.join(csrc, "ft_plan.cpp"),
-           os.path.join(csrc, "ft_pool.cpp"), "-o", exe]
+           os.path.join(root, "tests", "host", name + ".cpp"), *[os.path.join(csrc, f) for f in sources], "-o", exe]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0 and "sanitize" in res.stderr:
         cmd = [c for c in cmd if "sanitize" not in c]
         res = subprocess.run(cmd, capture_output=True, text=True)
     assert res.returncode == 0, res.stderr[-2000:]
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
-    run = subprocess.run([exe, "1", "150"], capture_output=True, text=True, timeout=300, env=env)
+    run = subprocess.run([exe, *args], capture_output=True, text=True, timeout=300)
     if run.returncode != 0 and "runtime does not come first" in run.stderr:
-        # another library is preloaded ahead of the sanitizer's: run the walk's own bounds checks alone
+        # another library is preloaded ahead of the sanitizer's: run the program's own checks alone
         res = subprocess.run([c for c in cmd if "sanitize" not in c], capture_output=True, text=True)
         assert res.returncode == 0, res.stderr[-2000:]
-        run = subprocess.run([exe, "1", "150"], capture_output=True, text=True, timeout=300)
+        run = subprocess.run([exe, *args], capture_output=True, text=True, timeout=300)
     assert run.returncode == 0, (run.stdout[-1000:], run.stderr[-3000:])
-    assert "done 1..150" in run.stdout
+    assert expect in run.stdout
+
+
+def test_every_ticket_walks_the_tables_in_bounds(tmp_path):
+    """tests/host/walk_tables.cpp: the planner's sources compiled for the host with sanitizers, random
+    submits, every ticket decoded as the kernel decodes it with each table read bounds-checked."""
+    _host_sanitizer_run(tmp_path, "walk_tables", ["ft_plan.cpp", "ft_pool.cpp"], ["1", "150"], "done 1..150")
+
+
+def test_policy_and_path_planners_under_sanitizers(tmp_path):
+    """tests/host/policy_calls.cpp: random calls of the migration planner, the pool sizer, the path planner
+    and the striping with output arrays of exactly the promised size (leaks included)."""
+    _host_sanitizer_run(tmp_path, "policy_calls", ["ft_policy.cpp", "ft_paths.cpp"], ["1", "300"], "done 1..300")
