@@ -85,5 +85,23 @@ def build(verbose=False):
     return LIB
 
 
+def build_native_tests(verbose=False):
+    """tests/host/c_abi_stress: a C++ program that uses the library through include/faastube.h only."""
+    root = os.path.dirname(HERE)
+    src = os.path.join(root, "tests", "host", "c_abi_stress.cpp")
+    exe = os.path.join(root, "tests", "host", "c_abi_stress")
+    cmd = [hipcc(), "-x", "hip", "-O2", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", src, "-L" + HERE, "-lfaastube", "-Wl,-rpath,$ORIGIN/../../paper_2411_01830_amd", "-lpthread", "-o", exe + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stderr)
+        raise RuntimeError("hipcc failed on c_abi_stress.cpp")
+    os.replace(exe + ".tmp", exe)
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))
+    print(build_native_tests(verbose="-v" in sys.argv))

@@ -1,0 +1,158 @@
+// A consumer of the C ABI without Python: links libfaastube.so, owns its memory through the HIP
+// runtime alone, and drives the engine from several threads at once - an open job (host->pool and
+// pool->pool functions) that two threads merge later jobs into while a third keeps changing its
+// weights, closed jobs of three sizes (tables inside the launch, a recycled counter pair, uploaded
+// tables), then the store. Every transfer is one contiguous piece, so what the pool must hold is
+// what memcpy puts into a host image; the whole pool is compared with it after every round.
+// Built by paper_2411_01830_amd/build.py (build_native_tests); run by tests/test_gpu_native.py.
+// The library's host sources can also be compiled with -Xarch_host -fsanitize=address and linked
+// into this program in place of the shared library: the address sanitizer then watches the feeder
+// threads, the table generations and the recycled buffers while the GPU does the real work.
+// Usage: c_abi_stress [rounds]
+#include <hip/hip_runtime.h>
+#include <atomic>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <random>
+#include <thread>
+#include <vector>
+#include "../../include/faastube.h"
+#define OK(c) do { int rc_ = (c); if (rc_ != 0) { std::fprintf(stderr, "FAIL %s -> %d line %d\n", #c, rc_, __LINE__); std::abort(); } } while (0)
+#define HIPOK(c) do { hipError_t e_ = (c); if (e_ != hipSuccess) { std::fprintf(stderr, "HIP FAIL %s -> %s line %d\n", #c, hipGetErrorString(e_), __LINE__); std::abort(); } } while (0)
+
+static const uint64_t MiB = 1ull << 20;
+
+int main(int argc, char **argv) {
+  const int rounds = argc > 1 ? atoi(argv[1]) : 6;
+  const uint64_t pool_bytes = 1024 * MiB, host_bytes = 512 * MiB;
+  char *dev = nullptr, *host = nullptr;
+  HIPOK(hipMalloc(&dev, pool_bytes));
+  HIPOK(hipHostMalloc(&host, host_bytes, hipHostMallocDefault));
+  std::mt19937_64 r(7);
+  for (uint64_t i = 0; i < host_bytes / 2; i += 8) *reinterpret_cast<uint64_t *>(host + i) = r();
+  std::vector<char> expect(pool_bytes, 0);
+  HIPOK(hipMemset(dev, 0, pool_bytes));
+  ft_pool *pool = nullptr;
+  OK(ft_pool_create(&pool, dev, pool_bytes, 64 * 1024, 0));
+  OK(ft_host_window_add(pool, host, host_bytes));
+  hipStream_t stream;
+  HIPOK(hipStreamCreate(&stream));
+  for (int round = 0; round < rounds; ++round) {
+    std::fprintf(stderr, "round %d\n", round);
+    OK(ft_set_batch(pool, 1 + round % 5, 1 + round % 3));
+    // open job: 4 functions host->pool, then merges and weight changes from threads
+    struct J { std::vector<ft_desc> d; std::vector<uint32_t> w; std::vector<ft_off_t> offs; ft_job_t id = 0; bool merged = false; };
+    auto make = [&](uint32_t nfunc, uint64_t lo, uint64_t hi, bool p2p) {
+      J j;
+      for (uint32_t f = 0; f < nfunc; ++f) {
+        const uint64_t n = lo + r() % (hi - lo + 1);
+        ft_off_t off = 0;
+        OK(ft_slab_alloc(pool, n + 32, &off));
+        ft_desc d{};
+        d.func = f; d.dst_space = FT_POOL; d.dst = off + r() % 16; d.row_bytes = n; d.rows = 1; d.src_pitch = d.dst_pitch = n;
+        if (p2p) {
+          ft_off_t s = 0;
+          OK(ft_slab_alloc(pool, n + 32, &s));
+          const uint64_t so = s + r() % 16, ho = r() % (host_bytes / 2 - n);
+          HIPOK(hipMemcpy(dev + so, host + ho, n, hipMemcpyHostToDevice));
+          std::memcpy(expect.data() + so, host + ho, n);
+          d.src_space = FT_POOL; d.src = so;
+          std::memcpy(expect.data() + d.dst, host + ho, n);
+          j.offs.push_back(s);
+        } else {
+          const uint64_t ho = r() % (host_bytes / 2 - n);
+          d.src_space = FT_HOST; d.src = reinterpret_cast<uint64_t>(host + ho);
+          std::memcpy(expect.data() + d.dst, host + ho, n);
+        }
+        j.offs.push_back(off);
+        j.d.push_back(d);
+        j.w.push_back(1 + r() % 7);
+      }
+      return j;
+    };
+    J first = make(4, 8 * MiB, 24 * MiB, false);
+    {
+      J extra = make(2, 16 * MiB, 32 * MiB, true);  // pool->pool functions in the same open job
+      for (auto &d : extra.d) { d.func += 4; first.d.push_back(d); }
+      first.w.insert(first.w.end(), extra.w.begin(), extra.w.end());
+      first.offs.insert(first.offs.end(), extra.offs.begin(), extra.offs.end());
+    }
+    std::vector<J> later;
+    for (int i = 0; i < 6; ++i) later.push_back(make(1 + i % 3, 64 * 1024, 3 * MiB, i % 2 == 1));
+    OK(ft_submit_transfers(pool, first.d.data(), (uint32_t)first.d.size(), first.w.data(), (uint32_t)first.w.size(), 256 * 1024,
+                           FT_OPEN | FT_KEEP, stream, &first.id));
+    std::atomic<int> stop{0};
+    std::thread changer([&] {
+      std::mt19937_64 q(round);
+      while (!stop.load()) {
+        std::vector<uint32_t> w(first.w.size());
+        for (auto &x : w) x = 1 + q() % 9;
+        uint64_t at[3];
+        int rc = ft_job_reweight(pool, first.id, w.data(), (uint32_t)w.size(), nullptr, at);
+        if (rc != 0) { std::fprintf(stderr, "reweight rc %d\n", rc); std::abort(); }
+        std::this_thread::sleep_for(std::chrono::microseconds(50 + q() % 200));
+      }
+    });
+    auto merger = [&](int from) {
+      hipStream_t s;
+      HIPOK(hipStreamCreate(&s));
+      for (int i = from; i < 6; i += 2) {
+        J &j = later[i];
+        int rc = ft_submit_merge(pool, first.id, j.d.data(), (uint32_t)j.d.size(), j.w.data(), (uint32_t)j.w.size(), 0, s, &j.id);
+        if (rc == FT_ECLOSED) rc = ft_submit_transfers(pool, j.d.data(), (uint32_t)j.d.size(), j.w.data(), (uint32_t)j.w.size(), 256 * 1024, 0, s, &j.id);
+        else j.merged = true;
+        if (rc != 0) { std::fprintf(stderr, "merge rc %d\n", rc); std::abort(); }
+        OK(ft_wait(pool, j.id));
+        (void)ft_job_release(pool, j.id);
+      }
+      HIPOK(hipStreamSynchronize(s));
+      HIPOK(hipStreamDestroy(s));
+    };
+    std::thread m0(merger, 0), m1(merger, 1);
+    OK(ft_wait(pool, first.id));
+    m0.join();
+    m1.join();
+    stop.store(1);
+    changer.join();
+    (void)ft_job_release(pool, first.id);
+    // closed jobs: one small (tables with the launch), one larger (counter pair), one plain
+    for (uint64_t n : {uint64_t(4096), 3 * MiB, 40 * MiB}) {
+      J j = make(1 + (n > MiB ? 2 : 0), n, n + 100, n == 3 * MiB);
+      OK(ft_submit_transfers(pool, j.d.data(), (uint32_t)j.d.size(), j.w.data(), (uint32_t)j.w.size(), 2 * MiB, round % 2 ? FT_VALIDATE : 0, stream, &j.id));
+      OK(ft_wait(pool, j.id));
+      (void)ft_job_release(pool, j.id);
+      for (ft_off_t o : j.offs) (void)o;
+      later.push_back(std::move(j));
+    }
+    HIPOK(hipDeviceSynchronize());
+    std::vector<char> got(pool_bytes);
+    HIPOK(hipMemcpy(got.data(), dev, pool_bytes, hipMemcpyDeviceToHost));
+    if (std::memcmp(got.data(), expect.data(), pool_bytes) != 0) { std::fprintf(stderr, "bytes differ in round %d\n", round); std::abort(); }
+    for (ft_off_t o : first.offs) OK(ft_slab_free(pool, o));
+    for (J &j : later) for (ft_off_t o : j.offs) OK(ft_slab_free(pool, o));
+  }
+  // the store on top
+  {
+    char *spill = host + host_bytes / 2;
+    ft_store *st = nullptr;
+    OK(ft_store_create(&st, pool, spill, 256 * MiB, 48 * MiB, 2 * MiB, stream));
+    for (uint64_t id = 1; id <= 30; ++id) {
+      ft_off_t off = 0;
+      OK(ft_store_put(st, id, (1 + id % 5) * 2 * MiB, 40 - id + id % 7, &off));
+      if (id % 3 == 0) { uint32_t was = 0; OK(ft_store_get(st, id - 2, &off, &was)); OK(ft_store_done(st, id - 2)); }
+      OK(ft_store_advance(st, 1));
+    }
+    ft_store_stats_t s{};
+    OK(ft_store_stats(st, &s));
+    std::fprintf(stderr, "store: out %llu in %llu stalls %llu\n", (unsigned long long)s.moved_out, (unsigned long long)s.moved_in, (unsigned long long)s.stalls);
+    OK(ft_store_destroy(st));
+  }
+  HIPOK(hipStreamSynchronize(stream));
+  OK(ft_pool_destroy(pool));
+  HIPOK(hipStreamDestroy(stream));
+  HIPOK(hipHostFree(host));
+  HIPOK(hipFree(dev));
+  std::printf("c_abi_stress done\n");
+  return 0;
+}
