@@ -253,7 +253,10 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
  * with nothing merged, if the open job has already triggered its last batch on a link
  * class the new transfers use. Flags: FT_VALIDATE, FT_KEEP (others are taken from the
  * open job). The caller's stream is never made to wait (as with FT_DETACHED); the
- * transfers start after the work already on hip_stream.
+ * transfers start after the work already on hip_stream. FT_EINVAL also if open_job is
+ * no live handle of a job submitted with FT_OPEN: where merges or weight changes may
+ * come after the open job has been waited for, submit it with FT_KEEP, so that they
+ * meet FT_ECLOSED (or no effect) rather than a dead handle.
  */
 int ft_submit_merge(ft_pool *p, ft_job_t open_job, const ft_desc *descs, uint32_t ndesc,
                     const uint32_t *weights, uint32_t nfunc, uint32_t flags, void *hip_stream,
