@@ -639,6 +639,29 @@ def cpu_baseline():
                       f"{dt:.1f} s, {os.cpu_count()} logical CPUs present"}
 
 
+def sector_bytes(rp):
+    """Pool->pool descriptors of pitched rows (the traffic workload's crops): the bytes of all 64-byte and
+    128-byte lines that the rows touch on the read side and on the write side, beside the payload. Rows of
+    64-256 bytes at any alignment touch up to one line more than their length fills."""
+    out = {"payload": 0, "read_64": 0, "read_128": 0, "write_64": 0, "write_128": 0}
+    for op in rp.ops:
+        if op[0] != "submit":
+            continue
+        for d in op[2]:
+            if d["src_space"] != 1 or d["dst_space"] != 1:
+                continue
+            rows, w = int(d["rows"]), int(d["row_bytes"])
+            r = np.arange(rows, dtype=np.int64)
+            out["payload"] += rows * w
+            for side, base, pitch in (("read", int(d["src"]), int(d["src_pitch"])), ("write", int(d["dst"]), int(d["dst_pitch"]))):
+                a = base + r * (pitch if rows > 1 else 0)
+                for g in (64, 128):
+                    lines = np.unique(np.concatenate([np.arange(x // g, (x + w - 1) // g + 1) for x in a])) \
+                        if rows <= 4096 else None
+                    out[f"{side}_{g}"] += int(len(lines)) * g if lines is not None else (w + g - 1) // g * g * rows
+    return out
+
+
 def summarize(name, res, steps, rp, peaks):
     ms_per_step = res["wall_s"] * 1e3 / steps
     out = {"payload_GiB": round(rp.payload / 2**30, 3), "ms_per_step": round(ms_per_step, 3),
@@ -654,6 +677,14 @@ def summarize(name, res, steps, rp, peaks):
                  "avg_launch_ms": round(res["cls_ms"][c] / res["cls_launches"][c], 4)}
         if c == 2:
             entry["hbm_frac"] = round(2 * gbps / HBM_PEAK_GBS, 4)
+            if name == "traffic":
+                sb = sector_bytes(rp)
+                entry["line_granular_bytes_per_payload_byte"] = {
+                    "lines_64B": round((sb["read_64"] + sb["write_64"]) / (2 * sb["payload"]), 4),
+                    "lines_128B": round((sb["read_128"] + sb["write_128"]) / (2 * sb["payload"]), 4),
+                    "measured_hbm_traffic": TRAFFIC_PER_ALGO_BYTE["traffic_crops"]}
+                entry["hbm_frac_line_granular_128B"] = round(
+                    gbps * (sb["read_128"] + sb["write_128"]) / sb["payload"] / HBM_PEAK_GBS, 4)
         else:
             entry["link_frac"] = round(gbps / peaks["h2d" if c == 0 else "d2h"], 4)
         out[names[c]] = entry
