@@ -653,7 +653,7 @@ def cpu_baseline():
         t.join()
     dt2 = time.perf_counter() - t0
     out["parallel_variant"] = {"value": plan.payload_bytes() / dt2 / 1e9, "unit": "GB/s", "threads": len(threads),
-                               "what": "byte movement only, one thread per function, same sample"}
+                               "what": "byte movement only (every buffer in host memory, no link crossed), one thread per function, same sample"}
     return out
 
 
