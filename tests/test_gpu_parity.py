@@ -256,9 +256,35 @@ def test_log_and_timing(gpu):
         assert st.cls[2].device_ms > 0
         span_ms = (int(log["t_end_ns"].max()) - int(log["t_begin_ns"].min())) / 1e6
         assert span_ms <= st.cls[2].device_ms * 1.5 + 0.5
+        # which workgroup moved which ticket, and when each workgroup came and went (same clock)
+        wg, t_in, t_out = binding.job_log_workgroups(eng.pool, j, 2, len(log["bytes"]))
+        assert len(t_in) == st.cls[2].workgroups == len(t_out)
+        assert int(wg.max()) < len(t_in)
+        assert set(np.unique(wg).tolist()) == set(range(len(t_in)))       # no more workgroups than tickets
+        assert np.all(t_out >= t_in)
+        for g in range(len(t_in)):
+            mine = wg == g
+            assert int(log["t_begin_ns"][mine].min()) >= int(t_in[g])
+            assert int(log["t_end_ns"][mine].max()) <= int(t_out[g])
+        # workgroup b starts on ticket b
+        assert wg[:len(t_in)].tolist() == list(range(len(t_in)))
         binding.job_release(eng.pool, j)
     finally:
         eng.close()
+
+
+def test_plain_copy_kernel_copies(gpu):
+    """The plain grid-stride copy that the benchmark uses as its yardstick, at a size with a ragged end."""
+    import torch
+    binding, _ = gpu
+    n = (3 << 20) + 16 * 7
+    a = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda:0")
+    b = torch.zeros(n + 64, dtype=torch.uint8, device="cuda:0")
+    for wg in (0, 1, 256):
+        b.zero_()
+        binding.plain_copy(b.data_ptr(), a.data_ptr(), n, wg, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(b[:n], a) and int(b[n:].sum()) == 0
 
 
 def test_small_jobs_take_the_launch_argument_path(gpu):

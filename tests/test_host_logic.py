@@ -380,3 +380,18 @@ def test_policy_and_path_planners_under_sanitizers(tmp_path):
     """tests/host/policy_calls.cpp: random calls of the migration planner, the pool sizer, the path planner
     and the striping with output arrays of exactly the promised size (leaks included)."""
     _host_sanitizer_run(tmp_path, "policy_calls", ["ft_policy.cpp", "ft_paths.cpp"], ["1", "300"], "done 1..300")
+
+
+def test_every_code_has_a_name_and_a_fresh_pool_no_hip_error():
+    codes = [fmt.FT_OK, fmt.FT_EINVAL, fmt.FT_ENOMEM, fmt.FT_ERANGE, fmt.FT_EOVERLAP, fmt.FT_EBUSY, fmt.FT_EHIP,
+             fmt.FT_ECLOSED]
+    names = [ft.strerror(c) for c in codes]
+    assert all(names) and len(set(names)) == len(names)
+    assert ft.strerror(-99) and ft.strerror(-99) not in names        # an unknown code still gets a text
+    # a pool handle needs no GPU (no HIP call before the first submit): its error text starts empty
+    pool = ft.pool_create(1 << 20, 1 << 20, 4096, 0)
+    assert ft._lib.ft_last_hip_error(pool) == b""
+    with pytest.raises(ft.FtError) as err:
+        ft.slab_alloc(pool, 2 << 20)
+    assert err.value.code == fmt.FT_ENOMEM and ft.strerror(fmt.FT_ENOMEM) in str(err.value)
+    ft.pool_destroy(pool)
