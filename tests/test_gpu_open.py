@@ -801,3 +801,59 @@ def test_weights_changed_on_every_class_at_once(gpu):
         binding.job_release(eng.pool, job)
     finally:
         eng.close()
+
+
+def test_pool_destroyed_with_open_jobs_in_flight(gpu):
+    """ft_pool_destroy waits for everything: an open job with all three classes and a pageable destination,
+    a job merged into it, a closed job - none of them waited for - and every byte is where it belongs
+    when the call returns."""
+    from workloads import FT_PAGEABLE
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 128 * MiB, 256 * MiB, seed=91)
+    try:
+        C = 256 * KiB
+        for e in (orc, eng):
+            e.pageable_arena(16 * MiB)
+        binding.set_batch(eng.pool, 3, 2)
+
+        def alloc(n):
+            a = orc.slab_alloc(n)
+            assert eng.slab_alloc(n) == a
+            return a
+
+        def filled(n):
+            a = alloc(n)
+            data = rng.integers(0, 256, n, dtype=np.uint8)
+            orc.write_pool(a, data)
+            eng.write_pool(a, data)
+            return a
+
+        big = 20 * MiB
+        recs0 = [dict(func=0, src_space=FT_HOST, dst_space=FT_POOL, src=8192 + 1, dst=alloc(big) + 2, row_bytes=big - 16),
+                 dict(func=1, src_space=FT_POOL, dst_space=FT_HOST, src=filled(big), dst=64 * MiB + 3, row_bytes=big),
+                 dict(func=2, src_space=FT_POOL, dst_space=FT_POOL, src=filled(big) + 5, dst=alloc(big), row_bytes=big - 16),
+                 dict(func=1, src_space=FT_POOL, dst_space=FT_PAGEABLE, src=filled(6 * MiB), dst=4096 + 7, row_bytes=6 * MiB)]
+        recs1 = [dict(func=0, src_space=FT_HOST, dst_space=FT_POOL, src=30 * MiB, dst=alloc(3 * MiB), row_bytes=3 * MiB)]
+        recs2 = [dict(func=0, src_space=FT_POOL, dst_space=FT_POOL, src=filled(5 * MiB), dst=alloc(5 * MiB) + 1,
+                      row_bytes=5 * MiB - 1)]
+        d0, d1, d2 = make_descs(recs0), make_descs(recs1), make_descs(recs2)
+        for d, w in ((d0, [1, 2, 1]), (d1, [4]), (d2, [1])):
+            orc.wait(orc.submit(d, w, C))
+        j0 = eng.submit(d0, [1, 2, 1], C, fmt.FT_OPEN)
+        try:
+            eng.merge(j0, d1, [4])
+        except binding.FtError as e:
+            assert e.code == fmt.FT_ECLOSED
+            eng.submit(d1, [4], C, fmt.FT_DETACHED)
+        eng.submit(d2, [1], C, fmt.FT_DETACHED)
+        segments = list(eng.segments)
+        print("destroying the pool with three jobs in flight", flush=True)
+        binding.pool_destroy(eng.pool)          # no ft_wait before it
+        eng.pool = None
+        import torch
+        assert np.array_equal(eng.host_np[:len(orc.host_mem)], orc.host_mem), "host image differs"
+        assert np.array_equal(eng.pageable_np, orc.pageable_mem), "pageable image differs"
+        got = torch.cat([t for t, _ in segments]).cpu().numpy()
+        assert np.array_equal(got, orc.pool_mem), "pool image differs"
+    finally:
+        eng.close()
