@@ -265,7 +265,7 @@ int ft_submit_merge(ft_pool *p, ft_job_t open_job, const ft_desc *descs, uint32_
 /*
  * Chunks per batch (>= 1) and batches queued ahead (>= 1) for open jobs submitted later.
  * batch_chunks is what a host-link class puts into one batch; the pool->pool class, which
- * moves a chunk some sixty times faster, puts 16 * batch_chunks into one (ft_job_batches
+ * moves a chunk some sixty times faster, puts 64 * batch_chunks into one (ft_job_batches
  * reports the batches as triggered).
  */
 int ft_set_batch(ft_pool *p, uint32_t batch_chunks, uint32_t depth);

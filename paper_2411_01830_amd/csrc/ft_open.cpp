@@ -145,9 +145,10 @@ struct OpenClass {
   uint64_t batches_triggered = 0;
   // chunks per batch of this class. The paper's batch (5 chunks of 2 MB) is sized for a PCIe
   // link, where it is a fraction of a millisecond; the on-device class moves a chunk about
-  // sixty times faster and a launch per 5 chunks would be all launch cost (1 GiB between
-  // slabs: 0.8 TB/s at 5 chunks a batch, 2.3 TB/s at 80), so its batches hold 16 times as
-  // many chunks - still well under 0.1 ms each.
+  // sixty times faster and a launch per 5 chunks would be all launch cost (8 GiB between
+  // slabs, payload rate against 3.3 TB/s for a closed job: 2.7 TB/s at 80 chunks a batch,
+  // 3.1 at 320), so its batches hold 64 times as many chunks - 0.2 ms each, a quarter of
+  // what five 2 MB chunks take on the paper's PCIe link.
   uint32_t batch_chunks = 5;
   uint64_t tile_bytes = 0;
   uint32_t tiles_per_chunk = 0;
@@ -274,7 +275,7 @@ void drop_generation(ft_pool *p, Generation *g) {
 }
 
 constexpr uint64_t kStagePiece = 256 * 1024;  // longest single copy handed to a helper
-constexpr uint32_t kOnDeviceBatchScale = 16;  // see OpenClass::batch_chunks
+constexpr uint32_t kOnDeviceBatchScale = 64;  // see OpenClass::batch_chunks
 
 struct Prepared {
   OpenBatch batch;

@@ -487,8 +487,8 @@ def test_pageable_destinations_through_the_ring(gpu, batch, depth, threads):
         eng.close()
 
 
-def test_pool_to_pool_open_job_triggers_sixteen_times_larger_batches(gpu):
-    """The on-device class puts 16 x batch_chunks chunks into a batch; the batches it triggers are the
+def test_pool_to_pool_open_job_triggers_larger_batches(gpu):
+    """The on-device class puts 64 x batch_chunks chunks into a batch; the batches it triggers are the
     oracle's for that batch size, merged job included."""
     binding, _ = gpu
     orc, eng, rng = _engines(gpu, 4 * MiB, 256 * MiB, seed=53)
@@ -529,8 +529,8 @@ def test_pool_to_pool_open_job_triggers_sixteen_times_larger_batches(gpu):
         _images_equal(orc, eng)
         got = binding.job_batches(eng.pool, j0, 2)
         got = [[(index[j], f, k) for j, f, k in b] for b in got]
-        assert got == batched_order(spec, 32)
-        assert max(len(b) for b in got) == 32
+        assert got == batched_order(spec, 128)
+        assert max(len(b) for b in got) == 128
         print("pool->pool batches", len(got), "arrivals", [s.get("arrive", 0) for s in spec], flush=True)
         binding.job_release(eng.pool, j0)
         binding.job_release(eng.pool, j1)
@@ -790,7 +790,7 @@ def test_weights_changed_on_every_class_at_once(gpu):
         eng.wait(job)
         _images_equal(orc, eng)
         print("reweighted at", at, "and", at2, flush=True)
-        for c, fs, B in ((0, (0, 1), 4), (1, (2, 3), 4), (2, (4, 5), 64)):
+        for c, fs, B in ((0, (0, 1), 4), (1, (2, 3), 4), (2, (4, 5), 256)):
             spec = {"n": [chunk_count(sizes[f], C) for f in fs], "w": [w0[f] for f in fs], "reweight": []}
             for when, w in ((at[c], w1), (at2[c], w2)):
                 if when is not None:
