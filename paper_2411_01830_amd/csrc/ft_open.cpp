@@ -30,6 +30,9 @@
 #include <condition_variable>
 #include <cstring>
 #include <deque>
+#include <functional>
+#include <memory>
+#include <mutex>
 #include <thread>
 
 #include "ft_internal.h"
@@ -82,6 +85,7 @@ class StagePool {
   explicit StagePool(unsigned helpers) {
     for (unsigned i = 0; i < helpers; ++i) threads_.emplace_back([this] { work(false); });
   }
+  unsigned helpers() const { return (unsigned)threads_.size(); }
   ~StagePool() {
     {
       std::lock_guard<std::mutex> lock(mu_);
@@ -129,6 +133,124 @@ class StagePool {
   bool quit_ = false;
 };
 
+// A parked thread that runs one task at a time: a feeder borrows one for the life of its
+// class's sequence instead of creating a thread of its own.
+class Worker {
+ public:
+  Worker() : thread_([this] { loop(); }) {}
+  ~Worker() {
+    {
+      std::lock_guard<std::mutex> lock(mu_);
+      quit_ = true;
+    }
+    cv_.notify_all();
+    thread_.join();
+  }
+  void start(std::function<void()> task) {
+    {
+      std::lock_guard<std::mutex> lock(mu_);
+      task_ = std::move(task);
+      busy_ = true;
+    }
+    cv_.notify_all();
+  }
+  void wait_idle() {
+    std::unique_lock<std::mutex> lock(mu_);
+    idle_.wait(lock, [this] { return !busy_; });
+  }
+
+ private:
+  void loop() {
+    std::unique_lock<std::mutex> lock(mu_);
+    for (;;) {
+      cv_.wait(lock, [this] { return quit_ || task_; });
+      if (quit_) return;
+      std::function<void()> task = std::move(task_);
+      task_ = nullptr;
+      lock.unlock();
+      task();
+      lock.lock();
+      busy_ = false;
+      idle_.notify_all();
+    }
+  }
+  std::mutex mu_;
+  std::condition_variable cv_, idle_;
+  std::function<void()> task_;
+  bool busy_ = false, quit_ = false;
+  std::thread thread_;  // last: the members above exist before the thread looks at them
+};
+
+// Threads between jobs. Creating a feeder and three staging helpers costs more than moving a
+// small transfer (64 KiB from pageable memory: 143 us with fresh threads per job), so they
+// are parked here when a sequence ends and handed to the next one. Never destroyed: parked
+// threads simply end with the process.
+struct ThreadCache {
+  std::mutex mu;
+  std::vector<std::unique_ptr<Worker>> workers;
+  std::vector<std::unique_ptr<StagePool>> stagers;
+};
+ThreadCache &thread_cache() {
+  static ThreadCache *cache = new ThreadCache();
+  return *cache;
+}
+constexpr size_t kMaxParkedWorkers = 12, kMaxParkedStagers = 6;
+
+std::unique_ptr<Worker> get_worker() {
+  ThreadCache &tc = thread_cache();
+  {
+    std::lock_guard<std::mutex> lock(tc.mu);
+    if (!tc.workers.empty()) {
+      std::unique_ptr<Worker> w = std::move(tc.workers.back());
+      tc.workers.pop_back();
+      return w;
+    }
+  }
+  return std::unique_ptr<Worker>(new Worker());
+}
+
+void put_worker(std::unique_ptr<Worker> w) {
+  if (!w) return;
+  ThreadCache &tc = thread_cache();
+  std::unique_lock<std::mutex> lock(tc.mu);
+  if (tc.workers.size() < kMaxParkedWorkers) {
+    tc.workers.push_back(std::move(w));
+    return;
+  }
+  lock.unlock();
+  w.reset();  // joins
+}
+
+std::unique_ptr<StagePool> get_stagers(unsigned helpers) {
+  ThreadCache &tc = thread_cache();
+  {
+    std::lock_guard<std::mutex> lock(tc.mu);
+    for (size_t i = 0; i < tc.stagers.size(); ++i)
+      if (tc.stagers[i]->helpers() == helpers) {
+        std::unique_ptr<StagePool> sp = std::move(tc.stagers[i]);
+        tc.stagers.erase(tc.stagers.begin() + (long)i);
+        return sp;
+      }
+  }
+  return std::unique_ptr<StagePool>(new StagePool(helpers));
+}
+
+void put_stagers(std::unique_ptr<StagePool> sp) {
+  if (!sp) return;
+  ThreadCache &tc = thread_cache();
+  std::unique_lock<std::mutex> lock(tc.mu);
+  if (tc.stagers.size() >= kMaxParkedStagers) {
+    // make room by dropping the oldest: thread counts in use change rarely
+    std::unique_ptr<StagePool> old = std::move(tc.stagers.front());
+    tc.stagers.erase(tc.stagers.begin());
+    tc.stagers.push_back(std::move(sp));
+    lock.unlock();
+    old.reset();  // joins its helpers
+    return;
+  }
+  tc.stagers.push_back(std::move(sp));
+}
+
 struct BatchRec {
   uint64_t job;
   uint32_t func;
@@ -162,7 +284,7 @@ struct OpenClass {
   uint64_t staged_bytes = 0;
   double stage_ms = 0;
   std::unique_ptr<StagePool> stagers;
-  std::thread feeder;
+  std::unique_ptr<Worker> feeder;   // runs feeder_main for this class until the sequence is dry
 };
 
 }  // namespace
@@ -183,8 +305,9 @@ struct OpenState {
 
   ~OpenState() {
     for (OpenClass &c : cls) {
-      if (c.feeder.joinable()) c.feeder.join();
-      c.stagers.reset();
+      if (c.feeder) c.feeder->wait_idle();
+      put_worker(std::move(c.feeder));
+      put_stagers(std::move(c.stagers));
       put_pinned(pool, c.ring, c.ring_cap);
     }
   }
@@ -510,7 +633,7 @@ int ensure_ring(ft_pool *p, OpenState *st, int c) {
   int rc = get_pinned(p, slots * st->chunk_bytes, &oc.ring, &oc.ring_cap);
   if (rc != FT_OK) return rc;
   oc.ring_slots = slots;
-  oc.stagers.reset(new StagePool(p->stage_threads ? p->stage_threads - 1 : 3));
+  oc.stagers = get_stagers(p->stage_threads ? p->stage_threads - 1 : 3);
   return FT_OK;
 }
 
@@ -588,7 +711,11 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
   }
   st->left[job->id] = chunks;
   for (int c = 0; c < FT_NCLASS; ++c)
-    if (st->cls[c].used) st->cls[c].feeder = std::thread(feeder_main, st.get(), c);
+    if (st->cls[c].used) {
+      OpenState *raw = st.get();  // outlives the task: ~OpenState waits for the feeders
+      st->cls[c].feeder = get_worker();
+      st->cls[c].feeder->start([raw, c] { feeder_main(raw, c); });
+    }
   lock.unlock();
   job->open = st;
   return FT_OK;
