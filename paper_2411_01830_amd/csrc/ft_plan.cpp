@@ -283,6 +283,14 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
   // ---- pass 2: ranges; resolve both sides to device-visible addresses
   std::vector<Xfer> resolved(ndesc);
   std::vector<uint64_t> used;
+  // The allocations met last, most recent first: descriptors of one submit mostly name the
+  // same few (the crops of a frame, the packed buffer of a consumer), and a hit spares the
+  // search of the allocation map, the search of the segment list and an entry in `used`.
+  struct Recent {
+    uint64_t lo = 1, hi = 0;  // offsets of the allocation, [lo, hi)
+    uint64_t dev = 0;         // device address of its first byte
+  };
+  Recent recent[4];
   for (uint32_t i = 0; i < ndesc; ++i) {
     const ft_desc &d = descs[i];
     Xfer x;
@@ -303,10 +311,28 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
       if (add_overflow(off, ext, &end)) return FT_ERANGE;
       uint64_t addr;
       if (space == FT_POOL) {
-        uint64_t start;
-        if (pool.owner(off, ext, &start) == nullptr) return FT_ERANGE;
-        used.push_back(start);
-        addr = reinterpret_cast<uint64_t>(pool.ptr(off));
+        int hit = -1;
+        for (int k = 0; k < 4; ++k)
+          if (off >= recent[k].lo && off < recent[k].hi && ext <= recent[k].hi - off) {
+            hit = k;
+            break;
+          }
+        if (hit < 0) {
+          uint64_t start;
+          const Allocation *al = pool.owner(off, ext, &start);
+          if (al == nullptr) return FT_ERANGE;
+          used.push_back(start);
+          Recent r;
+          r.lo = start;
+          r.hi = start + al->nslabs * pool.slab_bytes();
+          r.dev = reinterpret_cast<uint64_t>(pool.ptr(start));  // an allocation lies in one segment
+          recent[3] = recent[2];
+          recent[2] = recent[1];
+          recent[1] = recent[0];
+          recent[0] = r;
+          hit = 0;
+        }
+        addr = recent[hit].dev + (off - recent[hit].lo);
       } else if (space == FT_PAGEABLE) {
         // read or written by the library's own threads: only memory the caller has vouched for
         bool inside = false;
