@@ -639,6 +639,7 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
   w.b0 = w.b1 = 0;
   w.x = 0;
   w.stage = 0;
+  w.first = Xfer{};  // an empty ticket is handed on like any other: nothing of it is left unset
   if (t >= T.ntickets) return w;
   if (T.single) {
     // the only run of empty tiles lies behind the last ticket
