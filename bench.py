@@ -177,21 +177,27 @@ def link_peak():
 
 
 def plain_copy_ceiling():
-    """A plain grid-stride copy of 2 GiB: the practical HBM ceiling on this machine (GB/s, read+write)."""
+    """Plain grid-stride kernels on 2 GiB, one workgroup per CU: a copy, reads alone and writes alone (GB/s of
+    traffic). With read rate R and write rate W a copy cannot beat 2 / (1/R + 1/W)."""
     import torch
     from paper_2411_01830_amd import binding as ft
     n = 2 << 30
     a = torch.empty(n, dtype=torch.uint8, device="cuda:0")
     b = torch.empty(n, dtype=torch.uint8, device="cuda:0")
     st = torch.cuda.current_stream().cuda_stream
-    best = 0.0
+    legs = {"copy": (lambda: ft.plain_copy(b.data_ptr(), a.data_ptr(), n, 256, st), 2 * n),
+            "read": (lambda: ft.plain_read(a.data_ptr(), n, 256, st), n),
+            "write": (lambda: ft.plain_fill(b.data_ptr(), n, 0x5A5A5A5A, 256, st), n)}
+    best = {k: 0.0 for k in legs}
     for _ in range(6):
-        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        s.record()
-        ft.plain_copy(b.data_ptr(), a.data_ptr(), n, 256, st)
-        e.record()
-        torch.cuda.synchronize()
-        best = max(best, 2 * n / s.elapsed_time(e) / 1e6)
+        for k, (fn, traffic) in legs.items():
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record()
+            fn()
+            e.record()
+            torch.cuda.synchronize()
+            best[k] = max(best[k], traffic / s.elapsed_time(e) / 1e6)
+    best["copy_bound"] = 2.0 / (1.0 / best["read"] + 1.0 / best["write"])
     return best
 
 
@@ -777,7 +783,10 @@ def main():
             "avg_launch_ms": round(roof_src["cls_ms"][2] / roof_src["cls_launches"][2], 5),
             "launches": roof_src["cls_launches"][2],
             "traffic": None if traffic_factor is None else round(traffic_factor * algo / roof_src["cls_launches"][2]),
-            "plain_copy_ceiling_GBps": round(ceiling, 1),
+            "plain_copy_ceiling_GBps": round(ceiling["copy"], 1),
+            "plain_read_only_GBps": round(ceiling["read"], 1), "plain_write_only_GBps": round(ceiling["write"], 1),
+            "copy_bound_from_those_GBps": round(ceiling["copy_bound"], 1),
+            "frac_of_copy_bound": round(achieved / ceiling["copy_bound"], 4),
         }
     if res["cls_bytes"][0]:
         g = res["cls_bytes"][0] / res["cls_ms"][0] / 1e6

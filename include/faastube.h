@@ -513,6 +513,16 @@ int ft_plan_tickets(const uint64_t *stream_bytes, const uint32_t *weights, uint3
  */
 int ft_plain_copy(void *dst, const void *src, uint64_t bytes, uint32_t workgroups, void *hip_stream);
 
+/*
+ * Calibration: what the memory system gives to reads alone and to writes alone. ft_plain_read
+ * loads `bytes` from src and keeps nothing; ft_plain_fill stores `word` over `bytes` at dst
+ * (device pointers, 16-byte aligned, bytes a multiple of 16; workgroups 0 = 256). A copy moves
+ * every byte once each way, so with read rate R and write rate W it cannot beat
+ * 2 / (1/R + 1/W) bytes of traffic per second: the bound `bench.py` reports beside the peak.
+ */
+int ft_plain_read(const void *src, uint64_t bytes, uint32_t workgroups, void *hip_stream);
+int ft_plain_fill(void *dst, uint64_t bytes, uint32_t word, uint32_t workgroups, void *hip_stream);
+
 const char *ft_strerror(int rc);
 /* Text of the last failing HIP call on this pool ("" if none). */
 const char *ft_last_hip_error(ft_pool *p);

@@ -19,7 +19,7 @@ EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_shrink", "ft_pool_usage", 
            "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_submit_transfers", "ft_submit_merge", "ft_job_reweight", "ft_set_batch",
            "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
            "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
-           "ft_plain_copy", "ft_strerror", "ft_last_hip_error"]
+           "ft_plain_copy", "ft_plain_read", "ft_plain_fill", "ft_strerror", "ft_last_hip_error"]
 
 
 class FtError(Exception):
@@ -102,6 +102,8 @@ def _load():
         "ft_plan_schedule": (i32, [vp, vp, u32, u64, vp, vp, u64, P(u64)]),
         "ft_plan_tickets": (i32, [vp, vp, u32, u64, u64, vp, vp, vp, vp, u64, P(u64)]),
         "ft_plain_copy": (i32, [vp, vp, u64, u32, vp]),
+        "ft_plain_read": (i32, [vp, u64, u32, vp]),
+        "ft_plain_fill": (i32, [vp, u64, u32, u32, vp]),
         "ft_strerror": (C.c_char_p, [i32]),
         "ft_last_hip_error": (C.c_char_p, [vp]),
     }
@@ -445,3 +447,11 @@ def plan_tickets(stream_bytes, weights, chunk_bytes, tile_bytes):
 
 def plain_copy(dst_ptr, src_ptr, nbytes, workgroups=0, stream=0):
     _check(_lib.ft_plain_copy(dst_ptr, src_ptr, nbytes, workgroups, stream))
+
+
+def plain_read(src_ptr, nbytes, workgroups=0, stream=0):
+    _check(_lib.ft_plain_read(src_ptr, nbytes, workgroups, stream))
+
+
+def plain_fill(dst_ptr, nbytes, word, workgroups=0, stream=0):
+    _check(_lib.ft_plain_fill(dst_ptr, nbytes, word, workgroups, stream))

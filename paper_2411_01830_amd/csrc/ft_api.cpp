@@ -1079,6 +1079,20 @@ int ft_plain_copy(void *dst, const void *src, uint64_t bytes, uint32_t workgroup
   return e == hipSuccess ? FT_OK : FT_EHIP;
 }
 
+int ft_plain_read(const void *src, uint64_t bytes, uint32_t workgroups, void *hip_stream) {
+  if (bytes == 0) return FT_OK;
+  if (src == nullptr || bytes % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0) return FT_EINVAL;
+  hipError_t e = launch_plain_read(src, bytes, workgroups, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FT_OK : FT_EHIP;
+}
+
+int ft_plain_fill(void *dst, uint64_t bytes, uint32_t word, uint32_t workgroups, void *hip_stream) {
+  if (bytes == 0) return FT_OK;
+  if (dst == nullptr || bytes % 16 != 0 || reinterpret_cast<uintptr_t>(dst) % 16 != 0) return FT_EINVAL;
+  hipError_t e = launch_plain_fill(dst, bytes, word, workgroups, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FT_OK : FT_EHIP;
+}
+
 const char *ft_strerror(int rc) {
   switch (rc) {
     case FT_OK: return "ok";

@@ -19,5 +19,7 @@ hipError_t launch_decode(const ClassTable &T, uint32_t *func_out, uint32_t *chun
                          hipStream_t stream, const InlineBlob *tables = nullptr);
 // Plain grid-stride copy, no tickets and no tables.
 hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, uint32_t workgroups, hipStream_t stream);
+hipError_t launch_plain_read(const void *src, uint64_t bytes, uint32_t workgroups, hipStream_t stream);
+hipError_t launch_plain_fill(void *dst, uint64_t bytes, uint32_t word, uint32_t workgroups, hipStream_t stream);
 
 }  // namespace ft

@@ -909,6 +909,32 @@ __global__ __launch_bounds__(kThreads) void ft_plain_copy_kernel(u32x4 *dst, con
   for (; i < nvec; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// Reads `nvec` vectors and keeps nothing (the store below practically never happens: it only
+// keeps the loads alive), and writes `nvec` vectors of a fixed value: what the memory system
+// gives to reads alone and to writes alone, the two numbers that bound any copy.
+__global__ __launch_bounds__(kThreads) void ft_plain_read_kernel(const u32x4 *src, uint64_t nvec, u32x4 *sink) {
+  constexpr uint32_t kUnroll = 8;
+  const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+  u32x4 acc = {0, 0, 0, 0};
+  uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  for (; i + (kUnroll - 1) * stride < nvec; i += kUnroll * stride) {
+    u32x4 v[kUnroll];
+#pragma unroll
+    for (uint32_t j = 0; j < kUnroll; ++j) v[j] = __builtin_nontemporal_load(src + i + j * stride);
+#pragma unroll
+    for (uint32_t j = 0; j < kUnroll; ++j) acc ^= v[j];
+  }
+  for (; i < nvec; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+  if (sink != nullptr && (acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u && acc.x == 0x7f4a7c15u) sink[0] = acc;
+}
+
+__global__ __launch_bounds__(kThreads) void ft_plain_fill_kernel(u32x4 *dst, uint64_t nvec, uint32_t word) {
+  const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+  const u32x4 v = {word, word, word, word};
+  for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride)
+    __builtin_nontemporal_store(v, dst + i);
+}
+
 // What a launch passes as tables when the job's own are in device memory.
 static const InlineBlob kNoTables{};
 
@@ -943,6 +969,22 @@ hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, uint32_
   if (workgroups == 0) workgroups = 2048;
   hipLaunchKernelGGL(ft_plain_copy_kernel, dim3(workgroups), dim3(kThreads), 0, stream,
                      static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), bytes >> 4);
+  return hipGetLastError();
+}
+
+hipError_t launch_plain_read(const void *src, uint64_t bytes, uint32_t workgroups, hipStream_t stream) {
+  if (bytes == 0) return hipSuccess;
+  if (workgroups == 0) workgroups = 256;
+  hipLaunchKernelGGL(ft_plain_read_kernel, dim3(workgroups), dim3(kThreads), 0, stream,
+                     static_cast<const u32x4 *>(src), bytes >> 4, static_cast<u32x4 *>(nullptr));
+  return hipGetLastError();
+}
+
+hipError_t launch_plain_fill(void *dst, uint64_t bytes, uint32_t word, uint32_t workgroups, hipStream_t stream) {
+  if (bytes == 0) return hipSuccess;
+  if (workgroups == 0) workgroups = 256;
+  hipLaunchKernelGGL(ft_plain_fill_kernel, dim3(workgroups), dim3(kThreads), 0, stream, static_cast<u32x4 *>(dst),
+                     bytes >> 4, word);
   return hipGetLastError();
 }
 

@@ -287,6 +287,29 @@ def test_plain_copy_kernel_copies(gpu):
         assert torch.equal(b[:n], a) and int(b[n:].sum()) == 0
 
 
+def test_plain_read_and_fill_kernels(gpu):
+    """The two other yardsticks: the fill writes exactly its range, the read changes nothing."""
+    import torch
+    binding, _ = gpu
+    n = (2 << 20) + 16 * 5
+    st = torch.cuda.current_stream().cuda_stream
+    b = torch.full((n + 64,), 7, dtype=torch.uint8, device="cuda:0")
+    for wg in (0, 1, 300):
+        b.fill_(7)
+        binding.plain_fill(b.data_ptr() + 16, n, 0xC3C3C3C3, wg, st)
+        torch.cuda.synchronize()
+        assert int((b[16:16 + n] != 0xC3).sum()) == 0
+        assert int((b[:16] != 7).sum()) == 0 and int((b[16 + n:] != 7).sum()) == 0
+    before = b.clone()
+    binding.plain_read(b.data_ptr(), n, 0, st)
+    binding.plain_read(b.data_ptr(), 16, 64, st)
+    torch.cuda.synchronize()
+    assert torch.equal(b, before)
+    with pytest.raises(binding.FtError) as err:
+        binding.plain_fill(b.data_ptr() + 1, 16, 0, 0, st)
+    assert err.value.code == fmt.FT_EINVAL
+
+
 def test_small_jobs_take_the_launch_argument_path(gpu):
     """Single-class jobs of a few descriptors travel with the launch (tables as a kernel argument,
     one workgroup per ticket, the caller's stream). Same bytes and same order as the oracle for
