@@ -12,7 +12,7 @@
 using namespace ft;
 #define CHECK(c) do { if (!(c)) { std::fprintf(stderr, "FAIL %s line %d seed %llu\n", #c, __LINE__, (unsigned long long)g_seed); std::abort(); } } while (0)
 static uint64_t g_seed;
-static uint64_t n_per = 0, n_notable = 0, n_skips = 0, n_cls = 0, n_tickets = 0;
+static uint64_t n_planted = 0, n_per = 0, n_notable = 0, n_skips = 0, n_cls = 0, n_tickets = 0;
 template <class T> const T &at(const std::vector<T> &v, uint64_t i, int line) {
   if (i >= v.size()) { std::fprintf(stderr, "OOB read line %d idx %llu size %zu seed %llu\n", line, (unsigned long long)i, v.size(), (unsigned long long)g_seed); std::abort(); }
   return v[i];
@@ -110,11 +110,53 @@ int main(int argc, char **argv) {
       else { x.src_space = FT_POOL; x.src = a + U(0, 15); x.dst_space = FT_POOL; x.dst = b + U(0, 15); }
     }
     if (!ok) continue;
+    // two descriptors whose rows interleave in one allocation: their spans overlap, their rows do not
+    if (r() % 3 == 0) {
+      const uint64_t rb = U(1, 200), rows = U(2, 30);
+      uint64_t a = 0, b = 0;
+      if (pool.alloc(2 * rb * rows + 16, &a) == FT_OK && pool.alloc(2 * rb * rows + 16, &b) == FT_OK) {
+        for (int half = 0; half < 2; ++half) {
+          ft_desc x{};
+          x.func = (uint32_t)U(0, nfunc - 1);
+          x.src_space = x.dst_space = FT_POOL;
+          x.rows = rows; x.row_bytes = rb; x.src_pitch = x.dst_pitch = 2 * rb;
+          x.src = a + half * rb; x.dst = b + half * rb;
+          d.push_back(x);
+        }
+      }
+    }
+    // a planted collision: the new destination lands inside an earlier destination's first row,
+    // or the new source reads an earlier destination
+    int planted = 0;
+    if (r() % 4 == 0) {
+      const ft_desc &victim = d[U(0, d.size() - 1)];
+      if (victim.dst_space == FT_POOL) {
+        ft_desc x{};
+        x.func = (uint32_t)U(0, nfunc - 1);
+        x.rows = 1; x.row_bytes = U(1, 64); x.src_pitch = x.dst_pitch = x.row_bytes;
+        uint64_t a = 0;
+        if (pool.alloc(x.row_bytes + 16, &a) == FT_OK) {
+          x.src_space = x.dst_space = FT_POOL;
+          const uint64_t inside = victim.dst + U(0, victim.row_bytes - 1);
+          if (r() % 2) { x.src = a; x.dst = inside; x.row_bytes = x.src_pitch = x.dst_pitch = 1; planted = 1; }
+          else { x.src = inside; x.dst = a; x.row_bytes = x.src_pitch = x.dst_pitch = 1; planted = 2; }
+          d.push_back(x);
+        }
+      }
+    }
+    const uint32_t ndesc_all = (uint32_t)d.size();
     const uint64_t Cs[] = {16, 48, 4096, 65536, 100000 / 16 * 16, 1u << 20, 2u << 20};
     const uint64_t C = Cs[U(0, 6)];
     SubmitPlan plan;
-    int rc = plan_submit(pool, win, d.data(), ndesc, w.data(), nfunc, C, r() % 2 ? FT_VALIDATE : 0, &plan);
-    if (rc != FT_OK) { std::printf("seed %llu: plan rc %d\n", (unsigned long long)g_seed, rc); continue; }
+    const bool validate = r() % 2;
+    int rc = plan_submit(pool, win, d.data(), ndesc_all, w.data(), nfunc, C, validate ? FT_VALIDATE : 0, &plan);
+    if (planted && validate) {
+      CHECK(rc == FT_EOVERLAP);   // found, wherever it hides among the other descriptors
+      n_planted++;
+      continue;
+    }
+    CHECK(rc == FT_OK);           // nothing else collides: no false alarm either
+    if (planted) continue;        // (unchecked and colliding: the order of the bytes is not defined)
     for (int c = 0; c < FT_NCLASS; ++c) {
       ClassPlan &cp = plan.cls[c];
       if (cp.nchunks == 0) continue;
@@ -130,7 +172,7 @@ int main(int argc, char **argv) {
       walk(cp, C, tile, tpc, skips, nt);
     }
   }
-  std::printf("classes %llu, table per tile %llu, no table %llu, with skips %llu, tickets %llu\n", (unsigned long long)n_cls, (unsigned long long)n_per, (unsigned long long)n_notable, (unsigned long long)n_skips, (unsigned long long)n_tickets);
+  std::printf("planted collisions found %llu; classes %llu, table per tile %llu, no table %llu, with skips %llu, tickets %llu\n", (unsigned long long)n_planted, (unsigned long long)n_cls, (unsigned long long)n_per, (unsigned long long)n_notable, (unsigned long long)n_skips, (unsigned long long)n_tickets);
   std::printf("done %llu..%llu\n", (unsigned long long)first, (unsigned long long)(first + count - 1));
   return 0;
 }
