@@ -29,6 +29,10 @@ def test_bench_prints_one_json_line_with_the_contract_keys():
     assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s"
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-3 and 0.3 < r["frac"] < 1.0
     assert r["traffic"] is None or r["traffic"] >= r["algorithmic_bytes_per_launch"]
+    # no copy beats what reads alone and writes alone leave it, and nothing beats the peak
+    assert r["achieved"] < r["copy_bound_from_those_GBps"] < r["peak"]
+    assert max(r["plain_read_only_GBps"], r["plain_write_only_GBps"]) < r["peak"]
+    assert abs(r["frac_of_copy_bound"] - r["achieved"] / r["copy_bound_from_those_GBps"]) < 1e-3
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
     assert 0.8 < d["host_link"]["frac"] < 1.05
