@@ -169,11 +169,11 @@ Layout inline_layout_of(const ClassPlan &cp) {
 }
 
 void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, ClassTable *T) {
-  std::memcpy(h + lay.phases, cp.phases.data(), cp.phases.size() * sizeof(Phase));
-  std::memcpy(h + lay.slots, cp.slots.data(), cp.slots.size() * sizeof(Slot));
-  std::memcpy(h + lay.funcs, cp.funcs.data(), cp.funcs.size() * sizeof(Func));
-  std::memcpy(h + lay.xfers, cp.xfers.data(), cp.xfers.size() * sizeof(Xfer));
-  std::memcpy(h + lay.chunks, cp.chunk_desc.data(), cp.chunk_desc.size() * sizeof(uint32_t));
+  copy_table(h + lay.phases, cp.phases);
+  copy_table(h + lay.slots, cp.slots);
+  copy_table(h + lay.funcs, cp.funcs);
+  copy_table(h + lay.xfers, cp.xfers);
+  copy_table(h + lay.chunks, cp.chunk_desc);
   const uintptr_t base = reinterpret_cast<uintptr_t>(d);
   T->phases = reinterpret_cast<const Phase *>(base + lay.phases);
   T->slots = reinterpret_cast<const Slot *>(base + lay.slots);
@@ -373,7 +373,7 @@ int prepare_class(ft_pool *p, Job *job, int c, const ClassPlan &cp, const Layout
   const uint64_t ntickets = T.ntickets;  // from shape_classes
   fill_tables(cp, lay, h, d, &T);
   T.ntickets = ntickets;
-  std::memcpy(h + lay.skips, r.skips.data(), r.skips.size() * sizeof(Skip));
+  copy_table(h + lay.skips, r.skips);
   T.nskips = (uint32_t)r.skips.size();
   set_cursor_start(T, cp.phases.data(), (uint32_t)cp.phases.size(), r.skips.data(), T.nskips);
   T.chunk_bytes = chunk_bytes;

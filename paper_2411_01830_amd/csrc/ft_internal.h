@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime_api.h>
 
+#include <cstring>
 #include <memory>
 #include <mutex>
 #include <string>
@@ -151,6 +152,12 @@ int get_pinned(ft_pool *p, uint64_t need, char **out, uint64_t *cap);
 void put_pinned(ft_pool *p, char *ptr, uint64_t cap);
 
 // Byte layout of one class's tables inside a table blob.
+// A table copied to its place in a blob (memcpy must not be handed the null data() of an empty vector).
+template <class T>
+inline void copy_table(char *dst, const std::vector<T> &v) {
+  if (!v.empty()) std::memcpy(dst, v.data(), v.size() * sizeof(T));
+}
+
 struct Layout {
   uint64_t ticket, phases, slots, funcs, xfers, chunks, skips, end;
 };

@@ -404,7 +404,7 @@ int build_generation(ft_pool *p, OpenState *st, int c, hipStream_t user, std::sh
   if (rc != FT_OK) return rc;
   std::memset(g->blob.host, 0, lay.end);
   fill_tables(cp, lay, g->blob.host, g->blob.dev, &g->table);
-  std::memcpy(g->blob.host + lay.skips, g->skips.data(), g->skips.size() * sizeof(Skip));
+  copy_table(g->blob.host + lay.skips, g->skips);
   g->table.nskips = (uint32_t)g->skips.size();
   g->table.chunk_bytes = st->chunk_bytes;
   g->table.tile_bytes = oc.tile_bytes;

@@ -8,8 +8,11 @@
 // The library's host sources can also be compiled with -Xarch_host -fsanitize=address and linked
 // into this program in place of the shared library: the address sanitizer then watches the feeder
 // threads, the table generations and the recycled buffers while the GPU does the real work.
-// Usage: c_abi_stress [rounds]
-#include <hip/hip_runtime.h>
+// With tests/host/hip_stand_in.cpp in place of the HIP runtime and the kernels the same program runs
+// on a machine without a GPU, under the thread sanitizer (tests/test_host_logic.py does that, at a
+// sixteenth of the sizes).
+// Usage: c_abi_stress [rounds] [divide all sizes by]
+#include <hip/hip_runtime_api.h>
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
@@ -21,10 +24,11 @@
 #define OK(c) do { int rc_ = (c); if (rc_ != 0) { std::fprintf(stderr, "FAIL %s -> %d line %d\n", #c, rc_, __LINE__); std::abort(); } } while (0)
 #define HIPOK(c) do { hipError_t e_ = (c); if (e_ != hipSuccess) { std::fprintf(stderr, "HIP FAIL %s -> %s line %d\n", #c, hipGetErrorString(e_), __LINE__); std::abort(); } } while (0)
 
-static const uint64_t MiB = 1ull << 20;
+static uint64_t MiB = 1ull << 20;  // divided by the second argument: "MiB" is then the unit of all sizes
 
 int main(int argc, char **argv) {
   const int rounds = argc > 1 ? atoi(argv[1]) : 6;
+  if (argc > 2 && atoi(argv[2]) > 1) MiB /= (uint64_t)atoi(argv[2]);
   const uint64_t pool_bytes = 1024 * MiB, host_bytes = 512 * MiB;
   char *dev = nullptr, *host = nullptr;
   HIPOK(hipMalloc(&dev, pool_bytes));

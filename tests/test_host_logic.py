@@ -343,7 +343,7 @@ def test_slo_weights_match_the_oracle_rule():
         assert ei.value.code == fmt.FT_EINVAL
 
 
-def _host_sanitizer_run(tmp_path, name, sources, args, expect):
+def _host_sanitizer_run(tmp_path, name, sources, args, expect, sanitize="address,undefined", extra=(), env=None):
     """Build tests/host/<name>.cpp with the given library sources for the host, with sanitizers, and run it."""
     import shutil
     import subprocess
@@ -353,14 +353,15 @@ def _host_sanitizer_run(tmp_path, name, sources, args, expect):
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     csrc = os.path.join(root, "paper_2411_01830_amd", "csrc")
     exe = str(tmp_path / name)
-    cmd = [gxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+    cmd = [gxx, "-std=c++17", "-O1", "-g", "-fsanitize=" + sanitize, "-fno-sanitize-recover=undefined", "-pthread", *extra,
            os.path.join(root, "tests", "host", name + ".cpp"), *[os.path.join(csrc, f) for f in sources], "-o", exe]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0 and "sanitize" in res.stderr:
         cmd = [c for c in cmd if "sanitize" not in c]
         res = subprocess.run(cmd, capture_output=True, text=True)
     assert res.returncode == 0, res.stderr[-2000:]
-    run = subprocess.run([exe, *args], capture_output=True, text=True, timeout=300)
+    env = dict(os.environ, **(env or {}))
+    run = subprocess.run([exe, *args], capture_output=True, text=True, timeout=300, env=env)
     if run.returncode != 0 and "runtime does not come first" in run.stderr:
         # another library is preloaded ahead of the sanitizer's: run the program's own checks alone
         res = subprocess.run([c for c in cmd if "sanitize" not in c], capture_output=True, text=True)
@@ -395,3 +396,29 @@ def test_every_code_has_a_name_and_a_fresh_pool_no_hip_error():
         ft.slab_alloc(pool, 2 << 20)
     assert err.value.code == fmt.FT_ENOMEM and ft.strerror(fmt.FT_ENOMEM) in str(err.value)
     ft.pool_destroy(pool)
+
+
+HOST_SOURCES = ["ft_pool.cpp", "ft_plan.cpp", "ft_api.cpp", "ft_open.cpp", "ft_policy.cpp", "ft_store.cpp", "ft_paths.cpp"]
+
+
+def _with_the_stand_in(tmp_path, sanitize, rounds):
+    """tests/host/c_abi_stress.cpp over the library's host sources, with tests/host/hip_stand_in.cpp in place of
+    the HIP runtime and of the kernels (test infrastructure: the library itself has no CPU path)."""
+    rocm = "/opt/rocm/include"
+    if not os.path.exists(os.path.join(rocm, "hip", "hip_runtime_api.h")):
+        pytest.skip("no HIP headers")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    _host_sanitizer_run(tmp_path, "c_abi_stress", HOST_SOURCES, [str(rounds), "16"], "c_abi_stress done", sanitize=sanitize,
+                        extra=["-D__HIP_PLATFORM_AMD__", "-I" + rocm, "-w", os.path.join(root, "tests", "host", "hip_stand_in.cpp")],
+                        # streams, events, table buffers and parked threads are kept for the life of the process
+                        env={"ASAN_OPTIONS": "detect_leaks=0"})
+
+
+def test_host_threads_race_free_under_the_thread_sanitizer(tmp_path):
+    """An open job that two threads merge into while a third changes its weights and the main thread waits,
+    closed jobs on all launch routes, the store: every byte compared with memcpy's, no data race reported."""
+    _with_the_stand_in(tmp_path, "thread", 6)
+
+
+def test_host_code_clean_under_address_and_ub_sanitizers(tmp_path):
+    _with_the_stand_in(tmp_path, "address,undefined", 6)
