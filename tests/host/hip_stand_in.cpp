@@ -18,6 +18,39 @@
 #include "../../paper_2411_01830_amd/csrc/ft_kernels.h"
 #include "../../paper_2411_01830_amd/csrc/ft_tables.h"
 
+// Failure injection for tests of the error paths: stand_in_fail("hipMemcpyAsync", 3) makes the
+// third call from now of that function fail once (0 clears it). Names: the HIP calls below that
+// say FAIL_POINT, and "launch_copy".
+namespace {
+struct FailPoint {
+  const char *name;
+  std::atomic<int> countdown{0};
+};
+FailPoint g_fail[] = {{"hipMemcpyAsync"}, {"hipEventRecord"}, {"hipStreamWaitEvent"}, {"hipEventCreateWithFlags"},
+                      {"hipMalloc"},      {"hipHostMalloc"},  {"hipEventSynchronize"}, {"launch_copy"}};
+bool fails_now(const char *name) {
+  for (FailPoint &f : g_fail)
+    if (std::strcmp(f.name, name) == 0) {
+      int c = f.countdown.load();
+      while (c > 0 && !f.countdown.compare_exchange_weak(c, c - 1)) {
+      }
+      return c == 1;
+    }
+  return false;
+}
+}  // namespace
+#define FAIL_POINT(name, err) \
+  if (fails_now(name)) return err
+
+extern "C" int stand_in_fail(const char *name, int nth) {
+  for (FailPoint &f : g_fail)
+    if (std::strcmp(f.name, name) == 0) {
+      f.countdown.store(nth);
+      return 0;
+    }
+  return -1;
+}
+
 extern "C" {
 
 hipError_t hipGetDeviceCount(int *count) { *count = 1; return hipSuccess; }
@@ -35,20 +68,45 @@ hipError_t hipStreamCreate(hipStream_t *s) { *s = reinterpret_cast<hipStream_t>(
 hipError_t hipStreamCreateWithFlags(hipStream_t *s, unsigned) { return hipStreamCreate(s); }
 hipError_t hipStreamDestroy(hipStream_t s) { std::free(s); return hipSuccess; }
 hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
-hipError_t hipStreamWaitEvent(hipStream_t, hipEvent_t, unsigned) { return hipSuccess; }
+hipError_t hipStreamWaitEvent(hipStream_t, hipEvent_t, unsigned) {
+  FAIL_POINT("hipStreamWaitEvent", hipErrorUnknown);
+  return hipSuccess;
+}
 
-hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned) { *e = reinterpret_cast<hipEvent_t>(std::malloc(8)); return hipSuccess; }
-hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
-hipError_t hipEventSynchronize(hipEvent_t) { return hipSuccess; }
+hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned) {
+  FAIL_POINT("hipEventCreateWithFlags", hipErrorOutOfMemory);
+  *e = reinterpret_cast<hipEvent_t>(std::malloc(8));
+  return hipSuccess;
+}
+hipError_t hipEventRecord(hipEvent_t, hipStream_t) {
+  FAIL_POINT("hipEventRecord", hipErrorUnknown);
+  return hipSuccess;
+}
+hipError_t hipEventSynchronize(hipEvent_t) {
+  FAIL_POINT("hipEventSynchronize", hipErrorUnknown);
+  return hipSuccess;
+}
 hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t) { *ms = 0.001f; return hipSuccess; }
 
-hipError_t hipMalloc(void **p, size_t n) { *p = std::aligned_alloc(4096, (n + 4095) / 4096 * 4096); return *p ? hipSuccess : hipErrorOutOfMemory; }
-hipError_t hipHostMalloc(void **p, size_t n, unsigned) { return hipMalloc(p, n); }
+hipError_t hipMalloc(void **p, size_t n) {
+  FAIL_POINT("hipMalloc", hipErrorOutOfMemory);
+  *p = std::aligned_alloc(4096, (n + 4095) / 4096 * 4096);
+  return *p ? hipSuccess : hipErrorOutOfMemory;
+}
+hipError_t hipHostMalloc(void **p, size_t n, unsigned) {
+  FAIL_POINT("hipHostMalloc", hipErrorOutOfMemory);
+  *p = std::aligned_alloc(4096, (n + 4095) / 4096 * 4096);
+  return *p ? hipSuccess : hipErrorOutOfMemory;
+}
 hipError_t hipFree(void *p) { std::free(p); return hipSuccess; }
 hipError_t hipHostFree(void *p) { std::free(p); return hipSuccess; }
 hipError_t hipMemset(void *p, int v, size_t n) { std::memset(p, v, n); return hipSuccess; }
 hipError_t hipMemcpy(void *d, const void *s, size_t n, hipMemcpyKind) { std::memcpy(d, s, n); return hipSuccess; }
-hipError_t hipMemcpyAsync(void *d, const void *s, size_t n, hipMemcpyKind, hipStream_t) { std::memcpy(d, s, n); return hipSuccess; }
+hipError_t hipMemcpyAsync(void *d, const void *s, size_t n, hipMemcpyKind, hipStream_t) {
+  FAIL_POINT("hipMemcpyAsync", hipErrorUnknown);
+  std::memcpy(d, s, n);
+  return hipSuccess;
+}
 hipError_t hipMemcpy2DAsync(void *d, size_t dp, const void *s, size_t sp, size_t w, size_t h, hipMemcpyKind, hipStream_t) {
   for (size_t r = 0; r < h; ++r) std::memcpy(static_cast<char *>(d) + r * dp, static_cast<const char *>(s) + r * sp, w);
   return hipSuccess;
@@ -101,6 +159,7 @@ std::atomic<uint64_t> g_clock{1};
 hipError_t launch_copy(const ClassTable &T, int, uint32_t workgroups, hipStream_t, hipEvent_t, hipEvent_t,
                        const InlineBlob *blob) {
   if (workgroups == 0 || (T.inline_tables != 0) != (blob != nullptr)) return hipErrorInvalidValue;
+  FAIL_POINT("launch_copy", hipErrorLaunchFailure);
   const Tables tb = tables_of(T, blob);
   if (T.log)
     for (uint32_t g = 0; g < workgroups; ++g) T.wg_log[g].t_entry = g_clock++;

@@ -401,14 +401,14 @@ def test_every_code_has_a_name_and_a_fresh_pool_no_hip_error():
 HOST_SOURCES = ["ft_pool.cpp", "ft_plan.cpp", "ft_api.cpp", "ft_open.cpp", "ft_policy.cpp", "ft_store.cpp", "ft_paths.cpp"]
 
 
-def _with_the_stand_in(tmp_path, sanitize, rounds):
+def _with_the_stand_in(tmp_path, sanitize, rounds, program="c_abi_stress", args=None, expect="c_abi_stress done"):
     """tests/host/c_abi_stress.cpp over the library's host sources, with tests/host/hip_stand_in.cpp in place of
     the HIP runtime and of the kernels (test infrastructure: the library itself has no CPU path)."""
     rocm = "/opt/rocm/include"
     if not os.path.exists(os.path.join(rocm, "hip", "hip_runtime_api.h")):
         pytest.skip("no HIP headers")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    _host_sanitizer_run(tmp_path, "c_abi_stress", HOST_SOURCES, [str(rounds), "16"], "c_abi_stress done", sanitize=sanitize,
+    _host_sanitizer_run(tmp_path, program, HOST_SOURCES, [str(rounds), "16"] if args is None else args, expect, sanitize=sanitize,
                         extra=["-D__HIP_PLATFORM_AMD__", "-I" + rocm, "-w", os.path.join(root, "tests", "host", "hip_stand_in.cpp")],
                         # streams, events, table buffers and parked threads are kept for the life of the process
                         env={"ASAN_OPTIONS": "detect_leaks=0"})
@@ -422,3 +422,10 @@ def test_host_threads_race_free_under_the_thread_sanitizer(tmp_path):
 
 def test_host_code_clean_under_address_and_ub_sanitizers(tmp_path):
     _with_the_stand_in(tmp_path, "address,undefined", 6)
+
+
+def test_error_paths_with_injected_runtime_failures(tmp_path):
+    """tests/host/fault_paths.cpp: the n-th call of each runtime function (and of the kernel launch) fails in turn
+    while closed jobs, an open job, a merge and a weight change are attempted. Every call returns a code, nothing
+    hangs or stays busy, and the same jobs succeed byte for byte afterwards."""
+    _with_the_stand_in(tmp_path, "address,undefined", 0, program="fault_paths", args=[], expect="fault_paths done")
