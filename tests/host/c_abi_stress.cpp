@@ -1,9 +1,10 @@
 // A consumer of the C ABI without Python: links libfaastube.so, owns its memory through the HIP
 // runtime alone, and drives the engine from several threads at once - an open job (host->pool and
-// pool->pool functions) that two threads merge later jobs into while a third keeps changing its
-// weights, closed jobs of three sizes (tables inside the launch, a recycled counter pair, uploaded
-// tables), then the store. Every transfer is one contiguous piece, so what the pool must hold is
-// what memcpy puts into a host image; the whole pool is compared with it after every round.
+// pool->pool functions, one function from pageable memory and one to it) that two threads merge
+// later jobs into while a third keeps changing its weights, closed jobs of three sizes (tables
+// inside the launch, a recycled counter pair, uploaded tables), then the store. Every transfer is
+// one contiguous piece, so what the pool and the pageable memory must hold is what memcpy puts into
+// host images of them; both are compared whole after every round.
 // Built by paper_2411_01830_amd/build.py (build_native_tests); run by tests/test_gpu_native.py.
 // The library's host sources can also be compiled with -Xarch_host -fsanitize=address and linked
 // into this program in place of the shared library: the address sanitizer then watches the feeder
@@ -37,9 +38,15 @@ int main(int argc, char **argv) {
   for (uint64_t i = 0; i < host_bytes / 2; i += 8) *reinterpret_cast<uint64_t *>(host + i) = r();
   std::vector<char> expect(pool_bytes, 0);
   HIPOK(hipMemset(dev, 0, pool_bytes));
+  // ordinary host memory for the two functions that go through the pinned ring
+  const uint64_t page_bytes = 64 * MiB;
+  std::vector<char> pageable(page_bytes), pageable_expect;
+  for (uint64_t i = 0; i < page_bytes / 2; i += 8) *reinterpret_cast<uint64_t *>(pageable.data() + i) = r();
+  pageable_expect = pageable;
   ft_pool *pool = nullptr;
   OK(ft_pool_create(&pool, dev, pool_bytes, 64 * 1024, 0));
   OK(ft_host_window_add(pool, host, host_bytes));
+  OK(ft_pageable_window_add(pool, pageable.data(), page_bytes));
   hipStream_t stream;
   HIPOK(hipStreamCreate(&stream));
   for (int round = 0; round < rounds; ++round) {
@@ -81,6 +88,29 @@ int main(int argc, char **argv) {
       for (auto &d : extra.d) { d.func += 4; first.d.push_back(d); }
       first.w.insert(first.w.end(), extra.w.begin(), extra.w.end());
       first.offs.insert(first.offs.end(), extra.offs.begin(), extra.offs.end());
+    }
+    {
+      // function 6 comes from pageable memory, function 7 goes to it
+      const uint64_t n = 6 * MiB + r() % MiB;
+      ft_off_t in = 0, out = 0;
+      OK(ft_slab_alloc(pool, n + 32, &in));
+      OK(ft_slab_alloc(pool, n + 32, &out));
+      first.offs.push_back(in);
+      first.offs.push_back(out);
+      const uint64_t from = r() % (page_bytes / 2 - n), to = page_bytes / 2 + r() % 16, fill = r() % (host_bytes / 2 - n);
+      HIPOK(hipMemcpy(dev + out + 3, host + fill, n, hipMemcpyHostToDevice));
+      std::memcpy(expect.data() + out + 3, host + fill, n);
+      ft_desc a{}, b{};
+      a.func = 6; a.src_space = FT_PAGEABLE; a.src = reinterpret_cast<uint64_t>(pageable.data() + from);
+      a.dst_space = FT_POOL; a.dst = in + 7; a.row_bytes = n; a.rows = 1; a.src_pitch = a.dst_pitch = n;
+      std::memcpy(expect.data() + a.dst, pageable.data() + from, n);
+      b.func = 7; b.src_space = FT_POOL; b.src = out + 3;
+      b.dst_space = FT_PAGEABLE; b.dst = reinterpret_cast<uint64_t>(pageable.data() + to); b.row_bytes = n; b.rows = 1; b.src_pitch = b.dst_pitch = n;
+      std::memcpy(pageable_expect.data() + to, host + fill, n);
+      first.d.push_back(a);
+      first.d.push_back(b);
+      first.w.push_back(2);
+      first.w.push_back(3);
     }
     std::vector<J> later;
     for (int i = 0; i < 6; ++i) later.push_back(make(1 + i % 3, 64 * 1024, 3 * MiB, i % 2 == 1));
@@ -133,6 +163,7 @@ int main(int argc, char **argv) {
     std::vector<char> got(pool_bytes);
     HIPOK(hipMemcpy(got.data(), dev, pool_bytes, hipMemcpyDeviceToHost));
     if (std::memcmp(got.data(), expect.data(), pool_bytes) != 0) { std::fprintf(stderr, "bytes differ in round %d\n", round); std::abort(); }
+    if (pageable != pageable_expect) { std::fprintf(stderr, "pageable bytes differ in round %d\n", round); std::abort(); }
     for (ft_off_t o : first.offs) OK(ft_slab_free(pool, o));
     for (J &j : later) for (ft_off_t o : j.offs) OK(ft_slab_free(pool, o));
   }
