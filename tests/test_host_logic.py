@@ -343,7 +343,33 @@ def test_slo_weights_match_the_oracle_rule():
         assert ei.value.code == fmt.FT_EINVAL
 
 
-def _host_sanitizer_run(tmp_path, name, sources, args, expect, sanitize="address,undefined", extra=(), env=None):
+_OBJECTS = {}   # (compiler flags, source) -> object file, shared by the tests of one session
+
+
+def _build_for_host(tmp_path, exe, flags, sources):
+    """Compile the sources (in parallel, each once per set of flags) and link them; returns the compiler's result."""
+    import subprocess
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    cache = _OBJECTS.setdefault("dir", tempfile.mkdtemp(prefix="ft_host_objects_"))
+
+    def compile_one(src):
+        key = (tuple(flags), src)
+        if key not in _OBJECTS:
+            obj = os.path.join(cache, "%d_%s.o" % (abs(hash(key)) % 10 ** 9, os.path.basename(src)))
+            res = subprocess.run([*flags, "-c", src, "-o", obj], capture_output=True, text=True)
+            if res.returncode != 0:
+                return res
+            _OBJECTS[key] = obj
+        return None
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        for res in pool.map(compile_one, sources):
+            if res is not None:
+                return res
+    return subprocess.run([*flags, *[_OBJECTS[(tuple(flags), src)] for src in sources], "-o", exe], capture_output=True, text=True)
+
+
+def _host_sanitizer_run(tmp_path, name, sources, args, expect, sanitize="address,undefined", extra=(), extra_sources=(), env=None):
     """Build tests/host/<name>.cpp with the given library sources for the host, with sanitizers, and run it."""
     import shutil
     import subprocess
@@ -353,18 +379,18 @@ def _host_sanitizer_run(tmp_path, name, sources, args, expect, sanitize="address
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     csrc = os.path.join(root, "paper_2411_01830_amd", "csrc")
     exe = str(tmp_path / name)
-    cmd = [gxx, "-std=c++17", "-O1", "-g", "-fsanitize=" + sanitize, "-fno-sanitize-recover=undefined", "-pthread", *extra,
-           os.path.join(root, "tests", "host", name + ".cpp"), *[os.path.join(csrc, f) for f in sources], "-o", exe]
-    res = subprocess.run(cmd, capture_output=True, text=True)
+    flags = [gxx, "-std=c++17", "-O1", "-g", "-fsanitize=" + sanitize, "-fno-sanitize-recover=undefined", "-pthread", *extra]
+    files = [os.path.join(root, "tests", "host", name + ".cpp"), *extra_sources, *[os.path.join(csrc, f) for f in sources]]
+    res = _build_for_host(tmp_path, exe, flags, files)
+    plain = [c for c in flags if "sanitize" not in c]
     if res.returncode != 0 and "sanitize" in res.stderr:
-        cmd = [c for c in cmd if "sanitize" not in c]
-        res = subprocess.run(cmd, capture_output=True, text=True)
+        res = _build_for_host(tmp_path, exe, plain, files)
     assert res.returncode == 0, res.stderr[-2000:]
     env = dict(os.environ, **(env or {}))
     run = subprocess.run([exe, *args], capture_output=True, text=True, timeout=300, env=env)
     if run.returncode != 0 and "runtime does not come first" in run.stderr:
         # another library is preloaded ahead of the sanitizer's: run the program's own checks alone
-        res = subprocess.run([c for c in cmd if "sanitize" not in c], capture_output=True, text=True)
+        res = _build_for_host(tmp_path, exe, plain, files)
         assert res.returncode == 0, res.stderr[-2000:]
         run = subprocess.run([exe, *args], capture_output=True, text=True, timeout=300)
     assert run.returncode == 0, (run.stdout[-1000:], run.stderr[-3000:])
@@ -409,7 +435,8 @@ def _with_the_stand_in(tmp_path, sanitize, rounds, program="c_abi_stress", args=
         pytest.skip("no HIP headers")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     _host_sanitizer_run(tmp_path, program, HOST_SOURCES, [str(rounds), "16"] if args is None else args, expect, sanitize=sanitize,
-                        extra=["-D__HIP_PLATFORM_AMD__", "-I" + rocm, "-w", os.path.join(root, "tests", "host", "hip_stand_in.cpp")],
+                        extra=["-D__HIP_PLATFORM_AMD__", "-I" + rocm, "-w"],
+                        extra_sources=[os.path.join(root, "tests", "host", "hip_stand_in.cpp")],
                         # streams, events, table buffers and parked threads are kept for the life of the process
                         env={"ASAN_OPTIONS": "detect_leaks=0"})
 
