@@ -456,3 +456,9 @@ def test_error_paths_with_injected_runtime_failures(tmp_path):
     while closed jobs, an open job, a merge and a weight change are attempted. Every call returns a code, nothing
     hangs or stays busy, and the same jobs succeed byte for byte afterwards."""
     _with_the_stand_in(tmp_path, "address,undefined", 0, program="fault_paths", args=[], expect="fault_paths done")
+
+
+def test_rest_of_the_api_under_sanitizers(tmp_path):
+    """tests/host/api_tour.cpp: logs with exactly-sized arrays, the device's order against the host planner's, the
+    piece-by-piece comparison path, tuned launch shapes, pitched pieces in all classes, pool growth and shrinkage."""
+    _with_the_stand_in(tmp_path, "address,undefined", 0, program="api_tour", args=[], expect="api_tour done")
