@@ -434,8 +434,23 @@ def single_transfers():
         return round(ts[len(ts) // 2] * 1e6, 1)
     out = {"unit": "us, median of 25, submit -> wait returns", "sizes": {}}
     hp = host.data_ptr()
+    import numpy as np
+    page = np.zeros(8 << 20, dtype=np.uint8)          # ordinary host memory
+    ft.pageable_window_add(pool, page.ctypes.data, len(page))
+    page_t = torch.from_numpy(page)
     for n in (64 << 10, 1 << 20, 16 << 20, 64 << 20):
         row = {}
+        if n <= len(page):
+            # from pageable memory without an open job: through the job's own pinned buffer
+            dp = make_descs([dict(func=0, src_space=2, dst_space=FT_POOL, src=page.ctypes.data, dst=a, row_bytes=n)])
+
+            def engine_pageable():
+                ft.wait(pool, ft.submit_transfers(pool, dp, [1], 2 << 20, 0, stream))
+
+            def runtime_pageable():
+                buf[:n].copy_(page_t[:n])
+                torch.cuda.current_stream().synchronize()
+            row["pageable_to_pool"] = {"engine": med(engine_pageable), "runtime_copy": med(runtime_pageable)}
         for name, ss, ds, src, dst, tsrc, tdst in (("host_to_pool", FT_HOST, FT_POOL, hp, a, host, buf),
                                                    ("pool_to_host", FT_POOL, FT_HOST, a, hp, buf, host),
                                                    ("pool_to_pool", FT_POOL, FT_POOL, a, b, buf, buf[cap:])):

@@ -37,8 +37,9 @@ enum {
   FT_HOST = 0,     /* pinned host memory the device can address */
   FT_POOL = 1,     /* the pool's logical offset space */
   FT_PAGEABLE = 2  /* ordinary host memory, as the source of a host->pool or the destination of a
-                      pool->host transfer, only in open jobs: it travels through the circular
-                      pinned buffer (Sec. 6.1) */
+                      pool->host transfer. In open jobs it travels through the circular pinned
+                      buffer (Sec. 6.1); a job that is not open may name up to 8 MiB of it, which
+                      go through a pinned buffer of the job's own (see ft_pageable_window_add) */
 };
 
 /* link classes: each has its own chunk schedule and its own kernel */
@@ -190,6 +191,12 @@ int ft_host_window_add(ft_pool *p, void *host_base, uint64_t bytes);
  * threads copy them on to the destinations when the batch is complete; ft_wait returns
  * after that. Slots are reused depth + 1 batches later. Source memory must stay valid
  * and unchanged, destination memory valid, until the job has been waited for.
+ * A job without FT_OPEN takes a shorter way for little data: if its pageable sides add up
+ * to at most 8 MiB (each descriptor rounded up to 16 bytes), ft_submit_transfers copies the
+ * pageable sources into a pinned buffer before it returns (they may change afterwards), the
+ * device writes pageable destinations into that buffer, and ft_wait copies them on before it
+ * returns: only then are they complete, whatever the caller's stream has waited for. More than
+ * 8 MiB without FT_OPEN, or FT_PATH_DMA, is FT_EINVAL.
  */
 int ft_pageable_window_add(ft_pool *p, void *host_base, uint64_t bytes);
 
@@ -226,7 +233,7 @@ int ft_set_stage_threads(ft_pool *p, uint32_t threads);
  * (null pointers with non-zero counts, nfunc == 0, a weight of 0, chunk_bytes not a
  * positive multiple of 16, func >= nfunc, flags != 0, a space other than FT_HOST,
  * FT_POOL or FT_PAGEABLE, neither side in the pool, row_bytes == 0, rows == 0, a pitch <
- * row_bytes with rows > 1; FT_PAGEABLE without FT_OPEN is FT_EINVAL after the range checks),
+ * row_bytes with rows > 1; more than 8 MiB of FT_PAGEABLE without FT_OPEN is FT_EINVAL after the range checks),
  * then FT_ERANGE of every descriptor, then (FT_VALIDATE) FT_EOVERLAP, and last
  * FT_EINVAL if the weights are so large and so unlike that the schedule tables would
  * exceed 2^22 entries. ndesc == 0 is valid.

@@ -301,6 +301,9 @@ void retire(ft_pool *p, Job *job) {
 
 void release_device_side(ft_pool *p, Job *job) {
   put_blob(p, job->tables);
+  put_pinned(p, job->bounce, job->bounce_cap);
+  job->bounce = nullptr;
+  job->unstage.clear();
   for (int c = 0; c < FT_NCLASS; ++c) {
     if (job->run[c].counter_pair >= 0) {
       // the kernel is over (the job was waited for, or its launch failed and the device was
@@ -362,6 +365,55 @@ int fail_submit(ft_pool *p, Job *job, int code) {
   if (job->tables.dev != nullptr) (void)hipDeviceSynchronize();
   release_device_side(p, job);
   return code;
+}
+
+// A closed job may name pageable host memory if that is little (kBounceBytes in all): the
+// sources are copied into a pinned buffer here, before the launch, the destinations are written
+// there by the device and copied on by ft_wait. The descriptors are redirected, rows packed, so
+// everything after this sees an ordinary job on pinned memory - including the route on which a
+// small job travels with its launch. Longer pageable traffic belongs into an open job, whose
+// ring overlaps these copies with the link.
+constexpr uint64_t kBounceBytes = 8ull << 20;
+
+int stage_closed_job(ft_pool *p, Job *job, SubmitPlan &plan) {
+  uint64_t total = 0;
+  for (ClassPlan &cp : plan.cls)
+    for (const Xfer &x : cp.xfers)
+      if (x.staged) total += (x.row_bytes * x.rows + 15) / 16 * 16;
+  if (total > kBounceBytes) return FT_EINVAL;
+  int rc = get_pinned(p, total, &job->bounce, &job->bounce_cap);
+  if (rc != FT_OK) return rc;
+  uint64_t at = 0;
+  std::vector<HostCopy> in;
+  for (ClassPlan &cp : plan.cls)
+    for (Xfer &x : cp.xfers) {
+      if (!x.staged) continue;
+      char *slot = job->bounce + at;
+      at += (x.row_bytes * x.rows + 15) / 16 * 16;
+      for (uint64_t r = 0; r < x.rows; ++r) {
+        if (x.staged & kStagedSrc)
+          in.push_back(HostCopy{slot + r * x.row_bytes, reinterpret_cast<const char *>(x.src + r * x.src_pitch), x.row_bytes});
+        else
+          job->unstage.push_back(HostCopy{reinterpret_cast<char *>(x.dst + r * x.dst_pitch), slot + r * x.row_bytes, x.row_bytes});
+      }
+      if (x.staged & kStagedSrc) {
+        x.src = reinterpret_cast<uint64_t>(slot);
+        x.src_pitch = x.row_bytes;
+      } else {
+        x.dst = reinterpret_cast<uint64_t>(slot);
+        x.dst_pitch = x.row_bytes;
+      }
+      x.staged = 0;
+    }
+  run_host_copies(p, in);
+  return FT_OK;
+}
+
+// What a closed job with pageable destinations still owes once its device work is done.
+void finish_staging(ft_pool *p, Job *job) {
+  if (job->unstage.empty()) return;
+  run_host_copies(p, job->unstage);
+  job->unstage.clear();
 }
 
 // What is the same for both ways of launching: the class's table header once its tables lie at `d`
@@ -588,8 +640,9 @@ int ft_pool_destroy(ft_pool *p) {
       if (job->open) {
         if (open_wait(p, job->open, job->id) != FT_OK) rc = FT_EHIP;
         retire(p, job);
-      } else if (!job->waited && wait_locked(p, job) != FT_OK) {
-        rc = FT_EHIP;
+      } else if (!job->waited) {
+        if (wait_locked(p, job) != FT_OK) rc = FT_EHIP;
+        else finish_staging(p, job);
       }
       release_device_side(p, job);
     }
@@ -651,7 +704,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
   if (rc != FT_OK) return rc;
 
   if ((flags & FT_OPEN) && (flags & (FT_LOG | FT_PATH_DMA))) return FT_EINVAL;
-  if (plan.has_pageable && !(flags & FT_OPEN)) return FT_EINVAL;  // staged batch by batch
+  if (plan.has_pageable && !(flags & FT_OPEN) && (flags & FT_PATH_DMA)) return FT_EINVAL;
   std::unique_ptr<Job> job(new Job());
   job->flags = flags;
   job->keep = (flags & (FT_KEEP | FT_LOG | FT_TIMING)) != 0;
@@ -676,6 +729,10 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
     rc = ensure_device(p);
     if (rc != FT_OK) return rc;
     hipStream_t user = static_cast<hipStream_t>(hip_stream);
+    if (plan.has_pageable) {
+      rc = stage_closed_job(p, job.get(), plan);
+      if (rc != FT_OK) return fail_submit(p, job.get(), rc);
+    }
     shape_classes(p, job.get(), plan, chunk_bytes);
     bool launched = false;
     rc = launch_with_the_launch(p, job.get(), plan, chunk_bytes, flags, user, &launched);
@@ -797,8 +854,10 @@ int ft_wait(ft_pool *p, ft_job_t id) {
     lock.unlock();
     {
       DeviceGuard guard(p->device);
+      hipError_t e = hipSuccess;
       for (int c = 0; c < FT_NCLASS; ++c)
-        if (done[c] != nullptr) (void)hipEventSynchronize(done[c]);  // an error shows again below
+        if (done[c] != nullptr && hipEventSynchronize(done[c]) != hipSuccess) e = hipErrorUnknown;  // shows again below
+      if (e == hipSuccess) finish_staging(p, job);  // (`waiting` keeps the record alive meanwhile)
     }
     lock.lock();
     rc = wait_locked(p, job);  // the events have fired: reads times and logs, retires

@@ -47,6 +47,13 @@ struct ClassRun {
   float device_ms = -1.f;
 };
 
+// One host copy owed after a job's device work: from the job's bounce buffer to pageable memory.
+struct HostCopy {
+  char *dst;
+  const char *src;
+  uint64_t n;
+};
+
 struct Job {
   uint64_t id = 0;
   uint32_t flags = 0;
@@ -61,6 +68,11 @@ struct Job {
   uint32_t nfunc = 0;    // functions the job was submitted with
   double host_submit_us = 0;
   std::shared_ptr<OpenState> open;  // set for a job submitted with FT_OPEN or merged into one
+  // a closed job with pageable host sides: pinned buffer that stands in for them, and what
+  // ft_wait still has to copy out of it once the device is done
+  char *bounce = nullptr;
+  uint64_t bounce_cap = 0;
+  std::vector<HostCopy> unstage;
   uint64_t class_payload[FT_NCLASS] = {0, 0, 0};
   uint64_t class_chunks[FT_NCLASS] = {0, 0, 0};
 };
@@ -179,6 +191,9 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
                 hipStream_t user);
 int open_merge(ft_pool *p, Job *open_job, Job *job, SubmitPlan &plan, const uint32_t *weights,
                hipStream_t user);
+// Host copies between pageable memory and a pinned buffer; large ones are shared out among the
+// parked staging threads (the caller takes part). Takes none of the pool's or the jobs' locks itself.
+void run_host_copies(ft_pool *p, const std::vector<HostCopy> &copies);
 // New weights (one per function of the job) from the first batch of every class not yet
 // triggered; batch_out[FT_NCLASS] receives that batch's number, UINT64_MAX for a class in
 // which nothing of the job is left to trigger.

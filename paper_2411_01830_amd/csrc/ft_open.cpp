@@ -66,11 +66,7 @@ struct Generation {
   bool waited_upload[2] = {false, false};
 };
 
-struct StageCopy {
-  char *dst;
-  const char *src;
-  uint64_t n;
-};
+typedef HostCopy StageCopy;  // {dst, src, n}
 
 // Copy for staging. The bytes are not touched again by this core: they go to the device or
 // to a buffer that the caller reads much later, and a batch is larger than the caches. Stores
@@ -696,6 +692,22 @@ void add_functions(OpenClass &oc, uint64_t job_id, const ClassPlan &cp) {
 }
 
 }  // namespace
+
+void run_host_copies(ft_pool *p, const std::vector<HostCopy> &copies) {
+  uint64_t total = 0;
+  for (const HostCopy &c : copies) total += c.n;
+  if (total < 2 * kStagePiece) {
+    for (const HostCopy &c : copies) stage_copy(c.dst, c.src, c.n);
+    return;
+  }
+  std::vector<StageCopy> pieces;
+  for (const HostCopy &c : copies)
+    for (uint64_t o = 0; o < c.n; o += kStagePiece)
+      pieces.push_back(StageCopy{c.dst + o, c.src + o, std::min(kStagePiece, c.n - o)});
+  std::unique_ptr<StagePool> stagers = get_stagers(p->stage_threads ? p->stage_threads - 1 : 3);
+  stagers->run(pieces);
+  put_stagers(std::move(stagers));
+}
 
 int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights, uint64_t chunk_bytes,
                 hipStream_t user) {

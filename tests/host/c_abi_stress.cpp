@@ -159,6 +159,29 @@ int main(int argc, char **argv) {
       for (ft_off_t o : j.offs) (void)o;
       later.push_back(std::move(j));
     }
+    {
+      // a closed job with a little pageable memory on both sides: through a pinned buffer of its own
+      const uint64_t n = 3 * MiB / 16 + r() % 1000;
+      ft_off_t in = 0, out = 0;
+      OK(ft_slab_alloc(pool, n + 32, &in));
+      OK(ft_slab_alloc(pool, n + 32, &out));
+      first.offs.push_back(in);
+      first.offs.push_back(out);
+      const uint64_t from = r() % (page_bytes / 2 - n), to = page_bytes / 2 + 16 * MiB + r() % 16, fill = r() % (host_bytes / 2 - n);
+      HIPOK(hipMemcpy(dev + out + 1, host + fill, n, hipMemcpyHostToDevice));
+      std::memcpy(expect.data() + out + 1, host + fill, n);
+      ft_desc d2[2] = {};
+      d2[0].func = 0; d2[0].src_space = FT_PAGEABLE; d2[0].src = reinterpret_cast<uint64_t>(pageable.data() + from);
+      d2[0].dst_space = FT_POOL; d2[0].dst = in + 9; d2[0].row_bytes = n; d2[0].rows = 1;
+      d2[1].func = 1; d2[1].src_space = FT_POOL; d2[1].src = out + 1;
+      d2[1].dst_space = FT_PAGEABLE; d2[1].dst = reinterpret_cast<uint64_t>(pageable.data() + to); d2[1].row_bytes = n; d2[1].rows = 1;
+      std::memcpy(expect.data() + in + 9, pageable.data() + from, n);
+      std::memcpy(pageable_expect.data() + to, host + fill, n);
+      const uint32_t w2[2] = {1, 2};
+      ft_job_t id = 0;
+      OK(ft_submit_transfers(pool, d2, 2, w2, 2, 2 * MiB, 0, stream, &id));
+      OK(ft_wait(pool, id));
+    }
     HIPOK(hipDeviceSynchronize());
     std::vector<char> got(pool_bytes);
     HIPOK(hipMemcpy(got.data(), dev, pool_bytes, hipMemcpyDeviceToHost));

@@ -242,9 +242,9 @@ def test_pageable_sources_through_the_ring(gpu, batch, depth, threads):
         orc.wait(orc.submit(d0, [1, 2, 3], C))
         orc.wait(orc.submit(d1, [9], C))
         print(f"pageable batch={batch} depth={depth} threads={threads}", flush=True)
-        # outside an open job the ring does not exist
+        # the comparison path has no way for pageable memory
         with pytest.raises(binding.FtError) as ei:
-            eng.submit(d1, [9], C, 0)
+            eng.submit(d1, [9], C, fmt.FT_PATH_DMA)
         assert ei.value.code == fmt.FT_EINVAL
         j0 = eng.submit(d0, [1, 2, 3], C, fmt.FT_OPEN | fmt.FT_KEEP | fmt.FT_VALIDATE)
         try:
@@ -457,7 +457,7 @@ def test_pageable_destinations_through_the_ring(gpu, batch, depth, threads):
         orc.wait(orc.submit(d1, [9], C))
         print(f"pageable destinations batch={batch} depth={depth} threads={threads}", flush=True)
         with pytest.raises(binding.FtError) as ei:
-            eng.submit(d1, [9], C, 0)                      # outside an open job the ring does not exist
+            eng.submit(d1, [9], C, fmt.FT_PATH_DMA)        # the comparison path has no way for pageable memory
         assert ei.value.code == fmt.FT_EINVAL
         j0 = eng.submit(d0, [1, 2, 3], C, fmt.FT_OPEN | fmt.FT_KEEP | fmt.FT_VALIDATE)
         try:
@@ -855,5 +855,87 @@ def test_pool_destroyed_with_open_jobs_in_flight(gpu):
         assert np.array_equal(eng.pageable_np, orc.pageable_mem), "pageable image differs"
         got = torch.cat([t for t, _ in segments]).cpu().numpy()
         assert np.array_equal(got, orc.pool_mem), "pool image differs"
+    finally:
+        eng.close()
+
+
+def test_closed_jobs_with_little_pageable_memory(gpu):
+    """Without FT_OPEN up to 8 MiB of pageable memory go through a pinned buffer of the job's own: sources are
+    taken when the job is submitted, destinations are complete when ft_wait returns. Small and larger jobs (both
+    launch routes), pitched and plain, both directions mixed with pinned and pool->pool pieces, several jobs in
+    flight at once; more than 8 MiB is refused."""
+    from workloads import FT_PAGEABLE
+    binding, _ = gpu
+    orc, eng, rng = _engines(gpu, 32 * MiB, 128 * MiB, seed=61)
+    pyr = __import__("random").Random(61)
+    try:
+        page = rng.integers(0, 256, 12 * MiB, dtype=np.uint8)
+        for e in (orc, eng):
+            e.pageable_arena(32 * MiB)
+            e.write_pageable(0, page)
+        pdst = [16 * MiB]
+        pending = []
+        for case in range(40):
+            recs = []
+            for _ in range(pyr.choice([1, 1, 2, 4])):
+                kind = pyr.choice(["pg2p", "pg2p", "p2pg", "p2pg", "h2p", "p2p"])
+                rows = pyr.choice([1, 1, 3, 60])
+                rb = pyr.choice([1, 100, 4096, 70001, 900 * KiB]) if rows == 1 else pyr.choice([5, 64, 300, 2000])
+                sp, dp = rb + pyr.choice([0, 0, 8, 100]), rb + pyr.choice([0, 0, 24])
+                es, ed = (rows - 1) * sp + rb, (rows - 1) * dp + rb
+                if kind in ("pg2p", "h2p"):
+                    src, sspace = pyr.randrange(0, 10 * MiB - es), FT_PAGEABLE if kind == "pg2p" else FT_HOST
+                else:
+                    a = orc.slab_alloc(es + 32)
+                    assert eng.slab_alloc(es + 32) == a
+                    fill = rng.integers(0, 256, es + 32, dtype=np.uint8)
+                    orc.write_pool(a, fill)
+                    eng.write_pool(a, fill)
+                    src, sspace = a + pyr.randrange(16), FT_POOL
+                if kind == "p2pg":
+                    dst, dspace = pdst[0] + pyr.randrange(16), FT_PAGEABLE
+                    pdst[0] += (ed + 47) // 16 * 16
+                    assert pdst[0] < 31 * MiB
+                else:
+                    b = orc.slab_alloc(ed + 32)
+                    assert eng.slab_alloc(ed + 32) == b
+                    dst, dspace = b + pyr.randrange(16), FT_POOL
+                recs.append(dict(func=pyr.randrange(2), src_space=sspace, dst_space=dspace, src=src, dst=dst,
+                                 row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp))
+            d = make_descs(recs)
+            w = [pyr.choice([1, 3]), pyr.choice([1, 2])]
+            C = pyr.choice([64 * KiB, 2 * MiB])
+            orc.wait(orc.submit(d, w, C))
+            pending.append(eng.submit(d, w, C, pyr.choice([0, fmt.FT_DETACHED, fmt.FT_VALIDATE])))
+            if len(pending) == 3 or case == 39:
+                # pageable sources were taken at submit: overwriting them now changes nothing
+                for h in pending:
+                    eng.wait(h)
+                pending = []
+                _images_equal(orc, eng)
+                assert np.array_equal(eng.pageable_np, orc.pageable_mem), case
+        print("closed pageable jobs done", flush=True)
+        # sources are free again as soon as the submit has returned
+        n = 300 * KiB
+        a = orc.slab_alloc(n)
+        assert eng.slab_alloc(n) == a
+        d = make_descs([dict(func=0, src_space=FT_PAGEABLE, dst_space=FT_POOL, src=0, dst=a, row_bytes=n)])
+        orc.wait(orc.submit(d, [1], 2 * MiB))
+        h = eng.submit(d, [1], 2 * MiB)
+        eng.pageable_np[:n] ^= 0xFF                        # only on the engine's side
+        eng.wait(h)
+        eng.pageable_np[:n] ^= 0xFF
+        _images_equal(orc, eng)
+        # too much for the buffer: an open job is the way
+        big = 9 * MiB
+        b = orc.slab_alloc(big)
+        assert eng.slab_alloc(big) == b
+        d = make_descs([dict(func=0, src_space=FT_PAGEABLE, dst_space=FT_POOL, src=0, dst=b, row_bytes=big)])
+        with pytest.raises(binding.FtError) as ei:
+            eng.submit(d, [1], 2 * MiB)
+        assert ei.value.code == fmt.FT_EINVAL
+        orc.wait(orc.submit(d, [1], 2 * MiB))
+        eng.wait(eng.submit(d, [1], 2 * MiB, fmt.FT_OPEN))
+        _images_equal(orc, eng)
     finally:
         eng.close()
