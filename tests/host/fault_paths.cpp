@@ -27,6 +27,7 @@ struct World {
   char *dev = nullptr, *host = nullptr;
   uint64_t pool_bytes = 64 * MiB, host_bytes = 32 * MiB;
   std::vector<char> expect;
+  std::vector<char> pageable, pageable_expect;  // ordinary host memory for the jobs that stage
   ft_pool *pool = nullptr;
   std::vector<ft_off_t> allocs;
 };
@@ -100,6 +101,29 @@ static int pass(World &w, bool inject, const char *point, int n) {
                                        256 * KiB, FT_KEEP, nullptr, &id);
     outcome(rj, j, id);
   }
+  // a closed job with pageable memory on both sides (a pinned buffer of its own, copies in ft_wait)
+  {
+    const uint64_t n = 100 * KiB + 7;
+    const ft_off_t in = alloc(w, n + 16), out = alloc(w, n + 16);
+    std::memcpy(w.dev + out, w.host + 12345, n);
+    std::memcpy(w.expect.data() + out, w.dev + out, n);
+    ft_desc d2[2] = {};
+    d2[0].func = 0; d2[0].src_space = FT_PAGEABLE; d2[0].src = reinterpret_cast<uint64_t>(w.pageable.data() + 100);
+    d2[0].dst_space = FT_POOL; d2[0].dst = in + 3; d2[0].row_bytes = n; d2[0].rows = 1;
+    d2[1].func = 0; d2[1].src_space = FT_POOL; d2[1].src = out;
+    d2[1].dst_space = FT_PAGEABLE; d2[1].dst = reinterpret_cast<uint64_t>(w.pageable.data() + 2 * MiB + 5); d2[1].row_bytes = n; d2[1].rows = 1;
+    const uint32_t one = 1;
+    ft_job_t id = 0;
+    const int rj = ft_submit_transfers(w.pool, d2, 2, &one, 1, 64 * KiB, FT_KEEP, nullptr, &id);
+    CHECK(rj <= 0);
+    if (rj == FT_OK) {
+      std::memcpy(w.expect.data() + in + 3, w.pageable.data() + 100, n);
+      std::memcpy(w.pageable_expect.data() + 2 * MiB + 5, w.expect.data() + out, n);
+      to_wait.push_back(id);
+    } else {
+      failures += 1;
+    }
+  }
   // an open job, a merge into it, a change of its weights
   JobSpec open = make_job(w, 3, 2 * MiB, true, 29);
   ft_job_t open_id = 0;
@@ -142,8 +166,10 @@ static int pass(World &w, bool inject, const char *point, int n) {
   CHECK(ft_pool_usage(w.pool, &total, &live) == FT_OK && live == 0);
   if (data_defined) {
     CHECK(std::memcmp(w.dev, w.expect.data(), w.pool_bytes) == 0);
+    CHECK(w.pageable == w.pageable_expect);
   } else {
     std::memcpy(w.expect.data(), w.dev, w.pool_bytes);  // start the next pass from what is there
+    w.pageable_expect = w.pageable;
   }
   return failures;
 }
@@ -157,6 +183,10 @@ int main() {
   w.expect.assign(w.pool_bytes, 0);
   CHECK(ft_pool_create(&w.pool, w.dev, w.pool_bytes, 64 * KiB, 0) == FT_OK);
   CHECK(ft_host_window_add(w.pool, w.host, w.host_bytes) == FT_OK);
+  w.pageable.assign(4 * MiB, 0);
+  for (uint64_t i = 0; i < 1 * MiB; ++i) w.pageable[i] = (char)(i * 40503u >> 7);
+  w.pageable_expect = w.pageable;
+  CHECK(ft_pageable_window_add(w.pool, w.pageable.data(), w.pageable.size()) == FT_OK);
   CHECK(pass(w, false, "-", 0) == 0);  // also creates the per-device resources
   const char *points[] = {"hipMemcpyAsync", "hipEventRecord", "hipStreamWaitEvent", "hipEventCreateWithFlags",
                           "hipMalloc",      "hipHostMalloc",  "hipEventSynchronize", "launch_copy"};
