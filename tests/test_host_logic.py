@@ -393,6 +393,8 @@ def _host_sanitizer_run(tmp_path, name, sources, args, expect, sanitize="address
         res = _build_for_host(tmp_path, exe, plain, files)
         assert res.returncode == 0, res.stderr[-2000:]
         run = subprocess.run([exe, *args], capture_output=True, text=True, timeout=300)
+    if run.returncode != 0 and "unexpected memory mapping" in run.stderr:
+        pytest.skip("the thread sanitizer cannot run under this kernel's address space layout")
     assert run.returncode == 0, (run.stdout[-1000:], run.stderr[-3000:])
     assert expect in run.stdout
 
