@@ -352,25 +352,16 @@ def batched_triggering(peaks):
 
 def reserve_rings():
     """The pinned rings of the `pinned_ring` leg, taken at the start of the process as a long-running server
-    would have them (the library keeps a ring's memory for the life of the process once a job has used it):
-    one small open job from pageable memory and one to it, with that leg's chunk size, batch and depth. Pinned
-    memory that the runtime hands out after other large pinned allocations have come and gone takes device
-    writes at 46 GB/s here, memory taken early at 53-54."""
+    would (ft_reserve_rings; the library keeps a ring's memory for the life of the process). Pinned memory that
+    the runtime hands out after other large pinned allocations have come and gone takes device writes at
+    46 GB/s here, memory taken early at 53-54."""
     import torch
-    from paper_2411_01830_amd import binding as ft, harness
-    from workloads import make_descs
-    n, chunk = 24 << 20, 2 << 20
-    eng = harness.GpuEngine()
-    eng.host_arena(4096)
-    eng.pageable_arena(2 * n, fill=7)
-    eng.pool_create(4 * n, 1 << 20, fill=None)
-    ft.set_batch(eng.pool, 5, 3)
-    a = eng.slab_alloc(n)
-    for d in (dict(func=0, src_space=2, dst_space=1, src=0, dst=a, row_bytes=n),
-              dict(func=0, src_space=1, dst_space=2, src=a, dst=n, row_bytes=n)):
-        eng.wait(eng.submit(make_descs([d]), [1], chunk, ft.FT_OPEN))
-    torch.cuda.synchronize()
-    eng.close()
+    from paper_2411_01830_amd import binding as ft
+    seg = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    pool = ft.pool_create(seg.data_ptr(), seg.numel(), 1 << 20, 0)
+    ft.set_batch(pool, 5, 3)
+    ft.reserve_rings(pool, 2 << 20)
+    ft.pool_destroy(pool)
 
 
 def pinned_ring(peaks):
@@ -389,7 +380,7 @@ def pinned_ring(peaks):
     d = make_descs([dict(func=f, src_space=2, dst_space=1, src=f * per, dst=eng.slab_alloc(per), row_bytes=per)
                     for f in range(nf)])
     out = {"bytes": total, "chunk_bytes": chunk, "batch_chunks": 5, "depth": 3, "ring_MiB": 40,
-           "ring_memory": "taken at the start of the process (reserve_rings)", "ring_GBps": {}}
+           "ring_memory": "taken at the start of the process (ft_reserve_rings)", "ring_GBps": {}}
     for threads in (1, 4, 8):
         ft.set_batch(eng.pool, 5, 3)
         ft.set_stage_threads(eng.pool, threads)

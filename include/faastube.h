@@ -200,6 +200,17 @@ int ft_host_window_add(ft_pool *p, void *host_base, uint64_t bytes);
  */
 int ft_pageable_window_add(ft_pool *p, void *host_base, uint64_t bytes);
 
+/*
+ * Take the pinned memory of the two rings (one per direction of the host link) now, for open
+ * jobs of this chunk size under the current ft_set_batch settings, instead of when the first
+ * job with pageable memory arrives. A ring's memory stays with the device for the life of the
+ * process and serves every later job whose ring fits into it, so this is a call for the start
+ * of a long-running process: pinned memory that the runtime hands out early takes device
+ * writes faster than memory handed out after other large pinned allocations have come and
+ * gone (53 against 46 GB/s towards pageable memory on the machine this was measured on).
+ */
+int ft_reserve_rings(ft_pool *p, uint64_t chunk_bytes);
+
 /* Host threads (>= 1, the feeder included) that fill the ring of open jobs submitted later. */
 int ft_set_stage_threads(ft_pool *p, uint32_t threads);
 

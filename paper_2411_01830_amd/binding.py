@@ -16,7 +16,7 @@ EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_shrink", "ft_pool_usage", 
            "ft_sizer_observe", "ft_sizer_target", "ft_sizer_destroy", "ft_migrate_plan", "ft_links_create",
            "ft_links_select", "ft_links_paths", "ft_links_release", "ft_links_free", "ft_links_destroy",
            "ft_stripe_chunks", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
-           "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_submit_transfers", "ft_submit_merge", "ft_job_reweight", "ft_set_batch",
+           "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_reserve_rings", "ft_submit_transfers", "ft_submit_merge", "ft_job_reweight", "ft_set_batch",
            "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
            "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
            "ft_plain_copy", "ft_plain_read", "ft_plain_fill", "ft_strerror", "ft_last_hip_error"]
@@ -85,6 +85,7 @@ def _load():
         "ft_host_window_add": (i32, [vp, vp, u64]),
         "ft_pageable_window_add": (i32, [vp, vp, u64]),
         "ft_set_stage_threads": (i32, [vp, u32]),
+        "ft_reserve_rings": (i32, [vp, u64]),
         "ft_submit_transfers": (i32, [vp, vp, u32, vp, u32, u64, u32, vp, P(u64)]),
         "ft_submit_merge": (i32, [vp, u64, vp, u32, vp, u32, u32, vp, P(u64)]),
         "ft_job_reweight": (i32, [vp, u64, vp, u32, vp, vp]),
@@ -387,6 +388,10 @@ def job_reweight(pool, job, weights, stream=0):
 
 def pageable_window_add(pool, host_ptr, nbytes):
     _check(_lib.ft_pageable_window_add(pool, host_ptr, nbytes), pool)
+
+
+def reserve_rings(pool, chunk_bytes):
+    _check(_lib.ft_reserve_rings(pool, chunk_bytes), pool)
 
 
 def set_stage_threads(pool, threads):

@@ -816,6 +816,22 @@ int ft_job_reweight(ft_pool *p, ft_job_t id, const uint32_t *weights, uint32_t n
 }
 FT_CATCH_ALL
 
+int ft_reserve_rings(ft_pool *p, uint64_t chunk_bytes) try {
+  if (p == nullptr || chunk_bytes == 0 || chunk_bytes % 16 != 0) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  DeviceGuard guard(p->device);
+  int rc = ensure_device(p);
+  if (rc != FT_OK) return rc;
+  const uint64_t slots = (uint64_t)((p->batch_depth ? p->batch_depth : 3) + 1) * (p->batch_chunks ? p->batch_chunks : 5);
+  char *ring[2] = {nullptr, nullptr};
+  uint64_t cap[2] = {0, 0};
+  // both are taken before either is given back, so that they are two buffers
+  for (int k = 0; k < 2 && rc == FT_OK; ++k) rc = get_pinned(p, slots * chunk_bytes, &ring[k], &cap[k]);
+  for (int k = 0; k < 2; ++k) put_pinned(p, ring[k], cap[k]);
+  return rc;
+}
+FT_CATCH_ALL
+
 int ft_set_stage_threads(ft_pool *p, uint32_t threads) {
   if (p == nullptr || threads == 0 || threads > 64) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);

@@ -915,6 +915,13 @@ def test_closed_jobs_with_little_pageable_memory(gpu):
                 _images_equal(orc, eng)
                 assert np.array_equal(eng.pageable_np, orc.pageable_mem), case
         print("closed pageable jobs done", flush=True)
+        # rings taken ahead of time serve the open jobs that follow (and the call can be repeated)
+        binding.set_batch(eng.pool, 3, 2)
+        binding.reserve_rings(eng.pool, 256 * KiB)
+        binding.reserve_rings(eng.pool, 256 * KiB)
+        with pytest.raises(binding.FtError) as ei:
+            binding.reserve_rings(eng.pool, 100)
+        assert ei.value.code == fmt.FT_EINVAL
         # sources are free again as soon as the submit has returned
         n = 300 * KiB
         a = orc.slab_alloc(n)
