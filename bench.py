@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # workload (FETCH_SIZE and WRITE_SIZE runs, each scaled by a plain copy of known size);
 # see profiles/pmc_hbm_traffic_pool_to_pool_<workload>.md. Workloads without such a run
 # report null.
-TRAFFIC_PER_ALGO_BYTE = {"large_mixed": 1.0125, "feature": 1.0009, "traffic_crops": 1.4110}
+TRAFFIC_PER_ALGO_BYTE = {"large_mixed": 1.0125, "feature": 1.0010, "traffic_crops": 1.4126}
 
 
 def parse_args():
