@@ -55,8 +55,10 @@ enum {
   FT_EOVERLAP = -4, /* with FT_VALIDATE: a destination byte is written twice or also read */
   FT_EBUSY = -5,    /* ft_slab_free of an allocation a not-yet-waited job refers to */
   FT_EHIP = -6,     /* a HIP runtime call failed; ft_last_hip_error() gives its text */
-  FT_ECLOSED = -7   /* ft_submit_merge: the open job has no batch left to trigger on a link
+  FT_ECLOSED = -7,  /* ft_submit_merge: the open job has no batch left to trigger on a link
                        class the new transfers use; submit them as a job of their own */
+  FT_E2BIG = -8     /* ft_submit_static: the schedule tables of one link class exceed the library's
+                       fixed device buffer; use ft_submit_transfers */
 };
 
 /* flags of ft_submit_transfers */
@@ -252,6 +254,29 @@ int ft_set_stage_threads(ft_pool *p, uint32_t threads);
 int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
                         uint32_t nfunc, uint64_t chunk_bytes, uint32_t flags, void *hip_stream,
                         ft_job_t *job_out);
+
+/*
+ * For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc. ft_submit_transfers takes table buffers, events and counters from the
+ * runtime the first times it runs; this variant takes nothing from it, ever: no hipMalloc, no
+ * hipHostMalloc, no event, no stream. The schedule tables and the ticket counter of each link
+ * class lie in one array in device memory that is part of the library itself (64 KiB of tables
+ * plus one 256-byte counter line per link class, 197 376 bytes on every GPU the library runs on,
+ * held until the process ends).
+ *   Arguments as for ft_submit_transfers; flags: 0 or FT_VALIDATE. Sides: FT_HOST and FT_POOL only.
+ *   Same validation, same chunk order, same copy kernel and tile shapes, same bytes afterwards.
+ *   Everything is launched on hip_stream (table pieces travel with small launches, then one copy
+ *   kernel per link class in use, one after the other). There is no job handle and nothing to
+ *   wait for but the stream: the transfers are complete when the work queued on hip_stream by
+ *   this call is. The caller keeps every allocation it names alive until then (no FT_EBUSY
+ *   protects them) and may not have two such calls in flight at once on one GPU unless they are
+ *   on the same stream: every call on a GPU uses that GPU's one array, so calls that overlap race.
+ *   FT_E2BIG, with nothing launched: the tables of some link class do not fit 64 KiB (about 700
+ *   descriptors per class; 64-descriptor jobs such as the feature workload take 8 KiB).
+ *   FT_EINVAL also for other flags and for FT_PAGEABLE sides (their pinned buffer is an allocation).
+ */
+int ft_submit_static(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
+                     uint32_t nfunc, uint64_t chunk_bytes, uint32_t flags, void *hip_stream);
 
 /*
  * Batched transfer triggering (Sec. 6.1). A job submitted with FT_OPEN does not hand its

@@ -11,12 +11,13 @@ FT_NCLASS = 3
 FT_H2P, FT_P2H, FT_P2P = 0, 1, 2
 FT_VALIDATE, FT_LOG, FT_PATH_DMA, FT_TIMING, FT_DETACHED, FT_KEEP, FT_OPEN = 1, 2, 4, 8, 16, 32, 64
 FT_ECLOSED = -7
+FT_E2BIG = -8
 
 EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_shrink", "ft_pool_usage", "ft_sizer_create",
            "ft_sizer_observe", "ft_sizer_target", "ft_sizer_destroy", "ft_migrate_plan", "ft_links_create",
            "ft_links_select", "ft_links_paths", "ft_links_release", "ft_links_free", "ft_links_destroy",
            "ft_stripe_chunks", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
-           "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_reserve_rings", "ft_submit_transfers", "ft_submit_merge", "ft_job_reweight", "ft_set_batch",
+           "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_reserve_rings", "ft_submit_transfers", "ft_submit_static", "ft_submit_merge", "ft_job_reweight", "ft_set_batch",
            "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
            "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
            "ft_plain_copy", "ft_plain_read", "ft_plain_fill", "ft_strerror", "ft_last_hip_error"]
@@ -87,6 +88,7 @@ def _load():
         "ft_set_stage_threads": (i32, [vp, u32]),
         "ft_reserve_rings": (i32, [vp, u64]),
         "ft_submit_transfers": (i32, [vp, vp, u32, vp, u32, u64, u32, vp, P(u64)]),
+        "ft_submit_static": (i32, [vp, vp, u32, vp, u32, u64, u32, vp]),
         "ft_submit_merge": (i32, [vp, u64, vp, u32, vp, u32, u32, vp, P(u64)]),
         "ft_job_reweight": (i32, [vp, u64, vp, u32, vp, vp]),
         "ft_set_batch": (i32, [vp, u32, u32]),
@@ -302,6 +304,15 @@ def submit_transfers(pool, descs, weights, chunk_bytes, flags=0, stream=0):
                                     w.ctypes.data if len(w) else None, len(w), chunk_bytes, flags,
                                     stream, C.byref(job)), pool)
     return job.value
+
+
+def submit_static(pool, descs, weights, chunk_bytes, flags=0, stream=0):
+    """ft_submit_static: the submit that allocates nothing; complete when the stream has passed it."""
+    descs = np.ascontiguousarray(descs)
+    assert descs.dtype.itemsize == 64
+    w = np.ascontiguousarray(np.asarray(weights, dtype=np.uint32))
+    _check(_lib.ft_submit_static(pool, descs.ctypes.data if len(descs) else None, len(descs),
+                                 w.ctypes.data if len(w) else None, len(w), chunk_bytes, flags, stream), pool)
 
 
 def wait(pool, job):

@@ -7,7 +7,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfaastube.so")
-SOURCES = ["ft_pool.cpp", "ft_plan.cpp", "ft_api.cpp", "ft_open.cpp", "ft_policy.cpp", "ft_store.cpp", "ft_paths.cpp", "ft_kernels.hip"]
+SOURCES = ["ft_pool.cpp", "ft_plan.cpp", "ft_api.cpp", "ft_open.cpp", "ft_policy.cpp", "ft_store.cpp", "ft_paths.cpp", "ft_kernels.hip", "ft_static.hip"]
 # packed fp32 code generation is switched off for every translation unit
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-result",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -416,21 +416,27 @@ void finish_staging(ft_pool *p, Job *job) {
   job->unstage.clear();
 }
 
-// What is the same for both ways of launching: the class's table header once its tables lie at `d`
-// (or, d = null, travel with the launch), and the events of the class.
+// A class's table header once its tables lie at `d` (or, d = null, travel with the launch), for the
+// tile shape and the runs of empty tiles chosen for it; the tables themselves are copied to `h`.
+void fill_class_table(const ClassPlan &cp, const Layout &lay, char *h, char *d, const std::vector<Skip> &skips,
+                      uint64_t ntickets, uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t tiles_per_chunk,
+                      ClassTable *T) {
+  fill_tables(cp, lay, h, d, T);
+  T->ntickets = ntickets;
+  copy_table(h + lay.skips, skips);
+  T->nskips = (uint32_t)skips.size();
+  set_cursor_start(*T, cp.phases.data(), (uint32_t)cp.phases.size(), skips.data(), T->nskips);
+  T->chunk_bytes = chunk_bytes;
+  T->tile_bytes = tile_bytes;
+  T->tiles_per_chunk = tiles_per_chunk;
+}
+
+// What is the same for both ways of launching: the class's table header and the events of the class.
 int prepare_class(ft_pool *p, Job *job, int c, const ClassPlan &cp, const Layout &lay, char *h, char *d,
                   uint64_t chunk_bytes, bool timing) {
   ClassRun &r = job->run[c];
-  ClassTable &T = r.table;
-  const uint64_t ntickets = T.ntickets;  // from shape_classes
-  fill_tables(cp, lay, h, d, &T);
-  T.ntickets = ntickets;
-  copy_table(h + lay.skips, r.skips);
-  T.nskips = (uint32_t)r.skips.size();
-  set_cursor_start(T, cp.phases.data(), (uint32_t)cp.phases.size(), r.skips.data(), T.nskips);
-  T.chunk_bytes = chunk_bytes;
-  T.tile_bytes = r.tile_bytes;
-  T.tiles_per_chunk = r.tiles_per_chunk;
+  fill_class_table(cp, lay, h, d, r.skips, r.table.ntickets /* from shape_classes */, chunk_bytes, r.tile_bytes,
+                   r.tiles_per_chunk, &r.table);
   r.used = true;
   int rc = get_event(p, false, &r.ev_done);
   if (rc == FT_OK && timing) rc = get_event(p, true, &r.ev_begin);
@@ -1178,6 +1184,7 @@ const char *ft_strerror(int rc) {
     case FT_EBUSY: return "allocation is in use by a job that has not been waited for";
     case FT_EHIP: return "HIP runtime error";
     case FT_ECLOSED: return "the open job has triggered its last batch";
+    case FT_E2BIG: return "schedule tables exceed the library's fixed device buffer";
     default: return "unknown code";
   }
 }

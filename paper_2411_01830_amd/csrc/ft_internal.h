@@ -180,6 +180,11 @@ Layout layout_of(const ClassPlan &cp, uint64_t base, uint64_t ncounters = 1);
 void fill_tables(const ClassPlan &cp, const Layout &lay, char *h, char *d, ClassTable *T);
 // Layout without a ticket counter, from offset 0: for tables that travel with the launch.
 Layout inline_layout_of(const ClassPlan &cp);
+// fill_tables plus everything of the table header that depends on the tile shape: ticket count,
+// runs of empty tiles (copied to `h` as well), cursor start, chunk and tile sizes.
+void fill_class_table(const ClassPlan &cp, const Layout &lay, char *h, char *d, const std::vector<Skip> &skips,
+                      uint64_t ntickets, uint64_t chunk_bytes, uint64_t tile_bytes, uint32_t tiles_per_chunk,
+                      ClassTable *T);
 
 uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p);
 uint64_t default_tile(int cls, bool with_p2p, bool short_rows);

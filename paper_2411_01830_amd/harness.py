@@ -140,6 +140,15 @@ class GpuEngine:
         return ft.submit_transfers(self.pool, d, weights, int(chunk_bytes),
                                    int(flags) | self.default_flags, s)
 
+    def submit_static(self, descs, weights, chunk_bytes, flags=0, stream=None):
+        """ft_submit_static on the current (or given) stream; complete when that stream is."""
+        d = np.array(descs, copy=True)
+        base = self.host.data_ptr() if self.host is not None else 0
+        d["src"][d["src_space"] == 0] += np.uint64(base)
+        d["dst"][d["dst_space"] == 0] += np.uint64(base)
+        s = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
+        ft.submit_static(self.pool, d, weights, int(chunk_bytes), int(flags), s)
+
     def merge(self, open_job, descs, weights, flags=0, stream=None):
         d = np.array(descs, copy=True)
         base = self.host.data_ptr() if self.host is not None else 0

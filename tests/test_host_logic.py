@@ -413,7 +413,7 @@ def test_policy_and_path_planners_under_sanitizers(tmp_path):
 
 def test_every_code_has_a_name_and_a_fresh_pool_no_hip_error():
     codes = [fmt.FT_OK, fmt.FT_EINVAL, fmt.FT_ENOMEM, fmt.FT_ERANGE, fmt.FT_EOVERLAP, fmt.FT_EBUSY, fmt.FT_EHIP,
-             fmt.FT_ECLOSED]
+             fmt.FT_ECLOSED, fmt.FT_E2BIG]
     names = [ft.strerror(c) for c in codes]
     assert all(names) and len(set(names)) == len(names)
     assert ft.strerror(-99) and ft.strerror(-99) not in names        # an unknown code still gets a text

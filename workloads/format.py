@@ -22,6 +22,7 @@ FT_EOVERLAP = -4
 FT_EBUSY = -5
 FT_EHIP = -6
 FT_ECLOSED = -7
+FT_E2BIG = -8
 
 FT_VALIDATE = 1 << 0   # exact overlap check of the submit
 FT_LOG = 1 << 1        # per-ticket device timestamps
