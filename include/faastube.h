@@ -64,7 +64,8 @@ enum {
 /* flags of ft_submit_transfers */
 enum {
   FT_VALIDATE = 1 << 0, /* exact overlap check, O(rows log rows) on the host */
-  FT_LOG = 1 << 1,      /* the kernel records begin/end device time of every ticket */
+  FT_LOG = 1 << 1,      /* the kernel records, per ticket, begin/end device time and what its
+                           decode of the ticket gave (ft_job_log) */
   FT_PATH_DMA = 1 << 2, /* run the same schedule with hipMemcpyAsync / hipMemcpy2DAsync per
                            chunk piece instead of the copy kernel (comparison path) */
   FT_TIMING = 1 << 3,   /* bracket each class's work with timing events */
@@ -73,7 +74,7 @@ enum {
                            implied by FT_LOG and FT_TIMING */
   FT_OPEN = 1 << 6      /* trigger the chunks in batches and accept ft_submit_merge meanwhile
                            (Sec. 6.1, batched transfer triggering); implies FT_DETACHED; not
-                           with FT_LOG or FT_PATH_DMA */
+                           with FT_PATH_DMA */
 };
 
 /*
@@ -234,7 +235,7 @@ int ft_set_stage_threads(ft_pool *p, uint32_t threads);
  * tags first, equal tags by lower f - i.e. always serve the unfinished function with
  * the smallest (served+1)/weight. Persistent workgroups draw tickets from a device
  * counter in that order; the classes run concurrently on streams of their own.
- * A job of a single link class whose tables fit 3 KiB (not with FT_LOG, FT_PATH_DMA,
+ * A job of a single link class whose tables fit 3 KiB (not with FT_PATH_DMA,
  * FT_OPEN or a tuned workgroup count) is launched on hip_stream itself with its tables
  * as a kernel argument: same result and order, a tenth of the host time. If it has at
  * most one tile per workgroup (256 tiles pool->pool, 64 host->pool, 128 pool->host) it
@@ -254,6 +255,24 @@ int ft_set_stage_threads(ft_pool *p, uint32_t threads);
 int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const uint32_t *weights,
                         uint32_t nfunc, uint64_t chunk_bytes, uint32_t flags, void *hip_stream,
                         ft_job_t *job_out);
+
+/*
+ * Completion (Sec. 8: transfers are asynchronous with function execution, each direction of
+ * the host link and the on-device path on streams of their own). ft_submit_transfers only
+ * queues work; ft_wait blocks until every chunk of the job is visible at its destination
+ * (device memory, and host memory for pool->host). A job can be waited for once; unless it
+ * was submitted with FT_KEEP/FT_LOG/FT_TIMING the handle is dead afterwards. The pool's
+ * lock is not held while the call blocks: other threads may submit, merge and wait for
+ * other jobs of the same pool meanwhile (not destroy the pool).
+ */
+int ft_wait(ft_pool *p, ft_job_t job);
+
+/* Drop the record of a kept job (after ft_wait; FT_EBUSY while a thread is still inside ft_wait for it). */
+int ft_job_release(ft_pool *p, ft_job_t job);
+
+/* Figures of a kept job (Sec. 8: per-direction streams, so per link class); `out` is a host
+ * pointer. device_ms is valid after ft_wait. */
+int ft_job_stats(ft_pool *p, ft_job_t job, ft_job_stats_t *out);
 
 /*
  * For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
@@ -329,6 +348,20 @@ int ft_set_batch(ft_pool *p, uint32_t batch_chunks, uint32_t depth);
  */
 int ft_job_reweight(ft_pool *p, ft_job_t job, const uint32_t *weights, uint32_t nfunc, void *hip_stream,
                     uint64_t *batch_out);
+
+/*
+ * Transfer-rate observation (Sec. 6.1: the rate of each function's data is monitored while it
+ * moves, so that it stays above its least rate). For `job` - an open job or one merged into it,
+ * whether or not it has been waited for, as long as its record is alive (FT_KEEP) - and one link
+ * class: bytes_done[f] (host array of nfunc entries, nfunc as submitted) receives the bytes of
+ * function f's chunks whose batch is complete and in place, *batches_done (may be NULL) the
+ * number of the sequence's batches seen complete on that class. Two calls a known time apart
+ * give every function's rate over that time, at batch grain; a caller that finds a function
+ * below its least rate answers with ft_job_reweight. Thread-safe; never blocks on the device.
+ * FT_EINVAL: not a job of an open sequence, nfunc differs.
+ */
+int ft_job_progress(ft_pool *p, ft_job_t job, int link_class, uint64_t *bytes_done, uint32_t nfunc,
+                    uint64_t *batches_done);
 
 /*
  * Number of batches of `link_class` that the open job had triggered when `job` joined
@@ -476,38 +509,39 @@ int ft_links_destroy(ft_links *l);
 int ft_stripe_chunks(const uint32_t *path_bw, uint32_t npaths, uint64_t nchunks, uint32_t *path_of_chunk);
 
 /*
- * Block until every chunk of the job is visible at its destination (device memory,
- * and host memory for pool->host). A job can be waited for once; unless it was
- * submitted with FT_KEEP/FT_LOG/FT_TIMING the handle is dead afterwards. The pool's
- * lock is not held while the call blocks: other threads may submit, merge and wait for
- * other jobs of the same pool meanwhile (not destroy the pool).
- */
-int ft_wait(ft_pool *p, ft_job_t job);
-
-/* Drop the record of a kept job (after ft_wait; FT_EBUSY while a thread is still inside ft_wait for it). */
-int ft_job_release(ft_pool *p, ft_job_t job);
-
-/* Figures of a kept job; `out` is a host pointer. device_ms is valid after ft_wait. */
-int ft_job_stats(ft_pool *p, ft_job_t job, ft_job_stats_t *out);
-
-/*
- * Test hook: the ticket order the device uses for one class of a kept job. A small
- * kernel decodes every chunk rank with the same tables and device function as the
- * copy kernel and the result is copied back. func_out / chunk_out are host arrays
- * of `cap` entries; *n_out receives the number of chunks N (entries beyond cap are
- * not written).
+ * Test hook: the chunk order of one class of a kept job as a small kernel reads it from the
+ * job's tables on the device: every chunk rank is decoded by binary search over the phases
+ * (decode_rank, the planner's reference decoder), not by the copy kernel's own cursor-based
+ * decode - what that one did ticket by ticket is in the FT_LOG record (ft_job_log).
+ * func_out / chunk_out are host arrays of `cap` entries; *n_out receives the number of
+ * chunks N (entries beyond cap are not written).
  */
 int ft_job_schedule(ft_pool *p, ft_job_t job, int link_class, uint32_t *func_out,
                     uint32_t *chunk_out, uint64_t cap, uint64_t *n_out);
 
 /*
- * FT_LOG: per ticket of one class, after ft_wait: device clock (ns) at claim and at
- * completion, the function, the chunk and the bytes moved. Host arrays of `cap`
- * entries each (any may be NULL); *n_out receives the ticket count.
+ * FT_LOG: per ticket of one class, after ft_wait, as the copy kernel recorded it: device
+ * clock (ns) at claim and at completion, and what the kernel's own decode of the ticket
+ * gave - the function, the chunk of the function's stream, the offset of the tile's first
+ * byte in that stream and the bytes moved (Sec. 6.1: chunks of different functions are
+ * triggered in proportion; this is the order the device really followed). Host arrays of
+ * `cap` entries each (any may be NULL); *n_out receives the ticket count.
  */
 int ft_job_log(ft_pool *p, ft_job_t job, int link_class, uint64_t *t_begin_ns, uint64_t *t_end_ns,
-               uint32_t *func_out, uint32_t *chunk_out, uint32_t *bytes_out, uint64_t cap,
-               uint64_t *n_out);
+               uint32_t *func_out, uint32_t *chunk_out, uint64_t *byte_off_out, uint32_t *bytes_out,
+               uint64_t cap, uint64_t *n_out);
+
+/*
+ * FT_LOG on an open job (ft_job_log then lists every ticket of the whole sequence, merged jobs
+ * included, in the order triggered, func_out being the function's index inside its own job):
+ * per ticket the job it belongs to and the number of the batch that carried it. Both logs are
+ * available once the sequence has run dry on that link class (FT_EBUSY before): wait for the
+ * open job and for every job merged into it first. With them the rate of every function can be
+ * read off after the fact (Sec. 6.1 monitors it to keep each function above its least rate);
+ * ft_job_progress gives the same while the sequence runs, at batch grain.
+ */
+int ft_job_log_jobs(ft_pool *p, ft_job_t open_job, int link_class, uint64_t *job_out, uint32_t *batch_out,
+                    uint64_t cap, uint64_t *n_out);
 
 /*
  * FT_LOG: which workgroup moved each ticket (host array of `cap` entries, may be NULL)

@@ -19,7 +19,7 @@ EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_shrink", "ft_pool_usage", 
            "ft_stripe_chunks", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
            "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_reserve_rings", "ft_submit_transfers", "ft_submit_static", "ft_submit_merge", "ft_job_reweight", "ft_set_batch",
            "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
-           "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
+           "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_jobs", "ft_job_progress", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
            "ft_plain_copy", "ft_plain_read", "ft_plain_fill", "ft_strerror", "ft_last_hip_error"]
 
 
@@ -99,8 +99,10 @@ def _load():
         "ft_job_release": (i32, [vp, u64]),
         "ft_job_stats": (i32, [vp, u64, P(JobStats)]),
         "ft_job_schedule": (i32, [vp, u64, i32, vp, vp, u64, P(u64)]),
-        "ft_job_log": (i32, [vp, u64, i32, vp, vp, vp, vp, vp, u64, P(u64)]),
+        "ft_job_log": (i32, [vp, u64, i32, vp, vp, vp, vp, vp, vp, u64, P(u64)]),
         "ft_job_log_workgroups": (i32, [vp, u64, i32, vp, u64, vp, vp, u32, P(u32)]),
+        "ft_job_log_jobs": (i32, [vp, u64, i32, vp, vp, u64, P(u64)]),
+        "ft_job_progress": (i32, [vp, u64, i32, vp, u32, P(u64)]),
         "ft_set_tuning": (i32, [vp, i32, u32, u64]),
         "ft_plan_schedule": (i32, [vp, vp, u32, u64, vp, vp, u64, P(u64)]),
         "ft_plan_tickets": (i32, [vp, vp, u32, u64, u64, vp, vp, vp, vp, u64, P(u64)]),
@@ -340,16 +342,34 @@ def job_schedule(pool, job, link_class):
 
 
 def job_log(pool, job, link_class):
-    """dict of arrays: t_begin_ns, t_end_ns, func, chunk, bytes - one entry per ticket."""
+    """dict of arrays, one entry per ticket, all of it recorded by the copy kernel: t_begin_ns,
+    t_end_ns, and the kernel's own decode of the ticket: func, chunk, byte_off, bytes."""
     n = C.c_uint64()
-    _check(_lib.ft_job_log(pool, job, link_class, None, None, None, None, None, 0, C.byref(n)), pool)
+    _check(_lib.ft_job_log(pool, job, link_class, None, None, None, None, None, None, 0, C.byref(n)), pool)
     m = max(n.value, 1)
-    tb, te = np.zeros(m, np.uint64), np.zeros(m, np.uint64)
+    tb, te, bo = np.zeros(m, np.uint64), np.zeros(m, np.uint64), np.zeros(m, np.uint64)
     f, k, b = np.zeros(m, np.uint32), np.zeros(m, np.uint32), np.zeros(m, np.uint32)
     _check(_lib.ft_job_log(pool, job, link_class, tb.ctypes.data, te.ctypes.data, f.ctypes.data,
-                           k.ctypes.data, b.ctypes.data, n.value, C.byref(n)), pool)
+                           k.ctypes.data, bo.ctypes.data, b.ctypes.data, n.value, C.byref(n)), pool)
     s = slice(0, n.value)
-    return {"t_begin_ns": tb[s], "t_end_ns": te[s], "func": f[s], "chunk": k[s], "bytes": b[s]}
+    return {"t_begin_ns": tb[s], "t_end_ns": te[s], "func": f[s], "chunk": k[s], "byte_off": bo[s], "bytes": b[s]}
+
+
+def job_log_jobs(pool, open_job, link_class):
+    """FT_LOG on an open job: per ticket of the sequence (parallel to job_log) the job id and the batch."""
+    n = C.c_uint64()
+    _check(_lib.ft_job_log_jobs(pool, open_job, link_class, None, None, 0, C.byref(n)), pool)
+    m = max(n.value, 1)
+    j, b = np.zeros(m, np.uint64), np.zeros(m, np.uint32)
+    _check(_lib.ft_job_log_jobs(pool, open_job, link_class, j.ctypes.data, b.ctypes.data, n.value, C.byref(n)), pool)
+    return {"job": j[:n.value], "batch": b[:n.value]}
+
+
+def job_progress(pool, job, link_class, nfunc):
+    """(bytes complete per function of the job, batches of the sequence complete) on one link class."""
+    done, nb = np.zeros(max(nfunc, 1), np.uint64), C.c_uint64()
+    _check(_lib.ft_job_progress(pool, job, link_class, done.ctypes.data, nfunc, C.byref(nb)), pool)
+    return done[:nfunc].tolist(), nb.value
 
 
 def job_log_workgroups(pool, job, link_class, ntickets):

@@ -457,7 +457,7 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
   int only = -1;
   for (int c = 0; c < FT_NCLASS; ++c)
     if (plan.cls[c].nchunks > 0) only = only == -1 ? c : -2;
-  if (only < 0 || (flags & (FT_PATH_DMA | FT_LOG)) || p->tuning[only].workgroups != 0) return FT_OK;
+  if (only < 0 || (flags & FT_PATH_DMA) || p->tuning[only].workgroups != 0) return FT_OK;
   ClassPlan &cp = plan.cls[only];
   ClassRun &r = job->run[only];
   Layout lay = inline_layout_of(cp);
@@ -501,6 +501,12 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
   }
   r.workgroups = (uint32_t)wg;
   r.on_user_stream = true;
+  if (flags & FT_LOG) {
+    rc = get_blob(p, T.ntickets * sizeof(LogEntry) + wg * sizeof(WgLogEntry), false, &r.log);
+    if (rc != FT_OK) return fail_submit(p, job, rc);
+    T.log = reinterpret_cast<LogEntry *>(r.log.dev);
+    T.wg_log = reinterpret_cast<WgLogEntry *>(r.log.dev + T.ntickets * sizeof(LogEntry));
+  }
   hipError_t e = launch_copy(T, only, r.workgroups, user, r.ev_begin, r.ev_end, job->inline_tables.get());
   if (e == hipSuccess) e = hipEventRecord(r.ev_done, user);
   if (e != hipSuccess) {
@@ -709,7 +715,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
   int rc = plan_submit(p->slabs, p->windows, descs, ndesc, weights, nfunc, chunk_bytes, flags, &plan);
   if (rc != FT_OK) return rc;
 
-  if ((flags & FT_OPEN) && (flags & (FT_LOG | FT_PATH_DMA))) return FT_EINVAL;
+  if ((flags & FT_OPEN) && (flags & FT_PATH_DMA)) return FT_EINVAL;
   if (plan.has_pageable && !(flags & FT_OPEN) && (flags & FT_PATH_DMA)) return FT_EINVAL;
   std::unique_ptr<Job> job(new Job());
   job->flags = flags;
@@ -964,38 +970,49 @@ int ft_job_schedule(ft_pool *p, ft_job_t id, int link_class, uint32_t *func_out,
 FT_CATCH_ALL
 
 int ft_job_log(ft_pool *p, ft_job_t id, int link_class, uint64_t *t_begin_ns, uint64_t *t_end_ns,
-               uint32_t *func_out, uint32_t *chunk_out, uint32_t *bytes_out, uint64_t cap, uint64_t *n_out) try {
+               uint32_t *func_out, uint32_t *chunk_out, uint64_t *byte_off_out, uint32_t *bytes_out, uint64_t cap,
+               uint64_t *n_out) try {
   if (p == nullptr || n_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);
   auto it = p->jobs.find(id);
   if (it == p->jobs.end() || !it->second->waited || it->second->waiting || !(it->second->flags & FT_LOG))
     return FT_EINVAL;
   const Job *job = it->second.get();
+  const double ns_per_tick = p->ctx->clock_khz > 0 ? 1.0e6 / p->ctx->clock_khz : 10.0;
+  if (job->open) {
+    if (!(job->flags & FT_OPEN)) return FT_EINVAL;  // the log belongs to the sequence: ask the open job
+    return open_log(job->open, link_class, ns_per_tick, t_begin_ns, t_end_ns, nullptr, func_out, chunk_out,
+                    byte_off_out, bytes_out, nullptr, cap, n_out);
+  }
   const ClassRun &r = job->run[link_class];
   const uint64_t nt = r.log_host.size();
   *n_out = nt;
   const ClassPlan &cp = r.plan;
-  const double ns_per_tick = p->ctx->clock_khz > 0 ? 1.0e6 / p->ctx->clock_khz : 10.0;
   for (uint64_t t = 0; t < nt && t < cap; ++t) {
-    if (t_begin_ns) t_begin_ns[t] = (uint64_t)(r.log_host[t].t_begin * ns_per_tick);
-    if (t_end_ns) t_end_ns[t] = (uint64_t)(r.log_host[t].t_end * ns_per_tick);
-    if (func_out || chunk_out || bytes_out) {
-      const uint64_t v = ticket_to_tile(r.skips.data(), (uint32_t)r.skips.size(), t);
-      const uint64_t rank = v / r.tiles_per_chunk, ti = v % r.tiles_per_chunk;
-      const ChunkId cid = decode_rank(cp.phases.data(), (uint32_t)cp.phases.size(), cp.slots.data(), rank);
-      const Func &fn = cp.funcs[cid.fl];
-      uint64_t lo = ti * r.tile_bytes, hi = lo + r.tile_bytes;
-      if (hi > job->chunk_bytes) hi = job->chunk_bytes;
-      const uint64_t kabs = fn.chunk_base + cid.k;
-      uint64_t b0 = kabs * job->chunk_bytes + lo, b1 = kabs * job->chunk_bytes + hi;
-      if (b1 > fn.stream_bytes) b1 = fn.stream_bytes;
-      if (b0 > b1) b0 = b1;
-      if (func_out) func_out[t] = fn.func;
-      if (chunk_out) chunk_out[t] = (uint32_t)kabs;
-      if (bytes_out) bytes_out[t] = (uint32_t)(b1 - b0);
-    }
+    // everything below is what the copy kernel wrote: its clock, and what its own decode made of
+    // the ticket. The host only names the function (its table index -> the caller's id).
+    const LogEntry &L = r.log_host[t];
+    if (t_begin_ns) t_begin_ns[t] = (uint64_t)(L.t_begin * ns_per_tick);
+    if (t_end_ns) t_end_ns[t] = (uint64_t)(L.t_end * ns_per_tick);
+    if (func_out) func_out[t] = L.fl < cp.funcs.size() ? cp.funcs[L.fl].func : UINT32_MAX;
+    if (chunk_out) chunk_out[t] = (uint32_t)L.k;
+    if (byte_off_out) byte_off_out[t] = L.b0;
+    if (bytes_out) bytes_out[t] = (uint32_t)(L.b1 - L.b0);
   }
   return FT_OK;
+}
+FT_CATCH_ALL
+
+int ft_job_log_jobs(ft_pool *p, ft_job_t id, int link_class, uint64_t *job_out, uint32_t *batch_out, uint64_t cap,
+                    uint64_t *n_out) try {
+  if (p == nullptr || n_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->waited || it->second->waiting || !it->second->open ||
+      (it->second->flags & (FT_LOG | FT_OPEN)) != (FT_LOG | FT_OPEN))
+    return FT_EINVAL;
+  return open_log(it->second->open, link_class, 1.0, nullptr, nullptr, job_out, nullptr, nullptr, nullptr, nullptr,
+                  batch_out, cap, n_out);
 }
 FT_CATCH_ALL
 
@@ -1006,6 +1023,7 @@ int ft_job_log_workgroups(ft_pool *p, ft_job_t id, int link_class, uint32_t *tic
   auto it = p->jobs.find(id);
   if (it == p->jobs.end() || !it->second->waited || it->second->waiting || !(it->second->flags & FT_LOG))
     return FT_EINVAL;
+  if (it->second->open) return FT_EINVAL;  // an open sequence keeps the per-ticket record only
   const ClassRun &r = it->second->run[link_class];
   const double ns_per_tick = p->ctx->clock_khz > 0 ? 1.0e6 / p->ctx->clock_khz : 10.0;
   if (ticket_wg)
@@ -1024,6 +1042,15 @@ int ft_job_arrival(ft_pool *p, ft_job_t id, int link_class, uint64_t *batch_out)
   auto it = p->jobs.find(id);
   if (it == p->jobs.end() || !it->second->open) return FT_EINVAL;
   return open_arrival(it->second->open, id, link_class, batch_out);
+}
+
+int ft_job_progress(ft_pool *p, ft_job_t id, int link_class, uint64_t *bytes_done, uint32_t nfunc,
+                    uint64_t *batches_done) {
+  if (p == nullptr || bytes_done == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->open || it->second->nfunc != nfunc) return FT_EINVAL;
+  return open_progress(it->second->open, id, link_class, bytes_done, nfunc, batches_done);
 }
 
 int ft_job_batches(ft_pool *p, ft_job_t id, int link_class, uint64_t *job_out, uint32_t *func_out,

@@ -207,6 +207,14 @@ int open_wait(ft_pool *p, const std::shared_ptr<OpenState> &st, uint64_t job_id)
 void open_stats(const std::shared_ptr<OpenState> &st, int c, uint64_t *tickets, uint64_t *tile_bytes,
                 uint32_t *workgroups, float *kernel_ms, uint64_t *batches);
 int open_arrival(const std::shared_ptr<OpenState> &st, uint64_t job_id, int c, uint64_t *batch);
+// Bytes of each of the job's functions (class c) whose batches have been seen complete so far.
+int open_progress(const std::shared_ptr<OpenState> &st, uint64_t job_id, int c, uint64_t *bytes_done, uint32_t nfunc,
+                  uint64_t *batches_done);
+// FT_LOG of an open sequence: every ticket triggered on class c, in trigger order, as the copy kernel
+// recorded it. FT_EBUSY while the class still has batches to trigger or in flight.
+int open_log(const std::shared_ptr<OpenState> &st, int c, double ns_per_tick, uint64_t *t_begin_ns, uint64_t *t_end_ns,
+             uint64_t *job_out, uint32_t *func_out, uint32_t *chunk_out, uint64_t *byte_off_out, uint32_t *bytes_out,
+             uint32_t *batch_out, uint64_t cap, uint64_t *n_out);
 uint64_t open_order(const std::shared_ptr<OpenState> &st, int c, uint64_t *job_out, uint32_t *func_out,
                     uint32_t *chunk_out, uint32_t *batch_out, uint64_t cap);
 

@@ -571,6 +571,8 @@ __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t ta
 // b0 >= b1) and the descriptor holding b0.
 struct Work {
   uint64_t b0, b1;
+  uint32_t fl;     // the function (index into the class's table) and
+  uint64_t k;      // the chunk of its stream that the tile belongs to: only the log wants them
   uint32_t x;      // index of the descriptor that holds stream byte b0
   uint64_t stage;  // address of stream byte 0 of this function if its chunk's ring slot went on for ever
   Xfer first;      // that descriptor (already pointing into the ring if it is staged)
@@ -637,6 +639,8 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
                                               SkipCursor &sc_v, uint64_t t) {
   Work w;
   w.b0 = w.b1 = 0;
+  w.fl = 0;
+  w.k = 0;
   w.x = 0;
   w.stage = 0;
   w.first = Xfer{};  // an empty ticket is handed on like any other: nothing of it is left unset
@@ -661,6 +665,7 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
     if (b0 >= b1) return w;
     w.b0 = b0;
     w.b1 = b1;
+    w.k = rank;
     return w;
   }
   SkipCursor sc;
@@ -723,11 +728,23 @@ __device__ __forceinline__ Work decode_ticket(const ClassTable &T, const ConstTa
   if (b0 >= b1) return w;
   w.b0 = b0;
   w.b1 = b1;
+  w.fl = fl;
+  w.k = CT.funcs[fl].chunk_base + k;
   w.x = x0 == x1 ? x0 : find_xfer(CT.xfers, x0, x1, b0);
   w.first = read_xfer(CT.xfers, w.x);
   w.stage = T.stage_base + (T.stage_slot0 + (rank - T.stage_rank0)) * T.chunk_bytes - c0;
   into_ring(w.first, w.stage);
   return w;
+}
+
+// FT_LOG: what the decode made of ticket t goes into the ticket's log entry as it is, so that the
+// order the copy kernel really follows can be held against the proportional order of Sec. 6.1.
+__device__ __forceinline__ void log_decoded(const ClassTable &T, uint64_t t, const Work &w) {
+  if (T.log == nullptr || t >= T.ntickets) return;
+  T.log[t].fl = w.fl;
+  T.log[t].k = w.k;
+  T.log[t].b0 = w.b0;
+  T.log[t].b1 = w.b1;
 }
 
 // A decoded ticket on its way from the first wavefront to the others, in LDS.
@@ -816,7 +833,10 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
     // workgroup b starts on ticket b; the counter hands out the tickets from gridDim.x on
     const uint64_t t_first = T.ticket_base + blockIdx.x;
     const Work w = decode_ticket(T, CT, pc, sc, t_first);
-    if (tid == 0) put_work(s_work[0], t_first, w, (uint64_t)kThreads * U * 16);
+    if (tid == 0) {
+      put_work(s_work[0], t_first, w, (uint64_t)kThreads * U * 16);
+      log_decoded(T, t_first, w);
+    }
   }
   __syncthreads();
   uint32_t slot = 0;
@@ -860,7 +880,10 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
       // lane 0 holds the counter's answer; all 64 lanes of this wavefront are enabled
       const uint64_t t_next = T.ticket_base + gridDim.x + uniform64(claimed);
       const Work next = decode_ticket(T, CT, pc, sc, t_next);
-      if (tid == 0) put_work(s_work[slot ^ 1], t_next, next, (uint64_t)kThreads * U * 16);
+      if (tid == 0) {
+        put_work(s_work[slot ^ 1], t_next, next, (uint64_t)kThreads * U * 16);
+        log_decoded(T, t_next, next);
+      }
     }
 
     if (T.log) {

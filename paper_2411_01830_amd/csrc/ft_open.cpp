@@ -50,6 +50,7 @@ struct OpenFn {
   uint64_t nchunks;       // of the whole stream
   uint64_t next_chunk;    // first chunk not yet triggered
   bool staged;            // some descriptor reads or writes pageable host memory
+  uint64_t done_bytes = 0;  // bytes of its chunks whose batch has been seen complete
   std::vector<Xfer> xfers;
 };
 
@@ -64,6 +65,13 @@ struct Generation {
   uint32_t inflight = 0;            // batches launched with these tables and not seen complete
   hipEvent_t uploaded = nullptr;    // each of the class's two streams waits for it before its first batch
   bool waited_upload[2] = {false, false};
+  // FT_LOG: one LogEntry per ticket of this order, then one WgLogEntry per workgroup of every batch
+  Blob log;
+  struct Triggered {
+    uint64_t t0, t1;  // tickets of the batch
+    uint32_t batch;   // its number in the class's sequence
+  };
+  std::vector<Triggered> triggered;
 };
 
 typedef HostCopy StageCopy;  // {dst, src, n}
@@ -108,6 +116,7 @@ struct OpenBatch {
   uint32_t lane = 0;                // which of the class's two streams
   hipEvent_t done = nullptr, t_begin = nullptr, t_end = nullptr;
   std::vector<std::pair<uint64_t, uint64_t>> job_chunks;  // job id, chunks of it in this batch
+  std::vector<std::pair<uint32_t, uint64_t>> fn_bytes;    // function (index into OpenClass::fns), bytes of it in this batch
   std::vector<StageCopy> unstage;   // ring -> pageable destinations, once the batch is complete
 };
 
@@ -290,6 +299,15 @@ struct BatchRec {
   uint32_t batch;
 };
 
+// FT_LOG: one ticket as the copy kernel recorded it, with the job and function (index inside that
+// job) that the function-table index of the kernel's decode stands for.
+struct OpenLogRec {
+  LogEntry e;
+  uint64_t job;
+  uint32_t func;
+  uint32_t batch;
+};
+
 struct OpenClass {
   bool used = false;
   bool closed = false;              // ran dry: no batch left to trigger, feeder gone
@@ -297,6 +315,7 @@ struct OpenClass {
   std::shared_ptr<Generation> gen;  // the order in force
   std::deque<OpenBatch> inflight;
   uint64_t batches_triggered = 0;
+  uint64_t batches_done = 0;        // of them, seen complete (bytes in place)
   // chunks per batch of this class. The paper's batch (5 chunks of 2 MB) is sized for a PCIe
   // link, where it is a fraction of a millisecond; the on-device class moves a chunk about
   // sixty times faster and a launch per 5 chunks would be all launch cost (8 GiB between
@@ -310,6 +329,7 @@ struct OpenClass {
   uint64_t tickets = 0;
   double kernel_ms = 0;
   std::vector<BatchRec> order;
+  std::vector<OpenLogRec> log;      // FT_LOG: tickets of the orders already retired, in trigger order
   // staging ring, present once a function with pageable sources has joined
   char *ring = nullptr;
   uint64_t ring_cap = 0, ring_slots = 0;
@@ -405,9 +425,17 @@ int build_generation(ft_pool *p, OpenState *st, int c, hipStream_t user, std::sh
   g->table.chunk_bytes = st->chunk_bytes;
   g->table.tile_bytes = oc.tile_bytes;
   g->table.tiles_per_chunk = oc.tiles_per_chunk;
+  if (st->flags & FT_LOG) {
+    rc = get_blob(p, g->ntickets * sizeof(LogEntry) + ncounters * oc.workgroups * sizeof(WgLogEntry), false, &g->log);
+    if (rc != FT_OK) {
+      put_blob(p, g->blob);
+      return rc;
+    }
+  }
   rc = get_event(p, false, &g->uploaded);
   if (rc != FT_OK) {
     put_blob(p, g->blob);
+    put_blob(p, g->log);
     return rc;
   }
   hipError_t e = hipMemcpyAsync(g->blob.dev, g->blob.host, lay.end, hipMemcpyHostToDevice, user);
@@ -417,6 +445,7 @@ int build_generation(ft_pool *p, OpenState *st, int c, hipStream_t user, std::sh
     (void)hipStreamSynchronize(user);
     put_event(p, false, g->uploaded);
     put_blob(p, g->blob);
+    put_blob(p, g->log);
     p->hip_error = std::string("open job table upload: ") + hipGetErrorString(e);
     return FT_EHIP;
   }
@@ -427,6 +456,37 @@ int build_generation(ft_pool *p, OpenState *st, int c, hipStream_t user, std::sh
 void drop_generation(ft_pool *p, Generation *g) {
   put_event(p, false, g->uploaded);
   put_blob(p, g->blob);
+  put_blob(p, g->log);
+}
+
+// An order is retired (none of its batches is in flight any more): with FT_LOG, what the copy
+// kernel recorded for the tickets it triggered is taken over first. Called with st->mu held.
+void retire_generation(ft_pool *p, OpenState *st, int c, Generation *g) {
+  OpenClass &oc = st->cls[c];
+  if (g->log.dev != nullptr && !g->triggered.empty()) {
+    const uint64_t t_lo = g->triggered.front().t0, t_hi = g->triggered.back().t1;
+    std::vector<LogEntry> host(t_hi - t_lo);
+    if (hipMemcpy(host.data(), g->log.dev + t_lo * sizeof(LogEntry), host.size() * sizeof(LogEntry),
+                  hipMemcpyDeviceToHost) == hipSuccess) {
+      for (const Generation::Triggered &tr : g->triggered)
+        for (uint64_t t = tr.t0; t < tr.t1; ++t) {
+          OpenLogRec rec;
+          rec.e = host[t - t_lo];
+          rec.batch = tr.batch;
+          const uint32_t fl = rec.e.fl;
+          if (fl < g->plan.funcs.size()) {
+            const OpenFn &fn = oc.fns[g->plan.funcs[fl].func];
+            rec.job = fn.job;
+            rec.func = fn.func;
+          } else {
+            rec.job = 0;
+            rec.func = UINT32_MAX;
+          }
+          oc.log.push_back(rec);
+        }
+    }
+  }
+  drop_generation(p, g);
 }
 
 constexpr uint64_t kStagePiece = 256 * 1024;  // longest single copy handed to a helper
@@ -509,6 +569,11 @@ bool prepare_batch(OpenState *st, int c, Prepared *out) {
   T.stage_base = reinterpret_cast<uint64_t>(oc.ring);
   T.stage_rank0 = r0;
   T.stage_slot0 = slot0;
+  if (g.log.dev != nullptr) {
+    T.log = reinterpret_cast<LogEntry *>(g.log.dev);
+    T.wg_log = reinterpret_cast<WgLogEntry *>(g.log.dev + g.ntickets * sizeof(LogEntry)) +
+               (uint64_t)g.next_counter * oc.workgroups;
+  }
   OpenBatch &b = out->batch;
   b.gen = oc.gen;
   b.lane = (uint32_t)(oc.batches_triggered & 1);
@@ -538,11 +603,18 @@ bool prepare_batch(OpenState *st, int c, Prepared *out) {
     for (auto &jc : b.job_chunks)
       if (jc.first == fn.job) jc.second += 1, found = true;
     if (!found) b.job_chunks.push_back({fn.job, 1});
+    {
+      const uint64_t c0 = k * st->chunk_bytes;
+      const uint64_t n = std::min(st->chunk_bytes, fn.stream_bytes - c0);
+      if (!b.fn_bytes.empty() && b.fn_bytes.back().first == f.func) b.fn_bytes.back().second += n;
+      else b.fn_bytes.push_back({f.func, n});
+    }
     if (st->flags & FT_KEEP) oc.order.push_back(BatchRec{fn.job, fn.func, (uint32_t)k, batch_no});
     if (fn.staged)
       stage_chunk(cp, f, k, st->chunk_bytes, oc.ring + (slot0 + (r - r0)) * st->chunk_bytes, &out->copies,
                   &b.unstage, &oc.staged_bytes);
   }
+  if (g.log.dev != nullptr) g.triggered.push_back(Generation::Triggered{t0, t1, batch_no});
   g.next_rank = r1;
   g.next_counter += 1;
   g.inflight += 1;
@@ -570,6 +642,8 @@ void feeder_main(OpenState *st, int c) {
   std::unique_lock<std::mutex> lock(st->mu);
   // the chunks of a batch are complete: the jobs they belong to are told (lock held)
   auto count_done = [&](const OpenBatch &b) {
+    for (auto &fb : b.fn_bytes) oc.fns[fb.first].done_bytes += fb.second;
+    oc.batches_done += 1;
     for (auto &jc : b.job_chunks) {
       auto it = st->left.find(jc.first);
       if (it != st->left.end()) it->second = it->second > jc.second ? it->second - jc.second : 0;
@@ -625,7 +699,7 @@ void feeder_main(OpenState *st, int c) {
     if (oc.inflight.empty()) {
       // dry (or failed): later arrivals start a sequence of their own
       oc.closed = true;
-      drop_generation(p, oc.gen.get());
+      retire_generation(p, st, c, oc.gen.get());
       // chunks that will never be triggered count as done so that no waiter hangs
       if (st->error != FT_OK) {
         for (auto &kv : st->left) kv.second = 0;
@@ -646,7 +720,7 @@ void feeder_main(OpenState *st, int c) {
     put_event(p, true, b.t_begin);
     put_event(p, true, b.t_end);
     b.gen->inflight -= 1;
-    if (b.gen->inflight == 0 && b.gen != oc.gen) drop_generation(p, b.gen.get());
+    if (b.gen->inflight == 0 && b.gen != oc.gen) retire_generation(p, st, c, b.gen.get());
     if (st->error == FT_OK && !b.unstage.empty()) {
       carry = std::move(b);
       have_carry = true;
@@ -819,7 +893,7 @@ int open_merge(ft_pool *p, Job *open_job, Job *job, SubmitPlan &plan, const uint
     OpenClass &oc = st->cls[pd.c];
     std::shared_ptr<Generation> old = oc.gen;
     oc.gen = pd.gen;
-    if (old->inflight == 0) drop_generation(p, old.get());
+    if (old->inflight == 0) retire_generation(p, st.get(), pd.c, old.get());
     st->arrival[job->id << 2 | (uint64_t)pd.c] = oc.batches_triggered;
   }
   st->left[job->id] = chunks;
@@ -879,7 +953,7 @@ int open_reweight(ft_pool *p, Job *job, const uint32_t *weights, hipStream_t use
     OpenClass &oc = st->cls[pd.c];
     std::shared_ptr<Generation> old = oc.gen;
     oc.gen = pd.gen;
-    if (old->inflight == 0) drop_generation(p, old.get());
+    if (old->inflight == 0) retire_generation(p, st.get(), pd.c, old.get());
     batch_out[pd.c] = oc.batches_triggered;
   }
   return FT_OK;
@@ -914,6 +988,38 @@ int open_arrival(const std::shared_ptr<OpenState> &st, uint64_t job_id, int c, u
   auto it = st->arrival.find(job_id << 2 | (uint64_t)c);
   if (it == st->arrival.end()) return FT_EINVAL;
   *batch = it->second;
+  return FT_OK;
+}
+
+int open_progress(const std::shared_ptr<OpenState> &st, uint64_t job_id, int c, uint64_t *bytes_done, uint32_t nfunc,
+                  uint64_t *batches_done) {
+  std::lock_guard<std::mutex> lock(st->mu);
+  const OpenClass &oc = st->cls[c];
+  for (uint32_t f = 0; f < nfunc; ++f) bytes_done[f] = 0;
+  for (const OpenFn &fn : oc.fns)
+    if (fn.job == job_id && fn.func < nfunc) bytes_done[fn.func] = fn.done_bytes;
+  if (batches_done) *batches_done = oc.batches_done;
+  return FT_OK;
+}
+
+int open_log(const std::shared_ptr<OpenState> &st, int c, double ns_per_tick, uint64_t *t_begin_ns, uint64_t *t_end_ns,
+             uint64_t *job_out, uint32_t *func_out, uint32_t *chunk_out, uint64_t *byte_off_out, uint32_t *bytes_out,
+             uint32_t *batch_out, uint64_t cap, uint64_t *n_out) {
+  std::lock_guard<std::mutex> lock(st->mu);
+  const OpenClass &oc = st->cls[c];
+  if (oc.used && !oc.closed) return FT_EBUSY;  // orders still in force hold their part of the log on the device
+  *n_out = oc.log.size();
+  for (uint64_t t = 0; t < oc.log.size() && t < cap; ++t) {
+    const OpenLogRec &r = oc.log[t];
+    if (t_begin_ns) t_begin_ns[t] = (uint64_t)(r.e.t_begin * ns_per_tick);
+    if (t_end_ns) t_end_ns[t] = (uint64_t)(r.e.t_end * ns_per_tick);
+    if (job_out) job_out[t] = r.job;
+    if (func_out) func_out[t] = r.func;
+    if (chunk_out) chunk_out[t] = (uint32_t)r.e.k;
+    if (byte_off_out) byte_off_out[t] = r.e.b0;
+    if (bytes_out) bytes_out[t] = (uint32_t)(r.e.b1 - r.e.b0);
+    if (batch_out) batch_out[t] = r.batch;
+  }
   return FT_OK;
 }
 

@@ -81,7 +81,11 @@ struct LogEntry {
   uint64_t t_begin;
   uint64_t t_end;
   uint32_t wg;  // workgroup that moved the ticket
-  uint32_t _pad[3];
+  // what the copy kernel's own decode made of the ticket, written by the kernel: index into the
+  // class's function table, chunk of that function's stream, stream bytes [b0, b1) of the tile
+  uint32_t fl;
+  uint64_t k;
+  uint64_t b0, b1;
 };
 
 struct WgLogEntry {

@@ -125,13 +125,15 @@ int main() {
       CHECK(f1 == f2 && k1 == k2);
       if ((flags & FT_LOG) && !(flags & FT_PATH_DMA) && n > 0) {
         uint64_t nt = 0;
-        CHECK(ft_job_log(pool, job, c, nullptr, nullptr, nullptr, nullptr, nullptr, 0, &nt) == FT_OK && nt == st.cls[c].tickets);
+        CHECK(ft_job_log(pool, job, c, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, &nt) == FT_OK && nt == st.cls[c].tickets);
         std::vector<uint64_t> tb(nt), te(nt);
+        std::vector<uint64_t> lo(nt);
         std::vector<uint32_t> lf(nt), lk(nt), lb(nt), wg(nt);
-        CHECK(ft_job_log(pool, job, c, tb.data(), te.data(), lf.data(), lk.data(), lb.data(), nt, &nt) == FT_OK);
+        CHECK(ft_job_log(pool, job, c, tb.data(), te.data(), lf.data(), lk.data(), lo.data(), lb.data(), nt, &nt) == FT_OK);
         uint64_t sum = 0;
         for (uint64_t t = 0; t < nt; ++t) {
           CHECK(te[t] >= tb[t] && lb[t] > 0 && lf[t] < 3);
+          CHECK(lo[t] / C == lk[t] && (lo[t] + lb[t] - 1) / C == lk[t]);  // the tile lies inside its chunk
           sum += lb[t];
         }
         CHECK(sum == st.cls[c].payload_bytes);

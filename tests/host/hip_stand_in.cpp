@@ -165,7 +165,8 @@ hipError_t launch_copy(const ClassTable &T, int, uint32_t workgroups, hipStream_
     for (uint32_t g = 0; g < workgroups; ++g) T.wg_log[g].t_entry = g_clock++;
   for (uint64_t t = T.ticket_base; t < T.ntickets; ++t) {
     uint64_t rank, ti, b0, b1, c0;  // c0: stream offset of the chunk's first byte
-    uint32_t x = 0;
+    uint32_t x = 0, log_fl = 0;
+    uint64_t log_k = 0;
     if (T.single) {
       rank = t / T.tiles_per_chunk;
       ti = t % T.tiles_per_chunk;
@@ -176,6 +177,7 @@ hipError_t launch_copy(const ClassTable &T, int, uint32_t workgroups, hipStream_
       b0 = c0 + lo;
       b1 = c0 + hi;
       if (b1 > stream_bytes) b1 = stream_bytes;
+      log_k = rank;
     } else {
       const uint64_t v = ticket_to_tile(tb.skips, T.nskips, t);
       rank = v / T.tiles_per_chunk;
@@ -194,6 +196,8 @@ hipError_t launch_copy(const ClassTable &T, int, uint32_t workgroups, hipStream_
         x1 = x0 + f.ndesc - 1;
       }
       c0 = (f.chunk_base + id.k) * T.chunk_bytes;
+      log_fl = fl;
+      log_k = f.chunk_base + id.k;
       uint64_t lo = ti * T.tile_bytes, hi = lo + T.tile_bytes;
       if (hi > T.chunk_bytes) hi = T.chunk_bytes;
       b0 = c0 + lo;
@@ -226,6 +230,10 @@ hipError_t launch_copy(const ClassTable &T, int, uint32_t workgroups, hipStream_
       T.log[t].t_begin = begin;
       T.log[t].t_end = g_clock++;
       T.log[t].wg = (uint32_t)((t - T.ticket_base) % workgroups);
+      T.log[t].fl = log_fl;
+      T.log[t].k = log_k;
+      T.log[t].b0 = b0;
+      T.log[t].b1 = b1;
     }
   }
   if (T.log)
