@@ -27,6 +27,8 @@ if ROOT not in sys.path:
 
 import numpy as np
 
+from paper_2411_01830_amd.replay import Replay
+
 METRIC = "aggregate GB/s (host->pool, pool->pool) as % of roofline; weighted-share error"
 HBM_PEAK_GBS = 8000.0
 # HBM bytes the profiler counted per algorithmic byte for the pool->pool kernel, per
@@ -49,98 +51,41 @@ def parse_args():
     return ap.parse_args()
 
 
-class Replay:
-    """A workload made concrete once (memory allocated and filled, descriptors resolved
-    to addresses), then replayed step after step through the C ABI alone."""
-
-    def __init__(self, name, detached):
-        import torch
-        from paper_2411_01830_amd import binding as ft, harness
-        from workloads import configs, runner
-        self.ft = ft
-        self.torch = torch
-        self.name = name
-        self.plan = configs.CONFIGS[name](1.0)
-        self.eng = harness.GpuEngine(0, reuse_memory=True)
-        rec = runner.run_plan(self.plan, self.eng, flags=ft.FT_VALIDATE)     # fills inputs, checks aliasing once
-        torch.cuda.synchronize()
-        self.rec = rec
-        self.segs = list(self.eng._seg_cache)
-        self.host = self.eng.host
-        self.eng.close_pool()
-        base = np.uint64(self.host.data_ptr())
-        self.ops = []
-        for st in self.plan.steps:
-            if st[0] == "alloc":
-                self.ops.append(("alloc", int(st[2]), rec.alloc_off[st[1]]))
-            elif st[0] == "submit":
-                d = rec.descs[st[1]].copy()
-                d["src"][d["src_space"] == 0] += base
-                d["dst"][d["dst_space"] == 0] += base
-                self.ops.append(("submit", st[1], d, np.asarray(st[3], dtype=np.uint32), int(st[4])))
-            elif st[0] == "wait":
-                self.ops.append(("wait", st[1]))
-        self.detached = detached
-        self.payload = self.plan.payload_bytes()
-        self.stream = torch.cuda.current_stream().cuda_stream
-
-    def step(self, flags=0, collect=None, tuning=None):
-        ft = self.ft
-        pool = ft.pool_create(self.segs[0].data_ptr(), self.segs[0].numel(), self.plan.slab_bytes, 0)
-        ft.host_window_add(pool, self.host.data_ptr(), self.host.numel())
-        if tuning:
-            for cls, (wg, tile) in tuning.items():
-                ft.set_tuning(pool, cls, wg, tile)
-        nseg = 1
-        jobs = {}
-        flags |= ft.FT_TIMING | (ft.FT_DETACHED if self.detached else 0)
-        alloc_s = 0.0
-        for op in self.ops:
-            if op[0] == "alloc":
-                t0 = time.perf_counter()
-                while True:
-                    try:
-                        off = ft.slab_alloc(pool, op[1])
-                        break
-                    except ft.FtError as e:
-                        if e.code != -2 or nseg >= len(self.segs):
-                            raise
-                        ft.pool_grow(pool, self.segs[nseg].data_ptr(), self.segs[nseg].numel())
-                        nseg += 1
-                alloc_s += time.perf_counter() - t0
-                if off != op[2]:
-                    raise RuntimeError("allocator is not deterministic")
-            elif op[0] == "submit":
-                jobs[op[1]] = ft.submit_transfers(pool, op[2], op[3], op[4], flags, self.stream)
-            else:
-                ft.wait(pool, jobs[op[1]])
-        out = {}
-        for name, job in jobs.items():
-            out[name] = ft.job_stats(pool, job)
-            if collect is not None:
-                collect(name, pool, job, out[name])
-            ft.job_release(pool, job)
-        ft.pool_destroy(pool)
-        return out, alloc_s
-
-    def close(self):
-        self.eng.close()
+def busy_ms(intervals):
+    """Length of the union of [begin, end] intervals (ms): the time in which at least one of the launches ran."""
+    total, cur_b, cur_e = 0.0, None, None
+    for b, e in sorted(intervals):
+        if cur_e is None or b > cur_e:
+            if cur_e is not None:
+                total += cur_e - cur_b
+            cur_b, cur_e = b, e
+        else:
+            cur_e = max(cur_e, e)
+    if cur_e is not None:
+        total += cur_e - cur_b
+    return total
 
 
 def time_steps(rp, steps, warmup, flags=0):
+    """cls_ms: per link class the sum of the launches' own durations (events bound to each dispatch).
+    cls_busy_ms: the time in which at least one launch of the class was running - the union of the launches'
+    [begin, end] intervals on the device's clock. The two agree unless launches overlap, which those of
+    detached jobs do (two streams per class)."""
     torch = rp.torch
     for _ in range(warmup):
-        rp.step(flags)
+        rp.step(flags, epoch=rp.detached)
     torch.cuda.synchronize()
     cls_ms = [0.0, 0.0, 0.0]
+    cls_busy = [0.0, 0.0, 0.0]
     cls_bytes = [0, 0, 0]
     cls_launches = [0, 0, 0]
     submit_us = 0.0
     alloc_s = 0.0
     t0 = time.perf_counter()
     for _ in range(steps):
-        stats, a = rp.step(flags)
+        stats, a = rp.step(flags, epoch=rp.detached)
         alloc_s += a
+        spans = [[], [], []]
         for st in stats.values():
             submit_us += st.host_submit_us
             for c in range(3):
@@ -148,9 +93,15 @@ def time_steps(rp, steps, warmup, flags=0):
                     cls_ms[c] += st.cls[c].device_ms
                     cls_bytes[c] += st.cls[c].payload_bytes
                     cls_launches[c] += 1
+                    if st.cls[c].end_ms > 0:
+                        spans[c].append((st.cls[c].begin_ms, st.cls[c].end_ms))
+                    else:
+                        spans[c].append((-1e9 - len(spans[c]) * 1e6, -1e9 - len(spans[c]) * 1e6 + st.cls[c].device_ms))
+        for c in range(3):
+            cls_busy[c] += busy_ms(spans[c])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    return {"wall_s": wall, "cls_ms": cls_ms, "cls_bytes": cls_bytes, "cls_launches": cls_launches,
+    return {"wall_s": wall, "cls_ms": cls_ms, "cls_busy_ms": cls_busy, "cls_bytes": cls_bytes, "cls_launches": cls_launches,
             "submit_us_per_step": submit_us / steps, "alloc_us_per_step": alloc_s * 1e6 / steps}
 
 
@@ -611,13 +562,18 @@ def store_on_device():
             store.get(head)
             store.done(head)
             store.advance(1)
-        wall = time.perf_counter() - t0
+        calls = time.perf_counter() - t0        # what the store's calls held the host for
+        store.sync()
+        wall = time.perf_counter() - t0         # until the last move was in place
         st = store.stats()
         store.close()
         ft.pool_destroy(pool)
     out = {"requests": n, "capacity_GiB": 1.0, "stored_GiB": round(float(sizes.sum()) / 2**30, 2),
            "moved_out": st.moved_out, "moved_in": st.moved_in, "stalled_consumers": st.stalls,
-           "GiB_moved": round((st.bytes_out + st.bytes_in) / 2**30, 2), "ms_per_request": round(wall * 1e3 / n, 3),
+           "GiB_moved": round((st.bytes_out + st.bytes_in) / 2**30, 2),
+           "ms_per_request_in_store_calls": round(calls * 1e3 / n, 3), "ms_per_request": round(wall * 1e3 / n, 3),
+           "what": "moves are jobs on the store's stream that put/done do not wait for; get waits for the one "
+                   "result it returns (the consumer here asks right away, so it waits for the moves queued before it)",
            "moves_GBps": round((st.bytes_out + st.bytes_in) / wall / 1e9, 1)}
     return out
 
@@ -726,11 +682,13 @@ def summarize(name, res, steps, rp, peaks):
     for c in range(3):
         if res["cls_bytes"][c] == 0:
             continue
-        gbps = res["cls_bytes"][c] / res["cls_ms"][c] / 1e6
+        gbps = res["cls_bytes"][c] / res["cls_busy_ms"][c] / 1e6          # over the time the class was busy
         entry = {"payload_GBps": round(gbps, 2), "launches": res["cls_launches"][c],
-                 "avg_launch_ms": round(res["cls_ms"][c] / res["cls_launches"][c], 4)}
+                 "avg_launch_ms": round(res["cls_ms"][c] / res["cls_launches"][c], 4),
+                 "busy_ms_per_launch": round(res["cls_busy_ms"][c] / res["cls_launches"][c], 4)}
         if c == 2:
             entry["hbm_frac"] = round(2 * gbps / HBM_PEAK_GBS, 4)
+            entry["hbm_frac_per_dispatch"] = round(2 * res["cls_bytes"][c] / res["cls_ms"][c] / 1e6 / HBM_PEAK_GBS, 4)
             if name == "traffic":
                 sb = sector_bytes(rp)
                 entry["line_granular_bytes_per_payload_byte"] = {
@@ -806,11 +764,17 @@ def main():
     if roof_src is not None and roof_src["cls_bytes"][2]:
         algo = 2.0 * roof_src["cls_bytes"][2]
         traffic_factor = TRAFFIC_PER_ALGO_BYTE.get("traffic_crops" if roof_name == "traffic" else roof_name)
-        achieved = algo / roof_src["cls_ms"][2] / 1e6
+        achieved = algo / roof_src["cls_busy_ms"][2] / 1e6
+        per_dispatch = algo / roof_src["cls_ms"][2] / 1e6
         line["roofline"] = {
             "bound": "hbm", "kernel": "ft_copy_kernel<true, 2> (pool->pool)", "workload": roof_name,
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "time_base": "union of the launches' [begin, end] intervals on the device clock (launches of detached "
+                         "jobs overlap on the class's two streams); per_dispatch_* divide by the sum of the "
+                         "launches' own durations instead",
+            "busy_ms_per_launch": round(roof_src["cls_busy_ms"][2] / roof_src["cls_launches"][2], 5),
+            "per_dispatch_achieved": round(per_dispatch, 1), "per_dispatch_frac": round(per_dispatch / HBM_PEAK_GBS, 4),
             "algorithmic_bytes_per_launch": round(algo / roof_src["cls_launches"][2]),
             "avg_launch_ms": round(roof_src["cls_ms"][2] / roof_src["cls_launches"][2], 5),
             "launches": roof_src["cls_launches"][2],
@@ -821,7 +785,7 @@ def main():
             "frac_of_copy_bound": round(achieved / ceiling["copy_bound"], 4),
         }
     if res["cls_bytes"][0]:
-        g = res["cls_bytes"][0] / res["cls_ms"][0] / 1e6
+        g = res["cls_bytes"][0] / res["cls_busy_ms"][0] / 1e6
         line["host_link"] = {"direction": "host->pool", "achieved": round(g, 2), "peak_measured": round(peaks["h2d"], 2),
                              "unit": "GB/s", "frac": round(g / peaks["h2d"], 4),
                              "peak_is": "best of 5 hipMemcpyAsync of 1 GiB pinned, same run",

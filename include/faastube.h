@@ -111,6 +111,9 @@ typedef struct ft_class_stats {
   uint32_t in_launch;     /* 1: a small job - tables passed with the launch, run on the caller's stream */
   float device_ms;        /* FT_TIMING: duration of the class's kernel (events bound to its dispatch;
                              on the FT_PATH_DMA path: events around its copy calls), else -1 */
+  float begin_ms, end_ms; /* FT_TIMING after ft_timing_epoch: when that kernel began and ended, in ms since
+                             the epoch (launches of detached jobs overlap: the time a class was busy is
+                             the union of these intervals, not the sum of device_ms), else -1 */
   float _pad2;
 } ft_class_stats;
 
@@ -226,7 +229,11 @@ int ft_set_stage_threads(ft_pool *p, uint32_t threads);
  *   (the paper's default is 2 MB).
  *   hip_stream      a hipStream_t (NULL = the null stream). The job starts after all work
  *                   already on that stream; unless FT_DETACHED the stream also waits for
- *                   the job, so two jobs on one stream run in submit order.
+ *                   the job, so two jobs on one stream run in submit order. Nothing orders
+ *                   two FT_DETACHED jobs with respect to each other: their launches of one
+ *                   link class overlap (the head of one fills the compute units that the
+ *                   tail of the other leaves idle); a job that reads what a detached job
+ *                   writes is submitted after ft_wait for that one.
  *
  * Per link class (host->pool, pool->host, pool->pool) and function, the payloads of
  * the function's descriptors in submission order form a byte stream of S_f bytes;
@@ -267,8 +274,19 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
  */
 int ft_wait(ft_pool *p, ft_job_t job);
 
+/* Has everything ft_wait would wait for happened? *done_out (host pointer): 1 or 0. Never blocks;
+ * the job still has to be waited for once (which then returns at once). */
+int ft_job_done(ft_pool *p, ft_job_t job, int *done_out);
+
 /* Drop the record of a kept job (after ft_wait; FT_EBUSY while a thread is still inside ft_wait for it). */
 int ft_job_release(ft_pool *p, ft_job_t job);
+
+/*
+ * Sets the instant from which begin_ms / end_ms of ft_job_stats count, for every pool on this
+ * pool's device: a timing event recorded on hip_stream and waited for. Call it shortly before the
+ * jobs of interest (the times are single-precision milliseconds).
+ */
+int ft_timing_epoch(ft_pool *p, void *hip_stream);
 
 /* Figures of a kept job (Sec. 8: per-direction streams, so per link class); `out` is a host
  * pointer. device_ms is valid after ft_wait. */
@@ -443,16 +461,28 @@ int ft_migrate_plan(const ft_object *objs, uint32_t n, uint64_t capacity, uint64
  *                     first), allocates nbytes from the pool and returns the offset; the
  *                     caller then writes the result there. FT_ENOMEM: nbytes > capacity,
  *                     the spill arena is full, or the pool has no run of free slabs (grow
- *                     it and call again; what has been moved out stays out).
+ *                     it and call again; what has been moved out stays out). FT_EBUSY: the
+ *                     result that would have to leave is still used by a transfer of the
+ *                     caller's that has not been waited for; it stays, nothing is stored.
  *   ft_store_get      the consumer runs now: if the result was moved out, room is made
  *                     and it is brought back first (*was_out = 1, host pointer, may be
- *                     NULL). Returns where it is.
+ *                     NULL). Returns where it is, once it is there: the one call that waits
+ *                     for a move, and only for this result's.
  *   ft_store_done     the consumer has finished (and its transfers have been waited for,
  *                     else FT_EBUSY): the result is dropped, and results that were moved
  *                     out come back while they fit, nearest consumer first.
  *   ft_store_advance  the queue has moved: every queue_pos decreases by `steps` (not below 0).
- * Every move is one pool->host or host->pool job on hip_stream, waited for inside the
- * call. One mutex per store.
+ *   ft_store_sync     waits for every move still in flight (a quiescent point: pool and spill
+ *                     arena now hold what the decisions so far imply).
+ * Migrations run asynchronously with function execution (Sec. 7.2): every move is one
+ * pool->host or host->pool job on hip_stream that put / done / advance do not wait for. The
+ * moves pass that stream one after the other, and a slab that a move out has left is handed
+ * out again at once, in stream order: the caller writes a result into the offset that put
+ * returned with work enqueued on hip_stream (or on a stream that waits for an event recorded on
+ * hip_stream after the call), so that the write follows the move that emptied the slabs. The
+ * same holds for a consumer that reads a result which is still on its way back without having
+ * called ft_store_get for it. Decisions, offsets and bytes are those of carrying out every move
+ * at once; only the time at which the bytes are in place differs. One mutex per store.
  */
 typedef struct ft_store ft_store;
 typedef struct ft_store_stats_t {
@@ -461,6 +491,8 @@ typedef struct ft_store_stats_t {
   uint64_t moved_out, bytes_out;
   uint64_t moved_in, bytes_in;
   uint64_t stalls;         /* ft_store_get calls that had to bring the result back */
+  uint64_t moves_in_flight; /* moves nobody has waited for yet */
+  uint64_t spill_used_bytes; /* of the spill arena, in whole 4096-byte units */
 } ft_store_stats_t;
 int ft_store_create(ft_store **out, ft_pool *pool, void *spill_base, uint64_t spill_bytes, uint64_t capacity,
                     uint64_t chunk_bytes, void *hip_stream);
@@ -468,6 +500,7 @@ int ft_store_put(ft_store *s, uint64_t id, uint64_t nbytes, uint64_t queue_pos, 
 int ft_store_get(ft_store *s, uint64_t id, ft_off_t *off_out, uint32_t *was_out);
 int ft_store_done(ft_store *s, uint64_t id);
 int ft_store_advance(ft_store *s, uint64_t steps);
+int ft_store_sync(ft_store *s);
 int ft_store_stats(ft_store *s, ft_store_stats_t *out);
 int ft_store_destroy(ft_store *s);
 

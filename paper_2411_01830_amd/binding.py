@@ -17,8 +17,8 @@ EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_shrink", "ft_pool_usage", 
            "ft_sizer_observe", "ft_sizer_target", "ft_sizer_destroy", "ft_migrate_plan", "ft_links_create",
            "ft_links_select", "ft_links_paths", "ft_links_release", "ft_links_free", "ft_links_destroy",
            "ft_stripe_chunks", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
-           "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_reserve_rings", "ft_submit_transfers", "ft_submit_static", "ft_submit_merge", "ft_job_reweight", "ft_set_batch",
-           "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_release",
+           "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_sync", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_reserve_rings", "ft_submit_transfers", "ft_submit_static", "ft_submit_merge", "ft_job_reweight", "ft_set_batch",
+           "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_done", "ft_timing_epoch", "ft_job_release",
            "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_jobs", "ft_job_progress", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
            "ft_plain_copy", "ft_plain_read", "ft_plain_fill", "ft_strerror", "ft_last_hip_error"]
 
@@ -32,12 +32,12 @@ class FtError(Exception):
 class ClassStats(C.Structure):
     _fields_ = [("payload_bytes", C.c_uint64), ("chunks", C.c_uint64), ("tickets", C.c_uint64),
                 ("tile_bytes", C.c_uint64), ("workgroups", C.c_uint32), ("in_launch", C.c_uint32),
-                ("device_ms", C.c_float), ("_pad2", C.c_float)]
+                ("device_ms", C.c_float), ("begin_ms", C.c_float), ("end_ms", C.c_float), ("_pad2", C.c_float)]
 
 
 class StoreStats(C.Structure):
     _fields_ = [("objects", C.c_uint64), ("resident_bytes", C.c_uint64), ("moved_out", C.c_uint64),
-                ("bytes_out", C.c_uint64), ("moved_in", C.c_uint64), ("bytes_in", C.c_uint64), ("stalls", C.c_uint64)]
+                ("bytes_out", C.c_uint64), ("moved_in", C.c_uint64), ("bytes_in", C.c_uint64), ("stalls", C.c_uint64), ("moves_in_flight", C.c_uint64), ("spill_used_bytes", C.c_uint64)]
 
 
 class JobStats(C.Structure):
@@ -71,6 +71,7 @@ def _load():
         "ft_store_get": (i32, [vp, u64, C.POINTER(u64), C.POINTER(u32)]),
         "ft_store_done": (i32, [vp, u64]),
         "ft_store_advance": (i32, [vp, u64]),
+        "ft_store_sync": (i32, [vp]),
         "ft_store_stats": (i32, [vp, C.POINTER(StoreStats)]),
         "ft_store_destroy": (i32, [vp]),
         "ft_links_create": (i32, [P(vp), u32, vp, u32]),
@@ -96,6 +97,8 @@ def _load():
         "ft_job_batches": (i32, [vp, u64, i32, vp, vp, vp, vp, u64, P(u64)]),
         "ft_slo_weights": (i32, [vp, vp, vp, u32, C.c_double, u32, vp, vp]),
         "ft_wait": (i32, [vp, u64]),
+        "ft_timing_epoch": (i32, [vp, vp]),
+        "ft_job_done": (i32, [vp, u64, P(i32)]),
         "ft_job_release": (i32, [vp, u64]),
         "ft_job_stats": (i32, [vp, u64, P(JobStats)]),
         "ft_job_schedule": (i32, [vp, u64, i32, vp, vp, u64, P(u64)]),
@@ -218,6 +221,10 @@ class Store:
     def advance(self, steps):
         _check(_lib.ft_store_advance(self._h, steps), self.pool)
 
+    def sync(self):
+        """Wait for every move still in flight (a quiescent point)."""
+        _check(_lib.ft_store_sync(self._h), self.pool)
+
     def stats(self):
         st = StoreStats()
         _check(_lib.ft_store_stats(self._h, C.byref(st)), self.pool)
@@ -319,6 +326,16 @@ def submit_static(pool, descs, weights, chunk_bytes, flags=0, stream=0):
 
 def wait(pool, job):
     _check(_lib.ft_wait(pool, job), pool)
+
+
+def job_done(pool, job):
+    d = C.c_int()
+    _check(_lib.ft_job_done(pool, job, C.byref(d)), pool)
+    return bool(d.value)
+
+
+def timing_epoch(pool, stream=0):
+    _check(_lib.ft_timing_epoch(pool, stream), pool)
 
 
 def job_release(pool, job):

@@ -292,11 +292,37 @@ int run_dma(ft_pool *p, const ClassPlan &cp, uint64_t C, int cls, hipStream_t st
 }
 
 void retire(ft_pool *p, Job *job) {
-  for (uint64_t a : job->allocs) {
-    Allocation *al = p->slabs.at(a);
-    if (al && al->busy > 0) al->busy -= 1;
+  for (size_t i = 0; i < job->allocs.size(); ++i) {
+    Allocation *al = p->slabs.at(job->allocs[i]);
+    // (the allocation may have been returned in stream order meanwhile and its offset handed out again)
+    if (al && al->serial == job->alloc_serials[i] && al->busy > 0) al->busy -= 1;
   }
   job->allocs.clear();
+  job->alloc_serials.clear();
+}
+
+// The allocations a job refers to stay busy until it has been waited for.
+void hold_allocations(ft_pool *p, Job *job, const std::vector<uint64_t> &allocs) {
+  job->allocs = allocs;
+  job->alloc_serials.assign(allocs.size(), 0);
+  for (size_t i = 0; i < allocs.size(); ++i) {
+    Allocation *al = p->slabs.at(allocs[i]);
+    if (al) {
+      al->busy += 1;
+      job->alloc_serials[i] = al->serial;
+    }
+  }
+}
+
+uint32_t slab_busy(ft_pool *p, uint64_t off) {
+  std::lock_guard<std::mutex> lock(p->mu);
+  Allocation *al = p->slabs.at(off);
+  return al ? al->busy : 0;
+}
+
+int slab_free_ordered(ft_pool *p, uint64_t off) {
+  std::lock_guard<std::mutex> lock(p->mu);
+  return p->slabs.free(off, true);
 }
 
 void release_device_side(ft_pool *p, Job *job) {
@@ -325,7 +351,21 @@ int wait_locked(ft_pool *p, Job *job) {
     ClassRun &r = job->run[c];
     if (!r.used) continue;
     FT_HIP(p, hipEventSynchronize(r.ev_done));
-    if (job->flags & FT_TIMING) FT_HIP(p, hipEventElapsedTime(&r.device_ms, r.ev_begin, r.ev_end));
+    if (job->flags & FT_TIMING) {
+      FT_HIP(p, hipEventElapsedTime(&r.device_ms, r.ev_begin, r.ev_end));
+      hipEvent_t epoch = nullptr;
+      {
+        std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
+        epoch = p->ctx->epoch;
+      }
+      // an epoch recorded after the job began gives no usable time: leave -1
+      if (epoch != nullptr && hipEventElapsedTime(&r.begin_ms, epoch, r.ev_begin) == hipSuccess &&
+          hipEventElapsedTime(&r.end_ms, epoch, r.ev_end) == hipSuccess) {
+      } else {
+        (void)hipGetLastError();
+        r.begin_ms = r.end_ms = -1.f;
+      }
+    }
     if ((job->flags & FT_LOG) && r.log.dev != nullptr) {
       r.log_host.resize(r.table.ntickets);
       FT_HIP(p, hipMemcpy(r.log_host.data(), r.log.dev, r.table.ntickets * sizeof(LogEntry),
@@ -571,6 +611,13 @@ int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t
     ClassRun &r = job->run[c];
     if (!r.used) continue;
     hipStream_t s = p->ctx->streams[c];
+    if ((flags & FT_DETACHED) && c == FT_P2P) {
+      // only the on-device class: a host-link launch lasts milliseconds at the link's rate, so it has
+      // nothing to gain, and two of them side by side would double the host reads in flight
+      std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
+      if (p->ctx->detached_lane[c]++ & 1) s = p->ctx->alt_streams[c];
+    }
+    r.stream = s;
     e = hipStreamWaitEvent(s, fork, 0);
     if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(fork)");
     if (dma) {
@@ -753,11 +800,7 @@ int ft_submit_transfers(ft_pool *p, const ft_desc *descs, uint32_t ndesc, const 
   }
 
   for (int c = 0; c < FT_NCLASS; ++c) job->run[c].plan = std::move(plan.cls[c]);
-  for (uint64_t a : plan.allocs) {
-    Allocation *al = p->slabs.at(a);
-    if (al) al->busy += 1;
-  }
-  job->allocs = plan.allocs;
+  hold_allocations(p, job.get(), plan.allocs);
   p->next_job += 1;
   *job_out = job->id;
   job->host_submit_us =
@@ -796,11 +839,7 @@ int ft_submit_merge(ft_pool *p, ft_job_t open_id, const ft_desc *descs, uint32_t
     rc = open_merge(p, open_job, job.get(), plan, weights, static_cast<hipStream_t>(hip_stream));
     if (rc != FT_OK) return rc;
   }
-  for (uint64_t a : plan.allocs) {
-    Allocation *al = p->slabs.at(a);
-    if (al) al->busy += 1;
-  }
-  job->allocs = plan.allocs;
+  hold_allocations(p, job.get(), plan.allocs);
   p->next_job += 1;
   *job_out = job->id;
   job->host_submit_us =
@@ -859,6 +898,25 @@ int ft_set_batch(ft_pool *p, uint32_t batch_chunks, uint32_t depth) {
   return FT_OK;
 }
 
+int ft_timing_epoch(ft_pool *p, void *hip_stream) {
+  if (p == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  DeviceGuard guard(p->device);
+  int rc = ensure_device(p);
+  if (rc != FT_OK) return rc;
+  hipEvent_t ev = nullptr;
+  {
+    std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
+    ev = p->ctx->epoch;
+  }
+  if (ev == nullptr) FT_HIP(p, hipEventCreateWithFlags(&ev, hipEventDefault));
+  FT_HIP(p, hipEventRecord(ev, static_cast<hipStream_t>(hip_stream)));
+  FT_HIP(p, hipEventSynchronize(ev));
+  std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
+  p->ctx->epoch = ev;
+  return FT_OK;
+}
+
 int ft_wait(ft_pool *p, ft_job_t id) {
   if (p == nullptr) return FT_EINVAL;
   std::unique_lock<std::mutex> lock(p->mu);
@@ -899,6 +957,32 @@ int ft_wait(ft_pool *p, ft_job_t id) {
   return FT_OK;
 }
 
+int ft_job_done(ft_pool *p, ft_job_t id, int *done_out) {
+  if (p == nullptr || done_out == nullptr) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end()) return FT_EINVAL;
+  Job *job = it->second.get();
+  *done_out = 1;
+  if (job->waited) return FT_OK;
+  if (job->open) {
+    *done_out = open_done(job->open, id) ? 1 : 0;
+    return FT_OK;
+  }
+  DeviceGuard guard(p->device);
+  for (int c = 0; c < FT_NCLASS; ++c) {
+    if (!job->run[c].used) continue;
+    const hipError_t e = hipEventQuery(job->run[c].ev_done);
+    if (e == hipErrorNotReady) {
+      *done_out = 0;
+    } else if (e != hipSuccess) {
+      p->hip_error = std::string("hipEventQuery: ") + hipGetErrorString(e);
+      return FT_EHIP;
+    }
+  }
+  return FT_OK;
+}
+
 int ft_job_release(ft_pool *p, ft_job_t id) {
   if (p == nullptr) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);
@@ -927,6 +1011,8 @@ int ft_job_stats(ft_pool *p, ft_job_t id, ft_job_stats_t *out) {
     s.workgroups = r.workgroups;
     s.in_launch = r.on_user_stream ? 1u : 0u;
     s.device_ms = r.device_ms;
+    s.begin_ms = r.begin_ms;
+    s.end_ms = r.end_ms;
     if (job->open && (job->flags & FT_OPEN)) {
       // the whole sequence so far, merged jobs included: tickets and kernel time of all batches
       uint64_t batches = 0;
@@ -954,7 +1040,8 @@ int ft_job_schedule(ft_pool *p, ft_job_t id, int link_class, uint32_t *func_out,
   int rc = get_blob(p, 2 * n * sizeof(uint32_t), false, &out);
   if (rc != FT_OK) return rc;
   uint32_t *dev = reinterpret_cast<uint32_t *>(out.dev);
-  hipStream_t s = p->ctx->streams[link_class];  // ordered after the job's own kernel and table upload
+  // ordered after the job's own kernel and table upload (a job that went with its launch carries its tables along)
+  hipStream_t s = r.stream != nullptr ? r.stream : p->ctx->streams[link_class];
   hipError_t e = launch_decode(r.table, dev, dev + n, n, s, job->inline_tables.get());
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e == hipSuccess) e = hipMemcpy(func_out, dev, n * sizeof(uint32_t), hipMemcpyDeviceToHost);

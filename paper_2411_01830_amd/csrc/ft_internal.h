@@ -35,6 +35,7 @@ struct ClassRun {
   uint32_t tiles_per_chunk = 0;
   uint32_t workgroups = 0;
   bool on_user_stream = false;  // launched on the caller's stream, tables in the launch
+  hipStream_t stream = nullptr; // the library's stream it runs on otherwise
   int counter_pair = -1;        // its self-resetting counter pair, if it needed a counter
   // ev_done orders the caller's stream and ft_wait after the class's work. With FT_TIMING,
   // ev_begin / ev_end bracket it: bound to the kernel's dispatch on the kernel path,
@@ -45,6 +46,7 @@ struct ClassRun {
   std::vector<LogEntry> log_host;
   std::vector<WgLogEntry> wg_log_host;
   float device_ms = -1.f;
+  float begin_ms = -1.f, end_ms = -1.f;  // since the device's timing epoch, if one was set before the job
 };
 
 // One host copy owed after a job's device work: from the job's bounce buffer to pageable memory.
@@ -63,7 +65,8 @@ struct Job {
   ClassRun run[FT_NCLASS];
   Blob tables;
   std::unique_ptr<InlineBlob> inline_tables;  // a small job's tables, passed with the launch instead
-  std::vector<uint64_t> allocs;
+  std::vector<uint64_t> allocs;         // offsets of the pool allocations the job refers to,
+  std::vector<uint64_t> alloc_serials;  // and which allocation at that offset it was
   uint64_t chunk_bytes = 0;
   uint32_t nfunc = 0;    // functions the job was submitted with
   double host_submit_us = 0;
@@ -97,6 +100,12 @@ struct DeviceCtx {
   // head of one batch overlaps the tail of the one before and the link does not idle
   // (contended workload, batches of 2.5 MiB, 3 queued ahead: 46 -> 50 GB/s)
   hipStream_t alt_streams[FT_NCLASS] = {nullptr, nullptr, nullptr};
+  // Detached closed jobs also take the two pool->pool streams in turn: their launches are
+  // independent of each other (nothing orders two detached jobs), and on one stream every launch
+  // would wait for the last workgroup of the one before - in the large mixed workload sixteen
+  // pool->pool launches of 40-300 us each, every one paying its start and its tail alone.
+  uint32_t detached_lane[FT_NCLASS] = {0, 0, 0};  // guarded by mu
+  hipEvent_t epoch = nullptr;  // ft_timing_epoch: the instant that ft_job_stats' begin / end times count from
   std::vector<Blob> free_blobs;      // with a pinned twin
   std::vector<Blob> free_dev_blobs;  // device only
   std::vector<hipEvent_t> free_events, free_timing_events;
@@ -154,6 +163,11 @@ struct DeviceGuard {
 
 
 int ensure_device(ft_pool *p);
+// For the store (ft_store.cpp), which carries out its moves as jobs on one stream that it does not
+// wait for: jobs not yet waited for that refer to the allocation at `off` (0 if there is none), and
+// a free that does not mind them - what reuses the slabs is ordered after those jobs on that stream.
+uint32_t slab_busy(ft_pool *p, uint64_t off);
+int slab_free_ordered(ft_pool *p, uint64_t off);
 int get_blob(ft_pool *p, uint64_t need, bool pinned_twin, Blob *out);
 void put_blob(ft_pool *p, Blob &b);
 int get_event(ft_pool *p, bool timing, hipEvent_t *out);
@@ -204,6 +218,7 @@ void run_host_copies(ft_pool *p, const std::vector<HostCopy> &copies);
 // which nothing of the job is left to trigger.
 int open_reweight(ft_pool *p, Job *job, const uint32_t *weights, hipStream_t user, uint64_t *batch_out);
 int open_wait(ft_pool *p, const std::shared_ptr<OpenState> &st, uint64_t job_id);
+bool open_done(const std::shared_ptr<OpenState> &st, uint64_t job_id);  // what open_wait would wait for has happened
 void open_stats(const std::shared_ptr<OpenState> &st, int c, uint64_t *tickets, uint64_t *tile_bytes,
                 uint32_t *workgroups, float *kernel_ms, uint64_t *batches);
 int open_arrival(const std::shared_ptr<OpenState> &st, uint64_t job_id, int c, uint64_t *batch);

@@ -972,6 +972,12 @@ int open_wait(ft_pool *p, const std::shared_ptr<OpenState> &st, uint64_t job_id)
   return FT_OK;
 }
 
+bool open_done(const std::shared_ptr<OpenState> &st, uint64_t job_id) {
+  std::lock_guard<std::mutex> lock(st->mu);
+  auto it = st->left.find(job_id);
+  return it == st->left.end() || it->second == 0;
+}
+
 void open_stats(const std::shared_ptr<OpenState> &st, int c, uint64_t *tickets, uint64_t *tile_bytes,
                 uint32_t *workgroups, float *kernel_ms, uint64_t *batches) {
   std::lock_guard<std::mutex> lock(st->mu);

@@ -71,6 +71,7 @@ int SlabPool::alloc(uint64_t nbytes, uint64_t *off_out) {
     Allocation a;
     a.nslabs = need;
     a.busy = 0;
+    a.serial = next_serial_++;
     allocs_[start * slab_] = a;
     *off_out = start * slab_;
     return FT_OK;
@@ -78,10 +79,10 @@ int SlabPool::alloc(uint64_t nbytes, uint64_t *off_out) {
   return FT_ENOMEM;
 }
 
-int SlabPool::free(uint64_t off) {
+int SlabPool::free(uint64_t off, bool ordered) {
   auto it = allocs_.find(off);
   if (it == allocs_.end()) return FT_EINVAL;
-  if (it->second.busy != 0) return FT_EBUSY;
+  if (it->second.busy != 0 && !ordered) return FT_EBUSY;
   uint64_t start = off / slab_, len = it->second.nslabs;
   allocs_.erase(it);
   const Segment *seg = segment_of_slab(start);

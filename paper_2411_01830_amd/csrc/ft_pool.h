@@ -16,7 +16,8 @@ struct Segment {
 
 struct Allocation {
   uint64_t nslabs;
-  uint32_t busy;  // jobs not yet waited for that refer to it
+  uint32_t busy;    // jobs not yet waited for that refer to it
+  uint64_t serial;  // tells this allocation from an earlier one at the same offset
 };
 
 class SlabPool {
@@ -31,7 +32,9 @@ class SlabPool {
   int drop_last_segment(void **base_out, uint64_t *bytes_out);
   uint64_t live_bytes() const;
   int alloc(uint64_t nbytes, uint64_t *off_out);
-  int free(uint64_t off);
+  // FT_EBUSY while a job that has not been waited for refers to the allocation, unless `ordered`:
+  // then the caller vouches that whatever reuses the slabs is ordered after those jobs on the device.
+  int free(uint64_t off, bool ordered = false);
   // Live allocation containing [off, off+extent), or nullptr. *start_out = its offset.
   Allocation *owner(uint64_t off, uint64_t extent, uint64_t *start_out);
   Allocation *at(uint64_t start);
@@ -42,6 +45,7 @@ class SlabPool {
  private:
   uint64_t slab_;
   uint64_t total_slabs_ = 0;
+  uint64_t next_serial_ = 1;
   std::vector<Segment> segs_;
   std::map<uint64_t, uint64_t> free_runs_;   // first slab -> length; runs never cross a segment edge
   std::map<uint64_t, Allocation> allocs_;    // offset -> allocation

@@ -148,6 +148,47 @@ int main() {
     for (ft_off_t a : allocs) CHECK(ft_slab_free(pool, a) == FT_OK);
   }
   g_case = -1;
+  {
+    // The store while a consumer's transfer that has not been waited for still reads a result: the result
+    // cannot be moved out (FT_EBUSY), it stays where it is and no spill space is taken; once the transfer
+    // has been waited for the same put goes through, the move is not waited for by the call that starts
+    // it, and ft_store_get waits for the one result it returns.
+    char *spill = host + host_bytes / 2;
+    ft_store *store = nullptr;
+    CHECK(ft_store_create(&store, pool, spill, host_bytes / 2, 6 * MiB, 256 * KiB, nullptr) == FT_OK);
+    ft_off_t a = 0, b = 0, c = 0;
+    CHECK(ft_store_put(store, 1, 4 * MiB, 5, &a) == FT_OK);
+    std::memset(static_cast<char *>(ft_pool_ptr(pool, a)), 0x11, 4 * MiB);
+    ft_desc d{};
+    d.src_space = FT_POOL;
+    d.dst_space = FT_HOST;
+    d.src = a;
+    d.dst = reinterpret_cast<uint64_t>(host);
+    d.row_bytes = 64 * KiB;
+    d.rows = 1;
+    const uint32_t w = 1;
+    ft_job_t consumer = 0;
+    CHECK(ft_submit_transfers(pool, &d, 1, &w, 1, 64 * KiB, 0, nullptr, &consumer) == FT_OK);
+    ft_store_stats_t st{};
+    CHECK(ft_store_put(store, 2, 4 * MiB, 1, &b) == FT_EBUSY);
+    CHECK(ft_store_stats(store, &st) == FT_OK && st.spill_used_bytes == 0 && st.moved_out == 0 && st.objects == 1 &&
+          st.resident_bytes == 4 * MiB && st.moves_in_flight == 0);
+    CHECK(ft_wait(pool, consumer) == FT_OK);
+    CHECK(ft_store_put(store, 2, 4 * MiB, 1, &b) == FT_OK && b == a);  // the slabs that result 1 left, at once
+    CHECK(ft_store_stats(store, &st) == FT_OK && st.spill_used_bytes == 4 * MiB && st.moved_out == 1 &&
+          st.moves_in_flight == 1 && st.resident_bytes == 4 * MiB);
+    std::memset(static_cast<char *>(ft_pool_ptr(pool, b)), 0x22, 4 * MiB);
+    uint32_t was_out = 0;
+    CHECK(ft_store_get(store, 2, &c, &was_out) == FT_OK && c == b && was_out == 0);
+    CHECK(ft_store_done(store, 2) == FT_OK);  // result 1 comes back, nobody waits for it here
+    CHECK(ft_store_stats(store, &st) == FT_OK && st.moved_in == 1 && st.moves_in_flight == 1 && st.spill_used_bytes == 0);
+    CHECK(ft_store_get(store, 1, &c, &was_out) == FT_OK && was_out == 0);
+    CHECK(ft_store_stats(store, &st) == FT_OK && st.moves_in_flight == 0 && st.stalls == 0);
+    for (uint64_t i = 0; i < 4 * MiB; i += 4099) CHECK(static_cast<unsigned char *>(ft_pool_ptr(pool, c))[i] == 0x11);
+    CHECK(ft_store_done(store, 1) == FT_OK);
+    CHECK(ft_store_sync(store) == FT_OK);
+    CHECK(ft_store_destroy(store) == FT_OK);
+  }
   CHECK(ft_pool_destroy(pool) == FT_OK);
   std::printf("api_tour done\n");
   return 0;

@@ -86,6 +86,7 @@ hipError_t hipEventSynchronize(hipEvent_t) {
   FAIL_POINT("hipEventSynchronize", hipErrorUnknown);
   return hipSuccess;
 }
+hipError_t hipEventQuery(hipEvent_t) { return hipSuccess; }
 hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t) { *ms = 0.001f; return hipSuccess; }
 
 hipError_t hipMalloc(void **p, size_t n) {

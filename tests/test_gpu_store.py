@@ -180,12 +180,14 @@ def test_native_store_matches_the_oracle_store():
     for k in range(0, n - 3, 5):                      # now and then a later request overtakes
         order[k + 1], order[k + 2] = order[k + 2], order[k + 1]
 
-    def run(eng, store):
+    def run(eng, store, after_put=None):
         trace = []
         stored = 0
         for step, head in enumerate(order):
             while stored < n and stored <= step + lookahead:
                 off = store.put(stored, sizes[stored], stored - step if stored > step else 0)
+                if after_put is not None:
+                    after_put()
                 eng.write_pool(off, payload[stored])
                 trace.append(("put", stored, off))
                 stored += 1
@@ -211,9 +213,14 @@ def test_native_store_matches_the_oracle_store():
         eng.pool_create(pool_bytes, 64 * KiB)
         gst = ft.Store(eng.pool, eng.host.data_ptr() + spill_off, spill_bytes, capacity, 256 * KiB,
                        torch.cuda.current_stream().cuda_stream)
-        trace_g = run(eng, gst)
+        in_flight = []
+        trace_g = run(eng, gst, lambda: in_flight.append(gst.stats().moves_in_flight))
         assert trace_g == trace_o
+        # moves are not waited for by the calls that start them: some were still unsettled when a call returned
+        assert max(in_flight) >= 1, in_flight
+        gst.sync()                      # quiescent point: memory now holds what the decisions imply
         st = gst.stats()
+        assert st.moves_in_flight == 0
         outs = [e for e in ost.log if e[0] == "out"]
         ins = [e for e in ost.log if e[0] == "in"]
         assert (st.moved_out, st.moved_in, st.stalls) == (len(outs), len(ins), ost.stalls)

@@ -42,7 +42,7 @@ def test_constants_match_between_header_binding_and_shared_format():
         assert 1 << int(m.group(1)) == getattr(fmt, name) == getattr(ft, name)
     assert (oracle.EINVAL, oracle.ENOMEM, oracle.ERANGE, oracle.EOVERLAP, oracle.EBUSY) == \
         (fmt.FT_EINVAL, fmt.FT_ENOMEM, fmt.FT_ERANGE, fmt.FT_EOVERLAP, fmt.FT_EBUSY)
-    assert ctypes.sizeof(ft.JobStats) == 3 * 48 + 8
+    assert ctypes.sizeof(ft.JobStats) == 3 * 56 + 8
 
 
 def test_header_is_plain_c_and_its_layouts_are_the_bindings(tmp_path):
