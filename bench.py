@@ -163,33 +163,154 @@ def share_error(rp, cls):
         got["weights"] = rp.rec.weights[name]
 
     rp.step(ft.FT_LOG, collect)
-    return shares_from_log(got["log"], got["weights"])
+    return shares_from_log(got["log"], got["weights"], 512 << 10)
 
 
-def shares_from_log(log, weights):
-    w = np.asarray(weights, dtype=np.float64)
+def _share_errors(t_begin0, t_end, func, nbytes, w):
+    """max over active functions of |share - weight share| / weight share, over [0, T1] and per tenth of it;
+    T1 = first time any function's last byte lands. Returns (T1 - t0, error, per-tenth errors, tickets in window)."""
     F = len(w)
-    t_end = log["t_end_ns"].astype(np.int64)
-    t0 = int(log["t_begin_ns"].min())
-    last = np.array([t_end[log["func"] == f].max() if np.any(log["func"] == f) else np.iinfo(np.int64).max
-                     for f in range(F)])
+    last = np.array([t_end[func == f].max() if np.any(func == f) else np.iinfo(np.int64).max for f in range(F)])
     T1 = int(last.min())
-    active = np.array([np.any(log["func"] == f) for f in range(F)])
+    active = np.array([np.any(func == f) for f in range(F)])
     want = w * active / (w * active).sum()
 
     def err_at(lo, hi):
         m = (t_end > lo) & (t_end <= hi)
-        b = np.array([log["bytes"][m & (log["func"] == f)].sum() for f in range(F)], dtype=np.float64)
+        b = np.array([nbytes[m & (func == f)].sum() for f in range(F)], dtype=np.float64)
         if b.sum() == 0:
             return None
         share = b / b.sum()
         return float(np.max(np.abs(share - want)[active] / want[active]))
 
-    windows = [err_at(t0 + (T1 - t0) * i // 10, t0 + (T1 - t0) * (i + 1) // 10) for i in range(10)]
-    return {"window": "[0,T1], T1 = first function done", "T1_ms": (T1 - t0) / 1e6,
-            "max_rel_err": err_at(t0 - 1, T1),
-            "max_rel_err_tenths": [None if x is None else round(x, 4) for x in windows],
-            "weights": [int(x) for x in w]}
+    t0 = t_begin0
+    tenths = [err_at(t0 + (T1 - t0) * i // 10, t0 + (T1 - t0) * (i + 1) // 10) for i in range(10)]
+    return T1 - t0, err_at(t0 - 1, T1), tenths, int(np.sum(t_end <= T1))
+
+
+def shares_from_log(log, weights, chunk_bytes=None):
+    """Timed shares from the copy kernel's own record (times, and the function each ticket was decoded to, both
+    written by the kernel). Beside every timed figure the same statistic for the ticket order alone: the tickets
+    in the order the device decoded them, completing one after the other at a uniform byte rate - what the chunk
+    grain of the order contributes to the error before any timing effect."""
+    w = np.asarray(weights, dtype=np.float64)
+    func = log["func"].astype(np.int64)
+    nbytes = log["bytes"].astype(np.int64)
+    t_end = log["t_end_ns"].astype(np.int64)
+    span, err, tenths, ntick = _share_errors(int(log["t_begin_ns"].min()), t_end, func, nbytes, w)
+    ideal_end = np.cumsum(nbytes)
+    _, err_o, tenths_o, _ = _share_errors(0, ideal_end, func, nbytes, w)
+    rnd = lambda xs: [None if x is None else round(x, 4) for x in xs]
+    return {"window": "[0,T1], T1 = first function done", "T1_ms": span / 1e6, "tickets_in_window": ntick,
+            "max_rel_err": err, "max_rel_err_tenths": rnd(tenths),
+            "order_alone": {"what": "same tickets in the decoded order at a uniform byte rate",
+                            "max_rel_err": err_o, "max_rel_err_tenths": rnd(tenths_o)},
+            "weights": [int(x) for x in w],
+            **({"fluid_lag": lag_from_log(log, weights, chunk_bytes)} if chunk_bytes else {})}
+
+
+def fluid_lag(func, nbytes, w, chunk_bytes, order):
+    """How far every function is from its exact weighted share while the tickets complete in `order`: after each
+    completion, bytes_f done so far against the fluid allocation of the total done so far - a_f = min(S_f, w_f * x)
+    with x such that the a_f add up to the total (a function that has run dry leaves its part to the others in
+    proportion). Unlike a share over one window this is defined at every instant and for any mix of stream sizes.
+    Returns (largest |bytes_f - a_f| in chunks, its 99th percentile over completions and functions)."""
+    w = np.asarray(w, dtype=np.float64)
+    F = len(w)
+    S = np.array([nbytes[func == f].sum() for f in range(F)], dtype=np.float64)
+    act = S > 0
+    if not act.any():
+        return None, None
+    lam = np.where(act, S / w, 0.0)
+    by = np.argsort(lam)
+    by = by[act[by]]
+    lam_s, w_s, S_s = lam[by], w[by], S[by]
+    # total bytes handed out when x reaches the i-th breakpoint; weight still active before it
+    W_before = np.concatenate(([w_s.sum()], w_s.sum() - np.cumsum(w_s)[:-1]))
+    B_at = np.array([np.minimum(S_s, w_s * l).sum() for l in lam_s])
+    lam_prev = np.concatenate(([0.0], lam_s[:-1]))
+    B_prev = np.concatenate(([0.0], B_at[:-1]))
+    fo, bo = func[order], nbytes[order].astype(np.float64)
+    total = np.cumsum(bo)
+    seg = np.minimum(np.searchsorted(B_at, total, side="left"), len(B_at) - 1)
+    x = lam_prev[seg] + (total - B_prev[seg]) / W_before[seg]
+    done = np.zeros((len(fo), F))
+    done[np.arange(len(fo)), fo] = bo
+    done = np.cumsum(done, axis=0)
+    fluid = np.minimum(S[None, :], w[None, :] * x[:, None])
+    lag = np.abs(done - fluid)[:, act] / float(chunk_bytes)
+    return float(lag.max()), float(np.percentile(lag, 99))
+
+
+def lag_from_log(log, weights, chunk_bytes):
+    """fluid_lag of the tickets in the order they completed on the device clock, and in the order they were decoded
+    (ticket order: what the chunk order alone gives; anything beyond it is tiles in flight completing out of turn)."""
+    func, nbytes = log["func"].astype(np.int64), log["bytes"].astype(np.int64)
+    timed = fluid_lag(func, nbytes, weights, chunk_bytes, np.argsort(log["t_end_ns"], kind="stable"))
+    alone = fluid_lag(func, nbytes, weights, chunk_bytes, np.arange(len(func)))
+    r = lambda v: None if v is None else round(v, 3)
+    return {"unit": "chunks", "timed_max": r(timed[0]), "timed_p99": r(timed[1]),
+            "order_alone_max": r(alone[0]), "order_alone_p99": r(alone[1])}
+
+
+def share_error_large_mixed(rp):
+    """Timed shares where both kernels run side by side: one step of large_mixed with the per-ticket record, every
+    wave's host->pool and pool->pool launch on its own. A wave holds some 38 + 26 transfers of 16 functions with
+    lognormal sizes from 4 KiB up, so the first function is done after a handful of tickets and a share over
+    [0, T1] says nothing here; reported instead, per class, is the distance of every function from its fluid
+    weighted share at every completion (fluid_lag), the worst wave and the median wave."""
+    ft = rp.ft
+    per = {0: [], 2: []}
+
+    def collect(name, pool, job, st):
+        for cls in per:
+            if st.cls[cls].payload_bytes:
+                per[cls].append((ft.job_log(pool, job, cls), rp.rec.weights[name], st.cls[cls].tile_bytes))
+
+    rp.step(ft.FT_LOG, collect)
+    chunk = 2 << 20
+    out = {"what": "one step, FT_LOG; per wave and class the largest distance (in 2 MiB chunks) of any function from "
+                   "its fluid weighted share at any completion; order_alone = the same tickets completing in ticket order",
+           "chunk_bytes": chunk}
+    for cls, name in ((0, "h2p"), (2, "p2p")):
+        lags = [lag_from_log(log, weights, chunk) for log, weights, _ in per[cls]]
+        tile = per[cls][0][2] if per[cls] else 0
+        wgs = 32 if cls == 0 else 256
+        out[name] = {"waves": len(lags),
+                     "timed_max_chunks": {"median_wave": round(float(np.median([l["timed_max"] for l in lags])), 3),
+                                          "worst_wave": max(l["timed_max"] for l in lags)},
+                     "timed_p99_chunks_median_wave": round(float(np.median([l["timed_p99"] for l in lags])), 3),
+                     "order_alone_max_chunks": {"median_wave": round(float(np.median([l["order_alone_max"] for l in lags])), 3),
+                                                "worst_wave": max(l["order_alone_max"] for l in lags)},
+                     "in_flight_chunks": round(wgs * tile / chunk, 3)}
+    return out
+
+
+def share_error_pool_to_host():
+    """The same measure on the link's other direction: 16 functions (weights from {1,2,4}, seeded) each send 64 MiB
+    from the pool to pinned host memory in 512 KiB chunks, one job."""
+    import torch
+    from paper_2411_01830_amd import binding as ft
+    from workloads import make_descs, FT_HOST, FT_POOL
+    nf, per, chunk = 16, 64 << 20, 512 << 10
+    rng = np.random.Generator(np.random.PCG64(241101830 + 11))
+    w = [int(x) for x in rng.choice([1, 2, 4], nf)]
+    buf = torch.empty(nf * per, dtype=torch.uint8, device="cuda:0")
+    host = torch.empty(nf * per, dtype=torch.uint8, pin_memory=True)
+    pool = ft.pool_create(buf.data_ptr(), buf.numel(), 1 << 20, 0)
+    ft.host_window_add(pool, host.data_ptr(), host.numel())
+    src = [ft.slab_alloc(pool, per) for _ in range(nf)]
+    d = make_descs([dict(func=f, src_space=FT_POOL, dst_space=FT_HOST, src=src[f], dst=host.data_ptr() + f * per, row_bytes=per)
+                    for f in range(nf)])
+    stream = torch.cuda.current_stream().cuda_stream
+    ft.wait(pool, ft.submit_transfers(pool, d, w, chunk, 0, stream))      # the device's first writes into the fresh arena
+    job = ft.submit_transfers(pool, d, w, chunk, ft.FT_LOG | ft.FT_TIMING, stream)
+    ft.wait(pool, job)
+    out = shares_from_log(ft.job_log(pool, job, 1), w, chunk)
+    out["payload_GBps"] = round(nf * per / ft.job_stats(pool, job).cls[1].device_ms / 1e6, 2)
+    ft.job_release(pool, job)
+    ft.pool_destroy(pool)
+    return out
 
 
 def share_error_pool_to_pool():
@@ -212,7 +333,7 @@ def share_error_pool_to_pool():
     ft.wait(pool, ft.submit_transfers(pool, d, w, 2 << 20, 0, stream))      # touch everything once
     job = ft.submit_transfers(pool, d, w, 2 << 20, ft.FT_LOG | ft.FT_TIMING, stream)
     ft.wait(pool, job)
-    out = shares_from_log(ft.job_log(pool, job, 2), w)
+    out = shares_from_log(ft.job_log(pool, job, 2), w, 2 << 20)
     gbps = nf * per / ft.job_stats(pool, job).cls[2].device_ms / 1e6
     out["payload_GBps"] = round(gbps, 1)
     out["hbm_frac"] = round(2 * gbps / HBM_PEAK_GBS, 4)      # with the per-ticket log being written
@@ -792,6 +913,11 @@ def main():
                              "d2h_peak_measured": round(peaks["d2h"], 2)}
     if shares is not None:
         line["share_error"] = shares
+    if args.workload == "large_mixed" and not args.no_extras:
+        try:
+            line["share_error_large_mixed"] = share_error_large_mixed(rp)
+        except Exception as e:      # noqa: BLE001
+            line["share_error_large_mixed"] = {"error": repr(e)}
     line["per_workload"] = per
     if dma:
         line["dma_path"] = {"what": "FT_PATH_DMA: same chunk order, one hipMemcpyAsync / hipMemcpy2DAsync per chunk piece "
@@ -800,6 +926,7 @@ def main():
     if not args.no_extras:
         # the blocks that widen the path; one that fails must not take the headline figures with it
         for key, block in (("share_error_pool_to_pool", share_error_pool_to_pool),
+                           ("share_error_pool_to_host", share_error_pool_to_host),
                            ("batched_triggering", lambda: batched_triggering(peaks)),
                            ("pinned_ring", lambda: pinned_ring(peaks)),
                            ("single_transfers", single_transfers),

@@ -305,9 +305,11 @@ def host_window_add(pool, host_base, nbytes):
 
 def submit_transfers(pool, descs, weights, chunk_bytes, flags=0, stream=0):
     """descs: contiguous array of the 64-byte descriptor dtype; weights: uint32 sequence."""
-    descs = np.ascontiguousarray(descs)
+    if not descs.flags.c_contiguous:
+        descs = np.ascontiguousarray(descs)
     assert descs.dtype.itemsize == 64
-    w = np.ascontiguousarray(np.asarray(weights, dtype=np.uint32))
+    w = weights if isinstance(weights, np.ndarray) and weights.dtype == np.uint32 and weights.flags.c_contiguous \
+        else np.ascontiguousarray(np.asarray(weights, dtype=np.uint32))
     job = C.c_uint64()
     _check(_lib.ft_submit_transfers(pool, descs.ctypes.data if len(descs) else None, len(descs),
                                     w.ctypes.data if len(w) else None, len(w), chunk_bytes, flags,

@@ -484,6 +484,10 @@ int prepare_class(ft_pool *p, Job *job, int c, const ClassPlan &cp, const Layout
   return rc;
 }
 
+// Largest single tensor that is copied with ordinary (cached) loads and stores: with its copy it
+// still fits the chip's 256 MiB last-level cache.
+constexpr uint64_t kCacheResidentBytes = 128ull << 20;
+
 // A job of one link class whose tables fit into a kernel argument is launched on the
 // caller's stream itself, tables in the launch: one launch and one event record instead
 // of a table upload, a fork and a join across streams - 4 us of host time instead of
@@ -516,8 +520,11 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
   // host->pool: more than 64 tiles of 16 KiB requested at once is more than the link
   // takes (2 MiB as 128 x 16 KiB: 52 us; as 64 workgroups drawing tickets: 43 us)
   const uint64_t most = only == FT_P2P ? (uint64_t)p->ctx->cu_count : only == FT_H2P ? 64u : 128u;
-  const bool each_its_own = ntickets <= most;
-  if (!each_its_own) {
+  // one contiguous, 16-byte aligned transfer: the workgroups share the tiles out themselves (ClassTable::single >= 2)
+  const bool direct = cp.funcs.size() == 1 && cp.xfers.size() == 1 && cp.funcs[0].chunk_base == 0 && !(flags & FT_LOG) &&
+                      cp.xfers[0].rows == 1 && ((cp.xfers[0].src | cp.xfers[0].dst | cp.xfers[0].row_bytes) & 15) == 0;
+  const bool each_its_own = !direct && ntickets <= most;
+  if (!each_its_own && !direct) {
     if (flags & FT_DETACHED) return FT_OK;
     std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
     if (p->ctx->free_pairs.empty()) return FT_OK;
@@ -531,7 +538,18 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
   ClassTable &T = r.table;
   T.single = cp.funcs.size() == 1 && cp.xfers.size() == 1 && cp.funcs[0].chunk_base == 0 ? 1u : 0u;
   uint64_t wg = ntickets;
-  if (each_its_own) {
+  if (direct) {
+    T.ticket = p->ctx->idle_counter;  // never consulted
+    // A tensor that fits the last-level cache together with its copy (256 MiB on this chip) moves with
+    // ordinary loads and stores: its producer has just written it and its consumer is about to read the
+    // copy, so both may be served from that cache (64 MiB: 26 -> 20 us, 128 MiB: 51 -> 36 us when the
+    // source is still there). Larger ones stream past the caches like every other pool->pool transfer.
+    T.single = only == FT_P2P && cp.payload <= kCacheResidentBytes ? 3u : 2u;
+    // Host->pool: the link is full with 256 KiB of reads in flight, and a lone transfer is the faster the
+    // less is asked for at once beyond that (1 MiB: 64 workgroups x 16 KiB 25 us, 16 x 16 KiB 21 us).
+    wg = only == FT_H2P ? 16u : default_workgroups(p, only, only == FT_P2P);
+    if (wg > ntickets) wg = ntickets;
+  } else if (each_its_own) {
     T.ticket = p->ctx->idle_counter;
   } else {
     T.ticket = p->ctx->counter_pairs + 2 * r.counter_pair;
@@ -547,8 +565,15 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
     T.log = reinterpret_cast<LogEntry *>(r.log.dev);
     T.wg_log = reinterpret_cast<WgLogEntry *>(r.log.dev + T.ntickets * sizeof(LogEntry));
   }
-  hipError_t e = launch_copy(T, only, r.workgroups, user, r.ev_begin, r.ev_end, job->inline_tables.get());
-  if (e == hipSuccess) e = hipEventRecord(r.ev_done, user);
+  hipError_t e;
+  if (r.ev_begin == nullptr) {
+    // the done event is bound to the dispatch itself (it fires with the kernel's own completion
+    // signal) instead of being a marker queued behind it: 2 us less from submit to the end of wait
+    e = launch_copy(T, only, r.workgroups, user, nullptr, r.ev_done, job->inline_tables.get());
+  } else {
+    e = launch_copy(T, only, r.workgroups, user, r.ev_begin, r.ev_end, job->inline_tables.get());
+    if (e == hipSuccess) e = hipEventRecord(r.ev_done, user);
+  }
   if (e != hipSuccess) {
     p->hip_error = std::string("launch on the caller's stream: ") + hipGetErrorString(e);
     (void)hipDeviceSynchronize();  // the kernel may be running: its counter pair must be back at zero

@@ -9,7 +9,7 @@ namespace ft {
 // Persistent copy kernel of one link class (0 host->pool, 1 pool->host, 2 pool->pool).
 // Workgroup b starts on ticket b, the counter *T.ticket hands out the following ones: it
 // must be zero when the kernel starts unless workgroups >= the launch's tickets (then its
-// value does not matter). ev_start / ev_stop (both or neither) are timing events that will
+// value does not matter). ev_start / ev_stop (both, neither, or ev_stop alone) are events that will
 // read the start and the end of this dispatch. `tables`: the job's tables when
 // T.inline_tables is set, else null.
 hipError_t launch_copy(const ClassTable &T, int link_class, uint32_t workgroups, hipStream_t stream,

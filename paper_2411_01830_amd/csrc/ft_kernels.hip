@@ -792,6 +792,31 @@ __device__ __forceinline__ void get_work(const WorkSlot &slot, Work &w) {
   w.first.staged = 0;  // already applied
 }
 
+// The tiles of one contiguous, 16-byte aligned transfer, dealt out round robin among the workgroups.
+template <bool NT, uint32_t U>
+__device__ __forceinline__ void deal_out_tiles(const ClassTable &T, uint64_t src, uint64_t dst, uint64_t nbytes, uint32_t tid) {
+  for (uint64_t v = blockIdx.x; v < T.ntickets; v += gridDim.x) {
+    uint64_t rank, ti;
+    if (v < (1ull << 32)) {
+      rank = (uint32_t)v / T.tiles_per_chunk;
+      ti = (uint32_t)v - (uint32_t)rank * T.tiles_per_chunk;
+    } else {
+      rank = v / T.tiles_per_chunk;
+      ti = v - rank * T.tiles_per_chunk;
+    }
+    uint64_t lo = ti * T.tile_bytes, hi = lo + T.tile_bytes;
+    if (hi > T.chunk_bytes) hi = T.chunk_bytes;
+    const uint64_t b0 = rank * T.chunk_bytes + lo;
+    uint64_t b1 = rank * T.chunk_bytes + hi;
+    if (b1 > nbytes) b1 = nbytes;
+    if (b0 < b1) {
+      if (b1 - b0 == (uint64_t)kThreads * U * 16) copy_rows_of_vectors<NT, U>(dst + b0, src + b0, tid);
+      else copy_vectors<NT, U>(dst + b0, src + b0, (b1 - b0) >> 4, tid);
+    }
+    __syncthreads();  // keeps a workgroup's loads and stores in separate bursts, as in the ticket loop
+  }
+}
+
 // Persistent workgroups. Workgroup b starts on ticket b and every later ticket comes from
 // the counter (which therefore hands out the tickets from the grid size on; the host never
 // launches more workgroups than there are tickets). When all workgroups of a launch ask
@@ -815,9 +840,19 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
   constexpr uint32_t U = UnrollOf<CLS>::value;
   __shared__ WorkSlot s_work[2];
   const uint32_t tid = threadIdx.x;
+  const ConstTables CT = const_tables(T);
+  if (T.single >= 2) {
+    // One contiguous transfer, both sides and the length multiples of 16, nothing to record:
+    // passing a single tensor. With one function there is nothing to interleave - ticket t is
+    // tile t of the one stream - so the tiles are dealt out round robin, workgroup b taking
+    // tiles b, b + workgroups, ...: no counter, no decode by one wavefront for the others, no
+    // hand-over through LDS, and the first tile's loads are issued a microsecond after entry.
+    if (T.single == 3) deal_out_tiles<false, U>(T, CT.xfers[0].src, CT.xfers[0].dst, CT.xfers[0].row_bytes, tid);
+    else deal_out_tiles<NT, U>(T, CT.xfers[0].src, CT.xfers[0].dst, CT.xfers[0].row_bytes, tid);
+    return;
+  }
   const bool lead = tid < 64;  // the first wavefront: draws and decodes tickets
   if (T.log && tid == 0) T.wg_log[blockIdx.x].t_entry = wall_clock64();
-  const ConstTables CT = const_tables(T);
   PhaseCursor pc;
   SkipCursor sc;
   if (lead) {

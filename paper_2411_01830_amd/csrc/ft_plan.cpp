@@ -414,11 +414,14 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
   for (int c = 0; c < FT_NCLASS; ++c) {
     ClassPlan &cp = out->cls[c];
     cp = ClassPlan();
-    std::vector<uint64_t> stream(nfunc, 0);
-    std::vector<uint32_t> count(nfunc, 0);
     auto class_of = [](const ft_desc &d) {
       return d.src_space != FT_POOL ? FT_H2P : (d.dst_space != FT_POOL ? FT_P2H : FT_P2P);
     };
+    bool any = false;
+    for (uint32_t i = 0; i < ndesc && !any; ++i) any = class_of(descs[i]) == c;
+    if (!any) continue;  // a class without traffic costs no allocation (passing one tensor: two of three)
+    std::vector<uint64_t> stream(nfunc, 0);
+    std::vector<uint32_t> count(nfunc, 0);
     for (uint32_t i = 0; i < ndesc; ++i)
       if (class_of(descs[i]) == c) {
         count[descs[i].func] += 1;

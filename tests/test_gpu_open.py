@@ -190,15 +190,27 @@ def test_merge_other_classes_and_busy_allocations(gpu):
         eng.close()
 
 
-def test_open_rejects_log_and_dma(gpu):
+def test_open_rejects_dma_and_keeps_its_log_until_dry(gpu):
+    """The comparison path has no batches: FT_PATH_DMA with FT_OPEN is refused. FT_LOG is taken: the
+    per-ticket record of the whole sequence is there once the class has run dry."""
     binding, _ = gpu
     orc, eng, rng = _engines(gpu, 4 * MiB, 8 * MiB)
     try:
         d = make_descs(_h2p_job(orc, eng, rng, [64 * KiB], 1 * MiB))
-        for extra in (fmt.FT_LOG, fmt.FT_PATH_DMA):
-            with pytest.raises(binding.FtError) as ei:
-                eng.submit(d, [1], 4096, fmt.FT_OPEN | extra)
-            assert ei.value.code == fmt.FT_EINVAL
+        with pytest.raises(binding.FtError) as ei:
+            eng.submit(d, [1], 4096, fmt.FT_OPEN | fmt.FT_PATH_DMA)
+        assert ei.value.code == fmt.FT_EINVAL
+        orc.wait(orc.submit(d, [1], 4096))
+        job = eng.submit(d, [1], 4096, fmt.FT_OPEN | fmt.FT_LOG)
+        eng.wait(job)
+        _images_equal(orc, eng)
+        log = binding.job_log(eng.pool, job, 0)
+        assert int(log["bytes"].sum()) == 64 * KiB and set(log["func"].tolist()) == {0}
+        assert log["chunk"].tolist() == sorted(log["chunk"].tolist()) and int(log["chunk"].max()) == 15
+        with pytest.raises(binding.FtError) as ei:          # the per-workgroup record is a closed job's
+            binding.job_log_workgroups(eng.pool, job, 0, len(log["bytes"]))
+        assert ei.value.code == fmt.FT_EINVAL
+        binding.job_release(eng.pool, job)
     finally:
         eng.close()
 

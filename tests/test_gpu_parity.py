@@ -434,6 +434,58 @@ def test_larger_single_class_jobs_reuse_the_self_resetting_counters(gpu):
         eng.close()
 
 
+def test_one_aligned_tensor_is_dealt_out_without_a_counter(gpu):
+    """One contiguous transfer whose two sides and length are multiples of 16 and which has more tiles than
+    workgroups: the workgroups deal the tiles out round robin, no counter (Sec. 5.1: passing one tensor).
+    Every class, lengths with a ragged last tile and a ragged last chunk, chunk sizes that are not a
+    multiple of the tile, with and without timing, detached; canaries around every destination."""
+    binding, _ = gpu
+    orc, eng, rng = _pair(gpu, host=1 << 26, pool=3 << 27, slab=1 << 20, seed=83)
+    try:
+        case = 0
+        for cls in (0, 1, 2):
+            sizes = [17 << 20, (20 << 20) + 4096 + 16, (33 << 20) - 16] if cls == 2 else \
+                    [3 << 20, (5 << 20) + 48, (9 << 20) - 16]
+            for n in sizes:
+                for C in (2 << 20, (1 << 20) + 4096 + 16):
+                    a = b = None
+                    if cls == 0:
+                        src, sspace = 4096 + 16 * case, FT_HOST
+                    else:
+                        a = orc.slab_alloc(n + 64)
+                        assert eng.slab_alloc(n + 64) == a
+                        fill = rng.integers(0, 256, n + 64, dtype=np.uint8)
+                        orc.write_pool(a, fill)
+                        eng.write_pool(a, fill)
+                        src, sspace = a + 16, FT_POOL
+                    if cls == 1:
+                        dst, dspace = (1 << 25) + 32, FT_HOST
+                    else:
+                        b = orc.slab_alloc(n + 64)
+                        assert eng.slab_alloc(n + 64) == b
+                        dst, dspace = b + 32, FT_POOL
+                    d = make_descs([dict(func=0, src_space=sspace, dst_space=dspace, src=src, dst=dst, row_bytes=n)])
+                    flags = (fmt.FT_KEEP, fmt.FT_KEEP | fmt.FT_TIMING, fmt.FT_KEEP | fmt.FT_DETACHED)[case % 3]
+                    jo = orc.submit(d, [3], C)
+                    orc.wait(jo)
+                    jg = eng.submit(d, [3], C, flags)
+                    eng.wait(jg)
+                    st = binding.job_stats(eng.pool, jg)
+                    assert st.cls[cls].in_launch == 1 and st.cls[cls].workgroups < st.cls[cls].tickets, (cls, n, C)
+                    assert eng.job_schedule(jg, cls) == orc.job_schedule(jo, cls), (cls, n, C)
+                    if flags & fmt.FT_TIMING:
+                        assert st.cls[cls].device_ms > 0
+                    binding.job_release(eng.pool, jg)
+                    _compare_images(orc, eng)
+                    for off in (a, b):
+                        if off is not None:
+                            orc.slab_free(off)
+                            eng.slab_free(off)
+                    case += 1
+    finally:
+        eng.close()
+
+
 def test_random_sequences_of_mixed_jobs(gpu):
     """Sixty jobs per seed, each a random mix of classes, sizes from bytes to MiB, pitched and plain,
     every alignment, random weights, chunk sizes, tile sizes and workgroup counts (tuned and default, so
