@@ -31,11 +31,18 @@ from paper_2411_01830_amd.replay import Replay
 
 METRIC = "aggregate GB/s (host->pool, pool->pool) as % of roofline; weighted-share error"
 HBM_PEAK_GBS = 8000.0
-# HBM bytes the profiler counted per algorithmic byte for the pool->pool kernel, per
-# workload (FETCH_SIZE and WRITE_SIZE runs, each scaled by a plain copy of known size);
-# see profiles/pmc_hbm_traffic_pool_to_pool_<workload>.md. Workloads without such a run
-# report null.
-TRAFFIC_PER_ALGO_BYTE = {"large_mixed": 1.0125, "feature": 1.0010, "traffic_crops": 1.4126}
+# HBM bytes the profiler counted per algorithmic byte for the pool->pool kernel, per workload: two counter runs
+# of this very command under rocprofv3 (FETCH_SIZE, then WRITE_SIZE, each scaled by a plain copy of known size),
+# whose summaries are the files named here. Counters cannot be read from inside the run that is being timed, so
+# the line carries these constants and says where they come from (`traffic_source`); tests/test_host_logic.py
+# holds every constant against the figure in its file. Workloads without such a run report null.
+TRAFFIC_PER_ALGO_BYTE = {
+    "large_mixed": (1.0107, "profiles/pmc_hbm_traffic_pool_to_pool_large_mixed.md"),
+    "feature": (1.0010, "profiles/pmc_hbm_traffic_pool_to_pool_feature.md"),
+    "traffic_crops": (1.4114, "profiles/pmc_hbm_traffic_pool_to_pool_traffic_crops.md"),
+}
+EXTRA_BLOCKS = ("share_error_pool_to_pool", "share_error_pool_to_host", "batched_triggering", "pinned_ring",
+                "single_transfers", "elastic_store", "path_planner")
 
 
 def parse_args():
@@ -47,6 +54,9 @@ def parse_args():
                     choices=["tiny", "traffic", "feature", "contended", "large_mixed"])
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--blocks", default=None,
+                    help="comma-separated: run only these of the blocks that widen the path (" + ", ".join(EXTRA_BLOCKS) +
+                         ") and none of the other workloads; for profiling one block")
     ap.add_argument("--path", default="kernel", choices=["kernel", "dma"])
     return ap.parse_args()
 
@@ -265,7 +275,7 @@ def share_error_large_mixed(rp):
     def collect(name, pool, job, st):
         for cls in per:
             if st.cls[cls].payload_bytes:
-                per[cls].append((ft.job_log(pool, job, cls), rp.rec.weights[name], st.cls[cls].tile_bytes))
+                per[cls].append((ft.job_log(pool, job, cls), rp.rec.weights[name], st.cls[cls].tile_bytes * st.cls[cls].workgroups))
 
     rp.step(ft.FT_LOG, collect)
     chunk = 2 << 20
@@ -274,15 +284,14 @@ def share_error_large_mixed(rp):
            "chunk_bytes": chunk}
     for cls, name in ((0, "h2p"), (2, "p2p")):
         lags = [lag_from_log(log, weights, chunk) for log, weights, _ in per[cls]]
-        tile = per[cls][0][2] if per[cls] else 0
-        wgs = 32 if cls == 0 else 256
+        in_flight = per[cls][0][2] if per[cls] else 0       # one tile per workgroup
         out[name] = {"waves": len(lags),
                      "timed_max_chunks": {"median_wave": round(float(np.median([l["timed_max"] for l in lags])), 3),
                                           "worst_wave": max(l["timed_max"] for l in lags)},
                      "timed_p99_chunks_median_wave": round(float(np.median([l["timed_p99"] for l in lags])), 3),
                      "order_alone_max_chunks": {"median_wave": round(float(np.median([l["order_alone_max"] for l in lags])), 3),
                                                 "worst_wave": max(l["order_alone_max"] for l in lags)},
-                     "in_flight_chunks": round(wgs * tile / chunk, 3)}
+                     "in_flight_chunks": round(in_flight / chunk, 3)}
     return out
 
 
@@ -815,7 +824,9 @@ def summarize(name, res, steps, rp, peaks):
                 entry["line_granular_bytes_per_payload_byte"] = {
                     "lines_64B": round((sb["read_64"] + sb["write_64"]) / (2 * sb["payload"]), 4),
                     "lines_128B": round((sb["read_128"] + sb["write_128"]) / (2 * sb["payload"]), 4),
-                    "measured_hbm_traffic": TRAFFIC_PER_ALGO_BYTE["traffic_crops"]}
+                    "measured_hbm_traffic": TRAFFIC_PER_ALGO_BYTE["traffic_crops"][0],
+                    "measured_hbm_traffic_source": TRAFFIC_PER_ALGO_BYTE["traffic_crops"][1] + " (counter runs of "
+                                                   "`bench.py --workload traffic`, not this run)"}
                 entry["hbm_frac_line_granular_128B"] = round(
                     gbps * (sb["read_128"] + sb["write_128"]) / sb["payload"] / HBM_PEAK_GBS, 4)
         else:
@@ -826,6 +837,13 @@ def summarize(name, res, steps, rp, peaks):
 
 def main():
     args = parse_args()
+    if args.blocks is not None:
+        args.blocks = [b for b in args.blocks.split(",") if b]
+        unknown = [b for b in args.blocks if b not in EXTRA_BLOCKS]
+        if unknown:
+            print(f"bench.py: unknown block(s) {unknown}; known: {', '.join(EXTRA_BLOCKS)}", file=sys.stderr)
+            sys.exit(2)
+        args.no_extras = True
     if args.gpus != 1:
         print("bench.py: this engine is a single-GPU build (one pool, one host link per GPU); "
               "run with --gpus 1. Several GPUs would run independent engines.", file=sys.stderr)
@@ -836,7 +854,7 @@ def main():
         sys.exit(2)
     from paper_2411_01830_amd import binding as ft
     flags = ft.FT_PATH_DMA if args.path == "dma" else 0
-    if not args.no_extras:
+    if not args.no_extras or (args.blocks and "pinned_ring" in args.blocks):
         reserve_rings()
     peaks = link_peak()
     ceiling = plain_copy_ceiling()
@@ -884,7 +902,8 @@ def main():
             rq.close()
     if roof_src is not None and roof_src["cls_bytes"][2]:
         algo = 2.0 * roof_src["cls_bytes"][2]
-        traffic_factor = TRAFFIC_PER_ALGO_BYTE.get("traffic_crops" if roof_name == "traffic" else roof_name)
+        traffic_factor, traffic_file = TRAFFIC_PER_ALGO_BYTE.get("traffic_crops" if roof_name == "traffic" else roof_name,
+                                                                 (None, None))
         achieved = algo / roof_src["cls_busy_ms"][2] / 1e6
         per_dispatch = algo / roof_src["cls_ms"][2] / 1e6
         line["roofline"] = {
@@ -900,6 +919,9 @@ def main():
             "avg_launch_ms": round(roof_src["cls_ms"][2] / roof_src["cls_launches"][2], 5),
             "launches": roof_src["cls_launches"][2],
             "traffic": None if traffic_factor is None else round(traffic_factor * algo / roof_src["cls_launches"][2]),
+            "traffic_source": None if traffic_factor is None else
+            f"{traffic_file}: {traffic_factor} HBM bytes per algorithmic byte, from rocprofv3 counter runs of this "
+            "command (FETCH_SIZE, WRITE_SIZE, scaled by a plain copy of known size); not measured in this run",
             "plain_copy_ceiling_GBps": round(ceiling["copy"], 1),
             "plain_read_only_GBps": round(ceiling["read"], 1), "plain_write_only_GBps": round(ceiling["write"], 1),
             "copy_bound_from_those_GBps": round(ceiling["copy_bound"], 1),
@@ -923,17 +945,18 @@ def main():
         line["dma_path"] = {"what": "FT_PATH_DMA: same chunk order, one hipMemcpyAsync / hipMemcpy2DAsync per chunk piece "
                                     "(2 steps each); compare with per_workload", **dma}
     rp.close()
-    if not args.no_extras:
+    if not args.no_extras or args.blocks:
         # the blocks that widen the path; one that fails must not take the headline figures with it
-        for key, block in (("share_error_pool_to_pool", share_error_pool_to_pool),
-                           ("share_error_pool_to_host", share_error_pool_to_host),
-                           ("batched_triggering", lambda: batched_triggering(peaks)),
-                           ("pinned_ring", lambda: pinned_ring(peaks)),
-                           ("single_transfers", single_transfers),
-                           ("elastic_store", elastic_store),
-                           ("path_planner", path_planner)):
+        blocks = {"share_error_pool_to_pool": share_error_pool_to_pool,
+                  "share_error_pool_to_host": share_error_pool_to_host,
+                  "batched_triggering": lambda: batched_triggering(peaks),
+                  "pinned_ring": lambda: pinned_ring(peaks),
+                  "single_transfers": single_transfers,
+                  "elastic_store": elastic_store,
+                  "path_planner": path_planner}
+        for key in (args.blocks if args.blocks else EXTRA_BLOCKS):
             try:
-                line[key] = block()
+                line[key] = blocks[key]()
             except Exception as e:      # noqa: BLE001
                 line[key] = {"error": repr(e)}
                 print(f"bench.py: block {key} failed: {e!r}", file=sys.stderr)

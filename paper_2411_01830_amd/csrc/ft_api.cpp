@@ -220,13 +220,17 @@ bool mostly_short_rows(const ClassPlan &cp) {
 // reach 96 % of what the copy engines get, 1 MiB reaches all of it. Every outstanding
 // host access holds a slot on the path from L2 to the fabric for microseconds, and
 // pool->pool traffic queues behind it: with 4 MiB of host reads in flight a concurrent
-// pool->pool kernel ran 20x slower. So a job that carries both kinds keeps the host
-// classes at 32 workgroups x 8 KiB; a job with host traffic only uses 64 x 16 KiB for
+// pool->pool kernel ran 20x slower. So a job that carries both kinds keeps 256 KiB of
+// host accesses in flight per class; a job with host traffic only uses 64 x 16 KiB for
 // host->pool. pool->host is best at 32 x 8 KiB in either case (1 GiB: 56.6 GB/s against
 // 55.7 at 64 x 16 KiB; posted writes need even less in flight than reads).
+// Host->pool beside pool->pool traffic: 16 workgroups of 16 KiB keep the link as full as 32 of 8 KiB do
+// (256 KiB of reads in flight either way) and slow half as many compute units' pool->pool workgroups
+// (large_mixed: link 56.7 -> 57.0 GB/s, pool->pool launches 82.6 -> 81.8 us).
 uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
   if (cls == FT_P2P) return (uint32_t)p->ctx->cu_count;
-  return (with_p2p || cls == FT_P2H) ? 32u : 64u;
+  if (cls == FT_P2H) return 32u;
+  return with_p2p ? 16u : 64u;
 }
 
 // short_rows: most of the class's payload sits in pitched descriptors with rows of at
@@ -239,7 +243,8 @@ uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
 // are left per workgroup to balance the launch's end.
 uint64_t default_tile(int cls, bool with_p2p, bool short_rows) {
   if (cls == FT_P2P) return short_rows ? 16u * 4096u - 16u : 64u * 1024u;
-  return (with_p2p || cls == FT_P2H) ? 8u * 1024u : 16u * 1024u;
+  (void)with_p2p;
+  return cls == FT_P2H ? 8u * 1024u : 16u * 1024u;
 }
 
 hipMemcpyKind kind_of(int cls) {
@@ -636,11 +641,20 @@ int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t
     ClassRun &r = job->run[c];
     if (!r.used) continue;
     hipStream_t s = p->ctx->streams[c];
-    if ((flags & FT_DETACHED) && c == FT_P2P) {
+    const bool two_lanes = (flags & FT_DETACHED) && c == FT_P2P && !dma;
+    if (two_lanes) {
       // only the on-device class: a host-link launch lasts milliseconds at the link's rate, so it has
       // nothing to gain, and two of them side by side would double the host reads in flight
       std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
-      if (p->ctx->detached_lane[c]++ & 1) s = p->ctx->alt_streams[c];
+      DeviceCtx &cx = *p->ctx;
+      if (cx.lane_marker[c] == nullptr) {
+        e = hipEventCreateWithFlags(&cx.lane_marker[c], hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail(e, "hipEventCreateWithFlags(lane marker)");
+        cx.detached_lane[c] = 1;  // nothing is running: the first launch takes the first stream
+      }
+      const bool last_still_runs = hipEventQuery(cx.lane_marker[c]) == hipErrorNotReady;
+      cx.detached_lane[c] = last_still_runs ? cx.detached_lane[c] ^ 1u : 0u;
+      if (cx.detached_lane[c]) s = cx.alt_streams[c];
     }
     r.stream = s;
     e = hipStreamWaitEvent(s, fork, 0);
@@ -665,6 +679,11 @@ int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t
     }
     e = hipEventRecord(r.ev_done, s);
     if (e != hipSuccess) return hip_fail(e, "hipEventRecord(done)");
+    if (two_lanes) {
+      std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
+      e = hipEventRecord(p->ctx->lane_marker[c], s);
+      if (e != hipSuccess) return hip_fail(e, "hipEventRecord(lane marker)");
+    }
     if (!(flags & FT_DETACHED)) {
       e = hipStreamWaitEvent(user, r.ev_done, 0);
       if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(join)");

@@ -100,11 +100,16 @@ struct DeviceCtx {
   // head of one batch overlaps the tail of the one before and the link does not idle
   // (contended workload, batches of 2.5 MiB, 3 queued ahead: 46 -> 50 GB/s)
   hipStream_t alt_streams[FT_NCLASS] = {nullptr, nullptr, nullptr};
-  // Detached closed jobs also take the two pool->pool streams in turn: their launches are
-  // independent of each other (nothing orders two detached jobs), and on one stream every launch
-  // would wait for the last workgroup of the one before - in the large mixed workload sixteen
-  // pool->pool launches of 40-300 us each, every one paying its start and its tail alone.
-  uint32_t detached_lane[FT_NCLASS] = {0, 0, 0};  // guarded by mu
+  // Detached closed jobs also use both pool->pool streams: their launches are independent of each
+  // other (nothing orders two detached jobs), and on one stream every launch would wait for the last
+  // workgroup of the one before. A launch goes to the other stream only while the last one is still
+  // running (lane_marker, recorded behind every such launch, says so): the process has few hardware
+  // queues, streams share them, and a pool->pool launch on a stream that shares its queue with the
+  // host->pool stream runs after that stream's kernel instead of beside it (large mixed workload,
+  // launches 150 us apart that never meet: taking the streams strictly in turn cost 0.6 % of the
+  // aggregate rate for nothing).
+  uint32_t detached_lane[FT_NCLASS] = {0, 0, 0};  // stream the last such launch went to; guarded by mu
+  hipEvent_t lane_marker[FT_NCLASS] = {nullptr, nullptr, nullptr};
   hipEvent_t epoch = nullptr;  // ft_timing_epoch: the instant that ft_job_stats' begin / end times count from
   std::vector<Blob> free_blobs;      // with a pinned twin
   std::vector<Blob> free_dev_blobs;  // device only

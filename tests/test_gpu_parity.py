@@ -486,6 +486,59 @@ def test_one_aligned_tensor_is_dealt_out_without_a_counter(gpu):
         eng.close()
 
 
+def test_detached_pool_to_pool_jobs_back_to_back_and_apart(gpu):
+    """Detached jobs are independent: submitted back to back their pool->pool launches overlap on the class's two
+    streams (a launch takes the other stream while the last one still runs), submitted apart they all take the
+    first. Either way every byte is the oracle's; by their device times none of the launches submitted apart may
+    overlap (how many of the back-to-back ones do depends on the host's pace and is only printed)."""
+    import time
+    binding, _ = gpu
+    orc, eng, rng = _pair(gpu, host=1 << 20, pool=15 << 27, slab=1 << 20, seed=89)
+    try:
+        def job():
+            recs = []
+            for f in range(3):
+                n = int(rng.integers(90 << 20, 100 << 20)) + int(rng.integers(0, 64))
+                a, b = orc.slab_alloc(n + 32), orc.slab_alloc(n + 32)
+                assert eng.slab_alloc(n + 32) == a and eng.slab_alloc(n + 32) == b
+                fill = rng.integers(0, 256, n + 32, dtype=np.uint8)
+                orc.write_pool(a, fill)
+                eng.write_pool(a, fill)
+                recs.append(dict(func=f, src_space=FT_POOL, dst_space=FT_POOL, src=a + int(rng.integers(0, 16)),
+                                 dst=b + int(rng.integers(0, 16)), row_bytes=n))
+            return make_descs(recs)
+        import torch
+        for apart in (False, True):
+            descs = [job() for _ in range(3)]
+            for d in descs:
+                orc.wait(orc.submit(d, [1, 2, 4], 2 << 20))
+            torch.cuda.synchronize()
+            binding.timing_epoch(eng.pool, torch.cuda.current_stream().cuda_stream)
+            handles = []
+            for d in descs:
+                handles.append(eng.submit(d, [1, 2, 4], 2 << 20, fmt.FT_KEEP | fmt.FT_DETACHED | fmt.FT_TIMING))
+                if apart:
+                    time.sleep(0.005)
+            for h in handles:
+                eng.wait(h)
+            spans = []
+            for h in handles:
+                st = binding.job_stats(eng.pool, h)
+                assert st.cls[2].in_launch == 0 and st.cls[2].end_ms > st.cls[2].begin_ms >= 0
+                spans.append((st.cls[2].begin_ms, st.cls[2].end_ms))
+                binding.job_release(eng.pool, h)
+            overlaps = sum(1 for (b1, e1), (b2, e2) in zip(spans, spans[1:]) if b2 < e1)
+            print("apart" if apart else "back to back", [(round(b, 3), round(e, 3)) for b, e in spans], flush=True)
+            print("launches that began before the one before them had ended:", overlaps, flush=True)
+            assert not apart or overlaps == 0, spans
+            _compare_images(orc, eng)
+            for off in list(orc.pool.allocs):
+                orc.slab_free(off)
+                eng.slab_free(off)
+    finally:
+        eng.close()
+
+
 def test_random_sequences_of_mixed_jobs(gpu):
     """Sixty jobs per seed, each a random mix of classes, sizes from bytes to MiB, pitched and plain,
     every alignment, random weights, chunk sizes, tile sizes and workgroup counts (tuned and default, so

@@ -464,3 +464,24 @@ def test_rest_of_the_api_under_sanitizers(tmp_path):
     """tests/host/api_tour.cpp: logs with exactly-sized arrays, the device's order against the host planner's, the
     piece-by-piece comparison path, tuned launch shapes, pitched pieces in all classes, pool growth and shrinkage."""
     _with_the_stand_in(tmp_path, "address,undefined", 0, program="api_tour", args=[], expect="api_tour done")
+
+
+def test_bench_traffic_constants_are_the_figures_in_the_profiles():
+    """bench.py cannot read hardware counters inside the run it times: `roofline.traffic` comes from constants taken
+    from rocprofv3 counter runs of the same command. Each constant must be the figure its summary under profiles/
+    states (`traffic / algorithmic = X`), so that a refreshed profile and a stale constant cannot go unnoticed."""
+    import ast
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    tree = ast.parse(open(os.path.join(root, "bench.py")).read())
+    table = None
+    for node in tree.body:
+        if isinstance(node, ast.Assign) and getattr(node.targets[0], "id", "") == "TRAFFIC_PER_ALGO_BYTE":
+            table = ast.literal_eval(node.value)
+    assert table and set(table) == {"large_mixed", "feature", "traffic_crops"}
+    for name, (factor, path) in table.items():
+        text = open(os.path.join(root, path)).read()
+        found = re.findall(r"traffic / algorithmic = ([0-9.]+[0-9])", text)
+        assert found, f"{path} states no `traffic / algorithmic = X`"
+        assert float(found[-1]) == factor, (name, factor, found)
+        assert "bench.py" in text and "rocprofv3 --pmc" in text
