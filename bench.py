@@ -574,18 +574,12 @@ def elastic_store():
     allocation calls themselves against native device allocation."""
     import torch
     from paper_2411_01830_amd import binding as ft
+    from workloads import traces
     rng = np.random.Generator(np.random.PCG64(241101830 + 7))
     # ---- pool sizing
     sizer = ft.Sizer(300 << 20, 0.99, 60.0)
-    horizon, t, events = 3600.0, 0.0, []
-    for f, (rate_quiet, rate_burst, med) in enumerate(((0.002, 4.0, 24 << 20), (0.002, 1.0, 96 << 20), (0.5, 0.5, 6 << 20))):
-        t = 0.0
-        while t < horizon:
-            burst = (t // 300) % 4 == f
-            t += float(rng.exponential(1.0 / (rate_burst if burst else rate_quiet)))
-            size = int(min(max(rng.lognormal(np.log(med), 0.6), 1 << 20), 1 << 30))
-            events.append((t, f, size, int(rng.integers(1, 5 if burst else 2))))
-    events.sort()
+    horizon = 3600.0
+    events = traces.sizing_trace(rng, horizon)
     reserved_sum = held_sum = peak = 0.0
     hits = 0
     last_t, cur, held = 0.0, sizer.target(0.0), 300 << 20
@@ -608,36 +602,11 @@ def elastic_store():
               "requests_fitting_reservation": round(hits / len(events), 3)}
     # ---- migration
     n, look, cap = 2000, 12, 1 << 30
-    sizes = [int(min(max(rng.lognormal(np.log(96 << 20), 0.7), 1 << 20), 512 << 20)) for _ in range(n)]
+    sizes = traces.result_sizes(rng, n, 96 << 20, 0.7, 1 << 20, 512 << 20)
 
     def simulate(policy):
-        objs, stalls, moved = {}, 0, 0
-
-        def view(head, skip=None):
-            return [dict(id=i, bytes=o[0], queue_pos=i - head, resident=o[1]) for i, o in sorted(objs.items()) if i != skip]
-
-        def apply(ev, rl):
-            nonlocal moved
-            for i in ev:
-                objs[i][1] = False
-                moved += objs[i][0]
-            for i in rl:
-                objs[i][1] = True
-                moved += objs[i][0]
-        for i in range(look):
-            apply(ft.migrate_plan(view(0), cap, sizes[i], policy)[0], [])
-            objs[i] = [sizes[i], True]
-        for head in range(n):
-            j = head + look
-            if j < n:
-                apply(ft.migrate_plan(view(head), cap, sizes[j], policy)[0], [])
-                objs[j] = [sizes[j], True]
-            if not objs[head][1]:
-                stalls += 1
-                apply(ft.migrate_plan(view(head, head), cap, sizes[head], policy)[0], [head])
-            del objs[head]
-            apply(*ft.migrate_plan(view(head + 1), cap, 0, policy))
-        return stalls, moved
+        r = traces.two_stage_queue(sizes, cap, look, lambda objs, capacity, incoming: ft.migrate_plan(objs, capacity, incoming, policy))
+        return r["stalls"], r["bytes_out"] + r["bytes_in"]
     qa, lru = simulate(ft.FT_EVICT_QUEUE_AWARE), simulate(ft.FT_EVICT_LRU)
     migration = {"trace": f"{n} requests of a two-stage workflow, producers {look} requests ahead, 1 GiB store, "
                           "lognormal results (median 96 MiB, synthetic)",
@@ -712,13 +681,8 @@ def path_planner():
     """Sec. 6.2, Alg. 1 as a host-side planner (one GPU here, so nothing is moved): bandwidth of the
     parallel paths it finds on two synthetic 8-GPU topologies and what a selection costs."""
     from paper_2411_01830_amd import binding as ft
-    n = 8
-    cube = [[0] * n for _ in range(n)]
-    for a, b in ((0, 3), (1, 2), (4, 7), (5, 6), (0, 4), (1, 5), (2, 6), (3, 7)):
-        cube[a][b] = cube[b][a] = 48
-    for a, b in ((0, 1), (0, 2), (1, 3), (2, 3), (4, 5), (4, 6), (5, 7), (6, 7)):
-        cube[a][b] = cube[b][a] = 24
-    mesh = [[0 if a == b else 64 for b in range(n)] for a in range(n)]
+    from workloads import traces
+    cube, mesh = traces.hybrid_cube_mesh_24_48(), traces.full_mesh(8, 64)
     out = {}
     for name, topo, hops, (s, d) in (("hybrid_cube_mesh_24_48", cube, 0, (0, 3)), ("full_mesh_64", mesh, 3, (0, 5))):
         links = ft.Links(topo, hops)

@@ -160,20 +160,12 @@ def stripe_chunks(path_bw, nchunks):
 
 
 def dgx_v100_like():
-    """8 GPUs in a hybrid cube mesh, links of 24 or 48 GB/s per direction (one or two
-    bricks), 6 bricks per GPU; a synthetic stand-in for the server of the paper's
-    experiments (the text gives only the two link speeds and the non-uniformity)."""
-    n = 8
-    t = [[0] * n for _ in range(n)]
-    double = [(0, 3), (1, 2), (4, 7), (5, 6), (0, 4), (1, 5), (2, 6), (3, 7)]
-    single = [(0, 1), (0, 2), (1, 3), (2, 3), (4, 5), (4, 6), (5, 7), (6, 7)]
-    for (a, b) in double:
-        t[a][b] = t[b][a] = 48
-    for (a, b) in single:
-        t[a][b] = t[b][a] = 24
-    return t
+    """The hybrid-cube-mesh stand-in (links of 24 and 48 GB/s); an input, kept with the other synthetic inputs."""
+    from workloads.traces import hybrid_cube_mesh_24_48
+    return hybrid_cube_mesh_24_48()
 
 
 def xgmi_full_mesh(n=8, bw=64):
-    """Every GPU linked to every other by one link (MI300-class nodes: 7 links per GPU)."""
-    return [[0 if a == b else bw for b in range(n)] for a in range(n)]
+    """Every GPU linked to every other by one link; an input, kept with the other synthetic inputs."""
+    from workloads.traces import full_mesh
+    return full_mesh(n, bw)

@@ -15,8 +15,13 @@ Readings where the text is silent:
   * weights: the share of the weight total, `total` = 64 by default, that
     equals the function's share of the rate sum, rounded half up, at least 1.
     (One unit is then 1/64 of the link.) All arithmetic is IEEE double in the
-    order written here; the HIP library's host code computes the same
-    expression in the same order, so both sides round the same way.
+    order written here. The rule itself fixes the weights only up to the rounding
+    of a quotient that may fall within an ulp of a half: an implementation that
+    evaluates the expression in another order is still correct if every weight
+    differs from these by at most one unit. The library's host code happens to
+    use the same order, so its tests can ask for equality; that is a property of
+    the two implementations as they stand, not of the rule (the pins of this
+    module - hand values, unit invariance - hold for either order).
 
 TEST INFRASTRUCTURE ONLY (see the package docstring).
 """

@@ -103,47 +103,11 @@ def plan_lru(objects, capacity, incoming=0):
 
 
 def simulate_queue(sizes, capacity, lookahead, policy):
-    """A two-stage workflow a -> b under memory pressure (Sec. 7.2's example, at length).
-
-    Request i's first stage a_i stores sizes[i] bytes; its second stage b_i consumes them.
-    The a stages run `lookahead` requests ahead of the b stages: step i = a_{i+lookahead}
-    stores its output (if there is such a request), then b_i runs and its data is dropped.
-    Counts the b stages that found their input on the host (a reload on the critical
-    path) and the bytes moved out and back. Returns dict(stalls, bytes_out, bytes_in)."""
-    n = len(sizes)
-    objs = {}
-    stalls = bytes_out = bytes_in = 0
-
-    def view(head):
-        return [dict(id=i, bytes=o["bytes"], queue_pos=i - head, resident=o["resident"]) for i, o in sorted(objs.items())]
-
-    def apply(evict, reload):
-        nonlocal bytes_out, bytes_in
-        for i in evict:
-            objs[i]["resident"] = False
-            bytes_out += objs[i]["bytes"]
-        for i in reload:
-            objs[i]["resident"] = True
-            bytes_in += objs[i]["bytes"]
-
-    for i in range(min(lookahead, n)):           # the a stages that are ahead at the start
-        ev, rl = policy(view(0), capacity, sizes[i])
-        apply(ev, [])
-        objs[i] = {"bytes": sizes[i], "resident": True}
-    for head in range(n):
-        j = head + lookahead
-        if j < n:
-            ev, rl = policy(view(head), capacity, sizes[j])
-            apply(ev, [])
-            objs[j] = {"bytes": sizes[j], "resident": True}
-        if not objs[head]["resident"]:           # b_head needs its input now
-            stalls += 1
-            ev, _ = policy([o for o in view(head) if o["id"] != head], capacity, sizes[head])
-            apply(ev, [head])
-        del objs[head]                           # consumed: cleared at once
-        ev, rl = policy(view(head + 1), capacity, 0)
-        apply(ev, rl)
-    return {"stalls": stalls, "bytes_out": bytes_out, "bytes_in": bytes_in}
+    """The two-stage workflow of Sec. 7.2 under memory pressure, run through `policy` (one of the two plans
+    above). The workflow itself - who stores what when, who consumes it - is an input and lives with the other
+    synthetic inputs (workloads.traces.two_stage_queue); the decisions are this module's."""
+    from workloads.traces import two_stage_queue
+    return two_stage_queue(sizes, capacity, lookahead, policy)
 
 
 class Store:
