@@ -838,6 +838,19 @@ __device__ __forceinline__ void deal_out_tiles(const ClassTable &T, uint64_t src
   }
 }
 
+// A barrier for LDS traffic alone: what this wavefront wrote to LDS is there and every wavefront
+// has arrived; outstanding vector memory operations (the tile's stores) are not waited for.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// A barrier behind which every vector memory operation of the workgroup issued before it has
+// completed (its stores are acknowledged). The wavefronts of a workgroup touch disjoint payload
+// bytes, so nothing more is asked of it than that.
+__device__ __forceinline__ void drain_barrier() {
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Persistent workgroups. Workgroup b starts on ticket b and every later ticket comes from
 // the counter (which therefore hands out the tickets from the grid size on; the host never
 // launches more workgroups than there are tickets). When all workgroups of a launch ask
@@ -897,10 +910,8 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
   }
   __syncthreads();
   uint32_t slot = 0;
-  while (true) {
-    const uint64_t t_cur = uniform64(s_work[slot].t);
-    if (t_cur >= T.ntickets) break;
-    const uint64_t fd = uniform64(s_work[slot].fd), fs = uniform64(s_work[slot].fs);
+  uint64_t t_cur = uniform64(s_work[0].t), fd = uniform64(s_work[0].fd), fs = uniform64(s_work[0].fs);
+  while (t_cur < T.ntickets) {
     uint64_t t_begin = 0;
     if (T.log) t_begin = wall_clock64();
     unsigned long long claimed = 0;
@@ -934,11 +945,11 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
     }
     if (lead) {
       // lane 0 holds the counter's answer; all 64 lanes of this wavefront are enabled
-      const uint64_t t_next = T.ticket_base + gridDim.x + uniform64(claimed);
-      const Work next = decode_ticket(T, CT, pc, sc, t_next);
+      const uint64_t t_drawn = T.ticket_base + gridDim.x + uniform64(claimed);
+      const Work next = decode_ticket(T, CT, pc, sc, t_drawn);
       if (tid == 0) {
-        put_work(s_work[slot ^ 1], t_next, next, (uint64_t)kThreads * U * 16);
-        log_decoded(T, t_next, next);
+        put_work(s_work[slot ^ 1], t_drawn, next, (uint64_t)kThreads * U * 16);
+        log_decoded(T, t_drawn, next);
       }
     }
 
@@ -952,8 +963,19 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
         T.log[t_cur].wg = blockIdx.x;
       }
     }
-    __syncthreads();
+    // Two barriers end the tile. The first concerns LDS only (the decoded ticket is there; nobody
+    // waits for stores): behind it every wavefront fetches the next tile's ticket and addresses
+    // while its own stores still drain. The second waits for the stores of the whole workgroup,
+    // and the first load of the next tile follows it directly (0.1 us per tile less between the
+    // last acknowledged store and the first load than with the reads behind a single barrier).
+    lds_barrier();
+    const uint64_t t_next = uniform64(s_work[slot ^ 1].t);
+    const uint64_t fd_next = uniform64(s_work[slot ^ 1].fd), fs_next = uniform64(s_work[slot ^ 1].fs);
+    drain_barrier();
     slot ^= 1;
+    t_cur = t_next;
+    fd = fd_next;
+    fs = fs_next;
   }
   if (T.log && tid == 0) T.wg_log[blockIdx.x].t_exit = wall_clock64();
   if (T.self_reset && tid == 0) {
