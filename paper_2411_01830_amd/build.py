@@ -46,12 +46,14 @@ def check_registers(remarks):
         m = re.search(r"ft_copy_kernelILb1ELi(\d)E", k)
         if m:
             per_class[int(m.group(1))] = up8(v)
-    if sorted(per_class) != [0, 1, 2]:
+    if sorted(per_class) != [0, 1, 2, 3]:
         raise RuntimeError(f"could not read the copy kernels' register counts: {regs}")
     for host in (0, 1):
         if per_class[host] + per_class[2] > 512:
             raise RuntimeError(f"copy kernels no longer fit one CU together: class {host} uses "
                                f"{per_class[host]} registers, pool->pool {per_class[2]}")
+    if 2 * per_class[3] > 512:
+        raise RuntimeError(f"two workgroups of the light pool->pool build no longer fit one CU: {per_class[3]} registers each")
     return per_class
 
 
@@ -73,7 +75,7 @@ def build(verbose=False):
         if src == "ft_kernels.hip":
             per_class = check_registers(res.stderr)
             if verbose:
-                print("registers per lane (host->pool, pool->host, pool->pool):", per_class, flush=True)
+                print("registers per lane (host->pool, pool->host, pool->pool, pool->pool light):", per_class, flush=True)
         else:
             sys.stderr.write(res.stderr)
         objs.append(obj)

@@ -234,15 +234,16 @@ uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
 }
 
 // short_rows: most of the class's payload sits in pitched descriptors with rows of at
-// most 2 KiB (a gather of image crops). Such a tile is bound by latency - a pass of the
-// row-gather routine (4 destination granules per lane, 16 KiB) is one memory round trip -
-// and by what a tile costs whatever its size: its ticket (the counter hands out about 70
-// million tickets a second, all workgroups together, so tiles must not be too small), the
-// decode, the barrier. Tiles of just under 64 KiB measured best on the crops of the
-// traffic workload (58 us; 76 us at 16 KiB, 64 us at 32 KiB); beyond that too few tiles
-// are left per workgroup to balance the launch's end.
+// most 2 KiB (a gather of image crops). Such a job is bound by latency and by what a compute
+// unit's memory pipeline does with windows of 16 bytes at any address, not by HBM: it runs the
+// kernel's light build (blocks of 16 KiB instead of 64 KiB, under 200 registers per lane), two
+// workgroups per compute unit, and a tile costs a few microseconds whatever its size (its
+// ticket - the counter hands out about 70 million a second, all workgroups together -, the
+// decode, the barriers, a memory round trip per piece). Crops of the traffic workload, 512
+// workgroups: 47.7 us at 16 KiB tiles, 39.8 at 26 KiB, 38.1 at 43 KiB, 39.1 at 64 KiB (fewer
+// than two tiles per workgroup are left to balance the launch's end).
 uint64_t default_tile(int cls, bool with_p2p, bool short_rows) {
-  if (cls == FT_P2P) return short_rows ? 16u * 4096u - 16u : 64u * 1024u;
+  if (cls == FT_P2P) return short_rows ? 43u * 1024u : 64u * 1024u;
   (void)with_p2p;
   return cls == FT_P2H ? 8u * 1024u : 16u * 1024u;
 }
@@ -397,7 +398,9 @@ void shape_classes(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chunk_bytes)
     if (cp.nchunks == 0) continue;
     ClassRun &r = job->run[c];
     const Tuning &tn = p->tuning[c];
-    tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
+    const bool short_rows = mostly_short_rows(cp);
+    r.light = c == FT_P2P && short_rows && tn.workgroups == 0;
+    tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, short_rows),
                &r.tile_bytes, &r.tiles_per_chunk);
     build_chunk_table(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk);
     build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &r.table.ntickets);
@@ -524,7 +527,7 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
   const uint64_t ntickets = r.table.ntickets;
   // host->pool: more than 64 tiles of 16 KiB requested at once is more than the link
   // takes (2 MiB as 128 x 16 KiB: 52 us; as 64 workgroups drawing tickets: 43 us)
-  const uint64_t most = only == FT_P2P ? (uint64_t)p->ctx->cu_count : only == FT_H2P ? 64u : 128u;
+  const uint64_t most = only == FT_P2P ? (r.light ? 2u : 1u) * (uint64_t)p->ctx->cu_count : only == FT_H2P ? 64u : 128u;
   // one contiguous, 16-byte aligned transfer: the workgroups share the tiles out themselves (ClassTable::single >= 2)
   const bool direct = cp.funcs.size() == 1 && cp.xfers.size() == 1 && cp.funcs[0].chunk_base == 0 && !(flags & FT_LOG) &&
                       cp.xfers[0].rows == 1 && ((cp.xfers[0].src | cp.xfers[0].dst | cp.xfers[0].row_bytes) & 15) == 0;
@@ -559,7 +562,7 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
   } else {
     T.ticket = p->ctx->counter_pairs + 2 * r.counter_pair;
     T.self_reset = 1;
-    wg = default_workgroups(p, only, only == FT_P2P);
+    wg = (r.light ? 2u : 1u) * default_workgroups(p, only, only == FT_P2P);
     if (wg > ntickets) wg = ntickets;
   }
   r.workgroups = (uint32_t)wg;
@@ -574,9 +577,9 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
   if (r.ev_begin == nullptr) {
     // the done event is bound to the dispatch itself (it fires with the kernel's own completion
     // signal) instead of being a marker queued behind it: 2 us less from submit to the end of wait
-    e = launch_copy(T, only, r.workgroups, user, nullptr, r.ev_done, job->inline_tables.get());
+    e = launch_copy(T, r.light ? kLightPoolToPool : only, r.workgroups, user, nullptr, r.ev_done, job->inline_tables.get());
   } else {
-    e = launch_copy(T, only, r.workgroups, user, r.ev_begin, r.ev_end, job->inline_tables.get());
+    e = launch_copy(T, r.light ? kLightPoolToPool : only, r.workgroups, user, r.ev_begin, r.ev_end, job->inline_tables.get());
     if (e == hipSuccess) e = hipEventRecord(r.ev_done, user);
   }
   if (e != hipSuccess) {
@@ -613,7 +616,7 @@ int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t
     if (rc != FT_OK) return fail_submit(p, job, rc);
     ClassTable &T = r.table;
     const Tuning &tn = p->tuning[c];
-    uint64_t wg = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
+    uint64_t wg = tn.workgroups ? tn.workgroups : (r.light ? 2u : 1u) * default_workgroups(p, c, with_p2p);
     if (wg > T.ntickets) wg = T.ntickets;
     r.workgroups = dma ? 0 : (uint32_t)wg;
     if ((flags & FT_LOG) && !dma) {
@@ -674,7 +677,7 @@ int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t
         if (e != hipSuccess) return hip_fail(e, "hipEventRecord(end)");
       }
     } else {
-      e = launch_copy(r.table, c, r.workgroups, s, r.ev_begin, r.ev_end);
+      e = launch_copy(r.table, r.light ? kLightPoolToPool : c, r.workgroups, s, r.ev_begin, r.ev_end);
       if (e != hipSuccess) return hip_fail(e, "launch_copy");
     }
     e = hipEventRecord(r.ev_done, s);

@@ -34,6 +34,8 @@ struct ClassRun {
   uint64_t tile_bytes = 0;
   uint32_t tiles_per_chunk = 0;
   uint32_t workgroups = 0;
+  // pool->pool job of short pitched rows: the kernel's light build, two workgroups per compute unit
+  bool light = false;
   bool on_user_stream = false;  // launched on the caller's stream, tables in the launch
   hipStream_t stream = nullptr; // the library's stream it runs on otherwise
   int counter_pair = -1;        // its self-resetting counter pair, if it needed a counter

@@ -6,7 +6,12 @@
 
 namespace ft {
 
-// Persistent copy kernel of one link class (0 host->pool, 1 pool->host, 2 pool->pool).
+constexpr int kLightPoolToPool = 3;
+
+// Persistent copy kernel of one link class (0 host->pool, 1 pool->host, 2 pool->pool), or
+// kLightPoolToPool: the pool->pool class in the build of the kernel that moves blocks of 16 KiB
+// instead of 64 KiB and leaves room for two workgroups per compute unit (jobs of short pitched
+// rows, which memory latency bounds, not HBM).
 // Workgroup b starts on ticket b, the counter *T.ticket hands out the following ones: it
 // must be zero when the kernel starts unless workgroups >= the launch's tickets (then its
 // value does not matter). ev_start / ev_stop (both, neither, or ev_stop alone) are events that will

@@ -71,6 +71,7 @@ constexpr uint32_t kThreads = 256;  // 4 wavefronts per workgroup, one workgroup
 // U = 16 (64 KiB blocks, the whole tile in registers). The host-link classes use U = 4:
 // their tiles are 8-16 KiB, and the smaller register footprint lets a host-link
 // workgroup share a CU with a pool->pool workgroup instead of taking the CU for itself.
+// CLS 3 (kLightPoolToPool) is pool->pool with U = 4: two such workgroups fit a CU.
 template <int CLS>
 struct UnrollOf {
   static constexpr uint32_t value = CLS == 2 ? 16u : 4u;
@@ -510,6 +511,35 @@ __device__ __forceinline__ void row_part_store(const RowPart &P, uint32_t tid) {
   }
 }
 
+// Whole rows r0 .. rl of a pitched descriptor, R windows per lane and pass (see copy_rows_windows).
+template <bool NT, uint32_t R>
+__device__ __forceinline__ void move_windows(const Xfer &X, uint64_t r0, uint64_t rl, uint32_t tid) {
+  const uint32_t rb = (uint32_t)X.row_bytes;
+  const uint32_t S = (rb + 15) >> 4;
+  const uint32_t magic = (uint32_t)((1ull << 32) / S) + 1;  // q / S = mulhi(q, magic) or one less
+  const uint32_t Q = (uint32_t)(rl - r0 + 1) * S;
+  const uint64_t sb = X.src + r0 * X.src_pitch, db = X.dst + r0 * X.dst_pitch;
+  for (uint32_t blk = 0; blk < Q; blk += R * kThreads) {
+    u32x4 v[R];
+    uint64_t to[R];
+#pragma unroll
+    for (uint32_t k = 0; k < R; ++k) {
+      uint32_t q = blk + tid + k * kThreads;
+      const bool active = q < Q;
+      q = active ? q : Q - 1;
+      uint32_t i = S == 1 ? q : __umulhi(q, magic);  // (2^32 / 1 + 1 does not fit the magic)
+      i -= (i * S > q) ? 1u : 0u;
+      const uint32_t j = q - i * S;
+      const uint32_t col = j + 1 < S ? j << 4 : rb - 16;
+      v[k] = ld16_any<NT>(sb + (uint64_t)i * X.src_pitch + col);
+      to[k] = active ? db + (uint64_t)i * X.dst_pitch + col : 0;
+    }
+#pragma unroll
+    for (uint32_t k = 0; k < R; ++k)
+      if (to[k] != 0) st16_any<NT>(to[k], v[k]);
+  }
+}
+
 // Rows of 16 .. 4096 bytes between any two pitches (a gather into a packed buffer, a scatter out of
 // one, or pitched on both sides), window by window: a row of rb bytes is ceil(rb / 16) windows of 16 bytes, the last one moved back to end
 // with the row, and a lane moves a window with one load and one store at whatever addresses they
@@ -554,37 +584,19 @@ __device__ __forceinline__ void copy_rows_windows(const Xfer &X, uint64_t p, uin
   row_part_load<NT>(first, tid);
   row_part_load<NT>(last, tid);
   if (r0 <= rl) {
-    // whole rows r0 .. rl
-    const uint32_t S = (rb + 15) >> 4;
-    const uint32_t magic = (uint32_t)((1ull << 32) / S) + 1;  // q / S = mulhi(q, magic) or one less
-    const uint32_t Q = (uint32_t)(rl - r0 + 1) * S;
-    const uint64_t sb = X.src + r0 * X.src_pitch, db = X.dst + r0 * X.dst_pitch;
-    for (uint32_t blk = 0; blk < Q; blk += R * kThreads) {
-      u32x4 v[R];
-      uint64_t to[R];
-#pragma unroll
-      for (uint32_t k = 0; k < R; ++k) {
-        uint32_t q = blk + tid + k * kThreads;
-        const bool active = q < Q;
-        q = active ? q : Q - 1;
-        uint32_t i = S == 1 ? q : __umulhi(q, magic);  // (2^32 / 1 + 1 does not fit the magic)
-        i -= (i * S > q) ? 1u : 0u;
-        const uint32_t j = q - i * S;
-        const uint32_t col = j + 1 < S ? j << 4 : rb - 16;
-        v[k] = ld16_any<NT>(sb + (uint64_t)i * X.src_pitch + col);
-        to[k] = active ? db + (uint64_t)i * X.dst_pitch + col : 0;
-      }
-#pragma unroll
-      for (uint32_t k = 0; k < R; ++k)
-        if (to[k] != 0) st16_any<NT>(to[k], v[k]);
-    }
+    // whole rows r0 .. rl; a lane without a window repeats the last one's load (no load is predicated),
+    // so a short piece takes a pass with fewer loads per lane
+    const uint64_t windows = (rl - r0 + 1) * ((rb + 15) >> 4);
+    if (windows <= 2 * kThreads) move_windows<NT, 2>(X, r0, rl, tid);
+    else if (windows <= 4 * kThreads) move_windows<NT, 4>(X, r0, rl, tid);
+    else move_windows<NT, R>(X, r0, rl, tid);
   }
   row_part_store<NT>(first, tid);
   row_part_store<NT>(last, tid);
 }
 
 // Payload bytes [p, p+take) of a pitched descriptor.
-template <bool NT, uint32_t U>
+template <bool NT, uint32_t U, bool P2P>
 __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid) {
   const uint64_t rb = X.row_bytes;
   const uint64_t pend = p + take;
@@ -592,7 +604,7 @@ __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t ta
   const uint64_t c0 = p - r0 * rb;
   const uint64_t rl = (pend - 1) / rb;
   const uint64_t cl = pend - rl * rb;  // one past the last column in the last row
-  if (U >= 16 && rb >= 16 && rb <= 4096 && take < (1ull << 30)) {
+  if (P2P && rb >= 16 && rb <= 4096 && take < (1ull << 30)) {
     // pool->pool. Ordinary rather than nontemporal accesses: neighbouring windows share memory lines,
     // and such rows come out of frames that several consumers crop (47.2 -> 45.5 us on the crops
     // of the traffic workload)
@@ -899,7 +911,7 @@ __device__ __forceinline__ void drain_barrier() {
 // for the stores and publishes it. Keeping a CU's reads and writes in separate bursts,
 // one workgroup per CU, is what the memory controllers serve fastest.
 //
-// CLS (the link class) selects the block size of the copy routines and gives each
+// CLS (the link class, or kLightPoolToPool) selects the block size of the copy routines and gives each
 // class's kernel a name of its own, so that profiles keep host-link launches and
 // pool->pool launches apart.
 template <bool NT, int CLS>
@@ -967,7 +979,7 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
         Xfer Xn = X;
         if (more) Xn = read_xfer(CT.xfers, ++x);
         if (X.rows == 1) copy_piece<NT, U>(X.dst + p, X.src + p, take, tid);
-        else copy_rows<NT, U>(X, p, take, tid);
+        else copy_rows<NT, U, (CLS >= 2)>(X, p, take, tid);
         pos += take;
         if (more) {
           X = Xn;
@@ -1081,6 +1093,9 @@ hipError_t launch_copy(const ClassTable &T, int link_class, uint32_t workgroups,
     case 0: hipExtLaunchKernelGGL((ft_copy_kernel<true, 0>), grid, block, 0, stream, ev_start, ev_stop, 0, T, B); break;
     case 1: hipExtLaunchKernelGGL((ft_copy_kernel<true, 1>), grid, block, 0, stream, ev_start, ev_stop, 0, T, B); break;
     case 2: hipExtLaunchKernelGGL((ft_copy_kernel<true, 2>), grid, block, 0, stream, ev_start, ev_stop, 0, T, B); break;
+    case kLightPoolToPool:
+      hipExtLaunchKernelGGL((ft_copy_kernel<true, kLightPoolToPool>), grid, block, 0, stream, ev_start, ev_stop, 0, T, B);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

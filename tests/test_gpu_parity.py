@@ -539,6 +539,51 @@ def test_detached_pool_to_pool_jobs_back_to_back_and_apart(gpu):
         eng.close()
 
 
+def test_short_rows_run_the_light_build_two_workgroups_per_unit(gpu):
+    """A pool->pool job whose payload is mostly pitched rows of at most 2 KiB is launched with two workgroups per
+    compute unit (the kernel's light build); one of long rows or contiguous runs with one. Gather into packed
+    buffers, scatter out of them and pitched on both sides, row lengths 16 .. 1000 at every alignment, tiles that cut
+    rows; bytes and order against the oracle."""
+    import torch
+    binding, _ = gpu
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    orc, eng, rng = _pair(gpu, host=1 << 20, pool=1 << 29, slab=1 << 16, seed=97)
+    pyr = random.Random(97)
+    try:
+        for kind in ("gather", "scatter", "both", "long"):
+            recs = []
+            for i in range(32):
+                rb = pyr.choice([4000, 8192]) if kind == "long" else pyr.choice([16, 17, 63, 64, 100, 160, 255, 256, 1000])
+                rows = (1 << 20) // rb + pyr.randrange(7)
+                sp = rb if kind == "scatter" else rb + pyr.choice([1, 16, 48])
+                dp = rb if kind in ("gather", "long") else rb + pyr.choice([3, 16, 40])
+                es, ed = (rows - 1) * sp + rb, (rows - 1) * dp + rb
+                a, b = orc.slab_alloc(es + 32), orc.slab_alloc(ed + 32)
+                assert eng.slab_alloc(es + 32) == a and eng.slab_alloc(ed + 32) == b
+                fill = rng.integers(0, 256, es + 32, dtype=np.uint8)
+                orc.write_pool(a, fill)
+                eng.write_pool(a, fill)
+                recs.append(dict(func=i % 3, src_space=FT_POOL, dst_space=FT_POOL, src=a + pyr.randrange(16),
+                                 dst=b + pyr.randrange(16), row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp))
+            d = make_descs(recs)
+            jo = orc.submit(d, [1, 2, 3], 256 << 10)
+            orc.wait(jo)
+            jg = eng.submit(d, [1, 2, 3], 256 << 10, fmt.FT_VALIDATE | fmt.FT_KEEP)
+            eng.wait(jg)
+            st = binding.job_stats(eng.pool, jg)
+            print(kind, "tickets", st.cls[2].tickets, "workgroups", st.cls[2].workgroups, "tile", st.cls[2].tile_bytes, flush=True)
+            assert st.cls[2].tickets > 2 * cus
+            assert st.cls[2].workgroups == (cus if kind == "long" else 2 * cus), kind
+            assert eng.job_schedule(jg, 2) == orc.job_schedule(jo, 2)
+            binding.job_release(eng.pool, jg)
+            _compare_images(orc, eng)
+            for off in list(orc.pool.allocs):
+                orc.slab_free(off)
+                eng.slab_free(off)
+    finally:
+        eng.close()
+
+
 def test_random_sequences_of_mixed_jobs(gpu):
     """Sixty jobs per seed, each a random mix of classes, sizes from bytes to MiB, pitched and plain,
     every alignment, random weights, chunk sizes, tile sizes and workgroup counts (tuned and default, so
