@@ -532,8 +532,9 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
   const bool direct = cp.funcs.size() == 1 && cp.xfers.size() == 1 && cp.funcs[0].chunk_base == 0 && !(flags & FT_LOG) &&
                       cp.xfers[0].rows == 1 && ((cp.xfers[0].src | cp.xfers[0].dst | cp.xfers[0].row_bytes) & 15) == 0;
   const bool each_its_own = !direct && ntickets <= most;
+  // a job with more tiles than that holds the caller's stream for a while: not what FT_DETACHED asked for
+  if (ntickets > most && (flags & FT_DETACHED)) return FT_OK;
   if (!each_its_own && !direct) {
-    if (flags & FT_DETACHED) return FT_OK;
     std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
     if (p->ctx->free_pairs.empty()) return FT_OK;
     r.counter_pair = (int)p->ctx->free_pairs.back();
