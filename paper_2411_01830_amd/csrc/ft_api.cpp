@@ -628,6 +628,13 @@ int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t
     }
   }
 
+  // A job of one link class that the caller's stream is to wait for anyway runs on that stream itself:
+  // table upload, kernel, done event bound to the dispatch - three runtime calls instead of seven
+  // (no fork event, no wait on either side; the feature job: 57 -> 30 us inside ft_submit_transfers).
+  int nused = 0;
+  for (int c = 0; c < FT_NCLASS; ++c) nused += job->run[c].used ? 1 : 0;
+  const bool straight = nused == 1 && !(flags & FT_DETACHED) && !dma;
+
   // tables (and the zeroed ticket counters) travel on the caller's stream, then fork
   hipEvent_t fork = nullptr;
   rc = get_event(p, false, &fork);
@@ -639,11 +646,24 @@ int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t
   };
   hipError_t e = hipMemcpyAsync(job->tables.dev, job->tables.host, total, hipMemcpyHostToDevice, user);
   if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(tables)");
-  e = hipEventRecord(fork, user);
-  if (e != hipSuccess) return hip_fail(e, "hipEventRecord(fork)");
+  if (!straight) {
+    e = hipEventRecord(fork, user);
+    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(fork)");
+  }
   for (int c = 0; c < FT_NCLASS; ++c) {
     ClassRun &r = job->run[c];
     if (!r.used) continue;
+    if (straight) {
+      r.stream = user;
+      if (timing) {
+        e = launch_copy(r.table, r.light ? kLightPoolToPool : c, r.workgroups, user, r.ev_begin, r.ev_end);
+        if (e == hipSuccess) e = hipEventRecord(r.ev_done, user);
+      } else {
+        e = launch_copy(r.table, r.light ? kLightPoolToPool : c, r.workgroups, user, nullptr, r.ev_done);
+      }
+      if (e != hipSuccess) return hip_fail(e, "launch on the caller's stream");
+      continue;
+    }
     hipStream_t s = p->ctx->streams[c];
     const bool two_lanes = (flags & FT_DETACHED) && c == FT_P2P && !dma;
     if (two_lanes) {
