@@ -303,8 +303,30 @@ def host_window_add(pool, host_base, nbytes):
     _check(_lib.ft_host_window_add(pool, host_base, nbytes), pool)
 
 
+class Transfers:
+    """Descriptors and weights marshalled once, for a submit that is repeated (a server passing the same
+    tensors request after request): the arrays are kept alive here and their addresses are looked up once,
+    which is most of what a small submit costs on the Python side. Give it to submit_transfers in place of
+    the descriptor array, with weights=None."""
+    __slots__ = ("descs", "weights", "d_ptr", "nd", "w_ptr", "nw")
+
+    def __init__(self, descs, weights):
+        self.descs = np.ascontiguousarray(descs)
+        assert self.descs.dtype.itemsize == 64
+        self.weights = np.ascontiguousarray(np.asarray(weights, dtype=np.uint32))
+        self.nd, self.nw = len(self.descs), len(self.weights)
+        self.d_ptr = self.descs.ctypes.data if self.nd else None
+        self.w_ptr = self.weights.ctypes.data if self.nw else None
+
+
 def submit_transfers(pool, descs, weights, chunk_bytes, flags=0, stream=0):
-    """descs: contiguous array of the 64-byte descriptor dtype; weights: uint32 sequence."""
+    """descs: contiguous array of the 64-byte descriptor dtype; weights: uint32 sequence. Or descs: a
+    Transfers object (then weights is None)."""
+    if isinstance(descs, Transfers):
+        job = C.c_uint64()
+        _check(_lib.ft_submit_transfers(pool, descs.d_ptr, descs.nd, descs.w_ptr, descs.nw, chunk_bytes, flags,
+                                        stream, C.byref(job)), pool)
+        return job.value
     if not descs.flags.c_contiguous:
         descs = np.ascontiguousarray(descs)
     assert descs.dtype.itemsize == 64
