@@ -391,8 +391,8 @@ __device__ __forceinline__ uint32_t merge_dword(uint32_t a, uint32_t b, uint32_t
 }
 
 // The gather of the host-link classes, with aligned loads only (the source may be host memory,
-// where an access that straddles granules is two requests on the link). Rows gathered into a contiguous destination
-// (dst_pitch == row_bytes >= 16): payload
+// where an access that straddles granules is two requests on the link). Rows gathered into a
+// contiguous destination (dst_pitch == row_bytes >= 16): payload
 // bytes [p, p+take), take < 2^30, land in one run of destination bytes, so every lane
 // owns whole destination granules and only the first and last granule of the run are
 // partial. A granule holds bytes of at most two source rows: for each of the two pieces
