@@ -592,6 +592,17 @@ int ft_job_log_workgroups(ft_pool *p, ft_job_t job, int link_class, uint32_t *ti
                           uint32_t *nwg_out);
 
 /*
+ * FT_LOG: the compute unit every workgroup of the launch ran on (host array of `wg_cap`
+ * entries; *nwg_out receives the number of workgroups). The values are identifiers, equal for
+ * workgroups that ran on the same unit and otherwise meaningless. Together with the entry and
+ * exit times of ft_job_log_workgroups, which share one clock across launches, they show which
+ * workgroups of two kernels that ran side by side shared a unit (a job with both host-link
+ * and pool->pool traffic runs one kernel per class, Sec. 8: per-direction streams).
+ */
+int ft_job_log_units(ft_pool *p, ft_job_t job, int link_class, uint32_t *unit_out, uint32_t wg_cap,
+                     uint32_t *nwg_out);
+
+/*
  * Launch shape of one class: number of persistent workgroups (0 = default for the
  * device) and bytes per ticket (0 = default; rounded to a multiple of 16 that
  * divides the chunk into equal tiles). Applies to later submits.

@@ -19,7 +19,7 @@ EXPORTS = ["ft_pool_create", "ft_pool_grow", "ft_pool_shrink", "ft_pool_usage", 
            "ft_stripe_chunks", "ft_pool_destroy", "ft_slab_alloc", "ft_slab_free",
            "ft_pool_ptr", "ft_store_create", "ft_store_put", "ft_store_get", "ft_store_done", "ft_store_advance", "ft_store_sync", "ft_store_stats", "ft_store_destroy", "ft_host_window_add", "ft_pageable_window_add", "ft_set_stage_threads", "ft_reserve_rings", "ft_submit_transfers", "ft_submit_static", "ft_submit_merge", "ft_job_reweight", "ft_set_batch",
            "ft_job_arrival", "ft_job_batches", "ft_slo_weights", "ft_wait", "ft_job_done", "ft_timing_epoch", "ft_job_release",
-           "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_jobs", "ft_job_progress", "ft_job_log_workgroups", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
+           "ft_job_stats", "ft_job_schedule", "ft_job_log", "ft_job_log_jobs", "ft_job_progress", "ft_job_log_workgroups", "ft_job_log_units", "ft_set_tuning", "ft_plan_schedule", "ft_plan_tickets",
            "ft_plain_copy", "ft_plain_read", "ft_plain_fill", "ft_strerror", "ft_last_hip_error"]
 
 
@@ -104,6 +104,7 @@ def _load():
         "ft_job_schedule": (i32, [vp, u64, i32, vp, vp, u64, P(u64)]),
         "ft_job_log": (i32, [vp, u64, i32, vp, vp, vp, vp, vp, vp, u64, P(u64)]),
         "ft_job_log_workgroups": (i32, [vp, u64, i32, vp, u64, vp, vp, u32, P(u32)]),
+        "ft_job_log_units": (i32, [vp, u64, i32, vp, u32, P(u32)]),
         "ft_job_log_jobs": (i32, [vp, u64, i32, vp, vp, u64, P(u64)]),
         "ft_job_progress": (i32, [vp, u64, i32, vp, u32, P(u64)]),
         "ft_set_tuning": (i32, [vp, i32, u32, u64]),
@@ -422,6 +423,15 @@ def job_log_workgroups(pool, job, link_class, ntickets):
     _check(_lib.ft_job_log_workgroups(pool, job, link_class, wg.ctypes.data, int(ntickets), t_in.ctypes.data,
                                       t_out.ctypes.data, nwg.value, C.byref(nwg)), pool)
     return wg[:int(ntickets)], t_in[:nwg.value], t_out[:nwg.value]
+
+
+def job_log_units(pool, job, link_class):
+    """Identifier of the compute unit each workgroup of the launch ran on."""
+    nwg = C.c_uint32()
+    _check(_lib.ft_job_log_units(pool, job, link_class, None, 0, C.byref(nwg)), pool)
+    unit = np.zeros(max(nwg.value, 1), np.uint32)
+    _check(_lib.ft_job_log_units(pool, job, link_class, unit.ctypes.data, nwg.value, C.byref(nwg)), pool)
+    return unit[:nwg.value]
 
 
 def set_tuning(pool, link_class, workgroups=0, tile_bytes=0):

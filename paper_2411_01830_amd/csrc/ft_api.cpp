@@ -1191,6 +1191,20 @@ int ft_job_log_workgroups(ft_pool *p, ft_job_t id, int link_class, uint32_t *tic
   return FT_OK;
 }
 
+int ft_job_log_units(ft_pool *p, ft_job_t id, int link_class, uint32_t *unit_out, uint32_t wg_cap, uint32_t *nwg_out) {
+  if (p == nullptr || nwg_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
+  std::lock_guard<std::mutex> lock(p->mu);
+  auto it = p->jobs.find(id);
+  if (it == p->jobs.end() || !it->second->waited || it->second->waiting || !(it->second->flags & FT_LOG))
+    return FT_EINVAL;
+  if (it->second->open) return FT_EINVAL;  // an open sequence keeps the per-ticket record only
+  const ClassRun &r = it->second->run[link_class];
+  *nwg_out = (uint32_t)r.wg_log_host.size();
+  if (unit_out)
+    for (uint32_t w = 0; w < r.wg_log_host.size() && w < wg_cap; ++w) unit_out[w] = r.wg_log_host[w].unit;
+  return FT_OK;
+}
+
 int ft_job_arrival(ft_pool *p, ft_job_t id, int link_class, uint64_t *batch_out) {
   if (p == nullptr || batch_out == nullptr || link_class < 0 || link_class >= FT_NCLASS) return FT_EINVAL;
   std::lock_guard<std::mutex> lock(p->mu);

@@ -882,6 +882,15 @@ __device__ __forceinline__ void deal_out_tiles(const ClassTable &T, uint64_t src
   }
 }
 
+// Which compute unit this wavefront runs on, from the hardware's identification registers: the
+// accelerator die (HW_REG_XCC_ID, 4 bits) above shader engine, shader array and unit (bits 15:8 of
+// HW_REG_HW_ID). Equal values mean the same compute unit; used by the log only.
+__device__ __forceinline__ uint32_t compute_unit_id() {
+  const uint32_t hw = __builtin_amdgcn_s_getreg((8 - 1) << 11 | 8 << 6 | 4);    // HW_ID[15:8]: se_id, sh_id, cu_id
+  const uint32_t die = __builtin_amdgcn_s_getreg((4 - 1) << 11 | 0 << 6 | 20);  // XCC_ID[3:0]
+  return die << 8 | hw;
+}
+
 // A barrier for LDS traffic alone: what this wavefront wrote to LDS is there and every wavefront
 // has arrived; outstanding vector memory operations (the tile's stores) are not waited for.
 __device__ __forceinline__ void lds_barrier() {
@@ -931,7 +940,10 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
     return;
   }
   const bool lead = tid < 64;  // the first wavefront: draws and decodes tickets
-  if (T.log && tid == 0) T.wg_log[blockIdx.x].t_entry = wall_clock64();
+  if (T.log && tid == 0) {
+    T.wg_log[blockIdx.x].t_entry = wall_clock64();
+    T.wg_log[blockIdx.x].unit = compute_unit_id();
+  }
   PhaseCursor pc;
   SkipCursor sc;
   if (lead) {

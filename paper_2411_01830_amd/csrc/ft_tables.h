@@ -91,6 +91,8 @@ struct LogEntry {
 struct WgLogEntry {
   uint64_t t_entry;  // device clock when the workgroup started
   uint64_t t_exit;   // and when it found no ticket left
+  uint32_t unit;     // the compute unit it ran on: die << 8 | shader engine << 5 | shader array << 4 | unit
+  uint32_t _pad;
 };
 
 // Everything one class's kernel needs; passed by value as the kernel argument.

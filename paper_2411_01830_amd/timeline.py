@@ -7,8 +7,9 @@ per-ticket record (begin, end, workgroup) and the per-workgroup record (entry, e
 after the first workgroup's entry each workgroup entered and began its first tile, what a tile takes
 (first, middle, last of a workgroup), the gap between a workgroup's tiles, and the tail - workgroup
 time left idle between a workgroup's exit and the launch's last exit. Workgroups whose tiles are slow
-(median tile more than 1.25 x the launch's median: in a job that also carries host-link traffic these
-are the ones that share a compute unit with a host-link workgroup) are listed apart. Prints markdown.
+(median tile more than 1.25 x the launch's median) are listed apart; where the workload also carries
+host-link traffic the log's compute-unit identifiers say which workgroups of the chosen class ran on a
+unit that a host-link workgroup occupied at the same time, and what their tiles took. Prints markdown.
 The log costs a wait and a barrier per tile, so the launch it describes is a few per cent slower than
 the one bench.py times.
 """
@@ -81,14 +82,25 @@ def main():
     rp = Replay(args.workload, args.workload == "large_mixed")
     rows = []
 
+    raw = []       # (name, per-ticket log, workgroup of each ticket, entry, exit, unit) of the chosen class
+    others = []    # (entry, exit, unit) of every workgroup of the other classes' launches, same clock
+
     def collect(name, pool, job, st):
-        if st.cls[args.cls].payload_bytes == 0:
-            return
-        log = ft.job_log(pool, job, args.cls)
-        wg, t_in, t_out = ft.job_log_workgroups(pool, job, args.cls, len(log["bytes"]))
-        rows.append((name, launch_summary(log, wg, t_in, t_out, st.cls[args.cls].payload_bytes), st.cls[args.cls].device_ms))
+        for c in range(3):
+            if st.cls[c].payload_bytes == 0:
+                continue
+            if c != args.cls:
+                _, t_in, t_out = ft.job_log_workgroups(pool, job, c, 0)
+                others.append((t_in.astype(np.int64), t_out.astype(np.int64), ft.job_log_units(pool, job, c)))
+                continue
+            log = ft.job_log(pool, job, c)
+            wg, t_in, t_out = ft.job_log_workgroups(pool, job, c, len(log["bytes"]))
+            raw.append((name, log, wg, t_in, t_out, ft.job_log_units(pool, job, c)))
+            rows.append((name, launch_summary(log, wg, t_in, t_out, st.cls[c].payload_bytes), st.cls[c].device_ms))
     for i in range(args.steps):
         rows.clear()
+        raw.clear()
+        others.clear()
         rp.step(ft.FT_LOG, collect)
     rp.close()
     print(f"# Timeline of the class-{args.cls} launches of `{args.workload}` (one step, FT_LOG)\n")
@@ -109,6 +121,32 @@ def main():
         tot["span"] += s["span_us"]
         tot["head"] += s["idle_head_us_per_wg"]
         tot["tail"] += s["idle_tail_us_per_wg"]
+    if rows and others:
+        # which workgroups shared a compute unit with a workgroup of another class's kernel while they ran
+        o_in = np.concatenate([o[0] for o in others])
+        o_out = np.concatenate([o[1] for o in others])
+        o_unit = np.concatenate([o[2] for o in others])
+        n_all = n_shared = 0
+        tile_shared, tile_alone, units_seen = [], [], set()
+        for name, log, wg, t_in, t_out, unit in raw:
+            tb, te = log["t_begin_ns"].astype(np.int64), log["t_end_ns"].astype(np.int64)
+            units_seen.update(int(u) for u in unit)
+            for g in range(len(unit)):
+                mine = wg == g
+                if not mine.any():
+                    continue
+                m = (o_unit == unit[g]) & (o_in < int(t_out[g])) & (o_out > int(t_in[g]))
+                n_all += 1
+                d = float(np.median(te[mine] - tb[mine])) / 1e3
+                if m.any():
+                    n_shared += 1
+                    tile_shared.append(d)
+                else:
+                    tile_alone.append(d)
+        print(f"\nCompute units (identifiers from the log): {len(units_seen)} distinct units under the class-{args.cls} workgroups, "
+              f"{len(set(int(u) for u in o_unit))} under the other classes' workgroups. Of {n_all} class-{args.cls} workgroups, {n_shared} "
+              f"ran on a unit that a workgroup of another class occupied at the same time"
+              + (f": their median tile {np.median(tile_shared):.2f} us, the others' {np.median(tile_alone):.2f} us." if tile_shared and tile_alone else "."))
     if rows:
         print(f"\nAll launches: {tot['bytes']:.1f} MB in {tot['span']:.1f} us of kernel span = "
               f"{2 * tot['bytes'] / tot['span']:.2f} TB/s read+write; workgroup time idle at the head "

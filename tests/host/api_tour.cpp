@@ -141,6 +141,8 @@ int main() {
         CHECK(ft_job_log_workgroups(pool, job, c, nullptr, 0, nullptr, nullptr, 0, &nwg) == FT_OK && nwg == st.cls[c].workgroups);
         std::vector<uint64_t> t_in(nwg), t_out(nwg);
         CHECK(ft_job_log_workgroups(pool, job, c, wg.data(), nt, t_in.data(), t_out.data(), nwg, &nwg) == FT_OK);
+        std::vector<uint32_t> units(nwg);  // exactly as many as promised
+        CHECK(ft_job_log_units(pool, job, c, units.data(), nwg, &nwg) == FT_OK && nwg == st.cls[c].workgroups);
         for (uint64_t t = 0; t < nt; ++t) CHECK(wg[t] < nwg);
       }
     }

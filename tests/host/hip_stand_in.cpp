@@ -163,7 +163,10 @@ hipError_t launch_copy(const ClassTable &T, int, uint32_t workgroups, hipStream_
   FAIL_POINT("launch_copy", hipErrorLaunchFailure);
   const Tables tb = tables_of(T, blob);
   if (T.log)
-    for (uint32_t g = 0; g < workgroups; ++g) T.wg_log[g].t_entry = g_clock++;
+    for (uint32_t g = 0; g < workgroups; ++g) {
+      T.wg_log[g].t_entry = g_clock++;
+      T.wg_log[g].unit = g % 256;
+    }
   for (uint64_t t = T.ticket_base; t < T.ntickets; ++t) {
     uint64_t rank, ti, b0, b1, c0;  // c0: stream offset of the chunk's first byte
     uint32_t x = 0, log_fl = 0;

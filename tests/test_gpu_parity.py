@@ -587,6 +587,40 @@ def test_short_rows_run_the_light_build_two_workgroups_per_unit(gpu):
         eng.close()
 
 
+def test_log_names_the_compute_unit_of_every_workgroup(gpu):
+    """FT_LOG also records where a workgroup ran. A pool->pool launch of as many workgroups as the device has
+    compute units occupies every unit once (two such workgroups do not fit one unit: a tile lives in registers);
+    the light build for short rows occupies every unit twice."""
+    import torch
+    from collections import Counter
+    binding, _ = gpu
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    orc, eng, rng = _pair(gpu, host=1 << 20, pool=3 << 27, slab=1 << 20, seed=101)
+    try:
+        n = 96 << 20
+        a, b = orc.slab_alloc(n), orc.slab_alloc(n)
+        assert eng.slab_alloc(n) == a and eng.slab_alloc(n) == b
+        fill = rng.integers(0, 256, n, dtype=np.uint8)
+        orc.write_pool(a, fill)
+        eng.write_pool(a, fill)
+        for rows, rb, per_unit in ((1, n // 2, 1), (n // 2 // 200, 200, 2)):
+            recs = [dict(func=f, src_space=FT_POOL, dst_space=FT_POOL, src=a + f * (n // 2) + 3, dst=b + f * (n // 2) + 5,
+                         row_bytes=rb - 16, rows=rows, src_pitch=rb, dst_pitch=rb - 16) for f in range(2)]
+            d = make_descs(recs)
+            orc.wait(orc.submit(d, [1, 2], 2 << 20))
+            jg = eng.submit(d, [1, 2], 2 << 20, fmt.FT_LOG)
+            eng.wait(jg)
+            st = binding.job_stats(eng.pool, jg)
+            units = binding.job_log_units(eng.pool, jg, 2)
+            assert len(units) == st.cls[2].workgroups == per_unit * cus
+            count = Counter(int(u) for u in units)
+            assert len(count) == cus and set(count.values()) == {per_unit}, sorted(count.values())[-4:]
+            binding.job_release(eng.pool, jg)
+            _compare_images(orc, eng)
+    finally:
+        eng.close()
+
+
 def test_random_sequences_of_mixed_jobs(gpu):
     """Sixty jobs per seed, each a random mix of classes, sizes from bytes to MiB, pitched and plain,
     every alignment, random weights, chunk sizes, tile sizes and workgroup counts (tuned and default, so
