@@ -677,7 +677,8 @@ int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t
         cx.detached_lane[c] = 1;  // nothing is running: the first launch takes the first stream
       }
       const bool last_still_runs = hipEventQuery(cx.lane_marker[c]) == hipErrorNotReady;
-      cx.detached_lane[c] = last_still_runs ? cx.detached_lane[c] ^ 1u : 0u;
+      const bool host_link_busy = cx.hostlink_marker != nullptr && hipEventQuery(cx.hostlink_marker) == hipErrorNotReady;
+      cx.detached_lane[c] = last_still_runs && !host_link_busy ? cx.detached_lane[c] ^ 1u : 0u;
       if (cx.detached_lane[c]) s = cx.alt_streams[c];
     }
     r.stream = s;
@@ -707,6 +708,16 @@ int launch_with_uploaded_tables(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t
       std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
       e = hipEventRecord(p->ctx->lane_marker[c], s);
       if (e != hipSuccess) return hip_fail(e, "hipEventRecord(lane marker)");
+    }
+    if (c != FT_P2P && !dma && (flags & FT_DETACHED)) {
+      // a host-link kernel that detached pool->pool launches may meet: say when it is over
+      std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
+      if (p->ctx->hostlink_marker == nullptr) {
+        e = hipEventCreateWithFlags(&p->ctx->hostlink_marker, hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail(e, "hipEventCreateWithFlags(host-link marker)");
+      }
+      e = hipEventRecord(p->ctx->hostlink_marker, s);
+      if (e != hipSuccess) return hip_fail(e, "hipEventRecord(host-link marker)");
     }
     if (!(flags & FT_DETACHED)) {
       e = hipStreamWaitEvent(user, r.ev_done, 0);

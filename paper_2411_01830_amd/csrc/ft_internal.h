@@ -112,6 +112,10 @@ struct DeviceCtx {
   // aggregate rate for nothing).
   uint32_t detached_lane[FT_NCLASS] = {0, 0, 0};  // stream the last such launch went to; guarded by mu
   hipEvent_t lane_marker[FT_NCLASS] = {nullptr, nullptr, nullptr};
+  // recorded behind every host-link kernel of a closed job: while one of them runs, a pool->pool
+  // launch stays on the first stream (the second may share its hardware queue with a host-link
+  // stream, and would then wait milliseconds for that kernel instead of overlapping a tail)
+  hipEvent_t hostlink_marker = nullptr;
   hipEvent_t epoch = nullptr;  // ft_timing_epoch: the instant that ft_job_stats' begin / end times count from
   std::vector<Blob> free_blobs;      // with a pinned twin
   std::vector<Blob> free_dev_blobs;  // device only

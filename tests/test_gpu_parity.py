@@ -621,6 +621,53 @@ def test_log_names_the_compute_unit_of_every_workgroup(gpu):
         eng.close()
 
 
+def test_a_detached_pool_to_pool_job_does_not_wait_for_another_jobs_host_link_kernel(gpu):
+    """Job A carries 128 MiB host->pool (2 ms on the link) and 1 GiB pool->pool, job B, submitted right behind it, 64 MiB
+    pool->pool; both detached. B's launch may queue behind A's pool->pool launch but must be over long before A's
+    host->pool kernel is: the library's streams share the process's few hardware queues, and a pool->pool launch put
+    on a stream that shares one with the host->pool stream would run after that kernel instead of beside it."""
+    import torch
+    binding, _ = gpu
+    MiB = 1 << 20
+    orc, eng, rng = _pair(gpu, host=256 * MiB, pool=2432 * MiB, slab=MiB, seed=103)
+    try:
+        def alloc(n, fill):
+            a = orc.slab_alloc(n)
+            assert eng.slab_alloc(n) == a
+            if fill:
+                data = rng.integers(0, 256, n, dtype=np.uint8)
+                orc.write_pool(a, data)
+                eng.write_pool(a, data)
+            return a
+        h_dst, a_src, a_dst = alloc(128 * MiB, False), alloc(1024 * MiB, True), alloc(1024 * MiB, False)
+        b_src, b_dst = alloc(64 * MiB, True), alloc(64 * MiB, False)
+        job_a = make_descs([dict(func=0, src_space=FT_HOST, dst_space=FT_POOL, src=0, dst=h_dst, row_bytes=128 * MiB),
+                            dict(func=1, src_space=FT_POOL, dst_space=FT_POOL, src=a_src, dst=a_dst, row_bytes=1024 * MiB)])
+        job_b = make_descs([dict(func=0, src_space=FT_POOL, dst_space=FT_POOL, src=b_src, dst=b_dst, row_bytes=32 * MiB),
+                            dict(func=1, src_space=FT_POOL, dst_space=FT_POOL, src=b_src + 32 * MiB, dst=b_dst + 32 * MiB,
+                                 row_bytes=32 * MiB)])
+        for d in (job_a, job_b):
+            orc.wait(orc.submit(d, [1, 1], 2 * MiB))
+        for attempt in range(2):        # the first pass also pays for first touches of fresh memory
+            torch.cuda.synchronize()
+            binding.timing_epoch(eng.pool, torch.cuda.current_stream().cuda_stream)
+            flags = fmt.FT_KEEP | fmt.FT_DETACHED | fmt.FT_TIMING
+            ja = eng.submit(job_a, [1, 1], 2 * MiB, flags)
+            jb = eng.submit(job_b, [1, 1], 2 * MiB, flags)
+            eng.wait(ja)
+            eng.wait(jb)
+            sa, sb = binding.job_stats(eng.pool, ja), binding.job_stats(eng.pool, jb)
+            binding.job_release(eng.pool, ja)
+            binding.job_release(eng.pool, jb)
+        print("A host->pool", round(sa.cls[0].begin_ms, 3), round(sa.cls[0].end_ms, 3), "A pool->pool", round(sa.cls[2].begin_ms, 3),
+              round(sa.cls[2].end_ms, 3), "B pool->pool", round(sb.cls[2].begin_ms, 3), round(sb.cls[2].end_ms, 3), flush=True)
+        assert sa.cls[0].end_ms - sa.cls[0].begin_ms > 1.5
+        assert sb.cls[2].end_ms < sa.cls[0].begin_ms + 0.5 * (sa.cls[0].end_ms - sa.cls[0].begin_ms)
+        _compare_images(orc, eng)
+    finally:
+        eng.close()
+
+
 def test_random_sequences_of_mixed_jobs(gpu):
     """Sixty jobs per seed, each a random mix of classes, sizes from bytes to MiB, pitched and plain,
     every alignment, random weights, chunk sizes, tile sizes and workgroup counts (tuned and default, so
