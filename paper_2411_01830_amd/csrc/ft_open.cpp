@@ -628,6 +628,12 @@ bool prepare_batch(OpenState *st, int c, Prepared *out) {
 hipError_t launch_batch(ft_pool *p, int c, Prepared &pr) {
   OpenBatch &b = pr.batch;
   hipStream_t s = b.lane ? p->ctx->alt_streams[c] : p->ctx->streams[c];
+  if (c == FT_P2P && b.lane) {
+    // the class's second stream may share its hardware queue with a host-link stream: while a host-link
+    // kernel of a detached closed job runs, the batch queues behind its predecessor instead
+    std::lock_guard<std::mutex> ctx_lock(p->ctx->mu);
+    if (p->ctx->hostlink_marker != nullptr && hipEventQuery(p->ctx->hostlink_marker) == hipErrorNotReady) s = p->ctx->streams[c];
+  }
   hipError_t e = hipSuccess;
   if (pr.wait_upload) e = hipStreamWaitEvent(s, b.gen->uploaded, 0);
   if (e == hipSuccess) e = launch_copy(pr.T, c, pr.workgroups, s, b.t_begin, b.t_end);
