@@ -186,3 +186,39 @@ def test_transfers_larger_than_four_gib(route):
         ft.pool_destroy(pool)
         del buf
         torch.cuda.empty_cache()
+
+
+def test_one_aligned_tensor_larger_than_four_gib():
+    """The route on which the workgroups deal the tiles of one aligned tensor out among themselves, beyond 4 GiB:
+    tile numbers times tile bytes need their upper 32 bits. Destination against source on the device, canaries either
+    side; a length that leaves a ragged last tile."""
+    import torch
+    from paper_2411_01830_amd import binding as ft
+    GiB = 1 << 30
+    n = 4 * GiB + 5 * (1 << 20) + 4096 + 48
+    slab = 1 << 20
+    size = (n + 64 + slab - 1) // slab * slab
+    buf = torch.empty(2 * size, dtype=torch.uint8, device="cuda:0")
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(4343)
+    step = 1 << 28
+    for o in range(0, size, step):
+        m = min(step, size - o)
+        buf[o:o + m] = torch.randint(0, 256, (m,), dtype=torch.uint8, device="cuda:0", generator=g)
+    buf[size:] = 0xA5
+    pool = ft.pool_create(buf.data_ptr(), 2 * size, slab, 0)
+    try:
+        a, b = ft.slab_alloc(pool, size), ft.slab_alloc(pool, size)
+        d = make_descs([dict(func=0, src_space=FT_POOL, dst_space=FT_POOL, src=a + 16, dst=b + 32, row_bytes=n)])
+        print("one aligned tensor beyond 4 GiB", flush=True)
+        job = ft.submit_transfers(pool, d, [1], 2 << 20, ft.FT_KEEP, torch.cuda.current_stream().cuda_stream)
+        ft.wait(pool, job)
+        st = ft.job_stats(pool, job)
+        assert st.cls[2].in_launch == 1 and st.cls[2].workgroups < st.cls[2].tickets
+        assert torch.equal(buf[b + 32:b + 32 + n], buf[a + 16:a + 16 + n])
+        assert bool((buf[b:b + 32] == 0xA5).all()) and bool((buf[b + 32 + n:b + size] == 0xA5).all())
+        ft.job_release(pool, job)
+    finally:
+        ft.pool_destroy(pool)
+        del buf
+        torch.cuda.empty_cache()
