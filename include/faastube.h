@@ -248,8 +248,8 @@ int ft_set_stage_threads(ft_pool *p, uint32_t threads);
  * most one tile per workgroup (256 tiles pool->pool, 64 host->pool, 128 pool->host) it
  * needs no counter; a larger one takes one of 256 self-clearing counter pairs per device
  * (and the ordinary route if none is free or if FT_DETACHED is set, since the job holds
- * hip_stream like any kernel on it). One contiguous transfer whose two sides and length
- * are multiples of 16 (Sec. 5.1: passing one tensor) needs neither: its tiles are dealt
+ * hip_stream like any kernel on it). One contiguous transfer between 16-byte aligned
+ * addresses (Sec. 5.1: passing one tensor) needs neither: its tiles are dealt
  * out round robin among the workgroups. Any other job of a single link class without
  * FT_DETACHED also runs on hip_stream itself, its tables copied to the device ahead of it
  * on that stream (the stream was to wait for the job anyway).

@@ -528,9 +528,10 @@ int launch_with_the_launch(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chun
   // host->pool: more than 64 tiles of 16 KiB requested at once is more than the link
   // takes (2 MiB as 128 x 16 KiB: 52 us; as 64 workgroups drawing tickets: 43 us)
   const uint64_t most = only == FT_P2P ? (r.light ? 2u : 1u) * (uint64_t)p->ctx->cu_count : only == FT_H2P ? 64u : 128u;
-  // one contiguous, 16-byte aligned transfer: the workgroups share the tiles out themselves (ClassTable::single >= 2)
+  // one contiguous transfer between 16-byte aligned addresses (any length): the workgroups share the tiles out
+  // themselves (ClassTable::single >= 2)
   const bool direct = cp.funcs.size() == 1 && cp.xfers.size() == 1 && cp.funcs[0].chunk_base == 0 && !(flags & FT_LOG) &&
-                      cp.xfers[0].rows == 1 && ((cp.xfers[0].src | cp.xfers[0].dst | cp.xfers[0].row_bytes) & 15) == 0;
+                      cp.xfers[0].rows == 1 && ((cp.xfers[0].src | cp.xfers[0].dst) & 15) == 0;
   const bool each_its_own = !direct && ntickets <= most;
   // a job with more tiles than that holds the caller's stream for a while: not what FT_DETACHED asked for
   if (ntickets > most && (flags & FT_DETACHED)) return FT_OK;

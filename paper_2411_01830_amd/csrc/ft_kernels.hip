@@ -857,7 +857,8 @@ __device__ __forceinline__ void get_work(const WorkSlot &slot, Work &w) {
   w.first.staged = 0;  // already applied
 }
 
-// The tiles of one contiguous, 16-byte aligned transfer, dealt out round robin among the workgroups.
+// The tiles of one contiguous transfer whose two sides are 16-byte aligned, dealt out round robin among
+// the workgroups.
 template <bool NT, uint32_t U>
 __device__ __forceinline__ void deal_out_tiles(const ClassTable &T, uint64_t src, uint64_t dst, uint64_t nbytes, uint32_t tid) {
   for (uint64_t v = blockIdx.x; v < T.ntickets; v += gridDim.x) {
@@ -876,7 +877,8 @@ __device__ __forceinline__ void deal_out_tiles(const ClassTable &T, uint64_t src
     if (b1 > nbytes) b1 = nbytes;
     if (b0 < b1) {
       if (b1 - b0 == (uint64_t)kThreads * U * 16) copy_rows_of_vectors<NT, U>(dst + b0, src + b0, tid);
-      else copy_vectors<NT, U>(dst + b0, src + b0, (b1 - b0) >> 4, tid);
+      else if (((b1 - b0) & 15) == 0) copy_vectors<NT, U>(dst + b0, src + b0, (b1 - b0) >> 4, tid);
+      else copy_piece<NT, U>(dst + b0, src + b0, b1 - b0, tid);  // the tensor's last tile, a length that is no multiple of 16
     }
     __syncthreads();  // keeps a workgroup's loads and stores in separate bursts, as in the ticket loop
   }
@@ -930,7 +932,7 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
   const uint32_t tid = threadIdx.x;
   const ConstTables CT = const_tables(T);
   if (T.single >= 2) {
-    // One contiguous transfer, both sides and the length multiples of 16, nothing to record:
+    // One contiguous transfer, both sides multiples of 16, nothing to record:
     // passing a single tensor. With one function there is nothing to interleave - ticket t is
     // tile t of the one stream - so the tiles are dealt out round robin, workgroup b taking
     // tiles b, b + workgroups, ...: no counter, no decode by one wavefront for the others, no

@@ -149,7 +149,7 @@ struct ClassTable {
   // 1: one function with one descriptor (xfers[0]) and no chunks triggered before: tile v
   // is stream bytes [v / tiles_per_chunk * chunk_bytes + v % tiles_per_chunk * tile_bytes, ...)
   // of that descriptor and ticket t is tile t, so the decode reads no schedule table.
-  // 2: moreover the descriptor is contiguous, its two sides and its length are multiples of 16
+  // 2: moreover the descriptor is contiguous, its two sides are multiples of 16
   // and nothing is logged: the workgroups deal the tiles out among themselves round robin.
   // 3: as 2, with ordinary instead of nontemporal loads and stores (a tensor small enough to
   // stay in the last-level cache between its producer and its consumer)

@@ -435,7 +435,7 @@ def test_larger_single_class_jobs_reuse_the_self_resetting_counters(gpu):
 
 
 def test_one_aligned_tensor_is_dealt_out_without_a_counter(gpu):
-    """One contiguous transfer whose two sides and length are multiples of 16 and which has more tiles than
+    """One contiguous transfer between 16-byte aligned addresses (its length may be anything) which has more tiles than
     workgroups: the workgroups deal the tiles out round robin, no counter (Sec. 5.1: passing one tensor).
     Every class, lengths with a ragged last tile and a ragged last chunk, chunk sizes that are not a
     multiple of the tile, with and without timing; detached, such a job takes the ordinary route instead (it would
@@ -445,8 +445,8 @@ def test_one_aligned_tensor_is_dealt_out_without_a_counter(gpu):
     try:
         case = 0
         for cls in (0, 1, 2):
-            sizes = [17 << 20, (20 << 20) + 4096 + 16, (33 << 20) - 16] if cls == 2 else \
-                    [3 << 20, (5 << 20) + 48, (9 << 20) - 16]
+            sizes = [17 << 20, (20 << 20) + 4096 + 16, (33 << 20) - 9] if cls == 2 else \
+                    [3 << 20, (5 << 20) + 48, (9 << 20) - 3]
             for n in sizes:
                 for C in (2 << 20, (1 << 20) + 4096 + 16):
                     a = b = None
