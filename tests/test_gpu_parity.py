@@ -171,6 +171,39 @@ def test_random_pitched_descriptors(gpu):
             eng.close()
 
 
+def test_pitched_rows_at_the_limits_of_the_window_route(gpu):
+    """pool->pool rows of 16 .. 4096 bytes move window by window; rows just outside take the other routines.
+    Every row length at and around both limits and around a window's size, one to many rows (one pass of two,
+    four and eight windows per lane, and several passes), equal and unequal pitches, random byte offsets on
+    either side, and chunks small enough that tile boundaries cut rows. Whole pool image compared (the bytes
+    between the rows of a destination are part of it)."""
+    for seed, C in enumerate((16 * 1024, 1000 * 16, 1 << 21)):
+        orc, eng, rng = _pair(gpu, host=1 << 20, pool=1 << 26, slab=16384, seed=100 + seed)
+        pyr = random.Random(100 + seed)
+        try:
+            recs = []
+            for rb in (15, 16, 17, 31, 32, 33, 47, 48, 4095, 4096, 4097):
+                for rows in (2, 3, 40, 700):
+                    if rb > 4000 and rows > 40:
+                        rows = 300
+                    sp = rb + pyr.choice([0, 1, 48, 333])
+                    dp = rb + pyr.choice([0, 1, 48, 100])
+                    es, ed = (rows - 1) * sp + rb, (rows - 1) * dp + rb
+                    a = orc.slab_alloc(es + 32)
+                    assert eng.slab_alloc(es + 32) == a
+                    fill = rng.integers(0, 256, es + 32, dtype=np.uint8)
+                    orc.write_pool(a, fill)
+                    eng.write_pool(a, fill)
+                    b = orc.slab_alloc(ed + 32)
+                    assert eng.slab_alloc(ed + 32) == b
+                    recs.append(dict(func=len(recs) % 3, src_space=FT_POOL, dst_space=FT_POOL, src=a + pyr.randint(0, 31),
+                                     dst=b + pyr.randint(0, 31), row_bytes=rb, rows=rows, src_pitch=sp, dst_pitch=dp))
+            print(f"window limits seed={seed} descs={len(recs)} C={C}", flush=True)
+            _run_both(orc, eng, recs, [1, 2, 3], C)
+        finally:
+            eng.close()
+
+
 def test_chunk_and_tile_shapes(gpu):
     """Chunks smaller than, equal to and not a multiple of the tile; tuned tile sizes."""
     binding, _ = gpu
