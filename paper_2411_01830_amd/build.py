@@ -28,7 +28,10 @@ def check_registers(remarks):
     """A host-link workgroup and a pool->pool workgroup must fit on one CU together
     (one wavefront of each per SIMD, 512 registers per lane, allocated in eights):
     a job with both kinds of traffic runs the two kernels side by side, and a
-    host-link workgroup that took a CU for itself would idle that CU's share of HBM."""
+    host-link workgroup that took a CU for itself would idle that CU's share of HBM.
+    The limit checked is 480, not 512: builds whose two kernels added up to 488 and 496
+    registers measured 1.2 % less of the host link beside pool->pool launches (large_mixed:
+    99.6 -> 98.3 % of the measured peak), the build at 480 does not."""
     import re
     regs = {}
     name = None
@@ -49,7 +52,7 @@ def check_registers(remarks):
     if sorted(per_class) != [0, 1, 2, 3]:
         raise RuntimeError(f"could not read the copy kernels' register counts: {regs}")
     for host in (0, 1):
-        if per_class[host] + per_class[2] > 512:
+        if per_class[host] + per_class[2] > 480:
             raise RuntimeError(f"copy kernels no longer fit one CU together: class {host} uses "
                                f"{per_class[host]} registers, pool->pool {per_class[2]}")
     if 2 * per_class[3] > 512:
