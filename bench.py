@@ -37,9 +37,9 @@ HBM_PEAK_GBS = 8000.0
 # the line carries these constants and says where they come from (`traffic_source`); tests/test_host_logic.py
 # holds every constant against the figure in its file. Workloads without such a run report null.
 TRAFFIC_PER_ALGO_BYTE = {
-    "large_mixed": (1.0075, "profiles/pmc_hbm_traffic_pool_to_pool_large_mixed.md"),
-    "feature": (1.0012, "profiles/pmc_hbm_traffic_pool_to_pool_feature.md"),
-    "traffic_crops": (1.3745, "profiles/pmc_hbm_traffic_pool_to_pool_traffic_crops.md"),
+    "large_mixed": (1.0077, "profiles/pmc_hbm_traffic_pool_to_pool_large_mixed.md"),
+    "feature": (1.0010, "profiles/pmc_hbm_traffic_pool_to_pool_feature.md"),
+    "traffic_crops": (1.3749, "profiles/pmc_hbm_traffic_pool_to_pool_traffic_crops.md"),
 }
 EXTRA_BLOCKS = ("share_error_pool_to_pool", "share_error_pool_to_host", "batched_triggering", "pinned_ring",
                 "single_transfers", "elastic_store", "path_planner")

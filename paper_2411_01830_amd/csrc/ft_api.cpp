@@ -222,14 +222,18 @@ bool mostly_short_rows(const ClassPlan &cp) {
 // pool->pool traffic queues behind it: with 4 MiB of host reads in flight a concurrent
 // pool->pool kernel ran 20x slower. So a job that carries both kinds keeps 256 KiB of
 // host accesses in flight per class; a job with host traffic only uses 64 x 16 KiB for
-// host->pool. pool->host is best at 32 x 8 KiB in either case (1 GiB: 56.6 GB/s against
-// 55.7 at 64 x 16 KiB; posted writes need even less in flight than reads).
+// host->pool. pool->host, whose stores are written through to the link as they are issued: 64 x
+// 16 KiB for jobs without pool->pool traffic (one 16 MiB tensor 305 us and one of 64 MiB 1187 us,
+// within 1 % of the runtime's copy, against 315 and 1249 us at 32 x 8 KiB; the tiny workload's 32
+// tensors 96 % against 95 % of the link), 8 KiB tiles up to 256 KiB of payload (64 KiB: 12.3 against
+// 12.7 us), and 32 x 8 KiB beside pool->pool traffic, whose workgroups a host-link workgroup on the
+// same compute unit slows down.
 // Host->pool beside pool->pool traffic: 16 workgroups of 16 KiB keep the link as full as 32 of 8 KiB do
 // (256 KiB of reads in flight either way) and slow half as many compute units' pool->pool workgroups
 // (large_mixed: link 56.7 -> 57.0 GB/s, pool->pool launches 82.6 -> 81.8 us).
 uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
   if (cls == FT_P2P) return (uint32_t)p->ctx->cu_count;
-  if (cls == FT_P2H) return 32u;
+  if (cls == FT_P2H) return with_p2p ? 32u : 64u;
   return with_p2p ? 16u : 64u;
 }
 
@@ -242,10 +246,10 @@ uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p) {
 // decode, the barriers, a memory round trip per piece). Crops of the traffic workload, 512
 // workgroups: 47.7 us at 16 KiB tiles, 39.8 at 26 KiB, 38.1 at 43 KiB, 39.1 at 64 KiB (fewer
 // than two tiles per workgroup are left to balance the launch's end).
-uint64_t default_tile(int cls, bool with_p2p, bool short_rows) {
+uint64_t default_tile(int cls, bool with_p2p, bool short_rows, uint64_t payload) {
   if (cls == FT_P2P) return short_rows ? 43u * 1024u : 64u * 1024u;
-  (void)with_p2p;
-  return cls == FT_P2H ? 8u * 1024u : 16u * 1024u;
+  if (cls == FT_P2H) return with_p2p || payload <= 256u * 1024u ? 8u * 1024u : 16u * 1024u;
+  return 16u * 1024u;
 }
 
 hipMemcpyKind kind_of(int cls) {
@@ -400,7 +404,7 @@ void shape_classes(ft_pool *p, Job *job, SubmitPlan &plan, uint64_t chunk_bytes)
     const Tuning &tn = p->tuning[c];
     const bool short_rows = mostly_short_rows(cp);
     r.light = c == FT_P2P && short_rows && tn.workgroups == 0;
-    tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, short_rows),
+    tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, short_rows, cp.payload),
                &r.tile_bytes, &r.tiles_per_chunk);
     build_chunk_table(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk);
     build_skips(cp, chunk_bytes, r.tile_bytes, r.tiles_per_chunk, &r.skips, &r.table.ntickets);

@@ -212,7 +212,8 @@ void fill_class_table(const ClassPlan &cp, const Layout &lay, char *h, char *d, 
                       ClassTable *T);
 
 uint32_t default_workgroups(const ft_pool *p, int cls, bool with_p2p);
-uint64_t default_tile(int cls, bool with_p2p, bool short_rows);
+// payload: bytes of the class in the job (all ones for an open job, whose traffic is not known in advance)
+uint64_t default_tile(int cls, bool with_p2p, bool short_rows, uint64_t payload);
 bool mostly_short_rows(const ClassPlan &cp);
 
 // ft_open.cpp. All but open_wait are called with the pool's mutex held and the pool's

@@ -84,21 +84,33 @@ struct UnrollOf {
 typedef u32x4 FT_GLOBAL *GVecP;
 typedef uint8_t FT_GLOBAL *GByteP;
 
-template <bool NT>
+// How a routine reaches memory, its first template parameter NT: 0 ordinary loads and stores (data that
+// is wanted in the caches); kStream nontemporal loads and stores (payload streaming through HBM once);
+// kToHost nontemporal loads and stores that are written through to the fabric at once (the `sc1` bit)
+// for destinations in host memory. A nontemporal or ordinary store to host memory stays in the L2 until
+// that evicts it or the kernel ends: the tiny workload's pool->host kernel had every store issued after
+// 260 us and then ended 80 us later, when the L2 had written its lines back over the link (50 GB/s);
+// written through, the link carries them while the kernel runs (55 GB/s, what host->pool reaches on the
+// same buffers). `sc0 sc1` measured 53.4 GB/s, `sc0 sc1 nt` 53.5. Towards HBM every other combination
+// of the bits is slower than `nt` alone.
+constexpr int kStream = 1, kToHost = 2;
+
+template <int NT>
 __device__ __forceinline__ u32x4 ld16(uint64_t addr) {
   if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 FT_GLOBAL *>(addr));
   return *reinterpret_cast<const u32x4 FT_GLOBAL *>(addr);
 }
 // 16 bytes from any address (the hardware splits an access that straddles aligned granules).
 typedef uint32_t u32x4_any __attribute__((ext_vector_type(4), aligned(1)));
-template <bool NT>
+template <int NT>
 __device__ __forceinline__ u32x4 ld16_any(uint64_t addr) {
   if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_any FT_GLOBAL *>(addr));
   return *reinterpret_cast<const u32x4_any FT_GLOBAL *>(addr);
 }
-template <bool NT>
+template <int NT>
 __device__ __forceinline__ void st16(uint64_t addr, u32x4 v) {
-  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<GVecP>(addr));
+  if (NT == kToHost) asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(addr), "v"(v) : "memory");
+  else if (NT) __builtin_nontemporal_store(v, reinterpret_cast<GVecP>(addr));
   else *reinterpret_cast<GVecP>(addr) = v;
 }
 __device__ __forceinline__ uint8_t ld8(uint64_t addr) { return *reinterpret_cast<const uint8_t FT_GLOBAL *>(addr); }
@@ -121,7 +133,7 @@ __device__ __forceinline__ u32x4 funnel(u32x4 A, u32x4 B, uint32_t shift) {
 }
 
 // Write the bytes [lo, hi) of v to the aligned granule at ga.
-template <bool NT>
+template <int NT>
 __device__ __forceinline__ void store_granule(uint64_t ga, u32x4 v, uint32_t lo, uint32_t hi) {
   if (lo == 0 && hi == 16) {
     st16<NT>(ga, v);
@@ -140,7 +152,7 @@ __device__ __forceinline__ void store_granule(uint64_t ga, u32x4 v, uint32_t lo,
 // is clamped into the row's own source range, and what it returns is never stored - so
 // the code stays a straight line. Stores write only bytes of the destination range:
 // whole granules with one vector store, the first and last of a row byte-wise.
-template <bool NT, uint32_t L, uint32_t R>
+template <int NT, uint32_t L, uint32_t R>
 __device__ __forceinline__ void copy_rows_grouped(const Xfer &X, uint64_t r0, uint64_t c0, uint64_t rl, uint64_t cl,
                                                   uint32_t tid) {
   constexpr uint32_t kGroups = kThreads / L;
@@ -181,7 +193,7 @@ __device__ __forceinline__ void copy_rows_grouped(const Xfer &X, uint64_t r0, ui
 // R rows of kThreads aligned vectors each (R * 4 KiB), every lane issuing its R loads
 // before its first store. No lane is predicated, so the code is one straight line and
 // the loads are waited for once, not one by one.
-template <bool NT, uint32_t R>
+template <int NT, uint32_t R>
 __device__ __forceinline__ void copy_rows_of_vectors(uint64_t d, uint64_t s, uint32_t tid) {
   u32x4 v[R];
 #pragma unroll
@@ -196,7 +208,7 @@ __device__ __forceinline__ void copy_rows_of_vectors(uint64_t d, uint64_t s, uin
 // 2.2 us, however early the tile's data was there - and the workgroup held a ticket it had not started
 // for a whole tile, which is what the end of a launch waits for. Issued here the answer still arrives
 // while the stores drain (feature: 181.5 -> 178 us, the pool->pool launches of large_mixed 83.5 -> 82.5).
-template <bool NT, uint32_t R>
+template <int NT, uint32_t R>
 __device__ __forceinline__ unsigned long long copy_rows_of_vectors_draw(uint64_t d, uint64_t s, uint32_t tid,
                                                                         unsigned long long *ticket) {
   u32x4 v[R];
@@ -214,7 +226,7 @@ __device__ __forceinline__ unsigned long long copy_rows_of_vectors_draw(uint64_t
 // 1 <= nvec <= R * kThreads aligned vectors in one pass. Loads are never predicated: a
 // lane whose vector lies past the end loads the last vector instead (and does not store
 // it), so all R loads of a lane are in flight before its first store whatever nvec is.
-template <bool NT, uint32_t R>
+template <int NT, uint32_t R>
 __device__ __forceinline__ void copy_rows_clamped(uint64_t d, uint64_t s, uint32_t nvec, uint32_t tid) {
   u32x4 v[R];
   const uint32_t lastv = nvec - 1;
@@ -233,7 +245,7 @@ __device__ __forceinline__ void copy_rows_clamped(uint64_t d, uint64_t s, uint32
 
 // nvec aligned 16-byte vectors with the whole workgroup: full blocks of U rows, then one
 // clamped pass over what is left.
-template <bool NT, uint32_t U>
+template <int NT, uint32_t U>
 __device__ __forceinline__ void copy_vectors(uint64_t d, uint64_t s, uint64_t nvec, uint32_t tid) {
   constexpr uint32_t kBlockVec = kThreads * U;
   while (nvec >= kBlockVec) {
@@ -286,7 +298,7 @@ __device__ __forceinline__ u32x4 shifted_vector(u32x4 A, u32x4 nextrow, uint32_t
 // equals the aligned case, there is no barrier and nothing is parked in LDS. Loads are
 // never predicated: an index past the run's last source granule is clamped to it and
 // what it returns is never stored.
-template <bool NT, uint32_t R, uint32_t Q>
+template <int NT, uint32_t R, uint32_t Q>
 __device__ __forceinline__ void shifted_pass(uint64_t d, uint64_t a, uint32_t left, uint32_t r, uint32_t tid) {
   const uint32_t wave = tid >> 6, lane = tid & 63;
   const uint32_t wbase = wave * (R * 64);
@@ -313,7 +325,7 @@ __device__ __forceinline__ void shifted_pass(uint64_t d, uint64_t a, uint32_t le
 }
 
 // nfull whole destination granules from aligned d; s is the (unaligned) source of d.
-template <bool NT, uint32_t U, uint32_t Q>
+template <int NT, uint32_t U, uint32_t Q>
 __device__ __forceinline__ void copy_shifted_q(uint64_t d, uint64_t s, uint64_t nfull, uint32_t tid) {
   const uint32_t r = (uint32_t)s & 3;
   const uint64_t a_base = s & ~15ull;
@@ -333,7 +345,7 @@ __device__ __forceinline__ void copy_shifted_q(uint64_t d, uint64_t s, uint64_t 
 // Source and destination differ in alignment: the bytes before the first and after the
 // last whole destination granule go one by one, the granules between as aligned vectors
 // built from shifted source granules.
-template <bool NT, uint32_t U>
+template <int NT, uint32_t U>
 __device__ __forceinline__ void copy_shifted(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid) {
   uint64_t head = (16 - (d0 & 15)) & 15;
   if (head > n) head = n;
@@ -359,7 +371,7 @@ __device__ __forceinline__ void copy_shifted(uint64_t d0, uint64_t s0, uint64_t 
 }
 
 // One contiguous piece with the whole workgroup.
-template <bool NT, uint32_t U>
+template <int NT, uint32_t U>
 __device__ __forceinline__ void copy_piece(uint64_t d0, uint64_t s0, uint64_t n, uint32_t tid) {
   if (((d0 ^ s0) & 15) == 0) {
     if (n < 64) {
@@ -401,7 +413,7 @@ __device__ __forceinline__ uint32_t merge_dword(uint32_t a, uint32_t b, uint32_t
 // Loads are never predicated: an address outside the aligned granules that hold bytes of
 // its piece is clamped into them and what it returns is never stored; a granule without
 // a second piece repeats the first piece's addresses.
-template <bool NT, uint32_t R>
+template <int NT, uint32_t R>
 __device__ __forceinline__ void copy_rows_packed_pairs(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid) {
   const uint32_t rb = (uint32_t)X.row_bytes;
   const uint64_t d0 = X.dst + p, d1 = d0 + take;
@@ -472,7 +484,7 @@ __device__ __forceinline__ void copy_rows_packed_pairs(const Xfer &X, uint64_t p
 }
 
 // 16 bytes to any address.
-template <bool NT>
+template <int NT>
 __device__ __forceinline__ void st16_any(uint64_t addr, u32x4 v) {
   if (NT) __builtin_nontemporal_store(v, reinterpret_cast<u32x4_any FT_GLOBAL *>(addr));
   else *reinterpret_cast<u32x4_any FT_GLOBAL *>(addr) = v;
@@ -489,7 +501,7 @@ struct RowPart {
   uint8_t b;
 };
 
-template <bool NT>
+template <int NT>
 __device__ __forceinline__ void row_part_load(RowPart &P, uint32_t tid) {
   if (P.d == 0) return;
   if (P.len < 16) {
@@ -500,7 +512,7 @@ __device__ __forceinline__ void row_part_load(RowPart &P, uint32_t tid) {
   }
 }
 
-template <bool NT>
+template <int NT>
 __device__ __forceinline__ void row_part_store(const RowPart &P, uint32_t tid) {
   if (P.d == 0) return;
   if (P.len < 16) {
@@ -512,7 +524,7 @@ __device__ __forceinline__ void row_part_store(const RowPart &P, uint32_t tid) {
 }
 
 // Whole rows r0 .. rl of a pitched descriptor, R windows per lane and pass (see copy_rows_windows).
-template <bool NT, uint32_t R>
+template <int NT, uint32_t R>
 __device__ __forceinline__ void move_windows(const Xfer &X, uint64_t r0, uint64_t rl, uint32_t tid) {
   const uint32_t rb = (uint32_t)X.row_bytes;
   const uint32_t S = (rb + 15) >> 4;
@@ -552,7 +564,7 @@ __device__ __forceinline__ void move_windows(const Xfer &X, uint64_t r0, uint64_
 // their own. Windows aligned to the destination's granules (51 against 46.5 us on the crops of the
 // traffic workload) or to the source's (46.6) measured no better than windows counted from the
 // row's first byte.
-template <bool NT, uint32_t R>
+template <int NT, uint32_t R>
 __device__ __forceinline__ void copy_rows_windows(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid) {
   const uint32_t rb = (uint32_t)X.row_bytes;
   const uint64_t pend = p + take;
@@ -596,7 +608,7 @@ __device__ __forceinline__ void copy_rows_windows(const Xfer &X, uint64_t p, uin
 }
 
 // Payload bytes [p, p+take) of a pitched descriptor.
-template <bool NT, uint32_t U, bool P2P>
+template <int NT, uint32_t U, bool P2P>
 __device__ __forceinline__ void copy_rows(const Xfer &X, uint64_t p, uint64_t take, uint32_t tid) {
   const uint64_t rb = X.row_bytes;
   const uint64_t pend = p + take;
@@ -859,7 +871,7 @@ __device__ __forceinline__ void get_work(const WorkSlot &slot, Work &w) {
 
 // The tiles of one contiguous transfer whose two sides are 16-byte aligned, dealt out round robin among
 // the workgroups.
-template <bool NT, uint32_t U>
+template <int NT, uint32_t U>
 __device__ __forceinline__ void deal_out_tiles(const ClassTable &T, uint64_t src, uint64_t dst, uint64_t nbytes, uint32_t tid) {
   for (uint64_t v = blockIdx.x; v < T.ntickets; v += gridDim.x) {
     uint64_t rank, ti;
@@ -928,6 +940,7 @@ __device__ __forceinline__ void drain_barrier() {
 template <bool NT, int CLS>
 __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(ClassTable T, InlineBlob) {
   constexpr uint32_t U = UnrollOf<CLS>::value;
+  constexpr int MODE = !NT ? 0 : CLS == 1 ? kToHost : kStream;
   __shared__ WorkSlot s_work[2];
   const uint32_t tid = threadIdx.x;
   const ConstTables CT = const_tables(T);
@@ -938,7 +951,7 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
     // tiles b, b + workgroups, ...: no counter, no decode by one wavefront for the others, no
     // hand-over through LDS, and the first tile's loads are issued a microsecond after entry.
     if (T.single == 3) deal_out_tiles<false, U>(T, CT.xfers[0].src, CT.xfers[0].dst, CT.xfers[0].row_bytes, tid);
-    else deal_out_tiles<NT, U>(T, CT.xfers[0].src, CT.xfers[0].dst, CT.xfers[0].row_bytes, tid);
+    else deal_out_tiles<MODE, U>(T, CT.xfers[0].src, CT.xfers[0].dst, CT.xfers[0].row_bytes, tid);
     return;
   }
   const bool lead = tid < 64;  // the first wavefront: draws and decodes tickets
@@ -976,7 +989,7 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
     if (fd != 0) {
       // the common case, one full aligned block (64 KiB for pool->pool): 32 bytes read
       // from LDS, then straight-line code to the last store, the ticket draw on the way
-      claimed = copy_rows_of_vectors_draw<NT, U>(fd, fs, tid, T.ticket);
+      claimed = copy_rows_of_vectors_draw<MODE, U>(fd, fs, tid, T.ticket);
     } else {
       // Host-link classes draw before the tile's pieces: a tile lasts as long as the link takes, the
       // counter's answer is there long before, and the workgroups run ahead of the link anyway.
@@ -994,8 +1007,8 @@ __global__ __launch_bounds__(kThreads, (CLS == 2 ? 1 : 2)) void ft_copy_kernel(C
         const bool more = pos + take < cur.b1;
         Xfer Xn = X;
         if (more) Xn = read_xfer(CT.xfers, ++x);
-        if (X.rows == 1) copy_piece<NT, U>(X.dst + p, X.src + p, take, tid);
-        else copy_rows<NT, U, (CLS >= 2)>(X, p, take, tid);
+        if (X.rows == 1) copy_piece<MODE, U>(X.dst + p, X.src + p, take, tid);
+        else copy_rows<MODE, U, (CLS >= 2)>(X, p, take, tid);
         pos += take;
         if (more) {
           X = Xn;

@@ -825,7 +825,7 @@ int open_submit(ft_pool *p, Job *job, SubmitPlan &plan, const uint32_t *weights,
       if (rc != FT_OK) return undo(rc);
     }
     const Tuning &tn = p->tuning[c];
-    tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp)),
+    tile_shape(chunk_bytes, tn.tile_bytes ? tn.tile_bytes : default_tile(c, with_p2p, mostly_short_rows(cp), ~0ull),
                &oc.tile_bytes, &oc.tiles_per_chunk);
     oc.workgroups = tn.workgroups ? tn.workgroups : default_workgroups(p, c, with_p2p);
     // consecutive batches overlap on the class's two streams, so each launch gets a share of

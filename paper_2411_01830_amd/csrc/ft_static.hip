@@ -93,7 +93,7 @@ extern "C" int ft_submit_static(ft_pool *p, const ft_desc *descs, uint32_t ndesc
     if (cp.nchunks == 0) continue;
     StaticClass &s = sc[c];
     s.used = any = true;
-    tile_shape(chunk_bytes, default_tile(c, with_p2p, mostly_short_rows(cp)), &s.tile_bytes, &s.tiles_per_chunk);
+    tile_shape(chunk_bytes, default_tile(c, with_p2p, mostly_short_rows(cp), cp.payload), &s.tile_bytes, &s.tiles_per_chunk);
     build_chunk_table(cp, chunk_bytes, s.tile_bytes, s.tiles_per_chunk);
     build_skips(cp, chunk_bytes, s.tile_bytes, s.tiles_per_chunk, &s.skips, &s.ntickets);
     s.lay = layout_of(cp, 0, 1);

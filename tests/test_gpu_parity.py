@@ -654,6 +654,44 @@ def test_log_names_the_compute_unit_of_every_workgroup(gpu):
         eng.close()
 
 
+def test_pool_to_host_stores_reach_the_link_while_the_kernel_runs(gpu):
+    """The pool->host kernel writes its 16-byte stores through to the fabric as it issues them. Were they left in the
+    L2, the workgroups would have issued their last store long before the launch ends (the L2 writes the lines back
+    when the kernel finishes: 209 of 337 us on a job like this one). So: the workgroups' own record - first entry to
+    last exit on the device clock - must cover nearly all of the dispatch's duration by its events. Bytes compared
+    as everywhere."""
+    binding, _ = gpu
+    orc, eng, rng = _pair(gpu, host=1 << 25, pool=1 << 25, slab=1 << 16, seed=55)
+    try:
+        recs, hdst = [], 1 << 24
+        for i in range(12):
+            n = (1 << 20) + 16 * int(rng.integers(0, 4000)) + (i % 3)
+            a = orc.slab_alloc(n + 32)
+            assert eng.slab_alloc(n + 32) == a
+            fill = rng.integers(0, 256, n + 32, dtype=np.uint8)
+            orc.write_pool(a, fill)
+            eng.write_pool(a, fill)
+            recs.append(dict(func=i % 4, src_space=FT_POOL, dst_space=FT_HOST, src=a + (i % 5), dst=hdst + (i % 7), row_bytes=n))
+            hdst += (n + 64 + 4095) // 4096 * 4096
+        assert hdst <= 1 << 25
+        d = make_descs(recs)
+        orc.wait(orc.submit(d, [1, 1, 2, 2], 64 * 1024))
+        covered = []
+        for attempt in range(3):
+            jg = eng.submit(d, [1, 1, 2, 2], 64 * 1024, fmt.FT_LOG | fmt.FT_TIMING)
+            eng.wait(jg)
+            st = binding.job_stats(eng.pool, jg)
+            _, t_in, t_out = binding.job_log_workgroups(eng.pool, jg, 1, st.cls[1].tickets)
+            span_ms = (int(t_out.max()) - int(t_in.min())) / 1e6
+            covered.append(span_ms / st.cls[1].device_ms)
+            binding.job_release(eng.pool, jg)
+        _compare_images(orc, eng)
+        print(f"pool->host: workgroups at work for {[round(c, 3) for c in covered]} of the dispatch", flush=True)
+        assert max(covered) >= 0.85, covered
+    finally:
+        eng.close()
+
+
 def test_a_detached_pool_to_pool_job_does_not_wait_for_another_jobs_host_link_kernel(gpu):
     """Job A carries 128 MiB host->pool (2 ms on the link) and 1 GiB pool->pool, job B, submitted right behind it, 64 MiB
     pool->pool; both detached. B's launch may queue behind A's pool->pool launch but must be over long before A's
