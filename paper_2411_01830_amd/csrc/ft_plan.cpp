@@ -104,6 +104,16 @@ int build_phases(std::vector<Func> &funcs, std::vector<Phase> &phases, std::vect
   *nchunks_out = 0;
   const uint32_t F = (uint32_t)funcs.size();
   if (F == 0) return FT_OK;
+  if (F == 1) {
+    // one function (passing a single tensor is the commonest job there is): its chunks in stream
+    // order, one slot per round - what the general construction below arrives at, without its vectors
+    funcs[0].weight = 1;
+    funcs[0].chunk_off = 0;
+    phases.push_back(Phase{0, 0, 0, 1});
+    slots.push_back(Slot{0, 0, 1, 0});
+    *nchunks_out = funcs[0].nchunks;
+    return FT_OK;
+  }
   uint32_t g = 0;
   for (auto &f : funcs) g = std::gcd(g, f.weight);
   for (auto &f : funcs) f.weight /= g;
@@ -420,6 +430,32 @@ int plan_submit(SlabPool &pool, const std::vector<HostWindow> &windows, const ft
     bool any = false;
     for (uint32_t i = 0; i < ndesc && !any; ++i) any = class_of(descs[i]) == c;
     if (!any) continue;  // a class without traffic costs no allocation (passing one tensor: two of three)
+    if (ndesc == 1) {
+      // one descriptor: one function with one stream, nothing to count or to sort into place
+      Xfer x = resolved[0];
+      if (x.rows > 1 && x.src_pitch == x.row_bytes && x.dst_pitch == x.row_bytes) {
+        x.row_bytes *= x.rows;  // rows that touch are one contiguous run (cannot wrap: checked in pass 2)
+        x.rows = 1;
+        x.src_pitch = x.dst_pitch = x.row_bytes;
+      }
+      x.stream_off = 0;
+      Func fn;
+      fn.stream_bytes = x.row_bytes * x.rows;
+      fn.nchunks = fn.stream_bytes / chunk_bytes + (fn.stream_bytes % chunk_bytes != 0);
+      fn.func = descs[0].func;
+      fn.weight = weights[descs[0].func];
+      fn.desc_off = 0;
+      fn.ndesc = 1;
+      fn.chunk_off = 0;
+      fn._pad = 0;
+      fn.chunk_base = 0;
+      cp.funcs.push_back(fn);
+      cp.xfers.push_back(x);
+      cp.payload = fn.stream_bytes;
+      int rc = build_phases(cp.funcs, cp.phases, cp.slots, &cp.nchunks);
+      if (rc != FT_OK) return rc;
+      continue;
+    }
     std::vector<uint64_t> stream(nfunc, 0);
     std::vector<uint32_t> count(nfunc, 0);
     for (uint32_t i = 0; i < ndesc; ++i)
